@@ -1,0 +1,309 @@
+"""Pins of the CPU oracles against what the paper and the mathematics fix.
+
+The paper prints no numeric value of any state or output, so the oracle is
+pinned by its identities instead: each test below states the passage it uses.
+None of them calls the GPU library.  Tolerances are fp64 round-off levels.
+"""
+import json
+import os
+
+import numpy as np
+import pytest
+
+from oracle import chunk_oracle, token_oracle
+
+RNG = np.random.default_rng
+
+
+def _rand_problem(rng, T, H, dk, dv, N=1, h0=True):
+    q = rng.standard_normal((N, T, H, dk)).astype(np.float32)
+    k = rng.standard_normal((N, T, H, dk)).astype(np.float32)
+    v = rng.standard_normal((N, T, H, dv)).astype(np.float32)
+    la = -np.log1p(np.exp(rng.standard_normal((N, T, H))))
+    eta = 1.0 / (1.0 + np.exp(-rng.standard_normal((N, T, H))))
+    S0 = rng.standard_normal((N, H, dk, dv)) if h0 else None
+    return q, k, v, la, eta, S0
+
+
+def _steps(q, k, v, la, eta, eps, S0):
+    """Drive the oracle one token at a time so every intermediate state is visible."""
+    T = q.shape[0]
+    S = S0.copy()
+    states, outs = [S.copy()], []
+    for t in range(T):
+        o, S = token_oracle.kla_decode(q[t][None, None], k[t][None, None], v[t][None, None],
+                                       np.array([[la[t]]]), np.array([[eta[t]]]), eps, S[None, None])
+        S = S[0, 0]
+        states.append(S.copy())
+        outs.append(o[0, 0])
+    return states, np.array(outs)
+
+
+def test_hand_worked_example():
+    """tests/golden/hand_worked_3step.json: three tokens worked by hand from Algorithm 1 (left)."""
+    with open(os.path.join(os.path.dirname(__file__), "golden", "hand_worked_3step.json")) as f:
+        g = json.load(f)
+    q = np.array(g["q"], np.float32)[None, :, None, :]
+    k = np.array(g["k"], np.float32)[None, :, None, :]
+    v = np.array(g["v"], np.float32)[None, :, None, :]
+    la = np.log(np.array(g["alpha"]))[None, :, None]
+    eta = np.array(g["eta"])[None, :, None]
+    o, hT, _ = token_oracle.kla_recurrent(q, k, v, la, eta, g["eps"])
+    np.testing.assert_allclose(o[0, :, 0, :], np.array(g["o"]), rtol=0, atol=1e-15)
+    np.testing.assert_allclose(hT[0, 0], np.array(g["S_final"]), rtol=0, atol=1e-15)
+    # the chunkwise route must give the same numbers (any chunk length)
+    for C in (1, 2, 3):
+        oc, hc = chunk_oracle.kla_chunkwise(q, k, v, la, eta, g["eps"], chunk=C)
+        np.testing.assert_allclose(oc[0, :, 0, :], np.array(g["o"]), rtol=0, atol=1e-14)
+        np.testing.assert_allclose(hc[0, 0], np.array(g["S_final"]), rtol=0, atol=1e-14)
+
+
+def test_projection_property_theorem1():
+    """Theorem 1: alpha=1, eta=1, eps=0  =>  S_t^T k_t = v_t after every write (any S_0)."""
+    rng = RNG(1)
+    T, dk, dv = 40, 16, 12
+    q, k, v, la, eta, S0 = _rand_problem(rng, T, 1, dk, dv)
+    q, k, v = q[0, :, 0], k[0, :, 0], v[0, :, 0]
+    states, _ = _steps(q, k, v, np.zeros(T), np.ones(T), 0.0, S0[0, 0])
+    for t in range(T):
+        S = states[t + 1]
+        assert np.max(np.abs(S.T @ k[t].astype(np.float64) - v[t])) <= 1e-12 * np.max(np.abs(v))
+
+
+def test_residual_contraction_prop2_all_parameters():
+    """Proposition 2 / eq. (9): v - S_t^T k = (1 - eta |k|^2/(|k|^2+eps)) (v - alpha S_{t-1}^T k).
+
+    Holds for every alpha, eta, eps: pins decay-before-residual, beta and the write direction."""
+    rng = RNG(2)
+    T, dk, dv = 50, 8, 5
+    for eps in (0.0, 1e-6, 0.3):
+        q, k, v, la, eta, S0 = _rand_problem(rng, T, 1, dk, dv)
+        q, k, v, la, eta = q[0, :, 0], k[0, :, 0], v[0, :, 0], la[0, :, 0], eta[0, :, 0]
+        states, _ = _steps(q, k, v, la, eta, eps, S0[0, 0])
+        for t in range(T):
+            kk = k[t].astype(np.float64)
+            nk = kk @ kk
+            e_before = v[t] - np.exp(la[t]) * (states[t].T @ kk)
+            e_after = v[t] - states[t + 1].T @ kk
+            factor = 1.0 - eta[t] * nk / (nk + eps)
+            np.testing.assert_allclose(e_after, factor * e_before, rtol=1e-11, atol=1e-12)
+
+
+def test_minimum_norm_change_theorem1_i():
+    """Theorem 1(i): eta=1, eps=0 => |S_t - S~|_F = |e|/|k| and <S_t - S~, H>_F = 0 whenever H^T k = 0."""
+    rng = RNG(3)
+    dk, dv = 10, 7
+    q, k, v, la, eta, S0 = _rand_problem(rng, 1, 1, dk, dv)
+    kk = k[0, 0, 0].astype(np.float64)
+    alpha = np.exp(la[0, 0, 0])
+    states, _ = _steps(q[0, :, 0], k[0, :, 0], v[0, :, 0], la[0, :, 0], np.ones(1), 0.0, S0[0, 0])
+    S_tilde = alpha * states[0]
+    delta = states[1] - S_tilde
+    e = v[0, 0, 0] - S_tilde.T @ kk
+    np.testing.assert_allclose(np.linalg.norm(delta), np.linalg.norm(e) / np.linalg.norm(kk), rtol=1e-12)
+    for _ in range(5):
+        Hm = rng.standard_normal((dk, dv))
+        Hm -= np.outer(kk, kk @ Hm) / (kk @ kk)          # now H^T k = 0
+        assert abs(np.sum(delta * Hm)) <= 1e-12 * np.linalg.norm(delta) * np.linalg.norm(Hm)
+
+
+def test_line_search_eq4():
+    """eq. (4): along S~ + tau k e^T the loss is (1/2)(1 - tau |k|^2)^2 |e|^2.  With eps=0 the
+    oracle's step is tau = eta/|k|^2, so eta sweeps the path; the minimum sits at eta = 1."""
+    rng = RNG(4)
+    dk, dv = 6, 4
+    q, k, v, la, _, S0 = _rand_problem(rng, 1, 1, dk, dv)
+    kk = k[0, 0, 0].astype(np.float64)
+    vv = v[0, 0, 0].astype(np.float64)
+    S_tilde = np.exp(la[0, 0, 0]) * S0[0, 0]
+    e = vv - S_tilde.T @ kk
+    losses = []
+    for eta in (0.0, 0.25, 0.9, 1.0, 1.1, 1.7):
+        states, _ = _steps(q[0, :, 0], k[0, :, 0], v[0, :, 0], la[0, :, 0], np.array([eta]), 0.0, S0[0, 0])
+        loss = 0.5 * np.sum((states[1].T @ kk - vv) ** 2)
+        np.testing.assert_allclose(loss, 0.5 * (1.0 - eta) ** 2 * (e @ e), rtol=1e-10, atol=1e-24)
+        losses.append(loss)
+    assert int(np.argmin(losses)) == 3
+
+
+def test_proximal_stationarity_prop1():
+    """Proposition 1: S_t - S~ + mu k (S_t^T k - v)^T = 0 with mu = eta/((1-eta)|k|^2 + eps)."""
+    rng = RNG(5)
+    dk, dv = 9, 6
+    for eta, eps in ((0.3, 0.0), (0.8, 1e-6), (1.0, 0.2), (0.5, 0.7)):
+        q, k, v, la, _, S0 = _rand_problem(rng, 1, 1, dk, dv)
+        kk = k[0, 0, 0].astype(np.float64)
+        vv = v[0, 0, 0].astype(np.float64)
+        states, _ = _steps(q[0, :, 0], k[0, :, 0], v[0, :, 0], la[0, :, 0], np.array([eta]), eps, S0[0, 0])
+        S_tilde = np.exp(la[0, 0, 0]) * states[0]
+        mu = eta / ((1.0 - eta) * (kk @ kk) + eps)
+        grad = states[1] - S_tilde + mu * np.outer(kk, states[1].T @ kk - vv)
+        assert np.max(np.abs(grad)) <= 1e-11 * max(1.0, np.max(np.abs(states[1])) * mu)
+
+
+def test_pure_decay_eta_zero():
+    """eq. (3) with eta=0: beta=0, so S_t = (prod alpha) S_0 and o_t = (prod alpha) S_0^T q_t."""
+    rng = RNG(6)
+    T, H, dk, dv = 37, 2, 8, 6
+    q, k, v, la, eta, S0 = _rand_problem(rng, T, H, dk, dv, N=2)
+    o, hT, _ = token_oracle.kla_recurrent(q, k, v, la, np.zeros_like(eta), 1e-6, h0=S0)
+    cum = np.exp(np.cumsum(la, axis=1))                       # [N,T,H]
+    expect_o = cum[..., None] * np.einsum("nhkv,nthk->nthv", S0, q.astype(np.float64))
+    np.testing.assert_allclose(o, expect_o, rtol=1e-11, atol=1e-13)
+    np.testing.assert_allclose(hT, cum[:, -1][..., None, None] * S0, rtol=1e-11, atol=1e-14)
+    oc, hc = chunk_oracle.kla_chunkwise(q, k, v, la, np.zeros_like(eta), 1e-6, h0=S0, chunk=8)
+    np.testing.assert_allclose(oc, expect_o, rtol=1e-11, atol=1e-13)
+    np.testing.assert_allclose(hc, hT, rtol=1e-11, atol=1e-14)
+
+
+@pytest.mark.parametrize("C", [1, 16, 64, 150])
+@pytest.mark.parametrize("with_h0", [False, True])
+def test_chunkwise_equals_recurrent_props3_4(C, with_h0):
+    """Propositions 3-4 (eqs. (6)-(8)): the chunkwise solver reproduces the token loop for any C,
+    including T not a multiple of C, C=1 (no off-diagonal terms) and C>=T (one chunk)."""
+    rng = RNG(7 + C)
+    T, H, dk, dv = 150, 2, 12, 20
+    q, k, v, la, eta, S0 = _rand_problem(rng, T, H, dk, dv, N=2, h0=with_h0)
+    la = la * 0.3                                             # slower decay: early tokens still matter at T
+    o, hT, _ = token_oracle.kla_recurrent(q, k, v, la, eta, 1e-6, h0=S0)
+    oc, hc = chunk_oracle.kla_chunkwise(q, k, v, la, eta, 1e-6, h0=S0, chunk=C)
+    assert token_oracle.rel_err(oc, o) <= 1e-10
+    assert token_oracle.rel_err(hc, hT) <= 1e-10
+
+
+def test_chunk_intermediates_wy_factors():
+    """Propositions 5-6 and eq. (15): U = U0 - W S_0 with W = T B D_gamma K, U0 = T B V, and the
+    chunk transition P_C = gamma_C I - sum_r (gamma_C/gamma_r) k_r w_r^T equals the explicit product
+    of alpha_r (I - beta_r k_r k_r^T)."""
+    rng = RNG(8)
+    T, dk, dv = 16, 6, 5
+    q, k, v, la, eta, S0 = _rand_problem(rng, T, 1, dk, dv)
+    q, k, v, la, eta = q[0, :, 0], k[0, :, 0], v[0, :, 0], la[0, :, 0], eta[0, :, 0]
+    _, _, inter = chunk_oracle.kla_chunkwise_unit(q, k, v, la, eta, 1e-6, S0[0, 0], chunk=T, want=True)
+    c = inter[0]
+    np.testing.assert_allclose(c["U"], c["U0"] - c["W"] @ S0[0, 0], rtol=1e-11, atol=1e-12)
+    kk = k.astype(np.float64)
+    Pexp = np.eye(dk)
+    for r in range(T):
+        Pexp = np.exp(la[r]) * (np.eye(dk) - c["beta"][r] * np.outer(kk[r], kk[r])) @ Pexp
+    g = c["g"]
+    Pwy = np.exp(g[-1]) * np.eye(dk) - sum(np.exp(g[-1] - g[r]) * np.outer(kk[r], c["W"][r]) for r in range(T))
+    np.testing.assert_allclose(Pwy, Pexp, rtol=1e-10, atol=1e-12)
+
+
+def test_gdn_reduction_unit_keys():
+    """Sec. 3.1 'Connection to GDN' / Table 2: with |k|=1 and eps=0 the coefficient is beta=eta and
+    the update is S_t = (I - eta k k^T) alpha S_{t-1} + eta k v^T, coded here in that product form."""
+    rng = RNG(9)
+    T, dk, dv = 30, 8, 8
+    q, k, v, la, eta, S0 = _rand_problem(rng, T, 1, dk, dv)
+    k64 = k.astype(np.float64)
+    k64 /= np.linalg.norm(k64, axis=-1, keepdims=True)
+    k32 = k64.astype(np.float32)                              # unit norm only up to fp32 rounding
+    o, hT, _ = token_oracle.kla_recurrent(q, k32, v, la, eta, 0.0, h0=S0)
+    S = S0[0, 0].copy()
+    for t in range(T):
+        kk = k32[0, t, 0].astype(np.float64)
+        b = eta[0, t, 0] / (kk @ kk)                          # = eta up to 1e-7
+        assert abs(b - eta[0, t, 0]) < 1e-6
+        S = (np.eye(dk) - eta[0, t, 0] * np.outer(kk, kk)) @ (np.exp(la[0, t, 0]) * S) \
+            + eta[0, t, 0] * np.outer(kk, v[0, t, 0])
+        np.testing.assert_allclose(o[0, t, 0], S.T @ q[0, t, 0], rtol=0, atol=2e-6 * (1 + np.max(np.abs(S))))
+    np.testing.assert_allclose(hT[0, 0], S, rtol=0, atol=2e-6 * (1 + np.max(np.abs(S))))
+
+
+def test_bruteforce_product_form_table5():
+    """Table 5 (KLA row): o_t = sum_{j<=t} beta_j v_j k_j^T [M_{j+1} ... M_t] q_t with
+    M_s = alpha_s (I - beta_s k_s k_s^T), the factor s=j+1 next to k_j; S_0 = 0; tiny sizes."""
+    rng = RNG(10)
+    T, dk, dv = 7, 4, 3
+    q, k, v, la, eta, _ = _rand_problem(rng, T, 1, dk, dv, h0=False)
+    eps = 1e-3
+    o, _, _ = token_oracle.kla_recurrent(q, k, v, la, eta, eps)
+    kk, vv, qq = k[0, :, 0].astype(np.float64), v[0, :, 0].astype(np.float64), q[0, :, 0].astype(np.float64)
+    beta = eta[0, :, 0] / (np.sum(kk * kk, axis=1) + eps)
+    M = [np.exp(la[0, s, 0]) * (np.eye(dk) - beta[s] * np.outer(kk[s], kk[s])) for s in range(T)]
+    for t in range(T):
+        acc = np.zeros(dv)
+        for j in range(t + 1):
+            prod = np.eye(dk)
+            for s in range(j + 1, t + 1):
+                prod = prod @ M[s]
+            acc += beta[j] * vv[j] * (kk[j] @ prod @ qq[t])
+        np.testing.assert_allclose(o[0, t, 0], acc, rtol=1e-10, atol=1e-12)
+
+
+def test_textbook_kaczmarz_limits():
+    """Sec. 3.1 (row-action method): alpha=1, eta=1, eps=0, S_0=0.
+    (a) orthonormal keys: one pass gives S = sum_i k_i v_i^T exactly;
+    (b) T<=d_k independent keys swept cyclically converge to the minimum-norm solution pinv(K) V."""
+    rng = RNG(11)
+    dk, dv, T = 12, 5, 6
+    Qm, _ = np.linalg.qr(rng.standard_normal((dk, dk)))
+    K = Qm[:, :T].T.astype(np.float32)                         # rows orthonormal up to fp32 rounding
+    V = rng.standard_normal((T, dv)).astype(np.float32)
+    ones, zeros = np.ones((1, T, 1)), np.zeros((1, T, 1))
+    _, hT, _ = token_oracle.kla_recurrent(K[None, :, None], K[None, :, None], V[None, :, None], zeros, ones, 0.0)
+    np.testing.assert_allclose(hT[0, 0], K.astype(np.float64).T @ V, rtol=0, atol=5e-6)
+    K = rng.standard_normal((T, dk)).astype(np.float32)
+    sweeps = 400
+    Kc, Vc = np.tile(K, (sweeps, 1)), np.tile(V, (sweeps, 1))
+    n = T * sweeps
+    _, hT, _ = token_oracle.kla_recurrent(Kc[None, :, None], Kc[None, :, None], Vc[None, :, None],
+                                          np.zeros((1, n, 1)), np.ones((1, n, 1)), 0.0)
+    np.testing.assert_allclose(hT[0, 0], np.linalg.pinv(K.astype(np.float64)) @ V, rtol=0, atol=1e-9)
+
+
+def test_scaling_metamorphic_and_zero_key():
+    """eps=0: (k, q) -> (c k, c q) leaves every o_t unchanged and scales h_T by 1/c (beta ~ 1/c^2).
+    A zero key with eps=0 must write nothing and give finite numbers (beta := 0 reading)."""
+    rng = RNG(12)
+    T, dk, dv = 25, 8, 8
+    q, k, v, la, eta, _ = _rand_problem(rng, T, 1, dk, dv, h0=False)
+    o1, h1, _ = token_oracle.kla_recurrent(q, k, v, la, eta, 0.0)
+    o2, h2, _ = token_oracle.kla_recurrent(4 * q, 4 * k, v, la, eta, 0.0)
+    np.testing.assert_allclose(o2, o1, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(h2, h1 / 4, rtol=1e-12, atol=1e-14)
+    k[0, 5, 0] = 0.0
+    o3, h3, _ = token_oracle.kla_recurrent(q, k, v, la, eta, 0.0)
+    assert np.all(np.isfinite(o3)) and np.all(np.isfinite(h3))
+    oc, hc = chunk_oracle.kla_chunkwise(q, k, v, la, eta, 0.0, chunk=8)
+    assert token_oracle.rel_err(oc, o3) <= 1e-10 and token_oracle.rel_err(hc, h3) <= 1e-10
+
+
+def test_batch_head_independence_and_varlen():
+    """Every (sequence, head) is an independent recurrence (Algorithm 1 is per head): permuting
+    heads permutes outputs; a packed batch equals the sequences run one by one."""
+    rng = RNG(13)
+    T, H, dk, dv = 50, 3, 6, 4
+    q, k, v, la, eta, _ = _rand_problem(rng, T, H, dk, dv, h0=False)
+    o, hT, _ = token_oracle.kla_recurrent(q, k, v, la, eta, 1e-6)
+    perm = [2, 0, 1]
+    op, hp, _ = token_oracle.kla_recurrent(q[:, :, perm], k[:, :, perm], v[:, :, perm], la[:, :, perm],
+                                           eta[:, :, perm], 1e-6)
+    np.testing.assert_array_equal(op, o[:, :, perm])
+    np.testing.assert_array_equal(hp, hT[:, perm])
+    cu = [0, 13, 30, 50]
+    h0 = rng.standard_normal((3, H, dk, dv))
+    ov, hv, _ = token_oracle.kla_recurrent(q, k, v, la, eta, 1e-6, h0=h0, cu_seqlens=cu)
+    for s in range(3):
+        a, b = cu[s], cu[s + 1]
+        os_, hs, _ = token_oracle.kla_recurrent(q[:, a:b], k[:, a:b], v[:, a:b], la[:, a:b], eta[:, a:b],
+                                                1e-6, h0=h0[s:s + 1])
+        np.testing.assert_array_equal(ov[:, a:b], os_)
+        np.testing.assert_array_equal(hv[s], hs[0])
+    oc, hc = chunk_oracle.kla_chunkwise(q, k, v, la, eta, 1e-6, h0=h0, cu_seqlens=cu, chunk=16)
+    assert token_oracle.rel_err(oc, ov) <= 1e-10 and token_oracle.rel_err(hc, hv) <= 1e-10
+
+
+def test_split_invariance():
+    """The state is the only carry (Sec. 2): running T1 tokens, then T2 from h_T, equals one run."""
+    rng = RNG(14)
+    T, H, dk, dv = 60, 2, 8, 8
+    q, k, v, la, eta, S0 = _rand_problem(rng, T, H, dk, dv)
+    o, hT, _ = token_oracle.kla_recurrent(q, k, v, la, eta, 1e-6, h0=S0)
+    a = 23
+    o1, h1, _ = token_oracle.kla_recurrent(q[:, :a], k[:, :a], v[:, :a], la[:, :a], eta[:, :a], 1e-6, h0=S0)
+    o2, h2, _ = token_oracle.kla_recurrent(q[:, a:], k[:, a:], v[:, a:], la[:, a:], eta[:, a:], 1e-6, h0=h1)
+    np.testing.assert_array_equal(np.concatenate([o1, o2], axis=1), o)
+    np.testing.assert_array_equal(h2, hT)
