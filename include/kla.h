@@ -1,0 +1,138 @@
+/*
+ * kla.h - C ABI of the MI355X (gfx950) Kaczmarz Linear Attention hot path.
+ *
+ * The library computes, per sequence and per head, the gated delta-rule
+ * recurrence of the paper (Sec. 3.1 eq. (3), Sec. 3.3 Algorithm 1):
+ *
+ *     S~   = alpha_t S_{t-1}                      alpha_t = exp(log_alpha_t)
+ *     e_t  = v_t - S~^T k_t
+ *     beta = eta_t / (||k_t||^2 + eps)            (beta := 0 when the denominator is 0)
+ *     S_t  = S~ + beta k_t e_t^T
+ *     o_t  = S_t^T q_t                            (no query normalisation: the caller
+ *                                                  normalises q if it wants Sec. 3.3's read-out)
+ *
+ * with the state S a d_k x d_v matrix (Sec. 2), stored row-major with d_v
+ * contiguous, always fp32.  The same map written for R = S^T is eq. (5).
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers unless a parameter says "host".
+ *   - The caller owns every buffer and keeps it alive until the stream has
+ *     passed the call.  The library allocates and frees nothing, keeps no global
+ *     state, and is thread-safe.  Work is enqueued on `hip_stream`
+ *     (a hipStream_t, NULL = the default stream); the call returns without
+ *     waiting for it.
+ *   - Return value: KLA_OK or a negative kla_status.  A validation failure is
+ *     reported before anything is launched and leaves all outputs untouched.  A
+ *     failed launch is reported as KLA_ERR_HIP.
+ *   - q, k, v, o share one element type (kla_dtype).  Gates, eps, states are fp32.
+ *   - Token-major layout: a tensor "[N, T, H, D]" is contiguous with D fastest.
+ *     Data pointers must be 16-byte aligned.
+ *   - Supported shapes: dk in {64, 128}; dv in {64, 128, 256}; chunk == 64.
+ */
+#ifndef KLA_H
+#define KLA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { KLA_F32 = 0, KLA_BF16 = 1 } kla_dtype;
+
+typedef enum {
+    KLA_OK = 0,
+    KLA_ERR_NULL = -1,       /* a required pointer is NULL                               */
+    KLA_ERR_SHAPE = -2,      /* unsupported or inconsistent sizes, or eps < 0            */
+    KLA_ERR_DTYPE = -3,      /* unknown kla_dtype                                        */
+    KLA_ERR_ALIGN = -4,      /* a data pointer is not 16-byte aligned                    */
+    KLA_ERR_WORKSPACE = -5,  /* workspace missing or smaller than the query reports      */
+    KLA_ERR_SEQLENS = -6,    /* host cu_seqlens not starting at 0, decreasing, or != T   */
+    KLA_ERR_HIP = -7         /* the HIP runtime refused a launch                         */
+} kla_status;
+
+/* Human-readable name of a status code (static storage, never NULL). */
+const char *kla_status_string(int code);
+
+/*
+ * Bytes of device scratch kla_chunk_fwd needs for these sizes (0 on invalid sizes).
+ * For a packed batch pass the host copy of cu_seqlens and n_seq > 0 (then N must be 1
+ * and T the total token count); otherwise cu_seqlens_host = NULL, n_seq = 0.
+ */
+size_t kla_chunk_fwd_workspace_bytes(int N, int T, int H, int dk, int dv, int chunk, kla_dtype dt,
+                                     const int32_t *cu_seqlens_host, int n_seq);
+
+/*
+ * Chunkwise-parallel forward (Sec. 4, Algorithm 1 right panel, eqs. (6)-(8)): for every
+ * sequence and head, the outputs o_t of all tokens and the state after the last token.
+ * The result equals the token loop above; chunks of 64 tokens are counted from each
+ * sequence's own first token and never straddle sequences; a sequence of any length >= 0 is
+ * accepted (a short last chunk is handled inside the kernels).
+ *
+ *   q, k        [N, T, H, dk]  dt         in
+ *   v           [N, T, H, dv]  dt         in
+ *   log_alpha   [N, T, H]      fp32       in   natural log of the decay gate (<= 0 expected)
+ *   eta         [N, T, H]      fp32       in   write gate (0..1 expected)
+ *   eps                                   in   stabiliser of eq. (3), >= 0
+ *   h0          [n_states, H, dk, dv] fp32 in  initial states, or NULL for zeros
+ *   o           [N, T, H, dv]  dt         out  must not alias an input
+ *   hT          [n_states, H, dk, dv] fp32 out final states, or NULL if unwanted; may alias h0
+ *   cu_seqlens_dev  [n_seq+1] int32 device, or NULL for a fixed-length batch
+ *   cu_seqlens_host same values on the host (used for grid sizing and validation), or NULL
+ *   n_seq       number of packed sequences; 0 for fixed length.  If n_seq > 0 then N == 1,
+ *               T is the total token count and n_states = n_seq; otherwise n_states = N.
+ *   workspace   device scratch of at least kla_chunk_fwd_workspace_bytes(...) bytes,
+ *               256-byte aligned; contents undefined on return.
+ */
+int kla_chunk_fwd(const void *q, const void *k, const void *v,
+                  const float *log_alpha, const float *eta, float eps,
+                  const float *h0, void *o, float *hT,
+                  const int32_t *cu_seqlens_dev, const int32_t *cu_seqlens_host, int n_seq,
+                  int N, int T, int H, int dk, int dv, int chunk, kla_dtype dt,
+                  void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * One recurrent decode step (Algorithm 1 left panel) for B*H independent states.
+ *
+ *   q, k        [B, H, dk] dt     in
+ *   v           [B, H, dv] dt     in
+ *   log_alpha, eta [B, H]  fp32   in
+ *   S           [B, H, dk, dv] fp32   in/out, updated IN PLACE to S_t
+ *   o           [B, H, dv] dt     out
+ */
+int kla_decode_step(const void *q, const void *k, const void *v,
+                    const float *log_alpha, const float *eta, float eps,
+                    float *S, void *o,
+                    int B, int H, int dk, int dv, kla_dtype dt, void *hip_stream);
+
+/*
+ * The Kaczmarz coefficient alone (eq. (3)): beta[i] = eta[i] / (||k_i||^2 + eps), 0 when the
+ * denominator is 0, for n_token_heads rows of dk elements.
+ *   k [n_token_heads, dk] dt in;  eta [n_token_heads] fp32 in;  beta [n_token_heads] fp32 out.
+ */
+int kla_beta(const void *k, const float *eta, float eps, float *beta,
+             long n_token_heads, int dk, kla_dtype dt, void *hip_stream);
+
+/*
+ * Test hook: the per-chunk objects the first stage of kla_chunk_fwd leaves in its workspace,
+ * unpacked to plain row-major fp32 so that they can be compared one by one with eqs. (6)-(7).
+ * Arguments as in kla_chunk_fwd.  For every chunk c (global chunk index, sequences in order)
+ * and head h:
+ *   Tb_out  [n_chunks, H, 64, 64]  (I + B(A^- o K K^T))^{-1} B, i.e. the solve of eq. (6) as a matrix
+ *   P_out   [n_chunks, H, 64, 64]  A o Q K^T (lower triangle incl. diagonal) of eq. (7)
+ *   g_out   [n_chunks, H, 64]      chunk-local running sum of log_alpha (log gamma_i)
+ * Rows and columns beyond a short last chunk are zero (g repeats its last value).
+ * The values are those the second stage consumes (rounded to dt for dt = bf16).
+ */
+int kla_debug_intra_chunk(const void *q, const void *k,
+                          const float *log_alpha, const float *eta, float eps,
+                          float *Tb_out, float *P_out, float *g_out,
+                          const int32_t *cu_seqlens_dev, const int32_t *cu_seqlens_host, int n_seq,
+                          int N, int T, int H, int dk, int chunk, kla_dtype dt,
+                          void *workspace, size_t workspace_bytes, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KLA_H */

@@ -1,0 +1,172 @@
+"""Python binding of the MI355X KLA library (libkla.so, C ABI in include/kla.h).
+
+Argument marshalling only: every step of the path runs in the HIP kernels.  PyTorch supplies
+device memory and the current stream.  There is no CPU fallback: if the compiled library is
+missing, or a tensor is not on the GPU, the call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import threading
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libkla.so")
+HEADER_PATH = os.path.join(os.path.dirname(_HERE), "include", "kla.h")
+
+KLA_F32, KLA_BF16 = 0, 1
+_lock = threading.Lock()
+_lib = None
+
+_vp, _fp, _ip = ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p
+_SIGNATURES = {
+    "kla_status_string": (ctypes.c_char_p, [ctypes.c_int]),
+    "kla_chunk_fwd_workspace_bytes": (ctypes.c_size_t, [ctypes.c_int] * 6 + [ctypes.c_int, _ip, ctypes.c_int]),
+    "kla_chunk_fwd": (ctypes.c_int, [_vp, _vp, _vp, _fp, _fp, ctypes.c_float, _fp, _vp, _fp, _ip, _ip, ctypes.c_int]
+                      + [ctypes.c_int] * 6 + [ctypes.c_int, _vp, ctypes.c_size_t, _vp]),
+    "kla_decode_step": (ctypes.c_int, [_vp, _vp, _vp, _fp, _fp, ctypes.c_float, _fp, _vp]
+                        + [ctypes.c_int] * 4 + [ctypes.c_int, _vp]),
+    "kla_beta": (ctypes.c_int, [_vp, _fp, ctypes.c_float, _fp, ctypes.c_long, ctypes.c_int, ctypes.c_int, _vp]),
+    "kla_debug_intra_chunk": (ctypes.c_int, [_vp, _vp, _fp, _fp, ctypes.c_float, _fp, _fp, _fp, _ip, _ip, ctypes.c_int]
+                              + [ctypes.c_int] * 5 + [ctypes.c_int, _vp, ctypes.c_size_t, _vp]),
+}
+
+
+class KlaError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__("%s failed: %s" % (where, lib().kla_status_string(code).decode()))
+
+
+def lib():
+    """The loaded C library; raises if it has not been built (python -m paper_2605_08587_amd.build)."""
+    global _lib
+    with _lock:
+        if _lib is None:
+            if not os.path.exists(LIB_PATH):
+                raise RuntimeError("libkla.so is not built: run `python -m paper_2605_08587_amd.build` "
+                                   "(there is no CPU fallback)")
+            l = ctypes.CDLL(LIB_PATH)
+            for name, (res, args) in _SIGNATURES.items():
+                fn = getattr(l, name)
+                fn.restype, fn.argtypes = res, args
+            _lib = l
+    return _lib
+
+
+def _dt(t: torch.Tensor) -> int:
+    if t.dtype == torch.bfloat16:
+        return KLA_BF16
+    if t.dtype == torch.float32:
+        return KLA_F32
+    raise TypeError("q, k, v must be bfloat16 or float32, got %s" % t.dtype)
+
+
+def _dev(*ts):
+    for t in ts:
+        if t is not None:
+            if not t.is_cuda:
+                raise RuntimeError("KLA kernels need GPU tensors (no CPU fallback)")
+            if not t.is_contiguous():
+                raise ValueError("tensors must be contiguous")
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _host_cu(cu_seqlens):
+    if cu_seqlens is None:
+        return None, None, 0
+    cu_host = cu_seqlens.detach().to("cpu", torch.int32).contiguous()
+    return cu_host, ctypes.c_void_p(cu_host.data_ptr()), cu_host.numel() - 1
+
+
+def kla_chunk_fwd_workspace_bytes(N, T, H, dk, dv, dtype, cu_seqlens=None, chunk=64) -> int:
+    cu_host, cu_hp, n_seq = _host_cu(cu_seqlens)
+    dt = KLA_BF16 if dtype == torch.bfloat16 else KLA_F32
+    return int(lib().kla_chunk_fwd_workspace_bytes(N, T, H, dk, dv, chunk, dt, cu_hp, n_seq))
+
+
+def kla_chunk_fwd(q, k, v, log_alpha, eta, eps, h0=None, cu_seqlens=None, want_hT=True, workspace=None,
+                  out=None, hT=None, chunk=64):
+    """Chunkwise forward.  q,k [N,T,H,dk], v [N,T,H,dv], gates [N,T,H] fp32; returns (o, hT).
+
+    cu_seqlens: int32 device tensor [n_seq+1] for a packed batch (then N == 1).
+    workspace / out / hT may be passed in to avoid allocations (e.g. inside a timed loop).
+    """
+    _dev(q, k, v, log_alpha, eta, h0, cu_seqlens, workspace, out, hT)
+    N, T, H, dk = q.shape
+    dv = v.shape[-1]
+    dt = _dt(q)
+    cu_host, cu_hp, n_seq = _host_cu(cu_seqlens)
+    n_states = n_seq if n_seq > 0 else N
+    need = int(lib().kla_chunk_fwd_workspace_bytes(N, T, H, dk, dv, chunk, dt, cu_hp, n_seq))
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+    if out is None:
+        out = torch.empty((N, T, H, dv), dtype=q.dtype, device=q.device)
+    if hT is None and want_hT:
+        hT = torch.empty((n_states, H, dk, dv), dtype=torch.float32, device=q.device)
+    rc = lib().kla_chunk_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(eta), float(eps), _ptr(h0), _ptr(out),
+                             _ptr(hT), _ptr(cu_seqlens), cu_hp, n_seq, N, T, H, dk, dv, chunk, dt,
+                             _ptr(workspace), workspace.numel() * workspace.element_size(), _stream())
+    if rc != 0:
+        raise KlaError(rc, "kla_chunk_fwd")
+    return out, hT
+
+
+def kla_decode_step(q, k, v, log_alpha, eta, eps, S, out=None):
+    """One decode step; S [B,H,dk,dv] fp32 is updated in place; returns o [B,H,dv]."""
+    _dev(q, k, v, log_alpha, eta, S, out)
+    B, H, dk = q.shape
+    dv = v.shape[-1]
+    if out is None:
+        out = torch.empty((B, H, dv), dtype=q.dtype, device=q.device)
+    rc = lib().kla_decode_step(_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(eta), float(eps), _ptr(S), _ptr(out),
+                               B, H, dk, dv, _dt(q), _stream())
+    if rc != 0:
+        raise KlaError(rc, "kla_decode_step")
+    return out
+
+
+def kla_beta(k, eta, eps, out=None):
+    """beta = eta / (||k||^2 + eps) for k [..., dk], eta [...]; returns fp32 [...]."""
+    _dev(k, eta, out)
+    dk = k.shape[-1]
+    n = k.numel() // dk
+    if out is None:
+        out = torch.empty(k.shape[:-1], dtype=torch.float32, device=k.device)
+    rc = lib().kla_beta(_ptr(k), _ptr(eta), float(eps), _ptr(out), n, dk, _dt(k), _stream())
+    if rc != 0:
+        raise KlaError(rc, "kla_beta")
+    return out
+
+
+def kla_debug_intra_chunk(q, k, log_alpha, eta, eps, cu_seqlens=None, chunk=64):
+    """Test hook: (Tb, P, g) of every chunk as fp32 [n_chunks, H, 64, 64] / [n_chunks, H, 64]."""
+    _dev(q, k, log_alpha, eta, cu_seqlens)
+    N, T, H, dk = q.shape
+    dt = _dt(q)
+    cu_host, cu_hp, n_seq = _host_cu(cu_seqlens)
+    if n_seq > 0:
+        n_chunks = int(((cu_host[1:] - cu_host[:-1] + 63) // 64).sum())
+    else:
+        n_chunks = N * ((T + 63) // 64)
+    need = int(lib().kla_chunk_fwd_workspace_bytes(N, T, H, dk, 64, chunk, dt, cu_hp, n_seq))
+    ws = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+    Tb = torch.zeros((n_chunks, H, 64, 64), dtype=torch.float32, device=q.device)
+    P = torch.zeros_like(Tb)
+    g = torch.zeros((n_chunks, H, 64), dtype=torch.float32, device=q.device)
+    rc = lib().kla_debug_intra_chunk(_ptr(q), _ptr(k), _ptr(log_alpha), _ptr(eta), float(eps), _ptr(Tb), _ptr(P),
+                                     _ptr(g), _ptr(cu_seqlens), cu_hp, n_seq, N, T, H, dk, chunk, dt, _ptr(ws),
+                                     ws.numel(), _stream())
+    if rc != 0:
+        raise KlaError(rc, "kla_debug_intra_chunk")
+    return Tb, P, g

@@ -1,0 +1,234 @@
+// C ABI of the library (declared in include/kla.h): argument validation, workspace carving and
+// launch sequencing.  No allocation, no global state; everything is enqueued on the caller's stream.
+#include <math.h>
+#include <stdlib.h>
+
+#include "../../include/kla.h"
+#include "kla_kernels.hpp"
+
+namespace {
+
+using kla::bf16_t;
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t round256(size_t x) { return (x + 255) & ~(size_t)255; }
+inline bool dk_ok(int dk) { return dk == 64 || dk == 128; }
+inline bool dv_ok(int dv) { return dv == 64 || dv == 128 || dv == 256; }
+inline bool dt_ok(int dt) { return dt == KLA_F32 || dt == KLA_BF16; }
+inline size_t elem_bytes(int dt) { return dt == KLA_BF16 ? 2 : 4; }
+
+struct Plan {
+    long n_chunks;       // over all sequences
+    int n_states;        // sequences
+    size_t off_T, off_P, off_G, off_C, total;
+};
+
+// Validates the size arguments shared by the chunk entry points and lays out the workspace.
+int make_plan(int N, int T, int H, int dk, int dv, int chunk, int dt, const int32_t* cu_host, int n_seq, Plan* p)
+{
+    if (!dt_ok(dt)) return KLA_ERR_DTYPE;
+    if (N < 0 || T < 0 || H <= 0 || n_seq < 0 || !dk_ok(dk) || !dv_ok(dv) || chunk != 64) return KLA_ERR_SHAPE;
+    long n_chunks = 0;
+    if (n_seq > 0) {
+        if (N != 1) return KLA_ERR_SHAPE;
+        if (!cu_host) return KLA_ERR_NULL;
+        if (cu_host[0] != 0) return KLA_ERR_SEQLENS;
+        for (int s = 0; s < n_seq; ++s) {
+            if (cu_host[s + 1] < cu_host[s]) return KLA_ERR_SEQLENS;
+            n_chunks += (cu_host[s + 1] - cu_host[s] + 63) / 64;
+        }
+        if (cu_host[n_seq] != T) return KLA_ERR_SEQLENS;
+        p->n_states = n_seq;
+    } else {
+        if (cu_host) return KLA_ERR_SHAPE;
+        n_chunks = (long)N * ((T + 63) / 64);
+        p->n_states = N;
+    }
+    if (n_chunks * H > 0x7fffffffL || (long)p->n_states * H * (dv / 16) > 0x7fffffffL) return KLA_ERR_SHAPE;
+    p->n_chunks = n_chunks;
+    const size_t slots = (size_t)n_chunks * H * 512 * 8 * elem_bytes(dt);   // 512 slots of 8 elements per chunk-head
+    p->off_T = 0;
+    p->off_P = round256(p->off_T + slots);
+    p->off_G = round256(p->off_P + slots);
+    p->off_C = round256(p->off_G + (size_t)n_chunks * H * 64 * sizeof(float));
+    p->total = round256(p->off_C + (size_t)(n_seq + 1) * sizeof(int32_t));
+    return KLA_OK;
+}
+
+int scan_waves(int n_chains, int dv, int dt)
+{
+    int w;
+    const char* env = getenv("KLA_SCAN_WAVES");   // tuning knob: 1, 2 or 4 waves (16 state columns each) per workgroup
+    if (env && (atoi(env) == 1 || atoi(env) == 2 || atoi(env) == 4)) w = atoi(env);
+    else {
+        // enough workgroups to cover the 256 CUs, else the widest slice that still gives >= 2 waves of loaders
+        const long chains8 = ((long)n_chains + 7) / 8 * 8;
+        w = (chains8 * (dv / 64) >= 512) ? 4 : 2;
+    }
+    if (dt == KLA_F32 && w > 2) w = 2;            // fp32 operands take twice the LDS
+    while (16 * w > dv) w >>= 1;
+    return w;
+}
+
+template <typename E>
+int chunk_fwd_impl(const void* q, const void* k, const void* v, const float* log_alpha, const float* eta, float eps,
+                   const float* h0, void* o, float* hT, const int32_t* cu_dev, int n_seq, int N, int T, int H, int dk,
+                   int dv, const Plan& pl, char* ws, bool scan, float* Tb_out, float* P_out, float* g_out,
+                   hipStream_t st)
+{
+    E* wsT = reinterpret_cast<E*>(ws + pl.off_T);
+    E* wsP = reinterpret_cast<E*>(ws + pl.off_P);
+    float* wsG = reinterpret_cast<float*>(ws + pl.off_G);
+    int* chunk_off = reinterpret_cast<int*>(ws + pl.off_C);
+    const int NT = (T + 63) / 64;
+    if (n_seq > 0 && kla::launch_chunk_offsets(cu_dev, n_seq, chunk_off, st) != hipSuccess) return KLA_ERR_HIP;
+
+    kla::IntraArgs<E> ia;
+    ia.q = static_cast<const E*>(q); ia.k = static_cast<const E*>(k);
+    ia.log_alpha = log_alpha; ia.eta = eta; ia.eps = eps;
+    ia.cu_seqlens = n_seq > 0 ? cu_dev : nullptr; ia.chunk_off = chunk_off; ia.n_seq = n_seq;
+    ia.T = T; ia.NT = NT; ia.H = H;
+    ia.wsT = wsT; ia.wsP = wsP; ia.wsG = wsG;
+    if (kla::launch_intra<E>(ia, dk, (int)pl.n_chunks, st) != hipSuccess) return KLA_ERR_HIP;
+
+    if (!scan) {
+        if (kla::launch_unpack<E>(wsT, wsP, wsG, Tb_out, P_out, g_out, pl.n_chunks * H, st) != hipSuccess)
+            return KLA_ERR_HIP;
+        return KLA_OK;
+    }
+    kla::ScanArgs<E> sa;
+    sa.q = static_cast<const E*>(q); sa.k = static_cast<const E*>(k); sa.v = static_cast<const E*>(v);
+    sa.h0 = h0; sa.o = static_cast<E*>(o); sa.hT = hT;
+    sa.cu_seqlens = ia.cu_seqlens; sa.chunk_off = chunk_off; sa.n_seq = n_seq;
+    sa.N = N; sa.T = T; sa.NT = NT; sa.H = H; sa.dv = dv;
+    sa.wsT = wsT; sa.wsP = wsP; sa.wsG = wsG;
+    const int waves = scan_waves(pl.n_states * H, dv, sizeof(E) == 2 ? KLA_BF16 : KLA_F32);
+    if (kla::launch_scan<E>(sa, dk, waves, st) != hipSuccess) return KLA_ERR_HIP;
+    return KLA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* kla_status_string(int code)
+{
+    switch (code) {
+        case KLA_OK: return "KLA_OK";
+        case KLA_ERR_NULL: return "KLA_ERR_NULL: a required pointer is NULL";
+        case KLA_ERR_SHAPE: return "KLA_ERR_SHAPE: unsupported or inconsistent sizes";
+        case KLA_ERR_DTYPE: return "KLA_ERR_DTYPE: unknown element type";
+        case KLA_ERR_ALIGN: return "KLA_ERR_ALIGN: pointer not 16-byte aligned";
+        case KLA_ERR_WORKSPACE: return "KLA_ERR_WORKSPACE: workspace missing, misaligned or too small";
+        case KLA_ERR_SEQLENS: return "KLA_ERR_SEQLENS: bad cu_seqlens";
+        case KLA_ERR_HIP: return "KLA_ERR_HIP: kernel launch failed";
+        default: return "unknown kla status";
+    }
+}
+
+size_t kla_chunk_fwd_workspace_bytes(int N, int T, int H, int dk, int dv, int chunk, kla_dtype dt,
+                                     const int32_t* cu_seqlens_host, int n_seq)
+{
+    Plan pl;
+    if (make_plan(N, T, H, dk, dv, chunk, (int)dt, cu_seqlens_host, n_seq, &pl) != KLA_OK) return 0;
+    return pl.total;
+}
+
+int kla_chunk_fwd(const void* q, const void* k, const void* v, const float* log_alpha, const float* eta, float eps,
+                  const float* h0, void* o, float* hT, const int32_t* cu_seqlens_dev, const int32_t* cu_seqlens_host,
+                  int n_seq, int N, int T, int H, int dk, int dv, int chunk, kla_dtype dt, void* workspace,
+                  size_t workspace_bytes, void* hip_stream)
+{
+    Plan pl;
+    const int rc = make_plan(N, T, H, dk, dv, chunk, (int)dt, cu_seqlens_host, n_seq, &pl);
+    if (rc != KLA_OK) return rc;
+    if (!(eps >= 0.0f) || isinf(eps)) return KLA_ERR_SHAPE;
+    if (n_seq > 0 && !cu_seqlens_dev) return KLA_ERR_NULL;
+    if (n_seq == 0 && cu_seqlens_dev) return KLA_ERR_SHAPE;
+    const bool any_tokens = (long)N * T > 0;
+    if (any_tokens && (!q || !k || !v || !log_alpha || !eta || !o)) return KLA_ERR_NULL;
+    if (!workspace) return KLA_ERR_WORKSPACE;
+    if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0 || workspace_bytes < pl.total) return KLA_ERR_WORKSPACE;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(h0) || !aligned16(hT) ||
+        (reinterpret_cast<uintptr_t>(log_alpha) & 3u) || (reinterpret_cast<uintptr_t>(eta) & 3u))
+        return KLA_ERR_ALIGN;
+    if (pl.n_states == 0) return KLA_OK;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    char* ws = static_cast<char*>(workspace);
+    if (dt == KLA_BF16)
+        return chunk_fwd_impl<bf16_t>(q, k, v, log_alpha, eta, eps, h0, o, hT, cu_seqlens_dev, n_seq, N, T, H, dk, dv,
+                                      pl, ws, true, nullptr, nullptr, nullptr, st);
+    return chunk_fwd_impl<float>(q, k, v, log_alpha, eta, eps, h0, o, hT, cu_seqlens_dev, n_seq, N, T, H, dk, dv, pl, ws,
+                                 true, nullptr, nullptr, nullptr, st);
+}
+
+int kla_debug_intra_chunk(const void* q, const void* k, const float* log_alpha, const float* eta, float eps,
+                          float* Tb_out, float* P_out, float* g_out, const int32_t* cu_seqlens_dev,
+                          const int32_t* cu_seqlens_host, int n_seq, int N, int T, int H, int dk, int chunk,
+                          kla_dtype dt, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    Plan pl;
+    const int rc = make_plan(N, T, H, dk, 64, chunk, (int)dt, cu_seqlens_host, n_seq, &pl);
+    if (rc != KLA_OK) return rc;
+    if (!(eps >= 0.0f) || isinf(eps)) return KLA_ERR_SHAPE;
+    if (n_seq > 0 && !cu_seqlens_dev) return KLA_ERR_NULL;
+    if (n_seq == 0 && cu_seqlens_dev) return KLA_ERR_SHAPE;
+    if (!q || !k || !log_alpha || !eta || !Tb_out || !P_out || !g_out) return KLA_ERR_NULL;
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0 || workspace_bytes < pl.total)
+        return KLA_ERR_WORKSPACE;
+    if (!aligned16(q) || !aligned16(k)) return KLA_ERR_ALIGN;
+    if (pl.n_chunks == 0) return KLA_OK;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    char* ws = static_cast<char*>(workspace);
+    if (dt == KLA_BF16)
+        return chunk_fwd_impl<bf16_t>(q, k, nullptr, log_alpha, eta, eps, nullptr, nullptr, nullptr, cu_seqlens_dev,
+                                      n_seq, N, T, H, dk, 64, pl, ws, false, Tb_out, P_out, g_out, st);
+    return chunk_fwd_impl<float>(q, k, nullptr, log_alpha, eta, eps, nullptr, nullptr, nullptr, cu_seqlens_dev, n_seq, N,
+                                 T, H, dk, 64, pl, ws, false, Tb_out, P_out, g_out, st);
+}
+
+int kla_decode_step(const void* q, const void* k, const void* v, const float* log_alpha, const float* eta, float eps,
+                    float* S, void* o, int B, int H, int dk, int dv, kla_dtype dt, void* hip_stream)
+{
+    if (!dt_ok((int)dt)) return KLA_ERR_DTYPE;
+    if (B < 0 || H <= 0 || !dk_ok(dk) || !dv_ok(dv) || (long)B * H > 0x7fffffffL) return KLA_ERR_SHAPE;
+    if (!(eps >= 0.0f) || isinf(eps)) return KLA_ERR_SHAPE;
+    if (B == 0) return KLA_OK;
+    if (!q || !k || !v || !log_alpha || !eta || !S || !o) return KLA_ERR_NULL;
+    if (!aligned16(S) || (reinterpret_cast<uintptr_t>(q) & 3u) || (reinterpret_cast<uintptr_t>(k) & 3u) ||
+        (reinterpret_cast<uintptr_t>(v) & 3u) || (reinterpret_cast<uintptr_t>(o) & 3u))
+        return KLA_ERR_ALIGN;
+    int slice = 64;                                   // state columns per workgroup
+    const char* env = getenv("KLA_DECODE_SLICE");     // tuning knob: 32, 64, 128 or 256
+    if (env) { const int x = atoi(env); if (x == 32 || x == 64 || x == 128 || x == 256) slice = x; }
+    if (slice > dv) slice = dv;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    hipError_t e;
+    if (dt == KLA_BF16)
+        e = kla::launch_decode<bf16_t>(static_cast<const bf16_t*>(q), static_cast<const bf16_t*>(k),
+                                       static_cast<const bf16_t*>(v), log_alpha, eta, eps, S, static_cast<bf16_t*>(o),
+                                       B * H, dk, dv, slice, st);
+    else
+        e = kla::launch_decode<float>(static_cast<const float*>(q), static_cast<const float*>(k),
+                                      static_cast<const float*>(v), log_alpha, eta, eps, S, static_cast<float*>(o),
+                                      B * H, dk, dv, slice, st);
+    return e == hipSuccess ? KLA_OK : KLA_ERR_HIP;
+}
+
+int kla_beta(const void* k, const float* eta, float eps, float* beta, long n_token_heads, int dk, kla_dtype dt,
+             void* hip_stream)
+{
+    if (!dt_ok((int)dt)) return KLA_ERR_DTYPE;
+    if (n_token_heads < 0 || !dk_ok(dk) || (n_token_heads * (dk / 8) + 255) / 256 > 0x7fffffffL) return KLA_ERR_SHAPE;
+    if (!(eps >= 0.0f) || isinf(eps)) return KLA_ERR_SHAPE;
+    if (n_token_heads == 0) return KLA_OK;
+    if (!k || !eta || !beta) return KLA_ERR_NULL;
+    if (!aligned16(k)) return KLA_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const hipError_t e = dt == KLA_BF16
+        ? kla::launch_beta<bf16_t>(static_cast<const bf16_t*>(k), eta, eps, beta, n_token_heads, dk, st)
+        : kla::launch_beta<float>(static_cast<const float*>(k), eta, eps, beta, n_token_heads, dk, st);
+    return e == hipSuccess ? KLA_OK : KLA_ERR_HIP;
+}
+
+}  // extern "C"

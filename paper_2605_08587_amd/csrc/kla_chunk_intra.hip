@@ -1,0 +1,322 @@
+// Intra-chunk stage of the chunkwise forward (Algorithm 1 right panel, lines 1-4 and the
+// matrix of eq. (6)); fully parallel over (chunk, head).
+//
+// Per chunk of C = 64 tokens of one head it computes
+//   beta_i = eta_i / (||k_i||^2 + eps)                                   eq. (3)
+//   g_i    = sum_{r<=i} log alpha_r   (log gamma_i, restarting at the chunk)
+//   L      = B (A^- o K K^T),  L_ij = beta_i exp(g_i - g_j) k_i.k_j  (j < i)
+//   T'     = (I + L)^{-1} B          so that eq. (6) reads  U = T' (V - D_gamma K S_0)
+//   P      = A o Q K^T,  P_ij = exp(g_i - g_j) q_i.k_j  (j <= i)         eq. (7)
+// and leaves T', P (in the element type, in MFMA operand order) and g in the workspace for the
+// scan stage.  Every decay ratio is formed as exp of a difference of g, masked before the exp,
+// because gamma itself underflows fp32 inside a chunk for fast decays.
+//
+// (I + L)^{-1} is built in fp32: the four 16x16 diagonal blocks by forward substitution in LDS,
+// then the off-diagonal blocks by two levels of block products on fp32 MFMA,
+//   [T11 0; T21 T22] with T21 = -T22 (L21 T11).
+#include "kla_common.hpp"
+#include "kla_kernels.hpp"
+#include "kla_mma.hpp"
+
+namespace kla {
+
+namespace {
+
+constexpr int kLdm = 68;   // row stride (floats) of the fp32 64x64 matrices in LDS: 16-byte aligned rows
+
+// lower-triangular 16x16 tile enumeration of a 64x64 matrix: 10 tiles
+__device__ __constant__ const int8_t kTileI[10] = {0, 1, 1, 2, 2, 2, 3, 3, 3, 3};
+__device__ __constant__ const int8_t kTileJ[10] = {0, 0, 1, 0, 1, 2, 0, 1, 2, 3};
+
+__device__ __forceinline__ float4 ld4(const float* p) { return *reinterpret_cast<const float4*>(p); }
+
+// B-operand quad of a row-major fp32 matrix: rows 4g..4g+3 of column r
+__device__ __forceinline__ float4 bquad(const float* m, int row0, int col0, int r, int g)
+{
+    const float* p = m + (row0 + 4 * g) * kLdm + col0 + r;
+    return make_float4(p[0], p[kLdm], p[2 * kLdm], p[3 * kLdm]);
+}
+// A-operand quad: columns 4g..4g+3 of row r
+__device__ __forceinline__ float4 aquad(const float* m, int row0, int col0, int r, int g)
+{
+    return ld4(m + (row0 + r) * kLdm + col0 + 4 * g);
+}
+__device__ __forceinline__ float4 acc_as_quad(floatx4 x) { return make_float4(x[0], x[1], x[2], x[3]); }
+
+}  // namespace
+
+template <typename E, int DK>
+__global__ __launch_bounds__(256) void intra_kernel(IntraArgs<E> a)
+{
+    constexpr int PPR = DK * (int)sizeof(E) / 16;    // 16-byte pieces per row
+    constexpr int EPP = 16 / (int)sizeof(E);         // elements per piece
+    constexpr int KP = DK / 32;                      // contraction pairs per row
+    constexpr int OPB = 64 * DK * (int)sizeof(E);    // bytes of one operand area
+
+    __shared__ __attribute__((aligned(16))) char op_area[2 * OPB > 64 * kLdm * 4 ? 2 * OPB : 64 * kLdm * 4];
+    __shared__ __attribute__((aligned(16))) float Lm[64 * kLdm];
+    __shared__ __attribute__((aligned(16))) float Tm[64 * kLdm];
+    __shared__ __attribute__((aligned(16))) float beta_s[64];
+    __shared__ __attribute__((aligned(16))) float g_s[64];
+    E* Krq = reinterpret_cast<E*>(op_area);
+    E* Qrq = reinterpret_cast<E*>(op_area + OPB);
+    float* Pm = reinterpret_cast<float*>(op_area);   // reused after the Gram products are in registers
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int r = lane & 15, g = lane >> 4;
+
+    // ---- which chunk of which sequence -------------------------------------------------------
+    const int h = blockIdx.x % a.H;
+    const int cg = blockIdx.x / a.H;                 // global chunk index
+    long tok0; int clen;
+    if (a.cu_seqlens) {
+        int lo = 0, hi = a.n_seq - 1;                // last s with chunk_off[s] <= cg
+        while (lo < hi) { const int mid = (lo + hi + 1) >> 1; if (a.chunk_off[mid] <= cg) lo = mid; else hi = mid - 1; }
+        const int c = cg - a.chunk_off[lo];
+        const int s0 = a.cu_seqlens[lo], s1 = a.cu_seqlens[lo + 1];
+        tok0 = (long)s0 + 64L * c;
+        clen = min(64, s1 - (int)tok0);
+    } else {
+        const int n = cg / a.NT, c = cg % a.NT;
+        tok0 = (long)n * a.T + 64L * c;
+        clen = min(64, a.T - 64 * c);
+    }
+
+    // ---- phase 1: K, Q -> LDS (operand order), key norms -> beta, log-decay prefix sum -> g ---
+    {
+        const size_t row_stride = (size_t)a.H * DK;
+        const E* kb = a.k + (size_t)tok0 * row_stride + (size_t)h * DK;
+        const E* qb = a.q + (size_t)tok0 * row_stride + (size_t)h * DK;
+#pragma unroll
+        for (int it = 0; it < 64 * PPR / 256; ++it) {
+            const int pi = tid + 256 * it;
+            const int row = pi / PPR, piece = pi % PPR;
+            uint4 kd = make_uint4(0, 0, 0, 0), qd = make_uint4(0, 0, 0, 0);
+            if (row < clen) {
+                kd = *reinterpret_cast<const uint4*>(kb + (size_t)row * row_stride + piece * EPP);
+                qd = *reinterpret_cast<const uint4*>(qb + (size_t)row * row_stride + piece * EPP);
+            }
+            store_rq_piece(Krq, KP, row, piece, kd);
+            store_rq_piece(Qrq, KP, row, piece, qd);
+            float ss = 0.f;
+            if constexpr (sizeof(E) == 2) {
+                const uint32_t w[4] = {kd.x, kd.y, kd.z, kd.w};
+#pragma unroll
+                for (int m = 0; m < 4; ++m) {
+                    const float x0 = bf16_bits_to_float(w[m] & 0xffffu), x1 = bf16_bits_to_float(w[m] >> 16);
+                    ss += x0 * x0; ss += x1 * x1;
+                }
+            } else {
+                const float x0 = __uint_as_float(kd.x), x1 = __uint_as_float(kd.y), x2 = __uint_as_float(kd.z),
+                            x3 = __uint_as_float(kd.w);
+                ss = x0 * x0 + x1 * x1 + x2 * x2 + x3 * x3;
+            }
+#pragma unroll
+            for (int off = 1; off < PPR; off <<= 1) ss += __shfl_xor(ss, off, kWave);
+            if (piece == 0) {
+                const float et = row < clen ? a.eta[(size_t)(tok0 + row) * a.H + h] : 0.f;
+                beta_s[row] = kaczmarz_beta(et, ss, a.eps);
+            }
+        }
+        if (wave == 0) {
+            float x = lane < clen ? a.log_alpha[(size_t)(tok0 + lane) * a.H + h] : 0.f;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const float y = __shfl_up(x, off, kWave);
+                if (lane >= off) x += y;
+            }
+            g_s[lane] = x;
+            a.wsG[(size_t)blockIdx.x * 64 + lane] = x;
+        }
+    }
+    __syncthreads();
+
+    // ---- phase 2a: Gram products K K^T and Q K^T on the lower-triangular tiles ---------------
+    floatx4 acc[5];
+#pragma unroll
+    for (int jb = 0; jb < 5; ++jb) {
+        const int job = wave + 4 * jb;               // 0..9: K K^T tiles, 10..19: Q K^T tiles
+        const int lt = job % 10;
+        const int ti = kTileI[lt], tj = kTileJ[lt];
+        const E* A = job < 10 ? Krq : Qrq;
+        floatx4 c = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kp = 0; kp < KP; ++kp) {
+            const Slot<E> sa = load_slot(A, ti * KP + kp, lane);
+            const Slot<E> sb = load_slot(Krq, tj * KP + kp, lane);
+            mma32<E>(c, sa, sb.q0, sb.q1);
+        }
+        acc[jb] = c;
+    }
+    __syncthreads();   // operand areas are dead from here on; Pm overlays them
+
+    // ---- phase 2b: decay, mask, beta -> L and P as fp32 matrices; zero the upper tiles --------
+#pragma unroll
+    for (int jb = 0; jb < 5; ++jb) {
+        const int job = wave + 4 * jb;
+        const int lt = job % 10;
+        const int ti = kTileI[lt], tj = kTileJ[lt];
+        const int j = 16 * tj + r;
+        const float gj = g_s[j];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int i = 16 * ti + 4 * g + e;
+            const float gi = g_s[i];
+            if (job < 10) {
+                const float val = (j < i) ? beta_s[i] * expf(gi - gj) * acc[jb][e] : 0.f;
+                Lm[i * kLdm + j] = val;
+            } else {
+                const float val = (j <= i) ? expf(gi - gj) * acc[jb][e] : 0.f;
+                Pm[i * kLdm + j] = val;
+            }
+        }
+    }
+    for (int x = tid; x < 6 * 256; x += 256) {       // the six strictly-upper tiles
+        const int t = x >> 8, e = x & 255;
+        const int ti = t < 3 ? 0 : (t < 5 ? 1 : 2);
+        const int tj = t < 3 ? t + 1 : (t < 5 ? t - 1 : 3);
+        const int idx = (16 * ti + (e >> 4)) * kLdm + 16 * tj + (e & 15);
+        Lm[idx] = 0.f; Pm[idx] = 0.f; Tm[idx] = 0.f;
+    }
+    __syncthreads();
+
+    // ---- phase 3: diagonal 16x16 blocks of (I+L)^{-1} by forward substitution (wave w: block w);
+    //      meanwhile P goes out to the workspace in operand order ------------------------------
+    {
+        const int b0 = 16 * wave;
+        float x[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            float s = (i == r) ? 1.f : 0.f;
+#pragma unroll
+            for (int rr = 0; rr < i; ++rr) s -= Lm[(b0 + i) * kLdm + b0 + rr] * x[rr];
+            x[i] = s;
+        }
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+            if ((i >> 2) == g) Tm[(b0 + i) * kLdm + b0 + r] = x[i];
+    }
+    {
+        char* out = reinterpret_cast<char*>(a.wsP) + (size_t)blockIdx.x * 512 * slot_bytes<E>();
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+            const int sl = tid + 256 * it;           // slot index: (tile row, pair) * 64 + lane
+            const int tp = sl >> 6, ln = sl & 63;
+            const int row = 16 * (tp >> 1) + (ln & 15), col = 32 * (tp & 1) + 4 * (ln >> 4);
+            floatx4 v0, v1;
+            const float4 f0 = ld4(Pm + row * kLdm + col), f1 = ld4(Pm + row * kLdm + col + 16);
+            v0[0] = f0.x; v0[1] = f0.y; v0[2] = f0.z; v0[3] = f0.w;
+            v1[0] = f1.x; v1[1] = f1.y; v1[2] = f1.z; v1[3] = f1.w;
+            Slot<E> s; s.q0 = acc_to_quad<E>(v0); s.q1 = acc_to_quad<E>(v1);
+            *reinterpret_cast<Slot<E>*>(out + (size_t)sl * slot_bytes<E>()) = s;
+        }
+    }
+    __syncthreads();
+
+    // ---- phase 4: 32x32 level.  Waves 0,1: block pair (a, b) = (2m, 2m+1): T_ba = -D_b (L_ba D_a)
+    if (wave < 2) {
+        const int ra = 32 * wave, rb = ra + 16;
+        floatx4 y = {0.f, 0.f, 0.f, 0.f}, z = {0.f, 0.f, 0.f, 0.f};
+        mma16(y, aquad(Lm, rb, ra, r, g), bquad(Tm, ra, ra, r, g));
+        mma16(z, aquad(Tm, rb, rb, r, g), acc_as_quad(y));
+#pragma unroll
+        for (int e = 0; e < 4; ++e) Tm[(rb + 4 * g + e) * kLdm + ra + r] = -z[e];
+    }
+    __syncthreads();
+
+    // ---- phase 5: 64x64 level.  T[32:64, 0:32] = -T22 (L21 T11); wave = (row tile ti, col tile tj)
+    {
+        const int ti = wave >> 1, tj = wave & 1;
+        floatx4 y0 = {0.f, 0.f, 0.f, 0.f}, y1 = {0.f, 0.f, 0.f, 0.f}, z = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int tm = 0; tm < 2; ++tm) {
+            const float4 b = bquad(Tm, 16 * tm, 16 * tj, r, g);
+            mma16(y0, aquad(Lm, 32, 16 * tm, r, g), b);
+            mma16(y1, aquad(Lm, 48, 16 * tm, r, g), b);
+        }
+        mma16(z, aquad(Tm, 32 + 16 * ti, 32, r, g), acc_as_quad(y0));
+        mma16(z, aquad(Tm, 32 + 16 * ti, 48, r, g), acc_as_quad(y1));
+        // the block written below is read by no wave in this phase, so no barrier is needed here
+#pragma unroll
+        for (int e = 0; e < 4; ++e) Tm[(32 + 16 * ti + 4 * g + e) * kLdm + 16 * tj + r] = -z[e];
+    }
+    __syncthreads();
+
+    // ---- phase 6: T' = T diag(beta) -> workspace in operand order ------------------------------
+    {
+        char* out = reinterpret_cast<char*>(a.wsT) + (size_t)blockIdx.x * 512 * slot_bytes<E>();
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+            const int sl = tid + 256 * it;
+            const int tp = sl >> 6, ln = sl & 63;
+            const int row = 16 * (tp >> 1) + (ln & 15), col = 32 * (tp & 1) + 4 * (ln >> 4);
+            const float4 f0 = ld4(Tm + row * kLdm + col), f1 = ld4(Tm + row * kLdm + col + 16);
+            const float4 b0 = ld4(beta_s + col), b1 = ld4(beta_s + col + 16);
+            floatx4 v0, v1;
+            v0[0] = f0.x * b0.x; v0[1] = f0.y * b0.y; v0[2] = f0.z * b0.z; v0[3] = f0.w * b0.w;
+            v1[0] = f1.x * b1.x; v1[1] = f1.y * b1.y; v1[2] = f1.z * b1.z; v1[3] = f1.w * b1.w;
+            Slot<E> s; s.q0 = acc_to_quad<E>(v0); s.q1 = acc_to_quad<E>(v1);
+            *reinterpret_cast<Slot<E>*>(out + (size_t)sl * slot_bytes<E>()) = s;
+        }
+    }
+}
+
+template <typename E>
+hipError_t launch_intra(const IntraArgs<E>& a, int dk, int n_chunks, hipStream_t st)
+{
+    if (n_chunks == 0) return hipSuccess;
+    const dim3 grid((unsigned)n_chunks * a.H), block(256);
+    if (dk == 64) hipLaunchKernelGGL((intra_kernel<E, 64>), grid, block, 0, st, a);
+    else          hipLaunchKernelGGL((intra_kernel<E, 128>), grid, block, 0, st, a);
+    return hipGetLastError();
+}
+template hipError_t launch_intra<float>(const IntraArgs<float>&, int, int, hipStream_t);
+template hipError_t launch_intra<bf16_t>(const IntraArgs<bf16_t>&, int, int, hipStream_t);
+
+// ---- chunk offsets of a packed batch: chunk_off[s] = sum_{s'<s} ceil(len_s'/64) --------------
+__global__ void chunk_offsets_kernel(const int* __restrict__ cu_seqlens, int n_seq, int* __restrict__ chunk_off)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        int acc = 0;
+        for (int s = 0; s < n_seq; ++s) {
+            chunk_off[s] = acc;
+            acc += (cu_seqlens[s + 1] - cu_seqlens[s] + 63) / 64;
+        }
+        chunk_off[n_seq] = acc;
+    }
+}
+hipError_t launch_chunk_offsets(const int* cu_seqlens, int n_seq, int* chunk_off, hipStream_t st)
+{
+    hipLaunchKernelGGL(chunk_offsets_kernel, dim3(1), dim3(64), 0, st, cu_seqlens, n_seq, chunk_off);
+    return hipGetLastError();
+}
+
+// ---- test hook: unpack operand-order T', P to plain row-major fp32 ---------------------------
+template <typename E>
+__global__ void unpack_kernel(const E* __restrict__ wsT, const E* __restrict__ wsP, const float* __restrict__ wsG,
+                              float* __restrict__ Tb, float* __restrict__ P, float* __restrict__ gout, long n_ch)
+{
+    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= n_ch * 4096) return;
+    const long ch = idx >> 12;
+    const int i = (int)((idx >> 6) & 63), j = (int)(idx & 63);
+    const int tp = (i >> 4) * 2 + (j >> 5), ln = (i & 15) + 16 * ((j & 15) >> 2);
+    const size_t e = ((size_t)ch * 512 + (size_t)tp * 64 + ln) * 8 + ((j >> 4) & 1) * 4 + (j & 3);
+    Tb[idx] = to_float(wsT[e]);
+    P[idx] = to_float(wsP[e]);
+    if (j == 0) gout[ch * 64 + i] = wsG[ch * 64 + i];
+}
+template <typename E>
+hipError_t launch_unpack(const E* wsT, const E* wsP, const float* wsG, float* Tb, float* P, float* gout, long n_ch,
+                         hipStream_t st)
+{
+    if (n_ch == 0) return hipSuccess;
+    const long n = n_ch * 4096;
+    hipLaunchKernelGGL((unpack_kernel<E>), dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, wsT, wsP, wsG, Tb, P,
+                       gout, n_ch);
+    return hipGetLastError();
+}
+template hipError_t launch_unpack<float>(const float*, const float*, const float*, float*, float*, float*, long, hipStream_t);
+template hipError_t launch_unpack<bf16_t>(const bf16_t*, const bf16_t*, const float*, float*, float*, float*, long, hipStream_t);
+
+}  // namespace kla

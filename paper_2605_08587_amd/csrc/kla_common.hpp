@@ -1,0 +1,54 @@
+// Shared device helpers for the gfx950 KLA kernels: element types, bf16 conversion,
+// wave-level reductions.  gfx950 only (64-wide wavefronts).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace kla {
+
+constexpr int kWave = 64;
+constexpr int kChunk = 64;   // tokens per chunk (C in Algorithm 1, right panel)
+
+// Storage type of a bf16 element: raw bits.  Arithmetic is never done in bf16; values are
+// widened to fp32 exactly and rounded back with round-to-nearest-even.
+struct bf16_t { uint16_t bits; };
+
+__device__ __forceinline__ float to_float(float x) { return x; }
+__device__ __forceinline__ float to_float(bf16_t x) { return __uint_as_float(((uint32_t)x.bits) << 16); }
+__device__ __forceinline__ float bf16_bits_to_float(uint32_t b) { return __uint_as_float(b << 16); }
+
+__device__ __forceinline__ uint32_t float_to_bf16_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;   // NaN stays NaN
+    u += 0x7fffu + ((u >> 16) & 1u);                                    // round to nearest even
+    return u >> 16;
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
+{
+    return float_to_bf16_bits(lo) | (float_to_bf16_bits(hi) << 16);
+}
+
+template <typename T> __device__ __forceinline__ T from_float(float f);
+template <> __device__ __forceinline__ float from_float<float>(float f) { return f; }
+template <> __device__ __forceinline__ bf16_t from_float<bf16_t>(float f)
+{
+    bf16_t r; r.bits = (uint16_t)float_to_bf16_bits(f); return r;
+}
+
+__device__ __forceinline__ float wave_sum(float x)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) x += __shfl_xor(x, off, kWave);
+    return x;
+}
+
+// Kaczmarz coefficient of eq. (3); a zero denominator (zero key, eps = 0) gives beta = 0
+// because the write beta k e^T is then zero for every finite beta.
+__device__ __forceinline__ float kaczmarz_beta(float eta, float knorm2, float eps)
+{
+    const float den = knorm2 + eps;
+    return den == 0.0f ? 0.0f : eta / den;
+}
+
+}  // namespace kla

@@ -1,0 +1,46 @@
+// Host-side declarations of the kernel launchers (one translation unit per stage).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "kla_common.hpp"
+
+namespace kla {
+
+// ---- decode step and stand-alone coefficient -----------------------------------------------
+template <typename T>
+hipError_t launch_decode(const T* q, const T* k, const T* v, const float* log_alpha, const float* eta, float eps,
+                         float* S, T* o, int BH, int dk, int dv, int slice, hipStream_t st);
+template <typename T>
+hipError_t launch_beta(const T* k, const float* eta, float eps, float* beta, long n_rows, int dk, hipStream_t st);
+
+// ---- chunkwise forward ------------------------------------------------------------------------
+// Workspace areas, all indexed by chunk-head ch = global_chunk * H + h:
+//   wsT, wsP : 512 operand slots (8 elements each) per chunk-head, see kla_mma.hpp
+//   wsG      : 64 fp32 per chunk-head
+//   chunk_off: int32 [n_seq + 1], packed batches only
+template <typename E> struct IntraArgs {
+    const E* q; const E* k;
+    const float* log_alpha; const float* eta; float eps;
+    const int* cu_seqlens; const int* chunk_off; int n_seq;
+    int T, NT, H;
+    E* wsT; E* wsP; float* wsG;
+};
+template <typename E> hipError_t launch_intra(const IntraArgs<E>& a, int dk, int n_chunks, hipStream_t st);
+
+template <typename E> struct ScanArgs {
+    const E* q; const E* k; const E* v;
+    const float* h0; E* o; float* hT;
+    const int* cu_seqlens; const int* chunk_off; int n_seq;
+    int N, T, NT, H, dv;
+    const E* wsT; const E* wsP; const float* wsG;
+};
+// waves = 1, 2 or 4: each wave of a workgroup carries 16 state columns through the whole sequence
+template <typename E> hipError_t launch_scan(const ScanArgs<E>& a, int dk, int waves, hipStream_t st);
+
+hipError_t launch_chunk_offsets(const int* cu_seqlens, int n_seq, int* chunk_off, hipStream_t st);
+template <typename E>
+hipError_t launch_unpack(const E* wsT, const E* wsP, const float* wsG, float* Tb, float* P, float* gout, long n_ch,
+                         hipStream_t st);
+
+}  // namespace kla

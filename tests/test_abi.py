@@ -1,0 +1,133 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol that
+include/kla.h declares, and every validation error is reported before anything is launched."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2605_08587_amd as kla
+
+pytestmark = pytest.mark.skipif(not os.path.exists(kla.LIB_PATH),
+                                reason="libkla.so not built (python -m paper_2605_08587_amd.build)")
+
+OK, E_NULL, E_SHAPE, E_DTYPE, E_ALIGN, E_WS, E_SEQ, E_HIP = 0, -1, -2, -3, -4, -5, -6, -7
+
+
+def _declared_functions():
+    src = open(kla.HEADER_PATH).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(kla_[a-z_0-9]+)\s*\(", src)))
+
+
+def test_every_declared_symbol_is_exported():
+    names = _declared_functions()
+    assert {"kla_chunk_fwd", "kla_decode_step", "kla_beta", "kla_chunk_fwd_workspace_bytes", "kla_status_string",
+            "kla_debug_intra_chunk"} <= set(names)
+    lib = ctypes.CDLL(kla.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_status_strings():
+    lib = kla.lib()
+    for code in range(0, -8, -1):
+        s = lib.kla_status_string(code).decode()
+        assert s.startswith("KLA_")
+    assert "unknown" in lib.kla_status_string(-99).decode()
+
+
+def test_workspace_bytes():
+    lib = kla.lib()
+    f = lib.kla_chunk_fwd_workspace_bytes
+    # 4096 chunk-heads, bf16: 2 x 8 KiB operand areas + 256 B of g each, plus the (empty) offsets table
+    n = f(8, 4096, 8, 128, 128, 64, kla.KLA_BF16, None, 0)
+    assert n >= 4096 * (2 * 8192 + 256) and n <= 4096 * (2 * 8192 + 256) + 4 * 256
+    assert f(8, 4096, 8, 128, 128, 64, kla.KLA_F32, None, 0) > n
+    assert f(8, 4096, 8, 128, 128, 32, kla.KLA_BF16, None, 0) == 0        # chunk != 64
+    assert f(8, 4096, 8, 96, 128, 64, kla.KLA_BF16, None, 0) == 0         # bad dk
+    cu = np.array([0, 10, 10, 200], dtype=np.int32)                       # 1 + 0 + 3 chunks
+    n2 = f(1, 200, 2, 64, 64, 64, kla.KLA_BF16, cu.ctypes.data, 3)
+    assert n2 >= 4 * 2 * (2 * 8192 + 256)
+    bad = np.array([0, 10, 5, 200], dtype=np.int32)
+    assert f(1, 200, 2, 64, 64, 64, kla.KLA_BF16, bad.ctypes.data, 3) == 0
+
+
+def _chunk_call(**over):
+    """kla_chunk_fwd with fake but well-aligned non-NULL device pointers; only validation can run."""
+    a = dict(q=0x1000, k=0x2000, v=0x3000, la=0x4000, eta=0x5000, eps=1e-6, h0=None, o=0x6000, hT=None,
+             cu_dev=None, cu_host=None, n_seq=0, N=1, T=64, H=1, dk=64, dv=64, chunk=64, dt=kla.KLA_BF16,
+             ws=0x100000, ws_bytes=1 << 30, stream=None)
+    a.update(over)
+    return kla.lib().kla_chunk_fwd(a["q"], a["k"], a["v"], a["la"], a["eta"], a["eps"], a["h0"], a["o"], a["hT"],
+                                   a["cu_dev"], a["cu_host"], a["n_seq"], a["N"], a["T"], a["H"], a["dk"], a["dv"],
+                                   a["chunk"], a["dt"], a["ws"], a["ws_bytes"], a["stream"])
+
+
+def test_chunk_fwd_validation_errors():
+    assert _chunk_call(q=None) == E_NULL
+    assert _chunk_call(o=None) == E_NULL
+    assert _chunk_call(eta=None) == E_NULL
+    assert _chunk_call(dk=96) == E_SHAPE
+    assert _chunk_call(dv=32) == E_SHAPE
+    assert _chunk_call(chunk=128) == E_SHAPE
+    assert _chunk_call(H=0) == E_SHAPE
+    assert _chunk_call(eps=-1.0) == E_SHAPE
+    assert _chunk_call(eps=float("nan")) == E_SHAPE
+    assert _chunk_call(dt=7) == E_DTYPE
+    assert _chunk_call(q=0x1004) == E_ALIGN
+    assert _chunk_call(h0=0x7008) == E_ALIGN
+    assert _chunk_call(ws=None) == E_WS
+    assert _chunk_call(ws=0x100010) == E_WS
+    assert _chunk_call(ws_bytes=100) == E_WS
+    cu = np.array([0, 30, 64], dtype=np.int32)
+    assert _chunk_call(n_seq=2, cu_host=cu.ctypes.data, cu_dev=None) == E_NULL
+    assert _chunk_call(n_seq=2, cu_host=None, cu_dev=0x8000) == E_NULL
+    assert _chunk_call(n_seq=2, cu_host=cu.ctypes.data, cu_dev=0x8000, N=2) == E_SHAPE
+    assert _chunk_call(n_seq=0, cu_host=cu.ctypes.data) == E_SHAPE
+    bad = np.array([0, 40, 30], dtype=np.int32)
+    assert _chunk_call(n_seq=2, cu_host=bad.ctypes.data, cu_dev=0x8000) == E_SEQ
+    bad = np.array([1, 40, 64], dtype=np.int32)
+    assert _chunk_call(n_seq=2, cu_host=bad.ctypes.data, cu_dev=0x8000) == E_SEQ
+    bad = np.array([0, 40, 63], dtype=np.int32)
+    assert _chunk_call(n_seq=2, cu_host=bad.ctypes.data, cu_dev=0x8000) == E_SEQ
+    # nothing to do: no sequences at all
+    assert _chunk_call(N=0) == OK
+
+
+def test_decode_and_beta_validation_errors():
+    lib = kla.lib()
+    d = lambda **o: lib.kla_decode_step(*[{**dict(q=0x1000, k=0x2000, v=0x3000, la=0x4000, eta=0x5000, eps=1e-6,
+                                                  S=0x6000, o=0x7000, B=2, H=2, dk=128, dv=128, dt=kla.KLA_BF16,
+                                                  st=None), **o}[n]
+                                          for n in ("q", "k", "v", "la", "eta", "eps", "S", "o", "B", "H", "dk", "dv",
+                                                    "dt", "st")])
+    assert d(S=None) == E_NULL
+    assert d(k=None) == E_NULL
+    assert d(dk=100) == E_SHAPE
+    assert d(dv=512) == E_SHAPE
+    assert d(eps=-1e-3) == E_SHAPE
+    assert d(dt=2) == E_DTYPE
+    assert d(S=0x6004) == E_ALIGN
+    assert d(B=0) == OK
+    b = lambda **o: lib.kla_beta(*[{**dict(k=0x1000, eta=0x2000, eps=1e-6, beta=0x3000, n=10, dk=128,
+                                           dt=kla.KLA_F32, st=None), **o}[n]
+                                   for n in ("k", "eta", "eps", "beta", "n", "dk", "dt", "st")])
+    assert b(k=None) == E_NULL
+    assert b(beta=None) == E_NULL
+    assert b(dk=32) == E_SHAPE
+    assert b(n=-1) == E_SHAPE
+    assert b(dt=-1) == E_DTYPE
+    assert b(k=0x1002) == E_ALIGN
+    assert b(n=0) == OK
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    x = torch.zeros((1, 64, 1, 64))
+    g = torch.zeros((1, 64, 1))
+    with pytest.raises(RuntimeError):
+        kla.kla_chunk_fwd(x, x, x, g, g, 1e-6)
+    with pytest.raises(RuntimeError):
+        kla.kla_beta(x, g, 1e-6)
