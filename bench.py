@@ -1,0 +1,196 @@
+#!/usr/bin/env python3
+"""Benchmark of the KLA hot path on one MI355X.
+
+    python bench.py --gpus 1 --steps K --warmup W
+
+A "step" is one kla_chunk_fwd call (all stages: key-norm/beta, intra-chunk, state scan, outputs)
+on the 0.4B-scale training shape: N=8, H=8, T=4096, d_k=d_v=128, chunk 64, bf16 q/k/v, fp32 gates
+and state, inputs resident in HBM.  The same JSON line also carries the decode-step figures on the
+32K-context decode shape (B=64, H=8, d=128, 256 consecutive steps), the roofline of the dominant
+kernel and the CPU oracle timed on the host cores.  Synthetic seeded inputs (kla_inputs.py).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
+# algorithmic work per token-head of the chunk path at d_k = d_v = 128, C = 64:
+CHUNK_BYTES_PER_TOKEN_HEAD = 2 * (2 * 128 + 2 * 128) + 8          # q,k,v read + o written (bf16) + two fp32 gates
+CHUNK_FLOP_PER_TOKEN_HEAD = 6 * 128 * 128 + 64 * (3 * 128 + 2 * 128)  # triangular products at half cost
+DECODE_BYTES_PER_TOKEN_HEAD = 2 * 4 * 128 * 128 + 2 * (2 * 128 + 128) + 8 + 2 * 128   # state r+w, q,k,v, gates, o
+
+
+def _events(torch, fn, reps):
+    """Average milliseconds of fn() over reps launches, by events on the current stream."""
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
+def _traffic(name):
+    """HBM bytes per launch from committed rocprofv3 --pmc runs (profiles/<name>), or None."""
+    p = os.path.join(ROOT, "profiles", name)
+    if os.path.exists(p):
+        try:
+            return json.load(open(p)).get("hbm_bytes_per_launch")
+        except Exception:
+            return None
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--skip-cpu-baseline", action="store_true")
+    ap.add_argument("--skip-decode", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build is single-GPU by design (no collectives, no sharding); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import kla_inputs
+    import paper_2605_08587_amd as kla
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    kla.lib()   # fails loudly if the HIP library is not built
+
+    # ------------------------------------------------------------------ chunk forward, config 2
+    d = kla_inputs.config(2)
+    N, T, H, dk, dv = d["N"], d["T"], d["H"], d["dk"], d["dv"]
+    dev = {n: d[n].cuda() for n in ("q", "k", "v", "log_alpha", "eta")}
+    ws = torch.empty(kla.kla_chunk_fwd_workspace_bytes(N, T, H, dk, dv, torch.bfloat16), dtype=torch.uint8, device="cuda")
+    out = torch.empty((N, T, H, dv), dtype=torch.bfloat16, device="cuda")
+    hT = torch.empty((N, H, dk, dv), dtype=torch.float32, device="cuda")
+
+    def step():
+        kla.kla_chunk_fwd(dev["q"], dev["k"], dev["v"], dev["log_alpha"], dev["eta"], d["eps"], workspace=ws, out=out, hT=hT)
+
+    def stage(i):
+        kla.kla_debug_chunk_stage(i, dev["q"], dev["k"], dev["v"], dev["log_alpha"], dev["eta"], d["eps"], ws, out, hT=hT)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    tokens = N * T
+    token_heads = N * T * H
+    value = tokens / (ms_per_step * 1e-3)
+
+    ms_intra = _events(torch, lambda: stage(1), args.steps)
+    ms_scan = _events(torch, lambda: stage(2), args.steps)
+    dom = ("scan_kernel", ms_scan) if ms_scan >= ms_intra else ("intra_kernel", ms_intra)
+    alg_bytes = CHUNK_BYTES_PER_TOKEN_HEAD * token_heads
+    achieved = alg_bytes / (dom[1] * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": dom[0], "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": _traffic("chunk_%s_config2_traffic.json" % dom[0]),
+                "algorithmic_bytes_per_launch": alg_bytes, "ms_per_launch": round(dom[1], 4),
+                "ms_intra_kernel": round(ms_intra, 4), "ms_scan_kernel": round(ms_scan, 4)}
+    tflops = CHUNK_FLOP_PER_TOKEN_HEAD * token_heads / (ms_per_step * 1e-3) / 1e12
+    mfma = {"achieved": round(tflops, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4), "flop_per_token_head": CHUNK_FLOP_PER_TOKEN_HEAD,
+            "whole_path_hbm_frac": round(alg_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+
+    # ------------------------------------------------------------------ decode, config 4
+    decode = None
+    if not args.skip_decode:
+        dd = kla_inputs.config(4)
+        B, Hd, steps = dd["B"], dd["H"], dd["steps"]
+        g = {n: dd[n].cuda() for n in ("q", "k", "v", "log_alpha", "eta")}
+        S0 = dd["S"].cuda()
+        od = torch.empty((B, Hd, dd["dv"]), dtype=torch.bfloat16, device="cuda")
+
+        def run256(states):
+            ns = len(states)
+            for t in range(steps):
+                kla.kla_decode_step(g["q"][t], g["k"][t], g["v"][t], g["log_alpha"][t], g["eta"][t], dd["eps"],
+                                    states[t % ns], out=od)
+
+        S = S0.clone()
+        run256([S])
+        reps = 5
+        ms256 = _events(torch, lambda: run256([S]), reps)
+        many = [S0.clone() for _ in range(10)]      # 10 x 33.5 MB of state: larger than the 256 MB Infinity Cache
+        run256(many)
+        ms256_cold = _events(torch, lambda: run256(many), reps)
+        bytes256 = DECODE_BYTES_PER_TOKEN_HEAD * B * Hd * steps
+        decode = {"metric": "decode_tokens_per_s", "workload": "config4: B=64,H=8,dk=dv=128,bf16 q/k/v,fp32 state,256 steps",
+                  "value": round(B * steps / (ms256 * 1e-3), 1), "unit": "tokens/s",
+                  "us_per_step": round(ms256 * 1e3 / steps, 3),
+                  "roofline": {"bound": "hbm", "kernel": "decode_kernel",
+                               "achieved": round(bytes256 / (ms256_cold * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBS,
+                               "unit": "GB/s", "frac": round(bytes256 / (ms256_cold * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                               "traffic": _traffic("decode_kernel_config4_traffic.json"),
+                               "note": "state rotated over 10 sets (335 MB) so that it cannot stay in the Infinity Cache",
+                               "us_per_step": round(ms256_cold * 1e3 / steps, 3)},
+                  "same_state_GBps": round(bytes256 / (ms256 * 1e-3) / 1e9, 1)}
+        try:   # the same 256 steps as one graph launch: shows how much of the step time is launch overhead
+            Sg = S0.clone()
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                run256([Sg])
+            torch.cuda.current_stream().wait_stream(side)
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                run256([Sg])
+            graph.replay()
+            ms_graph = _events(torch, graph.replay, reps)
+            decode["graph_us_per_step"] = round(ms_graph * 1e3 / steps, 3)
+            decode["graph_tokens_per_s"] = round(B * steps / (ms_graph * 1e-3), 1)
+        except Exception as e:  # noqa: BLE001
+            decode["graph_us_per_step"] = None
+            decode["graph_error"] = str(e)[:120]
+
+    # ------------------------------------------------------------------ CPU oracle beside it
+    cpu = None
+    parity = None
+    if not args.skip_cpu_baseline:
+        from oracle import token_oracle
+        qn, kn, vn = (kla_inputs.to_numpy_f32(d[x]) for x in "qkv")
+        la, et = d["log_alpha"].numpy(), d["eta"].numpy()
+        t0 = time.perf_counter()
+        ro, rh, nthr = token_oracle.kla_recurrent(qn, kn, vn, la, et, d["eps"])
+        dt = time.perf_counter() - t0
+        cpu = {"value": round(tokens / dt, 1), "unit": "tokens/s", "cores": nthr, "kind": "oracle",
+               "sample": "all of config 2 (64 sequence-heads x 4096 tokens), fp64 token loop, %.1f s wall" % dt}
+        step()
+        torch.cuda.synchronize()
+        parity = {"o": float("%.3e" % token_oracle.rel_err(out.float().cpu().numpy(), ro)),
+                  "hT": float("%.3e" % token_oracle.rel_err(hT.cpu().numpy(), rh)), "bar": 2e-2}
+
+    line = {"metric": "chunk_fwd_tokens_per_s", "value": round(value, 1), "unit": "tokens/s", "n_gpus": 1,
+            "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": "config2: N=8,H=8,T=4096,dk=dv=128,chunk=64,bf16 q/k/v,fp32 gates+state",
+                       "global_batch": N, "seq_len": T, "heads": H},
+            "roofline": roofline, "mfma": mfma, "decode": decode, "cpu_baseline": cpu, "parity": parity}
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

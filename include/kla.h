@@ -132,6 +132,19 @@ int kla_debug_intra_chunk(const void *q, const void *k,
                           int N, int T, int H, int dk, int chunk, kla_dtype dt,
                           void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/*
+ * Profiling hook: one stage of kla_chunk_fwd alone, so that each kernel can be timed between two
+ * events.  Arguments as in kla_chunk_fwd.  stage = 1: the intra-chunk stage (fills the workspace);
+ * stage = 2: the scan stage (consumes a workspace that stage 1 filled for the same inputs, writes
+ * o and hT).  Any other stage is KLA_ERR_SHAPE.
+ */
+int kla_debug_chunk_stage(const void *q, const void *k, const void *v,
+                          const float *log_alpha, const float *eta, float eps,
+                          const float *h0, void *o, float *hT,
+                          const int32_t *cu_seqlens_dev, const int32_t *cu_seqlens_host, int n_seq,
+                          int N, int T, int H, int dk, int dv, int chunk, kla_dtype dt,
+                          void *workspace, size_t workspace_bytes, void *hip_stream, int stage);
+
 #ifdef __cplusplus
 }
 #endif

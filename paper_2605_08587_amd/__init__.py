@@ -26,6 +26,8 @@ _SIGNATURES = {
     "kla_chunk_fwd_workspace_bytes": (ctypes.c_size_t, [ctypes.c_int] * 6 + [ctypes.c_int, _ip, ctypes.c_int]),
     "kla_chunk_fwd": (ctypes.c_int, [_vp, _vp, _vp, _fp, _fp, ctypes.c_float, _fp, _vp, _fp, _ip, _ip, ctypes.c_int]
                       + [ctypes.c_int] * 6 + [ctypes.c_int, _vp, ctypes.c_size_t, _vp]),
+    "kla_debug_chunk_stage": (ctypes.c_int, [_vp, _vp, _vp, _fp, _fp, ctypes.c_float, _fp, _vp, _fp, _ip, _ip, ctypes.c_int]
+                              + [ctypes.c_int] * 6 + [ctypes.c_int, _vp, ctypes.c_size_t, _vp, ctypes.c_int]),
     "kla_decode_step": (ctypes.c_int, [_vp, _vp, _vp, _fp, _fp, ctypes.c_float, _fp, _vp]
                         + [ctypes.c_int] * 4 + [ctypes.c_int, _vp]),
     "kla_beta": (ctypes.c_int, [_vp, _fp, ctypes.c_float, _fp, ctypes.c_long, ctypes.c_int, ctypes.c_int, _vp]),
@@ -95,7 +97,7 @@ def kla_chunk_fwd_workspace_bytes(N, T, H, dk, dv, dtype, cu_seqlens=None, chunk
 
 
 def kla_chunk_fwd(q, k, v, log_alpha, eta, eps, h0=None, cu_seqlens=None, want_hT=True, workspace=None,
-                  out=None, hT=None, chunk=64):
+                  out=None, hT=None, chunk=64, _stage=None):
     """Chunkwise forward.  q,k [N,T,H,dk], v [N,T,H,dv], gates [N,T,H] fp32; returns (o, hT).
 
     cu_seqlens: int32 device tensor [n_seq+1] for a packed batch (then N == 1).
@@ -114,12 +116,19 @@ def kla_chunk_fwd(q, k, v, log_alpha, eta, eps, h0=None, cu_seqlens=None, want_h
         out = torch.empty((N, T, H, dv), dtype=q.dtype, device=q.device)
     if hT is None and want_hT:
         hT = torch.empty((n_states, H, dk, dv), dtype=torch.float32, device=q.device)
-    rc = lib().kla_chunk_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(eta), float(eps), _ptr(h0), _ptr(out),
-                             _ptr(hT), _ptr(cu_seqlens), cu_hp, n_seq, N, T, H, dk, dv, chunk, dt,
-                             _ptr(workspace), workspace.numel() * workspace.element_size(), _stream())
+    args = (_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(eta), float(eps), _ptr(h0), _ptr(out),
+            _ptr(hT), _ptr(cu_seqlens), cu_hp, n_seq, N, T, H, dk, dv, chunk, dt,
+            _ptr(workspace), workspace.numel() * workspace.element_size(), _stream())
+    rc = lib().kla_chunk_fwd(*args) if _stage is None else lib().kla_debug_chunk_stage(*args, int(_stage))
     if rc != 0:
         raise KlaError(rc, "kla_chunk_fwd")
     return out, hT
+
+
+def kla_debug_chunk_stage(stage, q, k, v, log_alpha, eta, eps, workspace, out, hT=None, h0=None, cu_seqlens=None):
+    """Profiling hook: stage 1 (intra-chunk) or stage 2 (scan) of kla_chunk_fwd alone, on preallocated buffers."""
+    return kla_chunk_fwd(q, k, v, log_alpha, eta, eps, h0=h0, cu_seqlens=cu_seqlens, want_hT=hT is not None,
+                         workspace=workspace, out=out, hT=hT, _stage=stage)
 
 
 def kla_decode_step(q, k, v, log_alpha, eta, eps, S, out=None):

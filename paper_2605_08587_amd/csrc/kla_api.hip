@@ -73,7 +73,7 @@ int scan_waves(int n_chains, int dv, int dt)
 template <typename E>
 int chunk_fwd_impl(const void* q, const void* k, const void* v, const float* log_alpha, const float* eta, float eps,
                    const float* h0, void* o, float* hT, const int32_t* cu_dev, int n_seq, int N, int T, int H, int dk,
-                   int dv, const Plan& pl, char* ws, bool scan, float* Tb_out, float* P_out, float* g_out,
+                   int dv, const Plan& pl, char* ws, int stages, float* Tb_out, float* P_out, float* g_out,
                    hipStream_t st)
 {
     E* wsT = reinterpret_cast<E*>(ws + pl.off_T);
@@ -81,7 +81,8 @@ int chunk_fwd_impl(const void* q, const void* k, const void* v, const float* log
     float* wsG = reinterpret_cast<float*>(ws + pl.off_G);
     int* chunk_off = reinterpret_cast<int*>(ws + pl.off_C);
     const int NT = (T + 63) / 64;
-    if (n_seq > 0 && kla::launch_chunk_offsets(cu_dev, n_seq, chunk_off, st) != hipSuccess) return KLA_ERR_HIP;
+    const bool intra = (stages & 1) != 0, scan = (stages & 2) != 0, unpack = (stages & 4) != 0;
+    if (intra && n_seq > 0 && kla::launch_chunk_offsets(cu_dev, n_seq, chunk_off, st) != hipSuccess) return KLA_ERR_HIP;
 
     kla::IntraArgs<E> ia;
     ia.q = static_cast<const E*>(q); ia.k = static_cast<const E*>(k);
@@ -89,13 +90,10 @@ int chunk_fwd_impl(const void* q, const void* k, const void* v, const float* log
     ia.cu_seqlens = n_seq > 0 ? cu_dev : nullptr; ia.chunk_off = chunk_off; ia.n_seq = n_seq;
     ia.T = T; ia.NT = NT; ia.H = H;
     ia.wsT = wsT; ia.wsP = wsP; ia.wsG = wsG;
-    if (kla::launch_intra<E>(ia, dk, (int)pl.n_chunks, st) != hipSuccess) return KLA_ERR_HIP;
-
-    if (!scan) {
-        if (kla::launch_unpack<E>(wsT, wsP, wsG, Tb_out, P_out, g_out, pl.n_chunks * H, st) != hipSuccess)
-            return KLA_ERR_HIP;
-        return KLA_OK;
-    }
+    if (intra && kla::launch_intra<E>(ia, dk, (int)pl.n_chunks, st) != hipSuccess) return KLA_ERR_HIP;
+    if (unpack && kla::launch_unpack<E>(wsT, wsP, wsG, Tb_out, P_out, g_out, pl.n_chunks * H, st) != hipSuccess)
+        return KLA_ERR_HIP;
+    if (!scan) return KLA_OK;
     kla::ScanArgs<E> sa;
     sa.q = static_cast<const E*>(q); sa.k = static_cast<const E*>(k); sa.v = static_cast<const E*>(v);
     sa.h0 = h0; sa.o = static_cast<E*>(o); sa.hT = hT;
@@ -134,10 +132,10 @@ size_t kla_chunk_fwd_workspace_bytes(int N, int T, int H, int dk, int dv, int ch
     return pl.total;
 }
 
-int kla_chunk_fwd(const void* q, const void* k, const void* v, const float* log_alpha, const float* eta, float eps,
-                  const float* h0, void* o, float* hT, const int32_t* cu_seqlens_dev, const int32_t* cu_seqlens_host,
-                  int n_seq, int N, int T, int H, int dk, int dv, int chunk, kla_dtype dt, void* workspace,
-                  size_t workspace_bytes, void* hip_stream)
+static int chunk_fwd_checked(const void* q, const void* k, const void* v, const float* log_alpha, const float* eta,
+                             float eps, const float* h0, void* o, float* hT, const int32_t* cu_seqlens_dev,
+                             const int32_t* cu_seqlens_host, int n_seq, int N, int T, int H, int dk, int dv, int chunk,
+                             kla_dtype dt, void* workspace, size_t workspace_bytes, void* hip_stream, int stages)
 {
     Plan pl;
     const int rc = make_plan(N, T, H, dk, dv, chunk, (int)dt, cu_seqlens_host, n_seq, &pl);
@@ -157,9 +155,28 @@ int kla_chunk_fwd(const void* q, const void* k, const void* v, const float* log_
     char* ws = static_cast<char*>(workspace);
     if (dt == KLA_BF16)
         return chunk_fwd_impl<bf16_t>(q, k, v, log_alpha, eta, eps, h0, o, hT, cu_seqlens_dev, n_seq, N, T, H, dk, dv,
-                                      pl, ws, true, nullptr, nullptr, nullptr, st);
+                                      pl, ws, stages, nullptr, nullptr, nullptr, st);
     return chunk_fwd_impl<float>(q, k, v, log_alpha, eta, eps, h0, o, hT, cu_seqlens_dev, n_seq, N, T, H, dk, dv, pl, ws,
-                                 true, nullptr, nullptr, nullptr, st);
+                                 stages, nullptr, nullptr, nullptr, st);
+}
+
+int kla_chunk_fwd(const void* q, const void* k, const void* v, const float* log_alpha, const float* eta, float eps,
+                  const float* h0, void* o, float* hT, const int32_t* cu_seqlens_dev, const int32_t* cu_seqlens_host,
+                  int n_seq, int N, int T, int H, int dk, int dv, int chunk, kla_dtype dt, void* workspace,
+                  size_t workspace_bytes, void* hip_stream)
+{
+    return chunk_fwd_checked(q, k, v, log_alpha, eta, eps, h0, o, hT, cu_seqlens_dev, cu_seqlens_host, n_seq, N, T, H,
+                             dk, dv, chunk, dt, workspace, workspace_bytes, hip_stream, 3);
+}
+
+int kla_debug_chunk_stage(const void* q, const void* k, const void* v, const float* log_alpha, const float* eta,
+                          float eps, const float* h0, void* o, float* hT, const int32_t* cu_seqlens_dev,
+                          const int32_t* cu_seqlens_host, int n_seq, int N, int T, int H, int dk, int dv, int chunk,
+                          kla_dtype dt, void* workspace, size_t workspace_bytes, void* hip_stream, int stage)
+{
+    if (stage != 1 && stage != 2) return KLA_ERR_SHAPE;
+    return chunk_fwd_checked(q, k, v, log_alpha, eta, eps, h0, o, hT, cu_seqlens_dev, cu_seqlens_host, n_seq, N, T, H,
+                             dk, dv, chunk, dt, workspace, workspace_bytes, hip_stream, stage);
 }
 
 int kla_debug_intra_chunk(const void* q, const void* k, const float* log_alpha, const float* eta, float eps,
@@ -182,9 +199,9 @@ int kla_debug_intra_chunk(const void* q, const void* k, const float* log_alpha, 
     char* ws = static_cast<char*>(workspace);
     if (dt == KLA_BF16)
         return chunk_fwd_impl<bf16_t>(q, k, nullptr, log_alpha, eta, eps, nullptr, nullptr, nullptr, cu_seqlens_dev,
-                                      n_seq, N, T, H, dk, 64, pl, ws, false, Tb_out, P_out, g_out, st);
+                                      n_seq, N, T, H, dk, 64, pl, ws, 5, Tb_out, P_out, g_out, st);
     return chunk_fwd_impl<float>(q, k, nullptr, log_alpha, eta, eps, nullptr, nullptr, nullptr, cu_seqlens_dev, n_seq, N,
-                                 T, H, dk, 64, pl, ws, false, Tb_out, P_out, g_out, st);
+                                 T, H, dk, 64, pl, ws, 5, Tb_out, P_out, g_out, st);
 }
 
 int kla_decode_step(const void* q, const void* k, const void* v, const float* log_alpha, const float* eta, float eps,
