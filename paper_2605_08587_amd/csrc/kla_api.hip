@@ -46,7 +46,7 @@ int make_plan(int N, int T, int H, int dk, int dv, int chunk, int dt, const int3
     }
     if (n_chunks * H > 0x7fffffffL || (long)p->n_states * H * (dv / 16) > 0x7fffffffL) return KLA_ERR_SHAPE;
     p->n_chunks = n_chunks;
-    const size_t slots = (size_t)n_chunks * H * 512 * 8 * elem_bytes(dt);   // 512 slots of 8 elements per chunk-head
+    const size_t slots = (size_t)n_chunks * H * 384 * 8 * elem_bytes(dt);   // 6 tile-pairs x 64 slots of 8 elements per chunk-head
     p->off_T = 0;
     p->off_P = round256(p->off_T + slots);
     p->off_G = round256(p->off_P + slots);

@@ -197,12 +197,14 @@ __global__ __launch_bounds__(256) void intra_kernel(IntraArgs<E> a)
             if ((i >> 2) == g) Tm[(b0 + i) * kLdm + b0 + r] = x[i];
     }
     {
-        char* out = reinterpret_cast<char*>(a.wsP) + (size_t)blockIdx.x * 512 * slot_bytes<E>();
+        char* out = reinterpret_cast<char*>(a.wsP) + (size_t)blockIdx.x * kTriPairs * 64 * slot_bytes<E>();
 #pragma unroll
         for (int it = 0; it < 2; ++it) {
-            const int sl = tid + 256 * it;           // slot index: (tile row, pair) * 64 + lane
-            const int tp = sl >> 6, ln = sl & 63;
-            const int row = 16 * (tp >> 1) + (ln & 15), col = 32 * (tp & 1) + 4 * (ln >> 4);
+            const int sl = tid + 256 * it;           // slot index: stored tile-pair * 64 + lane
+            if (sl >= kTriPairs * 64) break;
+            const int ctp = sl >> 6, ln = sl & 63;
+            const int ti = ctp < 2 ? ctp : 2 + ((ctp - 2) >> 1), jp = ctp < 2 ? 0 : ((ctp - 2) & 1);
+            const int row = 16 * ti + (ln & 15), col = 32 * jp + 4 * (ln >> 4);
             floatx4 v0, v1;
             const float4 f0 = ld4(Pm + row * kLdm + col), f1 = ld4(Pm + row * kLdm + col + 16);
             v0[0] = f0.x; v0[1] = f0.y; v0[2] = f0.z; v0[3] = f0.w;
@@ -244,12 +246,14 @@ __global__ __launch_bounds__(256) void intra_kernel(IntraArgs<E> a)
 
     // ---- phase 6: T' = T diag(beta) -> workspace in operand order ------------------------------
     {
-        char* out = reinterpret_cast<char*>(a.wsT) + (size_t)blockIdx.x * 512 * slot_bytes<E>();
+        char* out = reinterpret_cast<char*>(a.wsT) + (size_t)blockIdx.x * kTriPairs * 64 * slot_bytes<E>();
 #pragma unroll
         for (int it = 0; it < 2; ++it) {
             const int sl = tid + 256 * it;
-            const int tp = sl >> 6, ln = sl & 63;
-            const int row = 16 * (tp >> 1) + (ln & 15), col = 32 * (tp & 1) + 4 * (ln >> 4);
+            if (sl >= kTriPairs * 64) break;
+            const int ctp = sl >> 6, ln = sl & 63;
+            const int ti = ctp < 2 ? ctp : 2 + ((ctp - 2) >> 1), jp = ctp < 2 ? 0 : ((ctp - 2) & 1);
+            const int row = 16 * ti + (ln & 15), col = 32 * jp + 4 * (ln >> 4);
             const float4 f0 = ld4(Tm + row * kLdm + col), f1 = ld4(Tm + row * kLdm + col + 16);
             const float4 b0 = ld4(beta_s + col), b1 = ld4(beta_s + col + 16);
             floatx4 v0, v1;
@@ -300,10 +304,11 @@ __global__ void unpack_kernel(const E* __restrict__ wsT, const E* __restrict__ w
     if (idx >= n_ch * 4096) return;
     const long ch = idx >> 12;
     const int i = (int)((idx >> 6) & 63), j = (int)(idx & 63);
-    const int tp = (i >> 4) * 2 + (j >> 5), ln = (i & 15) + 16 * ((j & 15) >> 2);
-    const size_t e = ((size_t)ch * 512 + (size_t)tp * 64 + ln) * 8 + ((j >> 4) & 1) * 4 + (j & 3);
-    Tb[idx] = to_float(wsT[e]);
-    P[idx] = to_float(wsP[e]);
+    const int ti = i >> 4, jp = j >> 5, ln = (i & 15) + 16 * ((j & 15) >> 2);
+    const bool stored = jp <= (ti >> 1);             // only the lower-triangular tile-pairs exist
+    const size_t e = ((size_t)ch * (kTriPairs * 64) + (size_t)tri_pair(ti, jp) * 64 + ln) * 8 + ((j >> 4) & 1) * 4 + (j & 3);
+    Tb[idx] = stored ? to_float(wsT[e]) : 0.f;
+    P[idx] = stored ? to_float(wsP[e]) : 0.f;
     if (j == 0) gout[ch * 64 + i] = wsG[ch * 64 + i];
 }
 template <typename E>

@@ -14,6 +14,11 @@
 // product's B operand), so the only LDS traffic is the A operands K, Q, K^T, T', P and the V
 // slice, staged once per chunk for all waves of the workgroup.  No per-chunk state, W or U ever
 // goes to HBM.
+//
+// The chunk loop is the only serial dependency of the whole forward, so its latency is what
+// counts: the next chunk's operands are fetched from global memory into registers before the
+// current chunk's products are issued, and (bf16) written to the other half of a double-buffered
+// LDS area afterwards, leaving one barrier per chunk.
 #include "kla_common.hpp"
 #include "kla_kernels.hpp"
 #include "kla_mma.hpp"
@@ -29,34 +34,48 @@ __device__ __forceinline__ floatx4 ld_acc4(const float* p)
 }  // namespace
 
 template <typename E, int DK, int NW>
+struct ScanCfg {
+    static constexpr int NTH = 64 * NW;
+    static constexpr int KB = DK / 16, KP = DK / 32;
+    static constexpr int SLW = 16 * NW;                         // state columns per workgroup
+    static constexpr int PPR = DK * (int)sizeof(E) / 16;        // 16-byte pieces per K/Q row
+    static constexpr int EPP = 16 / (int)sizeof(E);             // elements per piece
+    static constexpr int VPP = SLW * (int)sizeof(E) / 16;       // pieces per V/O slice row
+    static constexpr int SB = 2 * (int)sizeof(typename QuadT<E>::type);
+    static constexpr int OPB = 64 * DK * (int)sizeof(E);        // one K/Q operand area
+    static constexpr int TPB = kTriPairs * 64 * SB;             // one T'/P operand area
+    static constexpr int VB = NW * 2 * 64 * SB;                 // V slice area
+    static constexpr int OLD = SLW + EPP;                       // row stride of the output staging tile
+    static constexpr int OSB = 64 * OLD * (int)sizeof(E);
+    // one stage: K rows | Q rows | K transposed | T' | P | V slice | gamma_i | gamma_C/gamma_i
+    static constexpr int OFF_Q = OPB, OFF_KT = 2 * OPB, OFF_T = 3 * OPB, OFF_P = OFF_T + TPB, OFF_V = OFF_P + TPB,
+                         OFF_EG = OFF_V + VB, OFF_ED = OFF_EG + 256, STAGE = OFF_ED + 256;
+    static constexpr int STAGES = sizeof(E) == 2 ? 2 : 1;      // fp32 operands take twice the LDS: single buffer
+    static constexpr int LDS = STAGES * (STAGE + OSB);
+    static constexpr int UK = (16 * PPR + NTH - 1) / NTH;       // (4-row group, piece) units of K/Q per thread
+    static constexpr int UV = (16 * VPP + NTH - 1) / NTH;
+    static constexpr int TP16 = TPB / 16;                       // 16-byte pieces of a T'/P area
+    static constexpr int UT = (TP16 + NTH - 1) / NTH;
+    static_assert(LDS <= 160 * 1024, "LDS budget of a gfx950 CU");
+};
+
+// The next chunk's operands on their way from global memory to LDS.
+template <typename E, int DK, int NW>
+struct Prefetch {
+    typedef ScanCfg<E, DK, NW> C;
+    uint4 k[C::UK][4], q[C::UK][4], v[C::UV][4], t[C::UT], p[C::UT];
+    float gv, gl;
+};
+
+template <typename E, int DK, int NW>
 __global__ __launch_bounds__(64 * NW) void scan_kernel(ScanArgs<E> a)
 {
-    constexpr int NTH = 64 * NW;
-    constexpr int KB = DK / 16, KP = DK / 32;
-    constexpr int SLW = 16 * NW;                         // state columns per workgroup
-    constexpr int PPR = DK * (int)sizeof(E) / 16;        // 16-byte pieces per K/Q row
-    constexpr int EPP = 16 / (int)sizeof(E);             // elements per piece
-    constexpr int VPP = SLW * (int)sizeof(E) / 16;       // pieces per V/O slice row
-    constexpr int SB = slot_bytes<E>();
-    constexpr int OPB = 64 * DK * (int)sizeof(E);
-    constexpr int OLD = SLW + EPP;                       // row stride of the output staging tile
+    typedef ScanCfg<E, DK, NW> C;
+    constexpr int NTH = C::NTH, KB = C::KB, KP = C::KP, SLW = C::SLW, PPR = C::PPR, EPP = C::EPP, VPP = C::VPP;
+    constexpr int OLD = C::OLD;
     typedef typename QuadT<E>::type Quad;
 
-    __shared__ __attribute__((aligned(16))) char Krq_[OPB];
-    __shared__ __attribute__((aligned(16))) char Qrq_[OPB];
-    __shared__ __attribute__((aligned(16))) char Ktq_[OPB];
-    __shared__ __attribute__((aligned(16))) char Trq_[512 * SB];
-    __shared__ __attribute__((aligned(16))) char Prq_[512 * SB];
-    __shared__ __attribute__((aligned(16))) char Vtq_[NW * 2 * 64 * SB];
-    __shared__ __attribute__((aligned(16))) E Ost[64 * OLD];
-    __shared__ __attribute__((aligned(16))) float eg[64];
-    __shared__ __attribute__((aligned(16))) float ed[64];
-    E* Krq = reinterpret_cast<E*>(Krq_);
-    E* Qrq = reinterpret_cast<E*>(Qrq_);
-    E* Ktq = reinterpret_cast<E*>(Ktq_);
-    E* Trq = reinterpret_cast<E*>(Trq_);
-    E* Prq = reinterpret_cast<E*>(Prq_);
-    E* Vtq = reinterpret_cast<E*>(Vtq_);
+    __shared__ __attribute__((aligned(16))) char lds[C::LDS];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int r = lane & 15, g = lane >> 4;
@@ -67,8 +86,8 @@ __global__ __launch_bounds__(64 * NW) void scan_kernel(ScanArgs<E> a)
     const int nsl = a.dv / SLW;
     const int n_states = a.n_seq > 0 ? a.n_seq : a.N;
     const int n_chains = n_states * a.H;
-    const int xcd = blockIdx.x & 7, p = blockIdx.x >> 3;
-    const int chain = (p / nsl) * 8 + xcd, slice = p % nsl;
+    const int xcd = blockIdx.x & 7, pidx = blockIdx.x >> 3;
+    const int chain = (pidx / nsl) * 8 + xcd, slice = pidx % nsl;
     if (chain >= n_chains) return;
     const int s = chain / a.H, h = chain % a.H;
     long t0; int len, ch0;
@@ -86,76 +105,101 @@ __global__ __launch_bounds__(64 * NW) void scan_kernel(ScanArgs<E> a)
 
     const size_t kq_stride = (size_t)a.H * DK, v_stride = (size_t)a.H * a.dv;
 
-    for (int c = 0; c < nch; ++c) {
+    // ---- global -> registers: everything chunk c needs -------------------------------------------
+    auto fetch = [&](int c, Prefetch<E, DK, NW>& pf) {
         const long tok0 = t0 + 64L * c;
         const int clen = min(64, len - 64 * c);
         const size_t ch = (size_t)(ch0 + c) * a.H + h;
-
-        __syncthreads();   // every wave is done with the previous chunk's operands and staging tile
-
-        // ---- stage this chunk's operands in LDS ------------------------------------------------
-        {
-            const E* kb = a.k + (size_t)tok0 * kq_stride + (size_t)h * DK;
-            const E* qb = a.q + (size_t)tok0 * kq_stride + (size_t)h * DK;
-            constexpr int UNITS = 16 * PPR;              // (4-row group, piece) units of a K/Q tile
+        const E* kb = a.k + (size_t)tok0 * kq_stride + (size_t)h * DK;
+        const E* qb = a.q + (size_t)tok0 * kq_stride + (size_t)h * DK;
+        const E* vb = a.v + (size_t)tok0 * v_stride + (size_t)h * a.dv + slice * SLW;
 #pragma unroll
-            for (int it = 0; it < (UNITS + NTH - 1) / NTH; ++it) {
-                const int u = tid + NTH * it;
-                if (UNITS % NTH == 0 || u < UNITS) {
-                    const int tq = u / PPR, piece = u % PPR;
-                    uint4 kd[4], qd[4];
+        for (int it = 0; it < C::UK; ++it) {
+            const int u = tid + NTH * it;
+            const int tq = u / PPR, piece = u % PPR;
 #pragma unroll
-                    for (int rr = 0; rr < 4; ++rr) {
-                        const int row = 4 * tq + rr;
-                        kd[rr] = make_uint4(0, 0, 0, 0); qd[rr] = make_uint4(0, 0, 0, 0);
-                        if (row < clen) {
-                            kd[rr] = *reinterpret_cast<const uint4*>(kb + (size_t)row * kq_stride + piece * EPP);
-                            qd[rr] = *reinterpret_cast<const uint4*>(qb + (size_t)row * kq_stride + piece * EPP);
-                        }
-                    }
-#pragma unroll
-                    for (int rr = 0; rr < 4; ++rr) {
-                        store_rq_piece(Krq, KP, 4 * tq + rr, piece, kd[rr]);
-                        store_rq_piece(Qrq, KP, 4 * tq + rr, piece, qd[rr]);
-                    }
-                    store_tq_rows(Ktq, 2, tq, piece, kd, 0);
+            for (int rr = 0; rr < 4; ++rr) {
+                const int row = 4 * tq + rr;
+                pf.k[it][rr] = make_uint4(0, 0, 0, 0); pf.q[it][rr] = make_uint4(0, 0, 0, 0);
+                if (((16 * PPR) % NTH == 0 || u < 16 * PPR) && row < clen) {
+                    pf.k[it][rr] = *reinterpret_cast<const uint4*>(kb + (size_t)row * kq_stride + piece * EPP);
+                    pf.q[it][rr] = *reinterpret_cast<const uint4*>(qb + (size_t)row * kq_stride + piece * EPP);
                 }
-            }
-            const E* vb = a.v + (size_t)tok0 * v_stride + (size_t)h * a.dv + slice * SLW;
-            constexpr int VUNITS = 16 * VPP;
-#pragma unroll
-            for (int it = 0; it < (VUNITS + NTH - 1) / NTH; ++it) {
-                const int u = tid + NTH * it;
-                if (VUNITS % NTH == 0 || u < VUNITS) {
-                    const int tq = u / VPP, pv = u % VPP;
-                    uint4 vd[4];
-#pragma unroll
-                    for (int rr = 0; rr < 4; ++rr) {
-                        const int row = 4 * tq + rr;
-                        vd[rr] = make_uint4(0, 0, 0, 0);
-                        if (row < clen) vd[rr] = *reinterpret_cast<const uint4*>(vb + (size_t)row * v_stride + pv * EPP);
-                    }
-                    store_tq_rows(Vtq, 2, tq, pv, vd, 0);
-                }
-            }
-            const uint4* tsrc = reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(a.wsT) + ch * 512 * SB);
-            const uint4* psrc = reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(a.wsP) + ch * 512 * SB);
-            constexpr int TP16 = 512 * SB / 16;
-#pragma unroll
-            for (int it = 0; it < TP16 / NTH; ++it) {
-                const int i = tid + NTH * it;
-                reinterpret_cast<uint4*>(Trq_)[i] = tsrc[i];
-                reinterpret_cast<uint4*>(Prq_)[i] = psrc[i];
-            }
-            if (tid < 64) {
-                const float gv = a.wsG[ch * 64 + tid], gl = a.wsG[ch * 64 + 63];
-                eg[tid] = expf(gv);                      // gamma_i
-                ed[tid] = expf(gl - gv);                 // gamma_C / gamma_i
             }
         }
-        __syncthreads();
+#pragma unroll
+        for (int it = 0; it < C::UV; ++it) {
+            const int u = tid + NTH * it;
+            const int tq = u / VPP, pv = u % VPP;
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) {
+                const int row = 4 * tq + rr;
+                pf.v[it][rr] = make_uint4(0, 0, 0, 0);
+                if (((16 * VPP) % NTH == 0 || u < 16 * VPP) && row < clen)
+                    pf.v[it][rr] = *reinterpret_cast<const uint4*>(vb + (size_t)row * v_stride + pv * EPP);
+            }
+        }
+        const uint4* tsrc = reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(a.wsT) + ch * C::TPB);
+        const uint4* psrc = reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(a.wsP) + ch * C::TPB);
+#pragma unroll
+        for (int it = 0; it < C::UT; ++it) {
+            const int i = tid + NTH * it;
+            pf.t[it] = make_uint4(0, 0, 0, 0); pf.p[it] = make_uint4(0, 0, 0, 0);
+            if (C::TP16 % NTH == 0 || i < C::TP16) { pf.t[it] = tsrc[i]; pf.p[it] = psrc[i]; }
+        }
+        pf.gv = a.wsG[ch * 64 + (tid & 63)];
+        pf.gl = a.wsG[ch * 64 + 63];
+    };
 
-        // ---- the chunk recurrence for this wave's 16 columns ------------------------------------
+    // ---- registers -> LDS stage, in MFMA operand order ----------------------------------------
+    auto stash = [&](const Prefetch<E, DK, NW>& pf, char* st) {
+        E* Krq = reinterpret_cast<E*>(st);
+        E* Qrq = reinterpret_cast<E*>(st + C::OFF_Q);
+        E* Ktq = reinterpret_cast<E*>(st + C::OFF_KT);
+        E* Vtq = reinterpret_cast<E*>(st + C::OFF_V);
+#pragma unroll
+        for (int it = 0; it < C::UK; ++it) {
+            const int u = tid + NTH * it;
+            if ((16 * PPR) % NTH == 0 || u < 16 * PPR) {
+                const int tq = u / PPR, piece = u % PPR;
+#pragma unroll
+                for (int rr = 0; rr < 4; ++rr) {
+                    store_rq_piece(Krq, KP, 4 * tq + rr, piece, pf.k[it][rr]);
+                    store_rq_piece(Qrq, KP, 4 * tq + rr, piece, pf.q[it][rr]);
+                }
+                store_tq_rows(Ktq, 2, tq, piece, pf.k[it], 0);
+            }
+        }
+#pragma unroll
+        for (int it = 0; it < C::UV; ++it) {
+            const int u = tid + NTH * it;
+            if ((16 * VPP) % NTH == 0 || u < 16 * VPP) store_tq_rows(Vtq, 2, u / VPP, u % VPP, pf.v[it], 0);
+        }
+#pragma unroll
+        for (int it = 0; it < C::UT; ++it) {
+            const int i = tid + NTH * it;
+            if (C::TP16 % NTH == 0 || i < C::TP16) {
+                reinterpret_cast<uint4*>(st + C::OFF_T)[i] = pf.t[it];
+                reinterpret_cast<uint4*>(st + C::OFF_P)[i] = pf.p[it];
+            }
+        }
+        if (tid < 64) {
+            reinterpret_cast<float*>(st + C::OFF_EG)[tid] = expf(pf.gv);            // gamma_i
+            reinterpret_cast<float*>(st + C::OFF_ED)[tid] = expf(pf.gl - pf.gv);    // gamma_C / gamma_i
+        }
+    };
+
+    // ---- the chunk recurrence for this wave's 16 columns, operands from LDS stage `st` ----------
+    auto compute = [&](const char* st, E* Ost) {
+        const E* Krq = reinterpret_cast<const E*>(st);
+        const E* Qrq = reinterpret_cast<const E*>(st + C::OFF_Q);
+        const E* Ktq = reinterpret_cast<const E*>(st + C::OFF_KT);
+        const E* Trq = reinterpret_cast<const E*>(st + C::OFF_T);
+        const E* Prq = reinterpret_cast<const E*>(st + C::OFF_P);
+        const E* Vtq = reinterpret_cast<const E*>(st + C::OFF_V);
+        const float* eg = reinterpret_cast<const float*>(st + C::OFF_EG);
+        const float* ed = reinterpret_cast<const float*>(st + C::OFF_ED);
+
         Quad Sq[KB];
 #pragma unroll
         for (int kt = 0; kt < KB; ++kt) Sq[kt] = acc_to_quad<E>(S[kt]);
@@ -189,23 +233,13 @@ __global__ __launch_bounds__(64 * NW) void scan_kernel(ScanArgs<E> a)
             U[it] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int jp = 0; jp <= (it >> 1); ++jp) {   // T' is lower triangular
-                const Slot<E> st = load_slot(Trq, it * 2 + jp, lane);
-                mma32<E>(U[it], st, Xq[2 * jp], Xq[2 * jp + 1]);
+                const Slot<E> sl = load_slot(Trq, tri_pair(it, jp), lane);
+                mma32<E>(U[it], sl, Xq[2 * jp], Xq[2 * jp + 1]);
             }
             Uq[it] = acc_to_quad<E>(U[it]);
             Udq[it] = acc_to_quad<E>(U[it] * ld_acc4(ed + 16 * it + 4 * g));
         }
-#pragma unroll
-        for (int it = 0; it < 4; ++it) {
-            floatx4 o = egv[it] * qs[it];
-#pragma unroll
-            for (int jp = 0; jp <= (it >> 1); ++jp) {   // P is lower triangular
-                const Slot<E> sp = load_slot(Prq, it * 2 + jp, lane);
-                mma32<E>(o, sp, Uq[2 * jp], Uq[2 * jp + 1]);
-            }
-#pragma unroll
-            for (int e = 0; e < 4; ++e) Ost[(16 * it + 4 * g + e) * OLD + 16 * wave + r] = from_float<E>(o[e]);
-        }
+        // state first: it is the only thing the next chunk waits for
         const float gC = eg[63];
 #pragma unroll
         for (int kt = 0; kt < KB; ++kt) {
@@ -216,19 +250,68 @@ __global__ __launch_bounds__(64 * NW) void scan_kernel(ScanArgs<E> a)
                 mma32<E>(S[kt], sk, Udq[2 * jp], Udq[2 * jp + 1]);
             }
         }
-        __syncthreads();
-
-        // ---- write the output rows of this slice, 16 bytes per lane ----------------------------
-        {
-            E* ob = a.o + (size_t)tok0 * v_stride + (size_t)h * a.dv + slice * SLW;
 #pragma unroll
-            for (int it = 0; it < (64 * VPP + NTH - 1) / NTH; ++it) {
-                const int i = tid + NTH * it;
-                const int row = i / VPP, pv = i % VPP;
-                if (row < clen)
-                    *reinterpret_cast<uint4*>(ob + (size_t)row * v_stride + pv * EPP) =
-                        *reinterpret_cast<const uint4*>(Ost + row * OLD + pv * EPP);
+        for (int it = 0; it < 4; ++it) {
+            floatx4 o = egv[it] * qs[it];
+#pragma unroll
+            for (int jp = 0; jp <= (it >> 1); ++jp) {   // P is lower triangular
+                const Slot<E> sp = load_slot(Prq, tri_pair(it, jp), lane);
+                mma32<E>(o, sp, Uq[2 * jp], Uq[2 * jp + 1]);
             }
+#pragma unroll
+            for (int e = 0; e < 4; ++e) Ost[(16 * it + 4 * g + e) * OLD + 16 * wave + r] = from_float<E>(o[e]);
+        }
+    };
+
+    // ---- staged output tile -> global, 16 bytes per lane ----------------------------------------
+    auto write_out = [&](int c, const E* Ost) {
+        const long tok0 = t0 + 64L * c;
+        const int clen = min(64, len - 64 * c);
+        E* ob = a.o + (size_t)tok0 * v_stride + (size_t)h * a.dv + slice * SLW;
+#pragma unroll
+        for (int it = 0; it < (64 * VPP + NTH - 1) / NTH; ++it) {
+            const int i = tid + NTH * it;
+            const int row = i / VPP, pv = i % VPP;
+            if (row < clen)
+                *reinterpret_cast<uint4*>(ob + (size_t)row * v_stride + pv * EPP) =
+                    *reinterpret_cast<const uint4*>(Ost + row * OLD + pv * EPP);
+        }
+    };
+
+    Prefetch<E, DK, NW> pf;
+    if constexpr (C::STAGES == 2) {
+        char* stage0 = lds;
+        char* stage1 = lds + C::STAGE;
+        E* ost0 = reinterpret_cast<E*>(lds + 2 * C::STAGE);
+        E* ost1 = reinterpret_cast<E*>(lds + 2 * C::STAGE + C::OSB);
+        if (nch > 0) { fetch(0, pf); stash(pf, stage0); }
+        __syncthreads();
+        for (int c = 0; c < nch; ++c) {
+            char* cur = (c & 1) ? stage1 : stage0;
+            char* nxt = (c & 1) ? stage0 : stage1;
+            E* ost = (c & 1) ? ost1 : ost0;
+            const bool more = c + 1 < nch;
+            if (more) fetch(c + 1, pf);                  // in flight while this chunk's products run
+            compute(cur, ost);
+            if (more) stash(pf, nxt);
+            // One barrier per chunk.  It orders (i) this chunk's staged outputs before their write-out,
+            // (ii) the next chunk's operands before their use, (iii) all reads of `cur` before it is
+            // overwritten one iteration later, and (iv) the write-out of chunk c-1 (done by every wave
+            // before it arrives here) before `ost` of that parity is staged again in chunk c+1.
+            __syncthreads();
+            write_out(c, ost);
+        }
+    } else {
+        char* stage0 = lds;
+        E* ost = reinterpret_cast<E*>(lds + C::STAGE);
+        for (int c = 0; c < nch; ++c) {
+            __syncthreads();                             // previous chunk's operands and staging tile are free
+            fetch(c, pf);
+            stash(pf, stage0);
+            __syncthreads();
+            compute(stage0, ost);
+            __syncthreads();
+            write_out(c, ost);
         }
     }
 

@@ -24,9 +24,13 @@ __device__ __forceinline__ uint32_t float_to_bf16_bits(float f)
     u += 0x7fffu + ((u >> 16) & 1u);                                    // round to nearest even
     return u >> 16;
 }
+// two fp32 -> packed bf16 pair, round to nearest even (one v_cvt_pk_bf16_f32 on gfx950)
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
 {
-    return float_to_bf16_bits(lo) | (float_to_bf16_bits(hi) << 16);
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    typedef float floatx2_t __attribute__((ext_vector_type(2)));
+    const floatx2_t f = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2_t));
 }
 
 template <typename T> __device__ __forceinline__ T from_float(float f);

@@ -39,6 +39,11 @@ template <typename E> struct Slot { typename QuadT<E>::type q0, q1; };
 
 template <typename E> constexpr int slot_bytes() { return 2 * (int)sizeof(typename QuadT<E>::type); }
 
+// T' and P are lower triangular: of the 8 tile-pairs (tile row it, pair jp) of a 64x64 operand only
+// the 6 with jp <= it/2 are stored, in this order.
+constexpr int kTriPairs = 6;
+__host__ __device__ constexpr int tri_pair(int it, int jp) { return it < 2 ? it : 2 * it - 2 + jp; }
+
 // ---- conversions between accumulator tiles and quads -------------------------------------
 __device__ __forceinline__ uint2 make_quad(floatx4 x, bf16_t)
 {
