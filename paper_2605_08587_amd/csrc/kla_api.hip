@@ -101,6 +101,11 @@ int chunk_fwd_impl(const void* q, const void* k, const void* v, const float* log
     sa.N = N; sa.T = T; sa.NT = NT; sa.H = H; sa.dv = dv;
     sa.wsT = wsT; sa.wsP = wsP; sa.wsG = wsG;
     const int waves = scan_waves(pl.n_states * H, dv, sizeof(E) == 2 ? KLA_BF16 : KLA_F32);
+    if constexpr (sizeof(E) == 2) {
+        const char* impl = getenv("KLA_SCAN_IMPL");   // "generic": the element-type-generic kernel (A/B testing)
+        if (!(impl && impl[0] == 'g'))
+            return kla::launch_scan_bf16(sa, dk, waves, st) == hipSuccess ? KLA_OK : KLA_ERR_HIP;
+    }
     if (kla::launch_scan<E>(sa, dk, waves, st) != hipSuccess) return KLA_ERR_HIP;
     return KLA_OK;
 }

@@ -40,6 +40,14 @@ template <> __device__ __forceinline__ bf16_t from_float<bf16_t>(float f)
     bf16_t r; r.bits = (uint16_t)float_to_bf16_bits(f); return r;
 }
 
+// Compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>).  Used where a
+// register array must be indexed by constants from the start (so that it never becomes a stack object).
+template <int I> struct IntC { static constexpr int value = I; constexpr operator int() const { return I; } };
+template <int N, int I = 0, typename F> __device__ __forceinline__ void static_for(F&& f)
+{
+    if constexpr (I < N) { f(IntC<I>()); static_for<N, I + 1>(f); }
+}
+
 __device__ __forceinline__ float wave_sum(float x)
 {
 #pragma unroll
