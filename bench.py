@@ -103,7 +103,7 @@ def main():
 
     ms_intra = _events(torch, lambda: stage(1), args.steps)
     ms_scan = _events(torch, lambda: stage(2), args.steps)
-    dom = ("scan_kernel", ms_scan) if ms_scan >= ms_intra else ("intra_kernel", ms_intra)
+    dom = ("scan_bf16_kernel", ms_scan) if ms_scan >= ms_intra else ("intra_kernel", ms_intra)
     alg_bytes = CHUNK_BYTES_PER_TOKEN_HEAD * token_heads
     achieved = alg_bytes / (dom[1] * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": dom[0], "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",

@@ -100,6 +100,7 @@ int chunk_fwd_impl(const void* q, const void* k, const void* v, const float* log
     sa.cu_seqlens = ia.cu_seqlens; sa.chunk_off = chunk_off; sa.n_seq = n_seq;
     sa.N = N; sa.T = T; sa.NT = NT; sa.H = H; sa.dv = dv;
     sa.wsT = wsT; sa.wsP = wsP; sa.wsG = wsG;
+    { const char* dbg = getenv("KLA_SCAN_DEBUG"); sa.debug = dbg ? atoi(dbg) : 0; }
     const int waves = scan_waves(pl.n_states * H, dv, sizeof(E) == 2 ? KLA_BF16 : KLA_F32);
     if constexpr (sizeof(E) == 2) {
         const char* impl = getenv("KLA_SCAN_IMPL");   // "generic": the element-type-generic kernel (A/B testing)

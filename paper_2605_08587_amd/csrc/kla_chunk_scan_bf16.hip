@@ -344,9 +344,9 @@ __global__ __launch_bounds__(64 * NW) void scan_bf16_kernel(ScanArgs<bf16_t> a)
         char* nxt = (c & 1) ? stage0 : stage1;
         char* ost = (c & 1) ? ost1 : ost0;
         const bool more = c + 1 < nch;
-        if (more) fetch(c + 1, pf);                      // in flight while this chunk's products run
-        compute(cur, ost);
-        if (more) stash(pf, nxt);
+        if (more && !(a.debug & 1)) fetch(c + 1, pf);                      // in flight while this chunk's products run
+        if (!(a.debug & 2)) compute(cur, ost);
+        if (more && !(a.debug & 4)) stash(pf, nxt);
         // One barrier per chunk: staged outputs before their write-out; the next chunk's operands
         // before their use; all reads of `cur` before it is overwritten one iteration later; and the
         // write-out of chunk c-1 (finished by every wave before it arrives here) before the staging

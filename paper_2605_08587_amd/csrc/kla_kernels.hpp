@@ -34,6 +34,7 @@ template <typename E> struct ScanArgs {
     const int* cu_seqlens; const int* chunk_off; int n_seq;
     int N, T, NT, H, dv;
     const E* wsT; const E* wsP; const float* wsG;
+    int debug;
 };
 // waves = 1, 2 or 4: each wave of a workgroup carries 16 state columns through the whole sequence
 template <typename E> hipError_t launch_scan(const ScanArgs<E>& a, int dk, int waves, hipStream_t st);
