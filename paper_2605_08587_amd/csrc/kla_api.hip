@@ -46,10 +46,11 @@ int make_plan(int N, int T, int H, int dk, int dv, int chunk, int dt, const int3
     }
     if (n_chunks * H > 0x7fffffffL || (long)p->n_states * H * (dv / 16) > 0x7fffffffL) return KLA_ERR_SHAPE;
     p->n_chunks = n_chunks;
-    const size_t slots = (size_t)n_chunks * H * 384 * 8 * elem_bytes(dt);   // 6 tile-pairs x 64 slots of 8 elements per chunk-head
+    // per chunk-head one record [T' | P], each 6 tile-pairs x 64 slots of 8 elements
+    const size_t half = (size_t)384 * 8 * elem_bytes(dt);
     p->off_T = 0;
-    p->off_P = round256(p->off_T + slots);
-    p->off_G = round256(p->off_P + slots);
+    p->off_P = half;
+    p->off_G = round256((size_t)n_chunks * H * (2 * half + 512));   // + gamma_i, gamma_C/gamma_i (64 fp32 each)
     p->off_C = round256(p->off_G + (size_t)n_chunks * H * 64 * sizeof(float));
     p->total = round256(p->off_C + (size_t)(n_seq + 1) * sizeof(int32_t));
     return KLA_OK;

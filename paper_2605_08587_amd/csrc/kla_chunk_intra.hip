@@ -127,6 +127,12 @@ __global__ __launch_bounds__(256) void intra_kernel(IntraArgs<E> a)
             }
             g_s[lane] = x;
             a.wsG[(size_t)blockIdx.x * 64 + lane] = x;
+            // decay factors the scan stage multiplies with: gamma_i and gamma_C / gamma_i
+            const float gl = __shfl(x, 63, kWave);
+            float* dec = reinterpret_cast<float*>(reinterpret_cast<char*>(a.wsT) + (size_t)blockIdx.x * ws_record_bytes<E>()
+                                                  + 2 * ws_half_bytes<E>());
+            dec[lane] = expf(x);
+            dec[64 + lane] = expf(gl - x);
         }
     }
     __syncthreads();
@@ -197,7 +203,7 @@ __global__ __launch_bounds__(256) void intra_kernel(IntraArgs<E> a)
             if ((i >> 2) == g) Tm[(b0 + i) * kLdm + b0 + r] = x[i];
     }
     {
-        char* out = reinterpret_cast<char*>(a.wsP) + (size_t)blockIdx.x * kTriPairs * 64 * slot_bytes<E>();
+        char* out = reinterpret_cast<char*>(a.wsP) + (size_t)blockIdx.x * ws_record_bytes<E>();
 #pragma unroll
         for (int it = 0; it < 2; ++it) {
             const int sl = tid + 256 * it;           // slot index: stored tile-pair * 64 + lane
@@ -246,7 +252,7 @@ __global__ __launch_bounds__(256) void intra_kernel(IntraArgs<E> a)
 
     // ---- phase 6: T' = T diag(beta) -> workspace in operand order ------------------------------
     {
-        char* out = reinterpret_cast<char*>(a.wsT) + (size_t)blockIdx.x * kTriPairs * 64 * slot_bytes<E>();
+        char* out = reinterpret_cast<char*>(a.wsT) + (size_t)blockIdx.x * ws_record_bytes<E>();
 #pragma unroll
         for (int it = 0; it < 2; ++it) {
             const int sl = tid + 256 * it;
@@ -306,7 +312,7 @@ __global__ void unpack_kernel(const E* __restrict__ wsT, const E* __restrict__ w
     const int i = (int)((idx >> 6) & 63), j = (int)(idx & 63);
     const int ti = i >> 4, jp = j >> 5, ln = (i & 15) + 16 * ((j & 15) >> 2);
     const bool stored = jp <= (ti >> 1);             // only the lower-triangular tile-pairs exist
-    const size_t e = ((size_t)ch * (kTriPairs * 64) + (size_t)tri_pair(ti, jp) * 64 + ln) * 8 + ((j >> 4) & 1) * 4 + (j & 3);
+    const size_t e = (size_t)ch * (ws_record_bytes<E>() / sizeof(E)) + ((size_t)tri_pair(ti, jp) * 64 + ln) * 8 + ((j >> 4) & 1) * 4 + (j & 3);
     Tb[idx] = stored ? to_float(wsT[e]) : 0.f;
     P[idx] = stored ? to_float(wsP[e]) : 0.f;
     if (j == 0) gout[ch * 64 + i] = wsG[ch * 64 + i];

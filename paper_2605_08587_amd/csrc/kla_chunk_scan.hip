@@ -139,8 +139,8 @@ __global__ __launch_bounds__(64 * NW) void scan_kernel(ScanArgs<E> a)
                     pf.v[it][rr] = *reinterpret_cast<const uint4*>(vb + (size_t)row * v_stride + pv * EPP);
             }
         }
-        const uint4* tsrc = reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(a.wsT) + ch * C::TPB);
-        const uint4* psrc = reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(a.wsP) + ch * C::TPB);
+        const uint4* tsrc = reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(a.wsT) + ch * ws_record_bytes<E>());
+        const uint4* psrc = reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(a.wsP) + ch * ws_record_bytes<E>());
 #pragma unroll
         for (int it = 0; it < C::UT; ++it) {
             const int i = tid + NTH * it;

@@ -1,9 +1,14 @@
-// bf16 inter-chunk stage: same recurrence as kla_chunk_scan.hip (eqs. (6)-(8) per chunk, the fp32
-// state of 16 columns per wave held in MFMA accumulators for the whole sequence), tuned for the
-// latency of the serial chunk loop on gfx950:
+// bf16 inter-chunk stage: the recurrence of eqs. (6)-(8) per chunk, with the fp32 state of 16 columns
+// per wave held in MFMA accumulators for the whole sequence (see kla_chunk_scan.hip for the algebra),
+// built around the latency of the serial chunk loop on gfx950:
 //
-//   * K, Q and the V slice are staged in LDS as plain token-major rows (16-byte columns XOR-swizzled
-//     by the row), written with full 128-bit stores in the order they arrive from global memory.
+//   * Operands go global memory -> LDS directly (global_load_lds_dwordx4: lane l's 16 bytes land at
+//     LDS base + 16 l, the global address is free per lane), two chunks ahead into a three-stage LDS
+//     ring, so no registers and no LDS store instructions are spent on staging and a chunk's operands
+//     have two chunk times to arrive.  One barrier per chunk.
+//   * K, Q and the V slice sit in LDS as plain token-major rows; the 16-byte columns of K and Q are
+//     XOR-swizzled by the row (applied on the global side of the copy) so that both kinds of read
+//     below are spread over the banks.
 //   * A operands whose contraction runs along a row (K S, Q S) are single 128-bit LDS reads of 8
 //     consecutive features.  To make that match the accumulator-as-B-operand trick of kla_mma.hpp,
 //     the state tiles carry a permuted feature index: element e of lane (r, g) of state tile
@@ -13,10 +18,9 @@
 //     (ds_read_b64_tr_b16): in each group of 16 lanes, lane j supplies the address of 4 consecutive
 //     elements, lanes 4a..4a+3 together forming row a of a 4x16 block, and lane i receives column
 //     i of that block.  No transposed copy of K exists anywhere.
-//   * LDS reads are issued in batches ahead of the MFMAs that consume them, the next chunk's
-//     operands travel global -> registers -> other LDS stage behind the current chunk's products,
-//     and there is one barrier per chunk.
-//   * A short last chunk is handled without branches: rows beyond it re-read the last valid row;
+//   * Every per-lane LDS offset is computed once before the loop; inside it an access is
+//     stage base + lane offset + immediate.
+//   * A short last chunk is handled without zero filling: rows beyond it re-read the last valid row;
 //     their T' rows and columns are zero (beta = 0 there), so they contribute nothing to U, to the
 //     state or to any stored output.
 #include "kla_common.hpp"
@@ -28,24 +32,36 @@ namespace kla {
 namespace {
 
 typedef short short4v __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) short4v* lds_short4_ptr;
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // native 128-bit register value (never a stack object)
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ u32x4 ld16(const void* p) { return *reinterpret_cast<const u32x4*>(p); }
 __device__ __forceinline__ void st16(void* p, u32x4 v) { *reinterpret_cast<u32x4*>(p) = v; }
-typedef __attribute__((address_space(3))) short4v* lds_short4_ptr;
 
-// 16-byte column swizzle of a token-major LDS tile: rows t..t+7 of one logical column land in 8
-// different bank groups (conflict-free 128-bit row reads), and the 16 lanes of a transposing read
-// (4 rows x 4 columns) land on 8 groups, two lanes each.
-__device__ __forceinline__ int swz(int col16, int row)
-{
-    return col16 ^ (((row & 1) << 2) | ((row >> 1) & 3));
-}
+// low three bits of the 16-byte column index are XORed with this function of the row
+__device__ __forceinline__ int swz_bits(int row) { return ((row & 1) << 2) | ((row >> 1) & 3); }
 
 __device__ __forceinline__ u32x2 lds_read_tr(const char* p)
 {
     const short4v v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(p));
     return __builtin_bit_cast(u32x2, v);
+}
+
+// 16 bytes per lane, global -> LDS without passing through registers: lane l's bytes land at
+// lds_wave_base + 16 l.  `lds_wave_base` must be wave-uniform (it goes to M0).  Written as inline
+// assembly on purpose: the compiler then keeps no book of these copies, so it puts no wait for them in
+// front of LDS reads of OTHER ring stages; completion is awaited explicitly (wait_vmcnt + barrier).
+__device__ __forceinline__ void dma16(const void* gptr, char* lds_wave_base)
+{
+    const uint32_t m = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) char*)lds_wave_base);
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(m) : "memory");
+}
+
+// s_waitcnt on the vector-memory counter only (gfx9 encoding: vmcnt in bits 3:0 and 15:14)
+template <int N> __device__ __forceinline__ void wait_vmcnt()
+{
+    static_assert(N >= 0 && N < 64, "6-bit counter");
+    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
 }
 
 __device__ __forceinline__ void mma_bf16(floatx4& acc, u32x4 a, u32x2 b0, u32x2 b1)
@@ -67,38 +83,36 @@ __device__ __forceinline__ u32x2 to_quad(floatx4 x)
 __device__ __forceinline__ floatx4 quad_to_f(u32x2 q)
 {
     floatx4 r;
-    r[0] = bf16_bits_to_float(q.x & 0xffffu); r[1] = bf16_bits_to_float(q.x >> 16);
-    r[2] = bf16_bits_to_float(q.y & 0xffffu); r[3] = bf16_bits_to_float(q.y >> 16);
+    r[0] = __uint_as_float(q.x << 16); r[1] = __uint_as_float(q.x & 0xffff0000u);
+    r[2] = __uint_as_float(q.y << 16); r[3] = __uint_as_float(q.y & 0xffff0000u);
     return r;
 }
-__device__ __forceinline__ floatx4 ld_f4(const float* p) { return *reinterpret_cast<const floatx4*>(p); }
+__device__ __forceinline__ floatx4 ld_f4(const char* p) { return *reinterpret_cast<const floatx4*>(p); }
 
 template <int DK, int NW>
 struct Cfg {
     static constexpr int NTH = 64 * NW;
     static constexpr int KB = DK / 16, KP = DK / 32;
     static constexpr int SLW = 16 * NW;                  // state columns per workgroup
-    static constexpr int RB = DK * 2;                    // bytes per K/Q row in LDS
+    static constexpr int RB = DK * 2;                    // bytes per K/Q row
     static constexpr int PPR = DK / 8;                   // 16-byte pieces per K/Q row
-    static constexpr int VPP = SLW / 8;                  // pieces per V/O slice row
-    static constexpr int VRB = SLW * 2 + 16;             // padded V / O row stride in LDS
-    static constexpr int TPB = kTriPairs * 64 * 16;      // bytes of one T' or P area
-    static constexpr int OFF_Q = 64 * RB, OFF_T = 2 * 64 * RB, OFF_P = OFF_T + TPB, OFF_V = OFF_P + TPB,
-                         OFF_EG = OFF_V + 64 * VRB, OFF_ED = OFF_EG + 256, STAGE = OFF_ED + 256;
-    static constexpr int OSB = 64 * VRB;                 // output staging tile
-    static constexpr int LDS = 2 * (STAGE + OSB);
-    static constexpr int UKQ = 64 * PPR / NTH;           // K (and Q) pieces per thread
-    static constexpr int UV = 64 * VPP / NTH;            // V pieces per thread (= 2)
-    static constexpr int TP16 = TPB / 16;
-    static constexpr int UT = (TP16 + NTH - 1) / NTH;
-    static_assert(64 * PPR % NTH == 0 && 64 * VPP % NTH == 0, "piece counts must divide");
-    static_assert(LDS <= 160 * 1024, "LDS budget of a gfx950 CU");
-};
-
-template <int DK, int NW> struct Pref {
-    typedef Cfg<DK, NW> C;
-    u32x4 k[C::UKQ], q[C::UKQ], v[C::UV], t[C::UT], p[C::UT];
-    float gv, gl;
+    static constexpr int RPB = 1024 / RB;                // K/Q rows per 1 KiB copy block
+    static constexpr int NKB = 64 / RPB;                 // copy blocks of a K (or Q) tile
+    static constexpr int VRW = SLW * 2;                  // bytes per V slice row (unpadded: filled by the copy engine)
+    static constexpr int VPP = VRW / 16;                 // pieces per V row
+    static constexpr int RPV = 64 / VPP;                 // V rows per copy block
+    static constexpr int NVB = 64 / RPV;                 // copy blocks of the V slice (= 2 NW)
+    static constexpr int TPB = kTriPairs * 64 * 16;      // bytes of one T' or P area; [T' | P] is one 12 KiB record
+    static constexpr int NTB = 2 * TPB / 1024;           // = 12
+    static constexpr int OFF_Q = 64 * RB, OFF_T = 2 * 64 * RB, OFF_P = OFF_T + TPB, OFF_V = OFF_T + 2 * TPB,
+                         OFF_EG = OFF_V + 64 * VRW, OFF_ED = OFF_EG + 256, STAGE = OFF_ED + 256;
+    static constexpr int ORB = SLW * 2 + 16;             // padded row stride of the output staging tile
+    static constexpr int OSB = 64 * ORB;
+    static constexpr int NST = (3 * STAGE + 2 * OSB <= 160 * 1024) ? 3 : 2;   // LDS ring depth
+    static constexpr int LDS = NST * STAGE + 2 * OSB;
+    static constexpr int NDMA = (2 * NKB + NTB + NVB) / NW + 1;   // copy instructions per wave per chunk (+1: decay factors)
+    static_assert(NKB % NW == 0 && NTB % NW == 0 && NVB % NW == 0, "copy blocks must divide among the waves");
+    static_assert(LDS <= 160 * 1024 && NDMA < 60, "LDS budget of a gfx950 CU; 6-bit vmcnt");
 };
 
 }  // namespace
@@ -107,12 +121,13 @@ template <int DK, int NW>
 __global__ __launch_bounds__(64 * NW) void scan_bf16_kernel(ScanArgs<bf16_t> a)
 {
     typedef Cfg<DK, NW> C;
-    constexpr int NTH = C::NTH, KB = C::KB, KP = C::KP, SLW = C::SLW, RB = C::RB, PPR = C::PPR, VPP = C::VPP,
-                  VRB = C::VRB;
+    constexpr int NTH = C::NTH, KB = C::KB, KP = C::KP, SLW = C::SLW, RB = C::RB, PPR = C::PPR, RPB = C::RPB,
+                  VRW = C::VRW, VPP = C::VPP, RPV = C::RPV, ORB = C::ORB, NST = C::NST;
 
-    __shared__ __attribute__((aligned(16))) char lds[C::LDS];
+    __shared__ __attribute__((aligned(1024))) char lds[C::LDS];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r = lane & 15, g = lane >> 4;
 
     // ---- workgroup -> (sequence, head, column slice); slices of one head share an XCD (ids congruent mod 8)
@@ -139,220 +154,239 @@ __global__ __launch_bounds__(64 * NW) void scan_bf16_kernel(ScanArgs<bf16_t> a)
             S[kt][e] = a.h0 ? a.h0[((size_t)chain * DK + f) * a.dv + col] : 0.f;
         }
 
-    const size_t kq_stride = (size_t)a.H * DK, v_stride = (size_t)a.H * a.dv;
-    const bf16_t* kbase = a.k + (size_t)t0 * kq_stride + (size_t)h * DK;
-    const bf16_t* qbase = a.q + (size_t)t0 * kq_stride + (size_t)h * DK;
-    const bf16_t* vbase = a.v + (size_t)t0 * v_stride + (size_t)h * a.dv + slice * SLW;
+    const size_t kq_row = (size_t)a.H * DK * 2, v_row = (size_t)a.H * a.dv * 2;     // bytes between tokens
+    const char* kbase = reinterpret_cast<const char*>(a.k) + (size_t)t0 * kq_row + (size_t)h * DK * 2;
+    const char* qbase = reinterpret_cast<const char*>(a.q) + (size_t)t0 * kq_row + (size_t)h * DK * 2;
+    const char* vbase = reinterpret_cast<const char*>(a.v) + (size_t)t0 * v_row + ((size_t)h * a.dv + slice * SLW) * 2;
+    constexpr int REC = ws_record_bytes<bf16_t>();
+    const char* tpbase = reinterpret_cast<const char*>(a.wsT) + ((size_t)ch0 * a.H + h) * REC;
 
-    // ---- global -> registers -----------------------------------------------------------------------
-    auto fetch = [&](int c, Pref<DK, NW>& pf) {
-        const int last = min(64, len - 64 * c) - 1;      // rows beyond the chunk re-read its last row
-        const size_t ch = (size_t)(ch0 + c) * a.H + h;
-        static_for<C::UKQ>([&](auto it) {
-            const int i = tid + NTH * it;
-            const size_t off = (size_t)(64 * c + min(i / PPR, last)) * kq_stride + (i % PPR) * 8;
-            pf.k[it] = ld16(kbase + off);
-            pf.q[it] = ld16(qbase + off);
-        });
-        static_for<C::UV>([&](auto it) {
-            const int i = tid + NTH * it;
-            pf.v[it] = ld16(vbase + (size_t)(64 * c + min(i / VPP, last)) * v_stride + (i % VPP) * 8);
-        });
-        const u32x4* tsrc = reinterpret_cast<const u32x4*>(reinterpret_cast<const char*>(a.wsT) + ch * C::TPB);
-        const u32x4* psrc = reinterpret_cast<const u32x4*>(reinterpret_cast<const char*>(a.wsP) + ch * C::TPB);
-        static_for<C::UT>([&](auto it) {
-            const int i = min(tid + NTH * it, C::TP16 - 1);
-            pf.t[it] = tsrc[i]; pf.p[it] = psrc[i];
-        });
-        pf.gv = a.wsG[ch * 64 + lane];
-        pf.gl = a.wsG[ch * 64 + 63];
-    };
+    // ---- loop-invariant per-lane offsets ------------------------------------------------------------
+    // copy engine, global side: lane l of copy block b fills LDS bytes [1024 b + 16 l, +16) of a tile, i.e.
+    // row 1024 b / RB + l / PPR, physical column l % PPR, which holds logical column (l % PPR) ^ swz(row).
+    // (row & 7) depends on the block only through its parity (RPB = 4) or not at all (RPB = 8).
+    const int lrow = lane / PPR, pcol = lane % PPR;
+    int gk[2];
+#pragma unroll
+    for (int par = 0; par < 2; ++par)
+        gk[par] = lrow * (int)kq_row + ((pcol ^ swz_bits(RPB * par + lrow)) * 16);
+    const int gv = (lane / VPP) * (int)v_row + (lane % VPP) * 16;
+    // LDS reads.  K/Q row slots: token row 16 it + r, logical column 4 kp + g = 8 m + 4 par + g:
+    int oK[2];
+#pragma unroll
+    for (int par = 0; par < 2; ++par) oK[par] = r * RB + (((4 * par + g) ^ swz_bits(r)) * 16);
+    // K^T slots through the transposing read: source lane (a4, c4) points at token 4 g + a4 (+ 16 beta + 32 jp),
+    // logical column 8 m + 4 par + c4, half b.
+    const int a4 = r >> 2, c4 = r & 3;
+    int oKT[2];
+#pragma unroll
+    for (int par = 0; par < 2; ++par) oKT[par] = (4 * g + a4) * RB + (((4 * par + c4) ^ swz_bits(4 * g + a4)) * 16);
+    const int oV = (4 * g + a4) * VRW + (16 * wave + 4 * c4) * 2;      // V tile rows 4 g + a4 (+ 16 it)
+    const int oO = (4 * g) * ORB + (16 * wave + r) * 2;                // staging tile, rows 4 g + e (+ 16 it)
 
-    // ---- registers -> LDS stage ----------------------------------------------------------------------
-    auto stash = [&](const Pref<DK, NW>& pf, char* st) {
-        static_for<C::UKQ>([&](auto it) {
-            const int i = tid + NTH * it;
-            const int row = i / PPR, piece = i % PPR;
-            const int o = row * RB + swz(piece, row) * 16;
-            st16(st + o, pf.k[it]);
-            st16(st + C::OFF_Q + o, pf.q[it]);
-        });
-        static_for<C::UV>([&](auto it) {
-            const int i = tid + NTH * it;
-            st16(st + C::OFF_V + (i / VPP) * VRB + (i % VPP) * 16, pf.v[it]);
-        });
-        static_for<C::UT>([&](auto it) {
-            const int i = tid + NTH * it;
-            if (C::TP16 % NTH == 0 || i < C::TP16) {
-                st16(st + C::OFF_T + i * 16, pf.t[it]);
-                st16(st + C::OFF_P + i * 16, pf.p[it]);
-            }
-        });
-        if (tid < 64) {
-            reinterpret_cast<float*>(st + C::OFF_EG)[tid] = expf(pf.gv);            // gamma_i
-            reinterpret_cast<float*>(st + C::OFF_ED)[tid] = expf(pf.gl - pf.gv);    // gamma_C / gamma_i
+    // ---- global -> LDS copy of everything chunk c needs except the decay factors ---------------------
+    auto issue = [&](int c, char* st) {
+        const int clen = min(64, len - 64 * c);
+        const char* kc = kbase + (size_t)(64 * c) * kq_row;
+        const char* qc = qbase + (size_t)(64 * c) * kq_row;
+        const char* vc = vbase + (size_t)(64 * c) * v_row;
+        const char* tc = tpbase + (size_t)c * a.H * REC + lane * 16;
+        if (clen == 64) {
+            static_for<C::NKB / NW>([&](auto i) {
+                const int b = wave + NW * i;
+                const size_t o = (size_t)(b * RPB) * kq_row + gk[RPB == 4 ? (b & 1) : 0];
+                dma16(kc + o, st + b * 1024);
+                dma16(qc + o, st + C::OFF_Q + b * 1024);
+            });
+            static_for<C::NVB / NW>([&](auto i) {
+                const int b = wave + NW * i;
+                dma16(vc + (size_t)(b * RPV) * v_row + gv, st + C::OFF_V + b * 1024);
+            });
+        } else {                                         // ragged last chunk: clamp the row
+            static_for<C::NKB / NW>([&](auto i) {
+                const int b = wave + NW * i;
+                const int row = b * RPB + lrow;
+                const size_t o = (size_t)min(row, clen - 1) * kq_row + ((pcol ^ swz_bits(row)) * 16);
+                dma16(kc + o, st + b * 1024);
+                dma16(qc + o, st + C::OFF_Q + b * 1024);
+            });
+            static_for<C::NVB / NW>([&](auto i) {
+                const int b = wave + NW * i;
+                const int row = b * RPV + lane / VPP;
+                dma16(vc + (size_t)min(row, clen - 1) * v_row + (lane % VPP) * 16, st + C::OFF_V + b * 1024);
+            });
         }
+        static_for<C::NTB / NW>([&](auto i) {
+            const int b = wave + NW * i;
+            dma16(tc + b * 1024, st + C::OFF_T + b * 1024);
+        });
+        // gamma_i | gamma_C/gamma_i: 512 bytes.  Every wave copies them (same bytes to the same place) so
+        // that all waves issue the same number of copies per chunk, which the counted wait relies on.
+        if (lane < 32) dma16(tc + 2 * C::TPB, st + C::OFF_EG);
     };
 
     // ---- one chunk of the recurrence for this wave's 16 columns ------------------------------------
     auto compute = [&](const char* st, char* ost) {
-        const char* Kr = st;
-        const char* Qr = st + C::OFF_Q;
-        const float* eg = reinterpret_cast<const float*>(st + C::OFF_EG);
-        const float* ed = reinterpret_cast<const float*>(st + C::OFF_ED);
+        const char* pK0 = st + oK[0];
+        const char* pK1 = st + oK[1];
+        const char* pT0 = st + oKT[0];
+        const char* pT1 = st + oKT[1];
+        const char* pS = st + lane * 16;                 // T' / P slots
+        const char* pV = st + C::OFF_V + oV;
+        const char* pG = st + C::OFF_EG + 16 * g;        // 4 consecutive floats: rows 4 g .. 4 g + 3
+        auto kslot = [&](int it, int kp, int base) {     // base 0: K, OFF_Q: Q
+            return ld16(((kp & 1) ? pK1 : pK0) + base + 16 * it * RB + 128 * (kp >> 1));
+        };
+        auto ktslot = [&](int kt, int jp, u32x2& q0, u32x2& q1) {
+            const int kp = kt >> 1, b = kt & 1;
+            const char* p = ((kp & 1) ? pT1 : pT0) + 32 * jp * RB + 128 * (kp >> 1) + 8 * b;
+            q0 = lds_read_tr(p);
+            q1 = lds_read_tr(p + 16 * RB);
+        };
 
         u32x2 Sq[KB];
 #pragma unroll
         for (int kt = 0; kt < KB; ++kt) Sq[kt] = to_quad(S[kt]);
 
-        // operands that do not depend on the state: T' slots, V tile, decay factors
+        // ---- K S (on the chain) and Q S (off it): A slots are 8 consecutive features of a token row
+        floatx4 ks[4], qs[4];
+        u32x4 ka[2][KP];
+#pragma unroll
+        for (int kp = 0; kp < KP; ++kp) { ka[0][kp] = kslot(0, kp, 0); ka[1][kp] = kslot(1, kp, 0); }
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            ks[it] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kp = 0; kp < KP; ++kp) mma_bf16(ks[it], ka[it & 1][kp], Sq[2 * kp], Sq[2 * kp + 1]);
+            if (it + 2 < 4) {
+#pragma unroll
+                for (int kp = 0; kp < KP; ++kp) ka[it & 1][kp] = kslot(it + 2, kp, 0);
+            }
+        }
+        // operands of the solve, in flight while Q S runs
         u32x4 tsl[kTriPairs];
 #pragma unroll
-        for (int i = 0; i < kTriPairs; ++i) tsl[i] = ld16(st + C::OFF_T + (i * 64 + lane) * 16);
+        for (int i = 0; i < kTriPairs; ++i) tsl[i] = ld16(pS + C::OFF_T + i * 1024);
         u32x2 vq[4];
         floatx4 egv[4], edv[4];
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
-            // lane j of a 16-lane group supplies row a = j/4 (token 16*it + 4*g + a), columns 4*(j%4)..+3
-            vq[it] = lds_read_tr(st + C::OFF_V + (16 * it + 4 * g + (r >> 2)) * VRB + (16 * wave + 4 * (r & 3)) * 2);
-            egv[it] = ld_f4(eg + 16 * it + 4 * g);
-            edv[it] = ld_f4(ed + 16 * it + 4 * g);
+            vq[it] = lds_read_tr(pV + 16 * it * VRW);
+            egv[it] = ld_f4(pG + 64 * it);
+            edv[it] = ld_f4(pG + 256 + 64 * it);
         }
+        u32x4 qa[2][KP];
+#pragma unroll
+        for (int kp = 0; kp < KP; ++kp) { qa[0][kp] = kslot(0, kp, C::OFF_Q); qa[1][kp] = kslot(1, kp, C::OFF_Q); }
 
-        // K S and Q S: A slots are 8 consecutive features of token row 16*it + r
-        floatx4 ks[4], qs[4];
-        u32x4 ka[KP], qa[KP];
-#pragma unroll
-        for (int kp = 0; kp < KP; ++kp) {
-            const int o = r * RB + swz(4 * kp + g, r) * 16;
-            ka[kp] = ld16(Kr + o);
-            qa[kp] = ld16(Qr + o);
-        }
-#pragma unroll
-        for (int it = 0; it < 4; ++it) {
-            u32x4 kn[KP], qn[KP];
-            if (it < 3) {
-#pragma unroll
-                for (int kp = 0; kp < KP; ++kp) {
-                    const int row = 16 * (it + 1) + r;
-                    const int o = row * RB + swz(4 * kp + g, row) * 16;
-                    kn[kp] = ld16(Kr + o);
-                    qn[kp] = ld16(Qr + o);
-                }
-            }
-            ks[it] = floatx4{0.f, 0.f, 0.f, 0.f};
-            qs[it] = floatx4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int kp = 0; kp < KP; ++kp) mma_bf16(ks[it], ka[kp], Sq[2 * kp], Sq[2 * kp + 1]);
-#pragma unroll
-            for (int kp = 0; kp < KP; ++kp) mma_bf16(qs[it], qa[kp], Sq[2 * kp], Sq[2 * kp + 1]);
-            if (it < 3) {
-#pragma unroll
-                for (int kp = 0; kp < KP; ++kp) { ka[kp] = kn[kp]; qa[kp] = qn[kp]; }
-            }
-        }
-
-        // X = V - D_gamma K S ;  U = T' X
+        // X = V - D_gamma K S
         u32x2 Xq[4];
 #pragma unroll
         for (int it = 0; it < 4; ++it) Xq[it] = to_quad(quad_to_f(vq[it]) - egv[it] * ks[it]);
 
-        // first K^T slots for the state update: issue before the solve so they arrive during it
-        auto kt_slot = [&](int kt, int jp, u32x2& q0, u32x2& q1) {
-            const int kp = kt >> 1, b = kt & 1;
-            const int a4 = r >> 2, c4 = r & 3;
-            const int tok = 32 * jp + 4 * g + a4;
-            q0 = lds_read_tr(Kr + tok * RB + swz(4 * kp + c4, tok) * 16 + 8 * b);
-            q1 = lds_read_tr(Kr + (tok + 16) * RB + swz(4 * kp + c4, tok + 16) * 16 + 8 * b);
-        };
-        u32x2 kt0[2][2];
-        kt_slot(0, 0, kt0[0][0], kt0[0][1]);
-        kt_slot(0, 1, kt0[1][0], kt0[1][1]);
-
+        // U = T' X (T' lower triangular), interleaved with Q S
         floatx4 U[4];
-        u32x2 Uq[4], Udq[4];
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
             U[it] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int jp = 0; jp <= (it >> 1); ++jp) {
-                const u32x4 sl = tsl[tri_pair(it, jp)];
-                mma_bf16(U[it], sl, Xq[2 * jp], Xq[2 * jp + 1]);
+            for (int jp = 0; jp <= (it >> 1); ++jp) mma_bf16(U[it], tsl[tri_pair(it, jp)], Xq[2 * jp], Xq[2 * jp + 1]);
+            qs[it] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kp = 0; kp < KP; ++kp) mma_bf16(qs[it], qa[it & 1][kp], Sq[2 * kp], Sq[2 * kp + 1]);
+            if (it + 2 < 4) {
+#pragma unroll
+                for (int kp = 0; kp < KP; ++kp) qa[it & 1][kp] = kslot(it + 2, kp, C::OFF_Q);
             }
         }
+        // K^T slots of the first state tiles and the P slots: on their way during the conversions below
+        u32x2 kt[3][2][2];
+        ktslot(0, 0, kt[0][0][0], kt[0][0][1]); ktslot(0, 1, kt[0][1][0], kt[0][1][1]);
+        ktslot(1, 0, kt[1][0][0], kt[1][0][1]); ktslot(1, 1, kt[1][1][0], kt[1][1][1]);
+        u32x4 psl[kTriPairs];
+#pragma unroll
+        for (int i = 0; i < kTriPairs; ++i) psl[i] = ld16(pS + C::OFF_P + i * 1024);
+
+        u32x2 Uq[4], Udq[4];
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
             Uq[it] = to_quad(U[it]);
             Udq[it] = to_quad(U[it] * edv[it]);
         }
-        // P slots for the outputs: in flight during the state update
-        u32x4 psl[kTriPairs];
-#pragma unroll
-        for (int i = 0; i < kTriPairs; ++i) psl[i] = ld16(st + C::OFF_P + (i * 64 + lane) * 16);
 
         // S = gamma_C S + K^T (diag(gamma_C/gamma_i) U): the only thing the next chunk waits for
-        const float gC = eg[63];
+        const float gC = *reinterpret_cast<const float*>(st + C::OFF_EG + 63 * 4);
 #pragma unroll
-        for (int kt = 0; kt < KB; ++kt) {
-            u32x2 nx[2][2];
-            if (kt + 1 < KB) {
-                kt_slot(kt + 1, 0, nx[0][0], nx[0][1]);
-                kt_slot(kt + 1, 1, nx[1][0], nx[1][1]);
+        for (int t = 0; t < KB; ++t) {
+            if (t + 2 < KB) {
+                ktslot(t + 2, 0, kt[(t + 2) % 3][0][0], kt[(t + 2) % 3][0][1]);
+                ktslot(t + 2, 1, kt[(t + 2) % 3][1][0], kt[(t + 2) % 3][1][1]);
             }
-            S[kt] = S[kt] * gC;
-            mma_bf16(S[kt], kt0[0][0], kt0[0][1], Udq[0], Udq[1]);
-            mma_bf16(S[kt], kt0[1][0], kt0[1][1], Udq[2], Udq[3]);
-            if (kt + 1 < KB) {
-                kt0[0][0] = nx[0][0]; kt0[0][1] = nx[0][1]; kt0[1][0] = nx[1][0]; kt0[1][1] = nx[1][1];
-            }
+            S[t] = S[t] * gC;
+            mma_bf16(S[t], kt[t % 3][0][0], kt[t % 3][0][1], Udq[0], Udq[1]);
+            mma_bf16(S[t], kt[t % 3][1][0], kt[t % 3][1][1], Udq[2], Udq[3]);
         }
 
-        // O = D_gamma Q S + P U, staged token-major for 16-byte global stores
+        // O = D_gamma Q S + P U (P lower triangular), staged token-major for 16-byte global stores
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
             floatx4 o = egv[it] * qs[it];
 #pragma unroll
             for (int jp = 0; jp <= (it >> 1); ++jp) mma_bf16(o, psl[tri_pair(it, jp)], Uq[2 * jp], Uq[2 * jp + 1]);
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-                *reinterpret_cast<uint16_t*>(ost + (16 * it + 4 * g + e) * VRB + (16 * wave + r) * 2) =
-                    (uint16_t)float_to_bf16_bits(o[e]);
+            const u32x2 ob = to_quad(o);
+            char* po = ost + oO + 16 * it * ORB;
+            *reinterpret_cast<uint16_t*>(po) = (uint16_t)(ob.x & 0xffffu);
+            *reinterpret_cast<uint16_t*>(po + ORB) = (uint16_t)(ob.x >> 16);
+            *reinterpret_cast<uint16_t*>(po + 2 * ORB) = (uint16_t)(ob.y & 0xffffu);
+            *reinterpret_cast<uint16_t*>(po + 3 * ORB) = (uint16_t)(ob.y >> 16);
         }
     };
 
     auto write_out = [&](int c, const char* ost) {
         const int clen = min(64, len - 64 * c);
-        bf16_t* ob = a.o + (size_t)(t0 + 64L * c) * v_stride + (size_t)h * a.dv + slice * SLW;
+        char* ob = reinterpret_cast<char*>(a.o) + (size_t)(t0 + 64L * c) * v_row + ((size_t)h * a.dv + slice * SLW) * 2;
 #pragma unroll
-        for (int it = 0; it < C::UV; ++it) {
+        for (int it = 0; it < 64 * VPP / NTH; ++it) {
             const int i = tid + NTH * it;
             const int row = i / VPP, pv = i % VPP;
-            if (row < clen)
-                st16(ob + (size_t)row * v_stride + pv * 8, ld16(ost + row * VRB + pv * 16));
+            if (row < clen) st16(ob + (size_t)row * v_row + pv * 16, ld16(ost + row * ORB + pv * 16));
         }
     };
 
-    Pref<DK, NW> pf;
-    char* stage0 = lds;
-    char* stage1 = lds + C::STAGE;
-    char* ost0 = lds + 2 * C::STAGE;
+    char* ost0 = lds + NST * C::STAGE;
     char* ost1 = ost0 + C::OSB;
-    if (nch > 0) { fetch(0, pf); stash(pf, stage0); }
+
+    // ---- prologue: chunks 0 .. NST-2 on their way, chunk 0 landed ------------------------------------
+#pragma unroll
+    for (int p = 0; p < NST - 1; ++p)
+        if (p < nch) issue(p, lds + p * C::STAGE);
+    wait_vmcnt<0>();
     __syncthreads();
+
+    int scur = 0;                                        // ring position of chunk c
     for (int c = 0; c < nch; ++c) {
-        char* cur = (c & 1) ? stage1 : stage0;
-        char* nxt = (c & 1) ? stage0 : stage1;
+        const int snext = (scur + 1 == NST) ? 0 : scur + 1;
+        const int spre = (scur == 0) ? NST - 1 : scur - 1;          // (scur + NST - 1) % NST
+        char* cur = lds + scur * C::STAGE;
         char* ost = (c & 1) ? ost1 : ost0;
         const bool more = c + 1 < nch;
-        if (more && !(a.debug & 1)) fetch(c + 1, pf);                      // in flight while this chunk's products run
-        if (!(a.debug & 2)) compute(cur, ost);
-        if (more && !(a.debug & 4)) stash(pf, nxt);
-        // One barrier per chunk: staged outputs before their write-out; the next chunk's operands
-        // before their use; all reads of `cur` before it is overwritten one iteration later; and the
-        // write-out of chunk c-1 (finished by every wave before it arrives here) before the staging
-        // tile of that parity is written again in chunk c+1.
+        const bool ahead = c + NST - 1 < nch;
+        // the stage being refilled was read by chunk c-1, which every wave finished before the last barrier
+        if (ahead) issue(c + NST - 1, lds + spre * C::STAGE);
+        compute(cur, ost);
+        if (more) {
+            // Vector-memory operations retire in order.  Younger than the copies of chunk c+1 are only the
+            // NDMA copies of chunk c+NST-1 issued above (when NST = 3), so this waits for chunk c+1's
+            // copies (this wave's share) and the previous output stores, nothing more.
+            if (NST == 3 && ahead) wait_vmcnt<C::NDMA>(); else wait_vmcnt<0>();
+        }
+        // One barrier per chunk: staged outputs before their write-out; chunk c+1's operands (all waves'
+        // shares) before their use; all reads of `cur` before it is refilled next iteration; and the
+        // write-out of chunk c-1 (finished by every wave before it arrives here) before the staging tile
+        // of that parity is written again in chunk c+1.
         __syncthreads();
         write_out(c, ost);
+        scur = snext;
     }
 
     if (a.hT) {

@@ -16,7 +16,9 @@ hipError_t launch_beta(const T* k, const float* eta, float eps, float* beta, lon
 
 // ---- chunkwise forward ------------------------------------------------------------------------
 // Workspace areas, all indexed by chunk-head ch = global_chunk * H + h:
-//   wsT, wsP : 6 tile-pairs x 64 operand slots (8 elements each) per chunk-head, see kla_mma.hpp
+//   wsT, wsP : per chunk-head one record [T' | P | gamma_i | gamma_C/gamma_i]; T' and P are 6 tile-pairs x 64
+//              operand slots of 8 elements (see kla_mma.hpp), the decay factors 64 fp32 each;
+//              wsP = wsT + one half, both advance by a whole record
 //   wsG      : 64 fp32 per chunk-head
 //   chunk_off: int32 [n_seq + 1], packed batches only
 template <typename E> struct IntraArgs {

@@ -41,15 +41,16 @@ def test_status_strings():
 def test_workspace_bytes():
     lib = kla.lib()
     f = lib.kla_chunk_fwd_workspace_bytes
-    # 4096 chunk-heads, bf16: 2 x 6 KiB operand areas + 256 B of g each, plus the (empty) offsets table
+    # 4096 chunk-heads, bf16: a record of 2 x 6 KiB operand areas + 512 B of decay factors, and 256 B of g
+    # each, plus the (empty) offsets table
     n = f(8, 4096, 8, 128, 128, 64, kla.KLA_BF16, None, 0)
-    assert n >= 4096 * (2 * 6144 + 256) and n <= 4096 * (2 * 6144 + 256) + 4 * 256
+    assert n >= 4096 * (2 * 6144 + 512 + 256) and n <= 4096 * (2 * 6144 + 512 + 256) + 4 * 256
     assert f(8, 4096, 8, 128, 128, 64, kla.KLA_F32, None, 0) > n
     assert f(8, 4096, 8, 128, 128, 32, kla.KLA_BF16, None, 0) == 0        # chunk != 64
     assert f(8, 4096, 8, 96, 128, 64, kla.KLA_BF16, None, 0) == 0         # bad dk
     cu = np.array([0, 10, 10, 200], dtype=np.int32)                       # 1 + 0 + 3 chunks
     n2 = f(1, 200, 2, 64, 64, 64, kla.KLA_BF16, cu.ctypes.data, 3)
-    assert n2 >= 4 * 2 * (2 * 6144 + 256)
+    assert n2 >= 4 * 2 * (2 * 6144 + 512 + 256)
     bad = np.array([0, 10, 5, 200], dtype=np.int32)
     assert f(1, 200, 2, 64, 64, 64, kla.KLA_BF16, bad.ctypes.data, 3) == 0
 
