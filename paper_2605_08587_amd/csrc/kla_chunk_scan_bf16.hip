@@ -6,6 +6,10 @@
 //     LDS base + 16 l, the global address is free per lane), two chunks ahead into a three-stage LDS
 //     ring, so no registers and no LDS store instructions are spent on staging and a chunk's operands
 //     have two chunk times to arrive.  One barrier per chunk.
+//   * The copies are issued by one extra wave of the workgroup that does nothing else.  The vector
+//     memory counter retires in order, so in a wave that also stores outputs every copy would queue
+//     behind the (slow) acknowledgement of the stores before it; the copy wave has no stores, and
+//     the compute waves never wait for memory at all.
 //   * K, Q and the V slice sit in LDS as plain token-major rows; the 16-byte columns of K and Q are
 //     XOR-swizzled by the row (applied on the global side of the copy) so that both kinds of read
 //     below are spread over the banks.
@@ -51,10 +55,12 @@ __device__ __forceinline__ u32x2 lds_read_tr(const char* p)
 // lds_wave_base + 16 l.  `lds_wave_base` must be wave-uniform (it goes to M0).  Written as inline
 // assembly on purpose: the compiler then keeps no book of these copies, so it puts no wait for them in
 // front of LDS reads of OTHER ring stages; completion is awaited explicitly (wait_vmcnt + barrier).
-__device__ __forceinline__ void dma16(const void* gptr, char* lds_wave_base)
+// The global address is a wave-uniform base plus a 32-bit per-lane byte offset.
+__device__ __forceinline__ void dma16(const char* gbase_uniform, int lane_off, char* lds_wave_base)
 {
     const uint32_t m = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) char*)lds_wave_base);
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(m) : "memory");
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane_off), "s"(gbase_uniform), "s"(m)
+                 : "memory");
 }
 
 // s_waitcnt on the vector-memory counter only (gfx9 encoding: vmcnt in bits 3:0 and 15:14)
@@ -91,7 +97,7 @@ __device__ __forceinline__ floatx4 ld_f4(const char* p) { return *reinterpret_ca
 
 template <int DK, int NW>
 struct Cfg {
-    static constexpr int NTH = 64 * NW;
+    static constexpr int NTH = 64 * NW;                  // compute threads (the workgroup has one more wave)
     static constexpr int KB = DK / 16, KP = DK / 32;
     static constexpr int SLW = 16 * NW;                  // state columns per workgroup
     static constexpr int RB = DK * 2;                    // bytes per K/Q row
@@ -110,15 +116,14 @@ struct Cfg {
     static constexpr int OSB = 64 * ORB;
     static constexpr int NST = (3 * STAGE + 2 * OSB <= 160 * 1024) ? 3 : 2;   // LDS ring depth
     static constexpr int LDS = NST * STAGE + 2 * OSB;
-    static constexpr int NDMA = (2 * NKB + NTB + NVB) / NW + 1;   // copy instructions per wave per chunk (+1: decay factors)
-    static_assert(NKB % NW == 0 && NTB % NW == 0 && NVB % NW == 0, "copy blocks must divide among the waves");
-    static_assert(LDS <= 160 * 1024 && NDMA < 60, "LDS budget of a gfx950 CU; 6-bit vmcnt");
+    static constexpr int NDMA = 2 * NKB + NTB + NVB + 1;   // copy instructions per chunk (+1: decay factors)
+    static_assert(LDS <= 160 * 1024 && NDMA < 64, "LDS budget of a gfx950 CU; 6-bit vmcnt");
 };
 
 }  // namespace
 
 template <int DK, int NW>
-__global__ __launch_bounds__(64 * NW) void scan_bf16_kernel(ScanArgs<bf16_t> a)
+__global__ __launch_bounds__(64 * NW + 64) void scan_bf16_kernel(ScanArgs<bf16_t> a)
 {
     typedef Cfg<DK, NW> C;
     constexpr int NTH = C::NTH, KB = C::KB, KP = C::KP, SLW = C::SLW, RB = C::RB, PPR = C::PPR, RPB = C::RPB,
@@ -151,7 +156,7 @@ __global__ __launch_bounds__(64 * NW) void scan_bf16_kernel(ScanArgs<bf16_t> a)
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const int f = 32 * (kt >> 1) + 8 * g + 4 * (kt & 1) + e;
-            S[kt][e] = a.h0 ? a.h0[((size_t)chain * DK + f) * a.dv + col] : 0.f;
+            S[kt][e] = (a.h0 && wave < NW) ? a.h0[((size_t)chain * DK + f) * a.dv + col] : 0.f;   // not the copy wave
         }
 
     const size_t kq_row = (size_t)a.H * DK * 2, v_row = (size_t)a.H * a.dv * 2;     // bytes between tokens
@@ -190,39 +195,38 @@ __global__ __launch_bounds__(64 * NW) void scan_bf16_kernel(ScanArgs<bf16_t> a)
         const char* kc = kbase + (size_t)(64 * c) * kq_row;
         const char* qc = qbase + (size_t)(64 * c) * kq_row;
         const char* vc = vbase + (size_t)(64 * c) * v_row;
-        const char* tc = tpbase + (size_t)c * a.H * REC + lane * 16;
+        const char* tc = tpbase + (size_t)c * a.H * REC;
         if (clen == 64) {
-            static_for<C::NKB / NW>([&](auto i) {
-                const int b = wave + NW * i;
-                const size_t o = (size_t)(b * RPB) * kq_row + gk[RPB == 4 ? (b & 1) : 0];
-                dma16(kc + o, st + b * 1024);
-                dma16(qc + o, st + C::OFF_Q + b * 1024);
+            static_for<C::NKB>([&](auto i) {
+                const int b = i;
+                const size_t o = (size_t)(b * RPB) * kq_row;
+                const int lo = (RPB == 4 && (b & 1)) ? gk[1] : gk[0];
+                dma16(kc + o, lo, st + b * 1024);
+                dma16(qc + o, lo, st + C::OFF_Q + b * 1024);
             });
-            static_for<C::NVB / NW>([&](auto i) {
-                const int b = wave + NW * i;
-                dma16(vc + (size_t)(b * RPV) * v_row + gv, st + C::OFF_V + b * 1024);
+            static_for<C::NVB>([&](auto i) {
+                const int b = i;
+                dma16(vc + (size_t)(b * RPV) * v_row, gv, st + C::OFF_V + b * 1024);
             });
         } else {                                         // ragged last chunk: clamp the row
-            static_for<C::NKB / NW>([&](auto i) {
-                const int b = wave + NW * i;
+            static_for<C::NKB>([&](auto i) {
+                const int b = i;
                 const int row = b * RPB + lrow;
-                const size_t o = (size_t)min(row, clen - 1) * kq_row + ((pcol ^ swz_bits(row)) * 16);
-                dma16(kc + o, st + b * 1024);
-                dma16(qc + o, st + C::OFF_Q + b * 1024);
+                const int lo = min(row, clen - 1) * (int)kq_row + ((pcol ^ swz_bits(row)) * 16);
+                dma16(kc, lo, st + b * 1024);
+                dma16(qc, lo, st + C::OFF_Q + b * 1024);
             });
-            static_for<C::NVB / NW>([&](auto i) {
-                const int b = wave + NW * i;
+            static_for<C::NVB>([&](auto i) {
+                const int b = i;
                 const int row = b * RPV + lane / VPP;
-                dma16(vc + (size_t)min(row, clen - 1) * v_row + (lane % VPP) * 16, st + C::OFF_V + b * 1024);
+                dma16(vc, min(row, clen - 1) * (int)v_row + (lane % VPP) * 16, st + C::OFF_V + b * 1024);
             });
         }
-        static_for<C::NTB / NW>([&](auto i) {
-            const int b = wave + NW * i;
-            dma16(tc + b * 1024, st + C::OFF_T + b * 1024);
+        static_for<C::NTB>([&](auto i) {
+            const int b = i;
+            dma16(tc + b * 1024, lane * 16, st + C::OFF_T + b * 1024);
         });
-        // gamma_i | gamma_C/gamma_i: 512 bytes.  Every wave copies them (same bytes to the same place) so
-        // that all waves issue the same number of copies per chunk, which the counted wait relies on.
-        if (lane < 32) dma16(tc + 2 * C::TPB, st + C::OFF_EG);
+        if (lane < 32) dma16(tc + 2 * C::TPB, lane * 16, st + C::OFF_EG);   // gamma_i | gamma_C/gamma_i: 512 bytes
     };
 
     // ---- one chunk of the recurrence for this wave's 16 columns ------------------------------------
@@ -244,29 +248,31 @@ __global__ __launch_bounds__(64 * NW) void scan_bf16_kernel(ScanArgs<bf16_t> a)
             q1 = lds_read_tr(p + 16 * RB);
         };
 
+        // bf16 copy of the incoming state (B operand of K S and Q S); the fp32 state is decayed right away
+        const float gC = *reinterpret_cast<const float*>(st + C::OFF_EG + 63 * 4);
         u32x2 Sq[KB];
 #pragma unroll
-        for (int kt = 0; kt < KB; ++kt) Sq[kt] = to_quad(S[kt]);
+        for (int kt = 0; kt < KB; ++kt) { Sq[kt] = to_quad(S[kt]); S[kt] = S[kt] * gC; }
 
-        // ---- K S (on the chain) and Q S (off it): A slots are 8 consecutive features of a token row
+        // Products are issued "independent first": consecutive MFMAs write different accumulators, so that a
+        // dependent one (same accumulator) follows only several instructions later.
+        // ---- K S (on the serial chain): A slots are 8 consecutive features of a token row
         floatx4 ks[4], qs[4];
-        u32x4 ka[2][KP];
 #pragma unroll
-        for (int kp = 0; kp < KP; ++kp) { ka[0][kp] = kslot(0, kp, 0); ka[1][kp] = kslot(1, kp, 0); }
+        for (int it = 0; it < 4; ++it) { ks[it] = floatx4{0.f, 0.f, 0.f, 0.f}; qs[it] = floatx4{0.f, 0.f, 0.f, 0.f}; }
+        u32x4 ka[2][4];
 #pragma unroll
-        for (int it = 0; it < 4; ++it) {
-            ks[it] = floatx4{0.f, 0.f, 0.f, 0.f};
+        for (int it = 0; it < 4; ++it) ka[0][it] = kslot(it, 0, 0);
 #pragma unroll
-            for (int kp = 0; kp < KP; ++kp) mma_bf16(ks[it], ka[it & 1][kp], Sq[2 * kp], Sq[2 * kp + 1]);
-            if (it + 2 < 4) {
+        for (int kp = 0; kp < KP; ++kp) {
+            if (kp + 1 < KP) {
 #pragma unroll
-                for (int kp = 0; kp < KP; ++kp) ka[it & 1][kp] = kslot(it + 2, kp, 0);
+                for (int it = 0; it < 4; ++it) ka[(kp + 1) & 1][it] = kslot(it, kp + 1, 0);
             }
-        }
-        // operands of the solve, in flight while Q S runs
-        u32x4 tsl[kTriPairs];
 #pragma unroll
-        for (int i = 0; i < kTriPairs; ++i) tsl[i] = ld16(pS + C::OFF_T + i * 1024);
+            for (int it = 0; it < 4; ++it) mma_bf16(ks[it], ka[kp & 1][it], Sq[2 * kp], Sq[2 * kp + 1]);
+        }
+        // operands of the solve and of Q S, in flight while K S drains
         u32x2 vq[4];
         floatx4 egv[4], edv[4];
 #pragma unroll
@@ -275,34 +281,43 @@ __global__ __launch_bounds__(64 * NW) void scan_bf16_kernel(ScanArgs<bf16_t> a)
             egv[it] = ld_f4(pG + 64 * it);
             edv[it] = ld_f4(pG + 256 + 64 * it);
         }
-        u32x4 qa[2][KP];
+        u32x4 tsl[kTriPairs];
 #pragma unroll
-        for (int kp = 0; kp < KP; ++kp) { qa[0][kp] = kslot(0, kp, C::OFF_Q); qa[1][kp] = kslot(1, kp, C::OFF_Q); }
+        for (int i = 0; i < kTriPairs; ++i) tsl[i] = ld16(pS + C::OFF_T + i * 1024);
+        u32x4 qa[2][4];
+#pragma unroll
+        for (int it = 0; it < 4; ++it) qa[0][it] = kslot(it, 0, C::OFF_Q);
 
-        // X = V - D_gamma K S
+        // ---- Q S (off the chain) fills the matrix pipe while X = V - D_gamma K S is formed on the VALU
+#pragma unroll
+        for (int kp = 0; kp < KP; ++kp) {
+            if (kp + 1 < KP) {
+#pragma unroll
+                for (int it = 0; it < 4; ++it) qa[(kp + 1) & 1][it] = kslot(it, kp + 1, C::OFF_Q);
+            }
+#pragma unroll
+            for (int it = 0; it < 4; ++it) mma_bf16(qs[it], qa[kp & 1][it], Sq[2 * kp], Sq[2 * kp + 1]);
+        }
         u32x2 Xq[4];
 #pragma unroll
         for (int it = 0; it < 4; ++it) Xq[it] = to_quad(quad_to_f(vq[it]) - egv[it] * ks[it]);
 
-        // U = T' X (T' lower triangular), interleaved with Q S
+        // K^T slots of the first state tiles and the P slots: on their way during the solve
+        u32x2 kt[2][KB][2];                              // [token pair jp][state tile][token block]
+#pragma unroll
+        for (int t = 0; t < KB; ++t) ktslot(t, 0, kt[0][t][0], kt[0][t][1]);
+
+        // ---- U = T' X (T' lower triangular)
         floatx4 U[4];
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
             U[it] = floatx4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int jp = 0; jp <= (it >> 1); ++jp) mma_bf16(U[it], tsl[tri_pair(it, jp)], Xq[2 * jp], Xq[2 * jp + 1]);
-            qs[it] = floatx4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int kp = 0; kp < KP; ++kp) mma_bf16(qs[it], qa[it & 1][kp], Sq[2 * kp], Sq[2 * kp + 1]);
-            if (it + 2 < 4) {
-#pragma unroll
-                for (int kp = 0; kp < KP; ++kp) qa[it & 1][kp] = kslot(it + 2, kp, C::OFF_Q);
-            }
+            mma_bf16(U[it], tsl[tri_pair(it, 0)], Xq[0], Xq[1]);
         }
-        // K^T slots of the first state tiles and the P slots: on their way during the conversions below
-        u32x2 kt[3][2][2];
-        ktslot(0, 0, kt[0][0][0], kt[0][0][1]); ktslot(0, 1, kt[0][1][0], kt[0][1][1]);
-        ktslot(1, 0, kt[1][0][0], kt[1][0][1]); ktslot(1, 1, kt[1][1][0], kt[1][1][1]);
+        mma_bf16(U[2], tsl[tri_pair(2, 1)], Xq[2], Xq[3]);
+        mma_bf16(U[3], tsl[tri_pair(3, 1)], Xq[2], Xq[3]);
+#pragma unroll
+        for (int t = 0; t < KB; ++t) ktslot(t, 1, kt[1][t][0], kt[1][t][1]);
         u32x4 psl[kTriPairs];
 #pragma unroll
         for (int i = 0; i < kTriPairs; ++i) psl[i] = ld16(pS + C::OFF_P + i * 1024);
@@ -310,30 +325,28 @@ __global__ __launch_bounds__(64 * NW) void scan_bf16_kernel(ScanArgs<bf16_t> a)
         u32x2 Uq[4], Udq[4];
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
-            Uq[it] = to_quad(U[it]);
             Udq[it] = to_quad(U[it] * edv[it]);
+            Uq[it] = to_quad(U[it]);
         }
 
-        // S = gamma_C S + K^T (diag(gamma_C/gamma_i) U): the only thing the next chunk waits for
-        const float gC = *reinterpret_cast<const float*>(st + C::OFF_EG + 63 * 4);
+        // ---- S = gamma_C S + K^T (diag(gamma_C/gamma_i) U): the only thing the next chunk waits for
 #pragma unroll
-        for (int t = 0; t < KB; ++t) {
-            if (t + 2 < KB) {
-                ktslot(t + 2, 0, kt[(t + 2) % 3][0][0], kt[(t + 2) % 3][0][1]);
-                ktslot(t + 2, 1, kt[(t + 2) % 3][1][0], kt[(t + 2) % 3][1][1]);
-            }
-            S[t] = S[t] * gC;
-            mma_bf16(S[t], kt[t % 3][0][0], kt[t % 3][0][1], Udq[0], Udq[1]);
-            mma_bf16(S[t], kt[t % 3][1][0], kt[t % 3][1][1], Udq[2], Udq[3]);
-        }
+        for (int t = 0; t < KB; ++t) mma_bf16(S[t], kt[0][t][0], kt[0][t][1], Udq[0], Udq[1]);
+#pragma unroll
+        for (int t = 0; t < KB; ++t) mma_bf16(S[t], kt[1][t][0], kt[1][t][1], Udq[2], Udq[3]);
 
-        // O = D_gamma Q S + P U (P lower triangular), staged token-major for 16-byte global stores
+        // ---- O = D_gamma Q S + P U (P lower triangular), staged token-major for 16-byte global stores
+        floatx4 o[4];
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
-            floatx4 o = egv[it] * qs[it];
+            o[it] = egv[it] * qs[it];
+            mma_bf16(o[it], psl[tri_pair(it, 0)], Uq[0], Uq[1]);
+        }
+        mma_bf16(o[2], psl[tri_pair(2, 1)], Uq[2], Uq[3]);
+        mma_bf16(o[3], psl[tri_pair(3, 1)], Uq[2], Uq[3]);
 #pragma unroll
-            for (int jp = 0; jp <= (it >> 1); ++jp) mma_bf16(o, psl[tri_pair(it, jp)], Uq[2 * jp], Uq[2 * jp + 1]);
-            const u32x2 ob = to_quad(o);
+        for (int it = 0; it < 4; ++it) {
+            const u32x2 ob = to_quad(o[it]);
             char* po = ost + oO + 16 * it * ORB;
             *reinterpret_cast<uint16_t*>(po) = (uint16_t)(ob.x & 0xffffu);
             *reinterpret_cast<uint16_t*>(po + ORB) = (uint16_t)(ob.x >> 16);
@@ -356,37 +369,40 @@ __global__ __launch_bounds__(64 * NW) void scan_bf16_kernel(ScanArgs<bf16_t> a)
     char* ost0 = lds + NST * C::STAGE;
     char* ost1 = ost0 + C::OSB;
 
-    // ---- prologue: chunks 0 .. NST-2 on their way, chunk 0 landed ------------------------------------
+    if (wave == NW) {
+        // ---- the copy wave: keeps chunks c+1 .. c+NST-1 on their way while chunk c is computed ---------
 #pragma unroll
-    for (int p = 0; p < NST - 1; ++p)
-        if (p < nch) issue(p, lds + p * C::STAGE);
-    wait_vmcnt<0>();
-    __syncthreads();
+        for (int p = 0; p < NST - 1; ++p)
+            if (p < nch) issue(p, lds + p * C::STAGE);
+        if (NST == 3 && nch > 1) wait_vmcnt<C::NDMA>(); else wait_vmcnt<0>();      // chunk 0 has landed
+        __syncthreads();
+        int spre = NST - 1;                              // ring position of chunk c + NST - 1
+        for (int c = 0; c < nch; ++c) {
+            const bool ahead = c + NST - 1 < nch;
+            // the stage being refilled was read by chunk c-1, which every wave finished before the last barrier
+            if (ahead) issue(c + NST - 1, lds + spre * C::STAGE);
+            // Copies retire in order and this wave issues nothing else: all but the NDMA just issued (when
+            // NST = 3) have landed once the counter is down to NDMA, i.e. chunk c+1 is complete.
+            if (NST == 3 && ahead) wait_vmcnt<C::NDMA>(); else wait_vmcnt<0>();
+            __syncthreads();
+            spre = (spre + 1 == NST) ? 0 : spre + 1;
+        }
+        return;
+    }
 
+    // ---- compute waves ---------------------------------------------------------------------------------
+    __syncthreads();                                     // chunk 0 is in stage 0
     int scur = 0;                                        // ring position of chunk c
     for (int c = 0; c < nch; ++c) {
-        const int snext = (scur + 1 == NST) ? 0 : scur + 1;
-        const int spre = (scur == 0) ? NST - 1 : scur - 1;          // (scur + NST - 1) % NST
-        char* cur = lds + scur * C::STAGE;
         char* ost = (c & 1) ? ost1 : ost0;
-        const bool more = c + 1 < nch;
-        const bool ahead = c + NST - 1 < nch;
-        // the stage being refilled was read by chunk c-1, which every wave finished before the last barrier
-        if (ahead) issue(c + NST - 1, lds + spre * C::STAGE);
-        compute(cur, ost);
-        if (more) {
-            // Vector-memory operations retire in order.  Younger than the copies of chunk c+1 are only the
-            // NDMA copies of chunk c+NST-1 issued above (when NST = 3), so this waits for chunk c+1's
-            // copies (this wave's share) and the previous output stores, nothing more.
-            if (NST == 3 && ahead) wait_vmcnt<C::NDMA>(); else wait_vmcnt<0>();
-        }
-        // One barrier per chunk: staged outputs before their write-out; chunk c+1's operands (all waves'
-        // shares) before their use; all reads of `cur` before it is refilled next iteration; and the
-        // write-out of chunk c-1 (finished by every wave before it arrives here) before the staging tile
-        // of that parity is written again in chunk c+1.
+        if (!(a.debug & 2)) compute(lds + scur * C::STAGE, ost);
+        // One barrier per chunk: staged outputs before their write-out; chunk c+1's operands before their
+        // use; all reads of this stage before it is refilled next iteration; and the write-out of chunk
+        // c-1 (finished by every compute wave before it arrives here) before the staging tile of that
+        // parity is written again in chunk c+1.
         __syncthreads();
-        write_out(c, ost);
-        scur = snext;
+        if (!(a.debug & 8)) write_out(c, ost);
+        scur = (scur + 1 == NST) ? 0 : scur + 1;
     }
 
     if (a.hT) {
@@ -409,9 +425,9 @@ static hipError_t launch_dk(const ScanArgs<bf16_t>& a, int waves, hipStream_t st
     const int nsl = a.dv / (16 * waves);
     const dim3 grid((unsigned)(((n_chains + 7) / 8) * 8 * nsl));
     switch (waves) {
-        case 1: hipLaunchKernelGGL((scan_bf16_kernel<DK, 1>), grid, dim3(64), 0, st, a); break;
-        case 2: hipLaunchKernelGGL((scan_bf16_kernel<DK, 2>), grid, dim3(128), 0, st, a); break;
-        default: hipLaunchKernelGGL((scan_bf16_kernel<DK, 4>), grid, dim3(256), 0, st, a); break;
+        case 1: hipLaunchKernelGGL((scan_bf16_kernel<DK, 1>), grid, dim3(128), 0, st, a); break;
+        case 2: hipLaunchKernelGGL((scan_bf16_kernel<DK, 2>), grid, dim3(192), 0, st, a); break;
+        default: hipLaunchKernelGGL((scan_bf16_kernel<DK, 4>), grid, dim3(320), 0, st, a); break;
     }
     return hipGetLastError();
 }
