@@ -91,7 +91,17 @@ int chunk_fwd_impl(const void* q, const void* k, const void* v, const float* log
     ia.cu_seqlens = n_seq > 0 ? cu_dev : nullptr; ia.chunk_off = chunk_off; ia.n_seq = n_seq;
     ia.T = T; ia.NT = NT; ia.H = H;
     ia.wsT = wsT; ia.wsP = wsP; ia.wsG = wsG;
-    if (intra && kla::launch_intra<E>(ia, dk, (int)pl.n_chunks, st) != hipSuccess) return KLA_ERR_HIP;
+    if (intra) {
+        bool done = false;
+        if constexpr (sizeof(E) == 2) {
+            const char* impl = getenv("KLA_INTRA_IMPL");   // "generic": the element-type-generic kernel (A/B testing)
+            if (!(impl && impl[0] == 'g')) {
+                if (kla::launch_intra_bf16(ia, dk, (int)pl.n_chunks, st) != hipSuccess) return KLA_ERR_HIP;
+                done = true;
+            }
+        }
+        if (!done && kla::launch_intra<E>(ia, dk, (int)pl.n_chunks, st) != hipSuccess) return KLA_ERR_HIP;
+    }
     if (unpack && kla::launch_unpack<E>(wsT, wsP, wsG, Tb_out, P_out, g_out, pl.n_chunks * H, st) != hipSuccess)
         return KLA_ERR_HIP;
     if (!scan) return KLA_OK;

@@ -1,0 +1,70 @@
+// Device helpers shared by the bf16 chunk kernels (gfx950 only): native 128-bit register values,
+// direct global->LDS copies, the transposing LDS read, the swizzle of token-major LDS tiles, the bf16
+// MFMA with the slot order of kla_mma.hpp, and a wait on the vector-memory counter alone.
+#pragma once
+#include "kla_common.hpp"
+#include "kla_mma.hpp"
+
+namespace kla {
+
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) short4v* lds_short4_ptr;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // native 128-bit register value (never a stack object)
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ u32x4 ld16(const void* p) { return *reinterpret_cast<const u32x4*>(p); }
+__device__ __forceinline__ void st16(void* p, u32x4 v) { *reinterpret_cast<u32x4*>(p) = v; }
+
+// low three bits of the 16-byte column index are XORed with this function of the row
+__device__ __forceinline__ int swz_bits(int row) { return ((row & 1) << 2) | ((row >> 1) & 3); }
+
+__device__ __forceinline__ u32x2 lds_read_tr(const char* p)
+{
+    const short4v v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(p));
+    return __builtin_bit_cast(u32x2, v);
+}
+
+// 16 bytes per lane, global -> LDS without passing through registers: lane l's bytes land at
+// lds_wave_base + 16 l.  `lds_wave_base` must be wave-uniform (it goes to M0).  Written as inline
+// assembly on purpose: the compiler then keeps no book of these copies, so it puts no wait for them in
+// front of LDS reads of OTHER ring stages; completion is awaited explicitly (wait_vmcnt + barrier).
+// The global address is a wave-uniform base plus a 32-bit per-lane byte offset.
+__device__ __forceinline__ void dma16(const char* gbase_uniform, int lane_off, char* lds_wave_base)
+{
+    const uint32_t m = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) char*)lds_wave_base);
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane_off), "s"(gbase_uniform), "s"(m)
+                 : "memory");
+}
+
+// s_waitcnt on the vector-memory counter only (gfx9 encoding: vmcnt in bits 3:0 and 15:14)
+template <int N> __device__ __forceinline__ void wait_vmcnt()
+{
+    static_assert(N >= 0 && N < 64, "6-bit counter");
+    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+}
+
+__device__ __forceinline__ void mma_bf16(floatx4& acc, u32x4 a, u32x2 b0, u32x2 b1)
+{
+    const u32x4 b = {b0.x, b0.y, b1.x, b1.y};
+    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b),
+                                                  acc, 0, 0, 0);
+}
+__device__ __forceinline__ void mma_bf16(floatx4& acc, u32x2 a0, u32x2 a1, u32x2 b0, u32x2 b1)
+{
+    const u32x4 a = {a0.x, a0.y, a1.x, a1.y};
+    mma_bf16(acc, a, b0, b1);
+}
+__device__ __forceinline__ u32x2 to_quad(floatx4 x)
+{
+    const u32x2 q = {pack_bf16x2(x[0], x[1]), pack_bf16x2(x[2], x[3])};
+    return q;
+}
+__device__ __forceinline__ floatx4 quad_to_f(u32x2 q)
+{
+    floatx4 r;
+    r[0] = __uint_as_float(q.x << 16); r[1] = __uint_as_float(q.x & 0xffff0000u);
+    r[2] = __uint_as_float(q.y << 16); r[3] = __uint_as_float(q.y & 0xffff0000u);
+    return r;
+}
+__device__ __forceinline__ floatx4 ld_f4(const char* p) { return *reinterpret_cast<const floatx4*>(p); }
+
+}  // namespace kla

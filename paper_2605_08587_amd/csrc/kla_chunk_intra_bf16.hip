@@ -1,0 +1,316 @@
+// bf16 intra-chunk stage: same objects as kla_chunk_intra.hip (beta of eq. (3), g = log gamma,
+// T' = (I + B(A^- o KK^T))^{-1} B of eq. (6), P = A o QK^T of eq. (7), and the decay factors the scan
+// stage multiplies with), laid out for gfx950:
+//
+//   * K and Q go global -> LDS directly (global_load_lds_dwordx4) as token-major rows with the
+//     16-byte columns XOR-swizzled by the row; every MFMA operand slot is then one conflict-free
+//     128-bit LDS read of 8 consecutive features (A and B operands of both Gram products are rows of
+//     K or Q, so any slot order common to both is valid).
+//   * Each wave runs its five 16x16 tiles with five independent accumulators, operands one
+//     contraction step ahead.
+//   * (I+L)^{-1} is built IN PLACE in one fp32 64x64 LDS matrix (diagonal 16x16 blocks by forward
+//     substitution with the rows read one ahead, off-diagonal blocks by two levels of fp32 MFMA block
+//     products), and the fp32 image of P overlays the dead K/Q tiles: 50 KB of LDS, three workgroups
+//     per CU, so that one workgroup's global-memory latency hides behind the others' arithmetic.
+//   * Rows beyond a short last chunk re-read its last row; beta = 0 there zeroes their rows and columns
+//     of T', and their rows of P are masked.
+#include "kla_bf16_ops.hpp"
+#include "kla_common.hpp"
+#include "kla_kernels.hpp"
+#include "kla_mma.hpp"
+
+namespace kla {
+
+namespace {
+
+constexpr int kLd = 68;   // row stride (floats) of the fp32 64x64 matrices in LDS
+
+__device__ __constant__ const int8_t kTi[10] = {0, 1, 1, 2, 2, 2, 3, 3, 3, 3};
+__device__ __constant__ const int8_t kTj[10] = {0, 0, 1, 0, 1, 2, 0, 1, 2, 3};
+
+__device__ __forceinline__ floatx4 ldf4(const float* p) { return *reinterpret_cast<const floatx4*>(p); }
+// fp32 MFMA 16x16x16 = four 16x16x4 steps; quads hold contraction indices 4g..4g+3
+__device__ __forceinline__ void mma16f(floatx4& acc, floatx4 a, floatx4 b)
+{
+    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[0], b[0], acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[1], b[1], acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[2], b[2], acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[3], b[3], acc, 0, 0, 0);
+}
+// A-operand quad of a row-major fp32 matrix: columns 4g..4g+3 of row r
+__device__ __forceinline__ floatx4 aq(const float* m, int row0, int col0, int r, int g)
+{
+    return ldf4(m + (row0 + r) * kLd + col0 + 4 * g);
+}
+// B-operand quad: rows 4g..4g+3 of column r
+__device__ __forceinline__ floatx4 bq(const float* m, int row0, int col0, int r, int g)
+{
+    const float* p = m + (row0 + 4 * g) * kLd + col0 + r;
+    floatx4 x; x[0] = p[0]; x[1] = p[kLd]; x[2] = p[2 * kLd]; x[3] = p[3 * kLd]; return x;
+}
+
+}  // namespace
+
+template <int DK>
+__global__ __launch_bounds__(256) void intra_bf16_kernel(IntraArgs<bf16_t> a)
+{
+    constexpr int RB = DK * 2, PPR = DK / 8, KP = DK / 32;
+    constexpr int RPB = 1024 / RB, NKB = 64 / RPB;           // rows per 1 KiB copy block, blocks per tile
+    constexpr int TILE = 64 * RB;
+    constexpr int REC = ws_record_bytes<bf16_t>(), HALF = ws_half_bytes<bf16_t>();
+    static_assert(2 * TILE >= 64 * kLd * 4 || DK == 64, "P image overlays the K/Q tiles");
+
+    __shared__ __attribute__((aligned(1024))) char kq[2 * TILE > 64 * kLd * 4 ? 2 * TILE : 64 * kLd * 4];
+    __shared__ __attribute__((aligned(16))) float M[64 * kLd];
+    __shared__ __attribute__((aligned(16))) float beta_s[64];
+    __shared__ __attribute__((aligned(16))) float g_s[64];
+    float* Pm = reinterpret_cast<float*>(kq);
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int r = lane & 15, g = lane >> 4;
+
+    // ---- which chunk of which sequence -------------------------------------------------------
+    const int h = blockIdx.x % a.H;
+    const int cg = blockIdx.x / a.H;
+    long tok0; int clen;
+    if (a.cu_seqlens) {
+        int lo = 0, hi = a.n_seq - 1;                // last s with chunk_off[s] <= cg
+        while (lo < hi) { const int mid = (lo + hi + 1) >> 1; if (a.chunk_off[mid] <= cg) lo = mid; else hi = mid - 1; }
+        const int c = cg - a.chunk_off[lo];
+        const int s0 = a.cu_seqlens[lo], s1 = a.cu_seqlens[lo + 1];
+        tok0 = (long)s0 + 64L * c;
+        clen = min(64, s1 - (int)tok0);
+    } else {
+        const int n = cg / a.NT, c = cg % a.NT;
+        tok0 = (long)n * a.T + 64L * c;
+        clen = min(64, a.T - 64 * c);
+    }
+    char* rec = reinterpret_cast<char*>(a.wsT) + (size_t)blockIdx.x * REC;
+
+    // ---- phase 0: K, Q -> LDS by the copy engine; gates meanwhile ---------------------------------
+    {
+        const size_t kq_row = (size_t)a.H * DK * 2;
+        const char* kb = reinterpret_cast<const char*>(a.k) + (size_t)tok0 * kq_row + (size_t)h * DK * 2;
+        const char* qb = reinterpret_cast<const char*>(a.q) + (size_t)tok0 * kq_row + (size_t)h * DK * 2;
+        const int lrow = lane / PPR, pcol = lane % PPR;
+#pragma unroll
+        for (int i = 0; i < NKB / 4; ++i) {
+            const int b = wave + 4 * i;
+            const int row = b * RPB + lrow;
+            const int lo = min(row, clen - 1) * (int)kq_row + ((pcol ^ swz_bits(row)) * 16);
+            dma16(kb, lo, kq + b * 1024);
+            dma16(qb, lo, kq + TILE + b * 1024);
+        }
+        if (wave == 0) {
+            float x = lane < clen ? a.log_alpha[(size_t)(tok0 + lane) * a.H + h] : 0.f;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const float y = __shfl_up(x, off, kWave);
+                if (lane >= off) x += y;
+            }
+            g_s[lane] = x;
+            a.wsG[(size_t)blockIdx.x * 64 + lane] = x;
+            const float gl = __shfl(x, 63, kWave);
+            float* dec = reinterpret_cast<float*>(rec + 2 * HALF);
+            dec[lane] = expf(x);                     // gamma_i
+            dec[64 + lane] = expf(gl - x);           // gamma_C / gamma_i
+        }
+        wait_vmcnt<0>();
+    }
+    __syncthreads();
+
+    // ---- phase 1: key norms -> beta (each row's 16-byte pieces are split over 4 lanes) ------------
+    {
+        const int row = tid >> 2, q4 = tid & 3;
+        float ss = 0.f;
+#pragma unroll
+        for (int j = 0; j < PPR / 4; ++j) {
+            const int p = q4 * (PPR / 4) + j;
+            const u32x4 d = ld16(kq + row * RB + ((p ^ swz_bits(row)) * 16));
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+                const float x0 = __uint_as_float(d[m] << 16), x1 = __uint_as_float(d[m] & 0xffff0000u);
+                ss += x0 * x0; ss += x1 * x1;
+            }
+        }
+        ss += __shfl_xor(ss, 1, kWave);
+        ss += __shfl_xor(ss, 2, kWave);
+        if (q4 == 0) {
+            const float et = row < clen ? a.eta[(size_t)(tok0 + row) * a.H + h] : 0.f;
+            beta_s[row] = kaczmarz_beta(et, ss, a.eps);
+        }
+    }
+
+    // ---- phase 2a: Gram products K K^T and Q K^T on the lower-triangular tiles; five tiles per wave,
+    //      five independent accumulators, operands one contraction step ahead -----------------------
+    floatx4 acc[5];
+    {
+        int oa[5], ob[5];                            // per-lane byte offsets of the A and B slots at kp = 0
+#pragma unroll
+        for (int jb = 0; jb < 5; ++jb) {
+            const int job = wave + 4 * jb;           // 0..9: K K^T tiles, 10..19: Q K^T tiles
+            const int lt = job % 10;
+            oa[jb] = (job < 10 ? 0 : TILE) + (16 * kTi[lt] + r) * RB;
+            ob[jb] = (16 * kTj[lt] + r) * RB;
+            acc[jb] = floatx4{0.f, 0.f, 0.f, 0.f};
+        }
+        const int sw = swz_bits(r);                  // (16 t + r) & 7 == r & 7
+        u32x4 sa[2][5], sb[2][5];
+#pragma unroll
+        for (int jb = 0; jb < 5; ++jb) {
+            sa[0][jb] = ld16(kq + oa[jb] + ((g ^ sw) * 16));
+            sb[0][jb] = ld16(kq + ob[jb] + ((g ^ sw) * 16));
+        }
+#pragma unroll
+        for (int kp = 0; kp < KP; ++kp) {
+            if (kp + 1 < KP) {
+#pragma unroll
+                for (int jb = 0; jb < 5; ++jb) {
+                    const int c16 = (4 * (kp + 1) + g) ^ sw;
+                    sa[(kp + 1) & 1][jb] = ld16(kq + oa[jb] + c16 * 16);
+                    sb[(kp + 1) & 1][jb] = ld16(kq + ob[jb] + c16 * 16);
+                }
+            }
+#pragma unroll
+            for (int jb = 0; jb < 5; ++jb) {
+                const u32x4 b = sb[kp & 1][jb];
+                const u32x2 b0 = {b[0], b[1]}, b1 = {b[2], b[3]};
+                mma_bf16(acc[jb], sa[kp & 1][jb], b0, b1);
+            }
+        }
+    }
+    __syncthreads();   // K/Q tiles are dead from here on (Pm overlays them); beta_s is complete
+
+    // ---- phase 2b: decay, mask, beta -> L (into M) and P (into Pm) as fp32; zero the upper tiles ----
+#pragma unroll
+    for (int jb = 0; jb < 5; ++jb) {
+        const int job = wave + 4 * jb;
+        const int lt = job % 10;
+        const int ti = kTi[lt], tj = kTj[lt];
+        const int j = 16 * tj + r;
+        const float gj = g_s[j];
+        const floatx4 gi = ldf4(g_s + 16 * ti + 4 * g);
+        const floatx4 bi = ldf4(beta_s + 16 * ti + 4 * g);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int i = 16 * ti + 4 * g + e;
+            if (job < 10) M[i * kLd + j] = (j < i) ? bi[e] * expf(gi[e] - gj) * acc[jb][e] : 0.f;
+            else          Pm[i * kLd + j] = (j <= i && i < clen) ? expf(gi[e] - gj) * acc[jb][e] : 0.f;
+        }
+    }
+    for (int x = tid; x < 6 * 256; x += 256) {       // the six strictly-upper tiles
+        const int t = x >> 8, e = x & 255;
+        const int ti = t < 3 ? 0 : (t < 5 ? 1 : 2);
+        const int tj = t < 3 ? t + 1 : (t < 5 ? t - 1 : 3);
+        const int idx = (16 * ti + (e >> 4)) * kLd + 16 * tj + (e & 15);
+        M[idx] = 0.f; Pm[idx] = 0.f;
+    }
+    __syncthreads();
+
+    // ---- phase 3: diagonal 16x16 blocks D = (I + L_bb)^{-1} by forward substitution (wave w: block w,
+    //      lane column r, the four 16-lane groups redundantly), rows read one ahead; in place ---------
+    {
+        const float* Lb = M + (16 * wave) * kLd + 16 * wave;
+        float x[16];
+        floatx4 row[4], nxt[4] = {};
+#pragma unroll
+        for (int c4 = 0; c4 < 4; ++c4) row[c4] = ldf4(Lb + kLd + 4 * c4);          // row 1
+        x[0] = (r == 0) ? 1.f : 0.f;
+#pragma unroll
+        for (int i = 1; i < 16; ++i) {
+            if (i + 1 < 16) {
+#pragma unroll
+                for (int c4 = 0; c4 < 4; ++c4)
+                    if (4 * c4 <= i) nxt[c4] = ldf4(Lb + (i + 1) * kLd + 4 * c4);
+            }
+            float s0 = (i == r) ? 1.f : 0.f, s1 = 0.f;
+#pragma unroll
+            for (int rr = 0; rr < i; ++rr) {
+                if (rr & 1) s1 -= row[rr >> 2][rr & 3] * x[rr];
+                else        s0 -= row[rr >> 2][rr & 3] * x[rr];
+            }
+            x[i] = s0 + s1;
+#pragma unroll
+            for (int c4 = 0; c4 < 4; ++c4) row[c4] = nxt[c4];
+        }
+        // only this wave touches block (w, w), and its reads above precede these writes in program order
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+            if ((i >> 2) == g) M[(16 * wave + i) * kLd + 16 * wave + r] = x[i];
+    }
+    // P goes out to the workspace in operand order (fp32 image -> bf16 slots)
+    {
+        char* out = rec + HALF;
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+            const int sl = tid + 256 * it;           // slot index: stored tile-pair * 64 + lane
+            if (sl < kTriPairs * 64) {
+                const int ctp = sl >> 6, ln = sl & 63;
+                const int ti = ctp < 2 ? ctp : 2 + ((ctp - 2) >> 1), jp = ctp < 2 ? 0 : ((ctp - 2) & 1);
+                const int rw = 16 * ti + (ln & 15), cl = 32 * jp + 4 * (ln >> 4);
+                const u32x2 q0 = to_quad(ldf4(Pm + rw * kLd + cl)), q1 = to_quad(ldf4(Pm + rw * kLd + cl + 16));
+                const u32x4 v = {q0.x, q0.y, q1.x, q1.y};
+                st16(out + (size_t)sl * 16, v);
+            }
+        }
+    }
+    __syncthreads();
+
+    // ---- phase 4: 32x32 level, in place.  Waves 0,1: block pair (a, b) = (2m, 2m+1): T_ba = -D_b (L_ba D_a)
+    if (wave < 2) {
+        const int ra = 32 * wave, rb = ra + 16;
+        floatx4 y = {0.f, 0.f, 0.f, 0.f}, z = {0.f, 0.f, 0.f, 0.f};
+        mma16f(y, aq(M, rb, ra, r, g), bq(M, ra, ra, r, g));
+        mma16f(z, aq(M, rb, rb, r, g), y);           // an accumulator tile is the next product's B quad
+#pragma unroll
+        for (int e = 0; e < 4; ++e) M[(rb + 4 * g + e) * kLd + ra + r] = -z[e];    // only this wave read L_ba
+    }
+    __syncthreads();
+
+    // ---- phase 5: 64x64 level, in place.  T[32:64, 0:32] = -T22 (L21 T11); wave = (row tile ti, col tile tj)
+    {
+        const int ti = wave >> 1, tj = wave & 1;
+        floatx4 y0 = {0.f, 0.f, 0.f, 0.f}, y1 = {0.f, 0.f, 0.f, 0.f}, z = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int tm = 0; tm < 2; ++tm) {
+            const floatx4 b = bq(M, 16 * tm, 16 * tj, r, g);
+            mma16f(y0, aq(M, 32, 16 * tm, r, g), b);
+            mma16f(y1, aq(M, 48, 16 * tm, r, g), b);
+        }
+        mma16f(z, aq(M, 32 + 16 * ti, 32, r, g), y0);
+        mma16f(z, aq(M, 32 + 16 * ti, 48, r, g), y1);
+        __syncthreads();                             // all waves have read L21 before it is overwritten
+#pragma unroll
+        for (int e = 0; e < 4; ++e) M[(32 + 16 * ti + 4 * g + e) * kLd + 16 * tj + r] = -z[e];
+    }
+    __syncthreads();
+
+    // ---- phase 6: T' = T diag(beta) -> workspace in operand order ------------------------------
+    {
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+            const int sl = tid + 256 * it;
+            if (sl < kTriPairs * 64) {
+                const int ctp = sl >> 6, ln = sl & 63;
+                const int ti = ctp < 2 ? ctp : 2 + ((ctp - 2) >> 1), jp = ctp < 2 ? 0 : ((ctp - 2) & 1);
+                const int rw = 16 * ti + (ln & 15), cl = 32 * jp + 4 * (ln >> 4);
+                const u32x2 q0 = to_quad(ldf4(M + rw * kLd + cl) * ldf4(beta_s + cl));
+                const u32x2 q1 = to_quad(ldf4(M + rw * kLd + cl + 16) * ldf4(beta_s + cl + 16));
+                const u32x4 v = {q0.x, q0.y, q1.x, q1.y};
+                st16(rec + (size_t)sl * 16, v);
+            }
+        }
+    }
+}
+
+hipError_t launch_intra_bf16(const IntraArgs<bf16_t>& a, int dk, int n_chunks, hipStream_t st)
+{
+    if (n_chunks == 0) return hipSuccess;
+    const dim3 grid((unsigned)n_chunks * a.H), block(256);
+    if (dk == 64) hipLaunchKernelGGL((intra_bf16_kernel<64>), grid, block, 0, st, a);
+    else          hipLaunchKernelGGL((intra_bf16_kernel<128>), grid, block, 0, st, a);
+    return hipGetLastError();
+}
+
+}  // namespace kla

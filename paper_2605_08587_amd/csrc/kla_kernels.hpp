@@ -41,7 +41,8 @@ template <typename E> struct ScanArgs {
 // waves = 1, 2 or 4: each wave of a workgroup carries 16 state columns through the whole sequence
 template <typename E> hipError_t launch_scan(const ScanArgs<E>& a, int dk, int waves, hipStream_t st);
 
-// bf16 specialisation of the scan stage (transposing LDS reads, swizzled token-major staging)
+// bf16 specialisations (direct global->LDS copies, swizzled token-major staging, transposing LDS reads)
+hipError_t launch_intra_bf16(const IntraArgs<bf16_t>& a, int dk, int n_chunks, hipStream_t st);
 hipError_t launch_scan_bf16(const ScanArgs<bf16_t>& a, int dk, int waves, hipStream_t st);
 
 hipError_t launch_chunk_offsets(const int* cu_seqlens, int n_seq, int* chunk_off, hipStream_t st);
