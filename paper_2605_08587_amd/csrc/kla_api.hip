@@ -91,6 +91,7 @@ int chunk_fwd_impl(const void* q, const void* k, const void* v, const float* log
     ia.cu_seqlens = n_seq > 0 ? cu_dev : nullptr; ia.chunk_off = chunk_off; ia.n_seq = n_seq;
     ia.T = T; ia.NT = NT; ia.H = H;
     ia.wsT = wsT; ia.wsP = wsP; ia.wsG = wsG;
+    { const char* dbg = getenv("KLA_INTRA_DEBUG"); ia.debug = dbg ? atoi(dbg) : 0; }
     if (intra) {
         bool done = false;
         if constexpr (sizeof(E) == 2) {

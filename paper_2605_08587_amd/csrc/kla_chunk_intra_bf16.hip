@@ -52,7 +52,7 @@ __device__ __forceinline__ floatx4 bq(const float* m, int row0, int col0, int r,
 }  // namespace
 
 template <int DK>
-__global__ __launch_bounds__(256) void intra_bf16_kernel(IntraArgs<bf16_t> a)
+__global__ __launch_bounds__(256, 3) void intra_bf16_kernel(IntraArgs<bf16_t> a)
 {
     constexpr int RB = DK * 2, PPR = DK / 8, KP = DK / 32;
     constexpr int RPB = 1024 / RB, NKB = 64 / RPB;           // rows per 1 KiB copy block, blocks per tile
@@ -109,7 +109,7 @@ __global__ __launch_bounds__(256) void intra_bf16_kernel(IntraArgs<bf16_t> a)
                 const float y = __shfl_up(x, off, kWave);
                 if (lane >= off) x += y;
             }
-            g_s[lane] = x;
+            g_s[lane] = x * 1.44269504088896341f;    // in units of log 2: ratios below are single v_exp_f32
             a.wsG[(size_t)blockIdx.x * 64 + lane] = x;
             const float gl = __shfl(x, 63, kWave);
             float* dec = reinterpret_cast<float*>(rec + 2 * HALF);
@@ -119,6 +119,7 @@ __global__ __launch_bounds__(256) void intra_bf16_kernel(IntraArgs<bf16_t> a)
         wait_vmcnt<0>();
     }
     __syncthreads();
+    if (a.debug & 32) return;
 
     // ---- phase 1: key norms -> beta (each row's 16-byte pieces are split over 4 lanes) ------------
     {
@@ -162,6 +163,7 @@ __global__ __launch_bounds__(256) void intra_bf16_kernel(IntraArgs<bf16_t> a)
             sa[0][jb] = ld16(kq + oa[jb] + ((g ^ sw) * 16));
             sb[0][jb] = ld16(kq + ob[jb] + ((g ^ sw) * 16));
         }
+        if (!(a.debug & 1))
 #pragma unroll
         for (int kp = 0; kp < KP; ++kp) {
             if (kp + 1 < KP) {
@@ -183,6 +185,7 @@ __global__ __launch_bounds__(256) void intra_bf16_kernel(IntraArgs<bf16_t> a)
     __syncthreads();   // K/Q tiles are dead from here on (Pm overlays them); beta_s is complete
 
     // ---- phase 2b: decay, mask, beta -> L (into M) and P (into Pm) as fp32; zero the upper tiles ----
+    if (!(a.debug & 8))
 #pragma unroll
     for (int jb = 0; jb < 5; ++jb) {
         const int job = wave + 4 * jb;
@@ -195,8 +198,9 @@ __global__ __launch_bounds__(256) void intra_bf16_kernel(IntraArgs<bf16_t> a)
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const int i = 16 * ti + 4 * g + e;
-            if (job < 10) M[i * kLd + j] = (j < i) ? bi[e] * expf(gi[e] - gj) * acc[jb][e] : 0.f;
-            else          Pm[i * kLd + j] = (j <= i && i < clen) ? expf(gi[e] - gj) * acc[jb][e] : 0.f;
+            // gamma_i / gamma_j = 2^(g_i - g_j), formed only where j <= i (the exponent is then <= 0)
+            if (job < 10) M[i * kLd + j] = (j < i) ? bi[e] * __builtin_amdgcn_exp2f(gi[e] - gj) * acc[jb][e] : 0.f;
+            else          Pm[i * kLd + j] = (j <= i && i < clen) ? __builtin_amdgcn_exp2f(gi[e] - gj) * acc[jb][e] : 0.f;
         }
     }
     for (int x = tid; x < 6 * 256; x += 256) {       // the six strictly-upper tiles
@@ -210,7 +214,7 @@ __global__ __launch_bounds__(256) void intra_bf16_kernel(IntraArgs<bf16_t> a)
 
     // ---- phase 3: diagonal 16x16 blocks D = (I + L_bb)^{-1} by forward substitution (wave w: block w,
     //      lane column r, the four 16-lane groups redundantly), rows read one ahead; in place ---------
-    {
+    if (!(a.debug & 2)) {
         const float* Lb = M + (16 * wave) * kLd + 16 * wave;
         float x[16];
         floatx4 row[4], nxt[4] = {};
@@ -240,7 +244,7 @@ __global__ __launch_bounds__(256) void intra_bf16_kernel(IntraArgs<bf16_t> a)
             if ((i >> 2) == g) M[(16 * wave + i) * kLd + 16 * wave + r] = x[i];
     }
     // P goes out to the workspace in operand order (fp32 image -> bf16 slots)
-    {
+    if (!(a.debug & 16)) {
         char* out = rec + HALF;
 #pragma unroll
         for (int it = 0; it < 2; ++it) {
@@ -258,7 +262,7 @@ __global__ __launch_bounds__(256) void intra_bf16_kernel(IntraArgs<bf16_t> a)
     __syncthreads();
 
     // ---- phase 4: 32x32 level, in place.  Waves 0,1: block pair (a, b) = (2m, 2m+1): T_ba = -D_b (L_ba D_a)
-    if (wave < 2) {
+    if (wave < 2 && !(a.debug & 4)) {
         const int ra = 32 * wave, rb = ra + 16;
         floatx4 y = {0.f, 0.f, 0.f, 0.f}, z = {0.f, 0.f, 0.f, 0.f};
         mma16f(y, aq(M, rb, ra, r, g), bq(M, ra, ra, r, g));
@@ -269,7 +273,7 @@ __global__ __launch_bounds__(256) void intra_bf16_kernel(IntraArgs<bf16_t> a)
     __syncthreads();
 
     // ---- phase 5: 64x64 level, in place.  T[32:64, 0:32] = -T22 (L21 T11); wave = (row tile ti, col tile tj)
-    {
+    if (!(a.debug & 4)) {
         const int ti = wave >> 1, tj = wave & 1;
         floatx4 y0 = {0.f, 0.f, 0.f, 0.f}, y1 = {0.f, 0.f, 0.f, 0.f}, z = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -287,7 +291,7 @@ __global__ __launch_bounds__(256) void intra_bf16_kernel(IntraArgs<bf16_t> a)
     __syncthreads();
 
     // ---- phase 6: T' = T diag(beta) -> workspace in operand order ------------------------------
-    {
+    if (!(a.debug & 16)) {
 #pragma unroll
         for (int it = 0; it < 2; ++it) {
             const int sl = tid + 256 * it;

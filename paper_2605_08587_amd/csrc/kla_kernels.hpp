@@ -27,6 +27,7 @@ template <typename E> struct IntraArgs {
     const int* cu_seqlens; const int* chunk_off; int n_seq;
     int T, NT, H;
     E* wsT; E* wsP; float* wsG;
+    int debug;
 };
 template <typename E> hipError_t launch_intra(const IntraArgs<E>& a, int dk, int n_chunks, hipStream_t st);
 
