@@ -63,8 +63,11 @@ int scan_waves(int n_chains, int dv, int dt)
     if (env && (atoi(env) == 1 || atoi(env) == 2 || atoi(env) == 4)) w = atoi(env);
     else {
         // enough workgroups to cover the 256 CUs, else the widest slice that still gives >= 2 waves of loaders
+        // workgroups for w waves: chains8 * dv / (16 w).  Wide slices halve the operand re-reads but need
+        // enough workgroups to cover the 256 CUs; a lone long sequence is latency-bound and runs best narrow.
         const long chains8 = ((long)n_chains + 7) / 8 * 8;
-        w = (chains8 * (dv / 64) >= 512) ? 4 : 2;
+        const long wg1 = chains8 * (dv / 16);
+        w = (wg1 / 4 >= 512) ? 4 : ((wg1 / 2 >= 192) ? 2 : 1);
     }
     if (dt == KLA_F32 && w > 2) w = 2;            // fp32 operands take twice the LDS
     while (16 * w > dv) w >>= 1;
@@ -233,7 +236,7 @@ int kla_decode_step(const void* q, const void* k, const void* v, const float* lo
     if (!aligned16(S) || (reinterpret_cast<uintptr_t>(q) & 3u) || (reinterpret_cast<uintptr_t>(k) & 3u) ||
         (reinterpret_cast<uintptr_t>(v) & 3u) || (reinterpret_cast<uintptr_t>(o) & 3u))
         return KLA_ERR_ALIGN;
-    int slice = 64;                                   // state columns per workgroup
+    int slice = 128;                                  // state columns per workgroup
     const char* env = getenv("KLA_DECODE_SLICE");     // tuning knob: 32, 64, 128 or 256
     if (env) { const int x = atoi(env); if (x == 32 || x == 64 || x == 128 || x == 256) slice = x; }
     if (slice > dv) slice = dv;
