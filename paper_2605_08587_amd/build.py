@@ -16,6 +16,9 @@ SOURCES = ["kla_api.hip", "kla_decode.hip", "kla_chunk_intra.hip", "kla_chunk_in
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          # hipcc -O3 must not form packed-fp32 instructions on the test machines
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # keep MFMA accumulators in ordinary VGPRs: the kernels scale and convert them between products,
+         # and the AGPR form costs a register move per element each way
+         "-mllvm", "-amdgpu-mfma-vgpr-form",
          "-Wno-unused-command-line-argument"]
 
 

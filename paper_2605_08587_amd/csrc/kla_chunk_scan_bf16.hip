@@ -303,7 +303,8 @@ __global__ __launch_bounds__(64 * NW + 64) void scan_bf16_kernel(ScanArgs<bf16_t
         for (int it = 0; it < 64 * VPP / NTH; ++it) {
             const int i = tid + NTH * it;
             const int row = i / VPP, pv = i % VPP;
-            if (row < clen) st16(ob + (size_t)row * v_row + pv * 16, ld16(ost + row * ORB + pv * 16));
+            // outputs are written once and not read again by this kernel: streamed past the caches
+            if (row < clen) __builtin_nontemporal_store(ld16(ost + row * ORB + pv * 16), reinterpret_cast<u32x4*>(ob + (size_t)row * v_row + pv * 16));
         }
     };
 
