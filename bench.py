@@ -41,14 +41,16 @@ def _events(torch, fn, reps):
     return e0.elapsed_time(e1) / reps
 
 
-def _traffic(name):
-    """HBM bytes per launch from committed rocprofv3 --pmc runs (profiles/<name>), or None."""
-    p = os.path.join(ROOT, "profiles", name)
-    if os.path.exists(p):
-        try:
-            return json.load(open(p)).get("hbm_bytes_per_launch")
-        except Exception:
-            return None
+def _traffic(key):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary (profiles/hbm_traffic_per_launch.txt), or None."""
+    p = os.path.join(ROOT, "profiles", "hbm_traffic_per_launch.txt")
+    try:
+        for line in open(p):
+            f = line.split()
+            if len(f) >= 2 and f[0] == key:
+                return int(f[1])
+    except OSError:
+        pass
     return None
 
 
@@ -59,6 +61,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--skip-cpu-baseline", action="store_true")
     ap.add_argument("--skip-decode", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="only run a plain device copy of 1 GiB five times (reference for the rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is single-GPU by design (no collectives, no sharding); run with --gpus 1",
@@ -74,6 +78,15 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     kla.lib()   # fails loudly if the HIP library is not built
+
+    if args.copy_probe:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe_bytes_read": 1 << 30, "copy_probe_bytes_written": 1 << 30, "launches": 5}))
+        return
 
     # ------------------------------------------------------------------ chunk forward, config 2
     d = kla_inputs.config(2)
@@ -107,7 +120,7 @@ def main():
     alg_bytes = CHUNK_BYTES_PER_TOKEN_HEAD * token_heads
     achieved = alg_bytes / (dom[1] * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": dom[0], "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": _traffic("chunk_%s_config2_traffic.json" % dom[0]),
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": _traffic("chunk_%s_config2" % dom[0]),
                 "algorithmic_bytes_per_launch": alg_bytes, "ms_per_launch": round(dom[1], 4),
                 "ms_intra_kernel": round(ms_intra, 4), "ms_scan_kernel": round(ms_scan, 4)}
     tflops = CHUNK_FLOP_PER_TOKEN_HEAD * token_heads / (ms_per_step * 1e-3) / 1e12
@@ -146,7 +159,7 @@ def main():
                   "roofline": {"bound": "hbm", "kernel": "decode_kernel",
                                "achieved": round(bytes256 / (ms256_cold * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBS,
                                "unit": "GB/s", "frac": round(bytes256 / (ms256_cold * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-                               "traffic": _traffic("decode_kernel_config4_traffic.json"),
+                               "traffic": _traffic("decode_kernel_config4"),
                                "note": "state rotated over 24 sets (805 MB, one per layer of the 0.4B model): never resident in the Infinity Cache",
                                "us_per_step": round(ms256_cold * 1e3 / steps, 3)},
                   "same_state_GBps": round(bytes256 / (ms256 * 1e-3) / 1e9, 1)}
