@@ -64,6 +64,7 @@ __global__ __launch_bounds__(256, 3) void intra_bf16_kernel(IntraArgs<bf16_t> a)
     __shared__ __attribute__((aligned(16))) float M[64 * kLd];
     __shared__ __attribute__((aligned(16))) float beta_s[64];
     __shared__ __attribute__((aligned(16))) float g_s[64];
+    __shared__ __attribute__((aligned(16))) float eta_s[64];
     float* Pm = reinterpret_cast<float*>(kq);
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -109,39 +110,19 @@ __global__ __launch_bounds__(256, 3) void intra_bf16_kernel(IntraArgs<bf16_t> a)
                 const float y = __shfl_up(x, off, kWave);
                 if (lane >= off) x += y;
             }
-            g_s[lane] = x * 1.44269504088896341f;    // in units of log 2: ratios below are single v_exp_f32
+            const float x2 = x * 1.44269504088896341f;   // in units of log 2: every decay ratio is one v_exp_f32
+            g_s[lane] = x2;
+            eta_s[lane] = lane < clen ? a.eta[(size_t)(tok0 + lane) * a.H + h] : 0.f;
             a.wsG[(size_t)blockIdx.x * 64 + lane] = x;
-            const float gl = __shfl(x, 63, kWave);
+            const float gl2 = __shfl(x2, 63, kWave);
             float* dec = reinterpret_cast<float*>(rec + 2 * HALF);
-            dec[lane] = expf(x);                     // gamma_i
-            dec[64 + lane] = expf(gl - x);           // gamma_C / gamma_i
+            dec[lane] = __builtin_amdgcn_exp2f(x2);            // gamma_i
+            dec[64 + lane] = __builtin_amdgcn_exp2f(gl2 - x2); // gamma_C / gamma_i
         }
         wait_vmcnt<0>();
     }
     __syncthreads();
     if (a.debug & 32) return;
-
-    // ---- phase 1: key norms -> beta (each row's 16-byte pieces are split over 4 lanes) ------------
-    {
-        const int row = tid >> 2, q4 = tid & 3;
-        float ss = 0.f;
-#pragma unroll
-        for (int j = 0; j < PPR / 4; ++j) {
-            const int p = q4 * (PPR / 4) + j;
-            const u32x4 d = ld16(kq + row * RB + ((p ^ swz_bits(row)) * 16));
-#pragma unroll
-            for (int m = 0; m < 4; ++m) {
-                const float x0 = __uint_as_float(d[m] << 16), x1 = __uint_as_float(d[m] & 0xffff0000u);
-                ss += x0 * x0; ss += x1 * x1;
-            }
-        }
-        ss += __shfl_xor(ss, 1, kWave);
-        ss += __shfl_xor(ss, 2, kWave);
-        if (q4 == 0) {
-            const float et = row < clen ? a.eta[(size_t)(tok0 + row) * a.H + h] : 0.f;
-            beta_s[row] = kaczmarz_beta(et, ss, a.eps);
-        }
-    }
 
     // ---- phase 2a: Gram products K K^T and Q K^T on the lower-triangular tiles; five tiles per wave,
     //      five independent accumulators, operands one contraction step ahead -----------------------
@@ -182,6 +163,18 @@ __global__ __launch_bounds__(256, 3) void intra_bf16_kernel(IntraArgs<bf16_t> a)
             }
         }
     }
+    // ||k_i||^2 is the diagonal of K K^T (exact bf16 products, fp32 sums): beta of eq. (3) from the four
+    // diagonal tiles, by the lane that holds element (i, i)
+#pragma unroll
+    for (int jb = 0; jb < 3; ++jb) {
+        const int job = wave + 4 * jb;
+        if (job == 0 || job == 2 || job == 5 || job == 9) {
+            const int ti = kTi[job];
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (4 * g + e == r) beta_s[16 * ti + r] = kaczmarz_beta(eta_s[16 * ti + r], acc[jb][e], a.eps);
+        }
+    }
     __syncthreads();   // K/Q tiles are dead from here on (Pm overlays them); beta_s is complete
 
     // ---- phase 2b: decay, mask, beta -> L (into M) and P (into Pm) as fp32; zero the upper tiles ----
@@ -203,13 +196,7 @@ __global__ __launch_bounds__(256, 3) void intra_bf16_kernel(IntraArgs<bf16_t> a)
             else          Pm[i * kLd + j] = (j <= i && i < clen) ? __builtin_amdgcn_exp2f(gi[e] - gj) * acc[jb][e] : 0.f;
         }
     }
-    for (int x = tid; x < 6 * 256; x += 256) {       // the six strictly-upper tiles
-        const int t = x >> 8, e = x & 255;
-        const int ti = t < 3 ? 0 : (t < 5 ? 1 : 2);
-        const int tj = t < 3 ? t + 1 : (t < 5 ? t - 1 : 3);
-        const int idx = (16 * ti + (e >> 4)) * kLd + 16 * tj + (e & 15);
-        M[idx] = 0.f; Pm[idx] = 0.f;
-    }
+    // the six strictly-upper tiles are never written: every reader below knows they are zero
     __syncthreads();
 
     // ---- phase 3: diagonal 16x16 blocks D = (I + L_bb)^{-1} by forward substitution (wave w: block w,
@@ -253,7 +240,9 @@ __global__ __launch_bounds__(256, 3) void intra_bf16_kernel(IntraArgs<bf16_t> a)
                 const int ctp = sl >> 6, ln = sl & 63;
                 const int ti = ctp < 2 ? ctp : 2 + ((ctp - 2) >> 1), jp = ctp < 2 ? 0 : ((ctp - 2) & 1);
                 const int rw = 16 * ti + (ln & 15), cl = 32 * jp + 4 * (ln >> 4);
-                const u32x2 q0 = to_quad(ldf4(Pm + rw * kLd + cl)), q1 = to_quad(ldf4(Pm + rw * kLd + cl + 16));
+                const bool up = ctp == 0 || ctp == 3;         // second block of the pair is an upper tile: zero
+                const u32x2 q0 = to_quad(ldf4(Pm + rw * kLd + cl));
+                const u32x2 q1 = up ? u32x2{0u, 0u} : to_quad(ldf4(Pm + rw * kLd + cl + 16));
                 const u32x4 v = {q0.x, q0.y, q1.x, q1.y};
                 st16(out + (size_t)sl * 16, v);
             }
@@ -278,12 +267,13 @@ __global__ __launch_bounds__(256, 3) void intra_bf16_kernel(IntraArgs<bf16_t> a)
         floatx4 y0 = {0.f, 0.f, 0.f, 0.f}, y1 = {0.f, 0.f, 0.f, 0.f}, z = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int tm = 0; tm < 2; ++tm) {
+            if (tm == 0 && tj == 1) continue;        // T11 tile (0, 1) is zero
             const floatx4 b = bq(M, 16 * tm, 16 * tj, r, g);
             mma16f(y0, aq(M, 32, 16 * tm, r, g), b);
             mma16f(y1, aq(M, 48, 16 * tm, r, g), b);
         }
         mma16f(z, aq(M, 32 + 16 * ti, 32, r, g), y0);
-        mma16f(z, aq(M, 32 + 16 * ti, 48, r, g), y1);
+        if (ti == 1) mma16f(z, aq(M, 32 + 16 * ti, 48, r, g), y1);   // T22 tile (0, 1) is zero
         __syncthreads();                             // all waves have read L21 before it is overwritten
 #pragma unroll
         for (int e = 0; e < 4; ++e) M[(32 + 16 * ti + 4 * g + e) * kLd + 16 * tj + r] = -z[e];
@@ -299,8 +289,9 @@ __global__ __launch_bounds__(256, 3) void intra_bf16_kernel(IntraArgs<bf16_t> a)
                 const int ctp = sl >> 6, ln = sl & 63;
                 const int ti = ctp < 2 ? ctp : 2 + ((ctp - 2) >> 1), jp = ctp < 2 ? 0 : ((ctp - 2) & 1);
                 const int rw = 16 * ti + (ln & 15), cl = 32 * jp + 4 * (ln >> 4);
+                const bool up = ctp == 0 || ctp == 3;
                 const u32x2 q0 = to_quad(ldf4(M + rw * kLd + cl) * ldf4(beta_s + cl));
-                const u32x2 q1 = to_quad(ldf4(M + rw * kLd + cl + 16) * ldf4(beta_s + cl + 16));
+                const u32x2 q1 = up ? u32x2{0u, 0u} : to_quad(ldf4(M + rw * kLd + cl + 16) * ldf4(beta_s + cl + 16));
                 const u32x4 v = {q0.x, q0.y, q1.x, q1.y};
                 st16(rec + (size_t)sl * 16, v);
             }
