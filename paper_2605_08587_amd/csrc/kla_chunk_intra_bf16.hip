@@ -25,8 +25,22 @@ namespace {
 
 constexpr int kLd = 68;   // row stride (floats) of the fp32 64x64 matrices in LDS
 
-__device__ __constant__ const int8_t kTi[10] = {0, 1, 1, 2, 2, 2, 3, 3, 3, 3};
-__device__ __constant__ const int8_t kTj[10] = {0, 0, 1, 0, 1, 2, 0, 1, 2, 3};
+// The 20 lower-triangular 16x16 tiles of K K^T (q = 0) and Q K^T (q = 1), five per wave, grouped so that a
+// wave's tiles share operands: the A slots of tile (ti, tj) are rows 16 ti.. of K (or Q), the B slots rows
+// 16 tj.. of K, and a K row block is the same registers in either role.  Waves 0..3 need 5, 4, 5, 4 distinct
+// row blocks per contraction step instead of 10.
+struct GramJob { int q, ti, tj; };
+constexpr GramJob kJobs[4][5] = {
+    {{1, 3, 0}, {1, 3, 1}, {1, 3, 2}, {1, 3, 3}, {0, 3, 3}},
+    {{0, 3, 0}, {0, 3, 1}, {0, 3, 2}, {0, 2, 0}, {0, 2, 1}},
+    {{1, 2, 0}, {1, 2, 1}, {1, 2, 2}, {1, 1, 0}, {1, 1, 1}},
+    {{0, 0, 0}, {0, 1, 0}, {0, 1, 1}, {0, 2, 2}, {1, 0, 0}}};
+constexpr bool gram_needs(int w, int blk)            // blk 0..3: K row block, 4..7: Q row block
+{
+    for (int j = 0; j < 5; ++j)
+        if (kJobs[w][j].q * 4 + kJobs[w][j].ti == blk || kJobs[w][j].tj == blk) return true;
+    return false;
+}
 
 __device__ __forceinline__ floatx4 ldf4(const float* p) { return *reinterpret_cast<const floatx4*>(p); }
 // fp32 MFMA 16x16x16 = four 16x16x4 steps; quads hold contraction indices 4g..4g+3
@@ -125,77 +139,85 @@ __global__ __launch_bounds__(256, 3) void intra_bf16_kernel(IntraArgs<bf16_t> a)
     if (a.debug & 32) return;
 
     // ---- phase 2a: Gram products K K^T and Q K^T on the lower-triangular tiles; five tiles per wave,
-    //      five independent accumulators, operands one contraction step ahead -----------------------
+    //      five independent accumulators, shared operand row blocks read one contraction step ahead ----
     floatx4 acc[5];
+#pragma unroll
+    for (int jb = 0; jb < 5; ++jb) acc[jb] = floatx4{0.f, 0.f, 0.f, 0.f};
     {
-        int oa[5], ob[5];                            // per-lane byte offsets of the A and B slots at kp = 0
-#pragma unroll
-        for (int jb = 0; jb < 5; ++jb) {
-            const int job = wave + 4 * jb;           // 0..9: K K^T tiles, 10..19: Q K^T tiles
-            const int lt = job % 10;
-            oa[jb] = (job < 10 ? 0 : TILE) + (16 * kTi[lt] + r) * RB;
-            ob[jb] = (16 * kTj[lt] + r) * RB;
-            acc[jb] = floatx4{0.f, 0.f, 0.f, 0.f};
-        }
         const int sw = swz_bits(r);                  // (16 t + r) & 7 == r & 7
-        u32x4 sa[2][5], sb[2][5];
+        const char* rowp = kq + r * RB;              // row r of row block 0 of K; block b: + (b & 3) 16 RB (+ TILE for Q)
+        static_for<4>([&](auto wc) {
+            constexpr int W = wc;
+            if (wave != W) return;
+            u32x4 sl[2][8];
+            auto load = [&](int kp, u32x4 (&dst)[8]) {
+                const int c16 = ((4 * kp + g) ^ sw) * 16;
+                static_for<8>([&](auto bc) {
+                    constexpr int B = bc;
+                    if constexpr (gram_needs(W, B)) dst[B] = ld16(rowp + (B >> 2) * TILE + (B & 3) * 16 * RB + c16);
+                });
+            };
+            load(0, sl[0]);
+            static_for<KP>([&](auto kc) {
+                constexpr int kp = kc;
+                if constexpr (kp + 1 < KP) load(kp + 1, sl[(kp + 1) & 1]);
+                static_for<5>([&](auto jc) {
+                    constexpr int jb = jc;
+                    constexpr GramJob J = kJobs[W][jb];
+                    const u32x4 b = sl[kp & 1][J.tj];
+                    const u32x2 b0 = {b[0], b[1]}, b1 = {b[2], b[3]};
+                    mma_bf16(acc[jb], sl[kp & 1][J.q * 4 + J.ti], b0, b1);
+                });
+            });
+            // ||k_i||^2 is the diagonal of K K^T (exact bf16 products, fp32 sums): beta of eq. (3) from the
+            // four diagonal tiles, by the lane that holds element (i, i)
+            static_for<5>([&](auto jc) {
+                constexpr int jb = jc;
+                constexpr GramJob J = kJobs[W][jb];
+                if constexpr (J.q == 0 && J.ti == J.tj) {
 #pragma unroll
-        for (int jb = 0; jb < 5; ++jb) {
-            sa[0][jb] = ld16(kq + oa[jb] + ((g ^ sw) * 16));
-            sb[0][jb] = ld16(kq + ob[jb] + ((g ^ sw) * 16));
-        }
-        if (!(a.debug & 1))
-#pragma unroll
-        for (int kp = 0; kp < KP; ++kp) {
-            if (kp + 1 < KP) {
-#pragma unroll
-                for (int jb = 0; jb < 5; ++jb) {
-                    const int c16 = (4 * (kp + 1) + g) ^ sw;
-                    sa[(kp + 1) & 1][jb] = ld16(kq + oa[jb] + c16 * 16);
-                    sb[(kp + 1) & 1][jb] = ld16(kq + ob[jb] + c16 * 16);
+                    for (int e = 0; e < 4; ++e)
+                        if (4 * g + e == r) beta_s[16 * J.ti + r] = kaczmarz_beta_fast(eta_s[16 * J.ti + r], acc[jb][e], a.eps);
                 }
-            }
-#pragma unroll
-            for (int jb = 0; jb < 5; ++jb) {
-                const u32x4 b = sb[kp & 1][jb];
-                const u32x2 b0 = {b[0], b[1]}, b1 = {b[2], b[3]};
-                mma_bf16(acc[jb], sa[kp & 1][jb], b0, b1);
-            }
-        }
-    }
-    // ||k_i||^2 is the diagonal of K K^T (exact bf16 products, fp32 sums): beta of eq. (3) from the four
-    // diagonal tiles, by the lane that holds element (i, i)
-#pragma unroll
-    for (int jb = 0; jb < 3; ++jb) {
-        const int job = wave + 4 * jb;
-        if (job == 0 || job == 2 || job == 5 || job == 9) {
-            const int ti = kTi[job];
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-                if (4 * g + e == r) beta_s[16 * ti + r] = kaczmarz_beta(eta_s[16 * ti + r], acc[jb][e], a.eps);
-        }
+            });
+        });
     }
     __syncthreads();   // K/Q tiles are dead from here on (Pm overlays them); beta_s is complete
 
-    // ---- phase 2b: decay, mask, beta -> L (into M) and P (into Pm) as fp32; zero the upper tiles ----
+    // ---- phase 2b: decay, mask, beta -> L (into M) and P (into Pm) as fp32.  Tile coordinates are compile-time
+    //      per wave, so only the diagonal tiles pay for the triangular mask ------------------------------
     if (!(a.debug & 8))
+    static_for<4>([&](auto wc) {
+        constexpr int W = wc;
+        if (wave != W) return;
+        static_for<5>([&](auto jc) {
+            constexpr int jb = jc;
+            constexpr GramJob J = kJobs[W][jb];
+            constexpr int ti = J.ti, tj = J.tj;
+            const float gj = g_s[16 * tj + r];
+            const floatx4 gi = ldf4(g_s + 16 * ti + 4 * g);
+            floatx4 f;                               // gamma_i / gamma_j = 2^(g_i - g_j), only used where j <= i
 #pragma unroll
-    for (int jb = 0; jb < 5; ++jb) {
-        const int job = wave + 4 * jb;
-        const int lt = job % 10;
-        const int ti = kTi[lt], tj = kTj[lt];
-        const int j = 16 * tj + r;
-        const float gj = g_s[j];
-        const floatx4 gi = ldf4(g_s + 16 * ti + 4 * g);
-        const floatx4 bi = ldf4(beta_s + 16 * ti + 4 * g);
+            for (int e = 0; e < 4; ++e) f[e] = __builtin_amdgcn_exp2f(ti == tj ? fminf(gi[e] - gj, 0.f) : gi[e] - gj);
+            if constexpr (J.q == 0) {
+                const floatx4 bi = ldf4(beta_s + 16 * ti + 4 * g);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const int i = 16 * ti + 4 * g + e;
-            // gamma_i / gamma_j = 2^(g_i - g_j), formed only where j <= i (the exponent is then <= 0)
-            if (job < 10) M[i * kLd + j] = (j < i) ? bi[e] * __builtin_amdgcn_exp2f(gi[e] - gj) * acc[jb][e] : 0.f;
-            else          Pm[i * kLd + j] = (j <= i && i < clen) ? __builtin_amdgcn_exp2f(gi[e] - gj) * acc[jb][e] : 0.f;
-        }
-    }
+                for (int e = 0; e < 4; ++e) {
+                    float x = bi[e] * f[e] * acc[jb][e];
+                    if (ti == tj) x = (r < 4 * g + e) ? x : 0.f;                       // strictly lower
+                    M[(16 * ti + 4 * g + e) * kLd + 16 * tj + r] = x;
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    float x = f[e] * acc[jb][e];
+                    if (ti == tj) x = (r <= 4 * g + e) ? x : 0.f;                      // lower with diagonal
+                    if (clen < 64) x = (16 * ti + 4 * g + e < clen) ? x : 0.f;         // rows beyond a short chunk
+                    Pm[(16 * ti + 4 * g + e) * kLd + 16 * tj + r] = x;
+                }
+            }
+        });
+    });
     // the six strictly-upper tiles are never written: every reader below knows they are zero
     __syncthreads();
 
@@ -230,21 +252,21 @@ __global__ __launch_bounds__(256, 3) void intra_bf16_kernel(IntraArgs<bf16_t> a)
         for (int i = 0; i < 16; ++i)
             if ((i >> 2) == g) M[(16 * wave + i) * kLd + 16 * wave + r] = x[i];
     }
-    // P goes out to the workspace in operand order (fp32 image -> bf16 slots)
+    // P goes out to the workspace in operand order (fp32 image -> bf16 slots).  Stored tile-pair ctp = wave
+    // (+ 4): wave-uniform, so its tile coordinates are scalars; slot = ctp * 64 + lane.
     if (!(a.debug & 16)) {
         char* out = rec + HALF;
 #pragma unroll
         for (int it = 0; it < 2; ++it) {
-            const int sl = tid + 256 * it;           // slot index: stored tile-pair * 64 + lane
-            if (sl < kTriPairs * 64) {
-                const int ctp = sl >> 6, ln = sl & 63;
+            const int ctp = wave + 4 * it;
+            if (ctp < kTriPairs) {
                 const int ti = ctp < 2 ? ctp : 2 + ((ctp - 2) >> 1), jp = ctp < 2 ? 0 : ((ctp - 2) & 1);
-                const int rw = 16 * ti + (ln & 15), cl = 32 * jp + 4 * (ln >> 4);
+                const float* src = Pm + (16 * ti + r) * kLd + 32 * jp + 4 * g;
                 const bool up = ctp == 0 || ctp == 3;         // second block of the pair is an upper tile: zero
-                const u32x2 q0 = to_quad(ldf4(Pm + rw * kLd + cl));
-                const u32x2 q1 = up ? u32x2{0u, 0u} : to_quad(ldf4(Pm + rw * kLd + cl + 16));
+                const u32x2 q0 = to_quad(ldf4(src));
+                const u32x2 q1 = up ? u32x2{0u, 0u} : to_quad(ldf4(src + 16));
                 const u32x4 v = {q0.x, q0.y, q1.x, q1.y};
-                st16(out + (size_t)sl * 16, v);
+                st16(out + (size_t)(ctp * 64 + lane) * 16, v);
             }
         }
     }
@@ -284,16 +306,16 @@ __global__ __launch_bounds__(256, 3) void intra_bf16_kernel(IntraArgs<bf16_t> a)
     if (!(a.debug & 16)) {
 #pragma unroll
         for (int it = 0; it < 2; ++it) {
-            const int sl = tid + 256 * it;
-            if (sl < kTriPairs * 64) {
-                const int ctp = sl >> 6, ln = sl & 63;
+            const int ctp = wave + 4 * it;
+            if (ctp < kTriPairs) {
                 const int ti = ctp < 2 ? ctp : 2 + ((ctp - 2) >> 1), jp = ctp < 2 ? 0 : ((ctp - 2) & 1);
-                const int rw = 16 * ti + (ln & 15), cl = 32 * jp + 4 * (ln >> 4);
+                const int cl = 32 * jp + 4 * g;
+                const float* src = M + (16 * ti + r) * kLd + cl;
                 const bool up = ctp == 0 || ctp == 3;
-                const u32x2 q0 = to_quad(ldf4(M + rw * kLd + cl) * ldf4(beta_s + cl));
-                const u32x2 q1 = up ? u32x2{0u, 0u} : to_quad(ldf4(M + rw * kLd + cl + 16) * ldf4(beta_s + cl + 16));
+                const u32x2 q0 = to_quad(ldf4(src) * ldf4(beta_s + cl));
+                const u32x2 q1 = up ? u32x2{0u, 0u} : to_quad(ldf4(src + 16) * ldf4(beta_s + cl + 16));
                 const u32x4 v = {q0.x, q0.y, q1.x, q1.y};
-                st16(rec + (size_t)sl * 16, v);
+                st16(rec + (size_t)(ctp * 64 + lane) * 16, v);
             }
         }
     }

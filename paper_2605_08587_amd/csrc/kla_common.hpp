@@ -63,4 +63,12 @@ __device__ __forceinline__ float kaczmarz_beta(float eta, float knorm2, float ep
     return den == 0.0f ? 0.0f : eta / den;
 }
 
+// The same with the hardware reciprocal (1 ulp) instead of an IEEE division: for results that are rounded to
+// bf16 right afterwards.
+__device__ __forceinline__ float kaczmarz_beta_fast(float eta, float knorm2, float eps)
+{
+    const float den = knorm2 + eps;
+    return den == 0.0f ? 0.0f : eta * __builtin_amdgcn_rcpf(den);
+}
+
 }  // namespace kla
