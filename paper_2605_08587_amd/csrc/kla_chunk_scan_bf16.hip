@@ -53,7 +53,9 @@ struct Cfg {
     static constexpr int NTB = 2 * TPB / 1024;           // = 12
     static constexpr int OFF_Q = 64 * RB, OFF_T = 2 * 64 * RB, OFF_P = OFF_T + TPB, OFF_V = OFF_T + 2 * TPB,
                          OFF_EG = OFF_V + 64 * VRW, OFF_ED = OFF_EG + 256, STAGE = OFF_ED + 256;
-    static constexpr int ORB = SLW * 2 + 16;             // padded row stride of the output staging tile
+    // row stride of the output staging tile: 24 (NW <= 2) or 40 (NW = 4) dwords, so that the 8-dword spans which
+    // one wave writes into 8 consecutive rows fall into disjoint banks
+    static constexpr int ORB = NW <= 2 ? 96 : 160;
     static constexpr int OSB = 64 * ORB;
     static constexpr int NST = (3 * STAGE + 2 * OSB <= 160 * 1024) ? 3 : 2;   // LDS ring depth
     static constexpr int LDS = NST * STAGE + 2 * OSB;
@@ -128,7 +130,11 @@ __global__ __launch_bounds__(64 * NW + 64) void scan_bf16_kernel(ScanArgs<bf16_t
 #pragma unroll
     for (int par = 0; par < 2; ++par) oKT[par] = (4 * g + a4) * RB + (((4 * par + c4) ^ swz_bits(4 * g + a4)) * 16);
     const int oV = (4 * g + a4) * VRW + (16 * wave + 4 * c4) * 2;      // V tile rows 4 g + a4 (+ 16 it)
-    const int oO = (4 * g) * ORB + (16 * wave + r) * 2;                // staging tile, rows 4 g + e (+ 16 it)
+    // staging tile: after the 4x4 transposition below lane (r, g) holds row 4 g + (r & 3) (+ 16 it), columns
+    // 4 (r >> 2) .. + 3 of this wave's 16
+    const int oO = (4 * g + (r & 3)) * ORB + (16 * wave + 4 * (r >> 2)) * 2;
+    const bool q_lo = (r & 3) < 2;                       // lane sits in the upper half of its quad's 4x4 block
+    const uint32_t psel = (r & 1) ? 0x03020706u : 0x05040100u;   // byte selectors of the 2x2 step (see below)
 
     // ---- global -> LDS copy of everything chunk c needs except the decay factors ---------------------
     auto issue = [&](int c, char* st) {
@@ -285,14 +291,21 @@ __global__ __launch_bounds__(64 * NW + 64) void scan_bf16_kernel(ScanArgs<bf16_t
         }
         mma_bf16(o[2], psl[tri_pair(2, 1)], Uq[2], Uq[3]);
         mma_bf16(o[3], psl[tri_pair(3, 1)], Uq[2], Uq[3]);
+        // A quad of lanes (r = 4 q .. 4 q + 3) holds a 4x4 block of bf16: lane j rows 4 g + e (e = 0..3, packed
+        // in two dwords) of column 4 q + j.  Transposed inside the quad by two exchange steps (dwords with lane
+        // j ^ 2, halves with lane j ^ 1), each lane then owns 4 consecutive columns of one row: one 64-bit LDS
+        // write per tile instead of four 16-bit ones (a compute wave is bound by its LDS instructions).
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
-            const u32x2 ob = to_quad(o[it]);
-            char* po = ost + oO + 16 * it * ORB;
-            *reinterpret_cast<uint16_t*>(po) = (uint16_t)(ob.x & 0xffffu);
-            *reinterpret_cast<uint16_t*>(po + ORB) = (uint16_t)(ob.x >> 16);
-            *reinterpret_cast<uint16_t*>(po + 2 * ORB) = (uint16_t)(ob.y & 0xffffu);
-            *reinterpret_cast<uint16_t*>(po + 3 * ORB) = (uint16_t)(ob.y >> 16);
+            u32x2 ob = to_quad(o[it]);
+            const uint32_t snd = q_lo ? ob.y : ob.x;
+            const uint32_t rcv = (uint32_t)__builtin_amdgcn_mov_dpp((int)snd, 0x4E, 0xf, 0xf, true);   // quad_perm [2,3,0,1]
+            if (q_lo) ob.y = rcv; else ob.x = rcv;
+            const uint32_t px = (uint32_t)__builtin_amdgcn_mov_dpp((int)ob.x, 0xB1, 0xf, 0xf, true);   // quad_perm [1,0,3,2]
+            const uint32_t py = (uint32_t)__builtin_amdgcn_mov_dpp((int)ob.y, 0xB1, 0xf, 0xf, true);
+            ob.x = __builtin_amdgcn_perm(px, ob.x, psel);
+            ob.y = __builtin_amdgcn_perm(py, ob.y, psel);
+            *reinterpret_cast<u32x2*>(ost + oO + 16 * it * ORB) = ob;
         }
     };
 
