@@ -94,7 +94,6 @@ int chunk_fwd_impl(const void* q, const void* k, const void* v, const float* log
     ia.cu_seqlens = n_seq > 0 ? cu_dev : nullptr; ia.chunk_off = chunk_off; ia.n_seq = n_seq;
     ia.T = T; ia.NT = NT; ia.H = H;
     ia.wsT = wsT; ia.wsP = wsP; ia.wsG = wsG;
-    { const char* dbg = getenv("KLA_INTRA_DEBUG"); ia.debug = dbg ? atoi(dbg) : 0; }
     if (intra) {
         bool done = false;
         if constexpr (sizeof(E) == 2) {
@@ -115,7 +114,6 @@ int chunk_fwd_impl(const void* q, const void* k, const void* v, const float* log
     sa.cu_seqlens = ia.cu_seqlens; sa.chunk_off = chunk_off; sa.n_seq = n_seq;
     sa.N = N; sa.T = T; sa.NT = NT; sa.H = H; sa.dv = dv;
     sa.wsT = wsT; sa.wsP = wsP; sa.wsG = wsG;
-    { const char* dbg = getenv("KLA_SCAN_DEBUG"); sa.debug = dbg ? atoi(dbg) : 0; }
     const int waves = scan_waves(pl.n_states * H, dv, sizeof(E) == 2 ? KLA_BF16 : KLA_F32);
     if constexpr (sizeof(E) == 2) {
         const char* impl = getenv("KLA_SCAN_IMPL");   // "generic": the element-type-generic kernel (A/B testing)

@@ -136,7 +136,6 @@ __global__ __launch_bounds__(256, 3) void intra_bf16_kernel(IntraArgs<bf16_t> a)
         wait_vmcnt<0>();
     }
     __syncthreads();
-    if (a.debug & 32) return;
 
     // ---- phase 2a: Gram products K K^T and Q K^T on the lower-triangular tiles; five tiles per wave,
     //      five independent accumulators, shared operand row blocks read one contraction step ahead ----
@@ -186,7 +185,6 @@ __global__ __launch_bounds__(256, 3) void intra_bf16_kernel(IntraArgs<bf16_t> a)
 
     // ---- phase 2b: decay, mask, beta -> L (into M) and P (into Pm) as fp32.  Tile coordinates are compile-time
     //      per wave, so only the diagonal tiles pay for the triangular mask ------------------------------
-    if (!(a.debug & 8))
     static_for<4>([&](auto wc) {
         constexpr int W = wc;
         if (wave != W) return;
@@ -223,7 +221,7 @@ __global__ __launch_bounds__(256, 3) void intra_bf16_kernel(IntraArgs<bf16_t> a)
 
     // ---- phase 3: diagonal 16x16 blocks D = (I + L_bb)^{-1} by forward substitution (wave w: block w,
     //      lane column r, the four 16-lane groups redundantly), rows read one ahead; in place ---------
-    if (!(a.debug & 2)) {
+    {
         const float* Lb = M + (16 * wave) * kLd + 16 * wave;
         float x[16];
         floatx4 row[4], nxt[4] = {};
@@ -254,7 +252,7 @@ __global__ __launch_bounds__(256, 3) void intra_bf16_kernel(IntraArgs<bf16_t> a)
     }
     // P goes out to the workspace in operand order (fp32 image -> bf16 slots).  Stored tile-pair ctp = wave
     // (+ 4): wave-uniform, so its tile coordinates are scalars; slot = ctp * 64 + lane.
-    if (!(a.debug & 16)) {
+    {
         char* out = rec + HALF;
 #pragma unroll
         for (int it = 0; it < 2; ++it) {
@@ -273,7 +271,7 @@ __global__ __launch_bounds__(256, 3) void intra_bf16_kernel(IntraArgs<bf16_t> a)
     __syncthreads();
 
     // ---- phase 4: 32x32 level, in place.  Waves 0,1: block pair (a, b) = (2m, 2m+1): T_ba = -D_b (L_ba D_a)
-    if (wave < 2 && !(a.debug & 4)) {
+    if (wave < 2) {
         const int ra = 32 * wave, rb = ra + 16;
         floatx4 y = {0.f, 0.f, 0.f, 0.f}, z = {0.f, 0.f, 0.f, 0.f};
         mma16f(y, aq(M, rb, ra, r, g), bq(M, ra, ra, r, g));
@@ -284,7 +282,7 @@ __global__ __launch_bounds__(256, 3) void intra_bf16_kernel(IntraArgs<bf16_t> a)
     __syncthreads();
 
     // ---- phase 5: 64x64 level, in place.  T[32:64, 0:32] = -T22 (L21 T11); wave = (row tile ti, col tile tj)
-    if (!(a.debug & 4)) {
+    {
         const int ti = wave >> 1, tj = wave & 1;
         floatx4 y0 = {0.f, 0.f, 0.f, 0.f}, y1 = {0.f, 0.f, 0.f, 0.f}, z = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -303,7 +301,7 @@ __global__ __launch_bounds__(256, 3) void intra_bf16_kernel(IntraArgs<bf16_t> a)
     __syncthreads();
 
     // ---- phase 6: T' = T diag(beta) -> workspace in operand order ------------------------------
-    if (!(a.debug & 16)) {
+    {
 #pragma unroll
         for (int it = 0; it < 2; ++it) {
             const int ctp = wave + 4 * it;

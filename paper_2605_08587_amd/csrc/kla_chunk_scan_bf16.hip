@@ -350,13 +350,13 @@ __global__ __launch_bounds__(64 * NW + 64) void scan_bf16_kernel(ScanArgs<bf16_t
     int scur = 0;                                        // ring position of chunk c
     for (int c = 0; c < nch; ++c) {
         char* ost = (c & 1) ? ost1 : ost0;
-        if (!(a.debug & 2)) compute(lds + scur * C::STAGE, ost);
+        compute(lds + scur * C::STAGE, ost);
         // One barrier per chunk: staged outputs before their write-out; chunk c+1's operands before their
         // use; all reads of this stage before it is refilled next iteration; and the write-out of chunk
         // c-1 (finished by every compute wave before it arrives here) before the staging tile of that
         // parity is written again in chunk c+1.
         __syncthreads();
-        if (!(a.debug & 8)) write_out(c, ost);
+        write_out(c, ost);
         scur = (scur + 1 == NST) ? 0 : scur + 1;
     }
 

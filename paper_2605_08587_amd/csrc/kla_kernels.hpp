@@ -27,7 +27,6 @@ template <typename E> struct IntraArgs {
     const int* cu_seqlens; const int* chunk_off; int n_seq;
     int T, NT, H;
     E* wsT; E* wsP; float* wsG;
-    int debug;
 };
 template <typename E> hipError_t launch_intra(const IntraArgs<E>& a, int dk, int n_chunks, hipStream_t st);
 
@@ -37,7 +36,6 @@ template <typename E> struct ScanArgs {
     const int* cu_seqlens; const int* chunk_off; int n_seq;
     int N, T, NT, H, dv;
     const E* wsT; const E* wsP; const float* wsG;
-    int debug;
 };
 // waves = 1, 2 or 4: each wave of a workgroup carries 16 state columns through the whole sequence
 template <typename E> hipError_t launch_scan(const ScanArgs<E>& a, int dk, int waves, hipStream_t st);
