@@ -143,6 +143,19 @@ def main():
                 kla.kla_decode_step(g["q"][t], g["k"][t], g["v"][t], g["log_alpha"][t], g["eta"][t], dd["eps"],
                                     states[t % ns], out=od)
 
+        def graph_ms(states):
+            """The 256 steps captured once and replayed as one graph launch: no per-step launch cost on the host."""
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                run256(states)
+            torch.cuda.current_stream().wait_stream(side)
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                run256(states)
+            graph.replay()
+            return _events(torch, graph.replay, reps)
+
         S = S0.clone()
         run256([S])
         reps = 5
@@ -153,33 +166,31 @@ def main():
         run256(many)
         ms256_cold = _events(torch, lambda: run256(many), reps)
         bytes256 = DECODE_BYTES_PER_TOKEN_HEAD * B * Hd * steps
-        decode = {"metric": "decode_tokens_per_s", "workload": "config4: B=64,H=8,dk=dv=128,bf16 q/k/v,fp32 state,256 steps",
-                  "value": round(B * steps / (ms256 * 1e-3), 1), "unit": "tokens/s",
-                  "us_per_step": round(ms256 * 1e3 / steps, 3),
-                  "roofline": {"bound": "hbm", "kernel": "decode_kernel",
-                               "achieved": round(bytes256 / (ms256_cold * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBS,
-                               "unit": "GB/s", "frac": round(bytes256 / (ms256_cold * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-                               "traffic": _traffic("decode_kernel_config4"),
-                               "note": "state rotated over 24 sets (805 MB, one per layer of the 0.4B model): never resident in the Infinity Cache",
-                               "us_per_step": round(ms256_cold * 1e3 / steps, 3)},
-                  "same_state_GBps": round(bytes256 / (ms256 * 1e-3) / 1e9, 1)}
-        try:   # the same 256 steps as one graph launch: shows how much of the step time is launch overhead
-            Sg = S0.clone()
-            side = torch.cuda.Stream()
-            side.wait_stream(torch.cuda.current_stream())
-            with torch.cuda.stream(side):
-                run256([Sg])
-            torch.cuda.current_stream().wait_stream(side)
-            graph = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(graph):
-                run256([Sg])
-            graph.replay()
-            ms_graph = _events(torch, graph.replay, reps)
-            decode["graph_us_per_step"] = round(ms_graph * 1e3 / steps, 3)
-            decode["graph_tokens_per_s"] = round(B * steps / (ms_graph * 1e-3), 1)
+        # Back-to-back eager launches are bound by the host's launch path (about 13 us per call through the
+        # Python binding), so the kernel's own rate is taken from graph replays; the eager figures stay beside it.
+        try:
+            ms_graph = graph_ms([S0.clone()])
+            ms_graph_cold = graph_ms(many)
+            graph_error = None
         except Exception as e:  # noqa: BLE001
-            decode["graph_us_per_step"] = None
-            decode["graph_error"] = str(e)[:120]
+            ms_graph, ms_graph_cold, graph_error = ms256, ms256_cold, str(e)[:120]
+        decode = {"metric": "decode_tokens_per_s", "workload": "config4: B=64,H=8,dk=dv=128,bf16 q/k/v,fp32 state,256 steps",
+                  "value": round(B * steps / (ms_graph * 1e-3), 1), "unit": "tokens/s",
+                  "us_per_step": round(ms_graph * 1e3 / steps, 3),
+                  "launch": "one graph of 256 steps, state updated in place",
+                  "eager_tokens_per_s": round(B * steps / (ms256 * 1e-3), 1),
+                  "eager_us_per_step": round(ms256 * 1e3 / steps, 3),
+                  "roofline": {"bound": "hbm", "kernel": "decode_kernel",
+                               "achieved": round(bytes256 / (ms_graph_cold * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBS,
+                               "unit": "GB/s", "frac": round(bytes256 / (ms_graph_cold * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                               "traffic": _traffic("decode_kernel_config4"),
+                               "note": "one graph of 256 steps rotating over 24 state sets (805 MB, one per layer of the "
+                                       "0.4B model): a set is never resident in the Infinity Cache when its turn comes",
+                               "us_per_step": round(ms_graph_cold * 1e3 / steps, 3),
+                               "eager_us_per_step": round(ms256_cold * 1e3 / steps, 3)},
+                  "same_state_GBps": round(bytes256 / (ms_graph * 1e-3) / 1e9, 1)}
+        if graph_error:
+            decode["graph_error"] = graph_error
 
     # ------------------------------------------------------------------ CPU oracle beside it
     cpu = None
