@@ -22,6 +22,14 @@
  * widens to float, and float to double, without rounding).  Plain loops, naive
  * summation order, no blocking.
  *
+ * Two options, both off in the plain entry points (the *_opts entry points take
+ * them):
+ *   - normalize_q: the readout of Sec. 3.3 / Algorithm 1 (left) as printed,
+ *     o_t = S_t^T q_t / ||q_t||; a zero query gives o_t = 0 (S^T 0 = 0);
+ *   - gdn_beta: beta_t = eta_t, the gated delta rule the paper starts from
+ *     (Table 2; the "w/o normalization" row of the ablation), i.e. eq. (3)
+ *     without the key-norm denominator.
+ *
  * Pins: see tests/test_oracle_pins.py (Theorem 1 projection property,
  * Proposition 2 contraction factor, Proposition 1 stationarity, eq. (4) line
  * search, pure decay at eta = 0, brute-force product form of Table 5, textbook
@@ -36,7 +44,7 @@
  * d_v outputs; e is caller-provided scratch of d_v doubles. */
 static void kla_token(double *S, const float *q, const float *k, const float *v,
                       double log_alpha, double eta, double eps, int dk, int dv,
-                      double *o, double *e)
+                      double *o, double *e, int normalize_q, int gdn_beta)
 {
     int i, j;
     /* line 1: S~ = alpha S */
@@ -56,7 +64,9 @@ static void kla_token(double *S, const float *q, const float *k, const float *v,
     for (i = 0; i < dk; ++i)
         nk += (double)k[i] * (double)k[i];
     const double den = nk + eps;
-    const double beta = (den == 0.0) ? 0.0 : eta / den;
+    double beta = (den == 0.0) ? 0.0 : eta / den;
+    if (gdn_beta)                 /* the delta rule without the Kaczmarz denominator */
+        beta = eta;
     /* line 4: S = S~ + beta k e^T */
     for (i = 0; i < dk; ++i)
         for (j = 0; j < dv; ++j)
@@ -67,6 +77,14 @@ static void kla_token(double *S, const float *q, const float *k, const float *v,
         for (i = 0; i < dk; ++i)
             r += S[(size_t)i * dv + j] * (double)q[i];
         o[j] = r;
+    }
+    if (normalize_q) {            /* line 5 as printed: o = S^T q / ||q|| */
+        double nq = 0.0;
+        for (i = 0; i < dk; ++i)
+            nq += (double)q[i] * (double)q[i];
+        nq = sqrt(nq);
+        for (j = 0; j < dv; ++j)
+            o[j] = (nq == 0.0) ? 0.0 : o[j] / nq;
     }
 }
 
@@ -82,10 +100,11 @@ static void kla_token(double *S, const float *q, const float *k, const float *v,
  *   h         head index
  * Returns 0, or -1 if scratch could not be allocated.
  */
-int kla_oracle_sequence(const float *q, const float *k, const float *v,
-                        const double *log_alpha, const double *eta, double eps,
-                        const double *h0, double *o, double *hT,
-                        long t0, long len, int h, int H, int dk, int dv)
+int kla_oracle_sequence_opts(const float *q, const float *k, const float *v,
+                             const double *log_alpha, const double *eta, double eps,
+                             const double *h0, double *o, double *hT,
+                             long t0, long len, int h, int H, int dk, int dv,
+                             int normalize_q, int gdn_beta)
 {
     double *S = (double *)malloc(sizeof(double) * (size_t)dk * dv);
     double *e = (double *)malloc(sizeof(double) * (size_t)dv);
@@ -95,11 +114,19 @@ int kla_oracle_sequence(const float *q, const float *k, const float *v,
     for (long t = t0; t < t0 + len; ++t) {
         const size_t th = (size_t)t * H + h;
         kla_token(S, q + th * dk, k + th * dk, v + th * dv,
-                  log_alpha[th], eta[th], eps, dk, dv, o + th * dv, e);
+                  log_alpha[th], eta[th], eps, dk, dv, o + th * dv, e, normalize_q, gdn_beta);
     }
     if (hT) memcpy(hT, S, sizeof(double) * (size_t)dk * dv);
     free(S); free(e);
     return 0;
+}
+
+int kla_oracle_sequence(const float *q, const float *k, const float *v,
+                        const double *log_alpha, const double *eta, double eps,
+                        const double *h0, double *o, double *hT,
+                        long t0, long len, int h, int H, int dk, int dv)
+{
+    return kla_oracle_sequence_opts(q, k, v, log_alpha, eta, eps, h0, o, hT, t0, len, h, H, dk, dv, 0, 0);
 }
 
 /*
@@ -107,13 +134,21 @@ int kla_oracle_sequence(const float *q, const float *k, const float *v,
  * loop body starting from the given state.  S [dk, dv] double is updated in
  * place, o [dv] double is written.  Returns 0 or -1.
  */
+int kla_oracle_decode_unit_opts(const float *q, const float *k, const float *v,
+                                double log_alpha, double eta, double eps,
+                                double *S, double *o, int dk, int dv,
+                                int normalize_q, int gdn_beta)
+{
+    double *e = (double *)malloc(sizeof(double) * (size_t)dv);
+    if (!e) return -1;
+    kla_token(S, q, k, v, log_alpha, eta, eps, dk, dv, o, e, normalize_q, gdn_beta);
+    free(e);
+    return 0;
+}
+
 int kla_oracle_decode_unit(const float *q, const float *k, const float *v,
                            double log_alpha, double eta, double eps,
                            double *S, double *o, int dk, int dv)
 {
-    double *e = (double *)malloc(sizeof(double) * (size_t)dv);
-    if (!e) return -1;
-    kla_token(S, q, k, v, log_alpha, eta, eps, dk, dv, o, e);
-    free(e);
-    return 0;
+    return kla_oracle_decode_unit_opts(q, k, v, log_alpha, eta, eps, S, o, dk, dv, 0, 0);
 }

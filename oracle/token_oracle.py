@@ -46,9 +46,13 @@ def _load():
             lib.kla_oracle_sequence.argtypes = [fp, fp, fp, dp, dp, ctypes.c_double, dp, dp, dp,
                                                 ctypes.c_long, ctypes.c_long, ctypes.c_int,
                                                 ctypes.c_int, ctypes.c_int, ctypes.c_int]
+            lib.kla_oracle_sequence_opts.restype = ctypes.c_int
+            lib.kla_oracle_sequence_opts.argtypes = lib.kla_oracle_sequence.argtypes + [ctypes.c_int, ctypes.c_int]
             lib.kla_oracle_decode_unit.restype = ctypes.c_int
             lib.kla_oracle_decode_unit.argtypes = [fp, fp, fp, ctypes.c_double, ctypes.c_double,
                                                    ctypes.c_double, dp, dp, ctypes.c_int, ctypes.c_int]
+            lib.kla_oracle_decode_unit_opts.restype = ctypes.c_int
+            lib.kla_oracle_decode_unit_opts.argtypes = lib.kla_oracle_decode_unit.argtypes + [ctypes.c_int, ctypes.c_int]
             _lib = lib
     return _lib
 
@@ -73,7 +77,8 @@ def default_threads() -> int:
     return len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
 
 
-def kla_recurrent(q, k, v, log_alpha, eta, eps, h0=None, cu_seqlens=None, threads=None, units=None):
+def kla_recurrent(q, k, v, log_alpha, eta, eps, h0=None, cu_seqlens=None, threads=None, units=None,
+                  normalize_q=False, gdn_beta=False):
     """Whole-batch recurrence.
 
     q, k: [N, T, H, dk]; v: [N, T, H, dv]; log_alpha, eta: [N, T, H];
@@ -81,6 +86,7 @@ def kla_recurrent(q, k, v, log_alpha, eta, eps, h0=None, cu_seqlens=None, thread
     token axis) N must be 1 and the sequences are packed along T.
     `units`, if given, restricts the work to those (sequence, head) pairs; the
     other rows of the outputs stay zero.
+    normalize_q: readout divided by ||q_t|| (Sec. 3.3); gdn_beta: beta_t = eta_t (no key-norm denominator).
     Returns (o [N, T, H, dv] float64, hT [n_seq, H, dk, dv] float64, threads_used).
     """
     lib = _load()
@@ -105,9 +111,9 @@ def kla_recurrent(q, k, v, log_alpha, eta, eps, h0=None, cu_seqlens=None, thread
     def run(unit):
         s, h = unit
         off = (s * H + h) * dk * dv
-        rc = lib.kla_oracle_sequence(_fp(q), _fp(k), _fp(v), _dp(la), _dp(et), float(eps),
-                                     None if h0d is None else _dp(h0d, off), _dp(o), _dp(hT, off),
-                                     starts[s], lens[s], h, H, dk, dv)
+        rc = lib.kla_oracle_sequence_opts(_fp(q), _fp(k), _fp(v), _dp(la), _dp(et), float(eps),
+                                          None if h0d is None else _dp(h0d, off), _dp(o), _dp(hT, off),
+                                          starts[s], lens[s], h, H, dk, dv, int(normalize_q), int(gdn_beta))
         if rc != 0:
             raise MemoryError("oracle scratch allocation failed")
 
@@ -121,7 +127,7 @@ def kla_recurrent(q, k, v, log_alpha, eta, eps, h0=None, cu_seqlens=None, thread
     return o, hT, nthr
 
 
-def kla_decode(q, k, v, log_alpha, eta, eps, S, threads=None):
+def kla_decode(q, k, v, log_alpha, eta, eps, S, threads=None, normalize_q=False, gdn_beta=False):
     """One decode step for every (batch, head).
 
     q, k: [B, H, dk]; v: [B, H, dv]; log_alpha, eta: [B, H]; S: [B, H, dk, dv].
@@ -136,12 +142,12 @@ def kla_decode(q, k, v, log_alpha, eta, eps, S, threads=None):
     o = np.zeros((B, H, dv), dtype=np.float64)
 
     def run(u):
-        rc = lib.kla_oracle_decode_unit(
+        rc = lib.kla_oracle_decode_unit_opts(
             ctypes.cast(q.ctypes.data + 4 * u * dk, ctypes.POINTER(ctypes.c_float)),
             ctypes.cast(k.ctypes.data + 4 * u * dk, ctypes.POINTER(ctypes.c_float)),
             ctypes.cast(v.ctypes.data + 4 * u * dv, ctypes.POINTER(ctypes.c_float)),
             float(la.reshape(-1)[u]), float(et.reshape(-1)[u]), float(eps),
-            _dp(S, u * dk * dv), _dp(o, u * dv), dk, dv)
+            _dp(S, u * dk * dv), _dp(o, u * dv), dk, dv, int(normalize_q), int(gdn_beta))
         if rc != 0:
             raise MemoryError("oracle scratch allocation failed")
 

@@ -307,3 +307,55 @@ def test_split_invariance():
     o2, h2, _ = token_oracle.kla_recurrent(q[:, a:], k[:, a:], v[:, a:], la[:, a:], eta[:, a:], 1e-6, h0=h1)
     np.testing.assert_array_equal(np.concatenate([o1, o2], axis=1), o)
     np.testing.assert_array_equal(h2, hT)
+
+
+def test_option_gdn_beta_product_form():
+    """Option gdn_beta (beta_t = eta_t, Table 2's gated delta rule) against the product form
+    S_t = (I - eta k k^T) alpha S_{t-1} + eta k v^T for keys of ANY norm, and against the default
+    coefficient after the substitution eta -> eta (|k|^2 + eps) that makes the two rules coincide."""
+    rng = RNG(21)
+    T, dk, dv = 25, 6, 5
+    q, k, v, la, eta, S0 = _rand_problem(rng, T, 1, dk, dv)
+    k *= 0.3                                                  # keep I - eta k k^T a contraction
+    eps = 1e-3
+    o, hT, _ = token_oracle.kla_recurrent(q, k, v, la, eta, eps, h0=S0, gdn_beta=True)
+    S = S0[0, 0].copy()
+    for t in range(T):
+        kk = k[0, t, 0].astype(np.float64)
+        S = (np.eye(dk) - eta[0, t, 0] * np.outer(kk, kk)) @ (np.exp(la[0, t, 0]) * S) \
+            + eta[0, t, 0] * np.outer(kk, v[0, t, 0])
+        np.testing.assert_allclose(o[0, t, 0], S.T @ q[0, t, 0], rtol=0, atol=1e-12 * (1 + np.max(np.abs(S))))
+    np.testing.assert_allclose(hT[0, 0], S, rtol=0, atol=1e-12 * (1 + np.max(np.abs(S))))
+    nk = np.sum(k.astype(np.float64) ** 2, axis=-1)
+    o2, hT2, _ = token_oracle.kla_recurrent(q, k, v, la, eta * (nk + eps), eps, h0=S0)
+    np.testing.assert_allclose(o2, o, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(hT2, hT, rtol=1e-12, atol=1e-13)
+    # and it is not the default rule
+    o3, _, _ = token_oracle.kla_recurrent(q, k, v, la, eta, eps, h0=S0)
+    assert np.max(np.abs(o3 - o)) > 1e-3
+
+
+def test_option_normalize_q():
+    """Option normalize_q (Sec. 3.3: o_t = S_t^T q_t / |q_t|): equals the plain readout divided by numpy's
+    norm, does not depend on the scale of q, leaves the states alone, and gives 0 for a zero query."""
+    rng = RNG(22)
+    T, H, dk, dv = 12, 2, 5, 4
+    q, k, v, la, eta, S0 = _rand_problem(rng, T, H, dk, dv)
+    q[0, 3, 1] = 0.0
+    eps = 1e-6
+    o, hT, _ = token_oracle.kla_recurrent(q, k, v, la, eta, eps, h0=S0)
+    on, hTn, _ = token_oracle.kla_recurrent(q, k, v, la, eta, eps, h0=S0, normalize_q=True)
+    nq = np.linalg.norm(q.astype(np.float64), axis=-1, keepdims=True)
+    want = np.divide(o, nq, out=np.zeros_like(o), where=nq > 0)
+    np.testing.assert_allclose(on, want, rtol=1e-13, atol=0)
+    assert np.all(on[0, 3, 1] == 0.0)
+    np.testing.assert_array_equal(hTn, hT)
+    scale = np.exp2(rng.integers(-3, 4, size=(1, T, H, 1))).astype(np.float32)   # exact in fp32
+    os_, _, _ = token_oracle.kla_recurrent(q * scale, k, v, la, eta, eps, h0=S0, normalize_q=True)
+    np.testing.assert_allclose(os_, on, rtol=1e-13, atol=0)
+    # decode entry point takes the same options
+    od, Sd = token_oracle.kla_decode(q[:, 0], k[:, 0], v[:, 0], la[:, 0], eta[:, 0], eps, S0, normalize_q=True, gdn_beta=True)
+    og, hg, _ = token_oracle.kla_recurrent(q[:, :1], k[:, :1], v[:, :1], la[:, :1], eta[:, :1], eps, h0=S0,
+                                           normalize_q=True, gdn_beta=True)
+    np.testing.assert_allclose(od, og[:, 0], rtol=1e-14, atol=0)
+    np.testing.assert_allclose(Sd, hg, rtol=1e-14, atol=0)
