@@ -107,6 +107,31 @@ int kla_decode_step(const void *q, const void *k, const void *v,
                     int B, int H, int dk, int dv, kla_dtype dt, void *hip_stream);
 
 /*
+ * Options of the *_opts entry points (bit flags; any other bit is KLA_ERR_SHAPE).
+ *   KLA_OPT_NORMALIZE_Q  the read-out of Sec. 3.3 / Algorithm 1 (left) as printed,
+ *                        o_t = S_t^T q_t / ||q_t||, with o_t = 0 for a zero query; the norm is
+ *                        taken over the stored q in fp32.  States are not affected.
+ *   KLA_OPT_GDN_BETA     beta_t = eta_t: the gated delta rule the paper starts from (Table 2; the
+ *                        "w/o normalization" row of its ablation) instead of eq. (3); eps is
+ *                        then unused.
+ */
+enum { KLA_OPT_NORMALIZE_Q = 1, KLA_OPT_GDN_BETA = 2 };
+
+/* kla_chunk_fwd with options; kla_chunk_fwd(...) is kla_chunk_fwd_opts(..., 0).  Same workspace. */
+int kla_chunk_fwd_opts(const void *q, const void *k, const void *v,
+                       const float *log_alpha, const float *eta, float eps,
+                       const float *h0, void *o, float *hT,
+                       const int32_t *cu_seqlens_dev, const int32_t *cu_seqlens_host, int n_seq,
+                       int N, int T, int H, int dk, int dv, int chunk, kla_dtype dt,
+                       void *workspace, size_t workspace_bytes, void *hip_stream, unsigned opts);
+
+/* kla_decode_step with options; kla_decode_step(...) is kla_decode_step_opts(..., 0). */
+int kla_decode_step_opts(const void *q, const void *k, const void *v,
+                         const float *log_alpha, const float *eta, float eps,
+                         float *S, void *o,
+                         int B, int H, int dk, int dv, kla_dtype dt, void *hip_stream, unsigned opts);
+
+/*
  * The Kaczmarz coefficient alone (eq. (3)): beta[i] = eta[i] / (||k_i||^2 + eps), 0 when the
  * denominator is 0, for n_token_heads rows of dk elements.
  *   k [n_token_heads, dk] dt in;  eta [n_token_heads] fp32 in;  beta [n_token_heads] fp32 out.

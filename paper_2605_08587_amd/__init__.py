@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libkla.so")
 HEADER_PATH = os.path.join(os.path.dirname(_HERE), "include", "kla.h")
 
 KLA_F32, KLA_BF16 = 0, 1
+KLA_OPT_NORMALIZE_Q, KLA_OPT_GDN_BETA = 1, 2
 _lock = threading.Lock()
 _lib = None
 
@@ -26,10 +27,14 @@ _SIGNATURES = {
     "kla_chunk_fwd_workspace_bytes": (ctypes.c_size_t, [ctypes.c_int] * 6 + [ctypes.c_int, _ip, ctypes.c_int]),
     "kla_chunk_fwd": (ctypes.c_int, [_vp, _vp, _vp, _fp, _fp, ctypes.c_float, _fp, _vp, _fp, _ip, _ip, ctypes.c_int]
                       + [ctypes.c_int] * 6 + [ctypes.c_int, _vp, ctypes.c_size_t, _vp]),
+    "kla_chunk_fwd_opts": (ctypes.c_int, [_vp, _vp, _vp, _fp, _fp, ctypes.c_float, _fp, _vp, _fp, _ip, _ip, ctypes.c_int]
+                           + [ctypes.c_int] * 6 + [ctypes.c_int, _vp, ctypes.c_size_t, _vp, ctypes.c_uint]),
     "kla_debug_chunk_stage": (ctypes.c_int, [_vp, _vp, _vp, _fp, _fp, ctypes.c_float, _fp, _vp, _fp, _ip, _ip, ctypes.c_int]
                               + [ctypes.c_int] * 6 + [ctypes.c_int, _vp, ctypes.c_size_t, _vp, ctypes.c_int]),
     "kla_decode_step": (ctypes.c_int, [_vp, _vp, _vp, _fp, _fp, ctypes.c_float, _fp, _vp]
                         + [ctypes.c_int] * 4 + [ctypes.c_int, _vp]),
+    "kla_decode_step_opts": (ctypes.c_int, [_vp, _vp, _vp, _fp, _fp, ctypes.c_float, _fp, _vp]
+                             + [ctypes.c_int] * 4 + [ctypes.c_int, _vp, ctypes.c_uint]),
     "kla_beta": (ctypes.c_int, [_vp, _fp, ctypes.c_float, _fp, ctypes.c_long, ctypes.c_int, ctypes.c_int, _vp]),
     "kla_debug_intra_chunk": (ctypes.c_int, [_vp, _vp, _fp, _fp, ctypes.c_float, _fp, _fp, _fp, _ip, _ip, ctypes.c_int]
                               + [ctypes.c_int] * 5 + [ctypes.c_int, _vp, ctypes.c_size_t, _vp]),
@@ -96,12 +101,17 @@ def kla_chunk_fwd_workspace_bytes(N, T, H, dk, dv, dtype, cu_seqlens=None, chunk
     return int(lib().kla_chunk_fwd_workspace_bytes(N, T, H, dk, dv, chunk, dt, cu_hp, n_seq))
 
 
+def _opts(normalize_q, gdn_beta) -> int:
+    return (KLA_OPT_NORMALIZE_Q if normalize_q else 0) | (KLA_OPT_GDN_BETA if gdn_beta else 0)
+
+
 def kla_chunk_fwd(q, k, v, log_alpha, eta, eps, h0=None, cu_seqlens=None, want_hT=True, workspace=None,
-                  out=None, hT=None, chunk=64, _stage=None):
+                  out=None, hT=None, chunk=64, _stage=None, normalize_q=False, gdn_beta=False):
     """Chunkwise forward.  q,k [N,T,H,dk], v [N,T,H,dv], gates [N,T,H] fp32; returns (o, hT).
 
     cu_seqlens: int32 device tensor [n_seq+1] for a packed batch (then N == 1).
     workspace / out / hT may be passed in to avoid allocations (e.g. inside a timed loop).
+    normalize_q: o_t = S_t^T q_t / ||q_t||;  gdn_beta: beta_t = eta_t (kla_chunk_fwd_opts of the C ABI).
     """
     _dev(q, k, v, log_alpha, eta, h0, cu_seqlens, workspace, out, hT)
     N, T, H, dk = q.shape
@@ -119,7 +129,15 @@ def kla_chunk_fwd(q, k, v, log_alpha, eta, eps, h0=None, cu_seqlens=None, want_h
     args = (_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(eta), float(eps), _ptr(h0), _ptr(out),
             _ptr(hT), _ptr(cu_seqlens), cu_hp, n_seq, N, T, H, dk, dv, chunk, dt,
             _ptr(workspace), workspace.numel() * workspace.element_size(), _stream())
-    rc = lib().kla_chunk_fwd(*args) if _stage is None else lib().kla_debug_chunk_stage(*args, int(_stage))
+    opts = _opts(normalize_q, gdn_beta)
+    if _stage is not None:
+        if opts:
+            raise ValueError("the single-stage hook takes no options")
+        rc = lib().kla_debug_chunk_stage(*args, int(_stage))
+    elif opts:
+        rc = lib().kla_chunk_fwd_opts(*args, opts)
+    else:
+        rc = lib().kla_chunk_fwd(*args)
     if rc != 0:
         raise KlaError(rc, "kla_chunk_fwd")
     return out, hT
@@ -131,15 +149,17 @@ def kla_debug_chunk_stage(stage, q, k, v, log_alpha, eta, eps, workspace, out, h
                          workspace=workspace, out=out, hT=hT, _stage=stage)
 
 
-def kla_decode_step(q, k, v, log_alpha, eta, eps, S, out=None):
-    """One decode step; S [B,H,dk,dv] fp32 is updated in place; returns o [B,H,dv]."""
+def kla_decode_step(q, k, v, log_alpha, eta, eps, S, out=None, normalize_q=False, gdn_beta=False):
+    """One decode step; S [B,H,dk,dv] fp32 is updated in place; returns o [B,H,dv].  Options as in kla_chunk_fwd."""
     _dev(q, k, v, log_alpha, eta, S, out)
     B, H, dk = q.shape
     dv = v.shape[-1]
     if out is None:
         out = torch.empty((B, H, dv), dtype=q.dtype, device=q.device)
-    rc = lib().kla_decode_step(_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(eta), float(eps), _ptr(S), _ptr(out),
-                               B, H, dk, dv, _dt(q), _stream())
+    args = (_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(eta), float(eps), _ptr(S), _ptr(out),
+            B, H, dk, dv, _dt(q), _stream())
+    opts = _opts(normalize_q, gdn_beta)
+    rc = lib().kla_decode_step_opts(*args, opts) if opts else lib().kla_decode_step(*args)
     if rc != 0:
         raise KlaError(rc, "kla_decode_step")
     return out

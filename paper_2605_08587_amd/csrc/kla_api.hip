@@ -17,6 +17,8 @@ inline bool dv_ok(int dv) { return dv == 64 || dv == 128 || dv == 256; }
 inline bool dt_ok(int dt) { return dt == KLA_F32 || dt == KLA_BF16; }
 inline size_t elem_bytes(int dt) { return dt == KLA_BF16 ? 2 : 4; }
 
+static_assert(KLA_OPT_NORMALIZE_Q == (int)kla::kOptNormalizeQ && KLA_OPT_GDN_BETA == (int)kla::kOptGdnBeta, "option bits");
+
 struct Plan {
     long n_chunks;       // over all sequences
     int n_states;        // sequences
@@ -50,8 +52,8 @@ int make_plan(int N, int T, int H, int dk, int dv, int chunk, int dt, const int3
     const size_t half = (size_t)384 * 8 * elem_bytes(dt);
     p->off_T = 0;
     p->off_P = half;
-    p->off_G = round256((size_t)n_chunks * H * (2 * half + 512));   // + gamma_i, gamma_C/gamma_i (64 fp32 each)
-    p->off_C = round256(p->off_G + (size_t)n_chunks * H * 64 * sizeof(float));
+    p->off_G = round256((size_t)n_chunks * H * (2 * half + 768));   // + three vectors of 64 fp32 (see kla_mma.hpp)
+    p->off_C = round256(p->off_G + (size_t)n_chunks * H * 128 * sizeof(float));      // g and 1/||q||
     p->total = round256(p->off_C + (size_t)(n_seq + 1) * sizeof(int32_t));
     return KLA_OK;
 }
@@ -78,7 +80,7 @@ template <typename E>
 int chunk_fwd_impl(const void* q, const void* k, const void* v, const float* log_alpha, const float* eta, float eps,
                    const float* h0, void* o, float* hT, const int32_t* cu_dev, int n_seq, int N, int T, int H, int dk,
                    int dv, const Plan& pl, char* ws, int stages, float* Tb_out, float* P_out, float* g_out,
-                   hipStream_t st)
+                   hipStream_t st, unsigned opts)
 {
     E* wsT = reinterpret_cast<E*>(ws + pl.off_T);
     E* wsP = reinterpret_cast<E*>(ws + pl.off_P);
@@ -93,7 +95,7 @@ int chunk_fwd_impl(const void* q, const void* k, const void* v, const float* log
     ia.log_alpha = log_alpha; ia.eta = eta; ia.eps = eps;
     ia.cu_seqlens = n_seq > 0 ? cu_dev : nullptr; ia.chunk_off = chunk_off; ia.n_seq = n_seq;
     ia.T = T; ia.NT = NT; ia.H = H;
-    ia.wsT = wsT; ia.wsP = wsP; ia.wsG = wsG;
+    ia.wsT = wsT; ia.wsP = wsP; ia.wsG = wsG; ia.opts = opts;
     if (intra) {
         bool done = false;
         if constexpr (sizeof(E) == 2) {
@@ -113,7 +115,7 @@ int chunk_fwd_impl(const void* q, const void* k, const void* v, const float* log
     sa.h0 = h0; sa.o = static_cast<E*>(o); sa.hT = hT;
     sa.cu_seqlens = ia.cu_seqlens; sa.chunk_off = chunk_off; sa.n_seq = n_seq;
     sa.N = N; sa.T = T; sa.NT = NT; sa.H = H; sa.dv = dv;
-    sa.wsT = wsT; sa.wsP = wsP; sa.wsG = wsG;
+    sa.wsT = wsT; sa.wsP = wsP; sa.wsG = wsG; sa.opts = opts;
     const int waves = scan_waves(pl.n_states * H, dv, sizeof(E) == 2 ? KLA_BF16 : KLA_F32);
     if constexpr (sizeof(E) == 2) {
         const char* impl = getenv("KLA_SCAN_IMPL");   // "generic": the element-type-generic kernel (A/B testing)
@@ -154,12 +156,14 @@ size_t kla_chunk_fwd_workspace_bytes(int N, int T, int H, int dk, int dv, int ch
 static int chunk_fwd_checked(const void* q, const void* k, const void* v, const float* log_alpha, const float* eta,
                              float eps, const float* h0, void* o, float* hT, const int32_t* cu_seqlens_dev,
                              const int32_t* cu_seqlens_host, int n_seq, int N, int T, int H, int dk, int dv, int chunk,
-                             kla_dtype dt, void* workspace, size_t workspace_bytes, void* hip_stream, int stages)
+                             kla_dtype dt, void* workspace, size_t workspace_bytes, void* hip_stream, int stages,
+                             unsigned opts)
 {
     Plan pl;
     const int rc = make_plan(N, T, H, dk, dv, chunk, (int)dt, cu_seqlens_host, n_seq, &pl);
     if (rc != KLA_OK) return rc;
     if (!(eps >= 0.0f) || isinf(eps)) return KLA_ERR_SHAPE;
+    if (opts & ~(unsigned)(KLA_OPT_NORMALIZE_Q | KLA_OPT_GDN_BETA)) return KLA_ERR_SHAPE;
     if (n_seq > 0 && !cu_seqlens_dev) return KLA_ERR_NULL;
     if (n_seq == 0 && cu_seqlens_dev) return KLA_ERR_SHAPE;
     const bool any_tokens = (long)N * T > 0;
@@ -174,9 +178,9 @@ static int chunk_fwd_checked(const void* q, const void* k, const void* v, const 
     char* ws = static_cast<char*>(workspace);
     if (dt == KLA_BF16)
         return chunk_fwd_impl<bf16_t>(q, k, v, log_alpha, eta, eps, h0, o, hT, cu_seqlens_dev, n_seq, N, T, H, dk, dv,
-                                      pl, ws, stages, nullptr, nullptr, nullptr, st);
+                                      pl, ws, stages, nullptr, nullptr, nullptr, st, opts);
     return chunk_fwd_impl<float>(q, k, v, log_alpha, eta, eps, h0, o, hT, cu_seqlens_dev, n_seq, N, T, H, dk, dv, pl, ws,
-                                 stages, nullptr, nullptr, nullptr, st);
+                                 stages, nullptr, nullptr, nullptr, st, opts);
 }
 
 int kla_chunk_fwd(const void* q, const void* k, const void* v, const float* log_alpha, const float* eta, float eps,
@@ -185,7 +189,16 @@ int kla_chunk_fwd(const void* q, const void* k, const void* v, const float* log_
                   size_t workspace_bytes, void* hip_stream)
 {
     return chunk_fwd_checked(q, k, v, log_alpha, eta, eps, h0, o, hT, cu_seqlens_dev, cu_seqlens_host, n_seq, N, T, H,
-                             dk, dv, chunk, dt, workspace, workspace_bytes, hip_stream, 3);
+                             dk, dv, chunk, dt, workspace, workspace_bytes, hip_stream, 3, 0u);
+}
+
+int kla_chunk_fwd_opts(const void* q, const void* k, const void* v, const float* log_alpha, const float* eta, float eps,
+                       const float* h0, void* o, float* hT, const int32_t* cu_seqlens_dev,
+                       const int32_t* cu_seqlens_host, int n_seq, int N, int T, int H, int dk, int dv, int chunk,
+                       kla_dtype dt, void* workspace, size_t workspace_bytes, void* hip_stream, unsigned opts)
+{
+    return chunk_fwd_checked(q, k, v, log_alpha, eta, eps, h0, o, hT, cu_seqlens_dev, cu_seqlens_host, n_seq, N, T, H,
+                             dk, dv, chunk, dt, workspace, workspace_bytes, hip_stream, 3, opts);
 }
 
 int kla_debug_chunk_stage(const void* q, const void* k, const void* v, const float* log_alpha, const float* eta,
@@ -195,7 +208,7 @@ int kla_debug_chunk_stage(const void* q, const void* k, const void* v, const flo
 {
     if (stage != 1 && stage != 2) return KLA_ERR_SHAPE;
     return chunk_fwd_checked(q, k, v, log_alpha, eta, eps, h0, o, hT, cu_seqlens_dev, cu_seqlens_host, n_seq, N, T, H,
-                             dk, dv, chunk, dt, workspace, workspace_bytes, hip_stream, stage);
+                             dk, dv, chunk, dt, workspace, workspace_bytes, hip_stream, stage, 0u);
 }
 
 int kla_debug_intra_chunk(const void* q, const void* k, const float* log_alpha, const float* eta, float eps,
@@ -218,15 +231,23 @@ int kla_debug_intra_chunk(const void* q, const void* k, const float* log_alpha, 
     char* ws = static_cast<char*>(workspace);
     if (dt == KLA_BF16)
         return chunk_fwd_impl<bf16_t>(q, k, nullptr, log_alpha, eta, eps, nullptr, nullptr, nullptr, cu_seqlens_dev,
-                                      n_seq, N, T, H, dk, 64, pl, ws, 5, Tb_out, P_out, g_out, st);
+                                      n_seq, N, T, H, dk, 64, pl, ws, 5, Tb_out, P_out, g_out, st, 0u);
     return chunk_fwd_impl<float>(q, k, nullptr, log_alpha, eta, eps, nullptr, nullptr, nullptr, cu_seqlens_dev, n_seq, N,
-                                 T, H, dk, 64, pl, ws, 5, Tb_out, P_out, g_out, st);
+                                 T, H, dk, 64, pl, ws, 5, Tb_out, P_out, g_out, st, 0u);
 }
 
 int kla_decode_step(const void* q, const void* k, const void* v, const float* log_alpha, const float* eta, float eps,
                     float* S, void* o, int B, int H, int dk, int dv, kla_dtype dt, void* hip_stream)
 {
+    return kla_decode_step_opts(q, k, v, log_alpha, eta, eps, S, o, B, H, dk, dv, dt, hip_stream, 0u);
+}
+
+int kla_decode_step_opts(const void* q, const void* k, const void* v, const float* log_alpha, const float* eta,
+                         float eps, float* S, void* o, int B, int H, int dk, int dv, kla_dtype dt, void* hip_stream,
+                         unsigned opts)
+{
     if (!dt_ok((int)dt)) return KLA_ERR_DTYPE;
+    if (opts & ~(unsigned)(KLA_OPT_NORMALIZE_Q | KLA_OPT_GDN_BETA)) return KLA_ERR_SHAPE;
     if (B < 0 || H <= 0 || !dk_ok(dk) || !dv_ok(dv) || (long)B * H > 0x7fffffffL) return KLA_ERR_SHAPE;
     if (!(eps >= 0.0f) || isinf(eps)) return KLA_ERR_SHAPE;
     if (B == 0) return KLA_OK;
@@ -243,11 +264,11 @@ int kla_decode_step(const void* q, const void* k, const void* v, const float* lo
     if (dt == KLA_BF16)
         e = kla::launch_decode<bf16_t>(static_cast<const bf16_t*>(q), static_cast<const bf16_t*>(k),
                                        static_cast<const bf16_t*>(v), log_alpha, eta, eps, S, static_cast<bf16_t*>(o),
-                                       B * H, dk, dv, slice, st);
+                                       B * H, dk, dv, slice, opts, st);
     else
         e = kla::launch_decode<float>(static_cast<const float*>(q), static_cast<const float*>(k),
                                       static_cast<const float*>(v), log_alpha, eta, eps, S, static_cast<float*>(o),
-                                      B * H, dk, dv, slice, st);
+                                      B * H, dk, dv, slice, opts, st);
     return e == hipSuccess ? KLA_OK : KLA_ERR_HIP;
 }
 

@@ -57,6 +57,7 @@ __global__ __launch_bounds__(256) void intra_kernel(IntraArgs<E> a)
     __shared__ __attribute__((aligned(16))) float Lm[64 * kLdm];
     __shared__ __attribute__((aligned(16))) float Tm[64 * kLdm];
     __shared__ __attribute__((aligned(16))) float beta_s[64];
+    __shared__ __attribute__((aligned(16))) float rq_s[64];      // 1/||q_i|| when the read-out is normalised, else 1
     __shared__ __attribute__((aligned(16))) float g_s[64];
     E* Krq = reinterpret_cast<E*>(op_area);
     E* Qrq = reinterpret_cast<E*>(op_area + OPB);
@@ -98,24 +99,30 @@ __global__ __launch_bounds__(256) void intra_kernel(IntraArgs<E> a)
             }
             store_rq_piece(Krq, KP, row, piece, kd);
             store_rq_piece(Qrq, KP, row, piece, qd);
-            float ss = 0.f;
-            if constexpr (sizeof(E) == 2) {
-                const uint32_t w[4] = {kd.x, kd.y, kd.z, kd.w};
+            auto sum_squares = [](uint4 d) {
+                float ss = 0.f;
+                if constexpr (sizeof(E) == 2) {
+                    const uint32_t w[4] = {d.x, d.y, d.z, d.w};
 #pragma unroll
-                for (int m = 0; m < 4; ++m) {
-                    const float x0 = bf16_bits_to_float(w[m] & 0xffffu), x1 = bf16_bits_to_float(w[m] >> 16);
-                    ss += x0 * x0; ss += x1 * x1;
+                    for (int m = 0; m < 4; ++m) {
+                        const float x0 = bf16_bits_to_float(w[m] & 0xffffu), x1 = bf16_bits_to_float(w[m] >> 16);
+                        ss += x0 * x0; ss += x1 * x1;
+                    }
+                } else {
+                    const float x0 = __uint_as_float(d.x), x1 = __uint_as_float(d.y), x2 = __uint_as_float(d.z),
+                                x3 = __uint_as_float(d.w);
+                    ss = x0 * x0 + x1 * x1 + x2 * x2 + x3 * x3;
                 }
-            } else {
-                const float x0 = __uint_as_float(kd.x), x1 = __uint_as_float(kd.y), x2 = __uint_as_float(kd.z),
-                            x3 = __uint_as_float(kd.w);
-                ss = x0 * x0 + x1 * x1 + x2 * x2 + x3 * x3;
-            }
+                return ss;
+            };
+            float ss = sum_squares(kd), sq = sum_squares(qd);
 #pragma unroll
-            for (int off = 1; off < PPR; off <<= 1) ss += __shfl_xor(ss, off, kWave);
+            for (int off = 1; off < PPR; off <<= 1) { ss += __shfl_xor(ss, off, kWave); sq += __shfl_xor(sq, off, kWave); }
             if (piece == 0) {
                 const float et = row < clen ? a.eta[(size_t)(tok0 + row) * a.H + h] : 0.f;
-                beta_s[row] = kaczmarz_beta(et, ss, a.eps);
+                beta_s[row] = (a.opts & kOptGdnBeta) ? et : kaczmarz_beta(et, ss, a.eps);
+                // scale of the normalised read-out o_t = S_t^T q_t / ||q_t|| (Sec. 3.3); a zero query gives 0
+                rq_s[row] = (a.opts & kOptNormalizeQ) ? (sq > 0.f ? 1.0f / sqrtf(sq) : 0.f) : 1.f;
             }
         }
         if (wave == 0) {
@@ -126,7 +133,7 @@ __global__ __launch_bounds__(256) void intra_kernel(IntraArgs<E> a)
                 if (lane >= off) x += y;
             }
             g_s[lane] = x;
-            a.wsG[(size_t)blockIdx.x * 64 + lane] = x;
+            a.wsG[(size_t)blockIdx.x * 128 + lane] = x;
             // decay factors the scan stage multiplies with: gamma_i and gamma_C / gamma_i
             const float gl = __shfl(x, 63, kWave);
             float* dec = reinterpret_cast<float*>(reinterpret_cast<char*>(a.wsT) + (size_t)blockIdx.x * ws_record_bytes<E>()
@@ -136,6 +143,12 @@ __global__ __launch_bounds__(256) void intra_kernel(IntraArgs<E> a)
         }
     }
     __syncthreads();
+    if (wave == 0) {                                     // third vector of the record and the scale itself
+        float* dec = reinterpret_cast<float*>(reinterpret_cast<char*>(a.wsT) + (size_t)blockIdx.x * ws_record_bytes<E>()
+                                              + 2 * ws_half_bytes<E>());
+        dec[128 + lane] = expf(g_s[lane]) * rq_s[lane];
+        a.wsG[(size_t)blockIdx.x * 128 + 64 + lane] = rq_s[lane];
+    }
 
     // ---- phase 2a: Gram products K K^T and Q K^T on the lower-triangular tiles ---------------
     floatx4 acc[5];
@@ -172,7 +185,7 @@ __global__ __launch_bounds__(256) void intra_kernel(IntraArgs<E> a)
                 const float val = (j < i) ? beta_s[i] * expf(gi - gj) * acc[jb][e] : 0.f;
                 Lm[i * kLdm + j] = val;
             } else {
-                const float val = (j <= i) ? expf(gi - gj) * acc[jb][e] : 0.f;
+                const float val = (j <= i) ? expf(gi - gj) * acc[jb][e] * rq_s[i] : 0.f;
                 Pm[i * kLdm + j] = val;
             }
         }
@@ -315,7 +328,7 @@ __global__ void unpack_kernel(const E* __restrict__ wsT, const E* __restrict__ w
     const size_t e = (size_t)ch * (ws_record_bytes<E>() / sizeof(E)) + ((size_t)tri_pair(ti, jp) * 64 + ln) * 8 + ((j >> 4) & 1) * 4 + (j & 3);
     Tb[idx] = stored ? to_float(wsT[e]) : 0.f;
     P[idx] = stored ? to_float(wsP[e]) : 0.f;
-    if (j == 0) gout[ch * 64 + i] = wsG[ch * 64 + i];
+    if (j == 0) gout[ch * 64 + i] = wsG[ch * 128 + i];
 }
 template <typename E>
 hipError_t launch_unpack(const E* wsT, const E* wsP, const float* wsG, float* Tb, float* P, float* gout, long n_ch,

@@ -79,11 +79,13 @@ __global__ __launch_bounds__(256, 3) void intra_bf16_kernel(IntraArgs<bf16_t> a)
     __shared__ __attribute__((aligned(16))) float beta_s[64];
     __shared__ __attribute__((aligned(16))) float g_s[64];
     __shared__ __attribute__((aligned(16))) float eta_s[64];
+    __shared__ __attribute__((aligned(16))) float rq_s[64];      // 1/||q_i|| when the read-out is normalised, else 1
     float* Pm = reinterpret_cast<float*>(kq);
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r = lane & 15, g = lane >> 4;
+    const bool norm_q = (a.opts & kOptNormalizeQ) != 0, gdn = (a.opts & kOptGdnBeta) != 0;
 
     // ---- which chunk of which sequence -------------------------------------------------------
     const int h = blockIdx.x % a.H;
@@ -127,7 +129,8 @@ __global__ __launch_bounds__(256, 3) void intra_bf16_kernel(IntraArgs<bf16_t> a)
             const float x2 = x * 1.44269504088896341f;   // in units of log 2: every decay ratio is one v_exp_f32
             g_s[lane] = x2;
             eta_s[lane] = lane < clen ? a.eta[(size_t)(tok0 + lane) * a.H + h] : 0.f;
-            a.wsG[(size_t)blockIdx.x * 64 + lane] = x;
+            a.wsG[(size_t)blockIdx.x * 128 + lane] = x;
+            rq_s[lane] = 1.f;
             const float gl2 = __shfl(x2, 63, kWave);
             float* dec = reinterpret_cast<float*>(rec + 2 * HALF);
             dec[lane] = __builtin_amdgcn_exp2f(x2);            // gamma_i
@@ -136,6 +139,26 @@ __global__ __launch_bounds__(256, 3) void intra_bf16_kernel(IntraArgs<bf16_t> a)
         wait_vmcnt<0>();
     }
     __syncthreads();
+
+    // ---- query norms for the normalised read-out o_t = S_t^T q_t / ||q_t|| (Sec. 3.3): wave w takes rows
+    //      16 w + r, each of its four lane groups a quarter of the row
+    if (norm_q) {
+        const int row = 16 * wave + r;
+        const char* qrow = kq + TILE + row * RB;
+        float ss = 0.f;
+#pragma unroll
+        for (int i = 0; i < PPR / 4; ++i) {
+            const u32x4 w = ld16(qrow + ((((PPR / 4) * g + i) ^ swz_bits(row)) * 16));
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+                const float x0 = __uint_as_float(w[m] << 16), x1 = __uint_as_float(w[m] & 0xffff0000u);
+                ss += x0 * x0; ss += x1 * x1;
+            }
+        }
+        ss += __shfl_xor(ss, 16, kWave);
+        ss += __shfl_xor(ss, 32, kWave);
+        if (g == 0) rq_s[row] = ss > 0.f ? 1.0f / sqrtf(ss) : 0.f;     // ordered after wave 0's default by the barrier above
+    }
 
     // ---- phase 2a: Gram products K K^T and Q K^T on the lower-triangular tiles; five tiles per wave,
     //      five independent accumulators, shared operand row blocks read one contraction step ahead ----
@@ -176,12 +199,17 @@ __global__ __launch_bounds__(256, 3) void intra_bf16_kernel(IntraArgs<bf16_t> a)
                 if constexpr (J.q == 0 && J.ti == J.tj) {
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
-                        if (4 * g + e == r) beta_s[16 * J.ti + r] = kaczmarz_beta_fast(eta_s[16 * J.ti + r], acc[jb][e], a.eps);
+                        if (4 * g + e == r) beta_s[16 * J.ti + r] = gdn ? eta_s[16 * J.ti + r] : kaczmarz_beta_fast(eta_s[16 * J.ti + r], acc[jb][e], a.eps);
                 }
             });
         });
     }
-    __syncthreads();   // K/Q tiles are dead from here on (Pm overlays them); beta_s is complete
+    __syncthreads();   // K/Q tiles are dead from here on (Pm overlays them); beta_s and rq_s are complete
+    if (wave == 0) {                                     // third vector of the record and the scale itself
+        float* dec = reinterpret_cast<float*>(rec + 2 * HALF);
+        dec[128 + lane] = __builtin_amdgcn_exp2f(g_s[lane]) * rq_s[lane];
+        a.wsG[(size_t)blockIdx.x * 128 + 64 + lane] = rq_s[lane];
+    }
 
     // ---- phase 2b: decay, mask, beta -> L (into M) and P (into Pm) as fp32.  Tile coordinates are compile-time
     //      per wave, so only the diagonal tiles pay for the triangular mask ------------------------------
@@ -206,9 +234,11 @@ __global__ __launch_bounds__(256, 3) void intra_bf16_kernel(IntraArgs<bf16_t> a)
                     M[(16 * ti + 4 * g + e) * kLd + 16 * tj + r] = x;
                 }
             } else {
+                floatx4 rqv = {1.f, 1.f, 1.f, 1.f};
+                if (norm_q) rqv = ldf4(rq_s + 16 * ti + 4 * g);
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    float x = f[e] * acc[jb][e];
+                    float x = f[e] * acc[jb][e] * rqv[e];
                     if (ti == tj) x = (r <= 4 * g + e) ? x : 0.f;                      // lower with diagonal
                     if (clen < 64) x = (16 * ti + 4 * g + e < clen) ? x : 0.f;         // rows beyond a short chunk
                     Pm[(16 * ti + 4 * g + e) * kLd + 16 * tj + r] = x;

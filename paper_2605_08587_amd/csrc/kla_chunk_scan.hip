@@ -47,9 +47,9 @@ struct ScanCfg {
     static constexpr int VB = NW * 2 * 64 * SB;                 // V slice area
     static constexpr int OLD = SLW + EPP;                       // row stride of the output staging tile
     static constexpr int OSB = 64 * OLD * (int)sizeof(E);
-    // one stage: K rows | Q rows | K transposed | T' | P | V slice | gamma_i | gamma_C/gamma_i
+    // one stage: K rows | Q rows | K transposed | T' | P | V slice | gamma_i | gamma_C/gamma_i | gamma_i/||q_i||
     static constexpr int OFF_Q = OPB, OFF_KT = 2 * OPB, OFF_T = 3 * OPB, OFF_P = OFF_T + TPB, OFF_V = OFF_P + TPB,
-                         OFF_EG = OFF_V + VB, OFF_ED = OFF_EG + 256, STAGE = OFF_ED + 256;
+                         OFF_EG = OFF_V + VB, OFF_ED = OFF_EG + 256, OFF_EQ = OFF_ED + 256, STAGE = OFF_EQ + 256;
     static constexpr int STAGES = sizeof(E) == 2 ? 2 : 1;      // fp32 operands take twice the LDS: single buffer
     static constexpr int LDS = STAGES * (STAGE + OSB);
     static constexpr int UK = (16 * PPR + NTH - 1) / NTH;       // (4-row group, piece) units of K/Q per thread
@@ -64,7 +64,7 @@ template <typename E, int DK, int NW>
 struct Prefetch {
     typedef ScanCfg<E, DK, NW> C;
     uint4 k[C::UK][4], q[C::UK][4], v[C::UV][4], t[C::UT], p[C::UT];
-    float gv, gl;
+    float gv, gl, rq;
 };
 
 template <typename E, int DK, int NW>
@@ -147,8 +147,9 @@ __global__ __launch_bounds__(64 * NW) void scan_kernel(ScanArgs<E> a)
             pf.t[it] = make_uint4(0, 0, 0, 0); pf.p[it] = make_uint4(0, 0, 0, 0);
             if (C::TP16 % NTH == 0 || i < C::TP16) { pf.t[it] = tsrc[i]; pf.p[it] = psrc[i]; }
         }
-        pf.gv = a.wsG[ch * 64 + (tid & 63)];
-        pf.gl = a.wsG[ch * 64 + 63];
+        pf.gv = a.wsG[ch * 128 + (tid & 63)];
+        pf.gl = a.wsG[ch * 128 + 63];
+        pf.rq = a.wsG[ch * 128 + 64 + (tid & 63)];       // 1/||q_i||, or 1 (read-out not normalised)
     };
 
     // ---- registers -> LDS stage, in MFMA operand order ----------------------------------------
@@ -186,6 +187,7 @@ __global__ __launch_bounds__(64 * NW) void scan_kernel(ScanArgs<E> a)
         if (tid < 64) {
             reinterpret_cast<float*>(st + C::OFF_EG)[tid] = expf(pf.gv);            // gamma_i
             reinterpret_cast<float*>(st + C::OFF_ED)[tid] = expf(pf.gl - pf.gv);    // gamma_C / gamma_i
+            reinterpret_cast<float*>(st + C::OFF_EQ)[tid] = expf(pf.gv) * pf.rq;    // scale of the Q S term
         }
     };
 
@@ -252,7 +254,7 @@ __global__ __launch_bounds__(64 * NW) void scan_kernel(ScanArgs<E> a)
         }
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
-            floatx4 o = egv[it] * qs[it];
+            floatx4 o = ld_acc4(reinterpret_cast<const float*>(st + C::OFF_EQ) + 16 * it + 4 * g) * qs[it];
 #pragma unroll
             for (int jp = 0; jp <= (it >> 1); ++jp) {   // P is lower triangular
                 const Slot<E> sp = load_slot(Prq, tri_pair(it, jp), lane);

@@ -52,7 +52,7 @@ struct Cfg {
     static constexpr int TPB = kTriPairs * 64 * 16;      // bytes of one T' or P area; [T' | P] is one 12 KiB record
     static constexpr int NTB = 2 * TPB / 1024;           // = 12
     static constexpr int OFF_Q = 64 * RB, OFF_T = 2 * 64 * RB, OFF_P = OFF_T + TPB, OFF_V = OFF_T + 2 * TPB,
-                         OFF_EG = OFF_V + 64 * VRW, OFF_ED = OFF_EG + 256, STAGE = OFF_ED + 256;
+                         OFF_EG = OFF_V + 64 * VRW, OFF_ED = OFF_EG + 256, OFF_EQ = OFF_ED + 256, STAGE = OFF_EQ + 256;
     // row stride of the output staging tile: 24 (NW <= 2) or 40 (NW = 4) dwords, so that the 8-dword spans which
     // one wave writes into 8 consecutive rows fall into disjoint banks
     static constexpr int ORB = NW <= 2 ? 96 : 160;
@@ -65,7 +65,9 @@ struct Cfg {
 
 }  // namespace
 
-template <int DK, int NW>
+// NQ: normalised read-out (Sec. 3.3): the output rows are scaled by 1/||q_i||, which stage 1 folded into P and
+// into the third vector of the record, gamma_i/||q_i||, read here in place of gamma_i for the Q S term.
+template <int DK, int NW, bool NQ>
 __global__ __launch_bounds__(64 * NW + 64) void scan_bf16_kernel(ScanArgs<bf16_t> a)
 {
     typedef Cfg<DK, NW> C;
@@ -173,7 +175,7 @@ __global__ __launch_bounds__(64 * NW + 64) void scan_bf16_kernel(ScanArgs<bf16_t
             const int b = i;
             dma16(tc + b * 1024, lane * 16, st + C::OFF_T + b * 1024);
         });
-        if (lane < 32) dma16(tc + 2 * C::TPB, lane * 16, st + C::OFF_EG);   // gamma_i | gamma_C/gamma_i: 512 bytes
+        if (lane < 48) dma16(tc + 2 * C::TPB, lane * 16, st + C::OFF_EG);   // gamma_i | gamma_C/gamma_i | gamma_i/||q_i||: 768 bytes
     };
 
     // ---- one chunk of the recurrence for this wave's 16 columns ------------------------------------
@@ -286,7 +288,7 @@ __global__ __launch_bounds__(64 * NW + 64) void scan_bf16_kernel(ScanArgs<bf16_t
         floatx4 o[4];
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
-            o[it] = egv[it] * qs[it];
+            if constexpr (NQ) o[it] = ld_f4(pG + 512 + 64 * it) * qs[it]; else o[it] = egv[it] * qs[it];
             mma_bf16(o[it], psl[tri_pair(it, 0)], Uq[0], Uq[1]);
         }
         mma_bf16(o[2], psl[tri_pair(2, 1)], Uq[2], Uq[3]);
@@ -379,10 +381,20 @@ static hipError_t launch_dk(const ScanArgs<bf16_t>& a, int waves, hipStream_t st
     if (n_chains == 0) return hipSuccess;
     const int nsl = a.dv / (16 * waves);
     const dim3 grid((unsigned)(((n_chains + 7) / 8) * 8 * nsl));
+    const bool nq = (a.opts & kOptNormalizeQ) != 0;
     switch (waves) {
-        case 1: hipLaunchKernelGGL((scan_bf16_kernel<DK, 1>), grid, dim3(128), 0, st, a); break;
-        case 2: hipLaunchKernelGGL((scan_bf16_kernel<DK, 2>), grid, dim3(192), 0, st, a); break;
-        default: hipLaunchKernelGGL((scan_bf16_kernel<DK, 4>), grid, dim3(320), 0, st, a); break;
+        case 1:
+            if (nq) hipLaunchKernelGGL((scan_bf16_kernel<DK, 1, true>), grid, dim3(128), 0, st, a);
+            else    hipLaunchKernelGGL((scan_bf16_kernel<DK, 1, false>), grid, dim3(128), 0, st, a);
+            break;
+        case 2:
+            if (nq) hipLaunchKernelGGL((scan_bf16_kernel<DK, 2, true>), grid, dim3(192), 0, st, a);
+            else    hipLaunchKernelGGL((scan_bf16_kernel<DK, 2, false>), grid, dim3(192), 0, st, a);
+            break;
+        default:
+            if (nq) hipLaunchKernelGGL((scan_bf16_kernel<DK, 4, true>), grid, dim3(320), 0, st, a);
+            else    hipLaunchKernelGGL((scan_bf16_kernel<DK, 4, false>), grid, dim3(320), 0, st, a);
+            break;
     }
     return hipGetLastError();
 }

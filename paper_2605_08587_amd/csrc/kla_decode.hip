@@ -19,7 +19,8 @@ __global__ __launch_bounds__(256) void decode_kernel(const T* __restrict__ q, co
                                                      const T* __restrict__ v,
                                                      const float* __restrict__ log_alpha,
                                                      const float* __restrict__ eta, float eps,
-                                                     float* __restrict__ S, T* __restrict__ o, int dv)
+                                                     float* __restrict__ S, T* __restrict__ o, int dv,
+                                                     unsigned opts)
 {
     constexpr int LPR = DVS / 4;
     constexpr int RPP = 256 / LPR;
@@ -58,7 +59,7 @@ __global__ __launch_bounds__(256) void decode_kernel(const T* __restrict__ q, co
     }
 
     __shared__ float ks[DK], qs[DK];
-    __shared__ float red[4][2];
+    __shared__ float red[4][3];
     __shared__ float part[4][LPR][8];
 
     if (tid < DK) {
@@ -67,13 +68,20 @@ __global__ __launch_bounds__(256) void decode_kernel(const T* __restrict__ q, co
     }
     const float kk = wave_sum(kv * kv);
     const float kq = wave_sum(kv * qv);
+    const float qq = wave_sum(qv * qv);
     const int wave = tid / kWave, lane = tid % kWave;
-    if (lane == 0) { red[wave][0] = kk; red[wave][1] = kq; }
+    if (lane == 0) { red[wave][0] = kk; red[wave][1] = kq; red[wave][2] = qq; }
     __syncthreads();
     const float knorm2 = red[0][0] + red[1][0] + red[2][0] + red[3][0];
     const float kdotq = red[0][1] + red[1][1] + red[2][1] + red[3][1];
     const float alpha = expf(la);
-    const float beta = kaczmarz_beta(et, knorm2, eps);
+    const float beta = (opts & kOptGdnBeta) ? et : kaczmarz_beta(et, knorm2, eps);
+    // read-out scale: 1, or 1/||q|| (0 for a zero query) for the normalised read-out of Sec. 3.3
+    float oscale = 1.f;
+    if (opts & kOptNormalizeQ) {
+        const float qnorm2 = red[0][2] + red[1][2] + red[2][2] + red[3][2];
+        oscale = qnorm2 > 0.f ? 1.0f / sqrtf(qnorm2) : 0.f;
+    }
 
     float pr[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};   // p[0..3], r[0..3] for this lane's 4 columns
 #pragma unroll
@@ -115,20 +123,20 @@ __global__ __launch_bounds__(256) void decode_kernel(const T* __restrict__ q, co
         T* ob = o + (size_t)bh * dv + col;
         const float bkq = beta * kdotq;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) ob[i] = from_float<T>(alpha * pr[4 + i] + bkq * e[i]);
+        for (int i = 0; i < 4; ++i) ob[i] = from_float<T>(oscale * (alpha * pr[4 + i] + bkq * e[i]));
     }
 }
 
 template <typename T, int DK, int NT>
 static hipError_t launch_decode_nt(const T* q, const T* k, const T* v, const float* la, const float* eta,
-                                   float eps, float* S, T* o, int BH, int dv, int slice, hipStream_t st)
+                                   float eps, float* S, T* o, int BH, int dv, int slice, unsigned opts, hipStream_t st)
 {
     dim3 grid(BH, dv / slice), block(256);
     switch (slice) {
-        case 32:  hipLaunchKernelGGL((decode_kernel<T, DK, 32, NT>), grid, block, 0, st, q, k, v, la, eta, eps, S, o, dv); break;
-        case 64:  hipLaunchKernelGGL((decode_kernel<T, DK, 64, NT>), grid, block, 0, st, q, k, v, la, eta, eps, S, o, dv); break;
-        case 128: hipLaunchKernelGGL((decode_kernel<T, DK, 128, NT>), grid, block, 0, st, q, k, v, la, eta, eps, S, o, dv); break;
-        default:  hipLaunchKernelGGL((decode_kernel<T, DK, 256, NT>), grid, block, 0, st, q, k, v, la, eta, eps, S, o, dv); break;
+        case 32:  hipLaunchKernelGGL((decode_kernel<T, DK, 32, NT>), grid, block, 0, st, q, k, v, la, eta, eps, S, o, dv, opts); break;
+        case 64:  hipLaunchKernelGGL((decode_kernel<T, DK, 64, NT>), grid, block, 0, st, q, k, v, la, eta, eps, S, o, dv, opts); break;
+        case 128: hipLaunchKernelGGL((decode_kernel<T, DK, 128, NT>), grid, block, 0, st, q, k, v, la, eta, eps, S, o, dv, opts); break;
+        default:  hipLaunchKernelGGL((decode_kernel<T, DK, 256, NT>), grid, block, 0, st, q, k, v, la, eta, eps, S, o, dv, opts); break;
     }
     return hipGetLastError();
 }
@@ -139,30 +147,30 @@ static hipError_t launch_decode_nt(const T* q, const T* k, const T* v, const flo
 // resident).  KLA_DECODE_NT = 0..3 overrides (bit 0: loads, bit 1: stores).
 template <typename T, int DK>
 static hipError_t launch_decode_dk(const T* q, const T* k, const T* v, const float* la, const float* eta,
-                                   float eps, float* S, T* o, int BH, int dv, int slice, hipStream_t st)
+                                   float eps, float* S, T* o, int BH, int dv, int slice, unsigned opts, hipStream_t st)
 {
     int nt = ((size_t)BH * DK * dv * sizeof(float) >= ((size_t)16 << 20)) ? 3 : 0;
     const char* env = getenv("KLA_DECODE_NT");
     if (env && env[0] >= '0' && env[0] <= '3') nt = env[0] - '0';
     switch (nt) {
-        case 0:  return launch_decode_nt<T, DK, 0>(q, k, v, la, eta, eps, S, o, BH, dv, slice, st);
-        case 1:  return launch_decode_nt<T, DK, 1>(q, k, v, la, eta, eps, S, o, BH, dv, slice, st);
-        case 2:  return launch_decode_nt<T, DK, 2>(q, k, v, la, eta, eps, S, o, BH, dv, slice, st);
-        default: return launch_decode_nt<T, DK, 3>(q, k, v, la, eta, eps, S, o, BH, dv, slice, st);
+        case 0:  return launch_decode_nt<T, DK, 0>(q, k, v, la, eta, eps, S, o, BH, dv, slice, opts, st);
+        case 1:  return launch_decode_nt<T, DK, 1>(q, k, v, la, eta, eps, S, o, BH, dv, slice, opts, st);
+        case 2:  return launch_decode_nt<T, DK, 2>(q, k, v, la, eta, eps, S, o, BH, dv, slice, opts, st);
+        default: return launch_decode_nt<T, DK, 3>(q, k, v, la, eta, eps, S, o, BH, dv, slice, opts, st);
     }
 }
 
 template <typename T>
 hipError_t launch_decode(const T* q, const T* k, const T* v, const float* la, const float* eta, float eps,
-                         float* S, T* o, int BH, int dk, int dv, int slice, hipStream_t st)
+                         float* S, T* o, int BH, int dk, int dv, int slice, unsigned opts, hipStream_t st)
 {
-    if (dk == 64) return launch_decode_dk<T, 64>(q, k, v, la, eta, eps, S, o, BH, dv, slice, st);
-    return launch_decode_dk<T, 128>(q, k, v, la, eta, eps, S, o, BH, dv, slice, st);
+    if (dk == 64) return launch_decode_dk<T, 64>(q, k, v, la, eta, eps, S, o, BH, dv, slice, opts, st);
+    return launch_decode_dk<T, 128>(q, k, v, la, eta, eps, S, o, BH, dv, slice, opts, st);
 }
 template hipError_t launch_decode<float>(const float*, const float*, const float*, const float*, const float*,
-                                         float, float*, float*, int, int, int, int, hipStream_t);
+                                         float, float*, float*, int, int, int, int, unsigned, hipStream_t);
 template hipError_t launch_decode<bf16_t>(const bf16_t*, const bf16_t*, const bf16_t*, const float*, const float*,
-                                          float, float*, bf16_t*, int, int, int, int, hipStream_t);
+                                          float, float*, bf16_t*, int, int, int, int, unsigned, hipStream_t);
 
 // eq. (3) alone: one group of DK/8 lanes per row, each lane squares 8 consecutive elements.
 template <typename T, int DK>

@@ -7,19 +7,22 @@
 
 namespace kla {
 
+// option bits (the values of KLA_OPT_* in include/kla.h)
+constexpr unsigned kOptNormalizeQ = 1u, kOptGdnBeta = 2u;
+
 // ---- decode step and stand-alone coefficient -----------------------------------------------
 template <typename T>
 hipError_t launch_decode(const T* q, const T* k, const T* v, const float* log_alpha, const float* eta, float eps,
-                         float* S, T* o, int BH, int dk, int dv, int slice, hipStream_t st);
+                         float* S, T* o, int BH, int dk, int dv, int slice, unsigned opts, hipStream_t st);
 template <typename T>
 hipError_t launch_beta(const T* k, const float* eta, float eps, float* beta, long n_rows, int dk, hipStream_t st);
 
 // ---- chunkwise forward ------------------------------------------------------------------------
 // Workspace areas, all indexed by chunk-head ch = global_chunk * H + h:
-//   wsT, wsP : per chunk-head one record [T' | P | gamma_i | gamma_C/gamma_i]; T' and P are 6 tile-pairs x 64
-//              operand slots of 8 elements (see kla_mma.hpp), the decay factors 64 fp32 each;
+//   wsT, wsP : per chunk-head one record [T' | P | gamma_i | gamma_C/gamma_i | gamma_i/||q_i||]; T' and P are 6
+//              tile-pairs x 64 operand slots of 8 elements (see kla_mma.hpp), the three vectors 64 fp32 each;
 //              wsP = wsT + one half, both advance by a whole record
-//   wsG      : 64 fp32 per chunk-head
+//   wsG      : 128 fp32 per chunk-head: g_i = log gamma_i, then 1/||q_i|| (1 unless the read-out is normalised)
 //   chunk_off: int32 [n_seq + 1], packed batches only
 template <typename E> struct IntraArgs {
     const E* q; const E* k;
@@ -27,6 +30,7 @@ template <typename E> struct IntraArgs {
     const int* cu_seqlens; const int* chunk_off; int n_seq;
     int T, NT, H;
     E* wsT; E* wsP; float* wsG;
+    unsigned opts;                               // kOptNormalizeQ | kOptGdnBeta
 };
 template <typename E> hipError_t launch_intra(const IntraArgs<E>& a, int dk, int n_chunks, hipStream_t st);
 
@@ -36,6 +40,7 @@ template <typename E> struct ScanArgs {
     const int* cu_seqlens; const int* chunk_off; int n_seq;
     int N, T, NT, H, dv;
     const E* wsT; const E* wsP; const float* wsG;
+    unsigned opts;
 };
 // waves = 1, 2 or 4: each wave of a workgroup carries 16 state columns through the whole sequence
 template <typename E> hipError_t launch_scan(const ScanArgs<E>& a, int dk, int waves, hipStream_t st);

@@ -42,9 +42,10 @@ template <typename E> constexpr int slot_bytes() { return 2 * (int)sizeof(typena
 // T' and P are lower triangular: of the 8 tile-pairs (tile row it, pair jp) of a 64x64 operand only
 // the 6 with jp <= it/2 are stored, in this order.
 constexpr int kTriPairs = 6;
-// Workspace record of one chunk-head: [T' | P | gamma_i (64 fp32) | gamma_C/gamma_i (64 fp32)]
+// Workspace record of one chunk-head: [T' | P | gamma_i | gamma_C/gamma_i | gamma_i/||q_i||] (64 fp32 each; the
+// last vector equals gamma_i unless the read-out is normalised)
 template <typename E> constexpr int ws_half_bytes() { return kTriPairs * 64 * 8 * (int)sizeof(E); }
-template <typename E> constexpr int ws_record_bytes() { return 2 * ws_half_bytes<E>() + 512; }
+template <typename E> constexpr int ws_record_bytes() { return 2 * ws_half_bytes<E>() + 768; }
 __host__ __device__ constexpr int tri_pair(int it, int jp) { return it < 2 ? it : 2 * it - 2 + jp; }
 
 // ---- conversions between accumulator tiles and quads -------------------------------------

@@ -24,7 +24,7 @@ def _declared_functions():
 def test_every_declared_symbol_is_exported():
     names = _declared_functions()
     assert {"kla_chunk_fwd", "kla_decode_step", "kla_beta", "kla_chunk_fwd_workspace_bytes", "kla_status_string",
-            "kla_debug_intra_chunk"} <= set(names)
+            "kla_debug_intra_chunk", "kla_chunk_fwd_opts", "kla_decode_step_opts"} <= set(names)
     lib = ctypes.CDLL(kla.LIB_PATH)
     for n in names:
         assert hasattr(lib, n), n
@@ -41,16 +41,16 @@ def test_status_strings():
 def test_workspace_bytes():
     lib = kla.lib()
     f = lib.kla_chunk_fwd_workspace_bytes
-    # 4096 chunk-heads, bf16: a record of 2 x 6 KiB operand areas + 512 B of decay factors, and 256 B of g
-    # each, plus the (empty) offsets table
+    # 4096 chunk-heads, bf16: a record of 2 x 6 KiB operand areas + 3 x 256 B of per-token factors, and 512 B of
+    # g and 1/|q| each, plus the (empty) offsets table
     n = f(8, 4096, 8, 128, 128, 64, kla.KLA_BF16, None, 0)
-    assert n >= 4096 * (2 * 6144 + 512 + 256) and n <= 4096 * (2 * 6144 + 512 + 256) + 4 * 256
+    assert n >= 4096 * (2 * 6144 + 768 + 512) and n <= 4096 * (2 * 6144 + 768 + 512) + 4 * 256
     assert f(8, 4096, 8, 128, 128, 64, kla.KLA_F32, None, 0) > n
     assert f(8, 4096, 8, 128, 128, 32, kla.KLA_BF16, None, 0) == 0        # chunk != 64
     assert f(8, 4096, 8, 96, 128, 64, kla.KLA_BF16, None, 0) == 0         # bad dk
     cu = np.array([0, 10, 10, 200], dtype=np.int32)                       # 1 + 0 + 3 chunks
     n2 = f(1, 200, 2, 64, 64, 64, kla.KLA_BF16, cu.ctypes.data, 3)
-    assert n2 >= 4 * 2 * (2 * 6144 + 512 + 256)
+    assert n2 >= 4 * 2 * (2 * 6144 + 768 + 512)
     bad = np.array([0, 10, 5, 200], dtype=np.int32)
     assert f(1, 200, 2, 64, 64, 64, kla.KLA_BF16, bad.ctypes.data, 3) == 0
 
@@ -132,3 +132,24 @@ def test_binding_refuses_cpu_tensors():
         kla.kla_chunk_fwd(x, x, x, g, g, 1e-6)
     with pytest.raises(RuntimeError):
         kla.kla_beta(x, g, 1e-6)
+
+
+def test_option_entry_points_validate_like_the_plain_ones():
+    lib = kla.lib()
+    chunk = lambda opts, **o: lib.kla_chunk_fwd_opts(
+        *[{**dict(q=0x1000, k=0x2000, v=0x3000, la=0x4000, eta=0x5000, eps=1e-6, h0=None, o=0x6000, hT=None,
+                  cu_dev=None, cu_host=None, n_seq=0, N=1, T=64, H=1, dk=64, dv=64, chunk=64, dt=kla.KLA_BF16,
+                  ws=0x100000, ws_bytes=1 << 30, stream=None), **o}[n]
+          for n in ("q", "k", "v", "la", "eta", "eps", "h0", "o", "hT", "cu_dev", "cu_host", "n_seq", "N", "T", "H",
+                    "dk", "dv", "chunk", "dt", "ws", "ws_bytes", "stream")], opts)
+    assert chunk(4) == E_SHAPE                      # unknown option bit
+    assert chunk(8 | kla.KLA_OPT_GDN_BETA) == E_SHAPE
+    assert chunk(kla.KLA_OPT_NORMALIZE_Q, q=None) == E_NULL
+    assert chunk(kla.KLA_OPT_NORMALIZE_Q | kla.KLA_OPT_GDN_BETA, N=0) == OK
+    dec = lambda opts, **o: lib.kla_decode_step_opts(
+        *[{**dict(q=0x1000, k=0x2000, v=0x3000, la=0x4000, eta=0x5000, eps=1e-6, S=0x6000, o=0x7000, B=2, H=2,
+                  dk=128, dv=128, dt=kla.KLA_BF16, st=None), **o}[n]
+          for n in ("q", "k", "v", "la", "eta", "eps", "S", "o", "B", "H", "dk", "dv", "dt", "st")], opts)
+    assert dec(16) == E_SHAPE
+    assert dec(kla.KLA_OPT_GDN_BETA, S=None) == E_NULL
+    assert dec(3, B=0) == OK

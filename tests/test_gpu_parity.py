@@ -251,3 +251,56 @@ def test_projection_property_on_gpu(kla):
     kla.kla_decode_step(q, k, v, torch.zeros((B, H)).cuda(), torch.ones((B, H)).cuda(), 0.0, S)
     res = torch.einsum("bhkv,bhk->bhv", S.double(), k.double()) - v.double()
     assert float(res.abs().max()) <= 1e-4 * float(v.abs().max())
+
+
+# ---------------------------------------------------------------------------------------------
+# options of the *_opts entry points: normalised read-out (Sec. 3.3) and beta = eta (Table 2)
+@pytest.mark.gpu
+@pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("nq,gdn", [(True, False), (False, True), (True, True)])
+@pytest.mark.parametrize("T,dk,dv", [(200, 128, 128), (65, 64, 256)])
+def test_chunk_options(kla, dt, nq, gdn, T, dk, dv):
+    # keys scaled down in the beta = eta mode: without the Kaczmarz denominator I - eta k k^T must stay a contraction
+    d = kla_inputs.chunk_inputs(2, T, 3, dk, dv, dtype=dt, seed=91 + T, h0_std=0.5)
+    if gdn:
+        d["k"] = (d["k"].float() * 0.08).to(dt)
+    if nq:                                            # one zero query: its output must be exactly 0
+        d["q"][1, min(7, T - 1), 2] = 0
+    q, k, v, la, eta, h0 = _gpu(d, "q", "k", "v", "log_alpha", "eta", "h0")
+    o, hT = kla.kla_chunk_fwd(q, k, v, la, eta, d["eps"], h0=h0, normalize_q=nq, gdn_beta=gdn)
+    torch.cuda.synchronize()
+    o, hT = o.float().cpu().numpy(), hT.cpu().numpy()
+    qn, kn, vn = (kla_inputs.to_numpy_f32(d[x]) for x in "qkv")
+    ro, rh, _ = token_oracle.kla_recurrent(qn, kn, vn, d["log_alpha"].numpy(), d["eta"].numpy(), d["eps"],
+                                           h0=d["h0"].numpy(), normalize_q=nq, gdn_beta=gdn)
+    eo, eh = token_oracle.rel_err(o, ro), token_oracle.rel_err(hT, rh)
+    print("options nq=%s gdn=%s %s T=%d dk=%d dv=%d: rel err o=%.3e hT=%.3e" % (nq, gdn, dt, T, dk, dv, eo, eh), flush=True)
+    assert eo <= TOL[dt] and eh <= TOL[dt]
+    if nq:
+        assert np.all(o[1, min(7, T - 1), 2] == 0.0)
+    # the options change the result (the comparison above is not vacuous)
+    po, ph = kla.kla_chunk_fwd(q, k, v, la, eta, d["eps"], h0=h0)
+    assert token_oracle.rel_err(po.float().cpu().numpy(), ro) > 10 * TOL[dt]
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("nq,gdn", [(True, False), (False, True), (True, True)])
+def test_decode_options(kla, dt, nq, gdn):
+    d = kla_inputs.decode_inputs(4, 5, 3, 128, 256, dtype=dt, seed=93)
+    S = d["S"].cuda()
+    Sref = d["S"].numpy().astype(np.float64)
+    for t in range(4):
+        qt, kt, vt = d["q"][t], (d["k"][t].float() * (0.08 if gdn else 1.0)).to(dt), d["v"][t]
+        if nq and t == 1:
+            qt = qt.clone(); qt[2, 1] = 0
+        o = kla.kla_decode_step(qt.cuda(), kt.cuda(), vt.cuda(), d["log_alpha"][t].cuda(), d["eta"][t].cuda(), d["eps"], S,
+                                normalize_q=nq, gdn_beta=gdn)
+        ro, Sref = token_oracle.kla_decode(kla_inputs.to_numpy_f32(qt), kla_inputs.to_numpy_f32(kt),
+                                           kla_inputs.to_numpy_f32(vt), d["log_alpha"][t].numpy(), d["eta"][t].numpy(),
+                                           d["eps"], Sref, normalize_q=nq, gdn_beta=gdn)
+        torch.cuda.synchronize()
+        assert token_oracle.rel_err(o.float().cpu().numpy(), ro) <= TOL[dt]
+        if nq and t == 1:
+            assert np.all(o[2, 1].float().cpu().numpy() == 0.0)
+    assert token_oracle.rel_err(S.cpu().numpy(), Sref) <= TOL[dt]
