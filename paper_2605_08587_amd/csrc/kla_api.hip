@@ -22,8 +22,36 @@ static_assert(KLA_OPT_NORMALIZE_Q == (int)kla::kOptNormalizeQ && KLA_OPT_GDN_BET
 struct Plan {
     long n_chunks;       // over all sequences
     int n_states;        // sequences
-    size_t off_T, off_P, off_G, off_C, total;
+    size_t off_T, off_P, off_G, off_C, off_M, off_S, total;
+    int seg_G, seg_Lc;   // segment-parallel scan: segments per sequence (1 = off) and chunks per segment
 };
+
+// Segments per sequence for the scan stage.  A small fixed-length bf16 batch of long sequences (at most 128
+// sixteen-column chains, at least 64 chunks) is cut so that about 256 workgroups of two chains run (measured
+// on one 65K-token sequence of 8 heads: 1.24 ms unsegmented, 0.70 ms with 4 segments, 0.57 ms with 8, 0.71 ms
+// with 16); KLA_SCAN_SEGMENTS = n forces n (1 = never).  Returns the number of non-empty segments and sets the chunks per segment.
+int plan_segments(int N, int NT, int H, int dv, int dt, int n_seq, int* Lc)
+{
+    *Lc = NT;
+    if (dt != KLA_BF16 || n_seq > 0 || N <= 0 || NT < 2) return 1;
+    { const char* impl = getenv("KLA_SCAN_IMPL"); if (impl && impl[0] == 'g') return 1; }   // generic kernels: never
+    const long groups = (long)N * H * (dv / 16);
+    int want = 1;
+    const char* env = getenv("KLA_SCAN_SEGMENTS");
+    if (env && atoi(env) >= 1) want = atoi(env) > 16 ? 16 : atoi(env);
+    else if (groups <= 128 && NT >= 64) {
+        // up to 512 sixteen-column chains (256 workgroups of two compute waves), segments of at least 16 chunks
+        want = 1;
+        while (want < 16 && (long)want * 2 * groups <= 512 && NT / (want * 2) >= 16) want *= 2;
+    }
+    if (want > NT) want = NT;
+    if (want <= 1) return 1;
+    const int lc = (NT + want - 1) / want;
+    const int G = (NT + lc - 1) / lc;
+    if (G <= 1) return 1;
+    *Lc = lc;
+    return G;
+}
 
 // Validates the size arguments shared by the chunk entry points and lays out the workspace.
 int make_plan(int N, int T, int H, int dk, int dv, int chunk, int dt, const int32_t* cu_host, int n_seq, Plan* p)
@@ -54,7 +82,13 @@ int make_plan(int N, int T, int H, int dk, int dv, int chunk, int dt, const int3
     p->off_P = half;
     p->off_G = round256((size_t)n_chunks * H * (2 * half + 768));   // + three vectors of 64 fp32 (see kla_mma.hpp)
     p->off_C = round256(p->off_G + (size_t)n_chunks * H * 128 * sizeof(float));      // g and 1/||q||
-    p->total = round256(p->off_C + (size_t)(n_seq + 1) * sizeof(int32_t));
+    p->off_M = round256(p->off_C + (size_t)(n_seq + 1) * sizeof(int32_t));
+    p->seg_G = plan_segments(N, (T + 63) / 64, H, dv, dt, n_seq, &p->seg_Lc);
+    // per (sequence, head): G - 1 maps [N | M] and G incoming states, fp32
+    const size_t maps = p->seg_G > 1 ? (size_t)N * (p->seg_G - 1) * H * dk * (dv + dk) * sizeof(float) : 0;
+    const size_t states = p->seg_G > 1 ? (size_t)N * p->seg_G * H * dk * dv * sizeof(float) : 0;
+    p->off_S = round256(p->off_M + maps);
+    p->total = round256(p->off_S + states);
     return KLA_OK;
 }
 
@@ -116,6 +150,24 @@ int chunk_fwd_impl(const void* q, const void* k, const void* v, const float* log
     sa.cu_seqlens = ia.cu_seqlens; sa.chunk_off = chunk_off; sa.n_seq = n_seq;
     sa.N = N; sa.T = T; sa.NT = NT; sa.H = H; sa.dv = dv;
     sa.wsT = wsT; sa.wsP = wsP; sa.wsG = wsG; sa.opts = opts;
+    sa.seg_G = 0; sa.seg_Lc = 0;
+    if constexpr (sizeof(E) == 2) {
+        if (pl.seg_G > 1) {
+            // segment-parallel scan: maps of all segments but the last, their prefix composition, then every
+            // segment at once from its incoming state (see kla_chunk_segments.hip)
+            float* maps = reinterpret_cast<float*>(ws + pl.off_M);
+            float* seg_state = reinterpret_cast<float*>(ws + pl.off_S);
+            sa.seg_G = pl.seg_G; sa.seg_Lc = pl.seg_Lc;
+            if (kla::launch_segment_maps_bf16(sa, dk, maps, st) != hipSuccess) return KLA_ERR_HIP;
+            if (kla::launch_segment_combine(h0, maps, seg_state, N, H, dk, dv, pl.seg_G, st) != hipSuccess) return KLA_ERR_HIP;
+            sa.h0 = seg_state; sa.hT = seg_state;
+            const int wseg = scan_waves(pl.n_states * pl.seg_G * H, dv, KLA_BF16);
+            if (kla::launch_scan_bf16(sa, dk, wseg, st) != hipSuccess) return KLA_ERR_HIP;
+            if (hT && kla::launch_segment_gather(seg_state, hT, N, H, dk, dv, pl.seg_G, pl.seg_G - 1, st) != hipSuccess)
+                return KLA_ERR_HIP;
+            return KLA_OK;
+        }
+    }
     const int waves = scan_waves(pl.n_states * H, dv, sizeof(E) == 2 ? KLA_BF16 : KLA_F32);
     if constexpr (sizeof(E) == 2) {
         const char* impl = getenv("KLA_SCAN_IMPL");   // "generic": the element-type-generic kernel (A/B testing)

@@ -82,7 +82,7 @@ __global__ __launch_bounds__(64 * NW + 64) void scan_bf16_kernel(ScanArgs<bf16_t
 
     // ---- workgroup -> (sequence, head, column slice); slices of one head share an XCD (ids congruent mod 8)
     const int nsl = a.dv / SLW;
-    const int n_states = a.n_seq > 0 ? a.n_seq : a.N;
+    const int n_states = a.n_seq > 0 ? a.n_seq : (a.seg_G > 0 ? a.N * a.seg_G : a.N);
     const int n_chains = n_states * a.H;
     const int xcd = blockIdx.x & 7, pidx = blockIdx.x >> 3;
     const int chain = (pidx / nsl) * 8 + xcd, slice = pidx % nsl;
@@ -90,6 +90,13 @@ __global__ __launch_bounds__(64 * NW + 64) void scan_bf16_kernel(ScanArgs<bf16_t
     const int s = chain / a.H, h = chain % a.H;
     long t0; int len, ch0;
     if (a.cu_seqlens) { t0 = a.cu_seqlens[s]; len = a.cu_seqlens[s + 1] - (int)t0; ch0 = a.chunk_off[s]; }
+    else if (a.seg_G > 0) {                              // segment sg of sequence n: chunks [sg Lc, (sg + 1) Lc)
+        const int n = s / a.seg_G, sg = s % a.seg_G;
+        const int tok = min(sg * a.seg_Lc * 64, a.T);
+        t0 = (long)n * a.T + tok;
+        len = min(a.seg_Lc * 64, a.T - tok);
+        ch0 = n * a.NT + sg * a.seg_Lc;
+    }
     else              { t0 = (long)s * a.T;   len = a.T;                           ch0 = s * a.NT; }
     const int nch = (len + 63) / 64;
     const int col = slice * SLW + 16 * wave + r;
@@ -376,7 +383,7 @@ __global__ __launch_bounds__(64 * NW + 64) void scan_bf16_kernel(ScanArgs<bf16_t
 template <int DK>
 static hipError_t launch_dk(const ScanArgs<bf16_t>& a, int waves, hipStream_t st)
 {
-    const int n_states = a.n_seq > 0 ? a.n_seq : a.N;
+    const int n_states = a.n_seq > 0 ? a.n_seq : (a.seg_G > 0 ? a.N * a.seg_G : a.N);
     const int n_chains = n_states * a.H;
     if (n_chains == 0) return hipSuccess;
     const int nsl = a.dv / (16 * waves);

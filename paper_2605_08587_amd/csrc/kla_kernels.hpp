@@ -41,6 +41,10 @@ template <typename E> struct ScanArgs {
     int N, T, NT, H, dv;
     const E* wsT; const E* wsP; const float* wsG;
     unsigned opts;
+    // Segmented mode (seg_G > 0, fixed-length batches only): "sequence" s of the kernel is segment s % seg_G of
+    // sequence s / seg_G, seg_Lc chunks long (the last one of a sequence takes what is left), and h0 / hT are
+    // indexed by segment.
+    int seg_G, seg_Lc;
 };
 // waves = 1, 2 or 4: each wave of a workgroup carries 16 state columns through the whole sequence
 template <typename E> hipError_t launch_scan(const ScanArgs<E>& a, int dk, int waves, hipStream_t st);
@@ -48,6 +52,15 @@ template <typename E> hipError_t launch_scan(const ScanArgs<E>& a, int dk, int w
 // bf16 specialisations (direct global->LDS copies, swizzled token-major staging, transposing LDS reads)
 hipError_t launch_intra_bf16(const IntraArgs<bf16_t>& a, int dk, int n_chunks, hipStream_t st);
 hipError_t launch_scan_bf16(const ScanArgs<bf16_t>& a, int dk, int waves, hipStream_t st);
+
+// Segment-parallel scan of long sequences in small batches (bf16): per-segment affine maps of the state, their
+// prefix composition, then the ordinary scan over all segments at once.  `maps` holds (G-1) x [N | M] per
+// sequence and head, `seg_state` the G incoming states; both fp32, in the workspace.
+hipError_t launch_segment_maps_bf16(const ScanArgs<bf16_t>& a, int dk, float* maps, hipStream_t st);
+hipError_t launch_segment_combine(const float* h0, const float* maps, float* seg_state, int N, int H, int dk, int dv,
+                                  int G, hipStream_t st);
+hipError_t launch_segment_gather(const float* seg_state, float* hT, int N, int H, int dk, int dv, int G, int g_last,
+                                 hipStream_t st);
 
 hipError_t launch_chunk_offsets(const int* cu_seqlens, int n_seq, int* chunk_off, hipStream_t st);
 template <typename E>

@@ -153,3 +153,22 @@ def test_option_entry_points_validate_like_the_plain_ones():
     assert dec(16) == E_SHAPE
     assert dec(kla.KLA_OPT_GDN_BETA, S=None) == E_NULL
     assert dec(3, B=0) == OK
+
+
+def test_workspace_bytes_of_the_segmented_scan(monkeypatch):
+    """A long sequence in a small bf16 batch is scanned in segments: the workspace then also holds, per
+    (sequence, head), G-1 maps [N | M] and G incoming states in fp32."""
+    f = kla.lib().kla_chunk_fwd_workspace_bytes
+    monkeypatch.setenv("KLA_SCAN_SEGMENTS", "1")
+    base = f(1, 65536, 8, 128, 128, 64, kla.KLA_BF16, None, 0)
+    monkeypatch.setenv("KLA_SCAN_SEGMENTS", "4")
+    extra = 8 * 128 * (3 * (128 + 128) + 4 * 128) * 4
+    assert base + extra <= f(1, 65536, 8, 128, 128, 64, kla.KLA_BF16, None, 0) <= base + extra + 512
+    assert f(1, 65536, 8, 128, 128, 64, kla.KLA_F32, None, 0) == \
+        (monkeypatch.setenv("KLA_SCAN_SEGMENTS", "1"), f(1, 65536, 8, 128, 128, 64, kla.KLA_F32, None, 0))[1]   # bf16 only
+    monkeypatch.delenv("KLA_SCAN_SEGMENTS")
+    assert f(1, 65536, 8, 128, 128, 64, kla.KLA_BF16, None, 0) > base          # chosen automatically here
+    # a large batch is never segmented: same size with and without the knob at 1
+    big = f(8, 4096, 8, 128, 128, 64, kla.KLA_BF16, None, 0)
+    monkeypatch.setenv("KLA_SCAN_SEGMENTS", "1")
+    assert f(8, 4096, 8, 128, 128, 64, kla.KLA_BF16, None, 0) == big
