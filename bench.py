@@ -57,10 +57,11 @@ def _traffic(key):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--skip-cpu-baseline", action="store_true")
     ap.add_argument("--skip-decode", action="store_true")
+    ap.add_argument("--skip-extra", action="store_true", help="skip the two secondary chunk workloads (configs 3 and 5)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="only run a plain device copy of 1 GiB five times (reference for the rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -127,6 +128,30 @@ def main():
     mfma = {"achieved": round(tflops, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
             "frac": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4), "flop_per_token_head": CHUNK_FLOP_PER_TOKEN_HEAD,
             "whole_path_hbm_frac": round(alg_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+
+    # ------------------------------------------------------------------ secondary chunk workloads (not the headline)
+    extra = None
+    if not args.skip_extra:
+        extra = {}
+        for ci, name in ((3, "config3: N=1,H=8,T=65536,d=128 (one long sequence; segment-parallel scan)"),
+                         (5, "config5: 16 packed sequences of 512..4096 tokens,H=16,dk=128,dv=256,h0")):
+            e = kla_inputs.config(ci)
+            g = {n: e[n].cuda() for n in ("q", "k", "v", "log_alpha", "eta")}
+            cu = None if e["cu_seqlens"] is None else e["cu_seqlens"].cuda()
+            h0 = None if e["h0"] is None else e["h0"].cuda()
+            n_states = e["N"] if cu is None else cu.numel() - 1
+            w2 = torch.empty(kla.kla_chunk_fwd_workspace_bytes(e["N"], e["T"], e["H"], e["dk"], e["dv"], torch.bfloat16,
+                                                               cu_seqlens=cu), dtype=torch.uint8, device="cuda")
+            o2 = torch.empty((e["N"], e["T"], e["H"], e["dv"]), dtype=torch.bfloat16, device="cuda")
+            h2 = torch.empty((n_states, e["H"], e["dk"], e["dv"]), dtype=torch.float32, device="cuda")
+            fn = lambda: kla.kla_chunk_fwd(g["q"], g["k"], g["v"], g["log_alpha"], g["eta"], e["eps"], h0=h0,
+                                           cu_seqlens=cu, workspace=w2, out=o2, hT=h2)
+            for _ in range(3):
+                fn()
+            ms = _events(torch, fn, 10)
+            extra["config%d" % ci] = {"workload": name, "ms_per_call": round(ms, 4),
+                                      "tokens_per_s": round(e["N"] * e["T"] / (ms * 1e-3), 1)}
+            del g, w2, o2, h2
 
     # ------------------------------------------------------------------ decode, config 4
     decode = None
@@ -214,7 +239,7 @@ def main():
             "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
             "config": {"workload": "config2: N=8,H=8,T=4096,dk=dv=128,chunk=64,bf16 q/k/v,fp32 gates+state",
                        "global_batch": N, "seq_len": T, "heads": H},
-            "roofline": roofline, "mfma": mfma, "decode": decode, "cpu_baseline": cpu, "parity": parity}
+            "roofline": roofline, "mfma": mfma, "other_chunk_workloads": extra, "decode": decode, "cpu_baseline": cpu, "parity": parity}
     print(json.dumps(line), flush=True)
 
 

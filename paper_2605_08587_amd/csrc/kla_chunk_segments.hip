@@ -221,38 +221,37 @@ __global__ __launch_bounds__(192) void scan_maps_bf16_kernel(ScanArgs<bf16_t> a,
         }
 }
 
-// S_in(0) = h0 (or 0), S_in(g+1) = M_g S_in(g) + N_g.  One workgroup per (sequence, head, 32 state columns):
-// thread t owns row t/2 and 16 of the columns; the current S slice sits in LDS.
+// S_in(0) = h0 (or 0), S_in(g+1) = M_g S_in(g) + N_g, in fp32.  The G - 1 steps are serial, so the work of a step
+// is spread wide: one workgroup per (sequence, head, 8 state columns), thread t owns row t/2 and 4 of the
+// columns, reads its row of M_g with all loads in flight at once, and takes S_in(g) from LDS.
 template <int DK>
 __global__ __launch_bounds__(2 * DK) void segment_combine_kernel(const float* __restrict__ h0, const float* __restrict__ maps,
                                                                 float* __restrict__ seg_state, int H, int dv, int G)
 {
-    __shared__ __attribute__((aligned(16))) float Ss[DK][36];
-    const int nh = blockIdx.x, c0 = blockIdx.y * 32;     // nh = n H + h
+    typedef float f4 __attribute__((ext_vector_type(4)));
+    __shared__ __attribute__((aligned(16))) f4 Ss[DK][2];
+    const int nh = blockIdx.x, c0 = blockIdx.y * 8;      // nh = n H + h
     const int n = nh / H, h = nh % H;
-    const int row = threadIdx.x >> 1, cc = (threadIdx.x & 1) * 16;
-    float acc[16];
-#pragma unroll
-    for (int j = 0; j < 16; ++j) acc[j] = h0 ? h0[((size_t)nh * DK + row) * dv + c0 + cc + j] : 0.f;
+    const int row = threadIdx.x >> 1, half = threadIdx.x & 1;
+    const int col = c0 + 4 * half;
+    f4 acc = {0.f, 0.f, 0.f, 0.f};
+    if (h0) acc = *reinterpret_cast<const f4*>(h0 + ((size_t)nh * DK + row) * dv + col);
     for (int sg = 0; sg < G; ++sg) {
-        float* dst = seg_state + ((size_t)((n * G + sg) * H + h) * DK + row) * dv + c0 + cc;
-#pragma unroll
-        for (int j = 0; j < 16; ++j) { dst[j] = acc[j]; Ss[row][cc + j] = acc[j]; }
+        *reinterpret_cast<f4*>(seg_state + ((size_t)((n * G + sg) * H + h) * DK + row) * dv + col) = acc;
         if (sg + 1 == G) break;
-        __syncthreads();
         const float* mp = maps + (size_t)((n * (G - 1) + sg) * H + h) * DK * (dv + DK);
-        const float* Nrow = mp + (size_t)row * dv + c0 + cc;
-        const float* Mrow = mp + (size_t)DK * dv + (size_t)row * DK;
+        const f4* Mrow = reinterpret_cast<const f4*>(mp + (size_t)DK * dv + (size_t)row * DK);
+        f4 m[DK / 4];
 #pragma unroll
-        for (int j = 0; j < 16; ++j) acc[j] = Nrow[j];
-        for (int k = 0; k < DK; k += 4) {
-            const float4 m = *reinterpret_cast<const float4*>(Mrow + k);
-            const float mm[4] = {m.x, m.y, m.z, m.w};
+        for (int i = 0; i < DK / 4; ++i) m[i] = Mrow[i];
+        const f4 nn = *reinterpret_cast<const f4*>(mp + (size_t)row * dv + col);
+        Ss[row][half] = acc;
+        __syncthreads();
+        acc = nn;
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk)
+        for (int i = 0; i < DK / 4; ++i)
 #pragma unroll
-                for (int j = 0; j < 16; ++j) acc[j] += mm[kk] * Ss[k + kk][cc + j];
-        }
+            for (int kk = 0; kk < 4; ++kk) acc += m[i][kk] * Ss[4 * i + kk][half];
         __syncthreads();                                 // every thread has read Ss before it is overwritten
     }
 }
@@ -281,7 +280,7 @@ hipError_t launch_segment_maps_bf16(const ScanArgs<bf16_t>& a, int dk, float* ma
 hipError_t launch_segment_combine(const float* h0, const float* maps, float* seg_state, int N, int H, int dk, int dv,
                                   int G, hipStream_t st)
 {
-    const dim3 grid((unsigned)(N * H), (unsigned)(dv / 32));
+    const dim3 grid((unsigned)(N * H), (unsigned)(dv / 8));
     if (dk == 64) hipLaunchKernelGGL((segment_combine_kernel<64>), grid, dim3(128), 0, st, h0, maps, seg_state, H, dv, G);
     else          hipLaunchKernelGGL((segment_combine_kernel<128>), grid, dim3(256), 0, st, h0, maps, seg_state, H, dv, G);
     return hipGetLastError();
