@@ -8,8 +8,8 @@
  *     e_t  = v_t - S~^T k_t
  *     beta = eta_t / (||k_t||^2 + eps)            (beta := 0 when the denominator is 0)
  *     S_t  = S~ + beta k_t e_t^T
- *     o_t  = S_t^T q_t                            (no query normalisation: the caller
- *                                                  normalises q if it wants Sec. 3.3's read-out)
+ *     o_t  = S_t^T q_t                            (no query normalisation in the plain entry points;
+ *                                                  the *_opts ones offer Sec. 3.3's o_t / ||q_t||)
  *
  * with the state S a d_k x d_v matrix (Sec. 2), stored row-major with d_v
  * contiguous, always fp32.  The same map written for R = S^T is eq. (5).
@@ -56,7 +56,9 @@ typedef enum {
 const char *kla_status_string(int code);
 
 /*
- * Bytes of device scratch kla_chunk_fwd needs for these sizes (0 on invalid sizes).
+ * Bytes of device scratch kla_chunk_fwd needs for these sizes (0 on invalid sizes).  It covers the per-chunk
+ * objects of eqs. (6)-(7) and, for a small bf16 batch of long sequences, the per-segment state maps of the
+ * segment-parallel scan; ask again whenever a size, the element type or a tuning variable changes.
  * For a packed batch pass the host copy of cu_seqlens and n_seq > 0 (then N must be 1
  * and T the total token count); otherwise cu_seqlens_host = NULL, n_seq = 0.
  */
