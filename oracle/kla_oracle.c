@@ -35,6 +35,13 @@
  * search, pure decay at eta = 0, brute-force product form of Table 5, textbook
  * Kaczmarz limits checked against numpy's pseudo-inverse, a hand-worked
  * rational example under tests/golden/).
+ *
+ * Gradients (kla_oracle_sequence_bwd): the paper states the forward map only and
+ * mentions training without deriving a backward pass, so the gradient oracle is
+ * the plain reverse accumulation through the same five lines of Algorithm 1
+ * (left), token by token from the last to the first, including the dependence of
+ * beta on k through eq. (3).  Its pins are central finite differences of the
+ * forward oracle above and closed forms for a single step and for eta = 0.
  */
 #include <math.h>
 #include <stdlib.h>
@@ -151,4 +158,142 @@ int kla_oracle_decode_unit(const float *q, const float *k, const float *v,
                            double *S, double *o, int dk, int dv)
 {
     return kla_oracle_decode_unit_opts(q, k, v, log_alpha, eta, eps, S, o, dk, dv, 0, 0);
+}
+
+/* Forward lines 1-4 of Algorithm 1 (left) for one token, out of place: Snew = alpha S + beta k e^T.
+ * Returns beta and 1/(||k||^2 + eps) (0 if the denominator is 0); St gets the decayed state alpha S, e the residual;
+ * Snew may be NULL when only those are wanted. */
+static double kla_token_state(const double *S, const float *k, const float *v, double log_alpha, double eta,
+                              double eps, int dk, int dv, double *St, double *e, double *Snew, double *inv_den)
+{
+    int i, j;
+    const double alpha = exp(log_alpha);
+    for (i = 0; i < dk * dv; ++i) St[i] = alpha * S[i];
+    for (j = 0; j < dv; ++j) {
+        double p = 0.0;
+        for (i = 0; i < dk; ++i) p += St[(size_t)i * dv + j] * (double)k[i];
+        e[j] = (double)v[j] - p;
+    }
+    double nk = 0.0;
+    for (i = 0; i < dk; ++i) nk += (double)k[i] * (double)k[i];
+    const double den = nk + eps;
+    *inv_den = (den == 0.0) ? 0.0 : 1.0 / den;
+    const double beta = eta * *inv_den;
+    if (Snew)
+        for (i = 0; i < dk; ++i)
+            for (j = 0; j < dv; ++j)
+                Snew[(size_t)i * dv + j] = St[(size_t)i * dv + j] + beta * (double)k[i] * e[j];
+    return beta;
+}
+
+/*
+ * Gradient of  L = sum_t <d_o[t], o_t> + <d_hT, h_T>  for one (sequence, head) unit of
+ * kla_oracle_sequence (no options), by reverse accumulation through Algorithm 1 (left).
+ *   d_o               [n_tokens_total, H, dv] double
+ *   d_hT              [dk, dv] double for this unit, or NULL for zeros
+ *   dq, dk_           [n_tokens_total, H, dk] double (only this unit's rows written)
+ *   dv_               [n_tokens_total, H, dv] double
+ *   dlog_alpha, deta  [n_tokens_total, H]     double
+ *   dh0               [dk, dv] double for this unit (out), may be NULL
+ * The states are recomputed from checkpoints kept every 64 tokens, so memory stays at
+ * (len/64 + 65) states.  Returns 0, or -1 if memory could not be allocated.
+ */
+int kla_oracle_sequence_bwd(const float *q, const float *k, const float *v,
+                            const double *log_alpha, const double *eta, double eps,
+                            const double *h0, const double *d_o, const double *d_hT,
+                            double *dq, double *dk_, double *dv_, double *dlog_alpha, double *deta,
+                            double *dh0, long t0, long len, int h, int H, int dk, int dv)
+{
+    enum { SEG = 64 };
+    const size_t sz = (size_t)dk * dv;
+    const long nseg = (len + SEG - 1) / SEG;
+    double *chk = (double *)malloc(sizeof(double) * sz * (size_t)(nseg + 1));
+    double *st = (double *)malloc(sizeof(double) * sz * (SEG + 1));
+    double *St = (double *)malloc(sizeof(double) * sz);
+    double *dS = (double *)malloc(sizeof(double) * sz);
+    double *e = (double *)malloc(sizeof(double) * (size_t)dv);
+    double *de = (double *)malloc(sizeof(double) * (size_t)dv);
+    if (!chk || !st || !St || !dS || !e || !de) { free(chk); free(st); free(St); free(dS); free(e); free(de); return -1; }
+    int i, j;
+    double inv_den;
+
+    /* forward sweep: the state at every segment start */
+    if (h0) memcpy(chk, h0, sizeof(double) * sz);
+    else    memset(chk, 0, sizeof(double) * sz);
+    for (long sg = 0; sg < nseg; ++sg) {
+        memcpy(st, chk + sz * (size_t)sg, sizeof(double) * sz);
+        const long a = t0 + sg * SEG, b = (a + SEG < t0 + len) ? a + SEG : t0 + len;
+        for (long t = a; t < b; ++t) {
+            const size_t th = (size_t)t * H + h;
+            kla_token_state(st, k + th * dk, v + th * dv, log_alpha[th], eta[th], eps, dk, dv, St, e, st + sz, &inv_den);
+            memcpy(st, st + sz, sizeof(double) * sz);
+        }
+        memcpy(chk + sz * (size_t)(sg + 1), st, sizeof(double) * sz);
+    }
+
+    /* reverse sweep */
+    if (d_hT) memcpy(dS, d_hT, sizeof(double) * sz);
+    else      memset(dS, 0, sizeof(double) * sz);
+    for (long sg = nseg - 1; sg >= 0; --sg) {
+        const long a = t0 + sg * SEG, b = (a + SEG < t0 + len) ? a + SEG : t0 + len;
+        /* st[i] = state before token a + i, st[i + 1] = state after it */
+        memcpy(st, chk + sz * (size_t)sg, sizeof(double) * sz);
+        for (long t = a; t < b; ++t) {
+            const size_t th = (size_t)t * H + h;
+            kla_token_state(st + sz * (size_t)(t - a), k + th * dk, v + th * dv, log_alpha[th], eta[th], eps, dk, dv,
+                            St, e, st + sz * (size_t)(t - a + 1), &inv_den);
+        }
+        for (long t = b - 1; t >= a; --t) {
+            const size_t th = (size_t)t * H + h;
+            const float *qt = q + th * dk, *kt = k + th * dk, *vt = v + th * dv;
+            const double *go = d_o + th * dv;
+            const double *Sprev = st + sz * (size_t)(t - a), *Scur = st + sz * (size_t)(t - a + 1);
+            double *gq = dq + th * dk, *gk = dk_ + th * dk, *gv = dv_ + th * dv;
+            /* line 5: o = S^T q */
+            for (i = 0; i < dk; ++i) {
+                double acc = 0.0;
+                for (j = 0; j < dv; ++j) {
+                    acc += Scur[(size_t)i * dv + j] * go[j];
+                    dS[(size_t)i * dv + j] += (double)qt[i] * go[j];
+                }
+                gq[i] = acc;
+            }
+            /* the forward quantities of this token again: decayed state, residual, beta */
+            const double beta = kla_token_state(Sprev, kt, vt, log_alpha[th], eta[th], eps, dk, dv, St, e, NULL, &inv_den);
+            /* line 4: S = S~ + beta k e^T */
+            double dbeta = 0.0;
+            for (j = 0; j < dv; ++j) de[j] = 0.0;
+            for (i = 0; i < dk; ++i) {
+                double acc = 0.0;
+                for (j = 0; j < dv; ++j) {
+                    acc += dS[(size_t)i * dv + j] * e[j];
+                    de[j] += dS[(size_t)i * dv + j] * (double)kt[i];
+                }
+                dbeta += (double)kt[i] * acc;
+                gk[i] = beta * acc;
+            }
+            for (j = 0; j < dv; ++j) de[j] *= beta;
+            /* line 2: e = v - S~^T k   (dS becomes the gradient of the decayed state) */
+            for (j = 0; j < dv; ++j) gv[j] = de[j];
+            for (i = 0; i < dk; ++i) {
+                double acc = 0.0;
+                for (j = 0; j < dv; ++j) {
+                    acc += St[(size_t)i * dv + j] * de[j];
+                    dS[(size_t)i * dv + j] -= (double)kt[i] * de[j];
+                }
+                gk[i] -= acc;
+            }
+            /* line 3 / eq. (3): beta = eta / (||k||^2 + eps) */
+            deta[th] = dbeta * inv_den;
+            for (i = 0; i < dk; ++i) gk[i] -= 2.0 * beta * dbeta * inv_den * (double)kt[i];
+            /* line 1: S~ = alpha S, alpha = exp(log_alpha) */
+            double dla = 0.0;
+            const double alpha = exp(log_alpha[th]);
+            for (i = 0; i < dk * dv; ++i) { dla += dS[i] * St[i]; dS[i] *= alpha; }
+            dlog_alpha[th] = dla;
+        }
+    }
+    if (dh0) memcpy(dh0, dS, sizeof(double) * sz);
+    free(chk); free(st); free(St); free(dS); free(e); free(de);
+    return 0;
 }

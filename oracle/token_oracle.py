@@ -53,6 +53,11 @@ def _load():
                                                    ctypes.c_double, dp, dp, ctypes.c_int, ctypes.c_int]
             lib.kla_oracle_decode_unit_opts.restype = ctypes.c_int
             lib.kla_oracle_decode_unit_opts.argtypes = lib.kla_oracle_decode_unit.argtypes + [ctypes.c_int, ctypes.c_int]
+            lib.kla_oracle_sequence_bwd.restype = ctypes.c_int
+            lib.kla_oracle_sequence_bwd.argtypes = [fp, fp, fp, dp, dp, ctypes.c_double, dp, dp, dp,
+                                                    dp, dp, dp, dp, dp, dp,
+                                                    ctypes.c_long, ctypes.c_long, ctypes.c_int,
+                                                    ctypes.c_int, ctypes.c_int, ctypes.c_int]
             _lib = lib
     return _lib
 
@@ -125,6 +130,54 @@ def kla_recurrent(q, k, v, log_alpha, eta, eps, h0=None, cu_seqlens=None, thread
         with ThreadPoolExecutor(nthr) as ex:
             list(ex.map(run, todo))
     return o, hT, nthr
+
+
+def kla_recurrent_bwd(q, k, v, log_alpha, eta, eps, d_o, h0=None, d_hT=None, cu_seqlens=None, threads=None):
+    """Gradient of L = sum <d_o, o> + sum <d_hT, hT> of kla_recurrent (no options) with respect to its inputs.
+
+    Shapes as in kla_recurrent; d_o: [N, T, H, dv]; d_hT: [n_seq, H, dk, dv] or None (zeros).
+    Returns a dict with dq, dk, dv, dlog_alpha, deta, dh0 (float64, shapes of the corresponding inputs).
+    """
+    lib = _load()
+    q, k, v = _f32(q), _f32(k), _f32(v)
+    la, et, go = _f64(log_alpha), _f64(eta), _f64(d_o)
+    N, T, H, dk = q.shape
+    dv = v.shape[-1]
+    if cu_seqlens is None:
+        starts = [n * T for n in range(N)]
+        lens = [T] * N
+    else:
+        assert N == 1
+        cu = [int(x) for x in cu_seqlens]
+        starts = cu[:-1]
+        lens = [cu[i + 1] - cu[i] for i in range(len(cu) - 1)]
+    n_seq = len(starts)
+    h0d = None if h0 is None else _f64(h0)
+    ghT = None if d_hT is None else _f64(d_hT)
+    out = {"dq": np.zeros((N, T, H, dk)), "dk": np.zeros((N, T, H, dk)), "dv": np.zeros((N, T, H, dv)),
+           "dlog_alpha": np.zeros((N, T, H)), "deta": np.zeros((N, T, H)), "dh0": np.zeros((n_seq, H, dk, dv))}
+    todo = [(s, h) for s in range(n_seq) for h in range(H)]
+
+    def run(unit):
+        s, h = unit
+        off = (s * H + h) * dk * dv
+        rc = lib.kla_oracle_sequence_bwd(_fp(q), _fp(k), _fp(v), _dp(la), _dp(et), float(eps),
+                                         None if h0d is None else _dp(h0d, off), _dp(go),
+                                         None if ghT is None else _dp(ghT, off),
+                                         _dp(out["dq"]), _dp(out["dk"]), _dp(out["dv"]), _dp(out["dlog_alpha"]),
+                                         _dp(out["deta"]), _dp(out["dh0"], off),
+                                         starts[s], lens[s], h, H, dk, dv)
+        if rc != 0:
+            raise MemoryError("oracle scratch allocation failed")
+
+    nthr = max(1, min(threads or default_threads(), len(todo))) if todo else 1
+    if nthr == 1:
+        for u in todo:
+            run(u)
+    else:
+        with ThreadPoolExecutor(nthr) as ex:
+            list(ex.map(run, todo))
+    return out
 
 
 def kla_decode(q, k, v, log_alpha, eta, eps, S, threads=None, normalize_q=False, gdn_beta=False):

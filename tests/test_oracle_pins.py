@@ -359,3 +359,111 @@ def test_option_normalize_q():
                                            normalize_q=True, gdn_beta=True)
     np.testing.assert_allclose(od, og[:, 0], rtol=1e-14, atol=0)
     np.testing.assert_allclose(Sd, hg, rtol=1e-14, atol=0)
+
+
+# ---- gradient oracle (reverse accumulation through Algorithm 1, left panel) ----------------------
+def _loss(q, k, v, la, eta, eps, S0, go, ghT):
+    o, hT, _ = token_oracle.kla_recurrent(q, k, v, la, eta, eps, h0=S0, threads=1)
+    return float(np.sum(o * go) + np.sum(hT * ghT))
+
+
+def test_gradient_central_differences():
+    """The gradient oracle against central finite differences of the (separately pinned) forward oracle.
+
+    q, k, v sit on a 2^-6 grid and move by 2^-9, so the perturbed fp32 inputs are exact; the sequence spans two
+    of the gradient oracle's 64-token checkpoint segments plus a ragged tail, with non-zero h0 and d_hT."""
+    rng = RNG(41)
+    T, H, dk, dv, eps = 133, 2, 4, 3, 1e-3
+    q, k, v, la, eta, S0 = _rand_problem(rng, T, H, dk, dv)
+    q, k, v = (np.round(x * 64) / 64 for x in (q, k, v))
+    q, k, v = q.astype(np.float32), k.astype(np.float32), v.astype(np.float32)
+    la = la * 0.2                                             # slow decay: early tokens still reach the loss
+    go = rng.standard_normal((1, T, H, dv))
+    ghT = rng.standard_normal((1, H, dk, dv))
+    g = token_oracle.kla_recurrent_bwd(q, k, v, la, eta, eps, go, h0=S0, d_hT=ghT)
+    args = {"q": q, "k": k, "v": v, "la": la, "eta": eta, "S0": S0}
+    names = {"q": "dq", "k": "dk", "v": "dv", "la": "dlog_alpha", "eta": "deta", "S0": "dh0"}
+    for name, arr in args.items():
+        h = 2.0 ** -9 if arr.dtype == np.float32 else 1e-5
+        flat_idx = rng.choice(arr.size, size=10, replace=False)
+        flat_idx[0] = 0                                       # always include the first token
+        scale = np.max(np.abs(g[names[name]]))
+        for fi in flat_idx:
+            idx = np.unravel_index(fi, arr.shape)
+            plus, minus = arr.copy(), arr.copy()
+            plus[idx] += h
+            minus[idx] -= h
+            a_p = dict(args); a_p[name] = plus
+            a_m = dict(args); a_m[name] = minus
+            fd = (_loss(a_p["q"], a_p["k"], a_p["v"], a_p["la"], a_p["eta"], eps, a_p["S0"], go, ghT)
+                  - _loss(a_m["q"], a_m["k"], a_m["v"], a_m["la"], a_m["eta"], eps, a_m["S0"], go, ghT)) / (2 * h)
+            assert abs(fd - g[names[name]][idx]) <= 2e-5 * scale + 1e-8, (name, idx, fd, g[names[name]][idx])
+
+
+def test_gradient_single_step_closed_form():
+    """One token: o = S_1^T q with S_1 = alpha (I - beta k k^T) h0 + beta k v^T (eq. (5) transposed), so
+    L = q^T S_1 d_o is an explicit polynomial in the inputs; its partial derivatives are written out here."""
+    rng = RNG(42)
+    dk, dv, eps = 5, 4, 0.37
+    q, k, v, la, eta, S0 = _rand_problem(rng, 1, 1, dk, dv)
+    go = rng.standard_normal((1, 1, 1, dv))
+    g = token_oracle.kla_recurrent_bwd(q, k, v, la, eta, eps, go, h0=S0)
+    qq, kk, vv, d = (x[0, 0, 0].astype(np.float64) for x in (q, k, v, go))
+    al, et, h0 = float(np.exp(la[0, 0, 0])), float(eta[0, 0, 0]), S0[0, 0]
+    den = kk @ kk + eps
+    beta = et / den
+    qk, hd = qq @ kk, h0 @ d                                  # h0 d is a d_k vector
+    # L = alpha q.(h0 d) - alpha beta (q.k)(k.(h0 d)) + beta (q.k)(v.d)
+    bracket = -al * qk * (kk @ hd) + qk * (vv @ d)            # dL/dbeta
+    S1 = al * (h0 - beta * np.outer(kk, kk @ h0)) + beta * np.outer(kk, vv)
+    np.testing.assert_allclose(g["dq"][0, 0, 0], S1 @ d, rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(g["dv"][0, 0, 0], beta * qk * d, rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(g["deta"][0, 0, 0], bracket / den, rtol=1e-12)
+    np.testing.assert_allclose(g["dlog_alpha"][0, 0, 0], al * (qq @ hd - beta * qk * (kk @ hd)), rtol=1e-12)
+    dk_expect = (-al * beta * (qq * (kk @ hd) + qk * hd) + beta * qq * (vv @ d)
+                 - 2.0 * beta / den * bracket * kk)
+    np.testing.assert_allclose(g["dk"][0, 0, 0], dk_expect, rtol=1e-11, atol=1e-13)
+    np.testing.assert_allclose(g["dh0"][0, 0], al * (np.outer(qq, d) - beta * qk * np.outer(kk, d)), rtol=1e-12, atol=1e-14)
+
+
+def test_gradient_eta_zero_closed_form():
+    """eta = 0: S_t = Gamma_t h0 (Gamma_t the decay product), so dq_t = Gamma_t h0 d_o_t, dh0 = sum_t Gamma_t q_t d_o_t^T
+    + Gamma_T d_hT, dlog_alpha_r = sum_{t>=r} Gamma_t q_t^T h0 d_o_t + Gamma_T <d_hT, h0>, and dk = dv = 0 because
+    the write vanishes together with the derivative of beta with respect to k."""
+    rng = RNG(43)
+    T, H, dk, dv = 90, 2, 6, 5
+    q, k, v, la, eta, S0 = _rand_problem(rng, T, H, dk, dv, N=2)
+    go = rng.standard_normal((2, T, H, dv))
+    ghT = rng.standard_normal((2, H, dk, dv))
+    g = token_oracle.kla_recurrent_bwd(q, k, v, la, np.zeros_like(eta), 1e-6, go, h0=S0, d_hT=ghT)
+    cum = np.exp(np.cumsum(la, axis=1))
+    q64 = q.astype(np.float64)
+    np.testing.assert_allclose(g["dq"], cum[..., None] * np.einsum("nhkv,nthv->nthk", S0, go), rtol=1e-10, atol=1e-12)
+    dh0 = np.einsum("nth,nthk,nthv->nhkv", cum, q64, go) + cum[:, -1][..., None, None] * ghT
+    np.testing.assert_allclose(g["dh0"], dh0, rtol=1e-10, atol=1e-12)
+    per_t = cum * np.einsum("nthk,nhkv,nthv->nth", q64, S0, go)
+    tail = np.flip(np.cumsum(np.flip(per_t, axis=1), axis=1), axis=1)
+    dla = tail + (cum[:, -1] * np.einsum("nhkv,nhkv->nh", ghT, S0))[:, None, :]
+    np.testing.assert_allclose(g["dlog_alpha"], dla, rtol=1e-9, atol=1e-11)
+    assert np.max(np.abs(g["dk"])) == 0.0 and np.max(np.abs(g["dv"])) == 0.0
+    assert np.max(np.abs(g["deta"])) > 0.0                    # d beta / d eta = 1/(||k||^2+eps) is not zero
+
+
+def test_gradient_packed_equals_separate():
+    """Sequences of a packed batch are independent: gradients equal those of each sequence run alone."""
+    rng = RNG(44)
+    lens = [70, 1, 129]
+    cu = np.concatenate([[0], np.cumsum(lens)])
+    T, H, dk, dv = int(cu[-1]), 2, 4, 4
+    q, k, v, la, eta, _ = _rand_problem(rng, T, H, dk, dv, h0=False)
+    S0 = rng.standard_normal((3, H, dk, dv))
+    go = rng.standard_normal((1, T, H, dv))
+    ghT = rng.standard_normal((3, H, dk, dv))
+    g = token_oracle.kla_recurrent_bwd(q, k, v, la, eta, 1e-4, go, h0=S0, d_hT=ghT, cu_seqlens=cu)
+    for s in range(3):
+        a, b = int(cu[s]), int(cu[s + 1])
+        gs = token_oracle.kla_recurrent_bwd(q[:, a:b], k[:, a:b], v[:, a:b], la[:, a:b], eta[:, a:b], 1e-4, go[:, a:b],
+                                            h0=S0[s:s + 1], d_hT=ghT[s:s + 1])
+        for name in ("dq", "dk", "dv", "dlog_alpha", "deta"):
+            np.testing.assert_array_equal(g[name][:, a:b], gs[name])
+        np.testing.assert_array_equal(g["dh0"][s], gs["dh0"][0])
