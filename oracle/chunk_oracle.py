@@ -104,3 +104,76 @@ def kla_chunkwise(q, k, v, log_alpha, eta, eps, h0=None, cu_seqlens=None, chunk=
             o[n, a:b, h] = oo
             hT[s, h] = ss
     return o, hT
+
+
+def kla_chunkwise_bwd_unit(q, k, v, log_alpha, eta, eps, d_o, h0=None, d_hT=None, chunk=64, want=False):
+    """Gradient of L = <d_o, o> + <d_hT, hT> for one (sequence, head), chunk by chunk.
+
+    The paper gives no backward pass; this is eqs. (6)-(8) differentiated by hand, written per chunk with
+    M = (I + L)^-1, X = V - D_gamma K S_in, U = M B X and the outgoing-state gradient dS':
+        dU   = P^T dO + diag(gamma_C/gamma_i) K dS'          Y = M^T dU        dX = B Y   (= dV)
+        dS_in = gamma_C dS' + Q^T D_gamma dO - K^T D_gamma dX
+        dP   = tril(dO U^T)        dL = -tril(Y U^T, -1)        dbeta_i = Y_i.X_i + sum_j dL_ij A_ij (K K^T)_ij
+        dQ   = D_gamma dO S_in^T + (A o dP) K
+        dK   = -D_gamma dX S_in^T + diag(gamma_C/gamma_i) U dS'^T + (A o dP)^T Q + (D + D^T) K - 2 beta dbeta/(|k|^2+eps) k
+               with D_ij = beta_i A_ij dL_ij
+        dg_i = [every place g_i enters: D_gamma in X and O, A in P and L, gamma_C and gamma_C/gamma_i in eq. (8)]
+        dlog_alpha_r = sum_{i >= r in the chunk} dg_i,     deta_i = dbeta_i / (|k_i|^2 + eps)
+    It is pinned against the token-by-token gradient oracle in tests/test_oracle_pins.py.
+    Returns a dict (dq, dk, dv, dlog_alpha, deta, dh0) and, if want, the per-chunk intermediates.
+    """
+    q = np.asarray(q, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    la = np.asarray(log_alpha, dtype=np.float64)
+    et = np.asarray(eta, dtype=np.float64)
+    go = np.asarray(d_o, dtype=np.float64)
+    T_len, dk = k.shape
+    dv = v.shape[1]
+    _, _, inter = kla_chunkwise_unit(q, k, v, la, et, eps, h0, chunk, want=True)
+    dS = np.zeros((dk, dv)) if d_hT is None else np.array(d_hT, dtype=np.float64)
+    out = dict(dq=np.zeros((T_len, dk)), dk=np.zeros((T_len, dk)), dv=np.zeros((T_len, dv)),
+               dlog_alpha=np.zeros(T_len), deta=np.zeros(T_len))
+    keep = []
+    starts = list(range(0, T_len, chunk))
+    for ci in reversed(range(len(starts))):
+        c0 = starts[ci]
+        c1 = min(T_len, c0 + chunk)
+        K, V, Q, dO = k[c0:c1], v[c0:c1], q[c0:c1], go[c0:c1]
+        it = inter[ci]
+        beta, g, M, P, U, S_in = it["beta"], it["g"], it["T"], it["P"], it["U"], it["S_in"]
+        c = c1 - c0
+        gam = np.exp(g)
+        tail = np.exp(g[-1] - g)
+        lower = np.tril(np.ones((c, c), dtype=bool))
+        A = np.where(lower, np.exp(np.where(lower, g[:, None] - g[None, :], 0.0)), 0.0)
+        G = K @ K.T
+        X = V - gam[:, None] * (K @ S_in)
+        dU = P.T @ dO + tail[:, None] * (K @ dS)
+        Y = M.T @ dU
+        dX = beta[:, None] * Y
+        dP = np.tril(dO @ U.T)
+        dL = -np.tril(Y @ U.T, -1)
+        dbeta = np.sum(Y * X, axis=1) + np.sum(dL * A * G, axis=1)
+        D = beta[:, None] * A * dL
+        den = np.sum(K * K, axis=1) + eps
+        inv_den = np.where(den == 0.0, 0.0, 1.0 / np.where(den == 0.0, 1.0, den))
+        dQ = gam[:, None] * (dO @ S_in.T) + (A * dP) @ K
+        dK_read = -gam[:, None] * (dX @ S_in.T) + D @ K                    # k_i acting with gamma_i (rows of L, of X)
+        dK_write = tail[:, None] * (U @ dS.T) + (A * dP).T @ Q + D.T @ K   # k_j acting with 1/gamma_j
+        dK = dK_read + dK_write - (2.0 * beta * dbeta * inv_den)[:, None] * K
+        # g_i multiplies q_i and the reading k_i, and divides the writing k_i; g_C enters eq. (8) twice more
+        dg = np.sum(dQ * Q, axis=1) + np.sum(dK_read * K, axis=1) - np.sum(dK_write * K, axis=1)
+        dg[-1] += gam[-1] * np.sum(dS * S_in) + np.sum((tail[:, None] * (U @ dS.T)) * K)
+        out["dq"][c0:c1] = dQ
+        out["dk"][c0:c1] = dK
+        out["dv"][c0:c1] = dX
+        out["deta"][c0:c1] = dbeta * inv_den
+        out["dlog_alpha"][c0:c1] = np.cumsum(dg[::-1])[::-1]
+        if want:
+            keep.append(dict(dS_out=dS.copy(), dU=dU, Y=Y, X=X, dP=dP, dL=dL, dbeta=dbeta, dg=dg))
+        dS = gam[-1] * dS + Q.T @ (gam[:, None] * dO) - K.T @ (gam[:, None] * dX)
+    out["dh0"] = dS
+    if want:
+        return out, keep[::-1]
+    return out

@@ -467,3 +467,22 @@ def test_gradient_packed_equals_separate():
         for name in ("dq", "dk", "dv", "dlog_alpha", "deta"):
             np.testing.assert_array_equal(g[name][:, a:b], gs[name])
         np.testing.assert_array_equal(g["dh0"][s], gs["dh0"][0])
+
+
+@pytest.mark.parametrize("C", [1, 16, 64])
+def test_chunkwise_gradient_equals_recurrent(C):
+    """Eqs. (6)-(8) differentiated chunk by chunk give the gradient of the tokenwise recurrence (two independent
+    routes: numpy chunk algebra vs the C reverse accumulation), for several chunk sizes and a ragged tail."""
+    rng = RNG(45)
+    T, H, dk, dv, eps = 150, 1, 6, 5, 1e-3
+    q, k, v, la, eta, S0 = _rand_problem(rng, T, H, dk, dv)
+    la = la * 0.3
+    go = rng.standard_normal((1, T, H, dv))
+    ghT = rng.standard_normal((1, H, dk, dv))
+    ref = token_oracle.kla_recurrent_bwd(q, k, v, la, eta, eps, go, h0=S0, d_hT=ghT)
+    got = chunk_oracle.kla_chunkwise_bwd_unit(q[0, :, 0], k[0, :, 0], v[0, :, 0], la[0, :, 0], eta[0, :, 0], eps,
+                                              go[0, :, 0], h0=S0[0, 0], d_hT=ghT[0, 0], chunk=C)
+    for name in ("dq", "dk", "dv", "dlog_alpha", "deta"):
+        r = ref[name][0, :, 0]
+        assert np.max(np.abs(got[name] - r)) <= 1e-9 * np.max(np.abs(r)), name
+    assert np.max(np.abs(got["dh0"] - ref["dh0"][0, 0])) <= 1e-9 * np.max(np.abs(ref["dh0"]))
