@@ -134,6 +134,40 @@ int kla_decode_step_opts(const void *q, const void *k, const void *v,
                          int B, int H, int dk, int dv, kla_dtype dt, void *hip_stream, unsigned opts);
 
 /*
+ * Backward pass of kla_chunk_fwd (no options): gradients of
+ *     L = sum_t <d_o_t, o_t> + sum <d_hT, hT>
+ * with respect to q, k, v, log_alpha, eta and h0.  The paper trains with this operator but states
+ * only its forward map (Algorithm 1; eqs. (3), (6)-(8)); the gradients are those equations
+ * differentiated chunk by chunk, including the dependence of beta_t on k_t through eq. (3)
+ * (d beta / d k = -2 eta k / (||k||^2 + eps)^2), which the delta rule with beta = eta does not have.
+ * The forward quantities are recomputed, not saved: only the inputs of the forward call are needed.
+ *
+ *   q, k, v, log_alpha, eta, eps, h0, cu_seqlens_*, n_seq, N, T, H, dk, dv, chunk, dt: as in kla_chunk_fwd
+ *   d_o         [N, T, H, dv]  dt                in   gradient of the outputs
+ *   d_hT        [n_states, H, dk, dv] fp32       in   gradient of the final states, or NULL for zeros
+ *   dq, dk_     [N, T, H, dk]  dt                out
+ *   dv_         [N, T, H, dv]  dt                out
+ *   dlog_alpha, deta  [N, T, H] fp32             out
+ *   dh0         [n_states, H, dk, dv] fp32       out  or NULL if unwanted
+ *   workspace   device scratch of at least kla_chunk_bwd_workspace_bytes(...) bytes, 256-byte aligned.
+ *               It holds, per chunk and head, the incoming state and the gradient of the outgoing state
+ *               (fp32, dk x dv each) and three [N, T, H, dv] arrays in dt, so it is much larger than the
+ *               forward's: about 2 * 4 * dk * dv / 64 + 3 * dv * sizeof(dt) bytes per token and head.
+ * Outputs must not alias inputs or each other.  Same error codes and conventions as kla_chunk_fwd;
+ * rows of the outputs are written for every token of every sequence, nothing else is touched.
+ * The result is deterministic (no atomics).
+ */
+size_t kla_chunk_bwd_workspace_bytes(int N, int T, int H, int dk, int dv, int chunk, kla_dtype dt,
+                                     const int32_t *cu_seqlens_host, int n_seq);
+int kla_chunk_bwd(const void *q, const void *k, const void *v,
+                  const float *log_alpha, const float *eta, float eps,
+                  const float *h0, const void *d_o, const float *d_hT,
+                  void *dq, void *dk_, void *dv_, float *dlog_alpha, float *deta, float *dh0,
+                  const int32_t *cu_seqlens_dev, const int32_t *cu_seqlens_host, int n_seq,
+                  int N, int T, int H, int dk, int dv, int chunk, kla_dtype dt,
+                  void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * The Kaczmarz coefficient alone (eq. (3)): beta[i] = eta[i] / (||k_i||^2 + eps), 0 when the
  * denominator is 0, for n_token_heads rows of dk elements.
  *   k [n_token_heads, dk] dt in;  eta [n_token_heads] fp32 in;  beta [n_token_heads] fp32 out.

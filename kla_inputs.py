@@ -87,3 +87,12 @@ def config(i: int):
 def to_numpy_f32(t):
     """Exact widening of a bf16/fp32 torch tensor to a float32 numpy array."""
     return t.detach().to("cpu").to(torch.float32).contiguous().numpy()
+
+
+def grad_inputs(d, seed=0, d_hT=True):
+    """Upstream gradients for a chunk-forward input set d: d_o ~ N(0,1) in the dtype of v, d_hT ~ N(0,1) fp32."""
+    gen = torch.Generator().manual_seed(10_000 + seed)
+    d_o = torch.randn(tuple(d["v"].shape), generator=gen, dtype=torch.float32).to(d["dtype"])
+    n_states = d["N"] if d["cu_seqlens"] is None else d["cu_seqlens"].numel() - 1
+    g = torch.randn((n_states, d["H"], d["dk"], d["dv"]), generator=gen, dtype=torch.float32) if d_hT else None
+    return d_o, g

@@ -132,10 +132,12 @@ def kla_recurrent(q, k, v, log_alpha, eta, eps, h0=None, cu_seqlens=None, thread
     return o, hT, nthr
 
 
-def kla_recurrent_bwd(q, k, v, log_alpha, eta, eps, d_o, h0=None, d_hT=None, cu_seqlens=None, threads=None):
+def kla_recurrent_bwd(q, k, v, log_alpha, eta, eps, d_o, h0=None, d_hT=None, cu_seqlens=None, threads=None,
+                      units=None):
     """Gradient of L = sum <d_o, o> + sum <d_hT, hT> of kla_recurrent (no options) with respect to its inputs.
 
     Shapes as in kla_recurrent; d_o: [N, T, H, dv]; d_hT: [n_seq, H, dk, dv] or None (zeros).
+    `units`, if given, restricts the work to those (sequence, head) pairs; other rows stay zero.
     Returns a dict with dq, dk, dv, dlog_alpha, deta, dh0 (float64, shapes of the corresponding inputs).
     """
     lib = _load()
@@ -156,7 +158,7 @@ def kla_recurrent_bwd(q, k, v, log_alpha, eta, eps, d_o, h0=None, d_hT=None, cu_
     ghT = None if d_hT is None else _f64(d_hT)
     out = {"dq": np.zeros((N, T, H, dk)), "dk": np.zeros((N, T, H, dk)), "dv": np.zeros((N, T, H, dv)),
            "dlog_alpha": np.zeros((N, T, H)), "deta": np.zeros((N, T, H)), "dh0": np.zeros((n_seq, H, dk, dv))}
-    todo = [(s, h) for s in range(n_seq) for h in range(H)]
+    todo = [(s, h) for s in range(n_seq) for h in range(H)] if units is None else list(units)
 
     def run(unit):
         s, h = unit

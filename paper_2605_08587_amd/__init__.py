@@ -29,6 +29,9 @@ _SIGNATURES = {
                       + [ctypes.c_int] * 6 + [ctypes.c_int, _vp, ctypes.c_size_t, _vp]),
     "kla_chunk_fwd_opts": (ctypes.c_int, [_vp, _vp, _vp, _fp, _fp, ctypes.c_float, _fp, _vp, _fp, _ip, _ip, ctypes.c_int]
                            + [ctypes.c_int] * 6 + [ctypes.c_int, _vp, ctypes.c_size_t, _vp, ctypes.c_uint]),
+    "kla_chunk_bwd_workspace_bytes": (ctypes.c_size_t, [ctypes.c_int] * 6 + [ctypes.c_int, _ip, ctypes.c_int]),
+    "kla_chunk_bwd": (ctypes.c_int, [_vp, _vp, _vp, _fp, _fp, ctypes.c_float, _fp, _vp, _fp, _vp, _vp, _vp, _fp, _fp, _fp,
+                                     _ip, _ip, ctypes.c_int] + [ctypes.c_int] * 6 + [ctypes.c_int, _vp, ctypes.c_size_t, _vp]),
     "kla_debug_chunk_stage": (ctypes.c_int, [_vp, _vp, _vp, _fp, _fp, ctypes.c_float, _fp, _vp, _fp, _ip, _ip, ctypes.c_int]
                               + [ctypes.c_int] * 6 + [ctypes.c_int, _vp, ctypes.c_size_t, _vp, ctypes.c_int]),
     "kla_decode_step": (ctypes.c_int, [_vp, _vp, _vp, _fp, _fp, ctypes.c_float, _fp, _vp]
@@ -141,6 +144,48 @@ def kla_chunk_fwd(q, k, v, log_alpha, eta, eps, h0=None, cu_seqlens=None, want_h
     if rc != 0:
         raise KlaError(rc, "kla_chunk_fwd")
     return out, hT
+
+
+def kla_chunk_bwd_workspace_bytes(N, T, H, dk, dv, dtype, cu_seqlens=None, chunk=64) -> int:
+    cu_host, cu_hp, n_seq = _host_cu(cu_seqlens)
+    dt = KLA_BF16 if dtype == torch.bfloat16 else KLA_F32
+    return int(lib().kla_chunk_bwd_workspace_bytes(N, T, H, dk, dv, chunk, dt, cu_hp, n_seq))
+
+
+def kla_chunk_bwd(q, k, v, log_alpha, eta, eps, d_o, h0=None, d_hT=None, cu_seqlens=None, want_dh0=True,
+                  workspace=None, out=None, chunk=64):
+    """Backward of kla_chunk_fwd (no options): gradients of sum <d_o, o> + sum <d_hT, hT>.
+
+    d_o [N,T,H,dv] in the dtype of q; d_hT [n_states,H,dk,dv] fp32 or None (zeros).
+    Returns a dict: dq, dk, dv (dtype of q), dlog_alpha, deta (fp32 [N,T,H]), dh0 (fp32, or None).
+    `out` may hold preallocated tensors under the same names; `workspace` a uint8 buffer.
+    """
+    _dev(q, k, v, log_alpha, eta, d_o, h0, d_hT, cu_seqlens, workspace)
+    N, T, H, dk = q.shape
+    dv = v.shape[-1]
+    dt = _dt(q)
+    cu_host, cu_hp, n_seq = _host_cu(cu_seqlens)
+    n_states = n_seq if n_seq > 0 else N
+    need = int(lib().kla_chunk_bwd_workspace_bytes(N, T, H, dk, dv, chunk, dt, cu_hp, n_seq))
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+    out = dict(out or {})
+    for name, like in (("dq", q), ("dk", k), ("dv", v)):
+        if name not in out:
+            out[name] = torch.empty_like(like)
+    for name in ("dlog_alpha", "deta"):
+        if name not in out:
+            out[name] = torch.empty((N, T, H), dtype=torch.float32, device=q.device)
+    if "dh0" not in out:
+        out["dh0"] = torch.empty((n_states, H, dk, dv), dtype=torch.float32, device=q.device) if want_dh0 else None
+    _dev(*out.values())
+    rc = lib().kla_chunk_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(eta), float(eps), _ptr(h0), _ptr(d_o),
+                             _ptr(d_hT), _ptr(out["dq"]), _ptr(out["dk"]), _ptr(out["dv"]), _ptr(out["dlog_alpha"]),
+                             _ptr(out["deta"]), _ptr(out["dh0"]), _ptr(cu_seqlens), cu_hp, n_seq, N, T, H, dk, dv, chunk,
+                             dt, _ptr(workspace), workspace.numel() * workspace.element_size(), _stream())
+    if rc != 0:
+        raise KlaError(rc, "kla_chunk_bwd")
+    return out
 
 
 def kla_debug_chunk_stage(stage, q, k, v, log_alpha, eta, eps, workspace, out, hT=None, h0=None, cu_seqlens=None):

@@ -178,6 +178,70 @@ int chunk_fwd_impl(const void* q, const void* k, const void* v, const float* log
     return KLA_OK;
 }
 
+// ---- backward pass ---------------------------------------------------------------------------------
+struct BwdPlan {
+    Plan base;
+    size_t off_rec, off_C, off_S, off_dS, off_X, off_U, off_Y, total;
+};
+
+int make_bwd_plan(int N, int T, int H, int dk, int dv, int chunk, int dt, const int32_t* cu_host, int n_seq, BwdPlan* p)
+{
+    const int rc = make_plan(N, T, H, dk, dv, chunk, dt, cu_host, n_seq, &p->base);
+    if (rc != KLA_OK) return rc;
+    const size_t half = (size_t)384 * 8 * elem_bytes(dt);
+    const size_t ch = (size_t)p->base.n_chunks * H;
+    const size_t states = ch * dk * dv * sizeof(float);
+    const size_t rows = (size_t)N * T * H * dv * elem_bytes(dt);
+    p->off_rec = 0;                                              // [M | M^T | P^T | four vectors] per chunk-head
+    p->off_C = round256(ch * (3 * half + 1024));
+    p->off_S = round256(p->off_C + (size_t)(n_seq + 1) * sizeof(int32_t));
+    p->off_dS = round256(p->off_S + states);
+    p->off_X = round256(p->off_dS + states);
+    p->off_U = round256(p->off_X + rows);
+    p->off_Y = round256(p->off_U + rows);
+    p->total = round256(p->off_Y + rows);
+    return KLA_OK;
+}
+
+template <typename E>
+int chunk_bwd_impl(const void* q, const void* k, const void* v, const float* log_alpha, const float* eta, float eps,
+                   const float* h0, const void* d_o, const float* d_hT, void* dq, void* dk_, void* dv_,
+                   float* dlog_alpha, float* deta, float* dh0, const int32_t* cu_dev, int n_seq, int N, int T, int H,
+                   int dk, int dv, const BwdPlan& pl, char* ws, hipStream_t st)
+{
+    int* chunk_off = reinterpret_cast<int*>(ws + pl.off_C);
+    const int NT = (T + 63) / 64;
+    if (n_seq > 0 && kla::launch_chunk_offsets(cu_dev, n_seq, chunk_off, st) != hipSuccess) return KLA_ERR_HIP;
+
+    kla::IntraArgs<E> ia;
+    ia.q = static_cast<const E*>(q); ia.k = static_cast<const E*>(k);
+    ia.log_alpha = log_alpha; ia.eta = eta; ia.eps = eps;
+    ia.cu_seqlens = n_seq > 0 ? cu_dev : nullptr; ia.chunk_off = chunk_off; ia.n_seq = n_seq;
+    ia.T = T; ia.NT = NT; ia.H = H;
+    ia.wsT = reinterpret_cast<E*>(ws + pl.off_rec); ia.wsP = nullptr; ia.wsG = nullptr; ia.opts = 0u;
+    if (kla::launch_intra_bwd<E>(ia, dk, (int)pl.base.n_chunks, st) != hipSuccess) return KLA_ERR_HIP;
+
+    kla::BwdArgs<E> ba;
+    ba.q = ia.q; ba.k = ia.k; ba.v = static_cast<const E*>(v);
+    ba.log_alpha = log_alpha; ba.eta = eta; ba.eps = eps;
+    ba.h0 = h0; ba.d_o = static_cast<const E*>(d_o); ba.d_hT = d_hT;
+    ba.dq = static_cast<E*>(dq); ba.dk = static_cast<E*>(dk_); ba.dv = static_cast<E*>(dv_);
+    ba.dlog_alpha = dlog_alpha; ba.deta = deta; ba.dh0 = dh0;
+    ba.cu_seqlens = ia.cu_seqlens; ba.chunk_off = chunk_off; ba.n_seq = n_seq;
+    ba.N = N; ba.T = T; ba.NT = NT; ba.H = H; ba.dv_dim = dv;
+    ba.rec = ws + pl.off_rec;
+    ba.s_chk = reinterpret_cast<float*>(ws + pl.off_S); ba.ds_chk = reinterpret_cast<float*>(ws + pl.off_dS);
+    ba.X = reinterpret_cast<E*>(ws + pl.off_X); ba.U = reinterpret_cast<E*>(ws + pl.off_U);
+    ba.Y = reinterpret_cast<E*>(ws + pl.off_Y);
+    // two waves (32 state columns) per workgroup once that still gives a workgroup per CU
+    const long chains8 = ((long)pl.base.n_states * H + 7) / 8 * 8;
+    const int waves = (chains8 * (dv / 32) >= 192) ? 2 : 1;
+    if (kla::launch_bwd_states<E>(ba, dk, waves, st) != hipSuccess) return KLA_ERR_HIP;
+    if (kla::launch_bwd_scan<E>(ba, dk, waves, st) != hipSuccess) return KLA_ERR_HIP;
+    if (kla::launch_bwd_assemble<E>(ba, dk, pl.base.n_chunks, st) != hipSuccess) return KLA_ERR_HIP;
+    return KLA_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -251,6 +315,46 @@ int kla_chunk_fwd_opts(const void* q, const void* k, const void* v, const float*
 {
     return chunk_fwd_checked(q, k, v, log_alpha, eta, eps, h0, o, hT, cu_seqlens_dev, cu_seqlens_host, n_seq, N, T, H,
                              dk, dv, chunk, dt, workspace, workspace_bytes, hip_stream, 3, opts);
+}
+
+size_t kla_chunk_bwd_workspace_bytes(int N, int T, int H, int dk, int dv, int chunk, kla_dtype dt,
+                                     const int32_t* cu_seqlens_host, int n_seq)
+{
+    BwdPlan pl;
+    if (make_bwd_plan(N, T, H, dk, dv, chunk, (int)dt, cu_seqlens_host, n_seq, &pl) != KLA_OK) return 0;
+    return pl.total;
+}
+
+int kla_chunk_bwd(const void* q, const void* k, const void* v, const float* log_alpha, const float* eta, float eps,
+                  const float* h0, const void* d_o, const float* d_hT, void* dq, void* dk_, void* dv_,
+                  float* dlog_alpha, float* deta, float* dh0, const int32_t* cu_seqlens_dev,
+                  const int32_t* cu_seqlens_host, int n_seq, int N, int T, int H, int dk, int dv, int chunk,
+                  kla_dtype dt, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    BwdPlan pl;
+    const int rc = make_bwd_plan(N, T, H, dk, dv, chunk, (int)dt, cu_seqlens_host, n_seq, &pl);
+    if (rc != KLA_OK) return rc;
+    if (!(eps >= 0.0f) || isinf(eps)) return KLA_ERR_SHAPE;
+    if (n_seq > 0 && !cu_seqlens_dev) return KLA_ERR_NULL;
+    if (n_seq == 0 && cu_seqlens_dev) return KLA_ERR_SHAPE;
+    const bool any_tokens = (long)N * T > 0;
+    if (any_tokens && (!q || !k || !v || !log_alpha || !eta || !d_o || !dq || !dk_ || !dv_ || !dlog_alpha || !deta))
+        return KLA_ERR_NULL;
+    if (!workspace) return KLA_ERR_WORKSPACE;
+    if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0 || workspace_bytes < pl.total) return KLA_ERR_WORKSPACE;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(d_o) || !aligned16(dq) || !aligned16(dk_) ||
+        !aligned16(dv_) || !aligned16(h0) || !aligned16(d_hT) || !aligned16(dh0) ||
+        (reinterpret_cast<uintptr_t>(log_alpha) & 3u) || (reinterpret_cast<uintptr_t>(eta) & 3u) ||
+        (reinterpret_cast<uintptr_t>(dlog_alpha) & 3u) || (reinterpret_cast<uintptr_t>(deta) & 3u))
+        return KLA_ERR_ALIGN;
+    if (pl.base.n_states == 0) return KLA_OK;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    char* ws = static_cast<char*>(workspace);
+    if (dt == KLA_BF16)
+        return chunk_bwd_impl<bf16_t>(q, k, v, log_alpha, eta, eps, h0, d_o, d_hT, dq, dk_, dv_, dlog_alpha, deta, dh0,
+                                      cu_seqlens_dev, n_seq, N, T, H, dk, dv, pl, ws, st);
+    return chunk_bwd_impl<float>(q, k, v, log_alpha, eta, eps, h0, d_o, d_hT, dq, dk_, dv_, dlog_alpha, deta, dh0,
+                                 cu_seqlens_dev, n_seq, N, T, H, dk, dv, pl, ws, st);
 }
 
 int kla_debug_chunk_stage(const void* q, const void* k, const void* v, const float* log_alpha, const float* eta,

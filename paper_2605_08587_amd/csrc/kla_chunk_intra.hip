@@ -43,11 +43,50 @@ __device__ __forceinline__ float4 aquad(const float* m, int row0, int col0, int 
 }
 __device__ __forceinline__ float4 acc_as_quad(floatx4 x) { return make_float4(x[0], x[1], x[2], x[3]); }
 
+// A triangular 64x64 fp32 matrix m (row stride kLdm) -> 6 stored tile-pairs of operand slots at `out`.
+// TRANSPOSE = false: the lower-triangular matrix itself (pairs tri_pair(it, jp), jp <= it/2), optionally with
+// column j scaled by colscale[j].  TRANSPOSE = true: its transpose, which is upper triangular (pairs
+// triu_pair(it, jp), jp >= it/2).  Called by all 256 threads.
+template <typename E, bool TRANSPOSE, bool SCALE>
+__device__ __forceinline__ void write_tri(char* out, const float* m, const float* colscale, int tid)
+{
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+        const int sl = tid + 256 * it;           // slot index: stored tile-pair * 64 + lane
+        if (sl >= kTriPairs * 64) break;
+        const int ctp = sl >> 6, ln = sl & 63;
+        int ti, jp;
+        if constexpr (TRANSPOSE) { ti = ctp < 4 ? (ctp >> 1) : ctp - 2; jp = ctp < 4 ? (ctp & 1) : 1; }
+        else                     { ti = ctp < 2 ? ctp : 2 + ((ctp - 2) >> 1); jp = ctp < 2 ? 0 : ((ctp - 2) & 1); }
+        const int row = 16 * ti + (ln & 15), col = 32 * jp + 4 * (ln >> 4);
+        floatx4 v0, v1;
+        if constexpr (TRANSPOSE) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { v0[e] = m[(col + e) * kLdm + row]; v1[e] = m[(col + 16 + e) * kLdm + row]; }
+        } else {
+            const float4 f0 = ld4(m + row * kLdm + col), f1 = ld4(m + row * kLdm + col + 16);
+            v0[0] = f0.x; v0[1] = f0.y; v0[2] = f0.z; v0[3] = f0.w;
+            v1[0] = f1.x; v1[1] = f1.y; v1[2] = f1.z; v1[3] = f1.w;
+            if constexpr (SCALE) {
+                const float4 b0 = ld4(colscale + col), b1 = ld4(colscale + col + 16);
+                v0[0] *= b0.x; v0[1] *= b0.y; v0[2] *= b0.z; v0[3] *= b0.w;
+                v1[0] *= b1.x; v1[1] *= b1.y; v1[2] *= b1.z; v1[3] *= b1.w;
+            }
+        }
+        Slot<E> s; s.q0 = acc_to_quad<E>(v0); s.q1 = acc_to_quad<E>(v1);
+        *reinterpret_cast<Slot<E>*>(out + (size_t)sl * slot_bytes<E>()) = s;
+    }
+}
+
 }  // namespace
 
-template <typename E, int DK>
+// BWD = false: the forward's records [T' | P | three vectors].  BWD = true: the records of the backward pass,
+// [M | M^T | P^T | gamma_i | gamma_C/gamma_i | beta_i | 1/(||k_i||^2+eps)] with M = (I + L)^{-1}; the transposes are stored as the
+// 6 upper-triangular tile-pairs (see bwd_record_bytes in kla_mma.hpp).
+template <typename E, int DK, bool BWD>
 __global__ __launch_bounds__(256) void intra_kernel(IntraArgs<E> a)
 {
+    constexpr int REC = BWD ? bwd_record_bytes<E>() : ws_record_bytes<E>();
     constexpr int PPR = DK * (int)sizeof(E) / 16;    // 16-byte pieces per row
     constexpr int EPP = 16 / (int)sizeof(E);         // elements per piece
     constexpr int KP = DK / 32;                      // contraction pairs per row
@@ -59,6 +98,7 @@ __global__ __launch_bounds__(256) void intra_kernel(IntraArgs<E> a)
     __shared__ __attribute__((aligned(16))) float beta_s[64];
     __shared__ __attribute__((aligned(16))) float rq_s[64];      // 1/||q_i|| when the read-out is normalised, else 1
     __shared__ __attribute__((aligned(16))) float g_s[64];
+    __shared__ __attribute__((aligned(16))) float invden_s[BWD ? 64 : 4];   // 1/(||k_i||^2 + eps), for the backward pass
     E* Krq = reinterpret_cast<E*>(op_area);
     E* Qrq = reinterpret_cast<E*>(op_area + OPB);
     float* Pm = reinterpret_cast<float*>(op_area);   // reused after the Gram products are in registers
@@ -123,6 +163,7 @@ __global__ __launch_bounds__(256) void intra_kernel(IntraArgs<E> a)
                 beta_s[row] = (a.opts & kOptGdnBeta) ? et : kaczmarz_beta(et, ss, a.eps);
                 // scale of the normalised read-out o_t = S_t^T q_t / ||q_t|| (Sec. 3.3); a zero query gives 0
                 rq_s[row] = (a.opts & kOptNormalizeQ) ? (sq > 0.f ? 1.0f / sqrtf(sq) : 0.f) : 1.f;
+                if constexpr (BWD) invden_s[row] = (ss + a.eps == 0.f) ? 0.f : 1.0f / (ss + a.eps);
             }
         }
         if (wave == 0) {
@@ -133,21 +174,24 @@ __global__ __launch_bounds__(256) void intra_kernel(IntraArgs<E> a)
                 if (lane >= off) x += y;
             }
             g_s[lane] = x;
-            a.wsG[(size_t)blockIdx.x * 128 + lane] = x;
+            if constexpr (!BWD) a.wsG[(size_t)blockIdx.x * 128 + lane] = x;
             // decay factors the scan stage multiplies with: gamma_i and gamma_C / gamma_i
             const float gl = __shfl(x, 63, kWave);
-            float* dec = reinterpret_cast<float*>(reinterpret_cast<char*>(a.wsT) + (size_t)blockIdx.x * ws_record_bytes<E>()
-                                                  + 2 * ws_half_bytes<E>());
+            float* dec = reinterpret_cast<float*>(reinterpret_cast<char*>(a.wsT) + (size_t)blockIdx.x * REC
+                                                  + (BWD ? 3 : 2) * ws_half_bytes<E>());
             dec[lane] = expf(x);
             dec[64 + lane] = expf(gl - x);
         }
     }
     __syncthreads();
-    if (wave == 0) {                                     // third vector of the record and the scale itself
-        float* dec = reinterpret_cast<float*>(reinterpret_cast<char*>(a.wsT) + (size_t)blockIdx.x * ws_record_bytes<E>()
-                                              + 2 * ws_half_bytes<E>());
-        dec[128 + lane] = expf(g_s[lane]) * rq_s[lane];
-        a.wsG[(size_t)blockIdx.x * 128 + 64 + lane] = rq_s[lane];
+    if (wave == 0) {                                     // third vector of the record (and the scale itself)
+        float* dec = reinterpret_cast<float*>(reinterpret_cast<char*>(a.wsT) + (size_t)blockIdx.x * REC
+                                              + (BWD ? 3 : 2) * ws_half_bytes<E>());
+        if constexpr (BWD) { dec[128 + lane] = beta_s[lane]; dec[192 + lane] = invden_s[lane]; }
+        else {
+            dec[128 + lane] = expf(g_s[lane]) * rq_s[lane];
+            a.wsG[(size_t)blockIdx.x * 128 + 64 + lane] = rq_s[lane];
+        }
     }
 
     // ---- phase 2a: Gram products K K^T and Q K^T on the lower-triangular tiles ---------------
@@ -215,23 +259,9 @@ __global__ __launch_bounds__(256) void intra_kernel(IntraArgs<E> a)
         for (int i = 0; i < 16; ++i)
             if ((i >> 2) == g) Tm[(b0 + i) * kLdm + b0 + r] = x[i];
     }
-    {
-        char* out = reinterpret_cast<char*>(a.wsP) + (size_t)blockIdx.x * ws_record_bytes<E>();
-#pragma unroll
-        for (int it = 0; it < 2; ++it) {
-            const int sl = tid + 256 * it;           // slot index: stored tile-pair * 64 + lane
-            if (sl >= kTriPairs * 64) break;
-            const int ctp = sl >> 6, ln = sl & 63;
-            const int ti = ctp < 2 ? ctp : 2 + ((ctp - 2) >> 1), jp = ctp < 2 ? 0 : ((ctp - 2) & 1);
-            const int row = 16 * ti + (ln & 15), col = 32 * jp + 4 * (ln >> 4);
-            floatx4 v0, v1;
-            const float4 f0 = ld4(Pm + row * kLdm + col), f1 = ld4(Pm + row * kLdm + col + 16);
-            v0[0] = f0.x; v0[1] = f0.y; v0[2] = f0.z; v0[3] = f0.w;
-            v1[0] = f1.x; v1[1] = f1.y; v1[2] = f1.z; v1[3] = f1.w;
-            Slot<E> s; s.q0 = acc_to_quad<E>(v0); s.q1 = acc_to_quad<E>(v1);
-            *reinterpret_cast<Slot<E>*>(out + (size_t)sl * slot_bytes<E>()) = s;
-        }
-    }
+    if constexpr (BWD) write_tri<E, true, false>(reinterpret_cast<char*>(a.wsT) + (size_t)blockIdx.x * REC + 2 * ws_half_bytes<E>(),
+                                                  Pm, nullptr, tid);           // P^T
+    else               write_tri<E, false, false>(reinterpret_cast<char*>(a.wsP) + (size_t)blockIdx.x * REC, Pm, nullptr, tid);
     __syncthreads();
 
     // ---- phase 4: 32x32 level.  Waves 0,1: block pair (a, b) = (2m, 2m+1): T_ba = -D_b (L_ba D_a)
@@ -263,23 +293,14 @@ __global__ __launch_bounds__(256) void intra_kernel(IntraArgs<E> a)
     }
     __syncthreads();
 
-    // ---- phase 6: T' = T diag(beta) -> workspace in operand order ------------------------------
+    // ---- phase 6: T' = T diag(beta) (forward) or T and T^T (backward) -> workspace in operand order ------------
     {
-        char* out = reinterpret_cast<char*>(a.wsT) + (size_t)blockIdx.x * ws_record_bytes<E>();
-#pragma unroll
-        for (int it = 0; it < 2; ++it) {
-            const int sl = tid + 256 * it;
-            if (sl >= kTriPairs * 64) break;
-            const int ctp = sl >> 6, ln = sl & 63;
-            const int ti = ctp < 2 ? ctp : 2 + ((ctp - 2) >> 1), jp = ctp < 2 ? 0 : ((ctp - 2) & 1);
-            const int row = 16 * ti + (ln & 15), col = 32 * jp + 4 * (ln >> 4);
-            const float4 f0 = ld4(Tm + row * kLdm + col), f1 = ld4(Tm + row * kLdm + col + 16);
-            const float4 b0 = ld4(beta_s + col), b1 = ld4(beta_s + col + 16);
-            floatx4 v0, v1;
-            v0[0] = f0.x * b0.x; v0[1] = f0.y * b0.y; v0[2] = f0.z * b0.z; v0[3] = f0.w * b0.w;
-            v1[0] = f1.x * b1.x; v1[1] = f1.y * b1.y; v1[2] = f1.z * b1.z; v1[3] = f1.w * b1.w;
-            Slot<E> s; s.q0 = acc_to_quad<E>(v0); s.q1 = acc_to_quad<E>(v1);
-            *reinterpret_cast<Slot<E>*>(out + (size_t)sl * slot_bytes<E>()) = s;
+        char* out = reinterpret_cast<char*>(a.wsT) + (size_t)blockIdx.x * REC;
+        if constexpr (BWD) {
+            write_tri<E, false, false>(out, Tm, nullptr, tid);
+            write_tri<E, true, false>(out + ws_half_bytes<E>(), Tm, nullptr, tid);
+        } else {
+            write_tri<E, false, true>(out, Tm, beta_s, tid);
         }
     }
 }
@@ -289,12 +310,25 @@ hipError_t launch_intra(const IntraArgs<E>& a, int dk, int n_chunks, hipStream_t
 {
     if (n_chunks == 0) return hipSuccess;
     const dim3 grid((unsigned)n_chunks * a.H), block(256);
-    if (dk == 64) hipLaunchKernelGGL((intra_kernel<E, 64>), grid, block, 0, st, a);
-    else          hipLaunchKernelGGL((intra_kernel<E, 128>), grid, block, 0, st, a);
+    if (dk == 64) hipLaunchKernelGGL((intra_kernel<E, 64, false>), grid, block, 0, st, a);
+    else          hipLaunchKernelGGL((intra_kernel<E, 128, false>), grid, block, 0, st, a);
     return hipGetLastError();
 }
 template hipError_t launch_intra<float>(const IntraArgs<float>&, int, int, hipStream_t);
 template hipError_t launch_intra<bf16_t>(const IntraArgs<bf16_t>&, int, int, hipStream_t);
+
+// The records of the backward pass: a.wsT points at them, a.wsP and a.wsG are not used, a.opts must be 0.
+template <typename E>
+hipError_t launch_intra_bwd(const IntraArgs<E>& a, int dk, int n_chunks, hipStream_t st)
+{
+    if (n_chunks == 0) return hipSuccess;
+    const dim3 grid((unsigned)n_chunks * a.H), block(256);
+    if (dk == 64) hipLaunchKernelGGL((intra_kernel<E, 64, true>), grid, block, 0, st, a);
+    else          hipLaunchKernelGGL((intra_kernel<E, 128, true>), grid, block, 0, st, a);
+    return hipGetLastError();
+}
+template hipError_t launch_intra_bwd<float>(const IntraArgs<float>&, int, int, hipStream_t);
+template hipError_t launch_intra_bwd<bf16_t>(const IntraArgs<bf16_t>&, int, int, hipStream_t);
 
 // ---- chunk offsets of a packed batch: chunk_off[s] = sum_{s'<s} ceil(len_s'/64) --------------
 __global__ void chunk_offsets_kernel(const int* __restrict__ cu_seqlens, int n_seq, int* __restrict__ chunk_off)

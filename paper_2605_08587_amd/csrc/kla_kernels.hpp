@@ -33,6 +33,8 @@ template <typename E> struct IntraArgs {
     unsigned opts;                               // kOptNormalizeQ | kOptGdnBeta
 };
 template <typename E> hipError_t launch_intra(const IntraArgs<E>& a, int dk, int n_chunks, hipStream_t st);
+// the records of the backward pass (see bwd_record_bytes in kla_mma.hpp) at a.wsT; a.wsP, a.wsG unused, a.opts = 0
+template <typename E> hipError_t launch_intra_bwd(const IntraArgs<E>& a, int dk, int n_chunks, hipStream_t st);
 
 template <typename E> struct ScanArgs {
     const E* q; const E* k; const E* v;
@@ -61,6 +63,27 @@ hipError_t launch_segment_combine(const float* h0, const float* maps, float* seg
                                   int G, hipStream_t st);
 hipError_t launch_segment_gather(const float* seg_state, float* hT, int N, int H, int dk, int dv, int G, int g_last,
                                  hipStream_t st);
+
+// ---- chunkwise backward (gradient of sum <d_o, o> + sum <d_hT, hT>) ----------------------------------
+// Stage 1 (launch_intra_bwd) leaves one record per chunk-head at `rec`.  Stage 2 walks every (sequence, head)
+// forward and leaves, per chunk, the incoming state S_c (fp32, [chunk-head][dk][dv]) and the rows X = V - D_gamma K S_c
+// and U = M B X of eq. (6) (element type, laid out like v).  Stage 3 walks backward and leaves the gradient dS'_c of
+// the state each chunk hands on, Y = M^T dU (laid out like v), and writes dv = B Y and dh0.  Stage 4 contracts those
+// over d_v per chunk-head and writes dq, dk, dlog_alpha, deta.
+template <typename E> struct BwdArgs {
+    const E* q; const E* k; const E* v;
+    const float* log_alpha; const float* eta; float eps;
+    const float* h0; const E* d_o; const float* d_hT;
+    E* dq; E* dk; E* dv; float* dlog_alpha; float* deta; float* dh0;
+    const int* cu_seqlens; const int* chunk_off; int n_seq;
+    int N, T, NT, H, dv_dim;
+    const char* rec;                 // stage-1 records
+    float* s_chk; float* ds_chk;     // [n_chunks * H][dk][dv]
+    E* X; E* U; E* Y;                // [tokens][H][dv]
+};
+template <typename E> hipError_t launch_bwd_states(const BwdArgs<E>& a, int dk, int waves, hipStream_t st);
+template <typename E> hipError_t launch_bwd_scan(const BwdArgs<E>& a, int dk, int waves, hipStream_t st);
+template <typename E> hipError_t launch_bwd_assemble(const BwdArgs<E>& a, int dk, long n_chunks, hipStream_t st);
 
 hipError_t launch_chunk_offsets(const int* cu_seqlens, int n_seq, int* chunk_off, hipStream_t st);
 template <typename E>

@@ -47,6 +47,11 @@ constexpr int kTriPairs = 6;
 template <typename E> constexpr int ws_half_bytes() { return kTriPairs * 64 * 8 * (int)sizeof(E); }
 template <typename E> constexpr int ws_record_bytes() { return 2 * ws_half_bytes<E>() + 768; }
 __host__ __device__ constexpr int tri_pair(int it, int jp) { return it < 2 ? it : 2 * it - 2 + jp; }
+// The transposes (upper triangular) keep the 6 tile-pairs with jp >= it/2, in this order.
+__host__ __device__ constexpr int triu_pair(int it, int jp) { return it < 2 ? 2 * it + jp : it + 2; }
+// Record of one chunk-head for the backward pass: [M | M^T | P^T | gamma_i | gamma_C/gamma_i | beta_i | 1/(|k_i|^2+eps)],
+// M = (I + L)^{-1}, three operand halves and four vectors of 64 fp32.
+template <typename E> constexpr int bwd_record_bytes() { return 3 * ws_half_bytes<E>() + 1024; }
 
 // ---- conversions between accumulator tiles and quads -------------------------------------
 __device__ __forceinline__ uint2 make_quad(floatx4 x, bf16_t)

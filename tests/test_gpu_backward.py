@@ -1,0 +1,143 @@
+"""GPU parity of the backward pass: kla_chunk_bwd, called through the C ABI, against the fp64 reverse-accumulation
+oracle on the same seeded inputs, element by element.
+
+Metric and bars as for the forward: max|x_gpu - x_ref| / max|x_ref| over the whole tensor, <= 1e-4 for fp32
+inputs and <= 2e-2 for bf16 inputs, separately for each of dq, dk, dv, dlog_alpha, deta and dh0.
+"""
+import numpy as np
+import pytest
+import torch
+
+import kla_inputs
+from oracle import token_oracle
+
+pytestmark = pytest.mark.gpu
+
+TOL = {torch.float32: 1e-4, torch.bfloat16: 2e-2}
+NAMES = ("dq", "dk", "dv", "dlog_alpha", "deta", "dh0")
+
+
+@pytest.fixture(scope="module")
+def kla():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2605_08587_amd as m
+    m.lib()          # raises if the HIP library is not built: there is no fallback to test instead
+    return m
+
+
+def _cuda(t):
+    return None if t is None else t.cuda()
+
+
+def _run(kla, d, d_o, d_hT, **kw):
+    out = kla.kla_chunk_bwd(_cuda(d["q"]), _cuda(d["k"]), _cuda(d["v"]), _cuda(d["log_alpha"]), _cuda(d["eta"]), d["eps"],
+                            _cuda(d_o), h0=_cuda(d["h0"]), d_hT=_cuda(d_hT), cu_seqlens=_cuda(d["cu_seqlens"]), **kw)
+    torch.cuda.synchronize()
+    return {n: (None if out[n] is None else out[n].float().cpu().numpy()) for n in NAMES}
+
+
+def _oracle(d, d_o, d_hT, units=None):
+    q, k, v = (kla_inputs.to_numpy_f32(d[x]) for x in "qkv")
+    return token_oracle.kla_recurrent_bwd(
+        q, k, v, d["log_alpha"].numpy(), d["eta"].numpy(), d["eps"], kla_inputs.to_numpy_f32(d_o),
+        h0=None if d["h0"] is None else d["h0"].numpy(), d_hT=None if d_hT is None else d_hT.numpy(),
+        cu_seqlens=None if d["cu_seqlens"] is None else d["cu_seqlens"].numpy(), units=units)
+
+
+def _check(kla, d, seed, d_hT=True, units=None, tol=None):
+    tol = tol or TOL[d["dtype"]]
+    print("case N=%d T=%d H=%d dk=%d dv=%d %s varlen=%s" % (d["N"], d["T"], d["H"], d["dk"], d["dv"], d["dtype"],
+                                                           d["cu_seqlens"] is not None), flush=True)
+    d_o, g = kla_inputs.grad_inputs(d, seed, d_hT=d_hT)
+    got = _run(kla, d, d_o, g)
+    ref = _oracle(d, d_o, g, units)
+    errs = {}
+    for n in NAMES:
+        x, r = got[n], ref[n]
+        assert np.all(np.isfinite(x)), n
+        if units is not None:                  # compare only the sampled (sequence, head) units
+            m = np.zeros(r.shape, bool)
+            for s, h in units:
+                if n == "dh0":
+                    m[s, h] = True
+                elif d["cu_seqlens"] is None:
+                    m[s, :, h] = True
+                else:
+                    m[0, int(d["cu_seqlens"][s]):int(d["cu_seqlens"][s + 1]), h] = True
+            x, r = x[m], r[m]
+        errs[n] = token_oracle.rel_err(x, r)
+    print("   rel err " + " ".join("%s=%.2e" % kv for kv in errs.items()) + " (bar %.0e)" % tol, flush=True)
+    for n in NAMES:
+        assert errs[n] <= tol, (n, errs[n])
+    return errs
+
+
+@pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("dk,dv", [(64, 64), (128, 128), (128, 256), (64, 128)])
+@pytest.mark.parametrize("T", [1, 63, 65, 200])
+def test_bwd_small_shapes(kla, dt, dk, dv, T):
+    """Single chunks, a ragged tail, several chunks; non-zero h0 and d_hT; both state widths per workgroup."""
+    _check(kla, kla_inputs.chunk_inputs(2, T, 3, dk, dv, dtype=dt, seed=300 + T + dk + dv, h0_std=0.5), seed=T)
+
+
+@pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16])
+def test_bwd_without_states(kla, dt):
+    """h0 = NULL, d_hT = NULL and dh0 unwanted."""
+    d = kla_inputs.chunk_inputs(1, 150, 2, 128, 128, dtype=dt, seed=311)
+    d_o, _ = kla_inputs.grad_inputs(d, 1, d_hT=False)
+    got = _run(kla, d, d_o, None, want_dh0=False)
+    ref = _oracle(d, d_o, None)
+    assert got["dh0"] is None
+    for n in NAMES[:-1]:
+        assert token_oracle.rel_err(got[n], ref[n]) <= TOL[dt], n
+
+
+@pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16])
+def test_bwd_varlen(kla, dt):
+    """Packed batch with per-sequence h0 and d_hT, lengths from 1 token to several chunks, one empty sequence."""
+    d = kla_inputs.varlen_inputs(6, 1, 300, 2, 128, 256 if dt == torch.bfloat16 else 128, dtype=dt, seed=320, h0_std=0.3)
+    cu = d["cu_seqlens"].clone()
+    cu[3] = cu[2]                              # sequence 2 is empty: its dh0 is d_hT itself
+    d["cu_seqlens"] = cu
+    _check(kla, d, seed=2)
+
+
+def test_bwd_two_waves_per_workgroup(kla):
+    """Enough (sequence, head) pairs for the 32-column workgroups the benchmark shape uses."""
+    _check(kla, kla_inputs.chunk_inputs(16, 192, 4, 128, 128, dtype=torch.bfloat16, seed=330, h0_std=0.1), seed=3)
+
+
+@pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16])
+def test_bwd_eta_zero_and_zero_keys(kla, dt):
+    """Tokens with eta = 0 (beta = 0 but d eta != 0) and zero keys (the coefficient's denominator is eps alone)."""
+    d = kla_inputs.chunk_inputs(1, 200, 2, 64, 64, dtype=dt, seed=340, h0_std=0.5)
+    d["eta"][:, ::5] = 0.0
+    d["k"][:, 7::11] = 0.0
+    d["eps"] = 0.5
+    _check(kla, d, seed=4)
+
+
+def test_bwd_slow_decay_long_carry(kla):
+    """Slow decay: gradients travel over a thousand tokens, so errors of the state sweeps would add up."""
+    d = kla_inputs.chunk_inputs(1, 1500, 2, 128, 128, dtype=torch.bfloat16, seed=350, log_alpha_scale=0.02, h0_std=0.2)
+    _check(kla, d, seed=5)
+    d = kla_inputs.chunk_inputs(1, 700, 2, 64, 64, dtype=torch.float32, seed=351, log_alpha_scale=0.02, h0_std=0.2)
+    _check(kla, d, seed=6)
+
+
+def test_bwd_config2_sampled(kla):
+    """Config 2 at full size, in the launch configuration the benchmark times; the oracle runs on 6 sampled
+    (sequence, head) units."""
+    d = kla_inputs.config(2)
+    _check(kla, d, seed=7, d_hT=True, units=[(0, 0), (3, 5), (7, 7), (1, 2), (6, 1), (4, 4)])
+
+
+def test_bwd_determinism(kla):
+    """No atomics: two runs are bitwise equal."""
+    d = kla_inputs.chunk_inputs(2, 300, 4, 128, 128, dtype=torch.bfloat16, seed=360, h0_std=0.2)
+    d_o, g = kla_inputs.grad_inputs(d, 8)
+    a = _run(kla, d, d_o, g)
+    b = _run(kla, d, d_o, g)
+    for n in NAMES:
+        assert np.array_equal(a[n], b[n]), n
