@@ -153,6 +153,24 @@ def main():
                                       "tokens_per_s": round(e["N"] * e["T"] / (ms * 1e-3), 1)}
             del g, w2, o2, h2
 
+    # ------------------------------------------------------------------ backward of the chunk path, config 2 (secondary)
+    backward = None
+    if not args.skip_extra:
+        d_o, d_hT = kla_inputs.grad_inputs(d, 1)
+        d_o, d_hT = d_o.cuda(), d_hT.cuda()
+        wb = torch.empty(kla.kla_chunk_bwd_workspace_bytes(N, T, H, dk, dv, torch.bfloat16), dtype=torch.uint8, device="cuda")
+        grads = kla.kla_chunk_bwd(dev["q"], dev["k"], dev["v"], dev["log_alpha"], dev["eta"], d["eps"], d_o, d_hT=d_hT,
+                                  workspace=wb)
+        fnb = lambda: kla.kla_chunk_bwd(dev["q"], dev["k"], dev["v"], dev["log_alpha"], dev["eta"], d["eps"], d_o,
+                                        d_hT=d_hT, workspace=wb, out=grads)
+        for _ in range(3):
+            fnb()
+        msb = _events(torch, fnb, 10)
+        backward = {"workload": "config2, gradients of q,k,v,log_alpha,eta,h0 (forward quantities recomputed)",
+                    "ms_per_call": round(msb, 4), "tokens_per_s": round(tokens / (msb * 1e-3), 1),
+                    "times_forward": round(msb / ms_per_step, 2), "workspace_MB": round(wb.numel() / 1e6, 1)}
+        del wb, grads, d_o, d_hT
+
     # ------------------------------------------------------------------ decode, config 4
     decode = None
     if not args.skip_decode:
@@ -239,7 +257,7 @@ def main():
             "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
             "config": {"workload": "config2: N=8,H=8,T=4096,dk=dv=128,chunk=64,bf16 q/k/v,fp32 gates+state",
                        "global_batch": N, "seq_len": T, "heads": H},
-            "roofline": roofline, "mfma": mfma, "other_chunk_workloads": extra, "decode": decode, "cpu_baseline": cpu, "parity": parity}
+            "roofline": roofline, "mfma": mfma, "other_chunk_workloads": extra, "backward": backward, "decode": decode, "cpu_baseline": cpu, "parity": parity}
     print(json.dumps(line), flush=True)
 
 
