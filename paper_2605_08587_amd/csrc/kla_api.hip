@@ -190,9 +190,9 @@ int make_bwd_plan(int N, int T, int H, int dk, int dv, int chunk, int dt, const 
     if (rc != KLA_OK) return rc;
     const size_t half = (size_t)384 * 8 * elem_bytes(dt);
     const size_t ch = (size_t)p->base.n_chunks * H;
-    const size_t states = ch * dk * dv * sizeof(float);
+    const size_t states = ch * dk * dv * elem_bytes(dt);          // checkpoints are kept in the element type
     const size_t rows = (size_t)N * T * H * dv * elem_bytes(dt);
-    p->off_rec = 0;                                              // [M | M^T | P^T | four vectors] per chunk-head
+    p->off_rec = 0;                                              // [T' | M^T | P^T | four vectors] per chunk-head
     p->off_C = round256(ch * (3 * half + 1024));
     p->off_S = round256(p->off_C + (size_t)(n_seq + 1) * sizeof(int32_t));
     p->off_dS = round256(p->off_S + states);
@@ -230,7 +230,7 @@ int chunk_bwd_impl(const void* q, const void* k, const void* v, const float* log
     ba.cu_seqlens = ia.cu_seqlens; ba.chunk_off = chunk_off; ba.n_seq = n_seq;
     ba.N = N; ba.T = T; ba.NT = NT; ba.H = H; ba.dv_dim = dv;
     ba.rec = ws + pl.off_rec;
-    ba.s_chk = reinterpret_cast<float*>(ws + pl.off_S); ba.ds_chk = reinterpret_cast<float*>(ws + pl.off_dS);
+    ba.s_chk = reinterpret_cast<E*>(ws + pl.off_S); ba.ds_chk = reinterpret_cast<E*>(ws + pl.off_dS);
     ba.X = reinterpret_cast<E*>(ws + pl.off_X); ba.U = reinterpret_cast<E*>(ws + pl.off_U);
     ba.Y = reinterpret_cast<E*>(ws + pl.off_Y);
     // two waves (32 state columns) per workgroup once that still gives a workgroup per CU

@@ -14,7 +14,8 @@
 //     dlog_alpha_r = sum_{i >= r in the chunk} dg_i,        deta_i = dbeta_i / (|k_i|^2 + eps)
 // (g_i multiplies q_i and the k_i that reads the state, and divides the k_i that writes to it; hence the signs.)
 //
-// Three kernels after the intra-chunk stage has left [M | M^T | P^T | gamma_i | gamma_C/gamma_i | beta_i | 1/(|k_i|^2+eps)]:
+// Three kernels after the intra-chunk stage has left [T' | M^T | P^T | gamma_i | gamma_C/gamma_i | beta_i | 1/(|k_i|^2+eps)]
+// (T' = M B, so U = T' X):
 //   bwd_states_kernel    forward over the chunks of a (sequence, head, column slice): S_c, X, U        -> workspace
 //   bwd_scan_kernel      backward over the same chunks: dS'_c, Y -> workspace, dv and dh0 -> outputs
 //   bwd_assemble_kernel  per chunk-head: the contractions over d_v and over the chunk -> dq, dk, dlog_alpha, deta
@@ -93,7 +94,7 @@ __global__ __launch_bounds__(64 * NW) void bwd_states_kernel(BwdArgs<E> a)
     typedef SweepCfg<E, DK, NW> C;
     constexpr int NTH = C::NTH, KB = C::KB, KP = C::KP, SLW = C::SLW, PPR = C::PPR, EPP = C::EPP, VPP = C::VPP;
     typedef typename QuadT<E>::type Quad;
-    // K rows | K transposed | M | V slice | gamma_i | gamma_C/gamma_i | beta_i
+    // K rows | K transposed | T' | V slice | gamma_i | gamma_C/gamma_i | beta_i
     constexpr int OFF_KT = C::OPB, OFF_M = 2 * C::OPB, OFF_V = OFF_M + C::TPB, OFF_VEC = OFF_V + C::VB, LDS = OFF_VEC + 768;
     __shared__ __attribute__((aligned(16))) char lds[LDS];
 
@@ -195,16 +196,14 @@ __global__ __launch_bounds__(64 * NW) void bwd_states_kernel(BwdArgs<E> a)
         const E* Vtq = reinterpret_cast<const E*>(lds + OFF_V);
         const float* eg = reinterpret_cast<const float*>(lds + OFF_VEC);
         const float* ed = eg + 64;
-        const float* be = eg + 128;
 
-        // the incoming state of this chunk
-        float* sck = a.s_chk + ((size_t)(p.ch0 + c) * a.H + h) * DK * a.dv_dim;
+        // the incoming state of this chunk, transposed: column `col` is a row of d_k elements
+        E* sck = a.s_chk + (((size_t)(p.ch0 + c) * a.H + h) * a.dv_dim + col) * DK;
         Quad Sq[KB];
 #pragma unroll
         for (int kt = 0; kt < KB; ++kt) {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) sck[(size_t)(16 * kt + 4 * g + e) * a.dv_dim + col] = S[kt][e];
             Sq[kt] = acc_to_quad<E>(S[kt]);
+            *reinterpret_cast<Quad*>(sck + 16 * kt + 4 * g) = Sq[kt];
         }
         E* xb = a.X + (size_t)tok0 * v_stride + (size_t)h * a.dv_dim + col;
         E* ub = a.U + (size_t)tok0 * v_stride + (size_t)h * a.dv_dim + col;
@@ -217,7 +216,7 @@ __global__ __launch_bounds__(64 * NW) void bwd_states_kernel(BwdArgs<E> a)
             const Slot<E> sv = load_slot(Vtq, wave * 2 + (it >> 1), lane);
             const floatx4 x = quad_to_acc((it & 1) ? sv.q1 : sv.q0) - ld_acc4(eg + 16 * it + 4 * g) * ks;   // eq. (6), right side
             store_rows<E>(xb, v_stride, x, it, g, clen);
-            Xq[it] = acc_to_quad<E>(x * ld_acc4(be + 16 * it + 4 * g));
+            Xq[it] = acc_to_quad<E>(x);
         }
         Quad Udq[4];
 #pragma unroll
@@ -364,14 +363,13 @@ __global__ __launch_bounds__(64 * NW) void bwd_scan_kernel(BwdArgs<E> a)
         const float* ed = eg + 64;
         const float* be = eg + 128;
 
-        // the gradient of the state this chunk hands on
-        float* dck = a.ds_chk + ((size_t)(p.ch0 + c) * a.H + h) * DK * a.dv_dim;
+        // the gradient of the state this chunk hands on (transposed, like the state checkpoints)
+        E* dck = a.ds_chk + (((size_t)(p.ch0 + c) * a.H + h) * a.dv_dim + col) * DK;
         Quad dSq[KB];
 #pragma unroll
         for (int kt = 0; kt < KB; ++kt) {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) dck[(size_t)(16 * kt + 4 * g + e) * a.dv_dim + col] = dS[kt][e];
             dSq[kt] = acc_to_quad<E>(dS[kt]);
+            *reinterpret_cast<Quad*>(dck + 16 * kt + 4 * g) = dSq[kt];
         }
         Quad dOq[4];
         floatx4 dOa[4];
@@ -581,8 +579,8 @@ __global__ __launch_bounds__(256) void bwd_assemble_kernel(BwdArgs<E> a)
     float sdot = 0.f;                                // <dS', S> over this thread's share
 
     // ---- first phase: everything that contracts over d_v, one slab of W columns at a time -----------
-    const float* Sg = a.s_chk + (size_t)blockIdx.x * DK * a.dv_dim;
-    const float* dSg = a.ds_chk + (size_t)blockIdx.x * DK * a.dv_dim;
+    const E* Sg = a.s_chk + (size_t)blockIdx.x * DK * a.dv_dim;
+    const E* dSg = a.ds_chk + (size_t)blockIdx.x * DK * a.dv_dim;
     for (int slab0 = 0; slab0 < a.dv_dim; slab0 += W) {
         __syncthreads();
 #pragma unroll
@@ -605,22 +603,21 @@ __global__ __launch_bounds__(256) void bwd_assemble_kernel(BwdArgs<E> a)
             store_rq_piece(reinterpret_cast<E*>(lds + A_GDX), NP, row, piece, scale_piece<E>(dy, -eg * be));
             yx[it] += dot_piece<E>(dy, dx);
         }
+        // S^T and dS'^T rows slab0 .. slab0 + W - 1 (d_k elements each) -> operands contracted over d_v
 #pragma unroll
-        for (int it = 0; it < DK * 8 / 256; ++it) {
-            const int pi = tid + 256 * it, row = pi >> 3, piece = pi & 7;
-            const float* sp = Sg + (size_t)row * a.dv_dim + slab0 + piece * EPP;
-            const float* dp = dSg + (size_t)row * a.dv_dim + slab0 + piece * EPP;
-            float fs[EPP], fd[EPP];
+        for (int it = 0; it < (W / 4 * PPR + 255) / 256; ++it) {
+            const int u = tid + 256 * it, tq = u / PPR, piece = u % PPR;
+            if ((W / 4 * PPR) % 256 != 0 && u >= W / 4 * PPR) break;
+            uint4 sd[4], dd[4];
 #pragma unroll
-            for (int i = 0; i < EPP; i += 4) {
-                const float4 x = *reinterpret_cast<const float4*>(sp + i), y = *reinterpret_cast<const float4*>(dp + i);
-                fs[i] = x.x; fs[i + 1] = x.y; fs[i + 2] = x.z; fs[i + 3] = x.w;
-                fd[i] = y.x; fd[i + 1] = y.y; fd[i + 2] = y.z; fd[i + 3] = y.w;
+            for (int rr = 0; rr < 4; ++rr) {
+                const size_t off = (size_t)(slab0 + 4 * tq + rr) * DK + piece * EPP;
+                sd[rr] = *reinterpret_cast<const uint4*>(Sg + off);
+                dd[rr] = *reinterpret_cast<const uint4*>(dSg + off);
+                sdot += dot_piece<E>(sd[rr], dd[rr]);
             }
-#pragma unroll
-            for (int i = 0; i < EPP; ++i) sdot += fs[i] * fd[i];
-            store_rq_piece(reinterpret_cast<E*>(lds + B_S), NP, row, piece, Piece<E>::pack(fs));
-            store_rq_piece(reinterpret_cast<E*>(lds + B_DS), NP, row, piece, Piece<E>::pack(fd));
+            store_tq_rows(reinterpret_cast<E*>(lds + B_S), NP, tq, piece, sd, 0);
+            store_tq_rows(reinterpret_cast<E*>(lds + B_DS), NP, tq, piece, dd, 0);
         }
         __syncthreads();
 #pragma unroll

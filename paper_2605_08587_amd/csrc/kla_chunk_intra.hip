@@ -81,7 +81,7 @@ __device__ __forceinline__ void write_tri(char* out, const float* m, const float
 }  // namespace
 
 // BWD = false: the forward's records [T' | P | three vectors].  BWD = true: the records of the backward pass,
-// [M | M^T | P^T | gamma_i | gamma_C/gamma_i | beta_i | 1/(||k_i||^2+eps)] with M = (I + L)^{-1}; the transposes are stored as the
+// [T' | M^T | P^T | gamma_i | gamma_C/gamma_i | beta_i | 1/(||k_i||^2+eps)] with M = (I + L)^{-1}, T' = M B; the transposes are stored as the
 // 6 upper-triangular tile-pairs (see bwd_record_bytes in kla_mma.hpp).
 template <typename E, int DK, bool BWD>
 __global__ __launch_bounds__(256) void intra_kernel(IntraArgs<E> a)
@@ -293,11 +293,11 @@ __global__ __launch_bounds__(256) void intra_kernel(IntraArgs<E> a)
     }
     __syncthreads();
 
-    // ---- phase 6: T' = T diag(beta) (forward) or T and T^T (backward) -> workspace in operand order ------------
+    // ---- phase 6: T' = T diag(beta) (and T^T for the backward) -> workspace in operand order ------------------
     {
         char* out = reinterpret_cast<char*>(a.wsT) + (size_t)blockIdx.x * REC;
         if constexpr (BWD) {
-            write_tri<E, false, false>(out, Tm, nullptr, tid);
+            write_tri<E, false, true>(out, Tm, beta_s, tid);
             write_tri<E, true, false>(out + ws_half_bytes<E>(), Tm, nullptr, tid);
         } else {
             write_tri<E, false, true>(out, Tm, beta_s, tid);

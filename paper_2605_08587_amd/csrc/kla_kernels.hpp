@@ -66,10 +66,11 @@ hipError_t launch_segment_gather(const float* seg_state, float* hT, int N, int H
 
 // ---- chunkwise backward (gradient of sum <d_o, o> + sum <d_hT, hT>) ----------------------------------
 // Stage 1 (launch_intra_bwd) leaves one record per chunk-head at `rec`.  Stage 2 walks every (sequence, head)
-// forward and leaves, per chunk, the incoming state S_c (fp32, [chunk-head][dk][dv]) and the rows X = V - D_gamma K S_c
-// and U = M B X of eq. (6) (element type, laid out like v).  Stage 3 walks backward and leaves the gradient dS'_c of
-// the state each chunk hands on, Y = M^T dU (laid out like v), and writes dv = B Y and dh0.  Stage 4 contracts those
-// over d_v per chunk-head and writes dq, dk, dlog_alpha, deta.
+// forward and leaves, per chunk, the incoming state S_c and the rows X = V - D_gamma K S_c and U = T' X of eq. (6).
+// Stage 3 walks backward and leaves the gradient dS'_c of the state each chunk hands on and Y = M^T dU, and writes
+// dv = B Y and dh0.  Stage 4 contracts those over d_v per chunk-head and writes dq, dk, dlog_alpha, deta.
+// X, U, Y are laid out like v.  The state checkpoints are stored transposed and in the element type:
+// [chunk-head][d_v][d_k], because stage 4 uses them only as MFMA operands contracted over d_v.
 template <typename E> struct BwdArgs {
     const E* q; const E* k; const E* v;
     const float* log_alpha; const float* eta; float eps;
@@ -78,7 +79,7 @@ template <typename E> struct BwdArgs {
     const int* cu_seqlens; const int* chunk_off; int n_seq;
     int N, T, NT, H, dv_dim;
     const char* rec;                 // stage-1 records
-    float* s_chk; float* ds_chk;     // [n_chunks * H][dk][dv]
+    E* s_chk; E* ds_chk;             // [n_chunks * H][dv][dk]
     E* X; E* U; E* Y;                // [tokens][H][dv]
 };
 template <typename E> hipError_t launch_bwd_states(const BwdArgs<E>& a, int dk, int waves, hipStream_t st);
