@@ -236,8 +236,19 @@ int chunk_bwd_impl(const void* q, const void* k, const void* v, const float* log
     // two waves (32 state columns) per workgroup once that still gives a workgroup per CU
     const long chains8 = ((long)pl.base.n_states * H + 7) / 8 * 8;
     const int waves = (chains8 * (dv / 32) >= 192) ? 2 : 1;
-    if (kla::launch_bwd_states<E>(ba, dk, waves, st) != hipSuccess) return KLA_ERR_HIP;
-    if (kla::launch_bwd_scan<E>(ba, dk, waves, st) != hipSuccess) return KLA_ERR_HIP;
+    bool swept = false;
+    if constexpr (sizeof(E) == 2) {
+        const char* impl = getenv("KLA_BWD_IMPL");    // "generic": the element-type-generic sweeps (A/B testing)
+        if (!(impl && impl[0] == 'g')) {
+            if (kla::launch_bwd_states_bf16(ba, dk, waves, st) != hipSuccess) return KLA_ERR_HIP;
+            if (kla::launch_bwd_scan_bf16(ba, dk, waves, st) != hipSuccess) return KLA_ERR_HIP;
+            swept = true;
+        }
+    }
+    if (!swept) {
+        if (kla::launch_bwd_states<E>(ba, dk, waves, st) != hipSuccess) return KLA_ERR_HIP;
+        if (kla::launch_bwd_scan<E>(ba, dk, waves, st) != hipSuccess) return KLA_ERR_HIP;
+    }
     if (kla::launch_bwd_assemble<E>(ba, dk, pl.base.n_chunks, st) != hipSuccess) return KLA_ERR_HIP;
     return KLA_OK;
 }

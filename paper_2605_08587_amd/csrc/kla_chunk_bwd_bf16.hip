@@ -1,0 +1,401 @@
+// bf16 state sweeps of the backward pass (see kla_chunk_bwd.hip for the algebra and for what each sweep leaves
+// behind), built like the forward's bf16 scan kernel (kla_chunk_scan_bf16.hip): operands travel global -> LDS
+// directly through a ring of stages filled by a copy wave, K and Q sit as swizzled token-major rows, the
+// contraction-along-a-column operands (K^T, Q^T, the V / dO tile) come from the transposing LDS read, and the
+// fp32 state (or state gradient) of 16 columns per wave stays in MFMA accumulators with the permuted feature
+// index of that kernel: element e of lane (r, g) of tile kt = 2 kp + b is feature 32 kp + 8 g + 4 b + e.
+//
+//   REV = false   forward sweep:  X = V - D_gamma K S,  U = T' X,  S <- gamma_C S + K^T diag(gamma_C/gamma_i) U;
+//                 leaves S_c (before the chunk), X and U.
+//   REV = true    backward sweep: dU = P^T dO + diag(gamma_C/gamma_i) K dS',  Y = M^T dU,  dV = B Y,
+//                 dS <- gamma_C dS' + Q^T D_gamma dO - K^T D_gamma dV;  leaves dS'_c, Y, dV and finally dh0.
+//
+// A short last chunk re-reads its last valid row for the rows beyond it (as in the forward).  Those rows have
+// beta = 0, zero rows and columns in T' and P^T and unit rows in M, so they reach neither U, Y (valid rows), dV nor
+// the state; the one place where they would, Q^T D_gamma dO, has their gamma masked to zero.
+#include "kla_bf16_ops.hpp"
+#include "kla_common.hpp"
+#include "kla_kernels.hpp"
+#include "kla_mma.hpp"
+
+namespace kla {
+
+namespace {
+
+template <int DK, int NW, bool REV>
+struct SweepCfg16 {
+    static constexpr int NTH = 64 * NW;                  // compute threads (the workgroup has one more wave)
+    static constexpr int KB = DK / 16, KP = DK / 32;
+    static constexpr int SLW = 16 * NW;                  // state columns per workgroup
+    static constexpr int RB = DK * 2;                    // bytes per K/Q row
+    static constexpr int PPR = DK / 8;                   // 16-byte pieces per K/Q row
+    static constexpr int RPB = 1024 / RB;                // K/Q rows per 1 KiB copy block
+    static constexpr int NKB = 64 / RPB;                 // copy blocks of a K (or Q) tile
+    static constexpr int VRW = SLW * 2;                  // bytes per row of the V / dO slice
+    static constexpr int VPP = VRW / 16;
+    static constexpr int RPV = 64 / VPP;
+    static constexpr int NVB = 64 / RPV;
+    static constexpr int TPB = kTriPairs * 64 * 16;      // bytes of one triangular operand area
+    static constexpr int NTB = (REV ? 2 : 1) * TPB / 1024;   // forward: T'; backward: M^T | P^T
+    // stage: K rows | (Q rows) | T'  or  M^T | P^T | V or dO slice | gamma_i | gamma_C/gamma_i | beta_i
+    static constexpr int OFF_Q = 64 * RB;
+    static constexpr int OFF_T = (REV ? 2 : 1) * 64 * RB, OFF_P = OFF_T + TPB, OFF_V = OFF_T + (REV ? 2 : 1) * TPB,
+                         OFF_EG = OFF_V + 64 * VRW, STAGE = OFF_EG + 768;
+    static constexpr int ORB = NW <= 2 ? 96 : 160;       // row stride of a staging tile (see the forward kernel)
+    static constexpr int OSB = 64 * ORB;
+    static constexpr int NST = (3 * STAGE + 4 * OSB <= 160 * 1024) ? 3 : 2;   // LDS ring depth
+    static constexpr int LDS = NST * STAGE + 4 * OSB;    // two staged tiles per chunk, two parities
+    static constexpr int NDMA = (REV ? 2 : 1) * NKB + NTB + NVB + 1;
+    static_assert(LDS <= 160 * 1024 && NDMA < 64, "LDS budget of a gfx950 CU; 6-bit vmcnt");
+};
+
+}  // namespace
+
+template <int DK, int NW, bool REV>
+__global__ __launch_bounds__(64 * NW + 64) void bwd_sweep_bf16_kernel(BwdArgs<bf16_t> a)
+{
+    typedef SweepCfg16<DK, NW, REV> C;
+    constexpr int NTH = C::NTH, KB = C::KB, KP = C::KP, SLW = C::SLW, RB = C::RB, PPR = C::PPR, RPB = C::RPB,
+                  VRW = C::VRW, VPP = C::VPP, RPV = C::RPV, ORB = C::ORB, NST = C::NST;
+
+    __shared__ __attribute__((aligned(1024))) char lds[C::LDS];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int r = lane & 15, g = lane >> 4;
+
+    const int nsl = a.dv_dim / SLW;
+    const int n_states = a.n_seq > 0 ? a.n_seq : a.N;
+    const int xcd = blockIdx.x & 7, pidx = blockIdx.x >> 3;
+    const int chain = (pidx / nsl) * 8 + xcd, slice = pidx % nsl;
+    if (chain >= n_states * a.H) return;
+    const int s = chain / a.H, h = chain % a.H;
+    long t0; int len, ch0;
+    if (a.cu_seqlens) { t0 = a.cu_seqlens[s]; len = a.cu_seqlens[s + 1] - (int)t0; ch0 = a.chunk_off[s]; }
+    else              { t0 = (long)s * a.T;   len = a.T;                           ch0 = s * a.NT; }
+    const int nch = (len + 63) / 64;
+    const int col = slice * SLW + 16 * wave + r;
+
+    // forward: the state; backward: its gradient
+    const float* init = REV ? a.d_hT : a.h0;
+    floatx4 S[KB];
+#pragma unroll
+    for (int kt = 0; kt < KB; ++kt)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int f = 32 * (kt >> 1) + 8 * g + 4 * (kt & 1) + e;
+            S[kt][e] = (init && wave < NW) ? init[((size_t)chain * DK + f) * a.dv_dim + col] : 0.f;   // not the copy wave
+        }
+
+    const size_t kq_row = (size_t)a.H * DK * 2, v_row = (size_t)a.H * a.dv_dim * 2;     // bytes between tokens
+    const char* kbase = reinterpret_cast<const char*>(a.k) + (size_t)t0 * kq_row + (size_t)h * DK * 2;
+    const char* qbase = reinterpret_cast<const char*>(a.q) + (size_t)t0 * kq_row + (size_t)h * DK * 2;
+    const char* vbase = reinterpret_cast<const char*>(REV ? a.d_o : a.v) + (size_t)t0 * v_row + ((size_t)h * a.dv_dim + slice * SLW) * 2;
+    constexpr int REC = bwd_record_bytes<bf16_t>();
+    const char* tpbase = a.rec + ((size_t)ch0 * a.H + h) * REC;
+
+    // ---- loop-invariant per-lane offsets (as in the forward kernel) -----------------------------------
+    const int lrow = lane / PPR, pcol = lane % PPR;
+    int gk[2];
+#pragma unroll
+    for (int par = 0; par < 2; ++par)
+        gk[par] = lrow * (int)kq_row + ((pcol ^ swz_bits(RPB * par + lrow)) * 16);
+    const int gv = (lane / VPP) * (int)v_row + (lane % VPP) * 16;
+    int oK[2];
+#pragma unroll
+    for (int par = 0; par < 2; ++par) oK[par] = r * RB + (((4 * par + g) ^ swz_bits(r)) * 16);
+    const int a4 = r >> 2, c4 = r & 3;
+    int oKT[2];
+#pragma unroll
+    for (int par = 0; par < 2; ++par) oKT[par] = (4 * g + a4) * RB + (((4 * par + c4) ^ swz_bits(4 * g + a4)) * 16);
+    const int oV = (4 * g + a4) * VRW + (16 * wave + 4 * c4) * 2;
+    const int oO = (4 * g + (r & 3)) * ORB + (16 * wave + 4 * (r >> 2)) * 2;
+    const bool q_lo = (r & 3) < 2;
+    const uint32_t psel = (r & 1) ? 0x03020706u : 0x05040100u;
+
+    // ---- global -> LDS copy of everything chunk c needs ---------------------------------------------------
+    auto issue = [&](int c, char* st) {
+        const int clen = min(64, len - 64 * c);
+        const char* kc = kbase + (size_t)(64 * c) * kq_row;
+        const char* qc = qbase + (size_t)(64 * c) * kq_row;
+        const char* vc = vbase + (size_t)(64 * c) * v_row;
+        const char* tc = tpbase + (size_t)c * a.H * REC;
+        if (clen == 64) {
+            static_for<C::NKB>([&](auto i) {
+                const int b = i;
+                const size_t o = (size_t)(b * RPB) * kq_row;
+                const int lo = (RPB == 4 && (b & 1)) ? gk[1] : gk[0];
+                dma16(kc + o, lo, st + b * 1024);
+                if constexpr (REV) dma16(qc + o, lo, st + C::OFF_Q + b * 1024);
+            });
+            static_for<C::NVB>([&](auto i) {
+                const int b = i;
+                dma16(vc + (size_t)(b * RPV) * v_row, gv, st + C::OFF_V + b * 1024);
+            });
+        } else {                                         // ragged last chunk: clamp the row
+            static_for<C::NKB>([&](auto i) {
+                const int b = i;
+                const int row = b * RPB + lrow;
+                const int lo = min(row, clen - 1) * (int)kq_row + ((pcol ^ swz_bits(row)) * 16);
+                dma16(kc, lo, st + b * 1024);
+                if constexpr (REV) dma16(qc, lo, st + C::OFF_Q + b * 1024);
+            });
+            static_for<C::NVB>([&](auto i) {
+                const int b = i;
+                const int row = b * RPV + lane / VPP;
+                dma16(vc, min(row, clen - 1) * (int)v_row + (lane % VPP) * 16, st + C::OFF_V + b * 1024);
+            });
+        }
+        // forward: T' (first half of the record); backward: M^T | P^T (second and third)
+        static_for<C::NTB>([&](auto i) {
+            const int b = i;
+            dma16(tc + (REV ? C::TPB : 0) + b * 1024, lane * 16, st + C::OFF_T + b * 1024);
+        });
+        if (lane < 48) dma16(tc + 3 * C::TPB, lane * 16, st + C::OFF_EG);   // gamma_i | gamma_C/gamma_i | beta_i
+    };
+
+    // 4x4 transposition inside each quad of lanes (see the forward kernel), then one 64-bit write: lane (r, g)
+    // ends up with row 4 g + (r & 3), columns 4 (r >> 2) .. + 3 of the wave's 16
+    auto stage_quad = [&](u32x2 ob, char* dst) {
+        const uint32_t snd = q_lo ? ob.y : ob.x;
+        const uint32_t rcv = (uint32_t)__builtin_amdgcn_mov_dpp((int)snd, 0x4E, 0xf, 0xf, true);
+        if (q_lo) ob.y = rcv; else ob.x = rcv;
+        const uint32_t px = (uint32_t)__builtin_amdgcn_mov_dpp((int)ob.x, 0xB1, 0xf, 0xf, true);
+        const uint32_t py = (uint32_t)__builtin_amdgcn_mov_dpp((int)ob.y, 0xB1, 0xf, 0xf, true);
+        ob.x = __builtin_amdgcn_perm(px, ob.x, psel);
+        ob.y = __builtin_amdgcn_perm(py, ob.y, psel);
+        *reinterpret_cast<u32x2*>(dst) = ob;
+    };
+
+    // ---- one chunk for this wave's 16 columns -----------------------------------------------------------
+    auto compute = [&](const char* st, char* ost, int c) {
+        const char* pK0 = st + oK[0];
+        const char* pK1 = st + oK[1];
+        const char* pT0 = st + oKT[0];
+        const char* pT1 = st + oKT[1];
+        const char* pS = st + lane * 16;
+        const char* pV = st + C::OFF_V + oV;
+        const char* pG = st + C::OFF_EG + 16 * g;
+        auto kslot = [&](int it, int kp) {
+            return ld16(((kp & 1) ? pK1 : pK0) + 16 * it * RB + 128 * (kp >> 1));
+        };
+        auto ktslot = [&](int kt, int jp, int base, u32x2& q0, u32x2& q1) {      // base 0: K^T, OFF_Q: Q^T
+            const int kp = kt >> 1, b = kt & 1;
+            const char* p = ((kp & 1) ? pT1 : pT0) + base + 32 * jp * RB + 128 * (kp >> 1) + 8 * b;
+            q0 = lds_read_tr(p);
+            q1 = lds_read_tr(p + 16 * RB);
+        };
+
+        const float gC = *reinterpret_cast<const float*>(st + C::OFF_EG + 63 * 4);
+        u32x2 Sq[KB];
+#pragma unroll
+        for (int kt = 0; kt < KB; ++kt) { Sq[kt] = to_quad(S[kt]); S[kt] = S[kt] * gC; }
+        {   // checkpoint, transposed: features 32 kp + 8 g .. + 7 of column `col` are 16 contiguous bytes
+            bf16_t* ck = (REV ? a.ds_chk : a.s_chk) + (((size_t)(ch0 + c) * a.H + h) * a.dv_dim + col) * DK + 8 * g;
+#pragma unroll
+            for (int kp = 0; kp < KP; ++kp) {
+                const u32x4 w = {Sq[2 * kp].x, Sq[2 * kp].y, Sq[2 * kp + 1].x, Sq[2 * kp + 1].y};
+                st16(ck + 32 * kp, w);
+            }
+        }
+
+        // ---- K S or K dS'
+        floatx4 ks[4];
+#pragma unroll
+        for (int it = 0; it < 4; ++it) ks[it] = floatx4{0.f, 0.f, 0.f, 0.f};
+        u32x4 ka[2][4];
+#pragma unroll
+        for (int it = 0; it < 4; ++it) ka[0][it] = kslot(it, 0);
+#pragma unroll
+        for (int kp = 0; kp < KP; ++kp) {
+            if (kp + 1 < KP) {
+#pragma unroll
+                for (int it = 0; it < 4; ++it) ka[(kp + 1) & 1][it] = kslot(it, kp + 1);
+            }
+#pragma unroll
+            for (int it = 0; it < 4; ++it) mma_bf16(ks[it], ka[kp & 1][it], Sq[2 * kp], Sq[2 * kp + 1]);
+        }
+        u32x2 vq[4];
+        floatx4 egv[4], edv[4];
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            vq[it] = lds_read_tr(pV + 16 * it * VRW);
+            egv[it] = ld_f4(pG + 64 * it);
+            edv[it] = ld_f4(pG + 256 + 64 * it);
+        }
+        u32x4 tsl[kTriPairs];
+#pragma unroll
+        for (int i = 0; i < kTriPairs; ++i) tsl[i] = ld16(pS + C::OFF_T + i * 1024);
+        u32x2 kt[2][KB][2];                              // [token pair jp][state tile][token block]
+
+        if constexpr (!REV) {
+            u32x2 Xq[4];
+#pragma unroll
+            for (int it = 0; it < 4; ++it) {
+                Xq[it] = to_quad(quad_to_f(vq[it]) - egv[it] * ks[it]);       // eq. (6), right-hand side without B
+                stage_quad(Xq[it], ost + oO + 16 * it * ORB);
+            }
+#pragma unroll
+            for (int t = 0; t < KB; ++t) ktslot(t, 0, 0, kt[0][t][0], kt[0][t][1]);
+            floatx4 U[4];
+#pragma unroll
+            for (int it = 0; it < 4; ++it) {
+                U[it] = floatx4{0.f, 0.f, 0.f, 0.f};
+                mma_bf16(U[it], tsl[tri_pair(it, 0)], Xq[0], Xq[1]);
+            }
+            mma_bf16(U[2], tsl[tri_pair(2, 1)], Xq[2], Xq[3]);
+            mma_bf16(U[3], tsl[tri_pair(3, 1)], Xq[2], Xq[3]);
+#pragma unroll
+            for (int t = 0; t < KB; ++t) ktslot(t, 1, 0, kt[1][t][0], kt[1][t][1]);
+            u32x2 Udq[4];
+#pragma unroll
+            for (int it = 0; it < 4; ++it) {
+                Udq[it] = to_quad(U[it] * edv[it]);
+                stage_quad(to_quad(U[it]), ost + C::OSB + oO + 16 * it * ORB);
+            }
+#pragma unroll
+            for (int t = 0; t < KB; ++t) mma_bf16(S[t], kt[0][t][0], kt[0][t][1], Udq[0], Udq[1]);
+#pragma unroll
+            for (int t = 0; t < KB; ++t) mma_bf16(S[t], kt[1][t][0], kt[1][t][1], Udq[2], Udq[3]);
+        } else {
+            const int clen = min(64, len - 64 * c);
+            u32x4 psl[kTriPairs];
+#pragma unroll
+            for (int i = 0; i < kTriPairs; ++i) psl[i] = ld16(pS + C::OFF_P + i * 1024);
+            // ---- dU = diag(gamma_C/gamma_i) K dS' + P^T dO   (P^T upper triangular)
+            floatx4 dU[4];
+#pragma unroll
+            for (int it = 0; it < 4; ++it) dU[it] = edv[it] * ks[it];
+            mma_bf16(dU[0], psl[triu_pair(0, 0)], vq[0], vq[1]);
+            mma_bf16(dU[1], psl[triu_pair(1, 0)], vq[0], vq[1]);
+#pragma unroll
+            for (int it = 0; it < 4; ++it) mma_bf16(dU[it], psl[triu_pair(it, 1)], vq[2], vq[3]);
+            u32x2 dUq[4];
+#pragma unroll
+            for (int it = 0; it < 4; ++it) dUq[it] = to_quad(dU[it]);
+#pragma unroll
+            for (int t = 0; t < KB; ++t) ktslot(t, 0, C::OFF_Q, kt[0][t][0], kt[0][t][1]);
+            // ---- Y = M^T dU
+            floatx4 Y[4];
+#pragma unroll
+            for (int it = 0; it < 4; ++it) Y[it] = floatx4{0.f, 0.f, 0.f, 0.f};
+            mma_bf16(Y[0], tsl[triu_pair(0, 0)], dUq[0], dUq[1]);
+            mma_bf16(Y[1], tsl[triu_pair(1, 0)], dUq[0], dUq[1]);
+#pragma unroll
+            for (int it = 0; it < 4; ++it) mma_bf16(Y[it], tsl[triu_pair(it, 1)], dUq[2], dUq[3]);
+#pragma unroll
+            for (int t = 0; t < KB; ++t) ktslot(t, 1, C::OFF_Q, kt[1][t][0], kt[1][t][1]);
+            u32x2 gdOq[4], gdXq[4];
+#pragma unroll
+            for (int it = 0; it < 4; ++it) {
+                const floatx4 dx = Y[it] * ld_f4(pG + 512 + 64 * it);           // dV = B Y
+                stage_quad(to_quad(Y[it]), ost + oO + 16 * it * ORB);
+                stage_quad(to_quad(dx), ost + C::OSB + oO + 16 * it * ORB);
+                floatx4 eg = egv[it];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) eg[e] = (16 * it + 4 * g + e < clen) ? eg[e] : 0.f;   // rows past a ragged end
+                gdOq[it] = to_quad(eg * quad_to_f(vq[it]));
+                gdXq[it] = to_quad(-(eg * dx));
+            }
+            // ---- dS = gamma_C dS' + Q^T D_gamma dO - K^T D_gamma dV
+#pragma unroll
+            for (int t = 0; t < KB; ++t) mma_bf16(S[t], kt[0][t][0], kt[0][t][1], gdOq[0], gdOq[1]);
+#pragma unroll
+            for (int t = 0; t < KB; ++t) mma_bf16(S[t], kt[1][t][0], kt[1][t][1], gdOq[2], gdOq[3]);
+#pragma unroll
+            for (int t = 0; t < KB; ++t) ktslot(t, 0, 0, kt[0][t][0], kt[0][t][1]);
+#pragma unroll
+            for (int t = 0; t < KB; ++t) ktslot(t, 1, 0, kt[1][t][0], kt[1][t][1]);
+#pragma unroll
+            for (int t = 0; t < KB; ++t) mma_bf16(S[t], kt[0][t][0], kt[0][t][1], gdXq[0], gdXq[1]);
+#pragma unroll
+            for (int t = 0; t < KB; ++t) mma_bf16(S[t], kt[1][t][0], kt[1][t][1], gdXq[2], gdXq[3]);
+        }
+    };
+
+    // the two staged tiles of chunk c -> global (forward: X, U; backward: Y, dV), 16 bytes per lane
+    auto write_out = [&](int c, const char* ost) {
+        const int clen = min(64, len - 64 * c);
+        const size_t off = (size_t)(t0 + 64L * c) * v_row + ((size_t)h * a.dv_dim + slice * SLW) * 2;
+        char* o0 = reinterpret_cast<char*>(REV ? a.Y : a.X) + off;
+        char* o1 = reinterpret_cast<char*>(REV ? a.dv : a.U) + off;
+#pragma unroll
+        for (int it = 0; it < 64 * VPP / NTH; ++it) {
+            const int i = tid + NTH * it;
+            const int row = i / VPP, pv = i % VPP;
+            if (row < clen) {
+                st16(o0 + (size_t)row * v_row + pv * 16, ld16(ost + row * ORB + pv * 16));
+                st16(o1 + (size_t)row * v_row + pv * 16, ld16(ost + C::OSB + row * ORB + pv * 16));
+            }
+        }
+    };
+
+    char* ost0 = lds + NST * C::STAGE;
+    char* ost1 = ost0 + 2 * C::OSB;
+    // chunks are visited in the order i = 0 .. nch-1; the backward sweep starts at the last chunk
+    auto chunk_of = [&](int i) { return REV ? nch - 1 - i : i; };
+
+    if (wave == NW) {
+        // ---- the copy wave: keeps the next NST-1 chunks on their way while one is computed -----------------
+#pragma unroll
+        for (int p = 0; p < NST - 1; ++p)
+            if (p < nch) issue(chunk_of(p), lds + p * C::STAGE);
+        if (NST == 3 && nch > 1) wait_vmcnt<C::NDMA>(); else wait_vmcnt<0>();
+        __syncthreads();
+        int spre = NST - 1;
+        for (int i = 0; i < nch; ++i) {
+            const bool ahead = i + NST - 1 < nch;
+            if (ahead) issue(chunk_of(i + NST - 1), lds + spre * C::STAGE);
+            if (NST == 3 && ahead) wait_vmcnt<C::NDMA>(); else wait_vmcnt<0>();
+            __syncthreads();
+            spre = (spre + 1 == NST) ? 0 : spre + 1;
+        }
+        return;
+    }
+
+    // ---- compute waves (same barrier discipline as the forward kernel) --------------------------------------
+    __syncthreads();
+    int scur = 0;
+    for (int i = 0; i < nch; ++i) {
+        const int c = chunk_of(i);
+        char* ost = (i & 1) ? ost1 : ost0;
+        compute(lds + scur * C::STAGE, ost, c);
+        __syncthreads();
+        write_out(c, ost);
+        scur = (scur + 1 == NST) ? 0 : scur + 1;
+    }
+
+    if (REV && a.dh0) {
+#pragma unroll
+        for (int kt = 0; kt < KB; ++kt)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int f = 32 * (kt >> 1) + 8 * g + 4 * (kt & 1) + e;
+                a.dh0[((size_t)chain * DK + f) * a.dv_dim + col] = S[kt][e];
+            }
+    }
+}
+
+template <int DK, bool REV>
+static hipError_t launch_sweep_dk(const BwdArgs<bf16_t>& a, int waves, hipStream_t st)
+{
+    const int n_chains = (a.n_seq > 0 ? a.n_seq : a.N) * a.H;
+    if (n_chains == 0) return hipSuccess;
+    const dim3 grid((unsigned)(((n_chains + 7) / 8) * 8 * (a.dv_dim / (16 * waves))));
+    if (waves == 1) hipLaunchKernelGGL((bwd_sweep_bf16_kernel<DK, 1, REV>), grid, dim3(128), 0, st, a);
+    else            hipLaunchKernelGGL((bwd_sweep_bf16_kernel<DK, 2, REV>), grid, dim3(192), 0, st, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_bwd_states_bf16(const BwdArgs<bf16_t>& a, int dk, int waves, hipStream_t st)
+{
+    if (waves != 1 && waves != 2) return hipErrorInvalidValue;
+    return dk == 64 ? launch_sweep_dk<64, false>(a, waves, st) : launch_sweep_dk<128, false>(a, waves, st);
+}
+hipError_t launch_bwd_scan_bf16(const BwdArgs<bf16_t>& a, int dk, int waves, hipStream_t st)
+{
+    if (waves != 1 && waves != 2) return hipErrorInvalidValue;
+    return dk == 64 ? launch_sweep_dk<64, true>(a, waves, st) : launch_sweep_dk<128, true>(a, waves, st);
+}
+
+}  // namespace kla
