@@ -462,14 +462,6 @@ template <> struct Piece<float> {
         return make_uint4(__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]), __float_as_uint(f[3]));
     }
 };
-template <typename E> __device__ __forceinline__ uint4 scale_piece(uint4 d, float s)
-{
-    float f[Piece<E>::N];
-    Piece<E>::unpack(d, f);
-#pragma unroll
-    for (int i = 0; i < Piece<E>::N; ++i) f[i] *= s;
-    return Piece<E>::pack(f);
-}
 template <typename E> __device__ __forceinline__ float dot_piece(uint4 x, uint4 y)
 {
     float fx[Piece<E>::N], fy[Piece<E>::N];
@@ -512,7 +504,7 @@ __device__ __forceinline__ float row16_sum(float x)       // sum over the 16 lan
 }  // namespace
 
 template <typename E, int DK>
-__global__ __launch_bounds__(256) void bwd_assemble_kernel(BwdArgs<E> a)
+__global__ __launch_bounds__(256, 2) void bwd_assemble_kernel(BwdArgs<E> a)
 {
     constexpr int KB = DK / 16;
     constexpr int W = 128 / (int)sizeof(E);          // d_v columns per slab: 8 pieces of 16 bytes per row
@@ -523,9 +515,9 @@ __global__ __launch_bounds__(256) void bwd_assemble_kernel(BwdArgs<E> a)
     constexpr int BB = DK * W * (int)sizeof(E);      // a [dk, slab] operand area
     constexpr int OPB = 64 * DK * (int)sizeof(E);
     constexpr int MB = 64 * kLdc * 4;
-    // first phase: dO | gamma dO | U | (gamma_C/gamma) U | Y | -gamma beta Y | S | dS'
-    constexpr int A_DO = 0, A_GDO = AB, A_U = 2 * AB, A_EDU = 3 * AB, A_Y = 4 * AB, A_GDX = 5 * AB, B_S = 6 * AB, B_DS = 6 * AB + BB;
-    constexpr int PH1 = 6 * AB + 2 * BB;
+    // first phase: dO | U | Y | S^T | dS'^T
+    constexpr int A_DO = 0, A_U = AB, A_Y = 2 * AB, B_S = 3 * AB, B_DS = 3 * AB + BB;
+    constexpr int PH1 = 3 * AB + 2 * BB;
     // second phase: K transposed | Q transposed | A o dP | D'
     constexpr int C_KT = 0, C_QT = OPB, C_E1 = 2 * OPB, C_DP = 2 * OPB + MB;
     constexpr int PH2 = 2 * OPB + 2 * MB;
@@ -594,13 +586,9 @@ __global__ __launch_bounds__(256) void bwd_assemble_kernel(BwdArgs<E> a)
                 dy = *reinterpret_cast<const uint4*>(a.Y + off);
                 dx = *reinterpret_cast<const uint4*>(a.X + off);
             }
-            const float eg = eg_s[row], ed = ed_s[row], be = beta_s[row];
             store_rq_piece(reinterpret_cast<E*>(lds + A_DO), NP, row, piece, d_o);
-            store_rq_piece(reinterpret_cast<E*>(lds + A_GDO), NP, row, piece, scale_piece<E>(d_o, eg));
             store_rq_piece(reinterpret_cast<E*>(lds + A_U), NP, row, piece, du);
-            store_rq_piece(reinterpret_cast<E*>(lds + A_EDU), NP, row, piece, scale_piece<E>(du, ed));
             store_rq_piece(reinterpret_cast<E*>(lds + A_Y), NP, row, piece, dy);
-            store_rq_piece(reinterpret_cast<E*>(lds + A_GDX), NP, row, piece, scale_piece<E>(dy, -eg * be));
             yx[it] += dot_piece<E>(dy, dx);
         }
         // S^T and dS'^T rows slab0 .. slab0 + W - 1 (d_k elements each) -> operands contracted over d_v
@@ -622,18 +610,17 @@ __global__ __launch_bounds__(256) void bwd_assemble_kernel(BwdArgs<E> a)
         __syncthreads();
 #pragma unroll
         for (int kp = 0; kp < NP; ++kp) {
+            // the row scalings D_gamma, -D_gamma B and diag(gamma_C/gamma_i) are applied to the sums afterwards
             const Slot<E> a_do = load_slot(reinterpret_cast<const E*>(lds + A_DO), wave * NP + kp, lane);
-            const Slot<E> a_gdo = load_slot(reinterpret_cast<const E*>(lds + A_GDO), wave * NP + kp, lane);
-            const Slot<E> a_edu = load_slot(reinterpret_cast<const E*>(lds + A_EDU), wave * NP + kp, lane);
+            const Slot<E> a_u = load_slot(reinterpret_cast<const E*>(lds + A_U), wave * NP + kp, lane);
             const Slot<E> a_y = load_slot(reinterpret_cast<const E*>(lds + A_Y), wave * NP + kp, lane);
-            const Slot<E> a_gdx = load_slot(reinterpret_cast<const E*>(lds + A_GDX), wave * NP + kp, lane);
 #pragma unroll
             for (int ct = 0; ct < KB; ++ct) {
                 const Slot<E> b_s = load_slot(reinterpret_cast<const E*>(lds + B_S), ct * NP + kp, lane);
                 const Slot<E> b_ds = load_slot(reinterpret_cast<const E*>(lds + B_DS), ct * NP + kp, lane);
-                mma32<E>(dQ[ct], a_gdo, b_s.q0, b_s.q1);       // D_gamma dO S^T
-                mma32<E>(dKr[ct], a_gdx, b_s.q0, b_s.q1);      // -D_gamma dX S^T
-                mma32<E>(dKw[ct], a_edu, b_ds.q0, b_ds.q1);    // diag(gamma_C/gamma_i) U dS'^T
+                mma32<E>(dQ[ct], a_do, b_s.q0, b_s.q1);        // dO S^T
+                mma32<E>(dKr[ct], a_y, b_s.q0, b_s.q1);        // Y S^T
+                mma32<E>(dKw[ct], a_u, b_ds.q0, b_ds.q1);      // U dS'^T
             }
             static_for<4>([&](auto jt) {
                 if (jt <= wave) {                              // lower-triangular tiles only
@@ -643,6 +630,12 @@ __global__ __launch_bounds__(256) void bwd_assemble_kernel(BwdArgs<E> a)
                 }
             });
         }
+    }
+    {   // D_gamma dO S^T,  -D_gamma dX S^T (dX = B Y),  diag(gamma_C/gamma_i) U dS'^T
+        const floatx4 egv = ld_acc4(eg_s + 16 * wave + 4 * g), edv = ld_acc4(ed_s + 16 * wave + 4 * g);
+        const floatx4 ngb = -(egv * ld_acc4(beta_s + 16 * wave + 4 * g));
+#pragma unroll
+        for (int ct = 0; ct < KB; ++ct) { dQ[ct] = dQ[ct] * egv; dKr[ct] = dKr[ct] * ngb; dKw[ct] = dKw[ct] * edv; }
     }
     // Y_i . X_i: the 8 threads of a row are neighbours
 #pragma unroll
