@@ -511,9 +511,10 @@ __global__ __launch_bounds__(256, 2) void bwd_assemble_kernel(BwdArgs<E> a)
     constexpr int NP = W / 32;                       // contraction pairs per slab
     constexpr int EPP = 16 / (int)sizeof(E);
     constexpr int PPR = DK * (int)sizeof(E) / 16;
-    constexpr int AB = 64 * W * (int)sizeof(E);      // a [64, slab] operand area: 8 KB
-    constexpr int BB = DK * W * (int)sizeof(E);      // a [dk, slab] operand area
-    constexpr int OPB = 64 * DK * (int)sizeof(E);
+    // operand areas are padded (one empty slot after every eight, see kla_mma.hpp): 9/8 of their contents
+    constexpr int AB = 64 * W * (int)sizeof(E) / 8 * 9;      // a [64, slab] operand area
+    constexpr int BB = DK * W * (int)sizeof(E) / 8 * 9;      // a [dk, slab] operand area
+    constexpr int OPB = 64 * DK * (int)sizeof(E) / 8 * 9;
     constexpr int MB = 64 * kLdc * 4;
     // first phase: dO | U | Y | S^T | dS'^T
     constexpr int A_DO = 0, A_U = AB, A_Y = 2 * AB, B_S = 3 * AB, B_DS = 3 * AB + BB;
@@ -586,9 +587,9 @@ __global__ __launch_bounds__(256, 2) void bwd_assemble_kernel(BwdArgs<E> a)
                 dy = *reinterpret_cast<const uint4*>(a.Y + off);
                 dx = *reinterpret_cast<const uint4*>(a.X + off);
             }
-            store_rq_piece(reinterpret_cast<E*>(lds + A_DO), NP, row, piece, d_o);
-            store_rq_piece(reinterpret_cast<E*>(lds + A_U), NP, row, piece, du);
-            store_rq_piece(reinterpret_cast<E*>(lds + A_Y), NP, row, piece, dy);
+            store_rq_piece_pad(reinterpret_cast<E*>(lds + A_DO), NP, row, piece, d_o);
+            store_rq_piece_pad(reinterpret_cast<E*>(lds + A_U), NP, row, piece, du);
+            store_rq_piece_pad(reinterpret_cast<E*>(lds + A_Y), NP, row, piece, dy);
             yx[it] += dot_piece<E>(dy, dx);
         }
         // S^T and dS'^T rows slab0 .. slab0 + W - 1 (d_k elements each) -> operands contracted over d_v
@@ -604,27 +605,27 @@ __global__ __launch_bounds__(256, 2) void bwd_assemble_kernel(BwdArgs<E> a)
                 dd[rr] = *reinterpret_cast<const uint4*>(dSg + off);
                 sdot += dot_piece<E>(sd[rr], dd[rr]);
             }
-            store_tq_rows(reinterpret_cast<E*>(lds + B_S), NP, tq, piece, sd, 0);
-            store_tq_rows(reinterpret_cast<E*>(lds + B_DS), NP, tq, piece, dd, 0);
+            store_tq_rows_pad(reinterpret_cast<E*>(lds + B_S), NP, tq, piece, sd, 0);
+            store_tq_rows_pad(reinterpret_cast<E*>(lds + B_DS), NP, tq, piece, dd, 0);
         }
         __syncthreads();
 #pragma unroll
         for (int kp = 0; kp < NP; ++kp) {
             // the row scalings D_gamma, -D_gamma B and diag(gamma_C/gamma_i) are applied to the sums afterwards
-            const Slot<E> a_do = load_slot(reinterpret_cast<const E*>(lds + A_DO), wave * NP + kp, lane);
-            const Slot<E> a_u = load_slot(reinterpret_cast<const E*>(lds + A_U), wave * NP + kp, lane);
-            const Slot<E> a_y = load_slot(reinterpret_cast<const E*>(lds + A_Y), wave * NP + kp, lane);
+            const Slot<E> a_do = load_slot_pad(reinterpret_cast<const E*>(lds + A_DO), wave * NP + kp, lane);
+            const Slot<E> a_u = load_slot_pad(reinterpret_cast<const E*>(lds + A_U), wave * NP + kp, lane);
+            const Slot<E> a_y = load_slot_pad(reinterpret_cast<const E*>(lds + A_Y), wave * NP + kp, lane);
 #pragma unroll
             for (int ct = 0; ct < KB; ++ct) {
-                const Slot<E> b_s = load_slot(reinterpret_cast<const E*>(lds + B_S), ct * NP + kp, lane);
-                const Slot<E> b_ds = load_slot(reinterpret_cast<const E*>(lds + B_DS), ct * NP + kp, lane);
+                const Slot<E> b_s = load_slot_pad(reinterpret_cast<const E*>(lds + B_S), ct * NP + kp, lane);
+                const Slot<E> b_ds = load_slot_pad(reinterpret_cast<const E*>(lds + B_DS), ct * NP + kp, lane);
                 mma32<E>(dQ[ct], a_do, b_s.q0, b_s.q1);        // dO S^T
                 mma32<E>(dKr[ct], a_y, b_s.q0, b_s.q1);        // Y S^T
                 mma32<E>(dKw[ct], a_u, b_ds.q0, b_ds.q1);      // U dS'^T
             }
             static_for<4>([&](auto jt) {
                 if (jt <= wave) {                              // lower-triangular tiles only
-                    const Slot<E> b_u = load_slot(reinterpret_cast<const E*>(lds + A_U), jt * NP + kp, lane);
+                    const Slot<E> b_u = load_slot_pad(reinterpret_cast<const E*>(lds + A_U), jt * NP + kp, lane);
                     mma32<E>(dP[jt], a_do, b_u.q0, b_u.q1);    // dO U^T
                     mma32<E>(N1[jt], a_y, b_u.q0, b_u.q1);     // Y U^T
                 }
@@ -669,8 +670,8 @@ __global__ __launch_bounds__(256, 2) void bwd_assemble_kernel(BwdArgs<E> a)
                     qd[rr] = *reinterpret_cast<const uint4*>(qb + (size_t)(4 * tq + rr) * kq_stride + piece * EPP);
                 }
             }
-            store_tq_rows(Ktq, 2, tq, piece, kd, 0);
-            store_tq_rows(Qtq, 2, tq, piece, qd, 0);
+            store_tq_rows_pad(Ktq, 2, tq, piece, kd, 0);
+            store_tq_rows_pad(Qtq, 2, tq, piece, qd, 0);
         }
         static_for<4>([&](auto jt) {
             const int j = 16 * jt + r;
@@ -688,7 +689,7 @@ __global__ __launch_bounds__(256, 2) void bwd_assemble_kernel(BwdArgs<E> a)
 
     // K and Q of this wave's rows in accumulator layout: rows 16 wave + 4 g + e, column 16 ct + r
     auto kacc = [&](const E* base, int ct) {
-        const Slot<E> s = load_slot(base, ct * 2 + (wave >> 1), lane);
+        const Slot<E> s = load_slot_pad(base, ct * 2 + (wave >> 1), lane);
         return quad_to_acc((wave & 1) ? s.q1 : s.q0);
     };
     // sum_i (gamma_C/gamma_i) k_i . (dS' U_i): the third bracket term alone, before the others are added to it
@@ -712,7 +713,7 @@ __global__ __launch_bounds__(256, 2) void bwd_assemble_kernel(BwdArgs<E> a)
             const Slot<E> a_dp = slot_from_rows<E>(Dp, row_a, jp, g);
 #pragma unroll
             for (int ct = 0; ct < KB; ++ct) {
-                const Slot<E> b_k = load_slot(Ktq, ct * 2 + jp, lane);
+                const Slot<E> b_k = load_slot_pad(Ktq, ct * 2 + jp, lane);
                 mma32<E>(dQ[ct], a_e1, b_k.q0, b_k.q1);        // (A o dP) K
                 mma32<E>(E2[ct], a_dp, b_k.q0, b_k.q1);        // D' K
             }
@@ -722,8 +723,8 @@ __global__ __launch_bounds__(256, 2) void bwd_assemble_kernel(BwdArgs<E> a)
             const Slot<E> a_dpt = slot_from_cols<E, true>(Dp, beta_s, row_a, jp, g);
 #pragma unroll
             for (int ct = 0; ct < KB; ++ct) {
-                const Slot<E> b_q = load_slot(Qtq, ct * 2 + jp, lane);
-                const Slot<E> b_k = load_slot(Ktq, ct * 2 + jp, lane);
+                const Slot<E> b_q = load_slot_pad(Qtq, ct * 2 + jp, lane);
+                const Slot<E> b_k = load_slot_pad(Ktq, ct * 2 + jp, lane);
                 mma32<E>(dKw[ct], a_e1t, b_q.q0, b_q.q1);      // (A o dP)^T Q
                 mma32<E>(dKw[ct], a_dpt, b_k.q0, b_k.q1);      // (B D')^T K
             }

@@ -104,6 +104,12 @@ __device__ __forceinline__ void mma32(floatx4& acc, const Slot<E>& a, typename Q
 }
 
 // ---- slot access --------------------------------------------------------------------------------
+// Padded areas (the *_pad functions): slot s sits at position s + s/8, i.e. one empty slot after every eight.
+// The stores below write one 8- or 16-byte part of many slots whose indices differ by multiples of 8; unpadded,
+// all of those fall into the same LDS banks.  An area of n slots needs pad_slots(n) slots of room.
+__host__ __device__ constexpr int pad_slots(int n) { return n + n / 8; }
+__device__ __forceinline__ size_t pad_pos(size_t slot) { return slot + (slot >> 3); }
+
 // Read the slot (tile-pair index tp, this lane) from an operand area in LDS.
 __device__ __forceinline__ Slot<bf16_t> load_slot(const bf16_t* base, int tp, int lane)
 {
@@ -164,6 +170,65 @@ __device__ __forceinline__ void store_tq_rows(float* base, int n_pairs, int tq, 
     const int ft = (piece >> 2) - ftile0;
     const int r0 = (piece & 3) * 4;
     char* p = reinterpret_cast<char*>(base) + ((size_t)(ft * n_pairs + jp) * 64 + r0 + 16 * g) * 32 + blk * 16;
+    *reinterpret_cast<uint4*>(p + 0 * 32) = make_uint4(d[0].x, d[1].x, d[2].x, d[3].x);
+    *reinterpret_cast<uint4*>(p + 1 * 32) = make_uint4(d[0].y, d[1].y, d[2].y, d[3].y);
+    *reinterpret_cast<uint4*>(p + 2 * 32) = make_uint4(d[0].z, d[1].z, d[2].z, d[3].z);
+    *reinterpret_cast<uint4*>(p + 3 * 32) = make_uint4(d[0].w, d[1].w, d[2].w, d[3].w);
+}
+
+// ---- the same accessors for padded areas -----------------------------------------------------------
+__device__ __forceinline__ Slot<bf16_t> load_slot_pad(const bf16_t* base, int tp, int lane)
+{
+    const uint4 x = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(base) + pad_pos((size_t)tp * 64 + lane) * 16);
+    Slot<bf16_t> s; s.q0 = make_uint2(x.x, x.y); s.q1 = make_uint2(x.z, x.w); return s;
+}
+__device__ __forceinline__ Slot<float> load_slot_pad(const float* base, int tp, int lane)
+{
+    const float4* p = reinterpret_cast<const float4*>(reinterpret_cast<const char*>(base) + pad_pos((size_t)tp * 64 + lane) * 32);
+    Slot<float> s; s.q0 = p[0]; s.q1 = p[1]; return s;
+}
+__device__ __forceinline__ void store_rq_piece_pad(bf16_t* base, int n_pairs, int row, int piece, uint4 d)
+{
+    const int tp = (row >> 4) * n_pairs + (piece >> 2);
+    const int blk = (piece >> 1) & 1, g0 = (piece & 1) * 2, r = row & 15;
+    const size_t s0 = (size_t)tp * 64 + r + 16 * g0;
+    char* b = reinterpret_cast<char*>(base) + blk * 8;
+    *reinterpret_cast<uint2*>(b + pad_pos(s0) * 16) = make_uint2(d.x, d.y);
+    *reinterpret_cast<uint2*>(b + pad_pos(s0 + 16) * 16) = make_uint2(d.z, d.w);
+}
+__device__ __forceinline__ void store_rq_piece_pad(float* base, int n_pairs, int row, int piece, uint4 d)
+{
+    const int tp = (row >> 4) * n_pairs + (piece >> 3);
+    const int blk = (piece >> 2) & 1, g = piece & 3, r = row & 15;
+    char* p = reinterpret_cast<char*>(base) + pad_pos((size_t)tp * 64 + r + 16 * g) * 32 + blk * 16;
+    *reinterpret_cast<uint4*>(p) = d;
+}
+__device__ __forceinline__ void store_tq_rows_pad(bf16_t* base, int n_pairs, int tq, int piece, const uint4 (&d)[4],
+                                                  int ftile0)
+{
+    const int jp = tq >> 3, blk = (tq >> 2) & 1, g = tq & 3;
+    const int ft = (piece >> 1) - ftile0;
+    const int r0 = (piece & 1) * 8;
+    const size_t s0 = (size_t)(ft * n_pairs + jp) * 64 + r0 + 16 * g;       // a multiple of 8: the 8 slots are contiguous
+    char* p = reinterpret_cast<char*>(base) + pad_pos(s0) * 16 + blk * 8;
+    const uint32_t w[4][4] = {{d[0].x, d[0].y, d[0].z, d[0].w}, {d[1].x, d[1].y, d[1].z, d[1].w},
+                              {d[2].x, d[2].y, d[2].z, d[2].w}, {d[3].x, d[3].y, d[3].z, d[3].w}};
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+        const uint2 lo = make_uint2((w[0][m] & 0xffffu) | (w[1][m] << 16), (w[2][m] & 0xffffu) | (w[3][m] << 16));
+        const uint2 hi = make_uint2((w[0][m] >> 16) | (w[1][m] & 0xffff0000u), (w[2][m] >> 16) | (w[3][m] & 0xffff0000u));
+        *reinterpret_cast<uint2*>(p + (2 * m) * 16) = lo;
+        *reinterpret_cast<uint2*>(p + (2 * m + 1) * 16) = hi;
+    }
+}
+__device__ __forceinline__ void store_tq_rows_pad(float* base, int n_pairs, int tq, int piece, const uint4 (&d)[4],
+                                                  int ftile0)
+{
+    const int jp = tq >> 3, blk = (tq >> 2) & 1, g = tq & 3;
+    const int ft = (piece >> 2) - ftile0;
+    const int r0 = (piece & 3) * 4;
+    const size_t s0 = (size_t)(ft * n_pairs + jp) * 64 + r0 + 16 * g;       // a multiple of 4: within one group of 8
+    char* p = reinterpret_cast<char*>(base) + pad_pos(s0) * 32 + blk * 16;
     *reinterpret_cast<uint4*>(p + 0 * 32) = make_uint4(d[0].x, d[1].x, d[2].x, d[3].x);
     *reinterpret_cast<uint4*>(p + 1 * 32) = make_uint4(d[0].y, d[1].y, d[2].y, d[3].y);
     *reinterpret_cast<uint4*>(p + 2 * 32) = make_uint4(d[0].z, d[1].z, d[2].z, d[3].z);
