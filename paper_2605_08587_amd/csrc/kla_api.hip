@@ -249,6 +249,9 @@ int chunk_bwd_impl(const void* q, const void* k, const void* v, const float* log
         if (kla::launch_bwd_states<E>(ba, dk, waves, st) != hipSuccess) return KLA_ERR_HIP;
         if (kla::launch_bwd_scan<E>(ba, dk, waves, st) != hipSuccess) return KLA_ERR_HIP;
     }
+    if constexpr (sizeof(E) == 2) {
+        if (swept) return kla::launch_bwd_assemble_bf16(ba, dk, pl.base.n_chunks, st) == hipSuccess ? KLA_OK : KLA_ERR_HIP;
+    }
     if (kla::launch_bwd_assemble<E>(ba, dk, pl.base.n_chunks, st) != hipSuccess) return KLA_ERR_HIP;
     return KLA_OK;
 }

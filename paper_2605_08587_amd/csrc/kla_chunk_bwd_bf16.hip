@@ -376,6 +376,372 @@ __global__ __launch_bounds__(64 * NW + 64) void bwd_sweep_bf16_kernel(BwdArgs<bf
     }
 }
 
+// =================================================================================================
+// per chunk-head contractions (bf16): the algebra of bwd_assemble_kernel in kla_chunk_bwd.hip on direct
+// global -> LDS copies.  Every operand sits in LDS as plain swizzled rows: the slab of S^T and dS'^T (64 rows of
+// d_k) and the K, Q tiles exactly like a K tile of the sweeps, the [64 tokens x 64 columns] slabs of dO, U, Y, X
+// like a K tile of d_k = 64.  Operands contracted along a row are two 64-bit reads, operands contracted down a
+// column (S^T, dS'^T, K, Q) come from the transposing read, which makes lane r of an output tile the feature
+// 32 kp + 8 (r / 4) + 4 b + r % 4 of tile 2 kp + b; the K and Q values that meet those outputs are read the same
+// way, and the 4x4 transposition before the staged write-out puts the features back in order.
+// A short last chunk re-reads its last valid row for the rows beyond it; the rows of A o dP and D', of the
+// <.,k> sums and of dg that belong to those rows are masked to zero.
+// =================================================================================================
+template <int DK>
+__global__ __launch_bounds__(256, 2) void bwd_assemble_bf16_kernel(BwdArgs<bf16_t> a)
+{
+    constexpr int KB = DK / 16, KP = DK / 32;
+    constexpr int RB = DK * 2, PPR = DK / 8, RPB = 1024 / RB, NKB = 64 / RPB;      // [64 x d_k] tiles
+    constexpr int RBA = 128, NAB = 8;                                                // [64 x 64] slabs: 8 blocks of 8 rows
+    constexpr int TK = 64 * RB, TA = 64 * RBA;
+    constexpr int kLd = 68, MB = 64 * kLd * 4;
+    // first phase: S^T | dS'^T | dO | U | Y | X          second phase: K | Q | A o dP | D'
+    constexpr int OFF_S = 0, OFF_DS = TK, OFF_DO = 2 * TK, OFF_U = OFF_DO + TA, OFF_Y = OFF_U + TA, OFF_X = OFF_Y + TA;
+    constexpr int PH1 = 2 * TK + 4 * TA;
+    constexpr int OFF_K = 0, OFF_Q = TK, OFF_E1 = 2 * TK, OFF_DP = 2 * TK + MB;
+    constexpr int PH2 = 2 * TK + 2 * MB;
+    constexpr int BIG = PH1 > PH2 ? PH1 : PH2;
+    constexpr int ORQ = RB + 16;                     // row stride of the dq / dk staging tiles (over A o dP and D')
+    static_assert(64 * ORQ <= MB, "staging tiles fit the fp32 matrices they replace");
+    __shared__ __attribute__((aligned(1024))) char lds[BIG];
+    __shared__ __attribute__((aligned(16))) float eg_s[64], ed_s[64], beta_s[64], invden_s[64], g_s[64], yx_s[64], dg_s[64],
+        dbeta_s[64];
+    __shared__ float red_s[8];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int r = lane & 15, g = lane >> 4;
+
+    const int h = blockIdx.x % a.H;
+    const int cg = blockIdx.x / a.H;
+    long tok0; int clen;
+    if (a.cu_seqlens) {
+        int lo = 0, hi = a.n_seq - 1;
+        while (lo < hi) { const int mid = (lo + hi + 1) >> 1; if (a.chunk_off[mid] <= cg) lo = mid; else hi = mid - 1; }
+        const int c = cg - a.chunk_off[lo];
+        const int s0 = a.cu_seqlens[lo], s1 = a.cu_seqlens[lo + 1];
+        tok0 = (long)s0 + 64L * c;
+        clen = min(64, s1 - (int)tok0);
+    } else {
+        const int n = cg / a.NT, c = cg % a.NT;
+        tok0 = (long)n * a.T + 64L * c;
+        clen = min(64, a.T - 64 * c);
+    }
+    const size_t kq_row = (size_t)a.H * DK * 2, v_row = (size_t)a.H * a.dv_dim * 2;
+    const char* rec = a.rec + (size_t)blockIdx.x * bwd_record_bytes<bf16_t>();
+    {
+        const float* vec = reinterpret_cast<const float*>(rec + 3 * ws_half_bytes<bf16_t>());
+        float* dst = wave == 0 ? eg_s : (wave == 1 ? ed_s : (wave == 2 ? beta_s : invden_s));
+        dst[lane] = vec[tid];
+        if (wave == 0) g_s[lane] = lane < clen ? a.log_alpha[(size_t)(tok0 + lane) * a.H + h] : 0.f;
+    }
+
+    // ---- per-lane offsets ---------------------------------------------------------------------------
+    // copies of [64 x d_k] tiles (global row stride `stride`) and of [64 x 64] slabs, swizzled on the global side
+    const int lrow = lane / PPR, pcol = lane % PPR;
+    const int lrowA = lane >> 3, pcolA = lane & 7;
+    auto copy_tile = [&](const char* src, size_t stride, char* dst, int b0, int b1) {       // blocks [b0, b1) of a [64 x d_k] tile
+        for (int b = b0; b < b1; ++b) {
+            const int row = b * RPB + lrow;
+            dma16(src, min(row, clen - 1) * (int)stride + ((pcol ^ swz_bits(row)) * 16), dst + b * 1024);
+        }
+    };
+    auto copy_state = [&](const char* src, char* dst, int b0, int b1) {                     // rows are d_v indices: never ragged
+        for (int b = b0; b < b1; ++b) {
+            const int row = b * RPB + lrow;
+            dma16(src, row * RB + ((pcol ^ swz_bits(row)) * 16), dst + b * 1024);
+        }
+    };
+    auto copy_slab = [&](const char* src, char* dst) {                                       // 8 blocks of 8 token rows x 128 bytes
+        for (int b = 0; b < NAB; ++b) {
+            const int row = b * 8 + lrowA;
+            dma16(src, min(row, clen - 1) * (int)v_row + ((pcolA ^ swz_bits(row)) * 16), dst + b * 1024);
+        }
+    };
+    // row-contracted operand of a slab: token row 16 t + r, contraction indices 32 kp + {4 g .. +3 | 16 + 4 g .. +3}
+    const int arow = r * RBA, asw = swz_bits(r), ahalf = (g & 1) * 8;
+    auto aslot = [&](int off, int t, int kp, u32x2& q0, u32x2& q1) {
+        const char* p = lds + off + 16 * t * RBA + arow + ahalf;
+        q0 = *reinterpret_cast<const u32x2*>(p + (((4 * kp + (g >> 1)) ^ asw) * 16));
+        q1 = *reinterpret_cast<const u32x2*>(p + (((4 * kp + 2 + (g >> 1)) ^ asw) * 16));
+    };
+    // column-contracted operand of a [64 x d_k] tile through the transposing read (as K^T in the sweeps)
+    const int a4 = r >> 2, c4 = r & 3;
+    int oKT[2];
+#pragma unroll
+    for (int par = 0; par < 2; ++par) oKT[par] = (4 * g + a4) * RB + (((4 * par + c4) ^ swz_bits(4 * g + a4)) * 16);
+    auto tslot = [&](int off, int kt, int jp, u32x2& q0, u32x2& q1) {
+        const int kp = kt >> 1, b = kt & 1;
+        const char* p = lds + off + oKT[kp & 1] + 32 * jp * RB + 128 * (kp >> 1) + 8 * b;
+        q0 = lds_read_tr(p);
+        q1 = lds_read_tr(p + 16 * RB);
+    };
+
+    floatx4 dQ[KB], dKr[KB], dKw[KB], dP[4], N1[4];
+#pragma unroll
+    for (int ct = 0; ct < KB; ++ct) { dQ[ct] = floatx4{0.f, 0.f, 0.f, 0.f}; dKr[ct] = dQ[ct]; dKw[ct] = dQ[ct]; }
+#pragma unroll
+    for (int jt = 0; jt < 4; ++jt) { dP[jt] = floatx4{0.f, 0.f, 0.f, 0.f}; N1[jt] = dP[jt]; }
+    float yx = 0.f, sdot = 0.f;
+
+    // ---- first phase: everything that contracts over d_v, 64 columns at a time -----------------------------
+    const char* Sg = reinterpret_cast<const char*>(a.s_chk) + (size_t)blockIdx.x * DK * a.dv_dim * 2;
+    const char* dSg = reinterpret_cast<const char*>(a.ds_chk) + (size_t)blockIdx.x * DK * a.dv_dim * 2;
+    const size_t vrow0 = (size_t)tok0 * v_row + (size_t)h * a.dv_dim * 2;
+    for (int slab0 = 0; slab0 < a.dv_dim; slab0 += 64) {
+        __syncthreads();                             // the previous slab's operands are no longer read
+        if (wave == 0)      copy_state(Sg + (size_t)slab0 * RB, lds + OFF_S, 0, NKB);
+        else if (wave == 1) copy_state(dSg + (size_t)slab0 * RB, lds + OFF_DS, 0, NKB);
+        else if (wave == 2) {
+            copy_slab(reinterpret_cast<const char*>(a.d_o) + vrow0 + slab0 * 2, lds + OFF_DO);
+            copy_slab(reinterpret_cast<const char*>(a.U) + vrow0 + slab0 * 2, lds + OFF_U);
+        } else {
+            copy_slab(reinterpret_cast<const char*>(a.Y) + vrow0 + slab0 * 2, lds + OFF_Y);
+            copy_slab(reinterpret_cast<const char*>(a.X) + vrow0 + slab0 * 2, lds + OFF_X);
+        }
+        wait_vmcnt<0>();
+        __syncthreads();
+        // Y_i . X_i and <dS', S>: plain 16-byte pieces, the swizzle is the same for both tiles of a pair
+        {
+            const int row = tid >> 2;
+#pragma unroll
+            for (int pc = 0; pc < 2; ++pc) {
+                const int o = row * RBA + ((tid & 3) + 4 * pc) * 16;
+                const u32x4 y = ld16(lds + OFF_Y + o), x = ld16(lds + OFF_X + o);
+#pragma unroll
+                for (int m = 0; m < 4; ++m) {
+                    yx += __uint_as_float(y[m] << 16) * __uint_as_float(x[m] << 16);
+                    yx += __uint_as_float(y[m] & 0xffff0000u) * __uint_as_float(x[m] & 0xffff0000u);
+                }
+            }
+#pragma unroll
+            for (int pc = 0; pc < TK / 16 / 256; ++pc) {
+                const int o = (tid + 256 * pc) * 16;
+                const u32x4 y = ld16(lds + OFF_S + o), x = ld16(lds + OFF_DS + o);
+#pragma unroll
+                for (int m = 0; m < 4; ++m) {
+                    sdot += __uint_as_float(y[m] << 16) * __uint_as_float(x[m] << 16);
+                    sdot += __uint_as_float(y[m] & 0xffff0000u) * __uint_as_float(x[m] & 0xffff0000u);
+                }
+            }
+        }
+#pragma unroll
+        for (int kp = 0; kp < 2; ++kp) {
+            u32x2 do0, do1, u0, u1, y0, y1;
+            aslot(OFF_DO, wave, kp, do0, do1);
+            aslot(OFF_U, wave, kp, u0, u1);
+            aslot(OFF_Y, wave, kp, y0, y1);
+#pragma unroll
+            for (int ct = 0; ct < KB; ++ct) {
+                u32x2 s0, s1, d0, d1;
+                tslot(OFF_S, ct, kp, s0, s1);
+                tslot(OFF_DS, ct, kp, d0, d1);
+                mma_bf16(dQ[ct], do0, do1, s0, s1);        // dO S^T
+                mma_bf16(dKr[ct], y0, y1, s0, s1);         // Y S^T
+                mma_bf16(dKw[ct], u0, u1, d0, d1);         // U dS'^T
+            }
+            static_for<4>([&](auto jt) {
+                if (jt <= wave) {                          // lower-triangular tiles only
+                    u32x2 b0, b1;
+                    aslot(OFF_U, jt, kp, b0, b1);
+                    mma_bf16(dP[jt], do0, do1, b0, b1);    // dO U^T
+                    mma_bf16(N1[jt], y0, y1, b0, b1);      // Y U^T
+                }
+            });
+        }
+    }
+    if (wave == 0) {                                 // g_i = log gamma_i (the first barrier of the loop ordered the loads)
+        float x = g_s[lane];
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) { const float y = __shfl_up(x, off, kWave); if (lane >= off) x += y; }
+        g_s[lane] = x;
+    }
+    {   // D_gamma dO S^T,  -D_gamma dX S^T (dX = B Y),  diag(gamma_C/gamma_i) U dS'^T
+        const floatx4 egv = ld_f4(reinterpret_cast<const char*>(eg_s + 16 * wave + 4 * g));
+        const floatx4 edv = ld_f4(reinterpret_cast<const char*>(ed_s + 16 * wave + 4 * g));
+        const floatx4 ngb = -(egv * ld_f4(reinterpret_cast<const char*>(beta_s + 16 * wave + 4 * g)));
+#pragma unroll
+        for (int ct = 0; ct < KB; ++ct) { dQ[ct] = dQ[ct] * egv; dKr[ct] = dKr[ct] * ngb; dKw[ct] = dKw[ct] * edv; }
+    }
+    yx += __shfl_xor(yx, 1, kWave); yx += __shfl_xor(yx, 2, kWave);      // the 4 threads of a row are neighbours
+    if ((tid & 3) == 0) yx_s[tid >> 2] = yx;
+    sdot = wave_sum(sdot);
+    if (lane == 0) red_s[wave] = sdot;
+    __syncthreads();                                 // the slab areas are dead from here on
+
+    // ---- second phase: K, Q tiles; A o dP and D' = -A^- o (Y U^T) as fp32 matrices ---------------------------
+    float* E1 = reinterpret_cast<float*>(lds + OFF_E1);
+    float* Dp = reinterpret_cast<float*>(lds + OFF_DP);
+    {
+        const char* kb = reinterpret_cast<const char*>(a.k) + (size_t)tok0 * kq_row + (size_t)h * DK * 2;
+        const char* qb = reinterpret_cast<const char*>(a.q) + (size_t)tok0 * kq_row + (size_t)h * DK * 2;
+        if (wave < 2) copy_tile(kb, kq_row, lds + OFF_K, wave * (NKB / 2), (wave + 1) * (NKB / 2));
+        else          copy_tile(qb, kq_row, lds + OFF_Q, (wave - 2) * (NKB / 2), (wave - 1) * (NKB / 2));
+        static_for<4>([&](auto jt) {
+            const int j = 16 * jt + r;
+            const float gj = g_s[j];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int i = 16 * wave + 4 * g + e;
+                const float dec = (jt <= wave && j <= i && i < clen) ? expf(g_s[i] - gj) : 0.f;
+                E1[i * kLd + j] = dec * dP[jt][e];
+                Dp[i * kLd + j] = (j < i) ? -dec * N1[jt][e] : 0.f;
+            }
+        });
+        wait_vmcnt<0>();
+    }
+    __syncthreads();
+
+    // K and Q of this wave's rows as accumulator tiles: token 16 wave + 4 g + e, feature of (tile ct, lane r)
+    auto kacc = [&](int off, int ct) {
+        u32x2 q0, q1;
+        tslot(off, ct, wave >> 1, q0, q1);
+        return quad_to_f((wave & 1) ? q1 : q0);
+    };
+    floatx4 rowmask;                                 // 1 for the rows of the chunk, 0 past a ragged end
+#pragma unroll
+    for (int e = 0; e < 4; ++e) rowmask[e] = (16 * wave + 4 * g + e < clen) ? 1.f : 0.f;
+    float zsum = 0.f;                                // sum_i (gamma_C/gamma_i) k_i . (dS' U_i)
+#pragma unroll
+    for (int ct = 0; ct < KB; ++ct) {
+        const floatx4 kk = kacc(OFF_K, ct);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) zsum += rowmask[e] * dKw[ct][e] * kk[e];
+    }
+    zsum = wave_sum(zsum);
+    if (lane == 0) red_s[4 + wave] = zsum;
+
+    floatx4 E2[KB];
+#pragma unroll
+    for (int ct = 0; ct < KB; ++ct) E2[ct] = floatx4{0.f, 0.f, 0.f, 0.f};
+    const int row_a = 16 * wave + r;
+    auto rows_slot = [&](const float* m, int jp, u32x2& q0, u32x2& q1) {
+        q0 = to_quad(ld_f4(reinterpret_cast<const char*>(m + row_a * kLd + 32 * jp + 4 * g)));
+        q1 = to_quad(ld_f4(reinterpret_cast<const char*>(m + row_a * kLd + 32 * jp + 16 + 4 * g)));
+    };
+    auto cols_slot = [&](const float* m, const float* scale, int jp, u32x2& q0, u32x2& q1) {
+        floatx4 x0, x1;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int i0 = 32 * jp + 4 * g + e, i1 = i0 + 16;
+            x0[e] = m[i0 * kLd + row_a]; x1[e] = m[i1 * kLd + row_a];
+            if (scale) { x0[e] *= scale[i0]; x1[e] *= scale[i1]; }
+        }
+        q0 = to_quad(x0); q1 = to_quad(x1);
+    };
+    static_for<2>([&](auto jp) {
+        if (jp <= (wave >> 1)) {
+            u32x2 e0, e1, d0, d1;
+            rows_slot(E1, jp, e0, e1);
+            rows_slot(Dp, jp, d0, d1);
+#pragma unroll
+            for (int ct = 0; ct < KB; ++ct) {
+                u32x2 k0, k1;
+                tslot(OFF_K, ct, jp, k0, k1);
+                mma_bf16(dQ[ct], e0, e1, k0, k1);          // (A o dP) K
+                mma_bf16(E2[ct], d0, d1, k0, k1);          // D' K
+            }
+        }
+        if (jp >= (wave >> 1)) {
+            u32x2 e0, e1, d0, d1;
+            cols_slot(E1, nullptr, jp, e0, e1);
+            cols_slot(Dp, beta_s, jp, d0, d1);
+#pragma unroll
+            for (int ct = 0; ct < KB; ++ct) {
+                u32x2 k0, k1, q0, q1;
+                tslot(OFF_Q, ct, jp, q0, q1);
+                tslot(OFF_K, ct, jp, k0, k1);
+                mma_bf16(dKw[ct], e0, e1, q0, q1);         // (A o dP)^T Q
+                mma_bf16(dKw[ct], d0, d1, k0, k1);         // (B D')^T K
+            }
+        }
+    });
+
+    // ---- rows: dbeta, dg, the beta term of dK -----------------------------------------------------------
+    float dbr[4] = {0.f, 0.f, 0.f, 0.f}, dgr[4] = {0.f, 0.f, 0.f, 0.f};
+    floatx4 kk[KB];
+    const floatx4 bev = ld_f4(reinterpret_cast<const char*>(beta_s + 16 * wave + 4 * g));
+#pragma unroll
+    for (int ct = 0; ct < KB; ++ct) {
+        kk[ct] = kacc(OFF_K, ct);
+        const floatx4 qq = kacc(OFF_Q, ct);
+        dKr[ct] = dKr[ct] + bev * E2[ct];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            dbr[e] += E2[ct][e] * kk[ct][e];
+            dgr[e] += dQ[ct][e] * qq[e] + (dKr[ct][e] - dKw[ct][e]) * kk[ct][e];
+        }
+    }
+    floatx4 c5;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const int i = 16 * wave + 4 * g + e;
+        float db = dbr[e], dgv = dgr[e];
+#pragma unroll
+        for (int off = 1; off < 16; off <<= 1) { db += __shfl_xor(db, off, kWave); dgv += __shfl_xor(dgv, off, kWave); }
+        db += yx_s[i];
+        if (r == 0) { dbeta_s[i] = db; dg_s[i] = rowmask[e] * dgv; }
+        c5[e] = -2.f * beta_s[i] * db * invden_s[i];
+    }
+    __syncthreads();                                 // every wave is done with A o dP and D': they become staging tiles
+
+    // ---- dq, dk: 4x4 transposition inside each quad of lanes, staged rows, 16-byte stores ----------------
+    {
+        char* sq = lds + OFF_E1;
+        char* sk = lds + OFF_DP;
+        const bool q_lo = (r & 3) < 2;
+        const uint32_t psel = (r & 1) ? 0x03020706u : 0x05040100u;
+        auto stage_quad = [&](u32x2 ob, char* dst) {
+            const uint32_t snd = q_lo ? ob.y : ob.x;
+            const uint32_t rcv = (uint32_t)__builtin_amdgcn_mov_dpp((int)snd, 0x4E, 0xf, 0xf, true);
+            if (q_lo) ob.y = rcv; else ob.x = rcv;
+            const uint32_t px = (uint32_t)__builtin_amdgcn_mov_dpp((int)ob.x, 0xB1, 0xf, 0xf, true);
+            const uint32_t py = (uint32_t)__builtin_amdgcn_mov_dpp((int)ob.y, 0xB1, 0xf, 0xf, true);
+            ob.x = __builtin_amdgcn_perm(px, ob.x, psel);
+            ob.y = __builtin_amdgcn_perm(py, ob.y, psel);
+            *reinterpret_cast<u32x2*>(dst) = ob;
+        };
+        // after the transposition lane (r, g) holds token row 16 wave + 4 g + r % 4, features 32 kp + 8 (r / 4) + 4 b .. + 3
+        const int orow = (16 * wave + 4 * g + (r & 3)) * ORQ + 16 * (r >> 2);
+#pragma unroll
+        for (int ct = 0; ct < KB; ++ct) {
+            const int fo = orow + 64 * (ct >> 1) + 8 * (ct & 1);
+            stage_quad(to_quad(dQ[ct]), sq + fo);
+            stage_quad(to_quad(dKr[ct] + dKw[ct] + c5 * kk[ct]), sk + fo);
+        }
+        __syncthreads();
+        char* qo = reinterpret_cast<char*>(a.dq) + (size_t)tok0 * kq_row + (size_t)h * DK * 2;
+        char* ko = reinterpret_cast<char*>(a.dk) + (size_t)tok0 * kq_row + (size_t)h * DK * 2;
+#pragma unroll
+        for (int it = 0; it < 64 * PPR / 256; ++it) {
+            const int i = tid + 256 * it, row = i / PPR, pc = i % PPR;
+            if (row < clen) {
+                st16(qo + (size_t)row * kq_row + pc * 16, ld16(sq + row * ORQ + pc * 16));
+                st16(ko + (size_t)row * kq_row + pc * 16, ld16(sk + row * ORQ + pc * 16));
+            }
+        }
+    }
+    if (wave == 0) {
+        float x = dg_s[lane];
+        if (lane == 63) x += eg_s[63] * (red_s[0] + red_s[1] + red_s[2] + red_s[3]) + (red_s[4] + red_s[5] + red_s[6] + red_s[7]);
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) { const float y = __shfl_down(x, off, kWave); if (lane + off < 64) x += y; }
+        if (lane < clen) {
+            a.dlog_alpha[(size_t)(tok0 + lane) * a.H + h] = x;
+            a.deta[(size_t)(tok0 + lane) * a.H + h] = dbeta_s[lane] * invden_s[lane];
+        }
+    }
+}
+
+hipError_t launch_bwd_assemble_bf16(const BwdArgs<bf16_t>& a, int dk, long n_chunks, hipStream_t st)
+{
+    if (n_chunks == 0) return hipSuccess;
+    const dim3 grid((unsigned)(n_chunks * a.H)), block(256);
+    if (dk == 64) hipLaunchKernelGGL((bwd_assemble_bf16_kernel<64>), grid, block, 0, st, a);
+    else          hipLaunchKernelGGL((bwd_assemble_bf16_kernel<128>), grid, block, 0, st, a);
+    return hipGetLastError();
+}
+
 template <int DK, bool REV>
 static hipError_t launch_sweep_dk(const BwdArgs<bf16_t>& a, int waves, hipStream_t st)
 {

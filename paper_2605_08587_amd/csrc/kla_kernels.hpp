@@ -87,6 +87,7 @@ template <typename E> hipError_t launch_bwd_scan(const BwdArgs<E>& a, int dk, in
 // bf16 specialisations of the two sweeps (copy wave, LDS ring, transposing reads: see kla_chunk_bwd_bf16.hip)
 hipError_t launch_bwd_states_bf16(const BwdArgs<bf16_t>& a, int dk, int waves, hipStream_t st);
 hipError_t launch_bwd_scan_bf16(const BwdArgs<bf16_t>& a, int dk, int waves, hipStream_t st);
+hipError_t launch_bwd_assemble_bf16(const BwdArgs<bf16_t>& a, int dk, long n_chunks, hipStream_t st);
 template <typename E> hipError_t launch_bwd_assemble(const BwdArgs<E>& a, int dk, long n_chunks, hipStream_t st);
 
 hipError_t launch_chunk_offsets(const int* cu_seqlens, int n_seq, int* chunk_off, hipStream_t st);
