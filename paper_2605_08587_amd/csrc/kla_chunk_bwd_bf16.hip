@@ -387,6 +387,15 @@ __global__ __launch_bounds__(64 * NW + 64) void bwd_sweep_bf16_kernel(BwdArgs<bf
 // A short last chunk re-reads its last valid row for the rows beyond it; the rows of A o dP and D', of the
 // <.,k> sums and of dg that belong to those rows are masked to zero.
 // =================================================================================================
+namespace {
+// acc + x.lo * y.lo + x.hi * y.hi for two packed bf16 pairs (v_dot2c_f32_bf16)
+__device__ __forceinline__ float dot2_bf16(uint32_t x, uint32_t y, float acc)
+{
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, x), __builtin_bit_cast(bf16x2_t, y), acc, false);
+}
+}  // namespace
+
 template <int DK>
 __global__ __launch_bounds__(256, 2) void bwd_assemble_bf16_kernel(BwdArgs<bf16_t> a)
 {
@@ -440,23 +449,35 @@ __global__ __launch_bounds__(256, 2) void bwd_assemble_bf16_kernel(BwdArgs<bf16_
     // copies of [64 x d_k] tiles (global row stride `stride`) and of [64 x 64] slabs, swizzled on the global side
     const int lrow = lane / PPR, pcol = lane % PPR;
     const int lrowA = lane >> 3, pcolA = lane & 7;
+    // The per-lane part of a copy's address does not depend on the block (8 rows per block) or only on its parity
+    // (4 rows per block) unless the chunk is ragged, where rows past its end re-read the last one.
+    const bool full = clen == 64;
+    int gkq[2], gst[2];
+#pragma unroll
+    for (int par = 0; par < 2; ++par) {
+        gkq[par] = lrow * (int)kq_row + ((pcol ^ swz_bits(RPB * par + lrow)) * 16);
+        gst[par] = lrow * RB + ((pcol ^ swz_bits(RPB * par + lrow)) * 16);
+    }
+    const int gsl = lrowA * (int)v_row + ((pcolA ^ swz_bits(lrowA)) * 16);
     auto copy_tile = [&](const char* src, size_t stride, char* dst, int b0, int b1) {       // blocks [b0, b1) of a [64 x d_k] tile
         for (int b = b0; b < b1; ++b) {
             const int row = b * RPB + lrow;
-            dma16(src, min(row, clen - 1) * (int)stride + ((pcol ^ swz_bits(row)) * 16), dst + b * 1024);
+            if (full) dma16(src + (size_t)(b * RPB) * stride, gkq[(RPB == 4) ? (b & 1) : 0], dst + b * 1024);
+            else      dma16(src, min(row, clen - 1) * (int)stride + ((pcol ^ swz_bits(row)) * 16), dst + b * 1024);
         }
     };
-    auto copy_state = [&](const char* src, char* dst, int b0, int b1) {                     // rows are d_v indices: never ragged
-        for (int b = b0; b < b1; ++b) {
-            const int row = b * RPB + lrow;
-            dma16(src, row * RB + ((pcol ^ swz_bits(row)) * 16), dst + b * 1024);
-        }
+    auto copy_state = [&](const char* src, char* dst) {                                      // rows are d_v indices: never ragged
+        static_for<NKB>([&](auto bb) {
+            const int b = bb;
+            dma16(src + b * RPB * RB, gst[(RPB == 4) ? (b & 1) : 0], dst + b * 1024);
+        });
     };
     auto copy_slab = [&](const char* src, char* dst) {                                       // 8 blocks of 8 token rows x 128 bytes
-        for (int b = 0; b < NAB; ++b) {
-            const int row = b * 8 + lrowA;
-            dma16(src, min(row, clen - 1) * (int)v_row + ((pcolA ^ swz_bits(row)) * 16), dst + b * 1024);
-        }
+        static_for<NAB>([&](auto bb) {
+            const int b = bb;
+            if (full) dma16(src + (size_t)(b * 8) * v_row, gsl, dst + b * 1024);
+            else      dma16(src, min(b * 8 + lrowA, clen - 1) * (int)v_row + ((pcolA ^ swz_bits(b * 8 + lrowA)) * 16), dst + b * 1024);
+        });
     };
     // row-contracted operand of a slab: token row 16 t + r, contraction indices 32 kp + {4 g .. +3 | 16 + 4 g .. +3}
     const int arow = r * RBA, asw = swz_bits(r), ahalf = (g & 1) * 8;
@@ -490,8 +511,8 @@ __global__ __launch_bounds__(256, 2) void bwd_assemble_bf16_kernel(BwdArgs<bf16_
     const size_t vrow0 = (size_t)tok0 * v_row + (size_t)h * a.dv_dim * 2;
     for (int slab0 = 0; slab0 < a.dv_dim; slab0 += 64) {
         __syncthreads();                             // the previous slab's operands are no longer read
-        if (wave == 0)      copy_state(Sg + (size_t)slab0 * RB, lds + OFF_S, 0, NKB);
-        else if (wave == 1) copy_state(dSg + (size_t)slab0 * RB, lds + OFF_DS, 0, NKB);
+        if (wave == 0)      copy_state(Sg + (size_t)slab0 * RB, lds + OFF_S);
+        else if (wave == 1) copy_state(dSg + (size_t)slab0 * RB, lds + OFF_DS);
         else if (wave == 2) {
             copy_slab(reinterpret_cast<const char*>(a.d_o) + vrow0 + slab0 * 2, lds + OFF_DO);
             copy_slab(reinterpret_cast<const char*>(a.U) + vrow0 + slab0 * 2, lds + OFF_U);
@@ -509,20 +530,14 @@ __global__ __launch_bounds__(256, 2) void bwd_assemble_bf16_kernel(BwdArgs<bf16_
                 const int o = row * RBA + ((tid & 3) + 4 * pc) * 16;
                 const u32x4 y = ld16(lds + OFF_Y + o), x = ld16(lds + OFF_X + o);
 #pragma unroll
-                for (int m = 0; m < 4; ++m) {
-                    yx += __uint_as_float(y[m] << 16) * __uint_as_float(x[m] << 16);
-                    yx += __uint_as_float(y[m] & 0xffff0000u) * __uint_as_float(x[m] & 0xffff0000u);
-                }
+                for (int m = 0; m < 4; ++m) yx = dot2_bf16(y[m], x[m], yx);
             }
 #pragma unroll
             for (int pc = 0; pc < TK / 16 / 256; ++pc) {
                 const int o = (tid + 256 * pc) * 16;
                 const u32x4 y = ld16(lds + OFF_S + o), x = ld16(lds + OFF_DS + o);
 #pragma unroll
-                for (int m = 0; m < 4; ++m) {
-                    sdot += __uint_as_float(y[m] << 16) * __uint_as_float(x[m] << 16);
-                    sdot += __uint_as_float(y[m] & 0xffff0000u) * __uint_as_float(x[m] & 0xffff0000u);
-                }
+                for (int m = 0; m < 4; ++m) sdot = dot2_bf16(y[m], x[m], sdot);
             }
         }
 #pragma unroll
@@ -554,7 +569,7 @@ __global__ __launch_bounds__(256, 2) void bwd_assemble_bf16_kernel(BwdArgs<bf16_
         float x = g_s[lane];
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) { const float y = __shfl_up(x, off, kWave); if (lane >= off) x += y; }
-        g_s[lane] = x;
+        g_s[lane] = x * 1.44269504088896341f;        // in units of log 2: the decay ratios below are exp2 of differences
     }
     {   // D_gamma dO S^T,  -D_gamma dX S^T (dX = B Y),  diag(gamma_C/gamma_i) U dS'^T
         const floatx4 egv = ld_f4(reinterpret_cast<const char*>(eg_s + 16 * wave + 4 * g));
@@ -583,7 +598,7 @@ __global__ __launch_bounds__(256, 2) void bwd_assemble_bf16_kernel(BwdArgs<bf16_
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const int i = 16 * wave + 4 * g + e;
-                const float dec = (jt <= wave && j <= i && i < clen) ? expf(g_s[i] - gj) : 0.f;
+                const float dec = (jt <= wave && j <= i && i < clen) ? __builtin_amdgcn_exp2f(g_s[i] - gj) : 0.f;
                 E1[i * kLd + j] = dec * dP[jt][e];
                 Dp[i * kLd + j] = (j < i) ? -dec * N1[jt][e] : 0.f;
             }
