@@ -219,7 +219,15 @@ int chunk_bwd_impl(const void* q, const void* k, const void* v, const float* log
     ia.cu_seqlens = n_seq > 0 ? cu_dev : nullptr; ia.chunk_off = chunk_off; ia.n_seq = n_seq;
     ia.T = T; ia.NT = NT; ia.H = H;
     ia.wsT = reinterpret_cast<E*>(ws + pl.off_rec); ia.wsP = nullptr; ia.wsG = nullptr; ia.opts = 0u;
-    if (kla::launch_intra_bwd<E>(ia, dk, (int)pl.base.n_chunks, st) != hipSuccess) return KLA_ERR_HIP;
+    bool fast = false;                                // bf16: the specialised kernels, unless KLA_BWD_IMPL=generic (A/B testing)
+    if constexpr (sizeof(E) == 2) {
+        const char* impl = getenv("KLA_BWD_IMPL");
+        fast = !(impl && impl[0] == 'g');
+    }
+    if constexpr (sizeof(E) == 2) {
+        if (fast && kla::launch_intra_bwd_bf16(ia, dk, (int)pl.base.n_chunks, st) != hipSuccess) return KLA_ERR_HIP;
+    }
+    if (!fast && kla::launch_intra_bwd<E>(ia, dk, (int)pl.base.n_chunks, st) != hipSuccess) return KLA_ERR_HIP;
 
     kla::BwdArgs<E> ba;
     ba.q = ia.q; ba.k = ia.k; ba.v = static_cast<const E*>(v);
@@ -236,22 +244,15 @@ int chunk_bwd_impl(const void* q, const void* k, const void* v, const float* log
     // two waves (32 state columns) per workgroup once that still gives a workgroup per CU
     const long chains8 = ((long)pl.base.n_states * H + 7) / 8 * 8;
     const int waves = (chains8 * (dv / 32) >= 192) ? 2 : 1;
-    bool swept = false;
     if constexpr (sizeof(E) == 2) {
-        const char* impl = getenv("KLA_BWD_IMPL");    // "generic": the element-type-generic sweeps (A/B testing)
-        if (!(impl && impl[0] == 'g')) {
+        if (fast) {
             if (kla::launch_bwd_states_bf16(ba, dk, waves, st) != hipSuccess) return KLA_ERR_HIP;
             if (kla::launch_bwd_scan_bf16(ba, dk, waves, st) != hipSuccess) return KLA_ERR_HIP;
-            swept = true;
+            return kla::launch_bwd_assemble_bf16(ba, dk, pl.base.n_chunks, st) == hipSuccess ? KLA_OK : KLA_ERR_HIP;
         }
     }
-    if (!swept) {
-        if (kla::launch_bwd_states<E>(ba, dk, waves, st) != hipSuccess) return KLA_ERR_HIP;
-        if (kla::launch_bwd_scan<E>(ba, dk, waves, st) != hipSuccess) return KLA_ERR_HIP;
-    }
-    if constexpr (sizeof(E) == 2) {
-        if (swept) return kla::launch_bwd_assemble_bf16(ba, dk, pl.base.n_chunks, st) == hipSuccess ? KLA_OK : KLA_ERR_HIP;
-    }
+    if (kla::launch_bwd_states<E>(ba, dk, waves, st) != hipSuccess) return KLA_ERR_HIP;
+    if (kla::launch_bwd_scan<E>(ba, dk, waves, st) != hipSuccess) return KLA_ERR_HIP;
     if (kla::launch_bwd_assemble<E>(ba, dk, pl.base.n_chunks, st) != hipSuccess) return KLA_ERR_HIP;
     return KLA_OK;
 }

@@ -63,15 +63,42 @@ __device__ __forceinline__ floatx4 bq(const float* m, int row0, int col0, int r,
     floatx4 x; x[0] = p[0]; x[1] = p[kLd]; x[2] = p[2 * kLd]; x[3] = p[3 * kLd]; return x;
 }
 
+// The transpose of a lower-triangular fp32 64x64 matrix (row stride kLd; its strictly-upper tiles hold garbage) as
+// the 6 upper-triangular tile-pairs of bf16 operand slots: pair ctp = wave (+ 4) is row tile jt, column pair ip with
+// (jt, ip) = (0,0) (0,1) (1,0) (1,1) (2,1) (3,1); slot entry (row j, column i) is m[i][j].
+__device__ __forceinline__ void write_transposed(char* out, const float* m, int wave, int lane)
+{
+    const int r = lane & 15, g = lane >> 4;
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+        const int ctp = wave + 4 * it;
+        if (ctp < kTriPairs) {
+            const int jt = ctp < 4 ? (ctp >> 1) : ctp - 2, ip = ctp < 4 ? (ctp & 1) : 1;
+            const float* src = m + (32 * ip + 4 * g) * kLd + 16 * jt + r;
+            const bool low = ctp == 2 || ctp == 5;        // first block of the pair lies below the diagonal of m^T: zero
+            floatx4 x0, x1;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { x0[e] = src[e * kLd]; x1[e] = src[(16 + e) * kLd]; }
+            const u32x2 q0 = low ? u32x2{0u, 0u} : to_quad(x0);
+            const u32x2 q1 = to_quad(x1);
+            const u32x4 v = {q0.x, q0.y, q1.x, q1.y};
+            st16(out + (size_t)(ctp * 64 + lane) * 16, v);
+        }
+    }
+}
+
 }  // namespace
 
-template <int DK>
+// BWD = true: the record of the backward pass, [T' | M^T | P^T | gamma_i | gamma_C/gamma_i | beta_i | 1/(||k_i||^2+eps)]
+// (M = (I + L)^{-1}; the transposes as the 6 upper-triangular tile-pairs, see kla_mma.hpp); options are not taken.
+template <int DK, bool BWD>
 __global__ __launch_bounds__(256, 3) void intra_bf16_kernel(IntraArgs<bf16_t> a)
 {
     constexpr int RB = DK * 2, PPR = DK / 8, KP = DK / 32;
     constexpr int RPB = 1024 / RB, NKB = 64 / RPB;           // rows per 1 KiB copy block, blocks per tile
     constexpr int TILE = 64 * RB;
-    constexpr int REC = ws_record_bytes<bf16_t>(), HALF = ws_half_bytes<bf16_t>();
+    constexpr int REC = BWD ? bwd_record_bytes<bf16_t>() : ws_record_bytes<bf16_t>(), HALF = ws_half_bytes<bf16_t>();
+    constexpr int VEC = (BWD ? 3 : 2) * HALF;                // offset of the fp32 vectors in the record
     static_assert(2 * TILE >= 64 * kLd * 4 || DK == 64, "P image overlays the K/Q tiles");
 
     __shared__ __attribute__((aligned(1024))) char kq[2 * TILE > 64 * kLd * 4 ? 2 * TILE : 64 * kLd * 4];
@@ -80,6 +107,7 @@ __global__ __launch_bounds__(256, 3) void intra_bf16_kernel(IntraArgs<bf16_t> a)
     __shared__ __attribute__((aligned(16))) float g_s[64];
     __shared__ __attribute__((aligned(16))) float eta_s[64];
     __shared__ __attribute__((aligned(16))) float rq_s[64];      // 1/||q_i|| when the read-out is normalised, else 1
+    __shared__ __attribute__((aligned(16))) float invden_s[BWD ? 64 : 4];
     float* Pm = reinterpret_cast<float*>(kq);
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -129,10 +157,10 @@ __global__ __launch_bounds__(256, 3) void intra_bf16_kernel(IntraArgs<bf16_t> a)
             const float x2 = x * 1.44269504088896341f;   // in units of log 2: every decay ratio is one v_exp_f32
             g_s[lane] = x2;
             eta_s[lane] = lane < clen ? a.eta[(size_t)(tok0 + lane) * a.H + h] : 0.f;
-            a.wsG[(size_t)blockIdx.x * 128 + lane] = x;
+            if constexpr (!BWD) a.wsG[(size_t)blockIdx.x * 128 + lane] = x;
             rq_s[lane] = 1.f;
             const float gl2 = __shfl(x2, 63, kWave);
-            float* dec = reinterpret_cast<float*>(rec + 2 * HALF);
+            float* dec = reinterpret_cast<float*>(rec + VEC);
             dec[lane] = __builtin_amdgcn_exp2f(x2);            // gamma_i
             dec[64 + lane] = __builtin_amdgcn_exp2f(gl2 - x2); // gamma_C / gamma_i
         }
@@ -199,16 +227,22 @@ __global__ __launch_bounds__(256, 3) void intra_bf16_kernel(IntraArgs<bf16_t> a)
                 if constexpr (J.q == 0 && J.ti == J.tj) {
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
-                        if (4 * g + e == r) beta_s[16 * J.ti + r] = gdn ? eta_s[16 * J.ti + r] : kaczmarz_beta_fast(eta_s[16 * J.ti + r], acc[jb][e], a.eps);
+                        if (4 * g + e == r) {
+                            beta_s[16 * J.ti + r] = gdn ? eta_s[16 * J.ti + r] : kaczmarz_beta_fast(eta_s[16 * J.ti + r], acc[jb][e], a.eps);
+                            if constexpr (BWD) invden_s[16 * J.ti + r] = kaczmarz_beta_fast(1.f, acc[jb][e], a.eps);
+                        }
                 }
             });
         });
     }
     __syncthreads();   // K/Q tiles are dead from here on (Pm overlays them); beta_s and rq_s are complete
-    if (wave == 0) {                                     // third vector of the record and the scale itself
-        float* dec = reinterpret_cast<float*>(rec + 2 * HALF);
-        dec[128 + lane] = __builtin_amdgcn_exp2f(g_s[lane]) * rq_s[lane];
-        a.wsG[(size_t)blockIdx.x * 128 + 64 + lane] = rq_s[lane];
+    if (wave == 0) {                                     // third vector of the record (and the scale itself)
+        float* dec = reinterpret_cast<float*>(rec + VEC);
+        if constexpr (BWD) { dec[128 + lane] = beta_s[lane]; dec[192 + lane] = invden_s[lane]; }
+        else {
+            dec[128 + lane] = __builtin_amdgcn_exp2f(g_s[lane]) * rq_s[lane];
+            a.wsG[(size_t)blockIdx.x * 128 + 64 + lane] = rq_s[lane];
+        }
     }
 
     // ---- phase 2b: decay, mask, beta -> L (into M) and P (into Pm) as fp32.  Tile coordinates are compile-time
@@ -280,9 +314,10 @@ __global__ __launch_bounds__(256, 3) void intra_bf16_kernel(IntraArgs<bf16_t> a)
         for (int i = 0; i < 16; ++i)
             if ((i >> 2) == g) M[(16 * wave + i) * kLd + 16 * wave + r] = x[i];
     }
-    // P goes out to the workspace in operand order (fp32 image -> bf16 slots).  Stored tile-pair ctp = wave
-    // (+ 4): wave-uniform, so its tile coordinates are scalars; slot = ctp * 64 + lane.
-    {
+    // P (forward) or P^T (backward) goes out to the workspace in operand order (fp32 image -> bf16 slots).  Stored
+    // tile-pair ctp = wave (+ 4): wave-uniform, so its tile coordinates are scalars; slot = ctp * 64 + lane.
+    if constexpr (BWD) write_transposed(rec + 2 * HALF, Pm, wave, lane);
+    else {
         char* out = rec + HALF;
 #pragma unroll
         for (int it = 0; it < 2; ++it) {
@@ -346,6 +381,7 @@ __global__ __launch_bounds__(256, 3) void intra_bf16_kernel(IntraArgs<bf16_t> a)
                 st16(rec + (size_t)(ctp * 64 + lane) * 16, v);
             }
         }
+        if constexpr (BWD) write_transposed(rec + HALF, M, wave, lane);      // M^T
     }
 }
 
@@ -353,8 +389,18 @@ hipError_t launch_intra_bf16(const IntraArgs<bf16_t>& a, int dk, int n_chunks, h
 {
     if (n_chunks == 0) return hipSuccess;
     const dim3 grid((unsigned)n_chunks * a.H), block(256);
-    if (dk == 64) hipLaunchKernelGGL((intra_bf16_kernel<64>), grid, block, 0, st, a);
-    else          hipLaunchKernelGGL((intra_bf16_kernel<128>), grid, block, 0, st, a);
+    if (dk == 64) hipLaunchKernelGGL((intra_bf16_kernel<64, false>), grid, block, 0, st, a);
+    else          hipLaunchKernelGGL((intra_bf16_kernel<128, false>), grid, block, 0, st, a);
+    return hipGetLastError();
+}
+
+// the records of the backward pass at a.wsT; a.wsP and a.wsG unused, a.opts = 0
+hipError_t launch_intra_bwd_bf16(const IntraArgs<bf16_t>& a, int dk, int n_chunks, hipStream_t st)
+{
+    if (n_chunks == 0) return hipSuccess;
+    const dim3 grid((unsigned)n_chunks * a.H), block(256);
+    if (dk == 64) hipLaunchKernelGGL((intra_bf16_kernel<64, true>), grid, block, 0, st, a);
+    else          hipLaunchKernelGGL((intra_bf16_kernel<128, true>), grid, block, 0, st, a);
     return hipGetLastError();
 }
 

@@ -85,6 +85,7 @@ template <typename E> struct BwdArgs {
 template <typename E> hipError_t launch_bwd_states(const BwdArgs<E>& a, int dk, int waves, hipStream_t st);
 template <typename E> hipError_t launch_bwd_scan(const BwdArgs<E>& a, int dk, int waves, hipStream_t st);
 // bf16 specialisations of the two sweeps (copy wave, LDS ring, transposing reads: see kla_chunk_bwd_bf16.hip)
+hipError_t launch_intra_bwd_bf16(const IntraArgs<bf16_t>& a, int dk, int n_chunks, hipStream_t st);
 hipError_t launch_bwd_states_bf16(const BwdArgs<bf16_t>& a, int dk, int waves, hipStream_t st);
 hipError_t launch_bwd_scan_bf16(const BwdArgs<bf16_t>& a, int dk, int waves, hipStream_t st);
 hipError_t launch_bwd_assemble_bf16(const BwdArgs<bf16_t>& a, int dk, long n_chunks, hipStream_t st);

@@ -103,6 +103,13 @@ def test_bwd_varlen(kla, dt):
     _check(kla, d, seed=2)
 
 
+@pytest.mark.parametrize("dk,dv,T", [(128, 128, 200), (64, 256, 130)])
+def test_bwd_generic_kernels_on_bf16(kla, dk, dv, T, monkeypatch):
+    """KLA_BWD_IMPL=generic: the element-type-generic kernels (the fp32 path's) on bf16 inputs."""
+    monkeypatch.setenv("KLA_BWD_IMPL", "generic")
+    _check(kla, kla_inputs.chunk_inputs(2, T, 2, dk, dv, dtype=torch.bfloat16, seed=325, h0_std=0.3), seed=9)
+
+
 def test_bwd_two_waves_per_workgroup(kla):
     """Enough (sequence, head) pairs for the 32-column workgroups the benchmark shape uses."""
     _check(kla, kla_inputs.chunk_inputs(16, 192, 4, 128, 128, dtype=torch.bfloat16, seed=330, h0_std=0.1), seed=3)
