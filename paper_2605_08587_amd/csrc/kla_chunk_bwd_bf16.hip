@@ -401,15 +401,19 @@ __global__ __launch_bounds__(256, 2) void bwd_assemble_bf16_kernel(BwdArgs<bf16_
 {
     constexpr int KB = DK / 16, KP = DK / 32;
     constexpr int RB = DK * 2, PPR = DK / 8, RPB = 1024 / RB, NKB = 64 / RPB;      // [64 x d_k] tiles
-    constexpr int RBA = 128, NAB = 8;                                                // [64 x 64] slabs: 8 blocks of 8 rows
-    constexpr int TK = 64 * RB, TA = 64 * RBA;
+    constexpr int RBA = 64, NAB = 4;                 // [64 tokens x 32 columns] slabs: 4 blocks of 16 rows of 64 bytes
+    constexpr int TK = 64 * RB, TS = 32 * RB, NSB = TS / 1024, TA = 64 * RBA;
     constexpr int kLd = 68, MB = 64 * kLd * 4;
-    // first phase: S^T | dS'^T | dO | U | Y | X          second phase: K | Q | A o dP | D'
-    constexpr int OFF_S = 0, OFF_DS = TK, OFF_DO = 2 * TK, OFF_U = OFF_DO + TA, OFF_Y = OFF_U + TA, OFF_X = OFF_Y + TA;
-    constexpr int PH1 = 2 * TK + 4 * TA;
+    // first phase, two buffers of one 32-column slab each: S^T | dS'^T | dO | U | Y | X
+    constexpr int OFF_S = 0, OFF_DS = TS, OFF_DO = 2 * TS, OFF_U = OFF_DO + TA, OFF_Y = OFF_U + TA, OFF_X = OFF_Y + TA;
+    constexpr int SLAB = 2 * TS + 4 * TA;
+    constexpr int PH1 = 2 * SLAB;
+    // second phase: K | Q | A o dP | D'.  K and Q are fetched into the first buffer while the last slab (always in the
+    // second one: d_v / 32 is even) is being used.
     constexpr int OFF_K = 0, OFF_Q = TK, OFF_E1 = 2 * TK, OFF_DP = 2 * TK + MB;
     constexpr int PH2 = 2 * TK + 2 * MB;
     constexpr int BIG = PH1 > PH2 ? PH1 : PH2;
+    static_assert(2 * TK <= SLAB, "the K and Q tiles fit one slab buffer");
     constexpr int ORQ = RB + 16;                     // row stride of the dq / dk staging tiles (over A o dP and D')
     static_assert(64 * ORQ <= MB, "staging tiles fit the fp32 matrices they replace");
     __shared__ __attribute__((aligned(1024))) char lds[BIG];
@@ -446,11 +450,12 @@ __global__ __launch_bounds__(256, 2) void bwd_assemble_bf16_kernel(BwdArgs<bf16_
     }
 
     // ---- per-lane offsets ---------------------------------------------------------------------------
-    // copies of [64 x d_k] tiles (global row stride `stride`) and of [64 x 64] slabs, swizzled on the global side
+    // copies of [rows x d_k] tiles and of [64 x 32] slabs, swizzled on the global side (the 16-byte column index is
+    // XORed with swz_bits(row) resp. (row / 2) % 4)
     const int lrow = lane / PPR, pcol = lane % PPR;
-    const int lrowA = lane >> 3, pcolA = lane & 7;
-    // The per-lane part of a copy's address does not depend on the block (8 rows per block) or only on its parity
-    // (4 rows per block) unless the chunk is ragged, where rows past its end re-read the last one.
+    const int lrowA = lane >> 2, pcolA = lane & 3;
+    // The per-lane part of a copy's address does not depend on the block, or only on its parity (4 rows per block),
+    // unless the chunk is ragged, where rows past its end re-read the last one.
     const bool full = clen == 64;
     int gkq[2], gst[2];
 #pragma unroll
@@ -458,7 +463,7 @@ __global__ __launch_bounds__(256, 2) void bwd_assemble_bf16_kernel(BwdArgs<bf16_
         gkq[par] = lrow * (int)kq_row + ((pcol ^ swz_bits(RPB * par + lrow)) * 16);
         gst[par] = lrow * RB + ((pcol ^ swz_bits(RPB * par + lrow)) * 16);
     }
-    const int gsl = lrowA * (int)v_row + ((pcolA ^ swz_bits(lrowA)) * 16);
+    const int gsl = lrowA * (int)v_row + ((pcolA ^ ((lrowA >> 1) & 3)) * 16);
     auto copy_tile = [&](const char* src, size_t stride, char* dst, int b0, int b1) {       // blocks [b0, b1) of a [64 x d_k] tile
         for (int b = b0; b < b1; ++b) {
             const int row = b * RPB + lrow;
@@ -466,34 +471,35 @@ __global__ __launch_bounds__(256, 2) void bwd_assemble_bf16_kernel(BwdArgs<bf16_
             else      dma16(src, min(row, clen - 1) * (int)stride + ((pcol ^ swz_bits(row)) * 16), dst + b * 1024);
         }
     };
-    auto copy_state = [&](const char* src, char* dst) {                                      // rows are d_v indices: never ragged
-        static_for<NKB>([&](auto bb) {
+    auto copy_state = [&](const char* src, char* dst) {                                      // 32 rows of a checkpoint: never ragged
+        static_for<NSB>([&](auto bb) {
             const int b = bb;
             dma16(src + b * RPB * RB, gst[(RPB == 4) ? (b & 1) : 0], dst + b * 1024);
         });
     };
-    auto copy_slab = [&](const char* src, char* dst) {                                       // 8 blocks of 8 token rows x 128 bytes
+    auto copy_slab = [&](const char* src, char* dst) {                                       // 4 blocks of 16 token rows x 64 bytes
         static_for<NAB>([&](auto bb) {
             const int b = bb;
-            if (full) dma16(src + (size_t)(b * 8) * v_row, gsl, dst + b * 1024);
-            else      dma16(src, min(b * 8 + lrowA, clen - 1) * (int)v_row + ((pcolA ^ swz_bits(b * 8 + lrowA)) * 16), dst + b * 1024);
+            if (full) dma16(src + (size_t)(b * 16) * v_row, gsl, dst + b * 1024);
+            else      dma16(src, min(b * 16 + lrowA, clen - 1) * (int)v_row + ((pcolA ^ ((lrowA >> 1) & 3)) * 16), dst + b * 1024);
         });
     };
-    // row-contracted operand of a slab: token row 16 t + r, contraction indices 32 kp + {4 g .. +3 | 16 + 4 g .. +3}
-    const int arow = r * RBA, asw = swz_bits(r), ahalf = (g & 1) * 8;
-    auto aslot = [&](int off, int t, int kp, u32x2& q0, u32x2& q1) {
-        const char* p = lds + off + 16 * t * RBA + arow + ahalf;
-        q0 = *reinterpret_cast<const u32x2*>(p + (((4 * kp + (g >> 1)) ^ asw) * 16));
-        q1 = *reinterpret_cast<const u32x2*>(p + (((4 * kp + 2 + (g >> 1)) ^ asw) * 16));
+    // row-contracted operand of a slab: token row 16 t + r, contraction indices {4 g .. +3 | 16 + 4 g .. +3}
+    const int arow = r * RBA + (g & 1) * 8, asw = (r >> 1) & 3;
+    const int acol0 = ((g >> 1) ^ asw) * 16, acol1 = ((2 + (g >> 1)) ^ asw) * 16;
+    auto aslot = [&](const char* tile, int t, u32x2& q0, u32x2& q1) {
+        const char* p = tile + 16 * t * RBA + arow;
+        q0 = *reinterpret_cast<const u32x2*>(p + acol0);
+        q1 = *reinterpret_cast<const u32x2*>(p + acol1);
     };
     // column-contracted operand of a [64 x d_k] tile through the transposing read (as K^T in the sweeps)
     const int a4 = r >> 2, c4 = r & 3;
     int oKT[2];
 #pragma unroll
     for (int par = 0; par < 2; ++par) oKT[par] = (4 * g + a4) * RB + (((4 * par + c4) ^ swz_bits(4 * g + a4)) * 16);
-    auto tslot = [&](int off, int kt, int jp, u32x2& q0, u32x2& q1) {
+    auto tslot = [&](const char* tile, int kt, int jp, u32x2& q0, u32x2& q1) {
         const int kp = kt >> 1, b = kt & 1;
-        const char* p = lds + off + oKT[kp & 1] + 32 * jp * RB + 128 * (kp >> 1) + 8 * b;
+        const char* p = tile + oKT[kp & 1] + 32 * jp * RB + 128 * (kp >> 1) + 8 * b;
         q0 = lds_read_tr(p);
         q1 = lds_read_tr(p + 16 * RB);
     };
@@ -505,67 +511,71 @@ __global__ __launch_bounds__(256, 2) void bwd_assemble_bf16_kernel(BwdArgs<bf16_
     for (int jt = 0; jt < 4; ++jt) { dP[jt] = floatx4{0.f, 0.f, 0.f, 0.f}; N1[jt] = dP[jt]; }
     float yx = 0.f, sdot = 0.f;
 
-    // ---- first phase: everything that contracts over d_v, 64 columns at a time -----------------------------
+    // ---- first phase: everything that contracts over d_v, 32 columns at a time; the next slab (after the last
+    //      one: K and Q) is on its way while a slab is used ---------------------------------------------------
     const char* Sg = reinterpret_cast<const char*>(a.s_chk) + (size_t)blockIdx.x * DK * a.dv_dim * 2;
     const char* dSg = reinterpret_cast<const char*>(a.ds_chk) + (size_t)blockIdx.x * DK * a.dv_dim * 2;
     const size_t vrow0 = (size_t)tok0 * v_row + (size_t)h * a.dv_dim * 2;
-    for (int slab0 = 0; slab0 < a.dv_dim; slab0 += 64) {
-        __syncthreads();                             // the previous slab's operands are no longer read
-        if (wave == 0)      copy_state(Sg + (size_t)slab0 * RB, lds + OFF_S);
-        else if (wave == 1) copy_state(dSg + (size_t)slab0 * RB, lds + OFF_DS);
+    auto issue_slab = [&](int sl, char* buf) {
+        if (wave == 0)      copy_state(Sg + (size_t)(32 * sl) * RB, buf + OFF_S);
+        else if (wave == 1) copy_state(dSg + (size_t)(32 * sl) * RB, buf + OFF_DS);
         else if (wave == 2) {
-            copy_slab(reinterpret_cast<const char*>(a.d_o) + vrow0 + slab0 * 2, lds + OFF_DO);
-            copy_slab(reinterpret_cast<const char*>(a.U) + vrow0 + slab0 * 2, lds + OFF_U);
+            copy_slab(reinterpret_cast<const char*>(a.d_o) + vrow0 + 64 * sl, buf + OFF_DO);
+            copy_slab(reinterpret_cast<const char*>(a.U) + vrow0 + 64 * sl, buf + OFF_U);
         } else {
-            copy_slab(reinterpret_cast<const char*>(a.Y) + vrow0 + slab0 * 2, lds + OFF_Y);
-            copy_slab(reinterpret_cast<const char*>(a.X) + vrow0 + slab0 * 2, lds + OFF_X);
+            copy_slab(reinterpret_cast<const char*>(a.Y) + vrow0 + 64 * sl, buf + OFF_Y);
+            copy_slab(reinterpret_cast<const char*>(a.X) + vrow0 + 64 * sl, buf + OFF_X);
         }
+    };
+    const int ns = a.dv_dim / 32;
+    issue_slab(0, lds);
+    for (int sl = 0; sl < ns; ++sl) {
+        const char* buf = lds + (sl & 1) * SLAB;
         wait_vmcnt<0>();
-        __syncthreads();
+        __syncthreads();                             // slab sl has landed; slab sl-1 is no longer read
+        if (sl + 1 < ns) issue_slab(sl + 1, lds + ((sl + 1) & 1) * SLAB);
+        else {
+            const char* kb = reinterpret_cast<const char*>(a.k) + (size_t)tok0 * kq_row + (size_t)h * DK * 2;
+            const char* qb = reinterpret_cast<const char*>(a.q) + (size_t)tok0 * kq_row + (size_t)h * DK * 2;
+            if (wave < 2) copy_tile(kb, kq_row, lds + OFF_K, wave * (NKB / 2), (wave + 1) * (NKB / 2));
+            else          copy_tile(qb, kq_row, lds + OFF_Q, (wave - 2) * (NKB / 2), (wave - 1) * (NKB / 2));
+        }
         // Y_i . X_i and <dS', S>: plain 16-byte pieces, the swizzle is the same for both tiles of a pair
         {
-            const int row = tid >> 2;
+            const u32x4 y = ld16(buf + OFF_Y + tid * 16), x = ld16(buf + OFF_X + tid * 16);
 #pragma unroll
-            for (int pc = 0; pc < 2; ++pc) {
-                const int o = row * RBA + ((tid & 3) + 4 * pc) * 16;
-                const u32x4 y = ld16(lds + OFF_Y + o), x = ld16(lds + OFF_X + o);
+            for (int m = 0; m < 4; ++m) yx = dot2_bf16(y[m], x[m], yx);
 #pragma unroll
-                for (int m = 0; m < 4; ++m) yx = dot2_bf16(y[m], x[m], yx);
-            }
-#pragma unroll
-            for (int pc = 0; pc < TK / 16 / 256; ++pc) {
+            for (int pc = 0; pc < TS / 16 / 256; ++pc) {
                 const int o = (tid + 256 * pc) * 16;
-                const u32x4 y = ld16(lds + OFF_S + o), x = ld16(lds + OFF_DS + o);
+                const u32x4 sv = ld16(buf + OFF_S + o), dv = ld16(buf + OFF_DS + o);
 #pragma unroll
-                for (int m = 0; m < 4; ++m) sdot = dot2_bf16(y[m], x[m], sdot);
+                for (int m = 0; m < 4; ++m) sdot = dot2_bf16(sv[m], dv[m], sdot);
             }
         }
+        u32x2 do0, do1, u0, u1, y0, y1;
+        aslot(buf + OFF_DO, wave, do0, do1);
+        aslot(buf + OFF_U, wave, u0, u1);
+        aslot(buf + OFF_Y, wave, y0, y1);
 #pragma unroll
-        for (int kp = 0; kp < 2; ++kp) {
-            u32x2 do0, do1, u0, u1, y0, y1;
-            aslot(OFF_DO, wave, kp, do0, do1);
-            aslot(OFF_U, wave, kp, u0, u1);
-            aslot(OFF_Y, wave, kp, y0, y1);
-#pragma unroll
-            for (int ct = 0; ct < KB; ++ct) {
-                u32x2 s0, s1, d0, d1;
-                tslot(OFF_S, ct, kp, s0, s1);
-                tslot(OFF_DS, ct, kp, d0, d1);
-                mma_bf16(dQ[ct], do0, do1, s0, s1);        // dO S^T
-                mma_bf16(dKr[ct], y0, y1, s0, s1);         // Y S^T
-                mma_bf16(dKw[ct], u0, u1, d0, d1);         // U dS'^T
-            }
-            static_for<4>([&](auto jt) {
-                if (jt <= wave) {                          // lower-triangular tiles only
-                    u32x2 b0, b1;
-                    aslot(OFF_U, jt, kp, b0, b1);
-                    mma_bf16(dP[jt], do0, do1, b0, b1);    // dO U^T
-                    mma_bf16(N1[jt], y0, y1, b0, b1);      // Y U^T
-                }
-            });
+        for (int ct = 0; ct < KB; ++ct) {
+            u32x2 s0, s1, d0, d1;
+            tslot(buf + OFF_S, ct, 0, s0, s1);
+            tslot(buf + OFF_DS, ct, 0, d0, d1);
+            mma_bf16(dQ[ct], do0, do1, s0, s1);            // dO S^T
+            mma_bf16(dKr[ct], y0, y1, s0, s1);             // Y S^T
+            mma_bf16(dKw[ct], u0, u1, d0, d1);             // U dS'^T
         }
+        static_for<4>([&](auto jt) {
+            if (jt <= wave) {                              // lower-triangular tiles only
+                u32x2 b0, b1;
+                aslot(buf + OFF_U, jt, b0, b1);
+                mma_bf16(dP[jt], do0, do1, b0, b1);        // dO U^T
+                mma_bf16(N1[jt], y0, y1, b0, b1);          // Y U^T
+            }
+        });
     }
-    if (wave == 0) {                                 // g_i = log gamma_i (the first barrier of the loop ordered the loads)
+    if (wave == 0) {                                 // g_i = log gamma_i
         float x = g_s[lane];
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) { const float y = __shfl_up(x, off, kWave); if (lane >= off) x += y; }
@@ -582,35 +592,29 @@ __global__ __launch_bounds__(256, 2) void bwd_assemble_bf16_kernel(BwdArgs<bf16_
     if ((tid & 3) == 0) yx_s[tid >> 2] = yx;
     sdot = wave_sum(sdot);
     if (lane == 0) red_s[wave] = sdot;
+    wait_vmcnt<0>();                                 // this wave's part of K and Q
     __syncthreads();                                 // the slab areas are dead from here on
 
-    // ---- second phase: K, Q tiles; A o dP and D' = -A^- o (Y U^T) as fp32 matrices ---------------------------
+    // ---- second phase: A o dP and D' = -A^- o (Y U^T) as fp32 matrices ------------------------------------------
     float* E1 = reinterpret_cast<float*>(lds + OFF_E1);
     float* Dp = reinterpret_cast<float*>(lds + OFF_DP);
-    {
-        const char* kb = reinterpret_cast<const char*>(a.k) + (size_t)tok0 * kq_row + (size_t)h * DK * 2;
-        const char* qb = reinterpret_cast<const char*>(a.q) + (size_t)tok0 * kq_row + (size_t)h * DK * 2;
-        if (wave < 2) copy_tile(kb, kq_row, lds + OFF_K, wave * (NKB / 2), (wave + 1) * (NKB / 2));
-        else          copy_tile(qb, kq_row, lds + OFF_Q, (wave - 2) * (NKB / 2), (wave - 1) * (NKB / 2));
-        static_for<4>([&](auto jt) {
-            const int j = 16 * jt + r;
-            const float gj = g_s[j];
+    static_for<4>([&](auto jt) {
+        const int j = 16 * jt + r;
+        const float gj = g_s[j];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int i = 16 * wave + 4 * g + e;
-                const float dec = (jt <= wave && j <= i && i < clen) ? __builtin_amdgcn_exp2f(g_s[i] - gj) : 0.f;
-                E1[i * kLd + j] = dec * dP[jt][e];
-                Dp[i * kLd + j] = (j < i) ? -dec * N1[jt][e] : 0.f;
-            }
-        });
-        wait_vmcnt<0>();
-    }
+        for (int e = 0; e < 4; ++e) {
+            const int i = 16 * wave + 4 * g + e;
+            const float dec = (jt <= wave && j <= i && i < clen) ? __builtin_amdgcn_exp2f(g_s[i] - gj) : 0.f;
+            E1[i * kLd + j] = dec * dP[jt][e];
+            Dp[i * kLd + j] = (j < i) ? -dec * N1[jt][e] : 0.f;
+        }
+    });
     __syncthreads();
 
     // K and Q of this wave's rows as accumulator tiles: token 16 wave + 4 g + e, feature of (tile ct, lane r)
     auto kacc = [&](int off, int ct) {
         u32x2 q0, q1;
-        tslot(off, ct, wave >> 1, q0, q1);
+        tslot(lds + off, ct, wave >> 1, q0, q1);
         return quad_to_f((wave & 1) ? q1 : q0);
     };
     floatx4 rowmask;                                 // 1 for the rows of the chunk, 0 past a ragged end
@@ -652,7 +656,7 @@ __global__ __launch_bounds__(256, 2) void bwd_assemble_bf16_kernel(BwdArgs<bf16_
 #pragma unroll
             for (int ct = 0; ct < KB; ++ct) {
                 u32x2 k0, k1;
-                tslot(OFF_K, ct, jp, k0, k1);
+                tslot(lds + OFF_K, ct, jp, k0, k1);
                 mma_bf16(dQ[ct], e0, e1, k0, k1);          // (A o dP) K
                 mma_bf16(E2[ct], d0, d1, k0, k1);          // D' K
             }
@@ -664,8 +668,8 @@ __global__ __launch_bounds__(256, 2) void bwd_assemble_bf16_kernel(BwdArgs<bf16_
 #pragma unroll
             for (int ct = 0; ct < KB; ++ct) {
                 u32x2 k0, k1, q0, q1;
-                tslot(OFF_Q, ct, jp, q0, q1);
-                tslot(OFF_K, ct, jp, k0, k1);
+                tslot(lds + OFF_Q, ct, jp, q0, q1);
+                tslot(lds + OFF_K, ct, jp, k0, k1);
                 mma_bf16(dKw[ct], e0, e1, q0, q1);         // (A o dP)^T Q
                 mma_bf16(dKw[ct], d0, d1, k0, k1);         // (B D')^T K
             }
