@@ -172,3 +172,41 @@ def test_workspace_bytes_of_the_segmented_scan(monkeypatch):
     big = f(8, 4096, 8, 128, 128, 64, kla.KLA_BF16, None, 0)
     monkeypatch.setenv("KLA_SCAN_SEGMENTS", "1")
     assert f(8, 4096, 8, 128, 128, 64, kla.KLA_BF16, None, 0) == big
+
+
+def test_chunk_bwd_validation_and_workspace():
+    """kla_chunk_bwd validates like kla_chunk_fwd (before any launch), and its workspace is the documented sum:
+    per chunk-head a record [T' | M^T | P^T | 4 vectors], two state checkpoints in the element type, and three
+    [tokens, H, dv] arrays in the element type."""
+    lib = kla.lib()
+    names = ("q", "k", "v", "la", "eta", "eps", "h0", "d_o", "d_hT", "dq", "dk_", "dv_", "dla", "deta", "dh0", "cu_dev",
+             "cu_host", "n_seq", "N", "T", "H", "dk", "dv", "chunk", "dt", "ws", "ws_bytes", "stream")
+    base = dict(q=0x1000, k=0x2000, v=0x3000, la=0x4000, eta=0x5000, eps=1e-6, h0=None, d_o=0x6000, d_hT=None,
+                dq=0x7000, dk_=0x8000, dv_=0x9000, dla=0xa000, deta=0xb000, dh0=None, cu_dev=None, cu_host=None, n_seq=0,
+                N=1, T=64, H=1, dk=64, dv=64, chunk=64, dt=kla.KLA_BF16, ws=0x100000, ws_bytes=1 << 30, stream=None)
+    call = lambda **o: lib.kla_chunk_bwd(*[{**base, **o}[n] for n in names])
+    assert call(q=None) == E_NULL
+    assert call(d_o=None) == E_NULL
+    assert call(dk_=None) == E_NULL
+    assert call(deta=None) == E_NULL
+    assert call(dk=96) == E_SHAPE
+    assert call(chunk=32) == E_SHAPE
+    assert call(eps=-1.0) == E_SHAPE
+    assert call(dt=5) == E_DTYPE
+    assert call(d_o=0x6008) == E_ALIGN
+    assert call(dh0=0xc004) == E_ALIGN
+    assert call(ws=None) == E_WS
+    assert call(ws_bytes=1000) == E_WS
+    cu = np.array([0, 30, 64], dtype=np.int32)
+    assert call(n_seq=2, cu_host=cu.ctypes.data, cu_dev=None) == E_NULL
+    assert call(N=0) == OK
+    r256 = lambda x: (x + 255) // 256 * 256
+    for dt, eb in ((kla.KLA_BF16, 2), (kla.KLA_F32, 4)):
+        N, T, H, dk, dv = 3, 200, 2, 128, 256
+        n_ch = N * 4 * H
+        expect = r256(n_ch * (3 * 384 * 8 * eb + 1024))
+        expect = r256(expect + 4)                              # chunk offsets of a packed batch (n_seq + 1 ints)
+        expect += 2 * r256(n_ch * dk * dv * eb)                # S_c and dS'_c
+        expect += 3 * r256(N * T * H * dv * eb)                # X, U, Y
+        assert lib.kla_chunk_bwd_workspace_bytes(N, T, H, dk, dv, 64, dt, None, 0) == expect
+    assert lib.kla_chunk_bwd_workspace_bytes(1, 64, 1, 100, 64, 64, kla.KLA_BF16, None, 0) == 0
