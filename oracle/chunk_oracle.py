@@ -177,3 +177,48 @@ def kla_chunkwise_bwd_unit(q, k, v, log_alpha, eta, eps, d_o, h0=None, d_hT=None
     if want:
         return out, keep[::-1]
     return out
+
+
+def kla_chunkwise_diag_unit(q, k, v, log_alpha, eta, eps, h0=None, chunk=64, want=False):
+    """Chunkwise form with diagonal gating (App. B, "Extension to diagonal gating") for one (sequence, head).
+
+    log_alpha is [T, dk].  gamma_i becomes a vector (running product of alpha per key channel, restarting at each
+    chunk) and every decay ratio acts elementwise inside the inner products:
+        L_ij = beta_i sum_c k_ic k_jc gamma_ic/gamma_jc  (j < i),     P_ij = sum_c q_ic k_jc gamma_ic/gamma_jc  (j <= i)
+        (I + L) U = B (V - (K o Gamma) S_0),     O = (Q o Gamma) S_0 + P U,
+        S_out = diag(gamma_C) S_0 + (K o (gamma_C / Gamma))^T U.
+    The ratios are formed as exp of differences of the running log sums.  Returns (o, hT) and, if want, the per-chunk
+    T = (I + L)^-1, P, beta and g.
+    """
+    q = np.asarray(q, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    la = np.asarray(log_alpha, dtype=np.float64)
+    et = np.asarray(eta, dtype=np.float64)
+    T_len, dk = k.shape
+    dv = v.shape[1]
+    S = np.zeros((dk, dv)) if h0 is None else np.array(h0, dtype=np.float64)
+    o = np.zeros((T_len, dv))
+    inter = []
+    for c0 in range(0, T_len, chunk):
+        c1 = min(T_len, c0 + chunk)
+        K, V, Q = k[c0:c1], v[c0:c1], q[c0:c1]
+        c = c1 - c0
+        g = np.cumsum(la[c0:c1], axis=0)                                   # [c, dk]
+        den = np.sum(K * K, axis=1) + eps
+        beta = np.where(den == 0.0, 0.0, et[c0:c1] / np.where(den == 0.0, 1.0, den))
+        ratio = np.exp(np.minimum(g[:, None, :] - g[None, :, :], 0.0))     # [i, j, channel]; only j <= i is used
+        KK = np.einsum("ic,jc,ijc->ij", K, K, ratio)
+        QK = np.einsum("ic,jc,ijc->ij", Q, K, ratio)
+        L = beta[:, None] * np.tril(KK, -1)
+        P = np.tril(QK)
+        gam = np.exp(g)
+        rhs = beta[:, None] * (V - (K * gam) @ S)
+        U = solve_triangular(np.eye(c) + L, rhs, lower=True, unit_diagonal=True)
+        o[c0:c1] = (Q * gam) @ S + P @ U
+        if want:
+            inter.append(dict(beta=beta, g=g, P=P, T=solve_triangular(np.eye(c) + L, np.eye(c), lower=True, unit_diagonal=True)))
+        S = gam[-1][:, None] * S + (K * np.exp(g[-1][None, :] - g)).T @ U
+    if want:
+        return o, S, inter
+    return o, S

@@ -36,6 +36,12 @@
  * Kaczmarz limits checked against numpy's pseudo-inverse, a hand-worked
  * rational example under tests/golden/).
  *
+ * Diagonal gating (the *_diag entry points): the decay operator of line 1 is
+ * D_t = diag(alpha_t) with one decay per key channel (App. B, "Extension to
+ * diagonal gating"; the decay-agnostic remark of App. A), S~ = diag(alpha_t) S,
+ * i.e. row i of the d_k x d_v state is scaled by alpha_t[i].  Lines 2-5 are
+ * unchanged.  log_alpha then has d_k entries per token and head.
+ *
  * Gradients (kla_oracle_sequence_bwd): the paper states the forward map only and
  * mentions training without deriving a backward pass, so the gradient oracle is
  * the plain reverse accumulation through the same five lines of Algorithm 1
@@ -295,5 +301,76 @@ int kla_oracle_sequence_bwd(const float *q, const float *k, const float *v,
     }
     if (dh0) memcpy(dh0, dS, sizeof(double) * sz);
     free(chk); free(st); free(St); free(dS); free(e); free(de);
+    return 0;
+}
+
+/* One token with diagonal gating: row i of S decays by exp(log_alpha[i]); lines 2-5 as in kla_token. */
+static void kla_token_diag(double *S, const float *q, const float *k, const float *v,
+                           const double *log_alpha, double eta, double eps, int dk, int dv,
+                           double *o, double *e)
+{
+    int i, j;
+    /* line 1 with D_t = diag(alpha_t): S~ = diag(alpha) S */
+    for (i = 0; i < dk; ++i) {
+        const double alpha = exp(log_alpha[i]);
+        for (j = 0; j < dv; ++j)
+            S[(size_t)i * dv + j] *= alpha;
+    }
+    /* line 2: e = v - S~^T k */
+    for (j = 0; j < dv; ++j) {
+        double p = 0.0;
+        for (i = 0; i < dk; ++i)
+            p += S[(size_t)i * dv + j] * (double)k[i];
+        e[j] = (double)v[j] - p;
+    }
+    /* line 3 / eq. (3) */
+    double nk = 0.0;
+    for (i = 0; i < dk; ++i)
+        nk += (double)k[i] * (double)k[i];
+    const double den = nk + eps;
+    const double beta = (den == 0.0) ? 0.0 : eta / den;
+    /* line 4: S = S~ + beta k e^T */
+    for (i = 0; i < dk; ++i)
+        for (j = 0; j < dv; ++j)
+            S[(size_t)i * dv + j] += beta * (double)k[i] * e[j];
+    /* line 5: o = S^T q */
+    for (j = 0; j < dv; ++j) {
+        double r = 0.0;
+        for (i = 0; i < dk; ++i)
+            r += S[(size_t)i * dv + j] * (double)q[i];
+        o[j] = r;
+    }
+}
+
+/* kla_oracle_sequence with diagonal gating: log_alpha is [n_tokens_total, H, dk]; everything else as there. */
+int kla_oracle_sequence_diag(const float *q, const float *k, const float *v,
+                             const double *log_alpha, const double *eta, double eps,
+                             const double *h0, double *o, double *hT,
+                             long t0, long len, int h, int H, int dk, int dv)
+{
+    double *S = (double *)malloc(sizeof(double) * (size_t)dk * dv);
+    double *e = (double *)malloc(sizeof(double) * (size_t)dv);
+    if (!S || !e) { free(S); free(e); return -1; }
+    if (h0) memcpy(S, h0, sizeof(double) * (size_t)dk * dv);
+    else    memset(S, 0, sizeof(double) * (size_t)dk * dv);
+    for (long t = t0; t < t0 + len; ++t) {
+        const size_t th = (size_t)t * H + h;
+        kla_token_diag(S, q + th * dk, k + th * dk, v + th * dv, log_alpha + th * dk, eta[th], eps, dk, dv,
+                       o + th * dv, e);
+    }
+    if (hT) memcpy(hT, S, sizeof(double) * (size_t)dk * dv);
+    free(S); free(e);
+    return 0;
+}
+
+/* One decode step with diagonal gating: log_alpha has dk entries. */
+int kla_oracle_decode_unit_diag(const float *q, const float *k, const float *v,
+                                const double *log_alpha, double eta, double eps,
+                                double *S, double *o, int dk, int dv)
+{
+    double *e = (double *)malloc(sizeof(double) * (size_t)dv);
+    if (!e) return -1;
+    kla_token_diag(S, q, k, v, log_alpha, eta, eps, dk, dv, o, e);
+    free(e);
     return 0;
 }

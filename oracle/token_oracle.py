@@ -53,6 +53,11 @@ def _load():
                                                    ctypes.c_double, dp, dp, ctypes.c_int, ctypes.c_int]
             lib.kla_oracle_decode_unit_opts.restype = ctypes.c_int
             lib.kla_oracle_decode_unit_opts.argtypes = lib.kla_oracle_decode_unit.argtypes + [ctypes.c_int, ctypes.c_int]
+            lib.kla_oracle_sequence_diag.restype = ctypes.c_int
+            lib.kla_oracle_sequence_diag.argtypes = lib.kla_oracle_sequence.argtypes
+            lib.kla_oracle_decode_unit_diag.restype = ctypes.c_int
+            lib.kla_oracle_decode_unit_diag.argtypes = [fp, fp, fp, dp, ctypes.c_double, ctypes.c_double, dp, dp,
+                                                        ctypes.c_int, ctypes.c_int]
             lib.kla_oracle_sequence_bwd.restype = ctypes.c_int
             lib.kla_oracle_sequence_bwd.argtypes = [fp, fp, fp, dp, dp, ctypes.c_double, dp, dp, dp,
                                                     dp, dp, dp, dp, dp, dp,
@@ -130,6 +135,67 @@ def kla_recurrent(q, k, v, log_alpha, eta, eps, h0=None, cu_seqlens=None, thread
         with ThreadPoolExecutor(nthr) as ex:
             list(ex.map(run, todo))
     return o, hT, nthr
+
+
+def kla_recurrent_diag(q, k, v, log_alpha, eta, eps, h0=None, cu_seqlens=None, threads=None, units=None):
+    """kla_recurrent with diagonal gating (App. B): log_alpha is [N, T, H, dk], one decay per key channel."""
+    lib = _load()
+    q, k, v = _f32(q), _f32(k), _f32(v)
+    la, et = _f64(log_alpha), _f64(eta)
+    N, T, H, dk = q.shape
+    dv = v.shape[-1]
+    assert la.shape == (N, T, H, dk)
+    if cu_seqlens is None:
+        starts = [n * T for n in range(N)]
+        lens = [T] * N
+    else:
+        assert N == 1
+        cu = [int(x) for x in cu_seqlens]
+        starts = cu[:-1]
+        lens = [cu[i + 1] - cu[i] for i in range(len(cu) - 1)]
+    n_seq = len(starts)
+    h0d = None if h0 is None else _f64(h0)
+    o = np.zeros((N, T, H, dv), dtype=np.float64)
+    hT = np.zeros((n_seq, H, dk, dv), dtype=np.float64)
+    todo = [(s, h) for s in range(n_seq) for h in range(H)] if units is None else list(units)
+
+    def run(unit):
+        s, h = unit
+        off = (s * H + h) * dk * dv
+        rc = lib.kla_oracle_sequence_diag(_fp(q), _fp(k), _fp(v), _dp(la), _dp(et), float(eps),
+                                          None if h0d is None else _dp(h0d, off), _dp(o), _dp(hT, off),
+                                          starts[s], lens[s], h, H, dk, dv)
+        if rc != 0:
+            raise MemoryError("oracle scratch allocation failed")
+
+    nthr = max(1, min(threads or default_threads(), len(todo))) if todo else 1
+    if nthr == 1:
+        for u in todo:
+            run(u)
+    else:
+        with ThreadPoolExecutor(nthr) as ex:
+            list(ex.map(run, todo))
+    return o, hT, nthr
+
+
+def kla_decode_diag(q, k, v, log_alpha, eta, eps, S, threads=None):
+    """kla_decode with diagonal gating: log_alpha is [B, H, dk].  Returns (o, S_new); S is not modified."""
+    lib = _load()
+    q, k, v = _f32(q), _f32(k), _f32(v)
+    la, et = _f64(log_alpha), _f64(eta)
+    S = np.array(S, dtype=np.float64, order="C", copy=True)
+    B, H, dk = q.shape
+    dv = v.shape[-1]
+    o = np.zeros((B, H, dv), dtype=np.float64)
+    for u in range(B * H):
+        rc = lib.kla_oracle_decode_unit_diag(
+            ctypes.cast(q.ctypes.data + 4 * u * dk, ctypes.POINTER(ctypes.c_float)),
+            ctypes.cast(k.ctypes.data + 4 * u * dk, ctypes.POINTER(ctypes.c_float)),
+            ctypes.cast(v.ctypes.data + 4 * u * dv, ctypes.POINTER(ctypes.c_float)),
+            _dp(la, u * dk), float(et.reshape(-1)[u]), float(eps), _dp(S, u * dk * dv), _dp(o, u * dv), dk, dv)
+        if rc != 0:
+            raise MemoryError("oracle scratch allocation failed")
+    return o, S
 
 
 def kla_recurrent_bwd(q, k, v, log_alpha, eta, eps, d_o, h0=None, d_hT=None, cu_seqlens=None, threads=None,

@@ -486,3 +486,83 @@ def test_chunkwise_gradient_equals_recurrent(C):
         r = ref[name][0, :, 0]
         assert np.max(np.abs(got[name] - r)) <= 1e-9 * np.max(np.abs(r)), name
     assert np.max(np.abs(got["dh0"] - ref["dh0"][0, 0])) <= 1e-9 * np.max(np.abs(ref["dh0"]))
+
+
+# ---- diagonal gating (App. B, "Extension to diagonal gating") -----------------------------------------
+def _rand_diag(rng, T, H, dk, dv, N=1):
+    q, k, v, la, eta, S0 = _rand_problem(rng, T, H, dk, dv, N=N)
+    lad = -np.log1p(np.exp(rng.standard_normal((N, T, H, dk))))
+    return q, k, v, lad, eta, S0
+
+
+def test_diag_equal_channels_is_scalar_gating():
+    """diag(alpha) with all channels equal is alpha I: the diagonal oracle then repeats the scalar one."""
+    rng = RNG(51)
+    T, H, dk, dv = 40, 2, 6, 5
+    q, k, v, la, eta, S0 = _rand_problem(rng, T, H, dk, dv, N=2)
+    lad = np.repeat(la[..., None], dk, axis=-1)
+    o1, h1, _ = token_oracle.kla_recurrent(q, k, v, la, eta, 1e-3, h0=S0)
+    o2, h2, _ = token_oracle.kla_recurrent_diag(q, k, v, lad, eta, 1e-3, h0=S0)
+    np.testing.assert_allclose(o2, o1, rtol=1e-13, atol=1e-15)
+    np.testing.assert_allclose(h2, h1, rtol=1e-13, atol=1e-15)
+
+
+def test_diag_projection_property_is_decay_agnostic():
+    """App. A, decay-agnostic remark: with eta = 1, eps = 0 the written state satisfies S_t^T k_t = v_t whatever
+    linear decay produced the base point; and the residual contracts by 1 - eta |k|^2/(|k|^2+eps) in general."""
+    rng = RNG(52)
+    T, dk, dv = 12, 7, 4
+    q, k, v, lad, eta, S0 = _rand_diag(rng, T, 1, dk, dv)
+    S = S0[0, 0].copy()
+    for t in range(T):
+        kt = k[0, t, 0].astype(np.float64)
+        S_tilde = np.exp(lad[0, t, 0])[:, None] * S
+        e = v[0, t, 0] - S_tilde.T @ kt
+        _, S1 = token_oracle.kla_decode_diag(q[0, t][None], k[0, t][None], v[0, t][None], lad[0, t][None], np.ones((1, 1)), 0.0, S[None, None])
+        assert np.max(np.abs(S1[0, 0].T @ kt - v[0, t, 0])) <= 1e-12 * np.max(np.abs(v[0, t, 0]))
+        eps, et = 0.3, float(eta[0, t, 0])
+        _, S2 = token_oracle.kla_decode_diag(q[0, t][None], k[0, t][None], v[0, t][None], lad[0, t][None], np.array([[et]]), eps, S[None, None])
+        nk = kt @ kt
+        np.testing.assert_allclose(v[0, t, 0] - S2[0, 0].T @ kt, (1.0 - et * nk / (nk + eps)) * e, rtol=1e-11, atol=1e-13)
+        S = S2[0, 0]
+
+
+def test_diag_product_form_brute_force():
+    """S_T = M_T ... M_1 S_0 + sum_j M_T ... M_{j+1} beta_j k_j v_j^T with the explicit d_k x d_k transitions
+    M_s = (I - beta_s k_s k_s^T) diag(alpha_s) (eq. (5) with the diagonal decay operator), and o_t = S_t^T q_t."""
+    rng = RNG(53)
+    T, dk, dv, eps = 7, 4, 3, 1e-2
+    q, k, v, lad, eta, S0 = _rand_diag(rng, T, 1, dk, dv)
+    o, hT, _ = token_oracle.kla_recurrent_diag(q, k, v, lad, eta, eps, h0=S0)
+    S = S0[0, 0].copy()
+    for t in range(T):
+        kt = k[0, t, 0].astype(np.float64)
+        beta = eta[0, t, 0] / (kt @ kt + eps)
+        M = (np.eye(dk) - beta * np.outer(kt, kt)) @ np.diag(np.exp(lad[0, t, 0]))
+        S = M @ S + beta * np.outer(kt, v[0, t, 0])
+        np.testing.assert_allclose(o[0, t, 0], S.T @ q[0, t, 0], rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(hT[0, 0], S, rtol=1e-12, atol=1e-14)
+
+
+def test_diag_pure_decay_eta_zero():
+    """eta = 0: every row of the state decays by its own running product."""
+    rng = RNG(54)
+    T, H, dk, dv = 33, 2, 5, 4
+    q, k, v, lad, eta, S0 = _rand_diag(rng, T, H, dk, dv)
+    o, hT, _ = token_oracle.kla_recurrent_diag(q, k, v, lad, np.zeros_like(eta), 1e-6, h0=S0)
+    cum = np.exp(np.cumsum(lad, axis=1))                                  # [N,T,H,dk]
+    np.testing.assert_allclose(hT, cum[:, -1][..., None] * S0, rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(o, np.einsum("nthk,nhkv,nthk->nthv", cum, S0, q.astype(np.float64)), rtol=1e-11, atol=1e-13)
+
+
+@pytest.mark.parametrize("C", [1, 16, 64])
+def test_diag_chunkwise_equals_recurrent(C):
+    """The elementwise-decay chunk algebra (App. B) against the token loop, with a ragged tail and h0."""
+    rng = RNG(55)
+    T, dk, dv, eps = 150, 6, 5, 1e-3
+    q, k, v, lad, eta, S0 = _rand_diag(rng, T, 1, dk, dv)
+    o, hT, _ = token_oracle.kla_recurrent_diag(q, k, v, lad, eta, eps, h0=S0)
+    oc, hc = chunk_oracle.kla_chunkwise_diag_unit(q[0, :, 0], k[0, :, 0], v[0, :, 0], lad[0, :, 0], eta[0, :, 0], eps,
+                                                  h0=S0[0, 0], chunk=C)
+    assert np.max(np.abs(oc - o[0, :, 0])) <= 1e-10 * np.max(np.abs(o))
+    assert np.max(np.abs(hc - hT[0, 0])) <= 1e-10 * np.max(np.abs(hT))
