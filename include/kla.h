@@ -168,6 +168,31 @@ int kla_chunk_bwd(const void *q, const void *k, const void *v,
                   void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * Diagonal gating (App. B, "Extension to diagonal gating"; App. A, decay-agnostic remark): the decay operator is
+ * D_t = diag(alpha_t) with one decay per key channel, S~ = diag(alpha_t) S_{t-1} (row i of the d_k x d_v state is
+ * scaled by alpha_t[i]); the residual, the Kaczmarz coefficient of eq. (3), the write and the read-out are unchanged.
+ * Inside a chunk gamma_i becomes a vector and every decay ratio acts elementwise inside the inner products
+ * (L_ij = beta_i sum_c k_ic k_jc gamma_ic/gamma_jc, and likewise for A o Q K^T, the right-hand side and eq. (8)).
+ *
+ *   log_alpha   [N, T, H, dk] fp32 (chunk forward) or [B, H, dk] fp32 (decode step): natural log of alpha_t per channel
+ * Every other argument, the conventions and the error codes are those of kla_chunk_fwd / kla_decode_step.  The
+ * workspace (kla_chunk_fwd_diag_workspace_bytes) also holds three [N, T, H, dk] arrays in dt: the keys and queries
+ * with the chunk-local decay folded in, which the scan stage consumes.
+ */
+size_t kla_chunk_fwd_diag_workspace_bytes(int N, int T, int H, int dk, int dv, int chunk, kla_dtype dt,
+                                          const int32_t *cu_seqlens_host, int n_seq);
+int kla_chunk_fwd_diag(const void *q, const void *k, const void *v,
+                       const float *log_alpha, const float *eta, float eps,
+                       const float *h0, void *o, float *hT,
+                       const int32_t *cu_seqlens_dev, const int32_t *cu_seqlens_host, int n_seq,
+                       int N, int T, int H, int dk, int dv, int chunk, kla_dtype dt,
+                       void *workspace, size_t workspace_bytes, void *hip_stream);
+int kla_decode_step_diag(const void *q, const void *k, const void *v,
+                         const float *log_alpha, const float *eta, float eps,
+                         float *S, void *o,
+                         int B, int H, int dk, int dv, kla_dtype dt, void *hip_stream);
+
+/*
  * The Kaczmarz coefficient alone (eq. (3)): beta[i] = eta[i] / (||k_i||^2 + eps), 0 when the
  * denominator is 0, for n_token_heads rows of dk elements.
  *   k [n_token_heads, dk] dt in;  eta [n_token_heads] fp32 in;  beta [n_token_heads] fp32 out.

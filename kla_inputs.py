@@ -96,3 +96,11 @@ def grad_inputs(d, seed=0, d_hT=True):
     n_states = d["N"] if d["cu_seqlens"] is None else d["cu_seqlens"].numel() - 1
     g = torch.randn((n_states, d["H"], d["dk"], d["dv"]), generator=gen, dtype=torch.float32) if d_hT else None
     return d_o, g
+
+
+def diag_gates(d, seed=0, scale=1.0):
+    """Per-channel decay gates for diagonal gating: log_alpha [.., dk] = -softplus(x) * scale, x ~ N(0,1), shaped like
+    d["k"] (chunk inputs) in fp32."""
+    gen = torch.Generator().manual_seed(20_000 + seed)
+    x = torch.randn(tuple(d["k"].shape), generator=gen, dtype=torch.float32)
+    return -torch.nn.functional.softplus(x) * scale

@@ -29,6 +29,11 @@ _SIGNATURES = {
                       + [ctypes.c_int] * 6 + [ctypes.c_int, _vp, ctypes.c_size_t, _vp]),
     "kla_chunk_fwd_opts": (ctypes.c_int, [_vp, _vp, _vp, _fp, _fp, ctypes.c_float, _fp, _vp, _fp, _ip, _ip, ctypes.c_int]
                            + [ctypes.c_int] * 6 + [ctypes.c_int, _vp, ctypes.c_size_t, _vp, ctypes.c_uint]),
+    "kla_chunk_fwd_diag_workspace_bytes": (ctypes.c_size_t, [ctypes.c_int] * 6 + [ctypes.c_int, _ip, ctypes.c_int]),
+    "kla_chunk_fwd_diag": (ctypes.c_int, [_vp, _vp, _vp, _fp, _fp, ctypes.c_float, _fp, _vp, _fp, _ip, _ip, ctypes.c_int]
+                           + [ctypes.c_int] * 6 + [ctypes.c_int, _vp, ctypes.c_size_t, _vp]),
+    "kla_decode_step_diag": (ctypes.c_int, [_vp, _vp, _vp, _fp, _fp, ctypes.c_float, _fp, _vp]
+                             + [ctypes.c_int] * 4 + [ctypes.c_int, _vp]),
     "kla_chunk_bwd_workspace_bytes": (ctypes.c_size_t, [ctypes.c_int] * 6 + [ctypes.c_int, _ip, ctypes.c_int]),
     "kla_chunk_bwd": (ctypes.c_int, [_vp, _vp, _vp, _fp, _fp, ctypes.c_float, _fp, _vp, _fp, _vp, _vp, _vp, _fp, _fp, _fp,
                                      _ip, _ip, ctypes.c_int] + [ctypes.c_int] * 6 + [ctypes.c_int, _vp, ctypes.c_size_t, _vp]),
@@ -144,6 +149,49 @@ def kla_chunk_fwd(q, k, v, log_alpha, eta, eps, h0=None, cu_seqlens=None, want_h
     if rc != 0:
         raise KlaError(rc, "kla_chunk_fwd")
     return out, hT
+
+
+def kla_chunk_fwd_diag(q, k, v, log_alpha, eta, eps, h0=None, cu_seqlens=None, want_hT=True, workspace=None,
+                       out=None, hT=None, chunk=64):
+    """Chunkwise forward with diagonal gating: log_alpha is [N,T,H,dk] fp32 (one decay per key channel).
+    Everything else as kla_chunk_fwd; returns (o, hT)."""
+    _dev(q, k, v, log_alpha, eta, h0, cu_seqlens, workspace, out, hT)
+    N, T, H, dk = q.shape
+    dv = v.shape[-1]
+    if tuple(log_alpha.shape) != (N, T, H, dk):
+        raise ValueError("log_alpha must be [N, T, H, dk] for diagonal gating")
+    dt = _dt(q)
+    cu_host, cu_hp, n_seq = _host_cu(cu_seqlens)
+    n_states = n_seq if n_seq > 0 else N
+    need = int(lib().kla_chunk_fwd_diag_workspace_bytes(N, T, H, dk, dv, chunk, dt, cu_hp, n_seq))
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+    if out is None:
+        out = torch.empty((N, T, H, dv), dtype=q.dtype, device=q.device)
+    if hT is None and want_hT:
+        hT = torch.empty((n_states, H, dk, dv), dtype=torch.float32, device=q.device)
+    rc = lib().kla_chunk_fwd_diag(_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(eta), float(eps), _ptr(h0), _ptr(out),
+                                  _ptr(hT), _ptr(cu_seqlens), cu_hp, n_seq, N, T, H, dk, dv, chunk, dt,
+                                  _ptr(workspace), workspace.numel() * workspace.element_size(), _stream())
+    if rc != 0:
+        raise KlaError(rc, "kla_chunk_fwd_diag")
+    return out, hT
+
+
+def kla_decode_step_diag(q, k, v, log_alpha, eta, eps, S, out=None):
+    """One decode step with diagonal gating: log_alpha is [B,H,dk]; S [B,H,dk,dv] fp32 is updated in place."""
+    _dev(q, k, v, log_alpha, eta, S, out)
+    B, H, dk = q.shape
+    dv = v.shape[-1]
+    if tuple(log_alpha.shape) != (B, H, dk):
+        raise ValueError("log_alpha must be [B, H, dk] for diagonal gating")
+    if out is None:
+        out = torch.empty((B, H, dv), dtype=q.dtype, device=q.device)
+    rc = lib().kla_decode_step_diag(_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(eta), float(eps), _ptr(S), _ptr(out),
+                                    B, H, dk, dv, _dt(q), _stream())
+    if rc != 0:
+        raise KlaError(rc, "kla_decode_step_diag")
+    return out
 
 
 def kla_chunk_bwd_workspace_bytes(N, T, H, dk, dv, dtype, cu_seqlens=None, chunk=64) -> int:

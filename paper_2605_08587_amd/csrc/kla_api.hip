@@ -150,7 +150,7 @@ int chunk_fwd_impl(const void* q, const void* k, const void* v, const float* log
     sa.cu_seqlens = ia.cu_seqlens; sa.chunk_off = chunk_off; sa.n_seq = n_seq;
     sa.N = N; sa.T = T; sa.NT = NT; sa.H = H; sa.dv = dv;
     sa.wsT = wsT; sa.wsP = wsP; sa.wsG = wsG; sa.opts = opts;
-    sa.seg_G = 0; sa.seg_Lc = 0;
+    sa.seg_G = 0; sa.seg_Lc = 0; sa.kt_src = nullptr; sa.gc_vec = nullptr;
     if constexpr (sizeof(E) == 2) {
         if (pl.seg_G > 1) {
             // segment-parallel scan: maps of all segments but the last, their prefix composition, then every
@@ -255,6 +255,55 @@ int chunk_bwd_impl(const void* q, const void* k, const void* v, const float* log
     if (kla::launch_bwd_scan<E>(ba, dk, waves, st) != hipSuccess) return KLA_ERR_HIP;
     if (kla::launch_bwd_assemble<E>(ba, dk, pl.base.n_chunks, st) != hipSuccess) return KLA_ERR_HIP;
     return KLA_OK;
+}
+
+// ---- diagonal gating ----------------------------------------------------------------------------------
+struct DiagPlan {
+    Plan base;
+    size_t off_kp, off_qp, off_kt, off_gc, total;
+};
+
+int make_diag_plan(int N, int T, int H, int dk, int dv, int chunk, int dt, const int32_t* cu_host, int n_seq, DiagPlan* p)
+{
+    const int rc = make_plan(N, T, H, dk, dv, chunk, dt, cu_host, n_seq, &p->base);
+    if (rc != KLA_OK) return rc;
+    const size_t rows = (size_t)N * T * H * dk * elem_bytes(dt);
+    p->off_kp = round256(p->base.off_M);             // the forward plan up to its chunk offsets; no segment maps here
+    p->off_qp = round256(p->off_kp + rows);
+    p->off_kt = round256(p->off_qp + rows);
+    p->off_gc = round256(p->off_kt + rows);
+    p->total = round256(p->off_gc + (size_t)p->base.n_chunks * H * dk * sizeof(float));
+    return KLA_OK;
+}
+
+template <typename E>
+int chunk_fwd_diag_impl(const void* q, const void* k, const void* v, const float* log_alpha, const float* eta, float eps,
+                        const float* h0, void* o, float* hT, const int32_t* cu_dev, int n_seq, int N, int T, int H,
+                        int dk, int dv, const DiagPlan& pl, char* ws, hipStream_t st)
+{
+    int* chunk_off = reinterpret_cast<int*>(ws + pl.base.off_C);
+    const int NT = (T + 63) / 64;
+    if (n_seq > 0 && kla::launch_chunk_offsets(cu_dev, n_seq, chunk_off, st) != hipSuccess) return KLA_ERR_HIP;
+    kla::IntraDiagArgs<E> ia;
+    ia.q = static_cast<const E*>(q); ia.k = static_cast<const E*>(k);
+    ia.log_alpha = log_alpha; ia.eta = eta; ia.eps = eps;
+    ia.cu_seqlens = n_seq > 0 ? cu_dev : nullptr; ia.chunk_off = chunk_off; ia.n_seq = n_seq;
+    ia.T = T; ia.NT = NT; ia.H = H;
+    ia.wsT = reinterpret_cast<E*>(ws + pl.base.off_T); ia.wsG = reinterpret_cast<float*>(ws + pl.base.off_G);
+    ia.kplus = reinterpret_cast<E*>(ws + pl.off_kp); ia.qplus = reinterpret_cast<E*>(ws + pl.off_qp);
+    ia.ktilde = reinterpret_cast<E*>(ws + pl.off_kt); ia.gc = reinterpret_cast<float*>(ws + pl.off_gc);
+    if (kla::launch_intra_diag<E>(ia, dk, (int)pl.base.n_chunks, st) != hipSuccess) return KLA_ERR_HIP;
+
+    kla::ScanArgs<E> sa;
+    sa.q = ia.qplus; sa.k = ia.kplus; sa.v = static_cast<const E*>(v);
+    sa.h0 = h0; sa.o = static_cast<E*>(o); sa.hT = hT;
+    sa.cu_seqlens = ia.cu_seqlens; sa.chunk_off = chunk_off; sa.n_seq = n_seq;
+    sa.N = N; sa.T = T; sa.NT = NT; sa.H = H; sa.dv = dv;
+    sa.wsT = ia.wsT; sa.wsP = reinterpret_cast<E*>(ws + pl.base.off_P); sa.wsG = ia.wsG; sa.opts = 0u;
+    sa.seg_G = 0; sa.seg_Lc = 0; sa.kt_src = ia.ktilde; sa.gc_vec = ia.gc;
+    const long chains8 = ((long)pl.base.n_states * H + 7) / 8 * 8;
+    const int waves = (chains8 * (dv / 32) >= 192) ? 2 : 1;
+    return kla::launch_scan_diag<E>(sa, dk, waves, st) == hipSuccess ? KLA_OK : KLA_ERR_HIP;
 }
 
 }  // namespace
@@ -370,6 +419,67 @@ int kla_chunk_bwd(const void* q, const void* k, const void* v, const float* log_
                                       cu_seqlens_dev, n_seq, N, T, H, dk, dv, pl, ws, st);
     return chunk_bwd_impl<float>(q, k, v, log_alpha, eta, eps, h0, d_o, d_hT, dq, dk_, dv_, dlog_alpha, deta, dh0,
                                  cu_seqlens_dev, n_seq, N, T, H, dk, dv, pl, ws, st);
+}
+
+size_t kla_chunk_fwd_diag_workspace_bytes(int N, int T, int H, int dk, int dv, int chunk, kla_dtype dt,
+                                          const int32_t* cu_seqlens_host, int n_seq)
+{
+    DiagPlan pl;
+    if (make_diag_plan(N, T, H, dk, dv, chunk, (int)dt, cu_seqlens_host, n_seq, &pl) != KLA_OK) return 0;
+    return pl.total;
+}
+
+int kla_chunk_fwd_diag(const void* q, const void* k, const void* v, const float* log_alpha, const float* eta, float eps,
+                       const float* h0, void* o, float* hT, const int32_t* cu_seqlens_dev,
+                       const int32_t* cu_seqlens_host, int n_seq, int N, int T, int H, int dk, int dv, int chunk,
+                       kla_dtype dt, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    DiagPlan pl;
+    const int rc = make_diag_plan(N, T, H, dk, dv, chunk, (int)dt, cu_seqlens_host, n_seq, &pl);
+    if (rc != KLA_OK) return rc;
+    if (!(eps >= 0.0f) || isinf(eps)) return KLA_ERR_SHAPE;
+    if (n_seq > 0 && !cu_seqlens_dev) return KLA_ERR_NULL;
+    if (n_seq == 0 && cu_seqlens_dev) return KLA_ERR_SHAPE;
+    const bool any_tokens = (long)N * T > 0;
+    if (any_tokens && (!q || !k || !v || !log_alpha || !eta || !o)) return KLA_ERR_NULL;
+    if (!workspace) return KLA_ERR_WORKSPACE;
+    if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0 || workspace_bytes < pl.total) return KLA_ERR_WORKSPACE;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(h0) || !aligned16(hT) ||
+        (reinterpret_cast<uintptr_t>(log_alpha) & 3u) || (reinterpret_cast<uintptr_t>(eta) & 3u))
+        return KLA_ERR_ALIGN;
+    if (pl.base.n_states == 0) return KLA_OK;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    char* ws = static_cast<char*>(workspace);
+    if (dt == KLA_BF16)
+        return chunk_fwd_diag_impl<bf16_t>(q, k, v, log_alpha, eta, eps, h0, o, hT, cu_seqlens_dev, n_seq, N, T, H, dk, dv,
+                                           pl, ws, st);
+    return chunk_fwd_diag_impl<float>(q, k, v, log_alpha, eta, eps, h0, o, hT, cu_seqlens_dev, n_seq, N, T, H, dk, dv, pl,
+                                      ws, st);
+}
+
+int kla_decode_step_diag(const void* q, const void* k, const void* v, const float* log_alpha, const float* eta,
+                         float eps, float* S, void* o, int B, int H, int dk, int dv, kla_dtype dt, void* hip_stream)
+{
+    if (!dt_ok((int)dt)) return KLA_ERR_DTYPE;
+    if (B < 0 || H <= 0 || !dk_ok(dk) || !dv_ok(dv) || (long)B * H > 0x7fffffffL) return KLA_ERR_SHAPE;
+    if (!(eps >= 0.0f) || isinf(eps)) return KLA_ERR_SHAPE;
+    if (B == 0) return KLA_OK;
+    if (!q || !k || !v || !log_alpha || !eta || !S || !o) return KLA_ERR_NULL;
+    if (!aligned16(S) || (reinterpret_cast<uintptr_t>(q) & 3u) || (reinterpret_cast<uintptr_t>(k) & 3u) ||
+        (reinterpret_cast<uintptr_t>(v) & 3u) || (reinterpret_cast<uintptr_t>(o) & 3u) ||
+        (reinterpret_cast<uintptr_t>(log_alpha) & 3u))
+        return KLA_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    hipError_t e;
+    if (dt == KLA_BF16)
+        e = kla::launch_decode<bf16_t>(static_cast<const bf16_t*>(q), static_cast<const bf16_t*>(k),
+                                       static_cast<const bf16_t*>(v), log_alpha, eta, eps, S, static_cast<bf16_t*>(o),
+                                       B * H, dk, dv, 64, kla::kOptDiagDecay, st);
+    else
+        e = kla::launch_decode<float>(static_cast<const float*>(q), static_cast<const float*>(k),
+                                      static_cast<const float*>(v), log_alpha, eta, eps, S, static_cast<float*>(o),
+                                      B * H, dk, dv, 64, kla::kOptDiagDecay, st);
+    return e == hipSuccess ? KLA_OK : KLA_ERR_HIP;
 }
 
 int kla_debug_chunk_stage(const void* q, const void* k, const void* v, const float* log_alpha, const float* eta,

@@ -78,6 +78,78 @@ __device__ __forceinline__ void write_tri(char* out, const float* m, const float
     }
 }
 
+
+// Phases 3-6 of the intra-chunk stage, shared by its variants: from L (strictly lower triangular, fp32, in Lm) and
+// the fp32 image of P (in Pm) to the record at `rec`: T' = (I + L)^{-1} B and P (forward), or T', M^T and P^T
+// (backward).  Tm receives (I + L)^{-1}; the strictly-upper tiles of Lm, Pm, Tm must be zero on entry.  Called by all
+// 256 threads after a barrier; contains barriers.
+template <typename E, bool BWD>
+__device__ __forceinline__ void invert_and_store(const float* Lm, float* Tm, const float* Pm, const float* beta_s, char* rec,
+                                                 int tid)
+{
+    const int lane = tid & 63, wave = tid >> 6;
+    const int r = lane & 15, g = lane >> 4;
+    // ---- phase 3: diagonal 16x16 blocks of (I+L)^{-1} by forward substitution (wave w: block w);
+    //      meanwhile P goes out to the workspace in operand order ------------------------------
+    {
+        const int b0 = 16 * wave;
+        float x[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            float s = (i == r) ? 1.f : 0.f;
+#pragma unroll
+            for (int rr = 0; rr < i; ++rr) s -= Lm[(b0 + i) * kLdm + b0 + rr] * x[rr];
+            x[i] = s;
+        }
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+            if ((i >> 2) == g) Tm[(b0 + i) * kLdm + b0 + r] = x[i];
+    }
+    if constexpr (BWD) write_tri<E, true, false>(rec + 2 * ws_half_bytes<E>(), Pm, nullptr, tid);      // P^T
+    else               write_tri<E, false, false>(rec + ws_half_bytes<E>(), Pm, nullptr, tid);
+    __syncthreads();
+
+    // ---- phase 4: 32x32 level.  Waves 0,1: block pair (a, b) = (2m, 2m+1): T_ba = -D_b (L_ba D_a)
+    if (wave < 2) {
+        const int ra = 32 * wave, rb = ra + 16;
+        floatx4 y = {0.f, 0.f, 0.f, 0.f}, z = {0.f, 0.f, 0.f, 0.f};
+        mma16(y, aquad(Lm, rb, ra, r, g), bquad(Tm, ra, ra, r, g));
+        mma16(z, aquad(Tm, rb, rb, r, g), acc_as_quad(y));
+#pragma unroll
+        for (int e = 0; e < 4; ++e) Tm[(rb + 4 * g + e) * kLdm + ra + r] = -z[e];
+    }
+    __syncthreads();
+
+    // ---- phase 5: 64x64 level.  T[32:64, 0:32] = -T22 (L21 T11); wave = (row tile ti, col tile tj)
+    {
+        const int ti = wave >> 1, tj = wave & 1;
+        floatx4 y0 = {0.f, 0.f, 0.f, 0.f}, y1 = {0.f, 0.f, 0.f, 0.f}, z = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int tm = 0; tm < 2; ++tm) {
+            const float4 b = bquad(Tm, 16 * tm, 16 * tj, r, g);
+            mma16(y0, aquad(Lm, 32, 16 * tm, r, g), b);
+            mma16(y1, aquad(Lm, 48, 16 * tm, r, g), b);
+        }
+        mma16(z, aquad(Tm, 32 + 16 * ti, 32, r, g), acc_as_quad(y0));
+        mma16(z, aquad(Tm, 32 + 16 * ti, 48, r, g), acc_as_quad(y1));
+        // the block written below is read by no wave in this phase, so no barrier is needed here
+#pragma unroll
+        for (int e = 0; e < 4; ++e) Tm[(32 + 16 * ti + 4 * g + e) * kLdm + 16 * tj + r] = -z[e];
+    }
+    __syncthreads();
+
+    // ---- phase 6: T' = T diag(beta) (and T^T for the backward) -> workspace in operand order ------------------
+    {
+        char* out = rec;
+        if constexpr (BWD) {
+            write_tri<E, false, true>(out, Tm, beta_s, tid);
+            write_tri<E, true, false>(out + ws_half_bytes<E>(), Tm, nullptr, tid);
+        } else {
+            write_tri<E, false, true>(out, Tm, beta_s, tid);
+        }
+    }
+}
+
 }  // namespace
 
 // BWD = false: the forward's records [T' | P | three vectors].  BWD = true: the records of the backward pass,
@@ -243,66 +315,7 @@ __global__ __launch_bounds__(256) void intra_kernel(IntraArgs<E> a)
     }
     __syncthreads();
 
-    // ---- phase 3: diagonal 16x16 blocks of (I+L)^{-1} by forward substitution (wave w: block w);
-    //      meanwhile P goes out to the workspace in operand order ------------------------------
-    {
-        const int b0 = 16 * wave;
-        float x[16];
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            float s = (i == r) ? 1.f : 0.f;
-#pragma unroll
-            for (int rr = 0; rr < i; ++rr) s -= Lm[(b0 + i) * kLdm + b0 + rr] * x[rr];
-            x[i] = s;
-        }
-#pragma unroll
-        for (int i = 0; i < 16; ++i)
-            if ((i >> 2) == g) Tm[(b0 + i) * kLdm + b0 + r] = x[i];
-    }
-    if constexpr (BWD) write_tri<E, true, false>(reinterpret_cast<char*>(a.wsT) + (size_t)blockIdx.x * REC + 2 * ws_half_bytes<E>(),
-                                                  Pm, nullptr, tid);           // P^T
-    else               write_tri<E, false, false>(reinterpret_cast<char*>(a.wsP) + (size_t)blockIdx.x * REC, Pm, nullptr, tid);
-    __syncthreads();
-
-    // ---- phase 4: 32x32 level.  Waves 0,1: block pair (a, b) = (2m, 2m+1): T_ba = -D_b (L_ba D_a)
-    if (wave < 2) {
-        const int ra = 32 * wave, rb = ra + 16;
-        floatx4 y = {0.f, 0.f, 0.f, 0.f}, z = {0.f, 0.f, 0.f, 0.f};
-        mma16(y, aquad(Lm, rb, ra, r, g), bquad(Tm, ra, ra, r, g));
-        mma16(z, aquad(Tm, rb, rb, r, g), acc_as_quad(y));
-#pragma unroll
-        for (int e = 0; e < 4; ++e) Tm[(rb + 4 * g + e) * kLdm + ra + r] = -z[e];
-    }
-    __syncthreads();
-
-    // ---- phase 5: 64x64 level.  T[32:64, 0:32] = -T22 (L21 T11); wave = (row tile ti, col tile tj)
-    {
-        const int ti = wave >> 1, tj = wave & 1;
-        floatx4 y0 = {0.f, 0.f, 0.f, 0.f}, y1 = {0.f, 0.f, 0.f, 0.f}, z = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int tm = 0; tm < 2; ++tm) {
-            const float4 b = bquad(Tm, 16 * tm, 16 * tj, r, g);
-            mma16(y0, aquad(Lm, 32, 16 * tm, r, g), b);
-            mma16(y1, aquad(Lm, 48, 16 * tm, r, g), b);
-        }
-        mma16(z, aquad(Tm, 32 + 16 * ti, 32, r, g), acc_as_quad(y0));
-        mma16(z, aquad(Tm, 32 + 16 * ti, 48, r, g), acc_as_quad(y1));
-        // the block written below is read by no wave in this phase, so no barrier is needed here
-#pragma unroll
-        for (int e = 0; e < 4; ++e) Tm[(32 + 16 * ti + 4 * g + e) * kLdm + 16 * tj + r] = -z[e];
-    }
-    __syncthreads();
-
-    // ---- phase 6: T' = T diag(beta) (and T^T for the backward) -> workspace in operand order ------------------
-    {
-        char* out = reinterpret_cast<char*>(a.wsT) + (size_t)blockIdx.x * REC;
-        if constexpr (BWD) {
-            write_tri<E, false, true>(out, Tm, beta_s, tid);
-            write_tri<E, true, false>(out + ws_half_bytes<E>(), Tm, nullptr, tid);
-        } else {
-            write_tri<E, false, true>(out, Tm, beta_s, tid);
-        }
-    }
+    invert_and_store<E, BWD>(Lm, Tm, Pm, beta_s, reinterpret_cast<char*>(a.wsT) + (size_t)blockIdx.x * REC, tid);
 }
 
 template <typename E>
@@ -329,6 +342,177 @@ hipError_t launch_intra_bwd(const IntraArgs<E>& a, int dk, int n_chunks, hipStre
 }
 template hipError_t launch_intra_bwd<float>(const IntraArgs<float>&, int, int, hipStream_t);
 template hipError_t launch_intra_bwd<bf16_t>(const IntraArgs<bf16_t>&, int, int, hipStream_t);
+
+// ---- diagonal gating (App. B, "Extension to diagonal gating") -----------------------------------------------
+// log_alpha holds d_k values per token and head; gamma_i is a vector and every decay ratio acts inside the inner
+// products:  L_ij = beta_i sum_c k_ic k_jc gamma_ic/gamma_jc (j < i),  P_ij = sum_c q_ic k_jc gamma_ic/gamma_jc (j <= i).
+// The sums are taken directly in fp32 on the vector ALUs, each thread a 4x4 block of (i, j), with every ratio split
+// at two reference rows so that no factor can overflow: for i in row block bi (first row m) and j in row block
+// bj <= bi (last row e),  gamma_i/gamma_j = [gamma_i/gamma_m] [gamma_m/gamma_e] [gamma_e/gamma_j], the outer two
+// factors <= 1 and tabulated once per chunk together with k and q, the middle one a single exp per (block pair,
+// channel) that is <= 1 unless bj = bi, where it spans 3 tokens.  The triangular inverse and the records are those of
+// the scalar kernel, with unit decay vectors: the decay travels in the operands the scan is given instead,
+//     K+ = K o Gamma,  Q+ = Q o Gamma,  K~ = K o (gamma_C / Gamma)   (all factors <= 1)  and gamma_C per channel,
+// which this kernel writes next to the records.
+template <typename E, int DK>
+__global__ __launch_bounds__(256) void intra_diag_kernel(IntraDiagArgs<E> a)
+{
+    constexpr int LD = DK + 1;                       // odd row stride: the 16 row blocks a wave reads fall into different banks
+    constexpr int TB = 64 * LD * 4;
+    constexpr int EPP = 16 / (int)sizeof(E), PPR = DK / EPP;
+    constexpr int REC = ws_record_bytes<E>();
+    __shared__ __attribute__((aligned(16))) char area[3 * TB > 3 * 64 * kLdm * 4 ? 3 * TB : 3 * 64 * kLdm * 4];
+    __shared__ __attribute__((aligned(16))) float beta_s[64];
+    float* Kp = reinterpret_cast<float*>(area);               // k_i gamma_i/gamma_m(i), later overlaid by Lm
+    float* Qp = reinterpret_cast<float*>(area + TB);          // q_i gamma_i/gamma_m(i)
+    float* Gs = reinterpret_cast<float*>(area + 2 * TB);      // running sums of log2 alpha per channel
+    float* Lm = reinterpret_cast<float*>(area);
+    float* Pm = reinterpret_cast<float*>(area + 64 * kLdm * 4);
+    float* Tm = reinterpret_cast<float*>(area + 2 * 64 * kLdm * 4);
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int h = blockIdx.x % a.H;
+    const int cg = blockIdx.x / a.H;
+    long tok0; int clen;
+    if (a.cu_seqlens) {
+        int lo = 0, hi = a.n_seq - 1;
+        while (lo < hi) { const int mid = (lo + hi + 1) >> 1; if (a.chunk_off[mid] <= cg) lo = mid; else hi = mid - 1; }
+        const int c = cg - a.chunk_off[lo];
+        const int s0 = a.cu_seqlens[lo], s1 = a.cu_seqlens[lo + 1];
+        tok0 = (long)s0 + 64L * c;
+        clen = min(64, s1 - (int)tok0);
+    } else {
+        const int n = cg / a.NT, c = cg % a.NT;
+        tok0 = (long)n * a.T + 64L * c;
+        clen = min(64, a.T - 64 * c);
+    }
+    const size_t row_stride = (size_t)a.H * DK;
+
+    // ---- phase 1: K, Q (fp32) and log2 alpha -> LDS; key norms -> beta -------------------------------------
+    {
+        const E* kb = a.k + (size_t)tok0 * row_stride + (size_t)h * DK;
+        const E* qb = a.q + (size_t)tok0 * row_stride + (size_t)h * DK;
+        const float* lb = a.log_alpha + (size_t)tok0 * row_stride + (size_t)h * DK;
+#pragma unroll
+        for (int it = 0; it < 64 * PPR / 256; ++it) {
+            const int pi = tid + 256 * it;
+            const int row = pi / PPR, piece = pi % PPR;
+            float kf[EPP], qf[EPP];
+#pragma unroll
+            for (int i = 0; i < EPP; ++i) { kf[i] = 0.f; qf[i] = 0.f; }
+            if (row < clen) {
+                const E* kr = kb + (size_t)row * row_stride + piece * EPP;
+                const E* qr = qb + (size_t)row * row_stride + piece * EPP;
+#pragma unroll
+                for (int i = 0; i < EPP; ++i) { kf[i] = to_float(kr[i]); qf[i] = to_float(qr[i]); }
+            }
+            float ss = 0.f;
+#pragma unroll
+            for (int i = 0; i < EPP; ++i) {
+                Kp[row * LD + piece * EPP + i] = kf[i];
+                Qp[row * LD + piece * EPP + i] = qf[i];
+                ss += kf[i] * kf[i];
+            }
+#pragma unroll
+            for (int off = 1; off < PPR; off <<= 1) ss += __shfl_xor(ss, off, kWave);
+            if (piece == 0) {
+                const float et = row < clen ? a.eta[(size_t)(tok0 + row) * a.H + h] : 0.f;
+                beta_s[row] = kaczmarz_beta(et, ss, a.eps);
+            }
+        }
+        for (int x = tid; x < 64 * DK; x += 256) {
+            const int row = x / DK, c = x % DK;
+            Gs[row * LD + c] = row < clen ? lb[(size_t)row * row_stride + c] * 1.44269504088896341f : 0.f;
+        }
+    }
+    __syncthreads();
+    if (tid < DK) {                                  // per channel: running sum over the tokens of the chunk
+        float acc = 0.f;
+        for (int i = 0; i < 64; ++i) { acc += Gs[i * LD + tid]; Gs[i * LD + tid] = acc; }
+        a.gc[(size_t)blockIdx.x * DK + tid] = __builtin_amdgcn_exp2f(acc);            // gamma_C
+    }
+    if (tid < 128) {                                 // unit decay vectors for the scan: g = 0, 1/||q|| = 1
+        a.wsG[(size_t)blockIdx.x * 128 + tid] = tid < 64 ? 0.f : 1.f;
+        float* dec = reinterpret_cast<float*>(reinterpret_cast<char*>(a.wsT) + (size_t)blockIdx.x * REC + 2 * ws_half_bytes<E>());
+        dec[tid] = 1.f;
+        if (tid < 64) dec[128 + tid] = 1.f;
+    }
+    __syncthreads();
+
+    // ---- phase 1b: the scan's operands K+, Q+, K~ in the element type; then the tables of phase 2 in place ----
+    {
+        E* kpo = a.kplus + (size_t)tok0 * row_stride + (size_t)h * DK;
+        E* qpo = a.qplus + (size_t)tok0 * row_stride + (size_t)h * DK;
+        E* kto = a.ktilde + (size_t)tok0 * row_stride + (size_t)h * DK;
+        for (int x = tid; x < 64 * DK; x += 256) {
+            const int row = x / DK, c = x % DK;
+            const float gi = Gs[row * LD + c], gl = Gs[63 * LD + c];
+            const float kv = Kp[row * LD + c], qv = Qp[row * LD + c];
+            if (row < clen) {
+                const float up = __builtin_amdgcn_exp2f(gi);
+                kpo[(size_t)row * row_stride + c] = from_float<E>(kv * up);
+                qpo[(size_t)row * row_stride + c] = from_float<E>(qv * up);
+                kto[(size_t)row * row_stride + c] = from_float<E>(kv * __builtin_amdgcn_exp2f(gl - gi));
+            }
+        }
+    }
+    __syncthreads();
+
+    // ---- phase 2a: 4x4 blocks of K K^T and Q K^T with the decay ratios inside the sums -----------------------
+    float kk[4][4], qk[4][4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+#pragma unroll
+        for (int f = 0; f < 4; ++f) { kk[e][f] = 0.f; qk[e][f] = 0.f; }
+    const int bi = tid >> 4, bj = tid & 15;
+    if (bj <= bi) {
+        const float* gm = Gs + (4 * bi) * LD;        // first row of the row block of i
+        const float* ge = Gs + (4 * bj + 3) * LD;    // last row of the row block of j
+        for (int c = 0; c < DK; ++c) {
+            const float m = gm[c], en = ge[c];
+            const float mid = __builtin_amdgcn_exp2f(m - en);
+            float ki[4], qi[4], kj[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float up = __builtin_amdgcn_exp2f(Gs[(4 * bi + e) * LD + c] - m) * mid;      // gamma_i / gamma_e
+                ki[e] = Kp[(4 * bi + e) * LD + c] * up;
+                qi[e] = Qp[(4 * bi + e) * LD + c] * up;
+            }
+#pragma unroll
+            for (int f = 0; f < 4; ++f) kj[f] = Kp[(4 * bj + f) * LD + c] * __builtin_amdgcn_exp2f(en - Gs[(4 * bj + f) * LD + c]);
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+#pragma unroll
+                for (int f = 0; f < 4; ++f) { kk[e][f] += ki[e] * kj[f]; qk[e][f] += qi[e] * kj[f]; }
+        }
+    }
+    __syncthreads();   // the tables are dead from here on; Lm, Pm, Tm overlay them
+
+    // ---- phase 2b: mask, beta -> L and P; zero everything above the diagonal ----------------------------------
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+#pragma unroll
+        for (int f = 0; f < 4; ++f) {
+            const int i = 4 * bi + e, j = 4 * bj + f;
+            Lm[i * kLdm + j] = (j < i) ? beta_s[i] * kk[e][f] : 0.f;
+            Pm[i * kLdm + j] = (j <= i) ? qk[e][f] : 0.f;
+            Tm[i * kLdm + j] = 0.f;
+        }
+    __syncthreads();
+    invert_and_store<E, false>(Lm, Tm, Pm, beta_s, reinterpret_cast<char*>(a.wsT) + (size_t)blockIdx.x * REC, tid);
+}
+
+template <typename E>
+hipError_t launch_intra_diag(const IntraDiagArgs<E>& a, int dk, int n_chunks, hipStream_t st)
+{
+    if (n_chunks == 0) return hipSuccess;
+    const dim3 grid((unsigned)n_chunks * a.H), block(256);
+    if (dk == 64) hipLaunchKernelGGL((intra_diag_kernel<E, 64>), grid, block, 0, st, a);
+    else          hipLaunchKernelGGL((intra_diag_kernel<E, 128>), grid, block, 0, st, a);
+    return hipGetLastError();
+}
+template hipError_t launch_intra_diag<float>(const IntraDiagArgs<float>&, int, int, hipStream_t);
+template hipError_t launch_intra_diag<bf16_t>(const IntraDiagArgs<bf16_t>&, int, int, hipStream_t);
 
 // ---- chunk offsets of a packed batch: chunk_off[s] = sum_{s'<s} ceil(len_s'/64) --------------
 __global__ void chunk_offsets_kernel(const int* __restrict__ cu_seqlens, int n_seq, int* __restrict__ chunk_off)

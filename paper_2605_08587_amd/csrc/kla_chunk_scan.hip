@@ -49,7 +49,8 @@ struct ScanCfg {
     static constexpr int OSB = 64 * OLD * (int)sizeof(E);
     // one stage: K rows | Q rows | K transposed | T' | P | V slice | gamma_i | gamma_C/gamma_i | gamma_i/||q_i||
     static constexpr int OFF_Q = OPB, OFF_KT = 2 * OPB, OFF_T = 3 * OPB, OFF_P = OFF_T + TPB, OFF_V = OFF_P + TPB,
-                         OFF_EG = OFF_V + VB, OFF_ED = OFF_EG + 256, OFF_EQ = OFF_ED + 256, STAGE = OFF_EQ + 256;
+                         OFF_EG = OFF_V + VB, OFF_ED = OFF_EG + 256, OFF_EQ = OFF_ED + 256, OFF_GC = OFF_EQ + 256,
+                         STAGE = OFF_GC + 512;        // OFF_GC: gamma_C per channel (diagonal gating only)
     static constexpr int STAGES = sizeof(E) == 2 ? 2 : 1;      // fp32 operands take twice the LDS: single buffer
     static constexpr int LDS = STAGES * (STAGE + OSB);
     static constexpr int UK = (16 * PPR + NTH - 1) / NTH;       // (4-row group, piece) units of K/Q per thread
@@ -60,14 +61,18 @@ struct ScanCfg {
 };
 
 // The next chunk's operands on their way from global memory to LDS.
-template <typename E, int DK, int NW>
+template <typename E, int DK, int NW, bool DIAG>
 struct Prefetch {
     typedef ScanCfg<E, DK, NW> C;
     uint4 k[C::UK][4], q[C::UK][4], v[C::UV][4], t[C::UT], p[C::UT];
+    uint4 kt[DIAG ? C::UK : 1][4];                   // diagonal gating: rows of the K operand of the state update
+    float gc[(DK + C::NTH - 1) / C::NTH];           //                   gamma_C per channel
     float gv, gl, rq;
 };
 
-template <typename E, int DK, int NW>
+// DIAG: diagonal gating (App. B).  The decay then sits in the operands (a.k = K o Gamma, a.q = Q o Gamma, a.kt_src =
+// K o (gamma_C/Gamma), unit decay vectors in the records) and the state decays per row by a.gc_vec.
+template <typename E, int DK, int NW, bool DIAG>
 __global__ __launch_bounds__(64 * NW) void scan_kernel(ScanArgs<E> a)
 {
     typedef ScanCfg<E, DK, NW> C;
@@ -106,7 +111,7 @@ __global__ __launch_bounds__(64 * NW) void scan_kernel(ScanArgs<E> a)
     const size_t kq_stride = (size_t)a.H * DK, v_stride = (size_t)a.H * a.dv;
 
     // ---- global -> registers: everything chunk c needs -------------------------------------------
-    auto fetch = [&](int c, Prefetch<E, DK, NW>& pf) {
+    auto fetch = [&](int c, Prefetch<E, DK, NW, DIAG>& pf) {
         const long tok0 = t0 + 64L * c;
         const int clen = min(64, len - 64 * c);
         const size_t ch = (size_t)(ch0 + c) * a.H + h;
@@ -125,7 +130,18 @@ __global__ __launch_bounds__(64 * NW) void scan_kernel(ScanArgs<E> a)
                     pf.k[it][rr] = *reinterpret_cast<const uint4*>(kb + (size_t)row * kq_stride + piece * EPP);
                     pf.q[it][rr] = *reinterpret_cast<const uint4*>(qb + (size_t)row * kq_stride + piece * EPP);
                 }
+                if constexpr (DIAG) {
+                    pf.kt[it][rr] = make_uint4(0, 0, 0, 0);
+                    if (((16 * PPR) % NTH == 0 || u < 16 * PPR) && row < clen)
+                        pf.kt[it][rr] = *reinterpret_cast<const uint4*>(a.kt_src + (size_t)tok0 * kq_stride + (size_t)h * DK +
+                                                                        (size_t)row * kq_stride + piece * EPP);
+                }
             }
+        }
+        if constexpr (DIAG) {
+#pragma unroll
+            for (int x = 0; x < (DK + NTH - 1) / NTH; ++x)
+                pf.gc[x] = (tid + NTH * x < DK) ? a.gc_vec[ch * DK + tid + NTH * x] : 0.f;
         }
 #pragma unroll
         for (int it = 0; it < C::UV; ++it) {
@@ -153,7 +169,7 @@ __global__ __launch_bounds__(64 * NW) void scan_kernel(ScanArgs<E> a)
     };
 
     // ---- registers -> LDS stage, in MFMA operand order ----------------------------------------
-    auto stash = [&](const Prefetch<E, DK, NW>& pf, char* st) {
+    auto stash = [&](const Prefetch<E, DK, NW, DIAG>& pf, char* st) {
         E* Krq = reinterpret_cast<E*>(st);
         E* Qrq = reinterpret_cast<E*>(st + C::OFF_Q);
         E* Ktq = reinterpret_cast<E*>(st + C::OFF_KT);
@@ -168,7 +184,8 @@ __global__ __launch_bounds__(64 * NW) void scan_kernel(ScanArgs<E> a)
                     store_rq_piece(Krq, KP, 4 * tq + rr, piece, pf.k[it][rr]);
                     store_rq_piece(Qrq, KP, 4 * tq + rr, piece, pf.q[it][rr]);
                 }
-                store_tq_rows(Ktq, 2, tq, piece, pf.k[it], 0);
+                if constexpr (DIAG) store_tq_rows(Ktq, 2, tq, piece, pf.kt[it], 0);
+                else                store_tq_rows(Ktq, 2, tq, piece, pf.k[it], 0);
             }
         }
 #pragma unroll
@@ -188,6 +205,11 @@ __global__ __launch_bounds__(64 * NW) void scan_kernel(ScanArgs<E> a)
             reinterpret_cast<float*>(st + C::OFF_EG)[tid] = expf(pf.gv);            // gamma_i
             reinterpret_cast<float*>(st + C::OFF_ED)[tid] = expf(pf.gl - pf.gv);    // gamma_C / gamma_i
             reinterpret_cast<float*>(st + C::OFF_EQ)[tid] = expf(pf.gv) * pf.rq;    // scale of the Q S term
+        }
+        if constexpr (DIAG) {
+#pragma unroll
+            for (int x = 0; x < (DK + NTH - 1) / NTH; ++x)
+                if (tid + NTH * x < DK) reinterpret_cast<float*>(st + C::OFF_GC)[tid + NTH * x] = pf.gc[x];
         }
     };
 
@@ -245,7 +267,8 @@ __global__ __launch_bounds__(64 * NW) void scan_kernel(ScanArgs<E> a)
         const float gC = eg[63];
 #pragma unroll
         for (int kt = 0; kt < KB; ++kt) {
-            S[kt] = S[kt] * gC;
+            if constexpr (DIAG) S[kt] = S[kt] * ld_acc4(reinterpret_cast<const float*>(st + C::OFF_GC) + 16 * kt + 4 * g);
+            else                S[kt] = S[kt] * gC;
 #pragma unroll
             for (int jp = 0; jp < 2; ++jp) {
                 const Slot<E> sk = load_slot(Ktq, kt * 2 + jp, lane);
@@ -280,7 +303,7 @@ __global__ __launch_bounds__(64 * NW) void scan_kernel(ScanArgs<E> a)
         }
     };
 
-    Prefetch<E, DK, NW> pf;
+    Prefetch<E, DK, NW, DIAG> pf;
     if constexpr (C::STAGES == 2) {
         char* stage0 = lds;
         char* stage1 = lds + C::STAGE;
@@ -326,7 +349,7 @@ __global__ __launch_bounds__(64 * NW) void scan_kernel(ScanArgs<E> a)
     }
 }
 
-template <typename E, int DK>
+template <typename E, int DK, bool DIAG>
 static hipError_t launch_scan_dk(const ScanArgs<E>& a, int waves, hipStream_t st)
 {
     const int n_states = a.n_seq > 0 ? a.n_seq : a.N;
@@ -335,10 +358,10 @@ static hipError_t launch_scan_dk(const ScanArgs<E>& a, int waves, hipStream_t st
     const int nsl = a.dv / (16 * waves);
     const dim3 grid((unsigned)(((n_chains + 7) / 8) * 8 * nsl));
     switch (waves) {
-        case 1: hipLaunchKernelGGL((scan_kernel<E, DK, 1>), grid, dim3(64), 0, st, a); break;
-        case 2: hipLaunchKernelGGL((scan_kernel<E, DK, 2>), grid, dim3(128), 0, st, a); break;
+        case 1: hipLaunchKernelGGL((scan_kernel<E, DK, 1, DIAG>), grid, dim3(64), 0, st, a); break;
+        case 2: hipLaunchKernelGGL((scan_kernel<E, DK, 2, DIAG>), grid, dim3(128), 0, st, a); break;
         default:
-            if constexpr (sizeof(E) == 2) { hipLaunchKernelGGL((scan_kernel<E, DK, 4>), grid, dim3(256), 0, st, a); break; }
+            if constexpr (sizeof(E) == 2 && !DIAG) { hipLaunchKernelGGL((scan_kernel<E, DK, 4, false>), grid, dim3(256), 0, st, a); break; }
             else return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -346,10 +369,20 @@ static hipError_t launch_scan_dk(const ScanArgs<E>& a, int waves, hipStream_t st
 
 template <typename E> hipError_t launch_scan(const ScanArgs<E>& a, int dk, int waves, hipStream_t st)
 {
-    if (dk == 64) return launch_scan_dk<E, 64>(a, waves, st);
-    return launch_scan_dk<E, 128>(a, waves, st);
+    if (dk == 64) return launch_scan_dk<E, 64, false>(a, waves, st);
+    return launch_scan_dk<E, 128, false>(a, waves, st);
 }
 template hipError_t launch_scan<float>(const ScanArgs<float>&, int, int, hipStream_t);
 template hipError_t launch_scan<bf16_t>(const ScanArgs<bf16_t>&, int, int, hipStream_t);
+
+// diagonal gating: waves = 1 or 2
+template <typename E> hipError_t launch_scan_diag(const ScanArgs<E>& a, int dk, int waves, hipStream_t st)
+{
+    if (waves != 1 && waves != 2) return hipErrorInvalidValue;
+    if (dk == 64) return launch_scan_dk<E, 64, true>(a, waves, st);
+    return launch_scan_dk<E, 128, true>(a, waves, st);
+}
+template hipError_t launch_scan_diag<float>(const ScanArgs<float>&, int, int, hipStream_t);
+template hipError_t launch_scan_diag<bf16_t>(const ScanArgs<bf16_t>&, int, int, hipStream_t);
 
 }  // namespace kla

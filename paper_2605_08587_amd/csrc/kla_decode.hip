@@ -14,7 +14,9 @@ namespace kla {
 
 // One block = one (batch, head) and a slice of DVS state columns.
 //   LPR lanes cover one row of the slice (4 columns each); the 256 threads cover RPP rows per pass.
-template <typename T, int DK, int DVS, int NT>
+// DIAG: diagonal gating (App. B): log_alpha holds d_k values per (batch, head) and row i of the state decays by
+// exp(log_alpha[i]); the decay is folded into the copies of k and q that the two column sums use.
+template <typename T, int DK, int DVS, int NT, bool DIAG>
 __global__ __launch_bounds__(256) void decode_kernel(const T* __restrict__ q, const T* __restrict__ k,
                                                      const T* __restrict__ v,
                                                      const float* __restrict__ log_alpha,
@@ -40,7 +42,10 @@ __global__ __launch_bounds__(256) void decode_kernel(const T* __restrict__ q, co
         kv = to_float(k[(size_t)bh * DK + tid]);
         qv = to_float(q[(size_t)bh * DK + tid]);
     }
-    const float la = log_alpha[bh], et = eta[bh];
+    float la;
+    if constexpr (DIAG) la = tid < DK ? log_alpha[(size_t)bh * DK + tid] : 0.f;
+    else                la = log_alpha[bh];
+    const float et = eta[bh];
     float vv[4];
     {
         const T* vb = v + (size_t)bh * dv + col;
@@ -59,12 +64,14 @@ __global__ __launch_bounds__(256) void decode_kernel(const T* __restrict__ q, co
     }
 
     __shared__ float ks[DK], qs[DK];
+    __shared__ float ka[DIAG ? DK : 1], qa[DIAG ? DK : 1], al[DIAG ? DK : 1];     // alpha_i k_i, alpha_i q_i, alpha_i
     __shared__ float red[4][3];
     __shared__ float part[4][LPR][8];
 
     if (tid < DK) {
         ks[tid] = kv;
         qs[tid] = qv;
+        if constexpr (DIAG) { const float ai = expf(la); al[tid] = ai; ka[tid] = ai * kv; qa[tid] = ai * qv; }
     }
     const float kk = wave_sum(kv * kv);
     const float kq = wave_sum(kv * qv);
@@ -74,7 +81,7 @@ __global__ __launch_bounds__(256) void decode_kernel(const T* __restrict__ q, co
     __syncthreads();
     const float knorm2 = red[0][0] + red[1][0] + red[2][0] + red[3][0];
     const float kdotq = red[0][1] + red[1][1] + red[2][1] + red[3][1];
-    const float alpha = expf(la);
+    const float alpha = DIAG ? 1.f : expf(la);       // diagonal gating: the decay sits in ka, qa and al instead
     const float beta = (opts & kOptGdnBeta) ? et : kaczmarz_beta(et, knorm2, eps);
     // read-out scale: 1, or 1/||q|| (0 for a zero query) for the normalised read-out of Sec. 3.3
     float oscale = 1.f;
@@ -86,7 +93,7 @@ __global__ __launch_bounds__(256) void decode_kernel(const T* __restrict__ q, co
     float pr[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};   // p[0..3], r[0..3] for this lane's 4 columns
 #pragma unroll
     for (int p = 0; p < NP; ++p) {
-        const float kr = ks[r0 + p * RPP], qr = qs[r0 + p * RPP];
+        const float kr = DIAG ? ka[r0 + p * RPP] : ks[r0 + p * RPP], qr = DIAG ? qa[r0 + p * RPP] : qs[r0 + p * RPP];
         pr[0] += s[p].x * kr; pr[1] += s[p].y * kr; pr[2] += s[p].z * kr; pr[3] += s[p].w * kr;
         pr[4] += s[p].x * qr; pr[5] += s[p].y * qr; pr[6] += s[p].z * qr; pr[7] += s[p].w * qr;
     }
@@ -109,11 +116,12 @@ __global__ __launch_bounds__(256) void decode_kernel(const T* __restrict__ q, co
 #pragma unroll
     for (int p = 0; p < NP; ++p) {
         const float bk = beta * ks[r0 + p * RPP];
+        const float ar = DIAG ? al[r0 + p * RPP] : alpha;
         float4 n;
-        n.x = alpha * s[p].x + bk * e[0];
-        n.y = alpha * s[p].y + bk * e[1];
-        n.z = alpha * s[p].z + bk * e[2];
-        n.w = alpha * s[p].w + bk * e[3];
+        n.x = ar * s[p].x + bk * e[0];
+        n.y = ar * s[p].y + bk * e[1];
+        n.z = ar * s[p].z + bk * e[2];
+        n.w = ar * s[p].w + bk * e[3];
         typedef float f4v __attribute__((ext_vector_type(4)));
         const f4v t = {n.x, n.y, n.z, n.w};
         f4v* dp = reinterpret_cast<f4v*>(Sb + (size_t)(r0 + p * RPP) * dv);
@@ -132,11 +140,15 @@ static hipError_t launch_decode_nt(const T* q, const T* k, const T* v, const flo
                                    float eps, float* S, T* o, int BH, int dv, int slice, unsigned opts, hipStream_t st)
 {
     dim3 grid(BH, dv / slice), block(256);
+    if (opts & kOptDiagDecay) {                      // diagonal gating: one slice shape, the options do not apply
+        hipLaunchKernelGGL((decode_kernel<T, DK, 64, NT, true>), dim3(BH, dv / 64), block, 0, st, q, k, v, la, eta, eps, S, o, dv, 0u);
+        return hipGetLastError();
+    }
     switch (slice) {
-        case 32:  hipLaunchKernelGGL((decode_kernel<T, DK, 32, NT>), grid, block, 0, st, q, k, v, la, eta, eps, S, o, dv, opts); break;
-        case 64:  hipLaunchKernelGGL((decode_kernel<T, DK, 64, NT>), grid, block, 0, st, q, k, v, la, eta, eps, S, o, dv, opts); break;
-        case 128: hipLaunchKernelGGL((decode_kernel<T, DK, 128, NT>), grid, block, 0, st, q, k, v, la, eta, eps, S, o, dv, opts); break;
-        default:  hipLaunchKernelGGL((decode_kernel<T, DK, 256, NT>), grid, block, 0, st, q, k, v, la, eta, eps, S, o, dv, opts); break;
+        case 32:  hipLaunchKernelGGL((decode_kernel<T, DK, 32, NT, false>), grid, block, 0, st, q, k, v, la, eta, eps, S, o, dv, opts); break;
+        case 64:  hipLaunchKernelGGL((decode_kernel<T, DK, 64, NT, false>), grid, block, 0, st, q, k, v, la, eta, eps, S, o, dv, opts); break;
+        case 128: hipLaunchKernelGGL((decode_kernel<T, DK, 128, NT, false>), grid, block, 0, st, q, k, v, la, eta, eps, S, o, dv, opts); break;
+        default:  hipLaunchKernelGGL((decode_kernel<T, DK, 256, NT, false>), grid, block, 0, st, q, k, v, la, eta, eps, S, o, dv, opts); break;
     }
     return hipGetLastError();
 }

@@ -9,6 +9,8 @@ namespace kla {
 
 // option bits (the values of KLA_OPT_* in include/kla.h)
 constexpr unsigned kOptNormalizeQ = 1u, kOptGdnBeta = 2u;
+// internal: diagonal gating (log_alpha holds d_k values per token and head); set by the *_diag entry points only
+constexpr unsigned kOptDiagDecay = 0x100u;
 
 // ---- decode step and stand-alone coefficient -----------------------------------------------
 template <typename T>
@@ -36,6 +38,20 @@ template <typename E> hipError_t launch_intra(const IntraArgs<E>& a, int dk, int
 // the records of the backward pass (see bwd_record_bytes in kla_mma.hpp) at a.wsT; a.wsP, a.wsG unused, a.opts = 0
 template <typename E> hipError_t launch_intra_bwd(const IntraArgs<E>& a, int dk, int n_chunks, hipStream_t st);
 
+// Diagonal gating (App. B): log_alpha is [tokens, H, dk].  Besides the records (with unit decay vectors) the stage
+// writes the operands the scan is then given in place of k and q - kplus = K o Gamma, qplus = Q o Gamma (rows of the
+// K S and Q S products), ktilde = K o (gamma_C / Gamma) (the state update) - and gc = gamma_C per channel,
+// [chunk-head][dk] fp32.
+template <typename E> struct IntraDiagArgs {
+    const E* q; const E* k;
+    const float* log_alpha; const float* eta; float eps;
+    const int* cu_seqlens; const int* chunk_off; int n_seq;
+    int T, NT, H;
+    E* wsT; float* wsG;
+    E* kplus; E* qplus; E* ktilde; float* gc;
+};
+template <typename E> hipError_t launch_intra_diag(const IntraDiagArgs<E>& a, int dk, int n_chunks, hipStream_t st);
+
 template <typename E> struct ScanArgs {
     const E* q; const E* k; const E* v;
     const float* h0; E* o; float* hT;
@@ -47,9 +63,13 @@ template <typename E> struct ScanArgs {
     // sequence s / seg_G, seg_Lc chunks long (the last one of a sequence takes what is left), and h0 / hT are
     // indexed by segment.
     int seg_G, seg_Lc;
+    // Diagonal gating (generic kernel only): the transposed K operand of the state update comes from kt_src instead of
+    // k, and the state decays per row by gc_vec[chunk-head][dk] instead of by gamma_C.  Both NULL otherwise.
+    const E* kt_src; const float* gc_vec;
 };
 // waves = 1, 2 or 4: each wave of a workgroup carries 16 state columns through the whole sequence
 template <typename E> hipError_t launch_scan(const ScanArgs<E>& a, int dk, int waves, hipStream_t st);
+template <typename E> hipError_t launch_scan_diag(const ScanArgs<E>& a, int dk, int waves, hipStream_t st);
 
 // bf16 specialisations (direct global->LDS copies, swizzled token-major staging, transposing LDS reads)
 hipError_t launch_intra_bf16(const IntraArgs<bf16_t>& a, int dk, int n_chunks, hipStream_t st);
