@@ -171,6 +171,21 @@ def main():
                     "times_forward": round(msb / ms_per_step, 2), "workspace_MB": round(wb.numel() / 1e6, 1)}
         del wb, grads, d_o, d_hT
 
+    # ------------------------------------------------------------------ diagonal gating on config 2's tensors (secondary)
+    diag = None
+    if not args.skip_extra:
+        lad = kla_inputs.diag_gates(d, 1).cuda()
+        wd = torch.empty(int(kla.lib().kla_chunk_fwd_diag_workspace_bytes(N, T, H, dk, dv, 64, kla.KLA_BF16, None, 0)),
+                         dtype=torch.uint8, device="cuda")
+        fnd = lambda: kla.kla_chunk_fwd_diag(dev["q"], dev["k"], dev["v"], lad, dev["eta"], d["eps"], workspace=wd, out=out, hT=hT)
+        for _ in range(3):
+            fnd()
+        msd = _events(torch, fnd, 10)
+        diag = {"workload": "config2 tensors with per-channel decay gates log_alpha [N,T,H,dk] (kla_chunk_fwd_diag)",
+                "ms_per_call": round(msd, 4), "tokens_per_s": round(tokens / (msd * 1e-3), 1),
+                "times_scalar_gate_forward": round(msd / ms_per_step, 2)}
+        del wd, lad
+
     # ------------------------------------------------------------------ decode, config 4
     decode = None
     if not args.skip_decode:
@@ -257,7 +272,7 @@ def main():
             "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
             "config": {"workload": "config2: N=8,H=8,T=4096,dk=dv=128,chunk=64,bf16 q/k/v,fp32 gates+state",
                        "global_batch": N, "seq_len": T, "heads": H},
-            "roofline": roofline, "mfma": mfma, "other_chunk_workloads": extra, "backward": backward, "decode": decode, "cpu_baseline": cpu, "parity": parity}
+            "roofline": roofline, "mfma": mfma, "other_chunk_workloads": extra, "backward": backward, "diagonal_gating": diag, "decode": decode, "cpu_baseline": cpu, "parity": parity}
     print(json.dumps(line), flush=True)
 
 

@@ -210,3 +210,37 @@ def test_chunk_bwd_validation_and_workspace():
         expect += 3 * r256(N * T * H * dv * eb)                # X, U, Y
         assert lib.kla_chunk_bwd_workspace_bytes(N, T, H, dk, dv, 64, dt, None, 0) == expect
     assert lib.kla_chunk_bwd_workspace_bytes(1, 64, 1, 100, 64, 64, kla.KLA_BF16, None, 0) == 0
+
+
+def test_diag_entry_points_validate():
+    lib = kla.lib()
+    names = ("q", "k", "v", "la", "eta", "eps", "h0", "o", "hT", "cu_dev", "cu_host", "n_seq", "N", "T", "H", "dk", "dv",
+             "chunk", "dt", "ws", "ws_bytes", "stream")
+    base = dict(q=0x1000, k=0x2000, v=0x3000, la=0x4000, eta=0x5000, eps=1e-6, h0=None, o=0x6000, hT=None, cu_dev=None,
+                cu_host=None, n_seq=0, N=1, T=64, H=1, dk=64, dv=64, chunk=64, dt=kla.KLA_BF16, ws=0x100000,
+                ws_bytes=1 << 30, stream=None)
+    call = lambda **o: lib.kla_chunk_fwd_diag(*[{**base, **o}[n] for n in names])
+    assert call(la=None) == E_NULL
+    assert call(dk=32) == E_SHAPE
+    assert call(dt=9) == E_DTYPE
+    assert call(v=0x3002) == E_ALIGN
+    assert call(ws_bytes=10) == E_WS
+    assert call(N=0) == OK
+    # workspace: the forward's records and vectors, then K+, Q+, K~ in the element type and gamma_C per channel
+    r256 = lambda x: (x + 255) // 256 * 256
+    N, T, H, dk, dv = 2, 130, 3, 128, 64
+    n_ch = N * 3 * H
+    expect = r256(n_ch * (2 * 6144 + 768))
+    expect = r256(expect + n_ch * 512)
+    expect = r256(expect + 4)
+    expect += 3 * r256(N * T * H * dk * 2) + r256(n_ch * dk * 4)
+    assert lib.kla_chunk_fwd_diag_workspace_bytes(N, T, H, dk, dv, 64, kla.KLA_BF16, None, 0) == expect
+    dec = lambda **o: lib.kla_decode_step_diag(*[{**dict(q=0x1000, k=0x2000, v=0x3000, la=0x4000, eta=0x5000, eps=1e-6,
+                                                        S=0x6000, o=0x7000, B=2, H=2, dk=128, dv=128, dt=kla.KLA_BF16,
+                                                        st=None), **o}[n]
+                                                 for n in ("q", "k", "v", "la", "eta", "eps", "S", "o", "B", "H", "dk", "dv",
+                                                           "dt", "st")])
+    assert dec(la=None) == E_NULL
+    assert dec(dv=100) == E_SHAPE
+    assert dec(S=0x6008) == E_ALIGN
+    assert dec(B=0) == OK
