@@ -303,6 +303,11 @@ int chunk_fwd_diag_impl(const void* q, const void* k, const void* v, const float
     sa.seg_G = 0; sa.seg_Lc = 0; sa.kt_src = ia.ktilde; sa.gc_vec = ia.gc;
     const long chains8 = ((long)pl.base.n_states * H + 7) / 8 * 8;
     const int waves = (chains8 * (dv / 32) >= 192) ? 2 : 1;
+    if constexpr (sizeof(E) == 2) {
+        const char* impl = getenv("KLA_SCAN_IMPL");   // "generic": the element-type-generic kernel (A/B testing)
+        if (!(impl && impl[0] == 'g'))
+            return kla::launch_scan_bf16_diag(sa, dk, waves, st) == hipSuccess ? KLA_OK : KLA_ERR_HIP;
+    }
     return kla::launch_scan_diag<E>(sa, dk, waves, st) == hipSuccess ? KLA_OK : KLA_ERR_HIP;
 }
 

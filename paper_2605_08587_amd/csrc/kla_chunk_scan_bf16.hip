@@ -36,7 +36,7 @@ namespace kla {
 
 namespace {
 
-template <int DK, int NW>
+template <int DK, int NW, bool DG = false>
 struct Cfg {
     static constexpr int NTH = 64 * NW;                  // compute threads (the workgroup has one more wave)
     static constexpr int KB = DK / 16, KP = DK / 32;
@@ -51,26 +51,30 @@ struct Cfg {
     static constexpr int NVB = 64 / RPV;                 // copy blocks of the V slice (= 2 NW)
     static constexpr int TPB = kTriPairs * 64 * 16;      // bytes of one T' or P area; [T' | P] is one 12 KiB record
     static constexpr int NTB = 2 * TPB / 1024;           // = 12
-    static constexpr int OFF_Q = 64 * RB, OFF_T = 2 * 64 * RB, OFF_P = OFF_T + TPB, OFF_V = OFF_T + 2 * TPB,
-                         OFF_EG = OFF_V + 64 * VRW, OFF_ED = OFF_EG + 256, OFF_EQ = OFF_ED + 256, STAGE = OFF_EQ + 256;
+    // DG (diagonal gating): a third [64 x d_k] tile, the K operand of the state update, and gamma_C per channel
+    static constexpr int OFF_Q = 64 * RB, OFF_K2 = 2 * 64 * RB, OFF_T = (DG ? 3 : 2) * 64 * RB, OFF_P = OFF_T + TPB,
+                         OFF_V = OFF_T + 2 * TPB, OFF_EG = OFF_V + 64 * VRW, OFF_ED = OFF_EG + 256, OFF_EQ = OFF_ED + 256,
+                         OFF_GC = OFF_EQ + 256, STAGE = OFF_GC + (DG ? 512 : 0);
     // row stride of the output staging tile: 24 (NW <= 2) or 40 (NW = 4) dwords, so that the 8-dword spans which
     // one wave writes into 8 consecutive rows fall into disjoint banks
     static constexpr int ORB = NW <= 2 ? 96 : 160;
     static constexpr int OSB = 64 * ORB;
     static constexpr int NST = (3 * STAGE + 2 * OSB <= 160 * 1024) ? 3 : 2;   // LDS ring depth
     static constexpr int LDS = NST * STAGE + 2 * OSB;
-    static constexpr int NDMA = 2 * NKB + NTB + NVB + 1;   // copy instructions per chunk (+1: decay factors)
-    static_assert(LDS <= 160 * 1024 && NDMA < 64, "LDS budget of a gfx950 CU; 6-bit vmcnt");
+    static constexpr int NDMA = (DG ? 3 : 2) * NKB + NTB + NVB + 1 + (DG ? 1 : 0);   // copy instructions per chunk (+1: decay factors)
+    static_assert(LDS <= 160 * 1024 && (NST != 3 || NDMA < 64), "LDS budget of a gfx950 CU; 6-bit vmcnt (counted waits only with three stages)");
 };
 
 }  // namespace
 
 // NQ: normalised read-out (Sec. 3.3): the output rows are scaled by 1/||q_i||, which stage 1 folded into P and
 // into the third vector of the record, gamma_i/||q_i||, read here in place of gamma_i for the Q S term.
-template <int DK, int NW, bool NQ>
+// DG: diagonal gating (App. B): a.k = K o Gamma and a.q = Q o Gamma feed K S and Q S, a.kt_src = K o (gamma_C/Gamma)
+// the state update, the records carry unit decay vectors and the state rows decay by a.gc_vec (see intra_diag_kernel).
+template <int DK, int NW, bool NQ, bool DG = false>
 __global__ __launch_bounds__(64 * NW + 64) void scan_bf16_kernel(ScanArgs<bf16_t> a)
 {
-    typedef Cfg<DK, NW> C;
+    typedef Cfg<DK, NW, DG> C;
     constexpr int NTH = C::NTH, KB = C::KB, KP = C::KP, SLW = C::SLW, RB = C::RB, PPR = C::PPR, RPB = C::RPB,
                   VRW = C::VRW, VPP = C::VPP, RPV = C::RPV, ORB = C::ORB, NST = C::NST;
 
@@ -115,6 +119,8 @@ __global__ __launch_bounds__(64 * NW + 64) void scan_bf16_kernel(ScanArgs<bf16_t
     const char* kbase = reinterpret_cast<const char*>(a.k) + (size_t)t0 * kq_row + (size_t)h * DK * 2;
     const char* qbase = reinterpret_cast<const char*>(a.q) + (size_t)t0 * kq_row + (size_t)h * DK * 2;
     const char* vbase = reinterpret_cast<const char*>(a.v) + (size_t)t0 * v_row + ((size_t)h * a.dv + slice * SLW) * 2;
+    const char* k2base = DG ? reinterpret_cast<const char*>(a.kt_src) + (size_t)t0 * kq_row + (size_t)h * DK * 2 : nullptr;
+    const char* gcbase = DG ? reinterpret_cast<const char*>(a.gc_vec) + ((size_t)ch0 * a.H + h) * DK * 4 : nullptr;
     constexpr int REC = ws_record_bytes<bf16_t>();
     const char* tpbase = reinterpret_cast<const char*>(a.wsT) + ((size_t)ch0 * a.H + h) * REC;
 
@@ -159,6 +165,7 @@ __global__ __launch_bounds__(64 * NW + 64) void scan_bf16_kernel(ScanArgs<bf16_t
                 const int lo = (RPB == 4 && (b & 1)) ? gk[1] : gk[0];
                 dma16(kc + o, lo, st + b * 1024);
                 dma16(qc + o, lo, st + C::OFF_Q + b * 1024);
+                if constexpr (DG) dma16(k2base + (size_t)(64 * c) * kq_row + o, lo, st + C::OFF_K2 + b * 1024);
             });
             static_for<C::NVB>([&](auto i) {
                 const int b = i;
@@ -171,6 +178,7 @@ __global__ __launch_bounds__(64 * NW + 64) void scan_bf16_kernel(ScanArgs<bf16_t
                 const int lo = min(row, clen - 1) * (int)kq_row + ((pcol ^ swz_bits(row)) * 16);
                 dma16(kc, lo, st + b * 1024);
                 dma16(qc, lo, st + C::OFF_Q + b * 1024);
+                if constexpr (DG) dma16(k2base + (size_t)(64 * c) * kq_row, lo, st + C::OFF_K2 + b * 1024);
             });
             static_for<C::NVB>([&](auto i) {
                 const int b = i;
@@ -183,6 +191,9 @@ __global__ __launch_bounds__(64 * NW + 64) void scan_bf16_kernel(ScanArgs<bf16_t
             dma16(tc + b * 1024, lane * 16, st + C::OFF_T + b * 1024);
         });
         if (lane < 48) dma16(tc + 2 * C::TPB, lane * 16, st + C::OFF_EG);   // gamma_i | gamma_C/gamma_i | gamma_i/||q_i||: 768 bytes
+        if constexpr (DG) {
+            if (lane < DK / 4) dma16(gcbase + (size_t)c * a.H * DK * 4, lane * 16, st + C::OFF_GC);   // gamma_C per channel
+        }
     };
 
     // ---- one chunk of the recurrence for this wave's 16 columns ------------------------------------
@@ -199,7 +210,7 @@ __global__ __launch_bounds__(64 * NW + 64) void scan_bf16_kernel(ScanArgs<bf16_t
         };
         auto ktslot = [&](int kt, int jp, u32x2& q0, u32x2& q1) {
             const int kp = kt >> 1, b = kt & 1;
-            const char* p = ((kp & 1) ? pT1 : pT0) + 32 * jp * RB + 128 * (kp >> 1) + 8 * b;
+            const char* p = ((kp & 1) ? pT1 : pT0) + (DG ? C::OFF_K2 : 0) + 32 * jp * RB + 128 * (kp >> 1) + 8 * b;
             q0 = lds_read_tr(p);
             q1 = lds_read_tr(p + 16 * RB);
         };
@@ -208,7 +219,13 @@ __global__ __launch_bounds__(64 * NW + 64) void scan_bf16_kernel(ScanArgs<bf16_t
         const float gC = *reinterpret_cast<const float*>(st + C::OFF_EG + 63 * 4);
         u32x2 Sq[KB];
 #pragma unroll
-        for (int kt = 0; kt < KB; ++kt) { Sq[kt] = to_quad(S[kt]); S[kt] = S[kt] * gC; }
+        for (int kt = 0; kt < KB; ++kt) {
+            Sq[kt] = to_quad(S[kt]);
+            // diagonal gating: row (feature) f of the state decays by gamma_C[f]; tile kt, element e is feature
+            // 32 (kt / 2) + 8 g + 4 (kt % 2) + e
+            if constexpr (DG) S[kt] = S[kt] * ld_f4(st + C::OFF_GC + (32 * (kt >> 1) + 8 * g + 4 * (kt & 1)) * 4);
+            else              S[kt] = S[kt] * gC;
+        }
 
         // Products are issued "independent first": consecutive MFMAs write different accumulators, so that a
         // dependent one (same accumulator) follows only several instructions later.
@@ -338,7 +355,7 @@ __global__ __launch_bounds__(64 * NW + 64) void scan_bf16_kernel(ScanArgs<bf16_t
 #pragma unroll
         for (int p = 0; p < NST - 1; ++p)
             if (p < nch) issue(p, lds + p * C::STAGE);
-        if (NST == 3 && nch > 1) wait_vmcnt<C::NDMA>(); else wait_vmcnt<0>();      // chunk 0 has landed
+        if (NST == 3 && nch > 1) wait_vmcnt<(NST == 3 ? C::NDMA : 0)>(); else wait_vmcnt<0>();      // chunk 0 has landed
         __syncthreads();
         int spre = NST - 1;                              // ring position of chunk c + NST - 1
         for (int c = 0; c < nch; ++c) {
@@ -347,7 +364,7 @@ __global__ __launch_bounds__(64 * NW + 64) void scan_bf16_kernel(ScanArgs<bf16_t
             if (ahead) issue(c + NST - 1, lds + spre * C::STAGE);
             // Copies retire in order and this wave issues nothing else: all but the NDMA just issued (when
             // NST = 3) have landed once the counter is down to NDMA, i.e. chunk c+1 is complete.
-            if (NST == 3 && ahead) wait_vmcnt<C::NDMA>(); else wait_vmcnt<0>();
+            if (NST == 3 && ahead) wait_vmcnt<(NST == 3 ? C::NDMA : 0)>(); else wait_vmcnt<0>();
             __syncthreads();
             spre = (spre + 1 == NST) ? 0 : spre + 1;
         }
@@ -410,6 +427,23 @@ hipError_t launch_scan_bf16(const ScanArgs<bf16_t>& a, int dk, int waves, hipStr
 {
     if (dk == 64) return launch_dk<64>(a, waves, st);
     return launch_dk<128>(a, waves, st);
+}
+
+// diagonal gating: waves = 1 or 2, fixed-length or packed batches, no options, no segments
+template <int DK>
+static hipError_t launch_diag_dk(const ScanArgs<bf16_t>& a, int waves, hipStream_t st)
+{
+    const int n_chains = (a.n_seq > 0 ? a.n_seq : a.N) * a.H;
+    if (n_chains == 0) return hipSuccess;
+    const dim3 grid((unsigned)(((n_chains + 7) / 8) * 8 * (a.dv / (16 * waves))));
+    if (waves == 1) hipLaunchKernelGGL((scan_bf16_kernel<DK, 1, false, true>), grid, dim3(128), 0, st, a);
+    else            hipLaunchKernelGGL((scan_bf16_kernel<DK, 2, false, true>), grid, dim3(192), 0, st, a);
+    return hipGetLastError();
+}
+hipError_t launch_scan_bf16_diag(const ScanArgs<bf16_t>& a, int dk, int waves, hipStream_t st)
+{
+    if ((waves != 1 && waves != 2) || a.seg_G > 0 || !a.kt_src || !a.gc_vec) return hipErrorInvalidValue;
+    return dk == 64 ? launch_diag_dk<64>(a, waves, st) : launch_diag_dk<128>(a, waves, st);
 }
 
 }  // namespace kla

@@ -74,6 +74,7 @@ template <typename E> hipError_t launch_scan_diag(const ScanArgs<E>& a, int dk, 
 // bf16 specialisations (direct global->LDS copies, swizzled token-major staging, transposing LDS reads)
 hipError_t launch_intra_bf16(const IntraArgs<bf16_t>& a, int dk, int n_chunks, hipStream_t st);
 hipError_t launch_scan_bf16(const ScanArgs<bf16_t>& a, int dk, int waves, hipStream_t st);
+hipError_t launch_scan_bf16_diag(const ScanArgs<bf16_t>& a, int dk, int waves, hipStream_t st);   // diagonal gating
 
 // Segment-parallel scan of long sequences in small batches (bf16): per-segment affine maps of the state, their
 // prefix composition, then the ordinary scan over all segments at once.  `maps` holds (G-1) x [N | M] per

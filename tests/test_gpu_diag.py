@@ -77,6 +77,12 @@ def test_diag_chunk_decay_range(kla, dt, scale):
     _check(kla, kla_inputs.chunk_inputs(1, 700, 2, 128, 128, dtype=dt, seed=430, h0_std=0.3), seed=3, scale=scale)
 
 
+def test_diag_generic_scan_on_bf16(kla, monkeypatch):
+    """KLA_SCAN_IMPL=generic: the element-type-generic scan kernel (the fp32 path's) on bf16 inputs."""
+    monkeypatch.setenv("KLA_SCAN_IMPL", "generic")
+    _check(kla, kla_inputs.chunk_inputs(2, 200, 2, 128, 128, dtype=torch.bfloat16, seed=435, h0_std=0.3), seed=4)
+
+
 def test_diag_equal_channels_repeat_the_scalar_path(kla):
     """All channels equal: the diagonal kernels must agree with the scalar-gate kernels (different code, same map)."""
     d = kla_inputs.chunk_inputs(2, 300, 2, 128, 128, dtype=torch.float32, seed=440, h0_std=0.3)
