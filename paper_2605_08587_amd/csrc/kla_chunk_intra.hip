@@ -346,11 +346,11 @@ template hipError_t launch_intra_bwd<bf16_t>(const IntraArgs<bf16_t>&, int, int,
 // ---- diagonal gating (App. B, "Extension to diagonal gating") -----------------------------------------------
 // log_alpha holds d_k values per token and head; gamma_i is a vector and every decay ratio acts inside the inner
 // products:  L_ij = beta_i sum_c k_ic k_jc gamma_ic/gamma_jc (j < i),  P_ij = sum_c q_ic k_jc gamma_ic/gamma_jc (j <= i).
-// The sums are taken directly in fp32 on the vector ALUs, each thread a 4x4 block of (i, j), with every ratio split
-// at two reference rows so that no factor can overflow: for i in row block bi (first row m) and j in row block
-// bj <= bi (last row e),  gamma_i/gamma_j = [gamma_i/gamma_m] [gamma_m/gamma_e] [gamma_e/gamma_j], the outer two
-// factors <= 1 and tabulated once per chunk together with k and q, the middle one a single exp per (block pair,
-// channel) that is <= 1 unless bj = bi, where it spans 3 tokens.  The triangular inverse and the records are those of
+// Every ratio is split at a reference row e with j <= e < i, gamma_i/gamma_j = [gamma_i/gamma_e][gamma_e/gamma_j], so
+// that both factors are <= 1 (gamma itself may underflow inside a chunk; nothing can overflow): the off-diagonal
+// 16x16 tiles and the lower-left 8x8 block of each diagonal tile become ordinary MFMA products of rescaled rows,
+// formed in registers from fp32 tables of K, Q and the running log sums; only the 8x8 blocks on the diagonal are
+// summed pair by pair on the vector ALUs (there gamma_i/gamma_j <= 1 directly).  The triangular inverse and the records are those of
 // the scalar kernel, with unit decay vectors: the decay travels in the operands the scan is given instead,
 //     K+ = K o Gamma,  Q+ = Q o Gamma,  K~ = K o (gamma_C / Gamma)   (all factors <= 1)  and gamma_C per channel,
 // which this kernel writes next to the records.
@@ -458,46 +458,100 @@ __global__ __launch_bounds__(256) void intra_diag_kernel(IntraDiagArgs<E> a)
     }
     __syncthreads();
 
-    // ---- phase 2a: 4x4 blocks of K K^T and Q K^T with the decay ratios inside the sums -----------------------
-    float kk[4][4], qk[4][4];
+    // ---- phase 2a: K K^T and Q K^T with the decay ratios inside the sums ---------------------------------------
+    // (1) MFMA jobs, operands formed in registers from the tables: the six off-diagonal 16x16 tiles (ti > tj), split at
+    //     e = last row of tile tj, A row i = k_i (or q_i) o gamma_i/gamma_e, B row j = k_j o gamma_e/gamma_j; and of
+    //     each diagonal tile the lower-left 8x8 block, split at e = row 7 of the tile, the other rows of both operands
+    //     zero.  Every factor is <= 1.  Jobs 0..9 go to wave (job % 4).
+    // (2) the 8x8 blocks on the diagonal, one (i, j) pair per thread over all channels: gamma_i/gamma_j <= 1 directly.
+    const int r = lane & 15, g = lane >> 4;
+    floatx4 tkk[3], tqk[3];
 #pragma unroll
-    for (int e = 0; e < 4; ++e)
+    for (int jb = 0; jb < 3; ++jb) { tkk[jb] = floatx4{0.f, 0.f, 0.f, 0.f}; tqk[jb] = tkk[jb]; }
 #pragma unroll
-        for (int f = 0; f < 4; ++f) { kk[e][f] = 0.f; qk[e][f] = 0.f; }
-    const int bi = tid >> 4, bj = tid & 15;
-    if (bj <= bi) {
-        const float* gm = Gs + (4 * bi) * LD;        // first row of the row block of i
-        const float* ge = Gs + (4 * bj + 3) * LD;    // last row of the row block of j
-        for (int c = 0; c < DK; ++c) {
-            const float m = gm[c], en = ge[c];
-            const float mid = __builtin_amdgcn_exp2f(m - en);
-            float ki[4], qi[4], kj[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const float up = __builtin_amdgcn_exp2f(Gs[(4 * bi + e) * LD + c] - m) * mid;      // gamma_i / gamma_e
-                ki[e] = Kp[(4 * bi + e) * LD + c] * up;
-                qi[e] = Qp[(4 * bi + e) * LD + c] * up;
-            }
-#pragma unroll
-            for (int f = 0; f < 4; ++f) kj[f] = Kp[(4 * bj + f) * LD + c] * __builtin_amdgcn_exp2f(en - Gs[(4 * bj + f) * LD + c]);
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-#pragma unroll
-                for (int f = 0; f < 4; ++f) { kk[e][f] += ki[e] * kj[f]; qk[e][f] += qi[e] * kj[f]; }
+    for (int jb = 0; jb < 3; ++jb) {
+        const int job = wave + 4 * jb;
+        if (job >= 10) break;
+        int ti, tj, e_row; bool a_ok, b_ok;
+        if (job < 6) {
+            ti = job < 1 ? 1 : (job < 3 ? 2 : 3);
+            tj = job < 1 ? 0 : (job < 3 ? job - 1 : job - 3);
+            e_row = 16 * tj + 15; a_ok = true; b_ok = true;
+        } else {
+            ti = tj = job - 6;
+            e_row = 16 * ti + 7; a_ok = r >= 8; b_ok = r < 8;
         }
+        const float* gi = Gs + (16 * ti + r) * LD;
+        const float* gj = Gs + (16 * tj + r) * LD;
+        const float* ge = Gs + e_row * LD;
+        const float* ki = Kp + (16 * ti + r) * LD;
+        const float* qi = Qp + (16 * ti + r) * LD;
+        const float* kj = Kp + (16 * tj + r) * LD;
+        for (int kp = 0; kp < DK / 32; ++kp) {
+            floatx4 ka[2], qa[2], kb[2];
+#pragma unroll
+            for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+                for (int x = 0; x < 4; ++x) {
+                    const int c = 32 * kp + 16 * blk + 4 * g + x;
+                    const float gev = ge[c];
+                    const float up = a_ok ? __builtin_amdgcn_exp2f(gi[c] - gev) : 0.f;      // gamma_i / gamma_e
+                    const float dn = b_ok ? __builtin_amdgcn_exp2f(gev - gj[c]) : 0.f;      // gamma_e / gamma_j
+                    ka[blk][x] = ki[c] * up; qa[blk][x] = qi[c] * up; kb[blk][x] = kj[c] * dn;
+                }
+            Slot<E> sk, sq;
+            sk.q0 = acc_to_quad<E>(ka[0]); sk.q1 = acc_to_quad<E>(ka[1]);
+            sq.q0 = acc_to_quad<E>(qa[0]); sq.q1 = acc_to_quad<E>(qa[1]);
+            const typename QuadT<E>::type b0 = acc_to_quad<E>(kb[0]), b1 = acc_to_quad<E>(kb[1]);
+            mma32<E>(tkk[jb], sk, b0, b1);
+            mma32<E>(tqk[jb], sq, b0, b1);
+        }
+    }
+    float pkk = 0.f, pqk = 0.f, pdg = 0.f;
+    int pi = 0, pj = 0;
+    if (tid < 224) {                                 // 8 blocks x 28 pairs with j < i
+        const int b8 = tid / 28, p = tid % 28;
+        int ii = 1;
+        while ((ii * (ii + 1)) / 2 <= p) ++ii;       // ii (ii - 1) / 2 <= p < ii (ii + 1) / 2
+        pi = 8 * b8 + ii; pj = 8 * b8 + p - (ii * (ii - 1)) / 2;
+        const float* gi = Gs + pi * LD; const float* gj = Gs + pj * LD;
+        const float* ki = Kp + pi * LD; const float* qi = Qp + pi * LD; const float* kj = Kp + pj * LD;
+        for (int c = 0; c < DK; ++c) {
+            const float w = kj[c] * __builtin_amdgcn_exp2f(gi[c] - gj[c]);
+            pkk += ki[c] * w; pqk += qi[c] * w;
+        }
+    }
+    if (tid < 64) {                                  // P_ii = q_i . k_i
+        const float* ki = Kp + tid * LD; const float* qi = Qp + tid * LD;
+        for (int c = 0; c < DK; ++c) pdg += qi[c] * ki[c];
     }
     __syncthreads();   // the tables are dead from here on; Lm, Pm, Tm overlay them
 
-    // ---- phase 2b: mask, beta -> L and P; zero everything above the diagonal ----------------------------------
+    // ---- phase 2b: beta -> L and P, everything else zero ---------------------------------------------------------
+    for (int x = tid; x < 64 * 64; x += 256) {
+        const int i = x >> 6, j = x & 63;
+        Lm[i * kLdm + j] = 0.f; Pm[i * kLdm + j] = 0.f; Tm[i * kLdm + j] = 0.f;
+    }
+    __syncthreads();
 #pragma unroll
-    for (int e = 0; e < 4; ++e)
+    for (int jb = 0; jb < 3; ++jb) {
+        const int job = wave + 4 * jb;
+        if (job >= 10) break;
+        int ti, tj;
+        if (job < 6) { ti = job < 1 ? 1 : (job < 3 ? 2 : 3); tj = job < 1 ? 0 : (job < 3 ? job - 1 : job - 3); }
+        else         { ti = tj = job - 6; }
 #pragma unroll
-        for (int f = 0; f < 4; ++f) {
-            const int i = 4 * bi + e, j = 4 * bj + f;
-            Lm[i * kLdm + j] = (j < i) ? beta_s[i] * kk[e][f] : 0.f;
-            Pm[i * kLdm + j] = (j <= i) ? qk[e][f] : 0.f;
-            Tm[i * kLdm + j] = 0.f;
+        for (int e = 0; e < 4; ++e) {
+            const int il = 4 * g + e;                // row inside the tile; column inside the tile is r
+            if (job < 6 || (il >= 8 && r < 8)) {
+                const int i = 16 * ti + il, j = 16 * tj + r;
+                Lm[i * kLdm + j] = beta_s[i] * tkk[jb][e];
+                Pm[i * kLdm + j] = tqk[jb][e];
+            }
         }
+    }
+    if (tid < 224) { Lm[pi * kLdm + pj] = beta_s[pi] * pkk; Pm[pi * kLdm + pj] = pqk; }
+    if (tid < 64) Pm[tid * kLdm + tid] = pdg;
     __syncthreads();
     invert_and_store<E, false>(Lm, Tm, Pm, beta_s, reinterpret_cast<char*>(a.wsT) + (size_t)blockIdx.x * REC, tid);
 }
