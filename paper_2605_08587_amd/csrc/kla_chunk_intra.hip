@@ -357,15 +357,18 @@ template hipError_t launch_intra_bwd<bf16_t>(const IntraArgs<bf16_t>&, int, int,
 template <typename E, int DK>
 __global__ __launch_bounds__(256) void intra_diag_kernel(IntraDiagArgs<E> a)
 {
-    constexpr int LD = DK + 1;                       // odd row stride: the 16 row blocks a wave reads fall into different banks
-    constexpr int TB = 64 * LD * 4;
     constexpr int EPP = 16 / (int)sizeof(E), PPR = DK / EPP;
+    constexpr int LE = DK + EPP;                     // row stride of the K, Q tables (elements): one 16-byte piece of padding
+    constexpr int LD = DK + 4;                       // row stride of the log-sum table (floats)
+    constexpr int TE = 64 * LE * (int)sizeof(E), TG = 64 * LD * 4;
+    constexpr int NSEG = 256 / DK, SROWS = 64 / NSEG;   // the running sums: 256 threads = d_k channels x NSEG row segments
     constexpr int REC = ws_record_bytes<E>();
-    __shared__ __attribute__((aligned(16))) char area[3 * TB > 3 * 64 * kLdm * 4 ? 3 * TB : 3 * 64 * kLdm * 4];
+    __shared__ __attribute__((aligned(16))) char area[2 * TE + TG > 3 * 64 * kLdm * 4 ? 2 * TE + TG : 3 * 64 * kLdm * 4];
     __shared__ __attribute__((aligned(16))) float beta_s[64];
-    float* Kp = reinterpret_cast<float*>(area);               // k_i gamma_i/gamma_m(i), later overlaid by Lm
-    float* Qp = reinterpret_cast<float*>(area + TB);          // q_i gamma_i/gamma_m(i)
-    float* Gs = reinterpret_cast<float*>(area + 2 * TB);      // running sums of log2 alpha per channel
+    __shared__ float segsum[NSEG][DK];
+    const E* Kp = reinterpret_cast<const E*>(area);           // K rows (element type), later overlaid by Lm, Pm, Tm
+    const E* Qp = reinterpret_cast<const E*>(area + TE);      // Q rows
+    float* Gs = reinterpret_cast<float*>(area + 2 * TE);      // running sums of log2 alpha per channel
     float* Lm = reinterpret_cast<float*>(area);
     float* Pm = reinterpret_cast<float*>(area + 64 * kLdm * 4);
     float* Tm = reinterpret_cast<float*>(area + 2 * 64 * kLdm * 4);
@@ -387,8 +390,23 @@ __global__ __launch_bounds__(256) void intra_diag_kernel(IntraDiagArgs<E> a)
         clen = min(64, a.T - 64 * c);
     }
     const size_t row_stride = (size_t)a.H * DK;
+    auto unpack = [](uint4 d, float (&f)[EPP]) {
+        if constexpr (sizeof(E) == 2) {
+            const uint32_t w[4] = {d.x, d.y, d.z, d.w};
+#pragma unroll
+            for (int m = 0; m < 4; ++m) { f[2 * m] = bf16_bits_to_float(w[m] & 0xffffu); f[2 * m + 1] = bf16_bits_to_float(w[m] >> 16); }
+        } else {
+            f[0] = __uint_as_float(d.x); f[1] = __uint_as_float(d.y); f[2] = __uint_as_float(d.z); f[3] = __uint_as_float(d.w);
+        }
+    };
+    auto pack = [](const float (&f)[EPP]) {
+        if constexpr (sizeof(E) == 2)
+            return make_uint4(pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]), pack_bf16x2(f[4], f[5]), pack_bf16x2(f[6], f[7]));
+        else
+            return make_uint4(__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]), __float_as_uint(f[3]));
+    };
 
-    // ---- phase 1: K, Q (fp32) and log2 alpha -> LDS; key norms -> beta -------------------------------------
+    // ---- phase 1: K, Q rows and log2 alpha -> LDS; key norms -> beta ---------------------------------------------
     {
         const E* kb = a.k + (size_t)tok0 * row_stride + (size_t)h * DK;
         const E* qb = a.q + (size_t)tok0 * row_stride + (size_t)h * DK;
@@ -397,22 +415,18 @@ __global__ __launch_bounds__(256) void intra_diag_kernel(IntraDiagArgs<E> a)
         for (int it = 0; it < 64 * PPR / 256; ++it) {
             const int pi = tid + 256 * it;
             const int row = pi / PPR, piece = pi % PPR;
-            float kf[EPP], qf[EPP];
-#pragma unroll
-            for (int i = 0; i < EPP; ++i) { kf[i] = 0.f; qf[i] = 0.f; }
+            uint4 kd = make_uint4(0, 0, 0, 0), qd = make_uint4(0, 0, 0, 0);
             if (row < clen) {
-                const E* kr = kb + (size_t)row * row_stride + piece * EPP;
-                const E* qr = qb + (size_t)row * row_stride + piece * EPP;
-#pragma unroll
-                for (int i = 0; i < EPP; ++i) { kf[i] = to_float(kr[i]); qf[i] = to_float(qr[i]); }
+                kd = *reinterpret_cast<const uint4*>(kb + (size_t)row * row_stride + piece * EPP);
+                qd = *reinterpret_cast<const uint4*>(qb + (size_t)row * row_stride + piece * EPP);
             }
+            *reinterpret_cast<uint4*>(area + (size_t)(row * LE + piece * EPP) * sizeof(E)) = kd;
+            *reinterpret_cast<uint4*>(area + TE + (size_t)(row * LE + piece * EPP) * sizeof(E)) = qd;
+            float kf[EPP];
+            unpack(kd, kf);
             float ss = 0.f;
 #pragma unroll
-            for (int i = 0; i < EPP; ++i) {
-                Kp[row * LD + piece * EPP + i] = kf[i];
-                Qp[row * LD + piece * EPP + i] = qf[i];
-                ss += kf[i] * kf[i];
-            }
+            for (int i = 0; i < EPP; ++i) ss += kf[i] * kf[i];
 #pragma unroll
             for (int off = 1; off < PPR; off <<= 1) ss += __shfl_xor(ss, off, kWave);
             if (piece == 0) {
@@ -420,16 +434,27 @@ __global__ __launch_bounds__(256) void intra_diag_kernel(IntraDiagArgs<E> a)
                 beta_s[row] = kaczmarz_beta(et, ss, a.eps);
             }
         }
-        for (int x = tid; x < 64 * DK; x += 256) {
-            const int row = x / DK, c = x % DK;
-            Gs[row * LD + c] = row < clen ? lb[(size_t)row * row_stride + c] * 1.44269504088896341f : 0.f;
+#pragma unroll
+        for (int it = 0; it < 64 * DK / 4 / 256; ++it) {
+            const int x = tid + 256 * it, row = x / (DK / 4), c4 = x % (DK / 4);
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (row < clen) v = *reinterpret_cast<const float4*>(lb + (size_t)row * row_stride + 4 * c4);
+            const float s2 = 1.44269504088896341f;
+            *reinterpret_cast<float4*>(Gs + row * LD + 4 * c4) = make_float4(v.x * s2, v.y * s2, v.z * s2, v.w * s2);
         }
     }
     __syncthreads();
-    if (tid < DK) {                                  // per channel: running sum over the tokens of the chunk
+    {   // per channel: running sum over the tokens of the chunk, NSEG row segments side by side, then their offsets
+        const int c = tid % DK, sg = tid / DK;
         float acc = 0.f;
-        for (int i = 0; i < 64; ++i) { acc += Gs[i * LD + tid]; Gs[i * LD + tid] = acc; }
-        a.gc[(size_t)blockIdx.x * DK + tid] = __builtin_amdgcn_exp2f(acc);            // gamma_C
+        for (int i = sg * SROWS; i < (sg + 1) * SROWS; ++i) { acc += Gs[i * LD + c]; Gs[i * LD + c] = acc; }
+        segsum[sg][c] = acc;
+        __syncthreads();
+        float base = 0.f;
+        for (int s2 = 0; s2 < sg; ++s2) base += segsum[s2][c];
+        if (sg > 0)
+            for (int i = sg * SROWS; i < (sg + 1) * SROWS; ++i) Gs[i * LD + c] += base;
+        if (sg == NSEG - 1) a.gc[(size_t)blockIdx.x * DK + c] = __builtin_amdgcn_exp2f(base + acc);      // gamma_C
     }
     if (tid < 128) {                                 // unit decay vectors for the scan: g = 0, 1/||q|| = 1
         a.wsG[(size_t)blockIdx.x * 128 + tid] = tid < 64 ? 0.f : 1.f;
@@ -439,24 +464,33 @@ __global__ __launch_bounds__(256) void intra_diag_kernel(IntraDiagArgs<E> a)
     }
     __syncthreads();
 
-    // ---- phase 1b: the scan's operands K+, Q+, K~ in the element type; then the tables of phase 2 in place ----
+    // ---- phase 1b: the scan's operands K+, Q+, K~ in the element type -----------------------------------------
     {
         E* kpo = a.kplus + (size_t)tok0 * row_stride + (size_t)h * DK;
         E* qpo = a.qplus + (size_t)tok0 * row_stride + (size_t)h * DK;
         E* kto = a.ktilde + (size_t)tok0 * row_stride + (size_t)h * DK;
-        for (int x = tid; x < 64 * DK; x += 256) {
-            const int row = x / DK, c = x % DK;
-            const float gi = Gs[row * LD + c], gl = Gs[63 * LD + c];
-            const float kv = Kp[row * LD + c], qv = Qp[row * LD + c];
+#pragma unroll
+        for (int it = 0; it < 64 * PPR / 256; ++it) {
+            const int pi = tid + 256 * it;
+            const int row = pi / PPR, piece = pi % PPR;
             if (row < clen) {
-                const float up = __builtin_amdgcn_exp2f(gi);
-                kpo[(size_t)row * row_stride + c] = from_float<E>(kv * up);
-                qpo[(size_t)row * row_stride + c] = from_float<E>(qv * up);
-                kto[(size_t)row * row_stride + c] = from_float<E>(kv * __builtin_amdgcn_exp2f(gl - gi));
+                float kf[EPP], qf[EPP], kp[EPP], qp[EPP], kt[EPP];
+                unpack(*reinterpret_cast<const uint4*>(area + (size_t)(row * LE + piece * EPP) * sizeof(E)), kf);
+                unpack(*reinterpret_cast<const uint4*>(area + TE + (size_t)(row * LE + piece * EPP) * sizeof(E)), qf);
+#pragma unroll
+                for (int i = 0; i < EPP; ++i) {
+                    const float gi = Gs[row * LD + piece * EPP + i], gl = Gs[63 * LD + piece * EPP + i];
+                    const float up = __builtin_amdgcn_exp2f(gi);
+                    kp[i] = kf[i] * up; qp[i] = qf[i] * up; kt[i] = kf[i] * __builtin_amdgcn_exp2f(gl - gi);
+                }
+                const size_t off = (size_t)row * row_stride + piece * EPP;
+                *reinterpret_cast<uint4*>(kpo + off) = pack(kp);
+                *reinterpret_cast<uint4*>(qpo + off) = pack(qp);
+                *reinterpret_cast<uint4*>(kto + off) = pack(kt);
             }
         }
     }
-    __syncthreads();
+    // (no barrier: phase 2a only reads the tables, like phase 1b)
 
     // ---- phase 2a: K K^T and Q K^T with the decay ratios inside the sums ---------------------------------------
     // (1) MFMA jobs, operands formed in registers from the tables: the six off-diagonal 16x16 tiles (ti > tj), split at
@@ -484,9 +518,9 @@ __global__ __launch_bounds__(256) void intra_diag_kernel(IntraDiagArgs<E> a)
         const float* gi = Gs + (16 * ti + r) * LD;
         const float* gj = Gs + (16 * tj + r) * LD;
         const float* ge = Gs + e_row * LD;
-        const float* ki = Kp + (16 * ti + r) * LD;
-        const float* qi = Qp + (16 * ti + r) * LD;
-        const float* kj = Kp + (16 * tj + r) * LD;
+        const E* ki = Kp + (16 * ti + r) * LE;
+        const E* qi = Qp + (16 * ti + r) * LE;
+        const E* kj = Kp + (16 * tj + r) * LE;
         for (int kp = 0; kp < DK / 32; ++kp) {
             floatx4 ka[2], qa[2], kb[2];
 #pragma unroll
@@ -497,7 +531,7 @@ __global__ __launch_bounds__(256) void intra_diag_kernel(IntraDiagArgs<E> a)
                     const float gev = ge[c];
                     const float up = a_ok ? __builtin_amdgcn_exp2f(gi[c] - gev) : 0.f;      // gamma_i / gamma_e
                     const float dn = b_ok ? __builtin_amdgcn_exp2f(gev - gj[c]) : 0.f;      // gamma_e / gamma_j
-                    ka[blk][x] = ki[c] * up; qa[blk][x] = qi[c] * up; kb[blk][x] = kj[c] * dn;
+                    ka[blk][x] = to_float(ki[c]) * up; qa[blk][x] = to_float(qi[c]) * up; kb[blk][x] = to_float(kj[c]) * dn;
                 }
             Slot<E> sk, sq;
             sk.q0 = acc_to_quad<E>(ka[0]); sk.q1 = acc_to_quad<E>(ka[1]);
@@ -515,15 +549,15 @@ __global__ __launch_bounds__(256) void intra_diag_kernel(IntraDiagArgs<E> a)
         while ((ii * (ii + 1)) / 2 <= p) ++ii;       // ii (ii - 1) / 2 <= p < ii (ii + 1) / 2
         pi = 8 * b8 + ii; pj = 8 * b8 + p - (ii * (ii - 1)) / 2;
         const float* gi = Gs + pi * LD; const float* gj = Gs + pj * LD;
-        const float* ki = Kp + pi * LD; const float* qi = Qp + pi * LD; const float* kj = Kp + pj * LD;
+        const E* ki = Kp + pi * LE; const E* qi = Qp + pi * LE; const E* kj = Kp + pj * LE;
         for (int c = 0; c < DK; ++c) {
-            const float w = kj[c] * __builtin_amdgcn_exp2f(gi[c] - gj[c]);
-            pkk += ki[c] * w; pqk += qi[c] * w;
+            const float w = to_float(kj[c]) * __builtin_amdgcn_exp2f(gi[c] - gj[c]);
+            pkk += to_float(ki[c]) * w; pqk += to_float(qi[c]) * w;
         }
     }
     if (tid < 64) {                                  // P_ii = q_i . k_i
-        const float* ki = Kp + tid * LD; const float* qi = Qp + tid * LD;
-        for (int c = 0; c < DK; ++c) pdg += qi[c] * ki[c];
+        const E* ki = Kp + tid * LE; const E* qi = Qp + tid * LE;
+        for (int c = 0; c < DK; ++c) pdg += to_float(qi[c]) * to_float(ki[c]);
     }
     __syncthreads();   // the tables are dead from here on; Lm, Pm, Tm overlay them
 
