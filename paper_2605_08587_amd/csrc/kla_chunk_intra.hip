@@ -406,6 +406,20 @@ __global__ __launch_bounds__(256) void intra_diag_kernel(IntraDiagArgs<E> a)
             return make_uint4(__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]), __float_as_uint(f[3]));
     };
 
+    auto ld4e = [](const E* p) {                     // 4 consecutive elements (8- resp. 16-byte aligned) as floats
+        floatx4 f;
+        if constexpr (sizeof(E) == 2) {
+            const uint2 w = *reinterpret_cast<const uint2*>(p);
+            f[0] = bf16_bits_to_float(w.x & 0xffffu); f[1] = bf16_bits_to_float(w.x >> 16);
+            f[2] = bf16_bits_to_float(w.y & 0xffffu); f[3] = bf16_bits_to_float(w.y >> 16);
+        } else {
+            const float4 w = *reinterpret_cast<const float4*>(p);
+            f[0] = w.x; f[1] = w.y; f[2] = w.z; f[3] = w.w;
+        }
+        return f;
+    };
+    auto ld4f = [](const float* p) { const float4 w = *reinterpret_cast<const float4*>(p); floatx4 f; f[0] = w.x; f[1] = w.y; f[2] = w.z; f[3] = w.w; return f; };
+
     // ---- phase 1: K, Q rows and log2 alpha -> LDS; key norms -> beta ---------------------------------------------
     {
         const E* kb = a.k + (size_t)tok0 * row_stride + (size_t)h * DK;
@@ -524,15 +538,17 @@ __global__ __launch_bounds__(256) void intra_diag_kernel(IntraDiagArgs<E> a)
         for (int kp = 0; kp < DK / 32; ++kp) {
             floatx4 ka[2], qa[2], kb[2];
 #pragma unroll
-            for (int blk = 0; blk < 2; ++blk)
+            for (int blk = 0; blk < 2; ++blk) {
+                const int c = 32 * kp + 16 * blk + 4 * g;
+                const floatx4 gev = ld4f(ge + c), giv = ld4f(gi + c), gjv = ld4f(gj + c);
+                const floatx4 kiv = ld4e(ki + c), qiv = ld4e(qi + c), kjv = ld4e(kj + c);
 #pragma unroll
                 for (int x = 0; x < 4; ++x) {
-                    const int c = 32 * kp + 16 * blk + 4 * g + x;
-                    const float gev = ge[c];
-                    const float up = a_ok ? __builtin_amdgcn_exp2f(gi[c] - gev) : 0.f;      // gamma_i / gamma_e
-                    const float dn = b_ok ? __builtin_amdgcn_exp2f(gev - gj[c]) : 0.f;      // gamma_e / gamma_j
-                    ka[blk][x] = to_float(ki[c]) * up; qa[blk][x] = to_float(qi[c]) * up; kb[blk][x] = to_float(kj[c]) * dn;
+                    const float up = a_ok ? __builtin_amdgcn_exp2f(giv[x] - gev[x]) : 0.f;      // gamma_i / gamma_e
+                    const float dn = b_ok ? __builtin_amdgcn_exp2f(gev[x] - gjv[x]) : 0.f;      // gamma_e / gamma_j
+                    ka[blk][x] = kiv[x] * up; qa[blk][x] = qiv[x] * up; kb[blk][x] = kjv[x] * dn;
                 }
+            }
             Slot<E> sk, sq;
             sk.q0 = acc_to_quad<E>(ka[0]); sk.q1 = acc_to_quad<E>(ka[1]);
             sq.q0 = acc_to_quad<E>(qa[0]); sq.q1 = acc_to_quad<E>(qa[1]);
@@ -550,14 +566,24 @@ __global__ __launch_bounds__(256) void intra_diag_kernel(IntraDiagArgs<E> a)
         pi = 8 * b8 + ii; pj = 8 * b8 + p - (ii * (ii - 1)) / 2;
         const float* gi = Gs + pi * LD; const float* gj = Gs + pj * LD;
         const E* ki = Kp + pi * LE; const E* qi = Qp + pi * LE; const E* kj = Kp + pj * LE;
-        for (int c = 0; c < DK; ++c) {
-            const float w = to_float(kj[c]) * __builtin_amdgcn_exp2f(gi[c] - gj[c]);
-            pkk += to_float(ki[c]) * w; pqk += to_float(qi[c]) * w;
+#pragma unroll 2
+        for (int c = 0; c < DK; c += 4) {
+            const floatx4 giv = ld4f(gi + c), gjv = ld4f(gj + c);
+            const floatx4 kiv = ld4e(ki + c), qiv = ld4e(qi + c), kjv = ld4e(kj + c);
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+                const float w = kjv[x] * __builtin_amdgcn_exp2f(giv[x] - gjv[x]);
+                pkk += kiv[x] * w; pqk += qiv[x] * w;
+            }
         }
     }
     if (tid < 64) {                                  // P_ii = q_i . k_i
         const E* ki = Kp + tid * LE; const E* qi = Qp + tid * LE;
-        for (int c = 0; c < DK; ++c) pdg += to_float(qi[c]) * to_float(ki[c]);
+        for (int c = 0; c < DK; c += 4) {
+            const floatx4 kiv = ld4e(ki + c), qiv = ld4e(qi + c);
+#pragma unroll
+            for (int x = 0; x < 4; ++x) pdg += qiv[x] * kiv[x];
+        }
     }
     __syncthreads();   // the tables are dead from here on; Lm, Pm, Tm overlay them
 
