@@ -168,6 +168,20 @@ int kla_chunk_bwd(const void *q, const void *k, const void *v,
                   void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * kla_chunk_bwd with options: the backward of kla_chunk_fwd_opts(..., opts).  Only KLA_OPT_GDN_BETA is taken
+ * (beta_t = eta_t: d eta = d beta and dk loses its term through the coefficient); KLA_OPT_NORMALIZE_Q is
+ * KLA_ERR_SHAPE - that read-out equals the plain one on q / ||q||, so a caller can normalise q itself and apply the
+ * chain rule to dq.  kla_chunk_bwd(...) is kla_chunk_bwd_opts(..., 0).  Same workspace.
+ */
+int kla_chunk_bwd_opts(const void *q, const void *k, const void *v,
+                       const float *log_alpha, const float *eta, float eps,
+                       const float *h0, const void *d_o, const float *d_hT,
+                       void *dq, void *dk_, void *dv_, float *dlog_alpha, float *deta, float *dh0,
+                       const int32_t *cu_seqlens_dev, const int32_t *cu_seqlens_host, int n_seq,
+                       int N, int T, int H, int dk, int dv, int chunk, kla_dtype dt,
+                       void *workspace, size_t workspace_bytes, void *hip_stream, unsigned opts);
+
+/*
  * Diagonal gating (App. B, "Extension to diagonal gating"; App. A, decay-agnostic remark): the decay operator is
  * D_t = diag(alpha_t) with one decay per key channel, S~ = diag(alpha_t) S_{t-1} (row i of the d_k x d_v state is
  * scaled by alpha_t[i]); the residual, the Kaczmarz coefficient of eq. (3), the write and the read-out are unchanged.

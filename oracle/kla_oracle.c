@@ -170,7 +170,8 @@ int kla_oracle_decode_unit(const float *q, const float *k, const float *v,
  * Returns beta and 1/(||k||^2 + eps) (0 if the denominator is 0); St gets the decayed state alpha S, e the residual;
  * Snew may be NULL when only those are wanted. */
 static double kla_token_state(const double *S, const float *k, const float *v, double log_alpha, double eta,
-                              double eps, int dk, int dv, double *St, double *e, double *Snew, double *inv_den)
+                              double eps, int dk, int dv, double *St, double *e, double *Snew, double *inv_den,
+                              int gdn_beta)
 {
     int i, j;
     const double alpha = exp(log_alpha);
@@ -184,6 +185,7 @@ static double kla_token_state(const double *S, const float *k, const float *v, d
     for (i = 0; i < dk; ++i) nk += (double)k[i] * (double)k[i];
     const double den = nk + eps;
     *inv_den = (den == 0.0) ? 0.0 : 1.0 / den;
+    if (gdn_beta) *inv_den = 1.0;                /* beta = eta: the coefficient does not see the key */
     const double beta = eta * *inv_den;
     if (Snew)
         for (i = 0; i < dk; ++i)
@@ -202,13 +204,14 @@ static double kla_token_state(const double *S, const float *k, const float *v, d
  *   dlog_alpha, deta  [n_tokens_total, H]     double
  *   dh0               [dk, dv] double for this unit (out), may be NULL
  * The states are recomputed from checkpoints kept every 64 tokens, so memory stays at
- * (len/64 + 65) states.  Returns 0, or -1 if memory could not be allocated.
+ * (len/64 + 65) states.  gdn_beta: beta_t = eta_t (no dependence on k).  Returns 0, or -1 if memory could not be
+ * allocated.
  */
-int kla_oracle_sequence_bwd(const float *q, const float *k, const float *v,
-                            const double *log_alpha, const double *eta, double eps,
-                            const double *h0, const double *d_o, const double *d_hT,
-                            double *dq, double *dk_, double *dv_, double *dlog_alpha, double *deta,
-                            double *dh0, long t0, long len, int h, int H, int dk, int dv)
+int kla_oracle_sequence_bwd_opts(const float *q, const float *k, const float *v,
+                                 const double *log_alpha, const double *eta, double eps,
+                                 const double *h0, const double *d_o, const double *d_hT,
+                                 double *dq, double *dk_, double *dv_, double *dlog_alpha, double *deta,
+                                 double *dh0, long t0, long len, int h, int H, int dk, int dv, int gdn_beta)
 {
     enum { SEG = 64 };
     const size_t sz = (size_t)dk * dv;
@@ -231,7 +234,7 @@ int kla_oracle_sequence_bwd(const float *q, const float *k, const float *v,
         const long a = t0 + sg * SEG, b = (a + SEG < t0 + len) ? a + SEG : t0 + len;
         for (long t = a; t < b; ++t) {
             const size_t th = (size_t)t * H + h;
-            kla_token_state(st, k + th * dk, v + th * dv, log_alpha[th], eta[th], eps, dk, dv, St, e, st + sz, &inv_den);
+            kla_token_state(st, k + th * dk, v + th * dv, log_alpha[th], eta[th], eps, dk, dv, St, e, st + sz, &inv_den, gdn_beta);
             memcpy(st, st + sz, sizeof(double) * sz);
         }
         memcpy(chk + sz * (size_t)(sg + 1), st, sizeof(double) * sz);
@@ -247,7 +250,7 @@ int kla_oracle_sequence_bwd(const float *q, const float *k, const float *v,
         for (long t = a; t < b; ++t) {
             const size_t th = (size_t)t * H + h;
             kla_token_state(st + sz * (size_t)(t - a), k + th * dk, v + th * dv, log_alpha[th], eta[th], eps, dk, dv,
-                            St, e, st + sz * (size_t)(t - a + 1), &inv_den);
+                            St, e, st + sz * (size_t)(t - a + 1), &inv_den, gdn_beta);
         }
         for (long t = b - 1; t >= a; --t) {
             const size_t th = (size_t)t * H + h;
@@ -265,7 +268,7 @@ int kla_oracle_sequence_bwd(const float *q, const float *k, const float *v,
                 gq[i] = acc;
             }
             /* the forward quantities of this token again: decayed state, residual, beta */
-            const double beta = kla_token_state(Sprev, kt, vt, log_alpha[th], eta[th], eps, dk, dv, St, e, NULL, &inv_den);
+            const double beta = kla_token_state(Sprev, kt, vt, log_alpha[th], eta[th], eps, dk, dv, St, e, NULL, &inv_den, gdn_beta);
             /* line 4: S = S~ + beta k e^T */
             double dbeta = 0.0;
             for (j = 0; j < dv; ++j) de[j] = 0.0;
@@ -291,7 +294,8 @@ int kla_oracle_sequence_bwd(const float *q, const float *k, const float *v,
             }
             /* line 3 / eq. (3): beta = eta / (||k||^2 + eps) */
             deta[th] = dbeta * inv_den;
-            for (i = 0; i < dk; ++i) gk[i] -= 2.0 * beta * dbeta * inv_den * (double)kt[i];
+            if (!gdn_beta)
+                for (i = 0; i < dk; ++i) gk[i] -= 2.0 * beta * dbeta * inv_den * (double)kt[i];
             /* line 1: S~ = alpha S, alpha = exp(log_alpha) */
             double dla = 0.0;
             const double alpha = exp(log_alpha[th]);
@@ -373,4 +377,15 @@ int kla_oracle_decode_unit_diag(const float *q, const float *k, const float *v,
     kla_token_diag(S, q, k, v, log_alpha, eta, eps, dk, dv, o, e);
     free(e);
     return 0;
+}
+
+/* The gradient for the plain recurrence (beta of eq. (3)). */
+int kla_oracle_sequence_bwd(const float *q, const float *k, const float *v,
+                            const double *log_alpha, const double *eta, double eps,
+                            const double *h0, const double *d_o, const double *d_hT,
+                            double *dq, double *dk_, double *dv_, double *dlog_alpha, double *deta,
+                            double *dh0, long t0, long len, int h, int H, int dk, int dv)
+{
+    return kla_oracle_sequence_bwd_opts(q, k, v, log_alpha, eta, eps, h0, d_o, d_hT, dq, dk_, dv_, dlog_alpha, deta, dh0,
+                                        t0, len, h, H, dk, dv, 0);
 }

@@ -58,11 +58,11 @@ def _load():
             lib.kla_oracle_decode_unit_diag.restype = ctypes.c_int
             lib.kla_oracle_decode_unit_diag.argtypes = [fp, fp, fp, dp, ctypes.c_double, ctypes.c_double, dp, dp,
                                                         ctypes.c_int, ctypes.c_int]
-            lib.kla_oracle_sequence_bwd.restype = ctypes.c_int
-            lib.kla_oracle_sequence_bwd.argtypes = [fp, fp, fp, dp, dp, ctypes.c_double, dp, dp, dp,
+            lib.kla_oracle_sequence_bwd_opts.restype = ctypes.c_int
+            lib.kla_oracle_sequence_bwd_opts.argtypes = [fp, fp, fp, dp, dp, ctypes.c_double, dp, dp, dp,
                                                     dp, dp, dp, dp, dp, dp,
                                                     ctypes.c_long, ctypes.c_long, ctypes.c_int,
-                                                    ctypes.c_int, ctypes.c_int, ctypes.c_int]
+                                                    ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int]
             _lib = lib
     return _lib
 
@@ -199,11 +199,12 @@ def kla_decode_diag(q, k, v, log_alpha, eta, eps, S, threads=None):
 
 
 def kla_recurrent_bwd(q, k, v, log_alpha, eta, eps, d_o, h0=None, d_hT=None, cu_seqlens=None, threads=None,
-                      units=None):
+                      units=None, gdn_beta=False):
     """Gradient of L = sum <d_o, o> + sum <d_hT, hT> of kla_recurrent (no options) with respect to its inputs.
 
     Shapes as in kla_recurrent; d_o: [N, T, H, dv]; d_hT: [n_seq, H, dk, dv] or None (zeros).
     `units`, if given, restricts the work to those (sequence, head) pairs; other rows stay zero.
+    gdn_beta: gradient of the recurrence with beta_t = eta_t.
     Returns a dict with dq, dk, dv, dlog_alpha, deta, dh0 (float64, shapes of the corresponding inputs).
     """
     lib = _load()
@@ -229,12 +230,12 @@ def kla_recurrent_bwd(q, k, v, log_alpha, eta, eps, d_o, h0=None, d_hT=None, cu_
     def run(unit):
         s, h = unit
         off = (s * H + h) * dk * dv
-        rc = lib.kla_oracle_sequence_bwd(_fp(q), _fp(k), _fp(v), _dp(la), _dp(et), float(eps),
+        rc = lib.kla_oracle_sequence_bwd_opts(_fp(q), _fp(k), _fp(v), _dp(la), _dp(et), float(eps),
                                          None if h0d is None else _dp(h0d, off), _dp(go),
                                          None if ghT is None else _dp(ghT, off),
                                          _dp(out["dq"]), _dp(out["dk"]), _dp(out["dv"]), _dp(out["dlog_alpha"]),
                                          _dp(out["deta"]), _dp(out["dh0"], off),
-                                         starts[s], lens[s], h, H, dk, dv)
+                                         starts[s], lens[s], h, H, dk, dv, int(gdn_beta))
         if rc != 0:
             raise MemoryError("oracle scratch allocation failed")
 

@@ -37,6 +37,9 @@ _SIGNATURES = {
     "kla_chunk_bwd_workspace_bytes": (ctypes.c_size_t, [ctypes.c_int] * 6 + [ctypes.c_int, _ip, ctypes.c_int]),
     "kla_chunk_bwd": (ctypes.c_int, [_vp, _vp, _vp, _fp, _fp, ctypes.c_float, _fp, _vp, _fp, _vp, _vp, _vp, _fp, _fp, _fp,
                                      _ip, _ip, ctypes.c_int] + [ctypes.c_int] * 6 + [ctypes.c_int, _vp, ctypes.c_size_t, _vp]),
+    "kla_chunk_bwd_opts": (ctypes.c_int, [_vp, _vp, _vp, _fp, _fp, ctypes.c_float, _fp, _vp, _fp, _vp, _vp, _vp, _fp, _fp, _fp,
+                                          _ip, _ip, ctypes.c_int] + [ctypes.c_int] * 6
+                           + [ctypes.c_int, _vp, ctypes.c_size_t, _vp, ctypes.c_uint]),
     "kla_debug_chunk_stage": (ctypes.c_int, [_vp, _vp, _vp, _fp, _fp, ctypes.c_float, _fp, _vp, _fp, _ip, _ip, ctypes.c_int]
                               + [ctypes.c_int] * 6 + [ctypes.c_int, _vp, ctypes.c_size_t, _vp, ctypes.c_int]),
     "kla_decode_step": (ctypes.c_int, [_vp, _vp, _vp, _fp, _fp, ctypes.c_float, _fp, _vp]
@@ -201,8 +204,9 @@ def kla_chunk_bwd_workspace_bytes(N, T, H, dk, dv, dtype, cu_seqlens=None, chunk
 
 
 def kla_chunk_bwd(q, k, v, log_alpha, eta, eps, d_o, h0=None, d_hT=None, cu_seqlens=None, want_dh0=True,
-                  workspace=None, out=None, chunk=64):
-    """Backward of kla_chunk_fwd (no options): gradients of sum <d_o, o> + sum <d_hT, hT>.
+                  workspace=None, out=None, chunk=64, gdn_beta=False):
+    """Backward of kla_chunk_fwd: gradients of sum <d_o, o> + sum <d_hT, hT>.  gdn_beta: of the forward with
+    beta_t = eta_t (kla_chunk_bwd_opts of the C ABI; the read-out normalisation has no backward).
 
     d_o [N,T,H,dv] in the dtype of q; d_hT [n_states,H,dk,dv] fp32 or None (zeros).
     Returns a dict: dq, dk, dv (dtype of q), dlog_alpha, deta (fp32 [N,T,H]), dh0 (fp32, or None).
@@ -227,10 +231,11 @@ def kla_chunk_bwd(q, k, v, log_alpha, eta, eps, d_o, h0=None, d_hT=None, cu_seql
     if "dh0" not in out:
         out["dh0"] = torch.empty((n_states, H, dk, dv), dtype=torch.float32, device=q.device) if want_dh0 else None
     _dev(*out.values())
-    rc = lib().kla_chunk_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(eta), float(eps), _ptr(h0), _ptr(d_o),
-                             _ptr(d_hT), _ptr(out["dq"]), _ptr(out["dk"]), _ptr(out["dv"]), _ptr(out["dlog_alpha"]),
-                             _ptr(out["deta"]), _ptr(out["dh0"]), _ptr(cu_seqlens), cu_hp, n_seq, N, T, H, dk, dv, chunk,
-                             dt, _ptr(workspace), workspace.numel() * workspace.element_size(), _stream())
+    args = (_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(eta), float(eps), _ptr(h0), _ptr(d_o),
+            _ptr(d_hT), _ptr(out["dq"]), _ptr(out["dk"]), _ptr(out["dv"]), _ptr(out["dlog_alpha"]),
+            _ptr(out["deta"]), _ptr(out["dh0"]), _ptr(cu_seqlens), cu_hp, n_seq, N, T, H, dk, dv, chunk,
+            dt, _ptr(workspace), workspace.numel() * workspace.element_size(), _stream())
+    rc = lib().kla_chunk_bwd_opts(*args, KLA_OPT_GDN_BETA) if gdn_beta else lib().kla_chunk_bwd(*args)
     if rc != 0:
         raise KlaError(rc, "kla_chunk_bwd")
     return out

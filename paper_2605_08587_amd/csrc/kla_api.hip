@@ -207,7 +207,7 @@ template <typename E>
 int chunk_bwd_impl(const void* q, const void* k, const void* v, const float* log_alpha, const float* eta, float eps,
                    const float* h0, const void* d_o, const float* d_hT, void* dq, void* dk_, void* dv_,
                    float* dlog_alpha, float* deta, float* dh0, const int32_t* cu_dev, int n_seq, int N, int T, int H,
-                   int dk, int dv, const BwdPlan& pl, char* ws, hipStream_t st)
+                   int dk, int dv, const BwdPlan& pl, char* ws, hipStream_t st, unsigned opts)
 {
     int* chunk_off = reinterpret_cast<int*>(ws + pl.off_C);
     const int NT = (T + 63) / 64;
@@ -218,7 +218,7 @@ int chunk_bwd_impl(const void* q, const void* k, const void* v, const float* log
     ia.log_alpha = log_alpha; ia.eta = eta; ia.eps = eps;
     ia.cu_seqlens = n_seq > 0 ? cu_dev : nullptr; ia.chunk_off = chunk_off; ia.n_seq = n_seq;
     ia.T = T; ia.NT = NT; ia.H = H;
-    ia.wsT = reinterpret_cast<E*>(ws + pl.off_rec); ia.wsP = nullptr; ia.wsG = nullptr; ia.opts = 0u;
+    ia.wsT = reinterpret_cast<E*>(ws + pl.off_rec); ia.wsP = nullptr; ia.wsG = nullptr; ia.opts = opts;
     bool fast = false;                                // bf16: the specialised kernels, unless KLA_BWD_IMPL=generic (A/B testing)
     if constexpr (sizeof(E) == 2) {
         const char* impl = getenv("KLA_BWD_IMPL");
@@ -241,6 +241,7 @@ int chunk_bwd_impl(const void* q, const void* k, const void* v, const float* log
     ba.s_chk = reinterpret_cast<E*>(ws + pl.off_S); ba.ds_chk = reinterpret_cast<E*>(ws + pl.off_dS);
     ba.X = reinterpret_cast<E*>(ws + pl.off_X); ba.U = reinterpret_cast<E*>(ws + pl.off_U);
     ba.Y = reinterpret_cast<E*>(ws + pl.off_Y);
+    ba.opts = opts;
     // two waves (32 state columns) per workgroup once that still gives a workgroup per CU
     const long chains8 = ((long)pl.base.n_states * H + 7) / 8 * 8;
     const int waves = (chains8 * (dv / 32) >= 192) ? 2 : 1;
@@ -400,6 +401,18 @@ int kla_chunk_bwd(const void* q, const void* k, const void* v, const float* log_
                   const int32_t* cu_seqlens_host, int n_seq, int N, int T, int H, int dk, int dv, int chunk,
                   kla_dtype dt, void* workspace, size_t workspace_bytes, void* hip_stream)
 {
+    return kla_chunk_bwd_opts(q, k, v, log_alpha, eta, eps, h0, d_o, d_hT, dq, dk_, dv_, dlog_alpha, deta, dh0,
+                              cu_seqlens_dev, cu_seqlens_host, n_seq, N, T, H, dk, dv, chunk, dt, workspace,
+                              workspace_bytes, hip_stream, 0u);
+}
+
+int kla_chunk_bwd_opts(const void* q, const void* k, const void* v, const float* log_alpha, const float* eta, float eps,
+                       const float* h0, const void* d_o, const float* d_hT, void* dq, void* dk_, void* dv_,
+                       float* dlog_alpha, float* deta, float* dh0, const int32_t* cu_seqlens_dev,
+                       const int32_t* cu_seqlens_host, int n_seq, int N, int T, int H, int dk, int dv, int chunk,
+                       kla_dtype dt, void* workspace, size_t workspace_bytes, void* hip_stream, unsigned opts)
+{
+    if (opts & ~(unsigned)KLA_OPT_GDN_BETA) return KLA_ERR_SHAPE;     // the read-out normalisation has no backward here
     BwdPlan pl;
     const int rc = make_bwd_plan(N, T, H, dk, dv, chunk, (int)dt, cu_seqlens_host, n_seq, &pl);
     if (rc != KLA_OK) return rc;
@@ -421,9 +434,9 @@ int kla_chunk_bwd(const void* q, const void* k, const void* v, const float* log_
     char* ws = static_cast<char*>(workspace);
     if (dt == KLA_BF16)
         return chunk_bwd_impl<bf16_t>(q, k, v, log_alpha, eta, eps, h0, d_o, d_hT, dq, dk_, dv_, dlog_alpha, deta, dh0,
-                                      cu_seqlens_dev, n_seq, N, T, H, dk, dv, pl, ws, st);
+                                      cu_seqlens_dev, n_seq, N, T, H, dk, dv, pl, ws, st, opts);
     return chunk_bwd_impl<float>(q, k, v, log_alpha, eta, eps, h0, d_o, d_hT, dq, dk_, dv_, dlog_alpha, deta, dh0,
-                                 cu_seqlens_dev, n_seq, N, T, H, dk, dv, pl, ws, st);
+                                 cu_seqlens_dev, n_seq, N, T, H, dk, dv, pl, ws, st, opts);
 }
 
 size_t kla_chunk_fwd_diag_workspace_bytes(int N, int T, int H, int dk, int dv, int chunk, kla_dtype dt,

@@ -753,7 +753,7 @@ __global__ __launch_bounds__(256, 2) void bwd_assemble_kernel(BwdArgs<E> a)
         const float db = row16_sum(dbr[e]) + yx_s[i];
         const float dgv = row16_sum(dgr[e]);
         if (r == 0) { dbeta_s[i] = db; dg_s[i] = dgv; }
-        c5[e] = -2.f * beta_s[i] * db * invden_s[i];
+        c5[e] = (a.opts & kOptGdnBeta) ? 0.f : -2.f * beta_s[i] * db * invden_s[i];   // beta = eta does not depend on k
     }
     {
         E* qo = a.dq + (size_t)tok0 * kq_stride + (size_t)h * DK + r;

@@ -700,7 +700,7 @@ __global__ __launch_bounds__(256, 2) void bwd_assemble_bf16_kernel(BwdArgs<bf16_
         for (int off = 1; off < 16; off <<= 1) { db += __shfl_xor(db, off, kWave); dgv += __shfl_xor(dgv, off, kWave); }
         db += yx_s[i];
         if (r == 0) { dbeta_s[i] = db; dg_s[i] = rowmask[e] * dgv; }
-        c5[e] = -2.f * beta_s[i] * db * invden_s[i];
+        c5[e] = (a.opts & kOptGdnBeta) ? 0.f : -2.f * beta_s[i] * db * invden_s[i];   // beta = eta does not depend on k
     }
     __syncthreads();                                 // every wave is done with A o dP and D': they become staging tiles
 

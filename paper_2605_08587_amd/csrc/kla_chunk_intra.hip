@@ -235,7 +235,7 @@ __global__ __launch_bounds__(256) void intra_kernel(IntraArgs<E> a)
                 beta_s[row] = (a.opts & kOptGdnBeta) ? et : kaczmarz_beta(et, ss, a.eps);
                 // scale of the normalised read-out o_t = S_t^T q_t / ||q_t|| (Sec. 3.3); a zero query gives 0
                 rq_s[row] = (a.opts & kOptNormalizeQ) ? (sq > 0.f ? 1.0f / sqrtf(sq) : 0.f) : 1.f;
-                if constexpr (BWD) invden_s[row] = (ss + a.eps == 0.f) ? 0.f : 1.0f / (ss + a.eps);
+                if constexpr (BWD) invden_s[row] = (a.opts & kOptGdnBeta) ? 1.f : ((ss + a.eps == 0.f) ? 0.f : 1.0f / (ss + a.eps));
             }
         }
         if (wave == 0) {
@@ -330,7 +330,8 @@ hipError_t launch_intra(const IntraArgs<E>& a, int dk, int n_chunks, hipStream_t
 template hipError_t launch_intra<float>(const IntraArgs<float>&, int, int, hipStream_t);
 template hipError_t launch_intra<bf16_t>(const IntraArgs<bf16_t>&, int, int, hipStream_t);
 
-// The records of the backward pass: a.wsT points at them, a.wsP and a.wsG are not used, a.opts must be 0.
+// The records of the backward pass: a.wsT points at them, a.wsP and a.wsG are not used; of the options only
+// kOptGdnBeta applies (beta = eta, and the record's fourth vector, d beta / d eta, is then 1).
 template <typename E>
 hipError_t launch_intra_bwd(const IntraArgs<E>& a, int dk, int n_chunks, hipStream_t st)
 {

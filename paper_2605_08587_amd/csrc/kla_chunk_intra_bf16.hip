@@ -90,7 +90,8 @@ __device__ __forceinline__ void write_transposed(char* out, const float* m, int 
 }  // namespace
 
 // BWD = true: the record of the backward pass, [T' | M^T | P^T | gamma_i | gamma_C/gamma_i | beta_i | 1/(||k_i||^2+eps)]
-// (M = (I + L)^{-1}; the transposes as the 6 upper-triangular tile-pairs, see kla_mma.hpp); options are not taken.
+// (M = (I + L)^{-1}; the transposes as the 6 upper-triangular tile-pairs, see kla_mma.hpp).  Of the options only
+// kOptGdnBeta applies there (beta = eta; the fourth vector, d beta / d eta, is then 1).
 template <int DK, bool BWD>
 __global__ __launch_bounds__(256, 3) void intra_bf16_kernel(IntraArgs<bf16_t> a)
 {
@@ -229,7 +230,7 @@ __global__ __launch_bounds__(256, 3) void intra_bf16_kernel(IntraArgs<bf16_t> a)
                     for (int e = 0; e < 4; ++e)
                         if (4 * g + e == r) {
                             beta_s[16 * J.ti + r] = gdn ? eta_s[16 * J.ti + r] : kaczmarz_beta_fast(eta_s[16 * J.ti + r], acc[jb][e], a.eps);
-                            if constexpr (BWD) invden_s[16 * J.ti + r] = kaczmarz_beta_fast(1.f, acc[jb][e], a.eps);
+                            if constexpr (BWD) invden_s[16 * J.ti + r] = gdn ? 1.f : kaczmarz_beta_fast(1.f, acc[jb][e], a.eps);
                         }
                 }
             });

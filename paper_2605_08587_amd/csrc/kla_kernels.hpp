@@ -35,7 +35,7 @@ template <typename E> struct IntraArgs {
     unsigned opts;                               // kOptNormalizeQ | kOptGdnBeta
 };
 template <typename E> hipError_t launch_intra(const IntraArgs<E>& a, int dk, int n_chunks, hipStream_t st);
-// the records of the backward pass (see bwd_record_bytes in kla_mma.hpp) at a.wsT; a.wsP, a.wsG unused, a.opts = 0
+// the records of the backward pass (see bwd_record_bytes in kla_mma.hpp) at a.wsT; a.wsP, a.wsG unused; a.opts: kOptGdnBeta or 0
 template <typename E> hipError_t launch_intra_bwd(const IntraArgs<E>& a, int dk, int n_chunks, hipStream_t st);
 
 // Diagonal gating (App. B): log_alpha is [tokens, H, dk].  Besides the records (with unit decay vectors) the stage
@@ -102,6 +102,7 @@ template <typename E> struct BwdArgs {
     const char* rec;                 // stage-1 records
     E* s_chk; E* ds_chk;             // [n_chunks * H][dv][dk]
     E* X; E* U; E* Y;                // [tokens][H][dv]
+    unsigned opts;                   // kOptGdnBeta: beta = eta, so dk has no term through the coefficient
 };
 template <typename E> hipError_t launch_bwd_states(const BwdArgs<E>& a, int dk, int waves, hipStream_t st);
 template <typename E> hipError_t launch_bwd_scan(const BwdArgs<E>& a, int dk, int waves, hipStream_t st);

@@ -210,6 +210,11 @@ def test_chunk_bwd_validation_and_workspace():
         expect += 3 * r256(N * T * H * dv * eb)                # X, U, Y
         assert lib.kla_chunk_bwd_workspace_bytes(N, T, H, dk, dv, 64, dt, None, 0) == expect
     assert lib.kla_chunk_bwd_workspace_bytes(1, 64, 1, 100, 64, 64, kla.KLA_BF16, None, 0) == 0
+    opt = lambda opts, **o: lib.kla_chunk_bwd_opts(*[{**base, **o}[n] for n in names], opts)
+    assert opt(kla.KLA_OPT_NORMALIZE_Q) == E_SHAPE            # no backward for the normalised read-out
+    assert opt(8) == E_SHAPE
+    assert opt(kla.KLA_OPT_GDN_BETA, q=None) == E_NULL
+    assert opt(kla.KLA_OPT_GDN_BETA, N=0) == OK
 
 
 def test_diag_entry_points_validate():

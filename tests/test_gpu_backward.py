@@ -110,6 +110,20 @@ def test_bwd_generic_kernels_on_bf16(kla, dk, dv, T, monkeypatch):
     _check(kla, kla_inputs.chunk_inputs(2, T, 2, dk, dv, dtype=torch.bfloat16, seed=325, h0_std=0.3), seed=9)
 
 
+@pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16])
+def test_bwd_gdn_beta_option(kla, dt):
+    """beta_t = eta_t (Table 2's delta rule): d eta = d beta, and dk has no term through the coefficient."""
+    d = kla_inputs.chunk_inputs(2, 200, 2, 128, 128, dtype=dt, seed=370, h0_std=0.3)
+    d["k"] = (d["k"].float() / d["k"].float().norm(dim=-1, keepdim=True)).to(dt)       # unit keys: the plain delta rule is stable
+    d_o, g = kla_inputs.grad_inputs(d, 10)
+    got = _run(kla, d, d_o, g, gdn_beta=True)
+    q, k, v = (kla_inputs.to_numpy_f32(d[x]) for x in "qkv")
+    ref = token_oracle.kla_recurrent_bwd(q, k, v, d["log_alpha"].numpy(), d["eta"].numpy(), d["eps"],
+                                         kla_inputs.to_numpy_f32(d_o), h0=d["h0"].numpy(), d_hT=g.numpy(), gdn_beta=True)
+    for n in NAMES:
+        assert token_oracle.rel_err(got[n], ref[n]) <= TOL[dt], n
+
+
 def test_bwd_two_waves_per_workgroup(kla):
     """Enough (sequence, head) pairs for the 32-column workgroups the benchmark shape uses."""
     _check(kla, kla_inputs.chunk_inputs(16, 192, 4, 128, 128, dtype=torch.bfloat16, seed=330, h0_std=0.1), seed=3)

@@ -566,3 +566,31 @@ def test_diag_chunkwise_equals_recurrent(C):
                                                   h0=S0[0, 0], chunk=C)
     assert np.max(np.abs(oc - o[0, :, 0])) <= 1e-10 * np.max(np.abs(o))
     assert np.max(np.abs(hc - hT[0, 0])) <= 1e-10 * np.max(np.abs(hT))
+
+
+def test_gradient_gdn_beta_central_differences():
+    """beta_t = eta_t: the gradient oracle's option against central differences of the forward oracle's option."""
+    rng = RNG(46)
+    T, H, dk, dv, eps = 70, 1, 4, 3, 1e-3
+    q, k, v, la, eta, S0 = _rand_problem(rng, T, H, dk, dv)
+    q, k, v = ((np.round(x * 64) / 64).astype(np.float32) for x in (q, k, v))
+    k = k * 0.5                                              # keeps eta |k|^2 below 2, so the delta rule stays stable
+    la = la * 0.2
+    go = rng.standard_normal((1, T, H, dv))
+    g = token_oracle.kla_recurrent_bwd(q, k, v, la, eta, eps, go, h0=S0, gdn_beta=True)
+    def loss(qq, kk, ee):
+        o, _, _ = token_oracle.kla_recurrent(qq, kk, v, la, ee, eps, h0=S0, threads=1, gdn_beta=True)
+        return float(np.sum(o * go))
+    for name, arr, key in (("k", k, "dk"), ("eta", eta, "deta"), ("q", q, "dq")):
+        h = 2.0 ** -9 if arr.dtype == np.float32 else 1e-5
+        scale = np.max(np.abs(g[key]))
+        for fi in rng.choice(arr.size, size=8, replace=False):
+            idx = np.unravel_index(fi, arr.shape)
+            plus, minus = arr.copy(), arr.copy()
+            plus[idx] += h
+            minus[idx] -= h
+            args_p = dict(qq=q, kk=k, ee=eta); args_m = dict(args_p)
+            args_p[{"k": "kk", "eta": "ee", "q": "qq"}[name]] = plus
+            args_m[{"k": "kk", "eta": "ee", "q": "qq"}[name]] = minus
+            fd = (loss(**args_p) - loss(**args_m)) / (2 * h)
+            assert abs(fd - g[key][idx]) <= 2e-5 * scale + 1e-8, (name, idx, fd, g[key][idx])
