@@ -65,6 +65,21 @@ __device__ __forceinline__ floatx4 quad_to_f(u32x2 q)
     r[2] = __uint_as_float(q.y << 16); r[3] = __uint_as_float(q.y & 0xffff0000u);
     return r;
 }
+// A quad of lanes (r = 4 q .. 4 q + 3) holds a 4x4 block of bf16 of an accumulator tile: lane j rows 4 g + e (e = 0..3,
+// packed in two dwords) of column 4 q + j.  Transposed inside the quad by two exchange steps (dwords with lane j ^ 2,
+// halves with lane j ^ 1) each lane then owns 4 consecutive columns of row 4 g + (r & 3): one 64-bit LDS write per tile
+// instead of four 16-bit ones.  q_lo = (r & 3) < 2; psel = (r & 1) ? 0x03020706 : 0x05040100.
+__device__ __forceinline__ u32x2 quad_transpose4x4(u32x2 ob, bool q_lo, uint32_t psel)
+{
+    const uint32_t snd = q_lo ? ob.y : ob.x;
+    const uint32_t rcv = (uint32_t)__builtin_amdgcn_mov_dpp((int)snd, 0x4E, 0xf, 0xf, true);   // quad_perm [2,3,0,1]
+    if (q_lo) ob.y = rcv; else ob.x = rcv;
+    const uint32_t px = (uint32_t)__builtin_amdgcn_mov_dpp((int)ob.x, 0xB1, 0xf, 0xf, true);   // quad_perm [1,0,3,2]
+    const uint32_t py = (uint32_t)__builtin_amdgcn_mov_dpp((int)ob.y, 0xB1, 0xf, 0xf, true);
+    ob.x = __builtin_amdgcn_perm(px, ob.x, psel);
+    ob.y = __builtin_amdgcn_perm(py, ob.y, psel);
+    return ob;
+}
 __device__ __forceinline__ floatx4 ld_f4(const char* p) { return *reinterpret_cast<const floatx4*>(p); }
 
 }  // namespace kla

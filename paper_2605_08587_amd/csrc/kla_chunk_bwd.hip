@@ -534,19 +534,9 @@ __global__ __launch_bounds__(256, 2) void bwd_assemble_kernel(BwdArgs<E> a)
     // ---- which chunk of which sequence (as in the intra-chunk stage) -------------------------------
     const int h = blockIdx.x % a.H;
     const int cg = blockIdx.x / a.H;
-    long tok0; int clen;
-    if (a.cu_seqlens) {
-        int lo = 0, hi = a.n_seq - 1;
-        while (lo < hi) { const int mid = (lo + hi + 1) >> 1; if (a.chunk_off[mid] <= cg) lo = mid; else hi = mid - 1; }
-        const int c = cg - a.chunk_off[lo];
-        const int s0 = a.cu_seqlens[lo], s1 = a.cu_seqlens[lo + 1];
-        tok0 = (long)s0 + 64L * c;
-        clen = min(64, s1 - (int)tok0);
-    } else {
-        const int n = cg / a.NT, c = cg % a.NT;
-        tok0 = (long)n * a.T + 64L * c;
-        clen = min(64, a.T - 64 * c);
-    }
+    const ChunkPos cp = chunk_pos(a.cu_seqlens, a.chunk_off, a.n_seq, a.T, a.NT, cg);
+    const long tok0 = cp.tok0;
+    const int clen = cp.clen;
     const size_t kq_stride = (size_t)a.H * DK, v_stride = (size_t)a.H * a.dv_dim;
     const char* rec = a.rec + (size_t)blockIdx.x * bwd_record_bytes<E>();
     {

@@ -154,18 +154,9 @@ __global__ __launch_bounds__(64 * NW + 64) void bwd_sweep_bf16_kernel(BwdArgs<bf
         if (lane < 48) dma16(tc + 3 * C::TPB, lane * 16, st + C::OFF_EG);   // gamma_i | gamma_C/gamma_i | beta_i
     };
 
-    // 4x4 transposition inside each quad of lanes (see the forward kernel), then one 64-bit write: lane (r, g)
-    // ends up with row 4 g + (r & 3), columns 4 (r >> 2) .. + 3 of the wave's 16
-    auto stage_quad = [&](u32x2 ob, char* dst) {
-        const uint32_t snd = q_lo ? ob.y : ob.x;
-        const uint32_t rcv = (uint32_t)__builtin_amdgcn_mov_dpp((int)snd, 0x4E, 0xf, 0xf, true);
-        if (q_lo) ob.y = rcv; else ob.x = rcv;
-        const uint32_t px = (uint32_t)__builtin_amdgcn_mov_dpp((int)ob.x, 0xB1, 0xf, 0xf, true);
-        const uint32_t py = (uint32_t)__builtin_amdgcn_mov_dpp((int)ob.y, 0xB1, 0xf, 0xf, true);
-        ob.x = __builtin_amdgcn_perm(px, ob.x, psel);
-        ob.y = __builtin_amdgcn_perm(py, ob.y, psel);
-        *reinterpret_cast<u32x2*>(dst) = ob;
-    };
+    // 4x4 transposition inside each quad of lanes, then one 64-bit write: lane (r, g) ends up with row 4 g + (r & 3),
+    // columns 4 (r >> 2) .. + 3 of the wave's 16
+    auto stage_quad = [&](u32x2 ob, char* dst) { *reinterpret_cast<u32x2*>(dst) = quad_transpose4x4(ob, q_lo, psel); };
 
     // ---- one chunk for this wave's 16 columns -----------------------------------------------------------
     auto compute = [&](const char* st, char* ost, int c) {
@@ -427,19 +418,9 @@ __global__ __launch_bounds__(256, 2) void bwd_assemble_bf16_kernel(BwdArgs<bf16_
 
     const int h = blockIdx.x % a.H;
     const int cg = blockIdx.x / a.H;
-    long tok0; int clen;
-    if (a.cu_seqlens) {
-        int lo = 0, hi = a.n_seq - 1;
-        while (lo < hi) { const int mid = (lo + hi + 1) >> 1; if (a.chunk_off[mid] <= cg) lo = mid; else hi = mid - 1; }
-        const int c = cg - a.chunk_off[lo];
-        const int s0 = a.cu_seqlens[lo], s1 = a.cu_seqlens[lo + 1];
-        tok0 = (long)s0 + 64L * c;
-        clen = min(64, s1 - (int)tok0);
-    } else {
-        const int n = cg / a.NT, c = cg % a.NT;
-        tok0 = (long)n * a.T + 64L * c;
-        clen = min(64, a.T - 64 * c);
-    }
+    const ChunkPos cp = chunk_pos(a.cu_seqlens, a.chunk_off, a.n_seq, a.T, a.NT, cg);
+    const long tok0 = cp.tok0;
+    const int clen = cp.clen;
     const size_t kq_row = (size_t)a.H * DK * 2, v_row = (size_t)a.H * a.dv_dim * 2;
     const char* rec = a.rec + (size_t)blockIdx.x * bwd_record_bytes<bf16_t>();
     {
@@ -710,16 +691,7 @@ __global__ __launch_bounds__(256, 2) void bwd_assemble_bf16_kernel(BwdArgs<bf16_
         char* sk = lds + OFF_DP;
         const bool q_lo = (r & 3) < 2;
         const uint32_t psel = (r & 1) ? 0x03020706u : 0x05040100u;
-        auto stage_quad = [&](u32x2 ob, char* dst) {
-            const uint32_t snd = q_lo ? ob.y : ob.x;
-            const uint32_t rcv = (uint32_t)__builtin_amdgcn_mov_dpp((int)snd, 0x4E, 0xf, 0xf, true);
-            if (q_lo) ob.y = rcv; else ob.x = rcv;
-            const uint32_t px = (uint32_t)__builtin_amdgcn_mov_dpp((int)ob.x, 0xB1, 0xf, 0xf, true);
-            const uint32_t py = (uint32_t)__builtin_amdgcn_mov_dpp((int)ob.y, 0xB1, 0xf, 0xf, true);
-            ob.x = __builtin_amdgcn_perm(px, ob.x, psel);
-            ob.y = __builtin_amdgcn_perm(py, ob.y, psel);
-            *reinterpret_cast<u32x2*>(dst) = ob;
-        };
+        auto stage_quad = [&](u32x2 ob, char* dst) { *reinterpret_cast<u32x2*>(dst) = quad_transpose4x4(ob, q_lo, psel); };
         // after the transposition lane (r, g) holds token row 16 wave + 4 g + r % 4, features 32 kp + 8 (r / 4) + 4 b .. + 3
         const int orow = (16 * wave + 4 * g + (r & 3)) * ORQ + 16 * (r >> 2);
 #pragma unroll

@@ -181,19 +181,9 @@ __global__ __launch_bounds__(256) void intra_kernel(IntraArgs<E> a)
     // ---- which chunk of which sequence -------------------------------------------------------
     const int h = blockIdx.x % a.H;
     const int cg = blockIdx.x / a.H;                 // global chunk index
-    long tok0; int clen;
-    if (a.cu_seqlens) {
-        int lo = 0, hi = a.n_seq - 1;                // last s with chunk_off[s] <= cg
-        while (lo < hi) { const int mid = (lo + hi + 1) >> 1; if (a.chunk_off[mid] <= cg) lo = mid; else hi = mid - 1; }
-        const int c = cg - a.chunk_off[lo];
-        const int s0 = a.cu_seqlens[lo], s1 = a.cu_seqlens[lo + 1];
-        tok0 = (long)s0 + 64L * c;
-        clen = min(64, s1 - (int)tok0);
-    } else {
-        const int n = cg / a.NT, c = cg % a.NT;
-        tok0 = (long)n * a.T + 64L * c;
-        clen = min(64, a.T - 64 * c);
-    }
+    const ChunkPos cp = chunk_pos(a.cu_seqlens, a.chunk_off, a.n_seq, a.T, a.NT, cg);
+    const long tok0 = cp.tok0;
+    const int clen = cp.clen;
 
     // ---- phase 1: K, Q -> LDS (operand order), key norms -> beta, log-decay prefix sum -> g ---
     {
@@ -377,19 +367,9 @@ __global__ __launch_bounds__(256) void intra_diag_kernel(IntraDiagArgs<E> a)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int h = blockIdx.x % a.H;
     const int cg = blockIdx.x / a.H;
-    long tok0; int clen;
-    if (a.cu_seqlens) {
-        int lo = 0, hi = a.n_seq - 1;
-        while (lo < hi) { const int mid = (lo + hi + 1) >> 1; if (a.chunk_off[mid] <= cg) lo = mid; else hi = mid - 1; }
-        const int c = cg - a.chunk_off[lo];
-        const int s0 = a.cu_seqlens[lo], s1 = a.cu_seqlens[lo + 1];
-        tok0 = (long)s0 + 64L * c;
-        clen = min(64, s1 - (int)tok0);
-    } else {
-        const int n = cg / a.NT, c = cg % a.NT;
-        tok0 = (long)n * a.T + 64L * c;
-        clen = min(64, a.T - 64 * c);
-    }
+    const ChunkPos cp = chunk_pos(a.cu_seqlens, a.chunk_off, a.n_seq, a.T, a.NT, cg);
+    const long tok0 = cp.tok0;
+    const int clen = cp.clen;
     const size_t row_stride = (size_t)a.H * DK;
     auto unpack = [](uint4 d, float (&f)[EPP]) {
         if constexpr (sizeof(E) == 2) {

@@ -317,22 +317,11 @@ __global__ __launch_bounds__(64 * NW + 64) void scan_bf16_kernel(ScanArgs<bf16_t
         }
         mma_bf16(o[2], psl[tri_pair(2, 1)], Uq[2], Uq[3]);
         mma_bf16(o[3], psl[tri_pair(3, 1)], Uq[2], Uq[3]);
-        // A quad of lanes (r = 4 q .. 4 q + 3) holds a 4x4 block of bf16: lane j rows 4 g + e (e = 0..3, packed
-        // in two dwords) of column 4 q + j.  Transposed inside the quad by two exchange steps (dwords with lane
-        // j ^ 2, halves with lane j ^ 1), each lane then owns 4 consecutive columns of one row: one 64-bit LDS
-        // write per tile instead of four 16-bit ones (a compute wave is bound by its LDS instructions).
+        // transposed 4x4 inside each quad of lanes (see quad_transpose4x4): one 64-bit LDS write per tile (a compute
+        // wave is bound by its instruction count)
 #pragma unroll
-        for (int it = 0; it < 4; ++it) {
-            u32x2 ob = to_quad(o[it]);
-            const uint32_t snd = q_lo ? ob.y : ob.x;
-            const uint32_t rcv = (uint32_t)__builtin_amdgcn_mov_dpp((int)snd, 0x4E, 0xf, 0xf, true);   // quad_perm [2,3,0,1]
-            if (q_lo) ob.y = rcv; else ob.x = rcv;
-            const uint32_t px = (uint32_t)__builtin_amdgcn_mov_dpp((int)ob.x, 0xB1, 0xf, 0xf, true);   // quad_perm [1,0,3,2]
-            const uint32_t py = (uint32_t)__builtin_amdgcn_mov_dpp((int)ob.y, 0xB1, 0xf, 0xf, true);
-            ob.x = __builtin_amdgcn_perm(px, ob.x, psel);
-            ob.y = __builtin_amdgcn_perm(py, ob.y, psel);
-            *reinterpret_cast<u32x2*>(ost + oO + 16 * it * ORB) = ob;
-        }
+        for (int it = 0; it < 4; ++it)
+            *reinterpret_cast<u32x2*>(ost + oO + 16 * it * ORB) = quad_transpose4x4(to_quad(o[it]), q_lo, psel);
     };
 
     auto write_out = [&](int c, const char* ost) {

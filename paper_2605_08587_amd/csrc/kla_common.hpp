@@ -55,6 +55,29 @@ __device__ __forceinline__ float wave_sum(float x)
     return x;
 }
 
+// Where a per-chunk workgroup works: global chunk index cg (sequences in order, chunks of 64 tokens counted from each
+// sequence's own first token) -> first token of the chunk and its length (64, or less for a ragged last chunk).
+// cu_seqlens / chunk_off (chunk_off[s] = number of chunks before sequence s) describe a packed batch; both NULL for a
+// fixed-length batch of sequences of T tokens (NT chunks each).
+struct ChunkPos { long tok0; int clen; };
+__device__ __forceinline__ ChunkPos chunk_pos(const int* cu_seqlens, const int* chunk_off, int n_seq, int T, int NT, int cg)
+{
+    ChunkPos p;
+    if (cu_seqlens) {
+        int lo = 0, hi = n_seq - 1;                  // last s with chunk_off[s] <= cg
+        while (lo < hi) { const int mid = (lo + hi + 1) >> 1; if (chunk_off[mid] <= cg) lo = mid; else hi = mid - 1; }
+        const int c = cg - chunk_off[lo];
+        const int s0 = cu_seqlens[lo], s1 = cu_seqlens[lo + 1];
+        p.tok0 = (long)s0 + 64L * c;
+        p.clen = min(64, s1 - (int)p.tok0);
+    } else {
+        const int n = cg / NT, c = cg % NT;
+        p.tok0 = (long)n * T + 64L * c;
+        p.clen = min(64, T - 64 * c);
+    }
+    return p;
+}
+
 // Kaczmarz coefficient of eq. (3); a zero denominator (zero key, eps = 0) gives beta = 0
 // because the write beta k e^T is then zero for every finite beta.
 __device__ __forceinline__ float kaczmarz_beta(float eta, float knorm2, float eps)
