@@ -162,3 +162,16 @@ def test_bwd_determinism(kla):
     b = _run(kla, d, d_o, g)
     for n in NAMES:
         assert np.array_equal(a[n], b[n]), n
+
+
+def test_bwd_no_tokens(kla):
+    """Sequences without tokens: the state passes through, so dh0 = d_hT and nothing else is written."""
+    H, dk, dv = 2, 128, 128
+    z = lambda *s: torch.zeros(s, dtype=torch.bfloat16, device="cuda")
+    g = torch.randn((3, H, dk, dv), generator=torch.Generator().manual_seed(1)).cuda()
+    cu = torch.zeros(4, dtype=torch.int32, device="cuda")
+    out = kla.kla_chunk_bwd(z(1, 0, H, dk), z(1, 0, H, dk), z(1, 0, H, dv), torch.zeros((1, 0, H), device="cuda"),
+                            torch.zeros((1, 0, H), device="cuda"), 1e-6, z(1, 0, H, dv), h0=torch.zeros_like(g), d_hT=g,
+                            cu_seqlens=cu)
+    torch.cuda.synchronize()
+    assert torch.equal(out["dh0"], g)

@@ -129,3 +129,14 @@ def test_diag_prefill_then_decode(kla):
                                   lad[:, T - 1].contiguous(), eta[:, T - 1].contiguous(), d["eps"], h1)
     assert token_oracle.rel_err(od.float().cpu().numpy(), o[:, T - 1].float().cpu().numpy()) <= 2e-2
     assert token_oracle.rel_err(h1.cpu().numpy(), hT.cpu().numpy()) <= 1e-2
+
+
+def test_diag_no_tokens(kla):
+    """A batch without tokens: the final state is the initial state."""
+    H, dk, dv = 2, 64, 128
+    z = lambda *s: torch.zeros(s, dtype=torch.bfloat16, device="cuda")
+    h0 = torch.randn((2, H, dk, dv), generator=torch.Generator().manual_seed(2)).cuda()
+    o, hT = kla.kla_chunk_fwd_diag(z(2, 0, H, dk), z(2, 0, H, dk), z(2, 0, H, dv), torch.zeros((2, 0, H, dk), device="cuda"),
+                                   torch.zeros((2, 0, H), device="cuda"), 1e-6, h0=h0)
+    torch.cuda.synchronize()
+    assert o.shape[1] == 0 and torch.equal(hT, h0)
