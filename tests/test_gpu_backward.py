@@ -175,3 +175,12 @@ def test_bwd_no_tokens(kla):
                             cu_seqlens=cu)
     torch.cuda.synchronize()
     assert torch.equal(out["dh0"], g)
+
+
+def test_bwd_config5_sampled(kla):
+    """Config 5 at full size (16 packed sequences, H = 16, d_v = 256, per-sequence h0); the oracle runs on 6 sampled
+    (sequence, head) units, the longest and the shortest sequence among them."""
+    d = kla_inputs.config(5)
+    lens = (d["cu_seqlens"][1:] - d["cu_seqlens"][:-1]).numpy()
+    units = sorted({(int(np.argmax(lens)), 0), (int(np.argmin(lens)), 15), (3, 7), (9, 2), (12, 11), (5, 5)})
+    _check(kla, d, seed=11, units=units)
