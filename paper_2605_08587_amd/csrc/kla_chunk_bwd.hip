@@ -2,7 +2,7 @@
 // log_alpha, eta and h0.  The paper states the forward map only (Algorithm 1; eqs. (6)-(8)); what follows is
 // those equations differentiated per chunk, including the dependence of beta on k through eq. (3).
 //
-// Per chunk, with M = (I + L)^{-1}, B = diag(beta), X = V - D_gamma K S (S the incoming state), U = M B X,
+// Per chunk, with M = (I + L)^{-1}, B = diag(beta), X = V - D_gamma K S (S the incoming state), U = M B X = T' X,
 // P = A o Q K^T, and dS' the gradient of the state the chunk hands on:
 //     dU = P^T dO + diag(gamma_C/gamma_i) K dS'        Y = M^T dU        dV = dX = B Y
 //     dS = gamma_C dS' + Q^T D_gamma dO - K^T D_gamma dX                          (gradient of the incoming state)
@@ -95,7 +95,7 @@ __global__ __launch_bounds__(64 * NW) void bwd_states_kernel(BwdArgs<E> a)
     constexpr int NTH = C::NTH, KB = C::KB, KP = C::KP, SLW = C::SLW, PPR = C::PPR, EPP = C::EPP, VPP = C::VPP;
     typedef typename QuadT<E>::type Quad;
     // K rows | K transposed | T' | V slice | gamma_i | gamma_C/gamma_i | beta_i
-    constexpr int OFF_KT = C::OPB, OFF_M = 2 * C::OPB, OFF_V = OFF_M + C::TPB, OFF_VEC = OFF_V + C::VB, LDS = OFF_VEC + 768;
+    constexpr int OFF_KT = C::OPB, OFF_T = 2 * C::OPB, OFF_V = OFF_T + C::TPB, OFF_VEC = OFF_V + C::VB, LDS = OFF_VEC + 768;
     __shared__ __attribute__((aligned(16))) char lds[LDS];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -173,7 +173,7 @@ __global__ __launch_bounds__(64 * NW) void bwd_states_kernel(BwdArgs<E> a)
 #pragma unroll
         for (int it = 0; it < C::UT; ++it) {
             const int i = tid + NTH * it;
-            if (C::TP16 % NTH == 0 || i < C::TP16) reinterpret_cast<uint4*>(lds + OFF_M)[i] = pm[it];
+            if (C::TP16 % NTH == 0 || i < C::TP16) reinterpret_cast<uint4*>(lds + OFF_T)[i] = pm[it];
         }
         if (tid < 64) {
 #pragma unroll
@@ -192,7 +192,7 @@ __global__ __launch_bounds__(64 * NW) void bwd_states_kernel(BwdArgs<E> a)
 
         const E* Krq = reinterpret_cast<const E*>(lds);
         const E* Ktq = reinterpret_cast<const E*>(lds + OFF_KT);
-        const E* Mrq = reinterpret_cast<const E*>(lds + OFF_M);
+        const E* Trq = reinterpret_cast<const E*>(lds + OFF_T);     // T' = (I + L)^{-1} B
         const E* Vtq = reinterpret_cast<const E*>(lds + OFF_V);
         const float* eg = reinterpret_cast<const float*>(lds + OFF_VEC);
         const float* ed = eg + 64;
@@ -223,7 +223,7 @@ __global__ __launch_bounds__(64 * NW) void bwd_states_kernel(BwdArgs<E> a)
         for (int it = 0; it < 4; ++it) {
             floatx4 u = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int jp = 0; jp <= (it >> 1); ++jp) mma32<E>(u, load_slot(Mrq, tri_pair(it, jp), lane), Xq[2 * jp], Xq[2 * jp + 1]);
+            for (int jp = 0; jp <= (it >> 1); ++jp) mma32<E>(u, load_slot(Trq, tri_pair(it, jp), lane), Xq[2 * jp], Xq[2 * jp + 1]);
             store_rows<E>(ub, v_stride, u, it, g, clen);
             Udq[it] = acc_to_quad<E>(u * ld_acc4(ed + 16 * it + 4 * g));
         }
