@@ -249,6 +249,24 @@ def main():
                   "same_state_GBps": round(bytes256 / (ms_graph * 1e-3) / 1e9, 1)}
         if graph_error:
             decode["graph_error"] = graph_error
+        else:
+            # the same steps with per-channel decay gates (kla_decode_step_diag), rotating over the 24 state sets
+            gen = torch.Generator().manual_seed(4)
+            lad = (-torch.nn.functional.softplus(torch.randn((steps, B, Hd, dd["dk"]), generator=gen))).cuda()
+
+            def run256_diag(states):
+                ns = len(states)
+                for t in range(steps):
+                    kla.kla_decode_step_diag(g["q"][t], g["k"][t], g["v"][t], lad[t], g["eta"][t], dd["eps"], states[t % ns], out=od)
+
+            run256_diag(many)
+            graph_d = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph_d):
+                run256_diag(many)
+            graph_d.replay()
+            ms_diag = _events(torch, graph_d.replay, reps)
+            decode["diagonal_gating_us_per_step"] = round(ms_diag * 1e3 / steps, 3)
+            del lad
 
     # ------------------------------------------------------------------ CPU oracle beside it
     cpu = None
