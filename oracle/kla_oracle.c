@@ -204,14 +204,16 @@ static double kla_token_state(const double *S, const float *k, const float *v, d
  *   dlog_alpha, deta  [n_tokens_total, H]     double
  *   dh0               [dk, dv] double for this unit (out), may be NULL
  * The states are recomputed from checkpoints kept every 64 tokens, so memory stays at
- * (len/64 + 65) states.  gdn_beta: beta_t = eta_t (no dependence on k).  Returns 0, or -1 if memory could not be
+ * (len/64 + 65) states.  normalize_q: the read-out is o_t = S_t^T q_t / ||q_t||.  gdn_beta: beta_t = eta_t (no
+ * dependence on k).  Returns 0, or -1 if memory could not be
  * allocated.
  */
 int kla_oracle_sequence_bwd_opts(const float *q, const float *k, const float *v,
                                  const double *log_alpha, const double *eta, double eps,
                                  const double *h0, const double *d_o, const double *d_hT,
                                  double *dq, double *dk_, double *dv_, double *dlog_alpha, double *deta,
-                                 double *dh0, long t0, long len, int h, int H, int dk, int dv, int gdn_beta)
+                                 double *dh0, long t0, long len, int h, int H, int dk, int dv,
+                                 int normalize_q, int gdn_beta)
 {
     enum { SEG = 64 };
     const size_t sz = (size_t)dk * dv;
@@ -258,14 +260,28 @@ int kla_oracle_sequence_bwd_opts(const float *q, const float *k, const float *v,
             const double *go = d_o + th * dv;
             const double *Sprev = st + sz * (size_t)(t - a), *Scur = st + sz * (size_t)(t - a + 1);
             double *gq = dq + th * dk, *gk = dk_ + th * dk, *gv = dv_ + th * dv;
-            /* line 5: o = S^T q */
+            /* line 5: o = S^T q, or o = S^T q / ||q|| (a zero query: o = 0, nothing flows back).
+             * With r = S^T q and n = ||q||:  dr = go / n,  dn = -<go, r> / n^2,  dq = S dr + dn q / n. */
+            double rn = 1.0, dn_over_n = 0.0;
+            if (normalize_q) {
+                double nq = 0.0, gr = 0.0;
+                for (i = 0; i < dk; ++i) nq += (double)qt[i] * (double)qt[i];
+                nq = sqrt(nq);
+                rn = (nq == 0.0) ? 0.0 : 1.0 / nq;
+                for (j = 0; j < dv; ++j) {
+                    double r = 0.0;
+                    for (i = 0; i < dk; ++i) r += Scur[(size_t)i * dv + j] * (double)qt[i];
+                    gr += go[j] * r;
+                }
+                dn_over_n = -gr * rn * rn * rn;
+            }
             for (i = 0; i < dk; ++i) {
                 double acc = 0.0;
                 for (j = 0; j < dv; ++j) {
-                    acc += Scur[(size_t)i * dv + j] * go[j];
-                    dS[(size_t)i * dv + j] += (double)qt[i] * go[j];
+                    acc += Scur[(size_t)i * dv + j] * go[j] * rn;
+                    dS[(size_t)i * dv + j] += (double)qt[i] * go[j] * rn;
                 }
-                gq[i] = acc;
+                gq[i] = acc + dn_over_n * (double)qt[i];
             }
             /* the forward quantities of this token again: decayed state, residual, beta */
             const double beta = kla_token_state(Sprev, kt, vt, log_alpha[th], eta[th], eps, dk, dv, St, e, NULL, &inv_den, gdn_beta);
@@ -387,5 +403,5 @@ int kla_oracle_sequence_bwd(const float *q, const float *k, const float *v,
                             double *dh0, long t0, long len, int h, int H, int dk, int dv)
 {
     return kla_oracle_sequence_bwd_opts(q, k, v, log_alpha, eta, eps, h0, d_o, d_hT, dq, dk_, dv_, dlog_alpha, deta, dh0,
-                                        t0, len, h, H, dk, dv, 0);
+                                        t0, len, h, H, dk, dv, 0, 0);
 }

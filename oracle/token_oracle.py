@@ -62,7 +62,8 @@ def _load():
             lib.kla_oracle_sequence_bwd_opts.argtypes = [fp, fp, fp, dp, dp, ctypes.c_double, dp, dp, dp,
                                                     dp, dp, dp, dp, dp, dp,
                                                     ctypes.c_long, ctypes.c_long, ctypes.c_int,
-                                                    ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int]
+                                                    ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                                    ctypes.c_int]
             _lib = lib
     return _lib
 
@@ -199,12 +200,12 @@ def kla_decode_diag(q, k, v, log_alpha, eta, eps, S, threads=None):
 
 
 def kla_recurrent_bwd(q, k, v, log_alpha, eta, eps, d_o, h0=None, d_hT=None, cu_seqlens=None, threads=None,
-                      units=None, gdn_beta=False):
-    """Gradient of L = sum <d_o, o> + sum <d_hT, hT> of kla_recurrent (no options) with respect to its inputs.
+                      units=None, gdn_beta=False, normalize_q=False):
+    """Gradient of L = sum <d_o, o> + sum <d_hT, hT> of kla_recurrent with respect to its inputs.
 
     Shapes as in kla_recurrent; d_o: [N, T, H, dv]; d_hT: [n_seq, H, dk, dv] or None (zeros).
     `units`, if given, restricts the work to those (sequence, head) pairs; other rows stay zero.
-    gdn_beta: gradient of the recurrence with beta_t = eta_t.
+    gdn_beta: gradient of the recurrence with beta_t = eta_t; normalize_q: of the read-out divided by ||q_t||.
     Returns a dict with dq, dk, dv, dlog_alpha, deta, dh0 (float64, shapes of the corresponding inputs).
     """
     lib = _load()
@@ -235,7 +236,7 @@ def kla_recurrent_bwd(q, k, v, log_alpha, eta, eps, d_o, h0=None, d_hT=None, cu_
                                          None if ghT is None else _dp(ghT, off),
                                          _dp(out["dq"]), _dp(out["dk"]), _dp(out["dv"]), _dp(out["dlog_alpha"]),
                                          _dp(out["deta"]), _dp(out["dh0"], off),
-                                         starts[s], lens[s], h, H, dk, dv, int(gdn_beta))
+                                         starts[s], lens[s], h, H, dk, dv, int(normalize_q), int(gdn_beta))
         if rc != 0:
             raise MemoryError("oracle scratch allocation failed")
 

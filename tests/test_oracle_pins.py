@@ -594,3 +594,43 @@ def test_gradient_gdn_beta_central_differences():
             args_m[{"k": "kk", "eta": "ee", "q": "qq"}[name]] = minus
             fd = (loss(**args_p) - loss(**args_m)) / (2 * h)
             assert abs(fd - g[key][idx]) <= 2e-5 * scale + 1e-8, (name, idx, fd, g[key][idx])
+
+
+def test_gradient_normalize_q_central_differences_and_scale_invariance():
+    """Read-out o_t = S_t^T q_t / ||q_t|| (Sec. 3.3): the gradient oracle's option against central differences
+    of the forward oracle's option; o_t does not change when q_t is scaled by c > 0, so <q_t, dq_t> = 0 (Euler);
+    a zero query has o_t = 0 and takes no gradient, and the other gradients equal those of the plain read-out
+    fed with d_o / ||q||."""
+    rng = RNG(47)
+    T, H, dk, dv, eps = 70, 2, 4, 3, 1e-3
+    q, k, v, la, eta, S0 = _rand_problem(rng, T, H, dk, dv)
+    q, k, v = ((np.round(x * 64) / 64).astype(np.float32) for x in (q, k, v))
+    q[0, 5, 1] = 0.0
+    go = rng.standard_normal((1, T, H, dv))
+    ghT = rng.standard_normal((1, H, dk, dv))
+    g = token_oracle.kla_recurrent_bwd(q, k, v, la, eta, eps, go, h0=S0, d_hT=ghT, normalize_q=True)
+    assert np.all(g["dq"][0, 5, 1] == 0.0)
+    assert np.max(np.abs(np.sum(g["dq"] * q, axis=-1))) <= 1e-12 * np.max(np.abs(g["dq"]))
+    nq = np.linalg.norm(q.astype(np.float64), axis=-1, keepdims=True)
+    rn = np.where(nq == 0.0, 0.0, 1.0 / np.where(nq == 0.0, 1.0, nq))
+    gp = token_oracle.kla_recurrent_bwd(q, k, v, la, eta, eps, go * rn, h0=S0, d_hT=ghT)
+    for key in ("dk", "dv", "dlog_alpha", "deta", "dh0"):
+        assert np.max(np.abs(g[key] - gp[key])) <= 1e-12 * np.max(np.abs(gp[key])), key
+
+    def loss(qq, kk, vv, ll, ee):
+        o, hT, _ = token_oracle.kla_recurrent(qq, kk, vv, ll, ee, eps, h0=S0, threads=1, normalize_q=True)
+        return float(np.sum(o * go) + np.sum(hT * ghT))
+    base = dict(qq=q, kk=k, vv=v, ll=la, ee=eta)
+    for name, key in (("qq", "dq"), ("kk", "dk"), ("vv", "dv"), ("ll", "dlog_alpha"), ("ee", "deta")):
+        arr = base[name]
+        h = 2.0 ** -9 if arr.dtype == np.float32 else 1e-5
+        scale = np.max(np.abs(g[key]))
+        for fi in rng.choice(arr.size, size=6, replace=False):
+            idx = np.unravel_index(fi, arr.shape)
+            if name == "qq" and not np.any(q[idx[:-1]]):
+                continue
+            plus, minus = arr.copy(), arr.copy()
+            plus[idx] += h
+            minus[idx] -= h
+            fd = (loss(**{**base, name: plus}) - loss(**{**base, name: minus})) / (2 * h)
+            assert abs(fd - g[key][idx]) <= 5e-5 * scale + 1e-8, (name, idx, fd, g[key][idx])
