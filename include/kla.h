@@ -168,10 +168,12 @@ int kla_chunk_bwd(const void *q, const void *k, const void *v,
                   void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
- * kla_chunk_bwd with options: the backward of kla_chunk_fwd_opts(..., opts).  Only KLA_OPT_GDN_BETA is taken
- * (beta_t = eta_t: d eta = d beta and dk loses its term through the coefficient); KLA_OPT_NORMALIZE_Q is
- * KLA_ERR_SHAPE - that read-out equals the plain one on q / ||q||, so a caller can normalise q itself and apply the
- * chain rule to dq.  kla_chunk_bwd(...) is kla_chunk_bwd_opts(..., 0).  Same workspace.
+ * kla_chunk_bwd with options: the backward of kla_chunk_fwd_opts(..., opts), same option bits.
+ *   KLA_OPT_GDN_BETA     beta_t = eta_t: d eta = d beta and dk loses its term through the coefficient.
+ *   KLA_OPT_NORMALIZE_Q  d_o is the gradient of o_t = S_t^T q_t / ||q_t|| (Sec. 3.3); dq is the gradient with respect to
+ *                        the stored q (orthogonal to q_t, since o_t does not depend on the length of q_t), 0 for a zero
+ *                        query.
+ * kla_chunk_bwd(...) is kla_chunk_bwd_opts(..., 0).  Same workspace.
  */
 int kla_chunk_bwd_opts(const void *q, const void *k, const void *v,
                        const float *log_alpha, const float *eta, float eps,

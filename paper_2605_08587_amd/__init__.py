@@ -204,9 +204,9 @@ def kla_chunk_bwd_workspace_bytes(N, T, H, dk, dv, dtype, cu_seqlens=None, chunk
 
 
 def kla_chunk_bwd(q, k, v, log_alpha, eta, eps, d_o, h0=None, d_hT=None, cu_seqlens=None, want_dh0=True,
-                  workspace=None, out=None, chunk=64, gdn_beta=False):
-    """Backward of kla_chunk_fwd: gradients of sum <d_o, o> + sum <d_hT, hT>.  gdn_beta: of the forward with
-    beta_t = eta_t (kla_chunk_bwd_opts of the C ABI; the read-out normalisation has no backward).
+                  workspace=None, out=None, chunk=64, gdn_beta=False, normalize_q=False):
+    """Backward of kla_chunk_fwd: gradients of sum <d_o, o> + sum <d_hT, hT>.  gdn_beta, normalize_q: of the forward
+    with the same options (kla_chunk_bwd_opts of the C ABI).
 
     d_o [N,T,H,dv] in the dtype of q; d_hT [n_states,H,dk,dv] fp32 or None (zeros).
     Returns a dict: dq, dk, dv (dtype of q), dlog_alpha, deta (fp32 [N,T,H]), dh0 (fp32, or None).
@@ -235,7 +235,8 @@ def kla_chunk_bwd(q, k, v, log_alpha, eta, eps, d_o, h0=None, d_hT=None, cu_seql
             _ptr(d_hT), _ptr(out["dq"]), _ptr(out["dk"]), _ptr(out["dv"]), _ptr(out["dlog_alpha"]),
             _ptr(out["deta"]), _ptr(out["dh0"]), _ptr(cu_seqlens), cu_hp, n_seq, N, T, H, dk, dv, chunk,
             dt, _ptr(workspace), workspace.numel() * workspace.element_size(), _stream())
-    rc = lib().kla_chunk_bwd_opts(*args, KLA_OPT_GDN_BETA) if gdn_beta else lib().kla_chunk_bwd(*args)
+    opts = _opts(normalize_q, gdn_beta)
+    rc = lib().kla_chunk_bwd_opts(*args, opts) if opts else lib().kla_chunk_bwd(*args)
     if rc != 0:
         raise KlaError(rc, "kla_chunk_bwd")
     return out

@@ -193,7 +193,7 @@ int make_bwd_plan(int N, int T, int H, int dk, int dv, int chunk, int dt, const 
     const size_t states = ch * dk * dv * elem_bytes(dt);          // checkpoints are kept in the element type
     const size_t rows = (size_t)N * T * H * dv * elem_bytes(dt);
     p->off_rec = 0;                                              // [T' | M^T | P^T | four vectors] per chunk-head
-    p->off_C = round256(ch * (3 * half + 1024));
+    p->off_C = round256(ch * (3 * half + 1280));
     p->off_S = round256(p->off_C + (size_t)(n_seq + 1) * sizeof(int32_t));
     p->off_dS = round256(p->off_S + states);
     p->off_X = round256(p->off_dS + states);
@@ -412,7 +412,7 @@ int kla_chunk_bwd_opts(const void* q, const void* k, const void* v, const float*
                        const int32_t* cu_seqlens_host, int n_seq, int N, int T, int H, int dk, int dv, int chunk,
                        kla_dtype dt, void* workspace, size_t workspace_bytes, void* hip_stream, unsigned opts)
 {
-    if (opts & ~(unsigned)KLA_OPT_GDN_BETA) return KLA_ERR_SHAPE;     // the read-out normalisation has no backward here
+    if (opts & ~(unsigned)(KLA_OPT_NORMALIZE_Q | KLA_OPT_GDN_BETA)) return KLA_ERR_SHAPE;
     BwdPlan pl;
     const int rc = make_bwd_plan(N, T, H, dk, dv, chunk, (int)dt, cu_seqlens_host, n_seq, &pl);
     if (rc != KLA_OK) return rc;

@@ -248,7 +248,7 @@ __global__ __launch_bounds__(64 * NW) void bwd_scan_kernel(BwdArgs<E> a)
     typedef typename QuadT<E>::type Quad;
     // K rows | K transposed | Q transposed | M^T | P^T | dO slice | gamma_i | gamma_C/gamma_i | beta_i
     constexpr int OFF_KT = C::OPB, OFF_QT = 2 * C::OPB, OFF_MT = 3 * C::OPB, OFF_PT = OFF_MT + C::TPB,
-                  OFF_DO = OFF_PT + C::TPB, OFF_VEC = OFF_DO + C::VB, LDS = OFF_VEC + 768;
+                  OFF_DO = OFF_PT + C::TPB, OFF_VEC = OFF_DO + C::VB, LDS = OFF_VEC + 1024;
     static_assert(LDS <= 160 * 1024, "LDS budget of a gfx950 CU");
     __shared__ __attribute__((aligned(16))) char lds[LDS];
 
@@ -267,7 +267,7 @@ __global__ __launch_bounds__(64 * NW) void bwd_scan_kernel(BwdArgs<E> a)
             dS[kt][e] = a.d_hT ? a.d_hT[((size_t)p.chain * DK + 16 * kt + 4 * g + e) * a.dv_dim + col] : 0.f;
 
     uint4 pk[C::UK][4], pq[C::UK][4], pd[C::UV][4], pm[C::UT], pp[C::UT];
-    float pvec[3];
+    float pvec[4];                                   // gamma_i | gamma_C/gamma_i | beta_i | 1/||q_i||
     auto fetch = [&](int c) {
         const long tok0 = p.t0 + 64L * c;
         const int clen = min(64, p.len - 64 * c);
@@ -308,6 +308,7 @@ __global__ __launch_bounds__(64 * NW) void bwd_scan_kernel(BwdArgs<E> a)
         const float* vec = reinterpret_cast<const float*>(rec + 3 * ws_half_bytes<E>());
 #pragma unroll
         for (int x = 0; x < 3; ++x) pvec[x] = vec[64 * x + lane];
+        pvec[3] = vec[256 + lane];
     };
     auto stash = [&]() {
         E* Krq = reinterpret_cast<E*>(lds);
@@ -340,7 +341,7 @@ __global__ __launch_bounds__(64 * NW) void bwd_scan_kernel(BwdArgs<E> a)
         }
         if (tid < 64) {
 #pragma unroll
-            for (int x = 0; x < 3; ++x) reinterpret_cast<float*>(lds + OFF_VEC)[64 * x + tid] = pvec[x];
+            for (int x = 0; x < 4; ++x) reinterpret_cast<float*>(lds + OFF_VEC)[64 * x + tid] = pvec[x];
         }
     };
 
@@ -362,6 +363,7 @@ __global__ __launch_bounds__(64 * NW) void bwd_scan_kernel(BwdArgs<E> a)
         const float* eg = reinterpret_cast<const float*>(lds + OFF_VEC);
         const float* ed = eg + 64;
         const float* be = eg + 128;
+        const float* rq = eg + 192;
 
         // the gradient of the state this chunk hands on (transposed, like the state checkpoints)
         E* dck = a.ds_chk + (((size_t)(p.ch0 + c) * a.H + h) * a.dv_dim + col) * DK;
@@ -406,7 +408,7 @@ __global__ __launch_bounds__(64 * NW) void bwd_scan_kernel(BwdArgs<E> a)
             const floatx4 dx = y * ld_acc4(be + 16 * it + 4 * g);
             store_rows<E>(vb, v_stride, dx, it, g, clen);
             const floatx4 egv = ld_acc4(eg + 16 * it + 4 * g);
-            gdOq[it] = acc_to_quad<E>(egv * dOa[it]);
+            gdOq[it] = acc_to_quad<E>(egv * ld_acc4(rq + 16 * it + 4 * g) * dOa[it]);   // D_gamma dO / ||q||
             gdXq[it] = acc_to_quad<E>(-(egv * dx));
         }
         // dS = gamma_C dS' + Q^T D_gamma dO - K^T D_gamma dX
@@ -524,8 +526,8 @@ __global__ __launch_bounds__(256, 2) void bwd_assemble_kernel(BwdArgs<E> a)
     constexpr int PH2 = 2 * OPB + 2 * MB;
     constexpr int BIG = PH1 > PH2 ? PH1 : PH2;
     __shared__ __attribute__((aligned(16))) char lds[BIG];
-    __shared__ __attribute__((aligned(16))) float eg_s[64], ed_s[64], beta_s[64], invden_s[64], g_s[64], yx_s[64], dg_s[64],
-        dbeta_s[64];
+    __shared__ __attribute__((aligned(16))) float eg_s[64], ed_s[64], beta_s[64], invden_s[64], rq_s[64], g_s[64], yx_s[64],
+        dg_s[64], dbeta_s[64];
     __shared__ float red_s[8];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -543,6 +545,9 @@ __global__ __launch_bounds__(256, 2) void bwd_assemble_kernel(BwdArgs<E> a)
         const float* vec = reinterpret_cast<const float*>(rec + 3 * ws_half_bytes<E>());
         float* dst = wave == 0 ? eg_s : (wave == 1 ? ed_s : (wave == 2 ? beta_s : invden_s));
         dst[lane] = vec[tid];
+        // Normalised read-out (Sec. 3.3): the rows of dO are scaled by 1/||q_i|| wherever they meet U or S, which makes
+        // dQ' = diag(1/||q||) dL/d(q/||q||); dq_i = dQ'_i - (q_i . dQ'_i) q_i / ||q_i||^2 at the end.
+        if (wave == 1) rq_s[lane] = vec[256 + lane];
         if (wave == 0) g_s[lane] = lane < clen ? a.log_alpha[(size_t)(tok0 + lane) * a.H + h] : 0.f;
     }
     __syncthreads();
@@ -625,8 +630,9 @@ __global__ __launch_bounds__(256, 2) void bwd_assemble_kernel(BwdArgs<E> a)
     {   // D_gamma dO S^T,  -D_gamma dX S^T (dX = B Y),  diag(gamma_C/gamma_i) U dS'^T
         const floatx4 egv = ld_acc4(eg_s + 16 * wave + 4 * g), edv = ld_acc4(ed_s + 16 * wave + 4 * g);
         const floatx4 ngb = -(egv * ld_acc4(beta_s + 16 * wave + 4 * g));
+        const floatx4 egq = egv * ld_acc4(rq_s + 16 * wave + 4 * g);
 #pragma unroll
-        for (int ct = 0; ct < KB; ++ct) { dQ[ct] = dQ[ct] * egv; dKr[ct] = dKr[ct] * ngb; dKw[ct] = dKw[ct] * edv; }
+        for (int ct = 0; ct < KB; ++ct) { dQ[ct] = dQ[ct] * egq; dKr[ct] = dKr[ct] * ngb; dKw[ct] = dKw[ct] * edv; }
     }
     // Y_i . X_i: the 8 threads of a row are neighbours
 #pragma unroll
@@ -670,7 +676,7 @@ __global__ __launch_bounds__(256, 2) void bwd_assemble_kernel(BwdArgs<E> a)
             for (int e = 0; e < 4; ++e) {
                 const int i = 16 * wave + 4 * g + e;
                 const float dec = (jt <= wave && j <= i) ? expf(g_s[i] - gj) : 0.f;
-                E1[i * kLdc + j] = dec * dP[jt][e];
+                E1[i * kLdc + j] = dec * rq_s[i] * dP[jt][e];
                 Dp[i * kLdc + j] = (j < i) ? -dec * N1[jt][e] : 0.f;
             }
         });
@@ -722,7 +728,7 @@ __global__ __launch_bounds__(256, 2) void bwd_assemble_kernel(BwdArgs<E> a)
     });
 
     // ---- rows: dbeta, dg, the beta term of dK; outputs ---------------------------------------------
-    float dbr[4] = {0.f, 0.f, 0.f, 0.f}, dgr[4] = {0.f, 0.f, 0.f, 0.f};
+    float dbr[4] = {0.f, 0.f, 0.f, 0.f}, dgr[4] = {0.f, 0.f, 0.f, 0.f}, dqr[4] = {0.f, 0.f, 0.f, 0.f};
     floatx4 kk[KB];
     const floatx4 bev = ld_acc4(beta_s + 16 * wave + 4 * g);
 #pragma unroll
@@ -733,16 +739,19 @@ __global__ __launch_bounds__(256, 2) void bwd_assemble_kernel(BwdArgs<E> a)
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             dbr[e] += E2[ct][e] * kk[ct][e];
-            dgr[e] += dQ[ct][e] * qq[e] + (dKr[ct][e] - dKw[ct][e]) * kk[ct][e];
+            dqr[e] += dQ[ct][e] * qq[e];
+            dgr[e] += (dKr[ct][e] - dKw[ct][e]) * kk[ct][e];
         }
     }
-    floatx4 c5;                                      // -2 beta dbeta / (|k|^2 + eps) per row
+    floatx4 c5, cq;                                  // -2 beta dbeta / (|k|^2 + eps) and -(q . dQ') / ||q||^2 per row
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
         const int i = 16 * wave + 4 * g + e;
         const float db = row16_sum(dbr[e]) + yx_s[i];
-        const float dgv = row16_sum(dgr[e]);
+        const float dqv = row16_sum(dqr[e]);
+        const float dgv = row16_sum(dgr[e]) + dqv;
         if (r == 0) { dbeta_s[i] = db; dg_s[i] = dgv; }
+        cq[e] = -dqv * rq_s[i] * rq_s[i];
         c5[e] = (a.opts & kOptGdnBeta) ? 0.f : -2.f * beta_s[i] * db * invden_s[i];   // beta = eta does not depend on k
     }
     {
@@ -751,6 +760,7 @@ __global__ __launch_bounds__(256, 2) void bwd_assemble_kernel(BwdArgs<E> a)
 #pragma unroll
         for (int ct = 0; ct < KB; ++ct) {
             const floatx4 dkv = dKr[ct] + dKw[ct] + c5 * kk[ct];
+            if (a.opts & kOptNormalizeQ) dQ[ct] = dQ[ct] + cq * kacc(Qtq, ct);
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const int row = 16 * wave + 4 * g + e;

@@ -37,10 +37,10 @@ struct SweepCfg16 {
     static constexpr int NVB = 64 / RPV;
     static constexpr int TPB = kTriPairs * 64 * 16;      // bytes of one triangular operand area
     static constexpr int NTB = (REV ? 2 : 1) * TPB / 1024;   // forward: T'; backward: M^T | P^T
-    // stage: K rows | (Q rows) | T'  or  M^T | P^T | V or dO slice | gamma_i | gamma_C/gamma_i | beta_i
+    // stage: K rows | (Q rows) | T'  or  M^T | P^T | V or dO slice | gamma_i | gamma_C/gamma_i | beta_i | (1/||q_i||)
     static constexpr int OFF_Q = 64 * RB;
     static constexpr int OFF_T = (REV ? 2 : 1) * 64 * RB, OFF_P = OFF_T + TPB, OFF_V = OFF_T + (REV ? 2 : 1) * TPB,
-                         OFF_EG = OFF_V + 64 * VRW, STAGE = OFF_EG + 768;
+                         OFF_EG = OFF_V + 64 * VRW, STAGE = OFF_EG + (REV ? 1024 : 768);
     static constexpr int ORB = NW <= 2 ? 96 : 160;       // row stride of a staging tile (see the forward kernel)
     static constexpr int OSB = 64 * ORB;
     static constexpr int NST = (3 * STAGE + 4 * OSB <= 160 * 1024) ? 3 : 2;   // LDS ring depth
@@ -151,7 +151,9 @@ __global__ __launch_bounds__(64 * NW + 64) void bwd_sweep_bf16_kernel(BwdArgs<bf
             const int b = i;
             dma16(tc + (REV ? C::TPB : 0) + b * 1024, lane * 16, st + C::OFF_T + b * 1024);
         });
-        if (lane < 48) dma16(tc + 3 * C::TPB, lane * 16, st + C::OFF_EG);   // gamma_i | gamma_C/gamma_i | beta_i
+        // gamma_i | gamma_C/gamma_i | beta_i, and for the reverse sweep 1/||q_i|| (the fifth vector of the record)
+        if constexpr (REV) dma16(tc + 3 * C::TPB, lane < 48 ? lane * 16 : 1024 + (lane - 48) * 16, st + C::OFF_EG);
+        else if (lane < 48) dma16(tc + 3 * C::TPB, lane * 16, st + C::OFF_EG);
     };
 
     // 4x4 transposition inside each quad of lanes, then one 64-bit write: lane (r, g) ends up with row 4 g + (r & 3),
@@ -285,7 +287,7 @@ __global__ __launch_bounds__(64 * NW + 64) void bwd_sweep_bf16_kernel(BwdArgs<bf
                 floatx4 eg = egv[it];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) eg[e] = (16 * it + 4 * g + e < clen) ? eg[e] : 0.f;   // rows past a ragged end
-                gdOq[it] = to_quad(eg * quad_to_f(vq[it]));
+                gdOq[it] = to_quad(eg * ld_f4(pG + 768 + 64 * it) * quad_to_f(vq[it]));   // D_gamma dO / ||q||
                 gdXq[it] = to_quad(-(eg * dx));
             }
             // ---- dS = gamma_C dS' + Q^T D_gamma dO - K^T D_gamma dV
@@ -408,8 +410,8 @@ __global__ __launch_bounds__(256, 2) void bwd_assemble_bf16_kernel(BwdArgs<bf16_
     constexpr int ORQ = RB + 16;                     // row stride of the dq / dk staging tiles (over A o dP and D')
     static_assert(64 * ORQ <= MB, "staging tiles fit the fp32 matrices they replace");
     __shared__ __attribute__((aligned(1024))) char lds[BIG];
-    __shared__ __attribute__((aligned(16))) float eg_s[64], ed_s[64], beta_s[64], invden_s[64], g_s[64], yx_s[64], dg_s[64],
-        dbeta_s[64];
+    __shared__ __attribute__((aligned(16))) float eg_s[64], ed_s[64], beta_s[64], invden_s[64], rq_s[64], g_s[64], yx_s[64],
+        dg_s[64], dbeta_s[64];
     __shared__ float red_s[8];
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -423,10 +425,15 @@ __global__ __launch_bounds__(256, 2) void bwd_assemble_bf16_kernel(BwdArgs<bf16_
     const int clen = cp.clen;
     const size_t kq_row = (size_t)a.H * DK * 2, v_row = (size_t)a.H * a.dv_dim * 2;
     const char* rec = a.rec + (size_t)blockIdx.x * bwd_record_bytes<bf16_t>();
+    // With the normalised read-out (Sec. 3.3) the query that meets the state is q^ = q / ||q||.  Scaling the rows of dO
+    // by 1/||q_i|| wherever they meet U or S gives dQ' = diag(1/||q||) dL/dq^ directly, (A o dP')^T Q is what dK
+    // needs, q_i . dQ'_i is what dg needs, and dq_i = dQ'_i - (q_i . dQ'_i) q_i / ||q_i||^2 at the end.
+    const bool norm_q = (a.opts & kOptNormalizeQ) != 0;
     {
         const float* vec = reinterpret_cast<const float*>(rec + 3 * ws_half_bytes<bf16_t>());
         float* dst = wave == 0 ? eg_s : (wave == 1 ? ed_s : (wave == 2 ? beta_s : invden_s));
         dst[lane] = vec[tid];
+        if (wave == 1) rq_s[lane] = vec[256 + lane];
         if (wave == 0) g_s[lane] = lane < clen ? a.log_alpha[(size_t)(tok0 + lane) * a.H + h] : 0.f;
     }
 
@@ -566,8 +573,9 @@ __global__ __launch_bounds__(256, 2) void bwd_assemble_bf16_kernel(BwdArgs<bf16_
         const floatx4 egv = ld_f4(reinterpret_cast<const char*>(eg_s + 16 * wave + 4 * g));
         const floatx4 edv = ld_f4(reinterpret_cast<const char*>(ed_s + 16 * wave + 4 * g));
         const floatx4 ngb = -(egv * ld_f4(reinterpret_cast<const char*>(beta_s + 16 * wave + 4 * g)));
+        const floatx4 egq = egv * ld_f4(reinterpret_cast<const char*>(rq_s + 16 * wave + 4 * g));
 #pragma unroll
-        for (int ct = 0; ct < KB; ++ct) { dQ[ct] = dQ[ct] * egv; dKr[ct] = dKr[ct] * ngb; dKw[ct] = dKw[ct] * edv; }
+        for (int ct = 0; ct < KB; ++ct) { dQ[ct] = dQ[ct] * egq; dKr[ct] = dKr[ct] * ngb; dKw[ct] = dKw[ct] * edv; }
     }
     yx += __shfl_xor(yx, 1, kWave); yx += __shfl_xor(yx, 2, kWave);      // the 4 threads of a row are neighbours
     if ((tid & 3) == 0) yx_s[tid >> 2] = yx;
@@ -586,7 +594,7 @@ __global__ __launch_bounds__(256, 2) void bwd_assemble_bf16_kernel(BwdArgs<bf16_
         for (int e = 0; e < 4; ++e) {
             const int i = 16 * wave + 4 * g + e;
             const float dec = (jt <= wave && j <= i && i < clen) ? __builtin_amdgcn_exp2f(g_s[i] - gj) : 0.f;
-            E1[i * kLd + j] = dec * dP[jt][e];
+            E1[i * kLd + j] = dec * rq_s[i] * dP[jt][e];
             Dp[i * kLd + j] = (j < i) ? -dec * N1[jt][e] : 0.f;
         }
     });
@@ -658,7 +666,7 @@ __global__ __launch_bounds__(256, 2) void bwd_assemble_bf16_kernel(BwdArgs<bf16_
     });
 
     // ---- rows: dbeta, dg, the beta term of dK -----------------------------------------------------------
-    float dbr[4] = {0.f, 0.f, 0.f, 0.f}, dgr[4] = {0.f, 0.f, 0.f, 0.f};
+    float dbr[4] = {0.f, 0.f, 0.f, 0.f}, dgr[4] = {0.f, 0.f, 0.f, 0.f}, dqr[4] = {0.f, 0.f, 0.f, 0.f};
     floatx4 kk[KB];
     const floatx4 bev = ld_f4(reinterpret_cast<const char*>(beta_s + 16 * wave + 4 * g));
 #pragma unroll
@@ -669,18 +677,22 @@ __global__ __launch_bounds__(256, 2) void bwd_assemble_bf16_kernel(BwdArgs<bf16_
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             dbr[e] += E2[ct][e] * kk[ct][e];
-            dgr[e] += dQ[ct][e] * qq[e] + (dKr[ct][e] - dKw[ct][e]) * kk[ct][e];
+            dqr[e] += dQ[ct][e] * qq[e];
+            dgr[e] += (dKr[ct][e] - dKw[ct][e]) * kk[ct][e];
         }
     }
-    floatx4 c5;
+    floatx4 c5, cq;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
         const int i = 16 * wave + 4 * g + e;
-        float db = dbr[e], dgv = dgr[e];
+        float db = dbr[e], dgv = dgr[e], dqv = dqr[e];
 #pragma unroll
-        for (int off = 1; off < 16; off <<= 1) { db += __shfl_xor(db, off, kWave); dgv += __shfl_xor(dgv, off, kWave); }
+        for (int off = 1; off < 16; off <<= 1) {
+            db += __shfl_xor(db, off, kWave); dgv += __shfl_xor(dgv, off, kWave); dqv += __shfl_xor(dqv, off, kWave);
+        }
         db += yx_s[i];
-        if (r == 0) { dbeta_s[i] = db; dg_s[i] = rowmask[e] * dgv; }
+        if (r == 0) { dbeta_s[i] = db; dg_s[i] = rowmask[e] * (dgv + dqv); }
+        cq[e] = -dqv * rq_s[i] * rq_s[i];
         c5[e] = (a.opts & kOptGdnBeta) ? 0.f : -2.f * beta_s[i] * db * invden_s[i];   // beta = eta does not depend on k
     }
     __syncthreads();                                 // every wave is done with A o dP and D': they become staging tiles
@@ -697,6 +709,7 @@ __global__ __launch_bounds__(256, 2) void bwd_assemble_bf16_kernel(BwdArgs<bf16_
 #pragma unroll
         for (int ct = 0; ct < KB; ++ct) {
             const int fo = orow + 64 * (ct >> 1) + 8 * (ct & 1);
+            if (norm_q) dQ[ct] = dQ[ct] + cq * kacc(OFF_Q, ct);
             stage_quad(to_quad(dQ[ct]), sq + fo);
             stage_quad(to_quad(dKr[ct] + dKw[ct] + c5 * kk[ct]), sk + fo);
         }

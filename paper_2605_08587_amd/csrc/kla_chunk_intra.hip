@@ -249,7 +249,7 @@ __global__ __launch_bounds__(256) void intra_kernel(IntraArgs<E> a)
     if (wave == 0) {                                     // third vector of the record (and the scale itself)
         float* dec = reinterpret_cast<float*>(reinterpret_cast<char*>(a.wsT) + (size_t)blockIdx.x * REC
                                               + (BWD ? 3 : 2) * ws_half_bytes<E>());
-        if constexpr (BWD) { dec[128 + lane] = beta_s[lane]; dec[192 + lane] = invden_s[lane]; }
+        if constexpr (BWD) { dec[128 + lane] = beta_s[lane]; dec[192 + lane] = invden_s[lane]; dec[256 + lane] = rq_s[lane]; }
         else {
             dec[128 + lane] = expf(g_s[lane]) * rq_s[lane];
             a.wsG[(size_t)blockIdx.x * 128 + 64 + lane] = rq_s[lane];

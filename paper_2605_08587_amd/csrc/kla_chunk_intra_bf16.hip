@@ -229,7 +229,7 @@ __global__ __launch_bounds__(256, 3) void intra_bf16_kernel(IntraArgs<bf16_t> a)
     __syncthreads();   // K/Q tiles are dead from here on (Pm overlays them); beta_s and rq_s are complete
     if (wave == 0) {                                     // third vector of the record (and the scale itself)
         float* dec = reinterpret_cast<float*>(rec + VEC);
-        if constexpr (BWD) { dec[128 + lane] = beta_s[lane]; dec[192 + lane] = invden_s[lane]; }
+        if constexpr (BWD) { dec[128 + lane] = beta_s[lane]; dec[192 + lane] = invden_s[lane]; dec[256 + lane] = rq_s[lane]; }
         else {
             dec[128 + lane] = __builtin_amdgcn_exp2f(g_s[lane]) * rq_s[lane];
             a.wsG[(size_t)blockIdx.x * 128 + 64 + lane] = rq_s[lane];

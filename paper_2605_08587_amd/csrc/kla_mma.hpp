@@ -49,9 +49,11 @@ template <typename E> constexpr int ws_record_bytes() { return 2 * ws_half_bytes
 __host__ __device__ constexpr int tri_pair(int it, int jp) { return it < 2 ? it : 2 * it - 2 + jp; }
 // The transposes (upper triangular) keep the 6 tile-pairs with jp >= it/2, in this order.
 __host__ __device__ constexpr int triu_pair(int it, int jp) { return it < 2 ? 2 * it + jp : it + 2; }
-// Record of one chunk-head for the backward pass: [T' | M^T | P^T | gamma_i | gamma_C/gamma_i | beta_i | 1/(|k_i|^2+eps)],
-// M = (I + L)^{-1}, T' = M B; three operand halves and four vectors of 64 fp32.
-template <typename E> constexpr int bwd_record_bytes() { return 3 * ws_half_bytes<E>() + 1024; }
+// Record of one chunk-head for the backward pass:
+// [T' | M^T | P^T | gamma_i | gamma_C/gamma_i | beta_i | 1/(|k_i|^2+eps) | 1/||q_i||],
+// M = (I + L)^{-1}, T' = M B; three operand halves and five vectors of 64 fp32.  The last vector is 1 unless the
+// read-out is normalised (then P^T carries it too).
+template <typename E> constexpr int bwd_record_bytes() { return 3 * ws_half_bytes<E>() + 1280; }
 
 // ---- conversions between accumulator tiles and quads -------------------------------------
 __device__ __forceinline__ uint2 make_quad(floatx4 x, bf16_t)

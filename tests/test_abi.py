@@ -204,17 +204,17 @@ def test_chunk_bwd_validation_and_workspace():
     for dt, eb in ((kla.KLA_BF16, 2), (kla.KLA_F32, 4)):
         N, T, H, dk, dv = 3, 200, 2, 128, 256
         n_ch = N * 4 * H
-        expect = r256(n_ch * (3 * 384 * 8 * eb + 1024))
+        expect = r256(n_ch * (3 * 384 * 8 * eb + 1280))
         expect = r256(expect + 4)                              # chunk offsets of a packed batch (n_seq + 1 ints)
         expect += 2 * r256(n_ch * dk * dv * eb)                # S_c and dS'_c
         expect += 3 * r256(N * T * H * dv * eb)                # X, U, Y
         assert lib.kla_chunk_bwd_workspace_bytes(N, T, H, dk, dv, 64, dt, None, 0) == expect
     assert lib.kla_chunk_bwd_workspace_bytes(1, 64, 1, 100, 64, 64, kla.KLA_BF16, None, 0) == 0
     opt = lambda opts, **o: lib.kla_chunk_bwd_opts(*[{**base, **o}[n] for n in names], opts)
-    assert opt(kla.KLA_OPT_NORMALIZE_Q) == E_SHAPE            # no backward for the normalised read-out
     assert opt(8) == E_SHAPE
     assert opt(kla.KLA_OPT_GDN_BETA, q=None) == E_NULL
     assert opt(kla.KLA_OPT_GDN_BETA, N=0) == OK
+    assert opt(kla.KLA_OPT_GDN_BETA | kla.KLA_OPT_NORMALIZE_Q, N=0) == OK
 
 
 def test_diag_entry_points_validate():

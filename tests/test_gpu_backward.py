@@ -124,6 +124,66 @@ def test_bwd_gdn_beta_option(kla, dt):
         assert token_oracle.rel_err(got[n], ref[n]) <= TOL[dt], n
 
 
+@pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("dk,dv,T,varlen", [(128, 128, 200, False), (64, 256, 130, False), (128, 256, 300, True)])
+def test_bwd_normalize_q_option(kla, dt, dk, dv, T, varlen):
+    """o_t = S_t^T q_t / ||q_t|| (Sec. 3.3): gradients of that read-out, with one zero query (dq = 0 there) and queries
+    of very different lengths; dq is orthogonal to q."""
+    if varlen:
+        d = kla_inputs.varlen_inputs(4, 1, T, 2, dk, dv, dtype=dt, seed=380, h0_std=0.3)
+    else:
+        d = kla_inputs.chunk_inputs(2, T, 2, dk, dv, dtype=dt, seed=381, h0_std=0.3)
+    scale = torch.logspace(-1.5, 1.5, d["T"]).reshape(1, d["T"], 1, 1)
+    d["q"] = (d["q"].float() * scale).to(dt)
+    d["q"][0, 7, 1] = 0
+    d_o, g = kla_inputs.grad_inputs(d, 11)
+    got = _run(kla, d, d_o, g, normalize_q=True)
+    q, k, v = (kla_inputs.to_numpy_f32(d[x]) for x in "qkv")
+    ref = token_oracle.kla_recurrent_bwd(q, k, v, d["log_alpha"].numpy(), d["eta"].numpy(), d["eps"],
+                                         kla_inputs.to_numpy_f32(d_o), h0=d["h0"].numpy(), d_hT=g.numpy(),
+                                         cu_seqlens=None if d["cu_seqlens"] is None else d["cu_seqlens"].numpy(),
+                                         normalize_q=True)
+    assert np.all(got["dq"][0, 7, 1] == 0.0)
+    # dq spans three decades with the query lengths: compare it in units of 1/||q|| (row by row), the rest as usual
+    nq = np.linalg.norm(q.astype(np.float64), axis=-1, keepdims=True)
+    errs = {n: token_oracle.rel_err(got[n], ref[n]) for n in NAMES if n != "dq"}
+    errs["dq"] = token_oracle.rel_err(got["dq"] * nq, ref["dq"] * nq)
+    print("   rel err " + " ".join("%s=%.2e" % kv for kv in errs.items()), flush=True)
+    for n in NAMES:
+        assert errs[n] <= TOL[dt], (n, errs[n])
+    if dt == torch.float32:
+        cosq = np.sum(got["dq"] * q, -1) / (np.linalg.norm(got["dq"], axis=-1) * nq[..., 0] + 1e-30)
+        assert np.max(np.abs(cosq)) <= 1e-3
+
+
+@pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16])
+def test_bwd_both_options(kla, dt):
+    """Normalised read-out and beta_t = eta_t together."""
+    d = kla_inputs.chunk_inputs(2, 150, 2, 128, 128, dtype=dt, seed=385, h0_std=0.3)
+    d["k"] = (d["k"].float() / d["k"].float().norm(dim=-1, keepdim=True)).to(dt)
+    d_o, g = kla_inputs.grad_inputs(d, 12)
+    got = _run(kla, d, d_o, g, normalize_q=True, gdn_beta=True)
+    q, k, v = (kla_inputs.to_numpy_f32(d[x]) for x in "qkv")
+    ref = token_oracle.kla_recurrent_bwd(q, k, v, d["log_alpha"].numpy(), d["eta"].numpy(), d["eps"],
+                                         kla_inputs.to_numpy_f32(d_o), h0=d["h0"].numpy(), d_hT=g.numpy(),
+                                         normalize_q=True, gdn_beta=True)
+    for n in NAMES:
+        assert token_oracle.rel_err(got[n], ref[n]) <= TOL[dt], n
+
+
+def test_bwd_normalize_q_generic_kernels_on_bf16(kla, monkeypatch):
+    """The element-type-generic backward kernels with the normalised read-out, on bf16 inputs."""
+    monkeypatch.setenv("KLA_BWD_IMPL", "generic")
+    d = kla_inputs.chunk_inputs(2, 130, 2, 128, 128, dtype=torch.bfloat16, seed=386, h0_std=0.3)
+    d_o, g = kla_inputs.grad_inputs(d, 13)
+    got = _run(kla, d, d_o, g, normalize_q=True)
+    q, k, v = (kla_inputs.to_numpy_f32(d[x]) for x in "qkv")
+    ref = token_oracle.kla_recurrent_bwd(q, k, v, d["log_alpha"].numpy(), d["eta"].numpy(), d["eps"],
+                                         kla_inputs.to_numpy_f32(d_o), h0=d["h0"].numpy(), d_hT=g.numpy(), normalize_q=True)
+    for n in NAMES:
+        assert token_oracle.rel_err(got[n], ref[n]) <= TOL[torch.bfloat16], n
+
+
 def test_bwd_two_waves_per_workgroup(kla):
     """Enough (sequence, head) pairs for the 32-column workgroups the benchmark shape uses."""
     _check(kla, kla_inputs.chunk_inputs(16, 192, 4, 128, 128, dtype=torch.bfloat16, seed=330, h0_std=0.1), seed=3)
