@@ -99,10 +99,15 @@ def _stream():
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 
-def _host_cu(cu_seqlens):
+def _host_cu(cu_seqlens, cu_seqlens_host=None):
+    """Host copy of the sequence offsets.  Copying a device tensor synchronises: callers that must not (inside a
+    stream capture, in a serving loop) pass the host copy they already have as cu_seqlens_host."""
     if cu_seqlens is None:
         return None, None, 0
-    cu_host = cu_seqlens.detach().to("cpu", torch.int32).contiguous()
+    src = cu_seqlens if cu_seqlens_host is None else cu_seqlens_host
+    cu_host = src.detach().to("cpu", torch.int32).contiguous()
+    if cu_host.numel() != cu_seqlens.numel():
+        raise ValueError("cu_seqlens_host must hold the same offsets as cu_seqlens")
     return cu_host, ctypes.c_void_p(cu_host.data_ptr()), cu_host.numel() - 1
 
 
@@ -117,18 +122,19 @@ def _opts(normalize_q, gdn_beta) -> int:
 
 
 def kla_chunk_fwd(q, k, v, log_alpha, eta, eps, h0=None, cu_seqlens=None, want_hT=True, workspace=None,
-                  out=None, hT=None, chunk=64, _stage=None, normalize_q=False, gdn_beta=False):
+                  out=None, hT=None, chunk=64, _stage=None, normalize_q=False, gdn_beta=False, cu_seqlens_host=None):
     """Chunkwise forward.  q,k [N,T,H,dk], v [N,T,H,dv], gates [N,T,H] fp32; returns (o, hT).
 
-    cu_seqlens: int32 device tensor [n_seq+1] for a packed batch (then N == 1).
-    workspace / out / hT may be passed in to avoid allocations (e.g. inside a timed loop).
+    cu_seqlens: int32 device tensor [n_seq+1] for a packed batch (then N == 1); cu_seqlens_host: the same offsets
+    as a CPU tensor, if the caller has them (saves the device-to-host copy, which synchronises).
+    workspace / out / hT may be passed in to avoid allocations (e.g. inside a timed loop or a stream capture).
     normalize_q: o_t = S_t^T q_t / ||q_t||;  gdn_beta: beta_t = eta_t (kla_chunk_fwd_opts of the C ABI).
     """
     _dev(q, k, v, log_alpha, eta, h0, cu_seqlens, workspace, out, hT)
     N, T, H, dk = q.shape
     dv = v.shape[-1]
     dt = _dt(q)
-    cu_host, cu_hp, n_seq = _host_cu(cu_seqlens)
+    cu_host, cu_hp, n_seq = _host_cu(cu_seqlens, cu_seqlens_host)
     n_states = n_seq if n_seq > 0 else N
     need = int(lib().kla_chunk_fwd_workspace_bytes(N, T, H, dk, dv, chunk, dt, cu_hp, n_seq))
     if workspace is None:
@@ -155,7 +161,7 @@ def kla_chunk_fwd(q, k, v, log_alpha, eta, eps, h0=None, cu_seqlens=None, want_h
 
 
 def kla_chunk_fwd_diag(q, k, v, log_alpha, eta, eps, h0=None, cu_seqlens=None, want_hT=True, workspace=None,
-                       out=None, hT=None, chunk=64):
+                       out=None, hT=None, chunk=64, cu_seqlens_host=None):
     """Chunkwise forward with diagonal gating: log_alpha is [N,T,H,dk] fp32 (one decay per key channel).
     Everything else as kla_chunk_fwd; returns (o, hT)."""
     _dev(q, k, v, log_alpha, eta, h0, cu_seqlens, workspace, out, hT)
@@ -164,7 +170,7 @@ def kla_chunk_fwd_diag(q, k, v, log_alpha, eta, eps, h0=None, cu_seqlens=None, w
     if tuple(log_alpha.shape) != (N, T, H, dk):
         raise ValueError("log_alpha must be [N, T, H, dk] for diagonal gating")
     dt = _dt(q)
-    cu_host, cu_hp, n_seq = _host_cu(cu_seqlens)
+    cu_host, cu_hp, n_seq = _host_cu(cu_seqlens, cu_seqlens_host)
     n_states = n_seq if n_seq > 0 else N
     need = int(lib().kla_chunk_fwd_diag_workspace_bytes(N, T, H, dk, dv, chunk, dt, cu_hp, n_seq))
     if workspace is None:
@@ -204,7 +210,7 @@ def kla_chunk_bwd_workspace_bytes(N, T, H, dk, dv, dtype, cu_seqlens=None, chunk
 
 
 def kla_chunk_bwd(q, k, v, log_alpha, eta, eps, d_o, h0=None, d_hT=None, cu_seqlens=None, want_dh0=True,
-                  workspace=None, out=None, chunk=64, gdn_beta=False, normalize_q=False):
+                  workspace=None, out=None, chunk=64, gdn_beta=False, normalize_q=False, cu_seqlens_host=None):
     """Backward of kla_chunk_fwd: gradients of sum <d_o, o> + sum <d_hT, hT>.  gdn_beta, normalize_q: of the forward
     with the same options (kla_chunk_bwd_opts of the C ABI).
 
@@ -216,7 +222,7 @@ def kla_chunk_bwd(q, k, v, log_alpha, eta, eps, d_o, h0=None, d_hT=None, cu_seql
     N, T, H, dk = q.shape
     dv = v.shape[-1]
     dt = _dt(q)
-    cu_host, cu_hp, n_seq = _host_cu(cu_seqlens)
+    cu_host, cu_hp, n_seq = _host_cu(cu_seqlens, cu_seqlens_host)
     n_states = n_seq if n_seq > 0 else N
     need = int(lib().kla_chunk_bwd_workspace_bytes(N, T, H, dk, dv, chunk, dt, cu_hp, n_seq))
     if workspace is None:

@@ -1,0 +1,118 @@
+"""The entry points under HIP graph capture: no call allocates, synchronises or copies from the host, so a training
+step or a serving loop can record them once and replay.  Each captured call is replayed several times, with eager
+work of the same library and synchronisations in between, and every replay must reproduce the eager result bit for
+bit (the kernels are deterministic: no atomics, fixed summation order)."""
+import pytest
+import torch
+
+import kla_inputs
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def kla():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2605_08587_amd as m
+    m.lib()
+    return m
+
+
+def _capture(fn):
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        fn()                                   # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        fn()
+    return graph
+
+
+def _dev(d, names):
+    return {n: (None if d[n] is None else d[n].cuda()) for n in names}
+
+
+@pytest.mark.parametrize("case", ["fixed", "packed", "segments"])
+def test_chunk_fwd_replays(kla, case):
+    if case == "fixed":
+        d = kla_inputs.chunk_inputs(4, 300, 4, 128, 128, seed=500, h0_std=0.2)
+    elif case == "packed":
+        d = kla_inputs.varlen_inputs(5, 1, 400, 2, 128, 256, seed=501, h0_std=0.2)
+    else:                                      # one long sequence on few heads: the segment-parallel scan
+        d = kla_inputs.chunk_inputs(1, 8192, 2, 128, 128, seed=502, h0_std=0.2)
+    g = _dev(d, ("q", "k", "v", "log_alpha", "eta", "h0", "cu_seqlens"))
+    N, T, H, dk, dv = d["N"], d["T"], d["H"], d["dk"], d["dv"]
+    ws = torch.empty(max(256, kla.kla_chunk_fwd_workspace_bytes(N, T, H, dk, dv, d["dtype"], cu_seqlens=g["cu_seqlens"])),
+                     dtype=torch.uint8, device="cuda")
+    n_states = N if g["cu_seqlens"] is None else g["cu_seqlens"].numel() - 1
+    out = torch.empty((N, T, H, dv), dtype=d["dtype"], device="cuda")
+    hT = torch.empty((n_states, H, dk, dv), dtype=torch.float32, device="cuda")
+
+    def call(o=out, h=hT, w=ws):
+        kla.kla_chunk_fwd(g["q"], g["k"], g["v"], g["log_alpha"], g["eta"], d["eps"], h0=g["h0"], cu_seqlens=g["cu_seqlens"],
+                          cu_seqlens_host=d["cu_seqlens"], workspace=w, out=o, hT=h)
+    o_ref, h_ref, ws2 = torch.empty_like(out), torch.empty_like(hT), torch.empty_like(ws)
+    call(o_ref, h_ref, ws2)
+    torch.cuda.synchronize()
+    graph = _capture(call)
+    for rep in range(3):
+        out.zero_(); hT.zero_(); ws.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        call(torch.empty_like(out), torch.empty_like(hT), ws2)      # eager work of the same library between replays
+        torch.cuda.synchronize()
+        assert torch.equal(out, o_ref) and torch.equal(hT, h_ref), (case, rep)
+
+
+@pytest.mark.parametrize("dt", [torch.bfloat16, torch.float32])
+def test_chunk_bwd_replays(kla, dt):
+    d = kla_inputs.varlen_inputs(4, 1, 300, 2, 128, 128, dtype=dt, seed=510, h0_std=0.2)
+    d_o, ghT = kla_inputs.grad_inputs(d, 5)
+    g = _dev(d, ("q", "k", "v", "log_alpha", "eta", "h0", "cu_seqlens"))
+    d_o, ghT = d_o.cuda(), ghT.cuda()
+    ws = torch.empty(kla.kla_chunk_bwd_workspace_bytes(d["N"], d["T"], d["H"], d["dk"], d["dv"], dt, cu_seqlens=g["cu_seqlens"]),
+                     dtype=torch.uint8, device="cuda")
+
+    def call(out=None, w=ws):
+        return kla.kla_chunk_bwd(g["q"], g["k"], g["v"], g["log_alpha"], g["eta"], d["eps"], d_o, h0=g["h0"], d_hT=ghT,
+                                 cu_seqlens=g["cu_seqlens"], cu_seqlens_host=d["cu_seqlens"], workspace=w, out=out)
+    ws2 = torch.empty_like(ws)
+    ref = call(w=ws2)
+    outs = {n: torch.empty_like(t) for n, t in ref.items()}
+    torch.cuda.synchronize()
+    graph = _capture(lambda: call(outs))
+    for rep in range(3):
+        for t in outs.values():
+            t.zero_()
+        ws.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        call(w=ws2)
+        torch.cuda.synchronize()
+        for n in ref:
+            assert torch.equal(outs[n], ref[n]), (n, rep)
+
+
+def test_decode_steps_replay(kla):
+    """Eight decode steps on one state, captured as one graph: replays continue the recurrence exactly like eager steps."""
+    d = kla_inputs.decode_inputs(8, 16, 4, 128, 128, seed=520)
+    g = {n: d[n].cuda() for n in ("q", "k", "v", "log_alpha", "eta")}
+    S_graph, S_eager = d["S"].cuda(), d["S"].cuda()
+    o_graph = torch.empty((8, 16, 4, 128), dtype=d["dtype"], device="cuda")
+    o_eager = torch.empty_like(o_graph)
+
+    def steps(S, o):
+        for t in range(8):
+            kla.kla_decode_step(g["q"][t], g["k"][t], g["v"][t], g["log_alpha"][t], g["eta"][t], d["eps"], S, out=o[t])
+    graph = _capture(lambda: steps(S_graph, o_graph))        # its warm-up call advanced S_graph: start again
+    S_graph.copy_(S_eager)
+    torch.cuda.synchronize()
+    for rep in range(3):                                      # 24 steps in all, the same 8 tokens three times
+        graph.replay()
+        steps(S_eager, o_eager)
+        torch.cuda.synchronize()
+        assert torch.equal(S_graph, S_eager) and torch.equal(o_graph, o_eager), rep
