@@ -104,3 +104,22 @@ def diag_gates(d, seed=0, scale=1.0):
     gen = torch.Generator().manual_seed(20_000 + seed)
     x = torch.randn(tuple(d["k"].shape), generator=gen, dtype=torch.float32)
     return -torch.nn.functional.softplus(x) * scale
+
+
+def device_randn(shape, dtype, seed, device="cuda", std=1.0):
+    """A large N(0, std^2) tensor drawn on `device`, one leading index at a time (bounded temporaries), each slice
+    from its own seed.  For the tests whose tensors exceed 2^31 elements: the values are compared with the oracle on
+    slices copied back to the host, so only reproducibility on one device matters."""
+    out = torch.empty(shape, dtype=dtype, device=device)
+    gen = torch.Generator(device=device)
+    for i in range(shape[0]):
+        gen.manual_seed(seed * 100_003 + i)
+        out[i] = (torch.randn(shape[1:], generator=gen, dtype=torch.float32, device=device) * std).to(dtype)
+    return out
+
+
+def device_gates(shape, seed, device="cuda"):
+    """log_alpha = -softplus(x), eta = sigmoid(x), x ~ N(0,1), drawn on `device` (see device_randn)."""
+    xa = device_randn(shape, torch.float32, seed, device)
+    xe = device_randn(shape, torch.float32, seed + 1, device)
+    return -torch.nn.functional.softplus(xa), torch.sigmoid(xe)

@@ -192,7 +192,7 @@ int make_bwd_plan(int N, int T, int H, int dk, int dv, int chunk, int dt, const 
     const size_t ch = (size_t)p->base.n_chunks * H;
     const size_t states = ch * dk * dv * elem_bytes(dt);          // checkpoints are kept in the element type
     const size_t rows = (size_t)N * T * H * dv * elem_bytes(dt);
-    p->off_rec = 0;                                              // [T' | M^T | P^T | four vectors] per chunk-head
+    p->off_rec = 0;                                              // [T' | M^T | P^T | five vectors] per chunk-head
     p->off_C = round256(ch * (3 * half + 1280));
     p->off_S = round256(p->off_C + (size_t)(n_seq + 1) * sizeof(int32_t));
     p->off_dS = round256(p->off_S + states);
