@@ -182,6 +182,9 @@ int chunk_fwd_impl(const void* q, const void* k, const void* v, const float* log
 struct BwdPlan {
     Plan base;
     size_t off_rec, off_C, off_S, off_dS, off_X, off_U, off_Y, total;
+    // segment-parallel sweeps (base.seg_G > 1): maps of the segments, states entering them, and for the reverse
+    // direction the state gradients leaving them and what each segment's pre-pass returns; all fp32
+    size_t off_maps, off_segS, off_segG, off_segB;
 };
 
 int make_bwd_plan(int N, int T, int H, int dk, int dv, int chunk, int dt, const int32_t* cu_host, int n_seq, BwdPlan* p)
@@ -199,7 +202,14 @@ int make_bwd_plan(int N, int T, int H, int dk, int dv, int chunk, int dt, const 
     p->off_X = round256(p->off_dS + states);
     p->off_U = round256(p->off_X + rows);
     p->off_Y = round256(p->off_U + rows);
-    p->total = round256(p->off_Y + rows);
+    const int G = p->base.seg_G;
+    const size_t maps = G > 1 ? (size_t)N * (G - 1) * H * dk * (dv + dk) * sizeof(float) : 0;
+    const size_t segst = G > 1 ? (size_t)N * G * H * dk * dv * sizeof(float) : 0;
+    p->off_maps = round256(p->off_Y + rows);
+    p->off_segS = round256(p->off_maps + maps);
+    p->off_segG = round256(p->off_segS + segst);
+    p->off_segB = round256(p->off_segG + segst);
+    p->total = round256(p->off_segB + segst);
     return KLA_OK;
 }
 
@@ -242,6 +252,43 @@ int chunk_bwd_impl(const void* q, const void* k, const void* v, const float* log
     ba.X = reinterpret_cast<E*>(ws + pl.off_X); ba.U = reinterpret_cast<E*>(ws + pl.off_U);
     ba.Y = reinterpret_cast<E*>(ws + pl.off_Y);
     ba.opts = opts;
+    ba.seg_G = 0; ba.seg_Lc = 0;
+    if constexpr (sizeof(E) == 2) {
+        if (fast && pl.base.seg_G > 1) {
+            // Segment-parallel sweeps for a few long sequences (see kla_chunk_segments.hip).  Forward: maps of all
+            // segments but the last, their composition, then every segment at once from its incoming state.  Reverse:
+            // the recursion dS = A dS' + b of a segment is affine with A the transpose of the forward map, so a
+            // pre-pass that stores nothing gives every b (the last segment runs with its true d_hT), the composition
+            // runs down the segments, and the real sweep starts every segment from its incoming gradient.
+            const int G = pl.base.seg_G;
+            float* maps = reinterpret_cast<float*>(ws + pl.off_maps);
+            float* segS = reinterpret_cast<float*>(ws + pl.off_segS);
+            float* segG = reinterpret_cast<float*>(ws + pl.off_segG);
+            float* segB = reinterpret_cast<float*>(ws + pl.off_segB);
+            kla::ScanArgs<E> sa;
+            sa.q = ba.q; sa.k = ba.k; sa.v = ba.v; sa.h0 = nullptr; sa.o = nullptr; sa.hT = nullptr;
+            sa.cu_seqlens = nullptr; sa.chunk_off = chunk_off; sa.n_seq = 0;
+            sa.N = N; sa.T = T; sa.NT = NT; sa.H = H; sa.dv = dv;
+            sa.wsT = reinterpret_cast<const E*>(ws + pl.off_rec); sa.wsP = nullptr; sa.wsG = nullptr; sa.opts = 0u;
+            sa.seg_G = G; sa.seg_Lc = pl.base.seg_Lc; sa.kt_src = nullptr; sa.gc_vec = nullptr;
+            if (kla::launch_segment_maps_bwdrec_bf16(sa, dk, maps, st) != hipSuccess) return KLA_ERR_HIP;
+            if (kla::launch_segment_combine(h0, maps, segS, N, H, dk, dv, G, st) != hipSuccess) return KLA_ERR_HIP;
+            if (kla::launch_segment_scatter(d_hT, segG, N, H, dk, dv, G, st) != hipSuccess) return KLA_ERR_HIP;
+            ba.seg_G = G; ba.seg_Lc = pl.base.seg_Lc;
+            const long sc8 = ((long)N * G * H + 7) / 8 * 8;
+            const int wseg = (sc8 * (dv / 32) >= 192) ? 2 : 1;
+            ba.h0 = segS;
+            if (kla::launch_bwd_states_bf16(ba, dk, wseg, st) != hipSuccess) return KLA_ERR_HIP;
+            ba.d_hT = segG; ba.dh0 = segB; ba.opts = opts | kla::kOptNoStore;
+            if (kla::launch_bwd_scan_bf16(ba, dk, wseg, st) != hipSuccess) return KLA_ERR_HIP;          // pre-pass: b per segment
+            if (kla::launch_segment_combine_rev(maps, segB, segG, N, H, dk, dv, G, st) != hipSuccess) return KLA_ERR_HIP;
+            ba.opts = opts;
+            if (kla::launch_bwd_scan_bf16(ba, dk, wseg, st) != hipSuccess) return KLA_ERR_HIP;          // the real sweep
+            if (dh0 && kla::launch_segment_gather(segB, dh0, N, H, dk, dv, G, 0, st) != hipSuccess) return KLA_ERR_HIP;
+            ba.seg_G = 0; ba.seg_Lc = 0; ba.h0 = h0; ba.d_hT = d_hT; ba.dh0 = dh0;
+            return kla::launch_bwd_assemble_bf16(ba, dk, pl.base.n_chunks, st) == hipSuccess ? KLA_OK : KLA_ERR_HIP;
+        }
+    }
     // two waves (32 state columns) per workgroup once that still gives a workgroup per CU
     const long chains8 = ((long)pl.base.n_states * H + 7) / 8 * 8;
     const int waves = (chains8 * (dv / 32) >= 192) ? 2 : 1;

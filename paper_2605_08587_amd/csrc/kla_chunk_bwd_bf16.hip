@@ -65,14 +65,22 @@ __global__ __launch_bounds__(64 * NW + 64) void bwd_sweep_bf16_kernel(BwdArgs<bf
     const int r = lane & 15, g = lane >> 4;
 
     const int nsl = a.dv_dim / SLW;
-    const int n_states = a.n_seq > 0 ? a.n_seq : a.N;
+    const int n_states = a.n_seq > 0 ? a.n_seq : (a.seg_G > 0 ? a.N * a.seg_G : a.N);
     const int xcd = blockIdx.x & 7, pidx = blockIdx.x >> 3;
     const int chain = (pidx / nsl) * 8 + xcd, slice = pidx % nsl;
     if (chain >= n_states * a.H) return;
     const int s = chain / a.H, h = chain % a.H;
     long t0; int len, ch0;
     if (a.cu_seqlens) { t0 = a.cu_seqlens[s]; len = a.cu_seqlens[s + 1] - (int)t0; ch0 = a.chunk_off[s]; }
+    else if (a.seg_G > 0) {                              // segment sg of sequence n: chunks [sg Lc, (sg + 1) Lc)
+        const int n = s / a.seg_G, sg = s % a.seg_G;
+        const int tok = min(sg * a.seg_Lc * 64, a.T);
+        t0 = (long)n * a.T + tok;
+        len = min(a.seg_Lc * 64, a.T - tok);
+        ch0 = n * a.NT + sg * a.seg_Lc;
+    }
     else              { t0 = (long)s * a.T;   len = a.T;                           ch0 = s * a.NT; }
+    const bool store = (a.opts & kOptNoStore) == 0;      // off: only the state is carried (segment pre-pass)
     const int nch = (len + 63) / 64;
     const int col = slice * SLW + 16 * wave + r;
 
@@ -183,7 +191,7 @@ __global__ __launch_bounds__(64 * NW + 64) void bwd_sweep_bf16_kernel(BwdArgs<bf
         u32x2 Sq[KB];
 #pragma unroll
         for (int kt = 0; kt < KB; ++kt) { Sq[kt] = to_quad(S[kt]); S[kt] = S[kt] * gC; }
-        {   // checkpoint, transposed: features 32 kp + 8 g .. + 7 of column `col` are 16 contiguous bytes
+        if (store) {   // checkpoint, transposed: features 32 kp + 8 g .. + 7 of column `col` are 16 contiguous bytes
             bf16_t* ck = (REV ? a.ds_chk : a.s_chk) + (((size_t)(ch0 + c) * a.H + h) * a.dv_dim + col) * DK + 8 * g;
 #pragma unroll
             for (int kp = 0; kp < KP; ++kp) {
@@ -316,7 +324,7 @@ __global__ __launch_bounds__(64 * NW + 64) void bwd_sweep_bf16_kernel(BwdArgs<bf
         for (int it = 0; it < 64 * VPP / NTH; ++it) {
             const int i = tid + NTH * it;
             const int row = i / VPP, pv = i % VPP;
-            if (row < clen) {
+            if (row < clen && store) {
                 st16(o0 + (size_t)row * v_row + pv * 16, ld16(ost + row * ORB + pv * 16));
                 st16(o1 + (size_t)row * v_row + pv * 16, ld16(ost + C::OSB + row * ORB + pv * 16));
             }
@@ -749,7 +757,7 @@ hipError_t launch_bwd_assemble_bf16(const BwdArgs<bf16_t>& a, int dk, long n_chu
 template <int DK, bool REV>
 static hipError_t launch_sweep_dk(const BwdArgs<bf16_t>& a, int waves, hipStream_t st)
 {
-    const int n_chains = (a.n_seq > 0 ? a.n_seq : a.N) * a.H;
+    const int n_chains = (a.n_seq > 0 ? a.n_seq : (a.seg_G > 0 ? a.N * a.seg_G : a.N)) * a.H;
     if (n_chains == 0) return hipSuccess;
     const dim3 grid((unsigned)(((n_chains + 7) / 8) * 8 * (a.dv_dim / (16 * waves))));
     if (waves == 1) hipLaunchKernelGGL((bwd_sweep_bf16_kernel<DK, 1, REV>), grid, dim3(128), 0, st, a);

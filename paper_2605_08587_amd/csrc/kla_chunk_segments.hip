@@ -46,7 +46,8 @@ struct MapCfg {
 // grid: (map chains rounded up to 8) x (d_v + d_k) / 32 workgroups of 2 compute waves + 1 copy wave.
 // Map chain = ((n (G-1) + sg) H + h): segment sg < G-1 of sequence n, head h.
 // maps: per map chain [N: DK x dv | M: DK x DK] fp32.
-template <int DK>
+// BREC: the records are those of the backward pass ([T' | M^T | P^T | vectors], see bwd_record_bytes).
+template <int DK, bool BREC = false>
 __global__ __launch_bounds__(192) void scan_maps_bf16_kernel(ScanArgs<bf16_t> a, float* __restrict__ maps)
 {
     typedef MapCfg<DK> C;
@@ -86,7 +87,8 @@ __global__ __launch_bounds__(192) void scan_maps_bf16_kernel(ScanArgs<bf16_t> a,
     const size_t kq_row = (size_t)a.H * DK * 2, v_row = (size_t)a.H * a.dv * 2;     // bytes between tokens
     const char* kbase = reinterpret_cast<const char*>(a.k) + (size_t)t0 * kq_row + (size_t)h * DK * 2;
     const char* vbase = reinterpret_cast<const char*>(a.v) + (size_t)t0 * v_row + ((size_t)h * a.dv + (phi ? 0 : slice) * SLW) * 2;
-    constexpr int REC = ws_record_bytes<bf16_t>();
+    constexpr int REC = BREC ? bwd_record_bytes<bf16_t>() : ws_record_bytes<bf16_t>();
+    constexpr int VEC = (BREC ? 3 : 2) * C::TPB;         // offset of gamma_i | gamma_C/gamma_i in a record
     const char* tpbase = reinterpret_cast<const char*>(a.wsT) + ((size_t)ch0 * a.H + h) * REC;
 
     if (wave == NW) {
@@ -115,7 +117,7 @@ __global__ __launch_bounds__(192) void scan_maps_bf16_kernel(ScanArgs<bf16_t> a,
                     dma16(vc + (size_t)(b * RPV) * v_row, gv, st + C::OFF_V + b * 1024);
                 });
             }
-            if (lane < 32) dma16(tc + 2 * C::TPB, lane * 16, st + C::OFF_EG);       // gamma_i | gamma_C/gamma_i
+            if (lane < 32) dma16(tc + VEC, lane * 16, st + C::OFF_EG);              // gamma_i | gamma_C/gamma_i
         };
         auto wait_behind = [&](bool ahead) {             // all but the copies of the newest chunk have landed
             if (!ahead) wait_vmcnt<0>();
@@ -256,6 +258,45 @@ __global__ __launch_bounds__(2 * DK) void segment_combine_kernel(const float* __
     }
 }
 
+// The backward counterpart: g(s-1) = M_s^T g(s) + b(s) down the segments (see launch_segment_combine_rev).  Same
+// decomposition; thread (row, half) reads column `row` of M_s, which consecutive rows read from consecutive addresses.
+template <int DK>
+__global__ __launch_bounds__(2 * DK) void segment_combine_rev_kernel(const float* __restrict__ maps, const float* __restrict__ bseg,
+                                                                    float* __restrict__ gseg, int H, int dv, int G)
+{
+    typedef float f4 __attribute__((ext_vector_type(4)));
+    __shared__ __attribute__((aligned(16))) f4 Gs[DK][2];
+    const int nh = blockIdx.x, c0 = blockIdx.y * 8;      // nh = n H + h
+    const int n = nh / H, h = nh % H;
+    const int row = threadIdx.x >> 1, half = threadIdx.x & 1;
+    const int col = c0 + 4 * half;
+    auto at = [&](int sg) { return ((size_t)((n * G + sg) * H + h) * DK + row) * dv + col; };
+    // g(G-2) = b(G-1): the last segment's sweep already ran with its true incoming gradient
+    f4 acc = *reinterpret_cast<const f4*>(bseg + at(G - 1));
+    *reinterpret_cast<f4*>(gseg + at(G - 2)) = acc;
+    for (int sg = G - 2; sg >= 1; --sg) {                // g(sg-1) = M_sg^T g(sg) + b(sg)
+        const float* mp = maps + (size_t)((n * (G - 1) + sg) * H + h) * DK * (dv + DK) + (size_t)DK * dv;   // M of segment sg
+        Gs[row][half] = acc;
+        __syncthreads();
+        acc = *reinterpret_cast<const f4*>(bseg + at(sg));
+#pragma unroll 8
+        for (int i = 0; i < DK; ++i) acc += mp[(size_t)i * DK + row] * Gs[i][half];
+        *reinterpret_cast<f4*>(gseg + at(sg - 1)) = acc;
+        __syncthreads();                                 // every thread has read Gs before it is overwritten
+    }
+}
+
+__global__ void segment_scatter_kernel(const float* __restrict__ d_hT, float* __restrict__ gseg, int H, long per_head,
+                                       int G, long total)
+{
+    const long i = (long)blockIdx.x * 256 + threadIdx.x;       // index into gseg
+    if (i >= total) return;
+    const long sh = i / per_head, e = i % per_head;            // sh = (n G + sg) H + h
+    const long s = sh / H, h = sh % H;
+    const long n = s / G, sg = s % G;
+    gseg[i] = (sg == G - 1 && d_hT) ? d_hT[(n * H + h) * per_head + e] : 0.f;
+}
+
 __global__ void segment_gather_kernel(const float* __restrict__ seg_state, float* __restrict__ hT, int H, long per_head,
                                       int G, int g_last, long total)
 {
@@ -277,12 +318,42 @@ hipError_t launch_segment_maps_bf16(const ScanArgs<bf16_t>& a, int dk, float* ma
     return hipGetLastError();
 }
 
+hipError_t launch_segment_maps_bwdrec_bf16(const ScanArgs<bf16_t>& a, int dk, float* maps, hipStream_t st)
+{
+    const int n_chains = a.N * (a.seg_G - 1) * a.H;
+    if (n_chains <= 0) return hipSuccess;
+    const int nsl = (a.dv + dk) / 32;
+    const dim3 grid((unsigned)(((n_chains + 7) / 8) * 8 * nsl));
+    if (dk == 64) hipLaunchKernelGGL((scan_maps_bf16_kernel<64, true>), grid, dim3(192), 0, st, a, maps);
+    else          hipLaunchKernelGGL((scan_maps_bf16_kernel<128, true>), grid, dim3(192), 0, st, a, maps);
+    return hipGetLastError();
+}
+
 hipError_t launch_segment_combine(const float* h0, const float* maps, float* seg_state, int N, int H, int dk, int dv,
                                   int G, hipStream_t st)
 {
     const dim3 grid((unsigned)(N * H), (unsigned)(dv / 8));
     if (dk == 64) hipLaunchKernelGGL((segment_combine_kernel<64>), grid, dim3(128), 0, st, h0, maps, seg_state, H, dv, G);
     else          hipLaunchKernelGGL((segment_combine_kernel<128>), grid, dim3(256), 0, st, h0, maps, seg_state, H, dv, G);
+    return hipGetLastError();
+}
+
+hipError_t launch_segment_combine_rev(const float* maps, const float* bseg, float* gseg, int N, int H, int dk, int dv,
+                                      int G, hipStream_t st)
+{
+    if (G < 2) return hipSuccess;
+    const dim3 grid((unsigned)(N * H), (unsigned)(dv / 8));
+    if (dk == 64) hipLaunchKernelGGL((segment_combine_rev_kernel<64>), grid, dim3(128), 0, st, maps, bseg, gseg, H, dv, G);
+    else          hipLaunchKernelGGL((segment_combine_rev_kernel<128>), grid, dim3(256), 0, st, maps, bseg, gseg, H, dv, G);
+    return hipGetLastError();
+}
+
+hipError_t launch_segment_scatter(const float* d_hT, float* gseg, int N, int H, int dk, int dv, int G, hipStream_t st)
+{
+    const long per_head = (long)dk * dv, total = (long)N * G * H * per_head;
+    if (total == 0) return hipSuccess;
+    hipLaunchKernelGGL(segment_scatter_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, d_hT, gseg, H,
+                       per_head, G, total);
     return hipGetLastError();
 }
 

@@ -11,6 +11,8 @@ namespace kla {
 constexpr unsigned kOptNormalizeQ = 1u, kOptGdnBeta = 2u;
 // internal: diagonal gating (log_alpha holds d_k values per token and head); set by the *_diag entry points only
 constexpr unsigned kOptDiagDecay = 0x100u;
+// internal: a backward sweep that only carries its state through the chunks (no checkpoints, no rows written)
+constexpr unsigned kOptNoStore = 0x200u;
 
 // ---- decode step and stand-alone coefficient -----------------------------------------------
 template <typename T>
@@ -80,6 +82,15 @@ hipError_t launch_scan_bf16_diag(const ScanArgs<bf16_t>& a, int dk, int waves, h
 // prefix composition, then the ordinary scan over all segments at once.  `maps` holds (G-1) x [N | M] per
 // sequence and head, `seg_state` the G incoming states; both fp32, in the workspace.
 hipError_t launch_segment_maps_bf16(const ScanArgs<bf16_t>& a, int dk, float* maps, hipStream_t st);
+// the same maps from the records of the backward pass (a.wsT = record base; see bwd_record_bytes)
+hipError_t launch_segment_maps_bwdrec_bf16(const ScanArgs<bf16_t>& a, int dk, float* maps, hipStream_t st);
+// Reverse composition for the backward pass: g(G-1) = d_hT (or 0), g(G-2) = b(G-1), g(s-1) = M_s^T g(s) + b(s) for
+// s = G-2 .. 1, where g(s) is the gradient of the state leaving segment s and b(s) what the reverse sweep of segment s
+// returns for a zero g(s) (for the last segment: for its true g).  gseg, bseg: [N * G][H][dk][dv] fp32.
+hipError_t launch_segment_combine_rev(const float* maps, const float* bseg, float* gseg, int N, int H, int dk, int dv,
+                                      int G, hipStream_t st);
+// gseg = 0 except the last segment of every sequence, which gets d_hT (or 0 when d_hT is NULL)
+hipError_t launch_segment_scatter(const float* d_hT, float* gseg, int N, int H, int dk, int dv, int G, hipStream_t st);
 hipError_t launch_segment_combine(const float* h0, const float* maps, float* seg_state, int N, int H, int dk, int dv,
                                   int G, hipStream_t st);
 hipError_t launch_segment_gather(const float* seg_state, float* hT, int N, int H, int dk, int dv, int G, int g_last,
@@ -103,6 +114,9 @@ template <typename E> struct BwdArgs {
     E* s_chk; E* ds_chk;             // [n_chunks * H][dv][dk]
     E* X; E* U; E* Y;                // [tokens][H][dv]
     unsigned opts;                   // kOptGdnBeta: beta = eta, so dk has no term through the coefficient
+    // Segmented sweeps (seg_G > 0, fixed-length bf16 batches only; see ScanArgs): h0, d_hT and dh0 are then indexed by
+    // segment, [N * seg_G][H][dk][dv].
+    int seg_G, seg_Lc;
 };
 template <typename E> hipError_t launch_bwd_states(const BwdArgs<E>& a, int dk, int waves, hipStream_t st);
 template <typename E> hipError_t launch_bwd_scan(const BwdArgs<E>& a, int dk, int waves, hipStream_t st);

@@ -244,3 +244,75 @@ def test_bwd_config5_sampled(kla):
     lens = (d["cu_seqlens"][1:] - d["cu_seqlens"][:-1]).numpy()
     units = sorted({(int(np.argmax(lens)), 0), (int(np.argmin(lens)), 15), (3, 7), (9, 2), (12, 11), (5, 5)})
     _check(kla, d, seed=11, units=units)
+
+
+# ---------------------------------------------------------------------------------------------
+# segment-parallel sweeps (long sequences in small batches): forced on small shapes, automatic on long ones
+@pytest.mark.parametrize("segs", ["2", "3", "5"])
+@pytest.mark.parametrize("N,T,H,dk,dv,h0,ghT", [(2, 1000, 2, 128, 128, None, True), (1, 777, 3, 64, 256, 0.3, True),
+                                               (1, 130, 1, 128, 64, 0.3, False)])
+def test_bwd_segmented(kla, segs, N, T, H, dk, dv, h0, ghT, monkeypatch):
+    """KLA_SCAN_SEGMENTS forces the segmented sweeps; ragged last segments, two segments (no reverse composition
+    step), with and without h0 and d_hT.  The two routes agree far inside the bar, and the segmented one really ran
+    (its workspace holds the maps and the per-segment states)."""
+    d = kla_inputs.chunk_inputs(N, T, H, dk, dv, dtype=torch.bfloat16, seed=197 + T, h0_std=h0)
+    d_o, g = kla_inputs.grad_inputs(d, 21, d_hT=ghT)
+    monkeypatch.setenv("KLA_SCAN_SEGMENTS", "1")
+    w1 = kla.kla_chunk_bwd_workspace_bytes(N, T, H, dk, dv, torch.bfloat16)
+    one = _run(kla, d, d_o, g)
+    monkeypatch.setenv("KLA_SCAN_SEGMENTS", segs)
+    assert kla.kla_chunk_bwd_workspace_bytes(N, T, H, dk, dv, torch.bfloat16) > w1
+    got = _run(kla, d, d_o, g)
+    ref = _oracle(d, d_o, g)
+    errs = {n: token_oracle.rel_err(got[n], ref[n]) for n in NAMES}
+    print("   rel err " + " ".join("%s=%.2e" % kv for kv in errs.items()), flush=True)
+    for n in NAMES:
+        assert errs[n] <= TOL[torch.bfloat16], (n, errs[n])
+        assert token_oracle.rel_err(got[n], one[n]) <= TOL[torch.bfloat16], n
+
+
+@pytest.mark.parametrize("segs", ["2", "3", "5"])
+def test_bwd_segmented_slow_decay(kla, segs, monkeypatch):
+    """log_alpha scaled by 0.02: states and their gradients carry over a thousand tokens, so the composed maps (forward)
+    and their transposes (reverse) matter - with the usual gates they are numerically zero.  The segmented route rounds
+    differently from the plain one (checked: they differ) and both stay inside the bar."""
+    d = kla_inputs.chunk_inputs(1, 1500, 2, 128, 128, dtype=torch.bfloat16, seed=352, log_alpha_scale=0.02, h0_std=0.2)
+    d_o, g = kla_inputs.grad_inputs(d, 24)
+    monkeypatch.setenv("KLA_SCAN_SEGMENTS", "1")
+    one = _run(kla, d, d_o, g)
+    monkeypatch.setenv("KLA_SCAN_SEGMENTS", segs)
+    got = _run(kla, d, d_o, g)
+    ref = _oracle(d, d_o, g)
+    errs = {n: token_oracle.rel_err(got[n], ref[n]) for n in NAMES}
+    print("   rel err " + " ".join("%s=%.2e" % kv for kv in errs.items()), flush=True)
+    print("   vs plain " + " ".join("%s=%.2e" % (n, token_oracle.rel_err(got[n], one[n])) for n in NAMES), flush=True)
+    # dq sees the forward states; dh0 only the reverse sweep, which with two segments is the plain computation
+    assert np.any(got["dq"] != one["dq"]) and (segs == "2" or np.any(got["dh0"] != one["dh0"]))
+    for n in NAMES:
+        assert errs[n] <= TOL[torch.bfloat16], (n, errs[n])
+        assert token_oracle.rel_err(got[n], one[n]) <= TOL[torch.bfloat16], n
+
+
+def test_bwd_segmented_with_options(kla, monkeypatch):
+    monkeypatch.setenv("KLA_SCAN_SEGMENTS", "4")
+    d = kla_inputs.chunk_inputs(1, 900, 2, 128, 128, dtype=torch.bfloat16, seed=199, h0_std=0.2)
+    d["k"] = (d["k"].float() / d["k"].float().norm(dim=-1, keepdim=True)).to(torch.bfloat16)
+    d_o, g = kla_inputs.grad_inputs(d, 22)
+    got = _run(kla, d, d_o, g, normalize_q=True, gdn_beta=True)
+    q, k, v = (kla_inputs.to_numpy_f32(d[x]) for x in "qkv")
+    ref = token_oracle.kla_recurrent_bwd(q, k, v, d["log_alpha"].numpy(), d["eta"].numpy(), d["eps"],
+                                         kla_inputs.to_numpy_f32(d_o), h0=d["h0"].numpy(), d_hT=g.numpy(),
+                                         normalize_q=True, gdn_beta=True)
+    for n in NAMES:
+        assert token_oracle.rel_err(got[n], ref[n]) <= TOL[torch.bfloat16], n
+
+
+def test_bwd_segmented_automatic_long_sequence(kla):
+    """One sequence of 8192 tokens on two heads: few chains, many chunks - the sweeps are cut into segments by the
+    library's own rule (the workspace says so); all gradients against the oracle."""
+    N, T, H, dk, dv = 1, 8192, 2, 128, 128
+    d = kla_inputs.chunk_inputs(N, T, H, dk, dv, dtype=torch.bfloat16, seed=198, h0_std=0.2)
+    eb = 2
+    plain = 3 * N * T * H * dv * eb + 2 * (N * (T // 64) * H) * dk * dv * eb + (N * (T // 64) * H) * (3 * 6144 + 1280)
+    assert kla.kla_chunk_bwd_workspace_bytes(N, T, H, dk, dv, torch.bfloat16) > plain + 4 * dk * dv * 4 * H
+    _check(kla, d, seed=23)

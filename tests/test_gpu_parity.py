@@ -328,6 +328,23 @@ def test_chunk_segmented(kla, segs, N, T, H, dk, dv, h0, monkeypatch):
 
 
 @pytest.mark.gpu
+@pytest.mark.parametrize("segs", ["3", "5"])
+def test_chunk_segmented_slow_decay(kla, segs, monkeypatch):
+    """With the usual gates a state is forgotten within a chunk or two, and the maps of a segment are numerically zero;
+    here log_alpha is scaled by 0.01, so the state entering a segment carries a thousand tokens of history through the
+    composed maps.  The segmented route then rounds differently from the plain one (checked: they differ) and both
+    stay inside the bar."""
+    d = kla_inputs.chunk_inputs(1, 2000, 2, 128, 128, dtype=torch.bfloat16, seed=98, h0_std=0.3, log_alpha_scale=0.01)
+    monkeypatch.setenv("KLA_SCAN_SEGMENTS", "1")
+    o1, h1 = _run_chunk(kla, d)
+    monkeypatch.setenv("KLA_SCAN_SEGMENTS", segs)
+    _check_chunk(kla, d)
+    o2, h2 = _run_chunk(kla, d)
+    assert np.any(h2 != h1)
+    assert token_oracle.rel_err(o2, o1) <= TOL[torch.bfloat16] and token_oracle.rel_err(h2, h1) <= TOL[torch.bfloat16]
+
+
+@pytest.mark.gpu
 def test_chunk_segmented_with_options(kla, monkeypatch):
     monkeypatch.setenv("KLA_SCAN_SEGMENTS", "4")
     d = kla_inputs.chunk_inputs(1, 900, 2, 128, 128, dtype=torch.bfloat16, seed=99, h0_std=0.2)
