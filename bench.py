@@ -189,6 +189,22 @@ def main():
                     "ms_per_call": round(msb, 4), "tokens_per_s": round(tokens / (msb * 1e-3), 1),
                     "times_forward": round(msb / ms_per_step, 2), "workspace_MB": round(wb.numel() / 1e6, 1)}
         del wb, grads, d_o, d_hT
+        # the same on config 3 (one 65K-token sequence): segment-parallel sweeps
+        e3 = kla_inputs.config(3)
+        g3 = {n: e3[n].cuda() for n in ("q", "k", "v", "log_alpha", "eta")}
+        do3, dh3 = kla_inputs.grad_inputs(e3, 2)
+        do3, dh3 = do3.cuda(), dh3.cuda()
+        w3 = torch.empty(kla.kla_chunk_bwd_workspace_bytes(e3["N"], e3["T"], e3["H"], e3["dk"], e3["dv"], torch.bfloat16),
+                         dtype=torch.uint8, device="cuda")
+        gr3 = kla.kla_chunk_bwd(g3["q"], g3["k"], g3["v"], g3["log_alpha"], g3["eta"], e3["eps"], do3, d_hT=dh3, workspace=w3)
+        fn3 = lambda: kla.kla_chunk_bwd(g3["q"], g3["k"], g3["v"], g3["log_alpha"], g3["eta"], e3["eps"], do3, d_hT=dh3,
+                                        workspace=w3, out=gr3)
+        for _ in range(2):
+            fn3()
+        ms3 = _events(torch, fn3, 5)
+        backward["config3"] = {"workload": "config3 (N=1,H=8,T=65536): segment-parallel sweeps", "ms_per_call": round(ms3, 4),
+                               "tokens_per_s": round(e3["N"] * e3["T"] / (ms3 * 1e-3), 1)}
+        del w3, gr3, do3, dh3, g3
 
     # ------------------------------------------------------------------ diagonal gating on config 2's tensors (secondary)
     diag = None
