@@ -37,7 +37,7 @@ template <typename E> struct IntraArgs {
     unsigned opts;                               // kOptNormalizeQ | kOptGdnBeta
 };
 template <typename E> hipError_t launch_intra(const IntraArgs<E>& a, int dk, int n_chunks, hipStream_t st);
-// the records of the backward pass (see bwd_record_bytes in kla_mma.hpp) at a.wsT; a.wsP, a.wsG unused; a.opts: kOptGdnBeta or 0
+// the records of the backward pass (see bwd_record_bytes in kla_mma.hpp) at a.wsT; a.wsP, a.wsG unused; a.opts: kOptNormalizeQ | kOptGdnBeta
 template <typename E> hipError_t launch_intra_bwd(const IntraArgs<E>& a, int dk, int n_chunks, hipStream_t st);
 
 // Diagonal gating (App. B): log_alpha is [tokens, H, dk].  Besides the records (with unit decay vectors) the stage
@@ -113,7 +113,8 @@ template <typename E> struct BwdArgs {
     const char* rec;                 // stage-1 records
     E* s_chk; E* ds_chk;             // [n_chunks * H][dv][dk]
     E* X; E* U; E* Y;                // [tokens][H][dv]
-    unsigned opts;                   // kOptGdnBeta: beta = eta, so dk has no term through the coefficient
+    unsigned opts;                   // kOptGdnBeta: beta = eta, so dk has no term through the coefficient; kOptNormalizeQ:
+                                     // read-out divided by ||q||; kOptNoStore (sweeps only, internal)
     // Segmented sweeps (seg_G > 0, fixed-length bf16 batches only; see ScanArgs): h0, d_hT and dh0 are then indexed by
     // segment, [N * seg_G][H][dk][dv].
     int seg_G, seg_Lc;
