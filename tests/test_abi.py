@@ -210,6 +210,18 @@ def test_chunk_bwd_validation_and_workspace():
         expect += 3 * r256(N * T * H * dv * eb)                # X, U, Y
         assert lib.kla_chunk_bwd_workspace_bytes(N, T, H, dk, dv, 64, dt, None, 0) == expect
     assert lib.kla_chunk_bwd_workspace_bytes(1, 64, 1, 100, 64, 64, kla.KLA_BF16, None, 0) == 0
+    # one long bf16 sequence on few heads: the sweeps run in segments (here 8 of 16 chunks), and the workspace also holds
+    # 7 maps [N | M] and 3 x 8 states per (sequence, head) in fp32; fp32 inputs never segment
+    N, T, H, dk, dv = 1, 8192, 2, 128, 128
+    plain = {}
+    for dt, eb in ((kla.KLA_BF16, 2), (kla.KLA_F32, 4)):
+        n_ch = N * (T // 64) * H
+        x = r256(r256(n_ch * (3 * 384 * 8 * eb + 1280)) + 4) + 2 * r256(n_ch * dk * dv * eb) + 3 * r256(N * T * H * dv * eb)
+        plain[dt] = x
+    seg = plain[kla.KLA_BF16] + r256(N * 7 * H * dk * (dv + dk) * 4) + 3 * r256(N * 8 * H * dk * dv * 4)
+    if not os.environ.get("KLA_SCAN_SEGMENTS") and not os.environ.get("KLA_SCAN_IMPL"):
+        assert lib.kla_chunk_bwd_workspace_bytes(N, T, H, dk, dv, 64, kla.KLA_BF16, None, 0) == seg
+    assert lib.kla_chunk_bwd_workspace_bytes(N, T, H, dk, dv, 64, kla.KLA_F32, None, 0) == plain[kla.KLA_F32]
     opt = lambda opts, **o: lib.kla_chunk_bwd_opts(*[{**base, **o}[n] for n in names], opts)
     assert opt(8) == E_SHAPE
     assert opt(kla.KLA_OPT_GDN_BETA, q=None) == E_NULL
