@@ -134,6 +134,16 @@ def test_binding_refuses_cpu_tensors():
         kla.kla_beta(x, g, 1e-6)
 
 
+def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
+    """No HIP library, no result: the product path has no CPU fallback to slip into."""
+    monkeypatch.setattr(kla, "LIB_PATH", str(tmp_path / "libkla.so"))
+    monkeypatch.setattr(kla, "_lib", None)
+    with pytest.raises(RuntimeError, match="not built"):
+        kla.lib()
+    with pytest.raises(RuntimeError, match="not built"):
+        kla.kla_chunk_fwd_workspace_bytes(1, 64, 1, 64, 64, None)
+
+
 def test_option_entry_points_validate_like_the_plain_ones():
     lib = kla.lib()
     chunk = lambda opts, **o: lib.kla_chunk_fwd_opts(
