@@ -320,8 +320,8 @@ hipError_t launch_intra(const IntraArgs<E>& a, int dk, int n_chunks, hipStream_t
 template hipError_t launch_intra<float>(const IntraArgs<float>&, int, int, hipStream_t);
 template hipError_t launch_intra<bf16_t>(const IntraArgs<bf16_t>&, int, int, hipStream_t);
 
-// The records of the backward pass: a.wsT points at them, a.wsP and a.wsG are not used; of the options only
-// kOptGdnBeta applies (beta = eta, and the record's fourth vector, d beta / d eta, is then 1).
+// The records of the backward pass: a.wsT points at them, a.wsP and a.wsG are not used.  kOptGdnBeta: beta = eta, and
+// the record's fourth vector, d beta / d eta, is 1; kOptNormalizeQ: P^T carries 1/||q_i||, which is also the fifth vector.
 template <typename E>
 hipError_t launch_intra_bwd(const IntraArgs<E>& a, int dk, int n_chunks, hipStream_t st)
 {

@@ -89,9 +89,11 @@ __device__ __forceinline__ void write_transposed(char* out, const float* m, int 
 
 }  // namespace
 
-// BWD = true: the record of the backward pass, [T' | M^T | P^T | gamma_i | gamma_C/gamma_i | beta_i | 1/(||k_i||^2+eps)]
-// (M = (I + L)^{-1}; the transposes as the 6 upper-triangular tile-pairs, see kla_mma.hpp).  Of the options only
-// kOptGdnBeta applies there (beta = eta; the fourth vector, d beta / d eta, is then 1).
+// BWD = true: the record of the backward pass,
+// [T' | M^T | P^T | gamma_i | gamma_C/gamma_i | beta_i | 1/(||k_i||^2+eps) | 1/||q_i||]
+// (M = (I + L)^{-1}; the transposes as the 6 upper-triangular tile-pairs, see kla_mma.hpp).  kOptGdnBeta: beta = eta
+// and the fourth vector, d beta / d eta, is 1; kOptNormalizeQ: P^T carries 1/||q_i|| and the fifth vector holds it
+// (1 otherwise).
 template <int DK, bool BWD>
 __global__ __launch_bounds__(256, 3) void intra_bf16_kernel(IntraArgs<bf16_t> a)
 {
