@@ -304,3 +304,32 @@ def kla_debug_intra_chunk(q, k, log_alpha, eta, eps, cu_seqlens=None, chunk=64):
     if rc != 0:
         raise KlaError(rc, "kla_debug_intra_chunk")
     return Tb, P, g
+
+
+class _KlaChunk(torch.autograd.Function):
+    """kla_chunk_fwd / kla_chunk_bwd as one differentiable call (marshalling only: every step runs in the library)."""
+
+    @staticmethod
+    def forward(ctx, q, k, v, log_alpha, eta, h0, eps, cu_seqlens, cu_seqlens_host, normalize_q, gdn_beta):
+        o, hT = kla_chunk_fwd(q, k, v, log_alpha, eta, eps, h0=h0, cu_seqlens=cu_seqlens, cu_seqlens_host=cu_seqlens_host,
+                              normalize_q=normalize_q, gdn_beta=gdn_beta)
+        ctx.save_for_backward(q, k, v, log_alpha, eta, h0 if h0 is not None else q.new_empty(0))
+        ctx.misc = (eps, cu_seqlens, cu_seqlens_host, normalize_q, gdn_beta, h0 is not None)
+        return o, hT
+
+    @staticmethod
+    def backward(ctx, d_o, d_hT):
+        q, k, v, log_alpha, eta, h0 = ctx.saved_tensors
+        eps, cu_seqlens, cu_seqlens_host, normalize_q, gdn_beta, has_h0 = ctx.misc
+        g = kla_chunk_bwd(q, k, v, log_alpha, eta, eps, d_o.contiguous(), h0=h0 if has_h0 else None,
+                          d_hT=None if d_hT is None else d_hT.contiguous(), cu_seqlens=cu_seqlens,
+                          cu_seqlens_host=cu_seqlens_host, want_dh0=has_h0 and ctx.needs_input_grad[5],
+                          normalize_q=normalize_q, gdn_beta=gdn_beta)
+        return (g["dq"], g["dk"], g["dv"], g["dlog_alpha"], g["deta"], g["dh0"], None, None, None, None, None)
+
+
+def kla_chunk(q, k, v, log_alpha, eta, eps, h0=None, cu_seqlens=None, cu_seqlens_host=None, normalize_q=False,
+              gdn_beta=False):
+    """Differentiable chunkwise forward for training loops: returns (o, hT) like kla_chunk_fwd; gradients with respect to
+    q, k, v, log_alpha, eta and h0 come from kla_chunk_bwd (the forward is recomputed there, nothing else is saved)."""
+    return _KlaChunk.apply(q, k, v, log_alpha, eta, h0, eps, cu_seqlens, cu_seqlens_host, normalize_q, gdn_beta)

@@ -335,3 +335,20 @@ def test_bwd_segmented_automatic_long_sequence(kla):
     plain = 3 * N * T * H * dv * eb + 2 * (N * (T // 64) * H) * dk * dv * eb + (N * (T // 64) * H) * (3 * 6144 + 1280)
     assert kla.kla_chunk_bwd_workspace_bytes(N, T, H, dk, dv, torch.bfloat16) > plain + 4 * dk * dv * 4 * H
     _check(kla, d, seed=23)
+
+
+def test_autograd_wrapper_matches_the_entry_points(kla):
+    """kla.kla_chunk: torch autograd through the two entry points gives exactly what calling them by hand gives."""
+    d = kla_inputs.chunk_inputs(2, 150, 2, 128, 128, dtype=torch.bfloat16, seed=390, h0_std=0.3)
+    d_o, g = kla_inputs.grad_inputs(d, 26)
+    leaves = {n: d[n].cuda().requires_grad_(True) for n in ("q", "k", "v", "log_alpha", "eta", "h0")}
+    o, hT = kla.kla_chunk(leaves["q"], leaves["k"], leaves["v"], leaves["log_alpha"], leaves["eta"], d["eps"], h0=leaves["h0"],
+                          normalize_q=True)
+    torch.autograd.backward([o, hT], [d_o.cuda(), g.cuda()])
+    torch.cuda.synchronize()
+    ref = _run(kla, d, d_o, g, normalize_q=True)
+    o2, h2 = kla.kla_chunk_fwd(*(leaves[n].detach() for n in ("q", "k", "v", "log_alpha", "eta")), d["eps"],
+                               h0=leaves["h0"].detach(), normalize_q=True)
+    assert torch.equal(o, o2) and torch.equal(hT, h2)
+    for n, leaf in (("dq", "q"), ("dk", "k"), ("dv", "v"), ("dlog_alpha", "log_alpha"), ("deta", "eta"), ("dh0", "h0")):
+        assert np.array_equal(leaves[leaf].grad.float().cpu().numpy(), ref[n]), n
