@@ -116,3 +116,35 @@ def test_decode_steps_replay(kla):
         steps(S_eager, o_eager)
         torch.cuda.synchronize()
         assert torch.equal(S_graph, S_eager) and torch.equal(o_graph, o_eager), rep
+
+
+def test_diag_entry_points_replay(kla):
+    """Diagonal gating: the chunk forward and a decode step under capture."""
+    d = kla_inputs.chunk_inputs(2, 300, 2, 128, 128, seed=530, h0_std=0.2)
+    g = _dev(d, ("q", "k", "v", "eta", "h0"))
+    lad = kla_inputs.diag_gates(d, 5).cuda()
+    N, T, H, dk, dv = d["N"], d["T"], d["H"], d["dk"], d["dv"]
+    ws = torch.empty(int(kla.lib().kla_chunk_fwd_diag_workspace_bytes(N, T, H, dk, dv, 64, kla.KLA_BF16, None, 0)),
+                     dtype=torch.uint8, device="cuda")
+    out = torch.empty((N, T, H, dv), dtype=d["dtype"], device="cuda")
+    hT = torch.empty((N, H, dk, dv), dtype=torch.float32, device="cuda")
+    S = torch.empty((N, H, dk, dv), dtype=torch.float32, device="cuda")
+    od = torch.empty((N, H, dv), dtype=d["dtype"], device="cuda")
+
+    def call(o=out, h=hT, w=ws, s=S, o1=od):
+        kla.kla_chunk_fwd_diag(g["q"], g["k"], g["v"], lad, g["eta"], d["eps"], h0=g["h0"], workspace=w, out=o, hT=h)
+        s.copy_(h)                                        # then one decode step on the final states, with the last token
+        kla.kla_decode_step_diag(g["q"][:, -1].contiguous(), g["k"][:, -1].contiguous(), g["v"][:, -1].contiguous(),
+                                 lad[:, -1].contiguous(), g["eta"][:, -1].contiguous(), d["eps"], s, out=o1)
+    ref = [torch.empty_like(t) for t in (out, hT, ws, S, od)]
+    call(*ref)
+    torch.cuda.synchronize()
+    graph = _capture(call)
+    for rep in range(3):
+        for t in (out, hT, ws, S, od):
+            t.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        call(*[torch.empty_like(t) for t in (out, hT, ws, S, od)])
+        torch.cuda.synchronize()
+        assert torch.equal(out, ref[0]) and torch.equal(hT, ref[1]) and torch.equal(S, ref[3]) and torch.equal(od, ref[4]), rep
