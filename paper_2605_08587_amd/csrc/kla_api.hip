@@ -601,8 +601,12 @@ int kla_decode_step_opts(const void* q, const void* k, const void* v, const floa
     if (!aligned16(S) || (reinterpret_cast<uintptr_t>(q) & 3u) || (reinterpret_cast<uintptr_t>(k) & 3u) ||
         (reinterpret_cast<uintptr_t>(v) & 3u) || (reinterpret_cast<uintptr_t>(o) & 3u))
         return KLA_ERR_ALIGN;
-    int slice = 128;                                  // state columns per workgroup
-    const char* env = getenv("KLA_DECODE_SLICE");     // tuning knob: 32, 64, 128 or 256
+    // State columns per workgroup: 128 (measured best at 512 workgroups, e.g. 64 x 8 states of 128 columns), narrower for
+    // small batches so that about 512 workgroups still share the chip (B = 1, H = 8: 3.2 us per step with 32 columns,
+    // 4.2 us with 128).  KLA_DECODE_SLICE = 32, 64, 128 or 256 overrides.
+    int slice = dv < 128 ? dv : 128;
+    while (slice > 32 && (long)B * H * (dv / slice) < 512) slice >>= 1;
+    const char* env = getenv("KLA_DECODE_SLICE");
     if (env) { const int x = atoi(env); if (x == 32 || x == 64 || x == 128 || x == 256) slice = x; }
     if (slice > dv) slice = dv;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);

@@ -100,6 +100,27 @@ def test_decode_small(kla, dt, dk, dv):
         assert token_oracle.rel_err(S.cpu().numpy(), Sref) <= 1e-5
 
 
+@pytest.mark.parametrize("B", [1, 16, 40])
+@pytest.mark.parametrize("sl", [None, "32", "64", "128", "256"])
+def test_decode_slice_widths(kla, B, sl, monkeypatch):
+    """Every width of the state slice a workgroup takes (the library picks 32 .. 128 columns by batch size;
+    KLA_DECODE_SLICE forces one), on a batch of 1, 16 and 40 x 8 heads: same results."""
+    if sl is None:
+        monkeypatch.delenv("KLA_DECODE_SLICE", raising=False)
+    else:
+        monkeypatch.setenv("KLA_DECODE_SLICE", sl)
+    d = kla_inputs.decode_inputs(2, B, 8, 128, 256, dtype=torch.bfloat16, seed=23, state_std=1.0)
+    S = d["S"].cuda().clone()
+    Sref = d["S"].double().numpy()
+    for t in range(d["steps"]):
+        q, k, v, la, eta = (d[n][t].contiguous().cuda() for n in ("q", "k", "v", "log_alpha", "eta"))
+        o = kla.kla_decode_step(q, k, v, la, eta, d["eps"], S)
+        ro, Sref = token_oracle.kla_decode(*(kla_inputs.to_numpy_f32(d[n][t]) for n in "qkv"),
+                                           d["log_alpha"][t].numpy(), d["eta"][t].numpy(), d["eps"], Sref)
+        assert token_oracle.rel_err(o.float().cpu().numpy(), ro) <= 1e-2
+        assert token_oracle.rel_err(S.cpu().numpy(), Sref) <= 1e-5
+
+
 def test_decode_config4_full(kla):
     """Config 4 as benchmarked: B=64, H=8, d=128, 256 consecutive steps, state updated in place."""
     d = kla_inputs.config(4)
