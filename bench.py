@@ -29,8 +29,21 @@ CHUNK_FLOP_PER_TOKEN_HEAD = 6 * 128 * 128 + 64 * (3 * 128 + 2 * 128)  # triangul
 DECODE_BYTES_PER_TOKEN_HEAD = 2 * 4 * 128 * 128 + 2 * (2 * 128 + 128) + 8 + 2 * 128   # state r+w, q,k,v, gates, o
 
 
-def _events(torch, fn, reps):
-    """Average milliseconds of fn() over reps launches, by events on the current stream."""
+def _warm(torch, fn, ms=50.0):
+    """Untimed: keeps the GPU busy with fn() for about `ms` milliseconds.  After an idle spell the first ~25 ms of work
+    run 10-20 % slower (clocks ramp up: config 2 steps take 0.144, 0.122, 0.120, 0.120 .. ms per hundred), so every timed
+    region below starts from a busy GPU, as a training or serving loop would."""
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    while (time.perf_counter() - t0) * 1e3 < ms:
+        for _ in range(4):
+            fn()
+        torch.cuda.synchronize()
+
+
+def _events(torch, fn, reps, warm_ms=50.0):
+    """Average milliseconds of fn() over reps launches, by events on the current stream (after an untimed warm-up)."""
+    _warm(torch, fn, warm_ms)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     e0.record()
@@ -57,8 +70,8 @@ def _traffic(key):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=100)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=500)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--skip-cpu-baseline", action="store_true")
     ap.add_argument("--skip-decode", action="store_true")
     ap.add_argument("--skip-extra", action="store_true", help="skip the two secondary chunk workloads (configs 3 and 5)")
@@ -103,6 +116,7 @@ def main():
     def stage(i):
         kla.kla_debug_chunk_stage(i, dev["q"], dev["k"], dev["v"], dev["log_alpha"], dev["eta"], d["eps"], ws, out, hT=hT)
 
+    _warm(torch, step)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
