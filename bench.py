@@ -74,6 +74,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--skip-cpu-baseline", action="store_true")
     ap.add_argument("--skip-decode", action="store_true")
+    ap.add_argument("--skip-rotating", action="store_true",
+                    help="skip the config-2 step on three rotating copies of its tensors (so that a kernel trace of this "
+                         "command holds the benchmarked launches only)")
     ap.add_argument("--skip-extra", action="store_true", help="skip the two secondary chunk workloads (configs 3 and 5)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="only run a plain device copy of 1 GiB five times (reference for the rocprofv3 byte counters)")
@@ -132,21 +135,23 @@ def main():
     # The same step over three copies of the inputs and outputs in turn (1 GB in all): nothing of a step's tensors is
     # still in the 256 MB memory-side cache when the step comes round again.  Reported beside `value`, which times
     # the repeated batch as the contract's step does.
-    rot = [{n: t.clone() for n, t in dev.items()} for _ in range(3)]
-    rot_out = [torch.empty_like(out) for _ in range(3)]
-    rot_i = [0]
+    rotating = None
+    if not args.skip_rotating:
+        rot = [{n: t.clone() for n, t in dev.items()} for _ in range(3)]
+        rot_out = [torch.empty_like(out) for _ in range(3)]
+        rot_i = [0]
 
-    def step_rot():
-        i = rot_i[0] = (rot_i[0] + 1) % 3
-        g = rot[i]
-        kla.kla_chunk_fwd(g["q"], g["k"], g["v"], g["log_alpha"], g["eta"], d["eps"], workspace=ws, out=rot_out[i], hT=hT)
-    for _ in range(6):
-        step_rot()
-    ms_rot = _events(torch, step_rot, max(3, args.steps // 3 * 3))
-    rotating = {"sets": 3, "ms_per_step": round(ms_rot, 4), "tokens_per_s": round(tokens / (ms_rot * 1e-3), 1),
-                "note": "same step cycling over three copies of the inputs and outputs, so no tensor of a step is left "
-                        "in the memory-side cache from its previous turn"}
-    del rot, rot_out
+        def step_rot():
+            i = rot_i[0] = (rot_i[0] + 1) % 3
+            g = rot[i]
+            kla.kla_chunk_fwd(g["q"], g["k"], g["v"], g["log_alpha"], g["eta"], d["eps"], workspace=ws, out=rot_out[i], hT=hT)
+        for _ in range(6):
+            step_rot()
+        ms_rot = _events(torch, step_rot, max(3, args.steps // 3 * 3))
+        rotating = {"sets": 3, "ms_per_step": round(ms_rot, 4), "tokens_per_s": round(tokens / (ms_rot * 1e-3), 1),
+                    "note": "same step cycling over three copies of the inputs and outputs, so no tensor of a step is left "
+                            "in the memory-side cache from its previous turn"}
+        del rot, rot_out
 
     ms_intra = _events(torch, lambda: stage(1), args.steps)
     ms_scan = _events(torch, lambda: stage(2), args.steps)
