@@ -327,7 +327,7 @@ int kla_oracle_sequence_bwd_opts(const float *q, const float *k, const float *v,
 /* One token with diagonal gating: row i of S decays by exp(log_alpha[i]); lines 2-5 as in kla_token. */
 static void kla_token_diag(double *S, const float *q, const float *k, const float *v,
                            const double *log_alpha, double eta, double eps, int dk, int dv,
-                           double *o, double *e)
+                           double *o, double *e, int normalize_q, int gdn_beta)
 {
     int i, j;
     /* line 1 with D_t = diag(alpha_t): S~ = diag(alpha) S */
@@ -348,25 +348,34 @@ static void kla_token_diag(double *S, const float *q, const float *k, const floa
     for (i = 0; i < dk; ++i)
         nk += (double)k[i] * (double)k[i];
     const double den = nk + eps;
-    const double beta = (den == 0.0) ? 0.0 : eta / den;
+    double beta = (den == 0.0) ? 0.0 : eta / den;
+    if (gdn_beta) beta = eta;                    /* the gated delta rule: no key-norm denominator */
     /* line 4: S = S~ + beta k e^T */
     for (i = 0; i < dk; ++i)
         for (j = 0; j < dv; ++j)
             S[(size_t)i * dv + j] += beta * (double)k[i] * e[j];
-    /* line 5: o = S^T q */
+    /* line 5: o = S^T q, or as printed o = S^T q / ||q|| (a zero query gives 0) */
     for (j = 0; j < dv; ++j) {
         double r = 0.0;
         for (i = 0; i < dk; ++i)
             r += S[(size_t)i * dv + j] * (double)q[i];
         o[j] = r;
     }
+    if (normalize_q) {
+        double nq = 0.0;
+        for (i = 0; i < dk; ++i)
+            nq += (double)q[i] * (double)q[i];
+        nq = sqrt(nq);
+        for (j = 0; j < dv; ++j)
+            o[j] = (nq == 0.0) ? 0.0 : o[j] / nq;
+    }
 }
 
 /* kla_oracle_sequence with diagonal gating: log_alpha is [n_tokens_total, H, dk]; everything else as there. */
-int kla_oracle_sequence_diag(const float *q, const float *k, const float *v,
-                             const double *log_alpha, const double *eta, double eps,
-                             const double *h0, double *o, double *hT,
-                             long t0, long len, int h, int H, int dk, int dv)
+int kla_oracle_sequence_diag_opts(const float *q, const float *k, const float *v,
+                                  const double *log_alpha, const double *eta, double eps,
+                                  const double *h0, double *o, double *hT,
+                                  long t0, long len, int h, int H, int dk, int dv, int normalize_q, int gdn_beta)
 {
     double *S = (double *)malloc(sizeof(double) * (size_t)dk * dv);
     double *e = (double *)malloc(sizeof(double) * (size_t)dv);
@@ -376,23 +385,38 @@ int kla_oracle_sequence_diag(const float *q, const float *k, const float *v,
     for (long t = t0; t < t0 + len; ++t) {
         const size_t th = (size_t)t * H + h;
         kla_token_diag(S, q + th * dk, k + th * dk, v + th * dv, log_alpha + th * dk, eta[th], eps, dk, dv,
-                       o + th * dv, e);
+                       o + th * dv, e, normalize_q, gdn_beta);
     }
     if (hT) memcpy(hT, S, sizeof(double) * (size_t)dk * dv);
     free(S); free(e);
     return 0;
 }
 
+int kla_oracle_sequence_diag(const float *q, const float *k, const float *v,
+                             const double *log_alpha, const double *eta, double eps,
+                             const double *h0, double *o, double *hT,
+                             long t0, long len, int h, int H, int dk, int dv)
+{
+    return kla_oracle_sequence_diag_opts(q, k, v, log_alpha, eta, eps, h0, o, hT, t0, len, h, H, dk, dv, 0, 0);
+}
+
 /* One decode step with diagonal gating: log_alpha has dk entries. */
+int kla_oracle_decode_unit_diag_opts(const float *q, const float *k, const float *v,
+                                     const double *log_alpha, double eta, double eps,
+                                     double *S, double *o, int dk, int dv, int normalize_q, int gdn_beta)
+{
+    double *e = (double *)malloc(sizeof(double) * (size_t)dv);
+    if (!e) return -1;
+    kla_token_diag(S, q, k, v, log_alpha, eta, eps, dk, dv, o, e, normalize_q, gdn_beta);
+    free(e);
+    return 0;
+}
+
 int kla_oracle_decode_unit_diag(const float *q, const float *k, const float *v,
                                 const double *log_alpha, double eta, double eps,
                                 double *S, double *o, int dk, int dv)
 {
-    double *e = (double *)malloc(sizeof(double) * (size_t)dv);
-    if (!e) return -1;
-    kla_token_diag(S, q, k, v, log_alpha, eta, eps, dk, dv, o, e);
-    free(e);
-    return 0;
+    return kla_oracle_decode_unit_diag_opts(q, k, v, log_alpha, eta, eps, S, o, dk, dv, 0, 0);
 }
 
 /* The gradient for the plain recurrence (beta of eq. (3)). */

@@ -53,11 +53,11 @@ def _load():
                                                    ctypes.c_double, dp, dp, ctypes.c_int, ctypes.c_int]
             lib.kla_oracle_decode_unit_opts.restype = ctypes.c_int
             lib.kla_oracle_decode_unit_opts.argtypes = lib.kla_oracle_decode_unit.argtypes + [ctypes.c_int, ctypes.c_int]
-            lib.kla_oracle_sequence_diag.restype = ctypes.c_int
-            lib.kla_oracle_sequence_diag.argtypes = lib.kla_oracle_sequence.argtypes
-            lib.kla_oracle_decode_unit_diag.restype = ctypes.c_int
-            lib.kla_oracle_decode_unit_diag.argtypes = [fp, fp, fp, dp, ctypes.c_double, ctypes.c_double, dp, dp,
-                                                        ctypes.c_int, ctypes.c_int]
+            lib.kla_oracle_sequence_diag_opts.restype = ctypes.c_int
+            lib.kla_oracle_sequence_diag_opts.argtypes = lib.kla_oracle_sequence.argtypes + [ctypes.c_int, ctypes.c_int]
+            lib.kla_oracle_decode_unit_diag_opts.restype = ctypes.c_int
+            lib.kla_oracle_decode_unit_diag_opts.argtypes = [fp, fp, fp, dp, ctypes.c_double, ctypes.c_double, dp, dp,
+                                                             ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int]
             lib.kla_oracle_sequence_bwd_opts.restype = ctypes.c_int
             lib.kla_oracle_sequence_bwd_opts.argtypes = [fp, fp, fp, dp, dp, ctypes.c_double, dp, dp, dp,
                                                     dp, dp, dp, dp, dp, dp,
@@ -138,8 +138,10 @@ def kla_recurrent(q, k, v, log_alpha, eta, eps, h0=None, cu_seqlens=None, thread
     return o, hT, nthr
 
 
-def kla_recurrent_diag(q, k, v, log_alpha, eta, eps, h0=None, cu_seqlens=None, threads=None, units=None):
-    """kla_recurrent with diagonal gating (App. B): log_alpha is [N, T, H, dk], one decay per key channel."""
+def kla_recurrent_diag(q, k, v, log_alpha, eta, eps, h0=None, cu_seqlens=None, threads=None, units=None,
+                       normalize_q=False, gdn_beta=False):
+    """kla_recurrent with diagonal gating (App. B): log_alpha is [N, T, H, dk], one decay per key channel.
+    normalize_q, gdn_beta: as in kla_recurrent."""
     lib = _load()
     q, k, v = _f32(q), _f32(k), _f32(v)
     la, et = _f64(log_alpha), _f64(eta)
@@ -163,9 +165,9 @@ def kla_recurrent_diag(q, k, v, log_alpha, eta, eps, h0=None, cu_seqlens=None, t
     def run(unit):
         s, h = unit
         off = (s * H + h) * dk * dv
-        rc = lib.kla_oracle_sequence_diag(_fp(q), _fp(k), _fp(v), _dp(la), _dp(et), float(eps),
-                                          None if h0d is None else _dp(h0d, off), _dp(o), _dp(hT, off),
-                                          starts[s], lens[s], h, H, dk, dv)
+        rc = lib.kla_oracle_sequence_diag_opts(_fp(q), _fp(k), _fp(v), _dp(la), _dp(et), float(eps),
+                                               None if h0d is None else _dp(h0d, off), _dp(o), _dp(hT, off),
+                                               starts[s], lens[s], h, H, dk, dv, int(normalize_q), int(gdn_beta))
         if rc != 0:
             raise MemoryError("oracle scratch allocation failed")
 
@@ -179,7 +181,7 @@ def kla_recurrent_diag(q, k, v, log_alpha, eta, eps, h0=None, cu_seqlens=None, t
     return o, hT, nthr
 
 
-def kla_decode_diag(q, k, v, log_alpha, eta, eps, S, threads=None):
+def kla_decode_diag(q, k, v, log_alpha, eta, eps, S, threads=None, normalize_q=False, gdn_beta=False):
     """kla_decode with diagonal gating: log_alpha is [B, H, dk].  Returns (o, S_new); S is not modified."""
     lib = _load()
     q, k, v = _f32(q), _f32(k), _f32(v)
@@ -189,11 +191,12 @@ def kla_decode_diag(q, k, v, log_alpha, eta, eps, S, threads=None):
     dv = v.shape[-1]
     o = np.zeros((B, H, dv), dtype=np.float64)
     for u in range(B * H):
-        rc = lib.kla_oracle_decode_unit_diag(
+        rc = lib.kla_oracle_decode_unit_diag_opts(
             ctypes.cast(q.ctypes.data + 4 * u * dk, ctypes.POINTER(ctypes.c_float)),
             ctypes.cast(k.ctypes.data + 4 * u * dk, ctypes.POINTER(ctypes.c_float)),
             ctypes.cast(v.ctypes.data + 4 * u * dv, ctypes.POINTER(ctypes.c_float)),
-            _dp(la, u * dk), float(et.reshape(-1)[u]), float(eps), _dp(S, u * dk * dv), _dp(o, u * dv), dk, dv)
+            _dp(la, u * dk), float(et.reshape(-1)[u]), float(eps), _dp(S, u * dk * dv), _dp(o, u * dv), dk, dv,
+            int(normalize_q), int(gdn_beta))
         if rc != 0:
             raise MemoryError("oracle scratch allocation failed")
     return o, S

@@ -507,6 +507,42 @@ def test_diag_equal_channels_is_scalar_gating():
     np.testing.assert_allclose(h2, h1, rtol=1e-13, atol=1e-15)
 
 
+def test_diag_options_reduce_to_the_scalar_options_and_to_their_definitions():
+    """The options of the diagonal-gating oracle.  With equal channels they repeat the (separately pinned) options of
+    the scalar oracle; with distinct channels the normalised read-out is the plain one divided by ||q_t|| row by row
+    (0 for a zero query, states untouched), and beta_t = eta_t equals the Kaczmarz coefficient fed with
+    eta_t (||k_t||^2 + eps) - eq. (3) solved for eta."""
+    rng = RNG(56)
+    T, H, dk, dv, eps = 30, 2, 6, 5, 1e-3
+    q, k, v, la, eta, S0 = _rand_problem(rng, T, H, dk, dv, N=2)
+    k = (k * 0.4).astype(np.float32)                          # keeps the plain delta rule stable
+    q[1, 4, 0] = 0.0
+    lad = np.repeat(la[..., None], dk, axis=-1)
+    for nq, gdn in ((True, False), (False, True), (True, True)):
+        o1, h1, _ = token_oracle.kla_recurrent(q, k, v, la, eta, eps, h0=S0, normalize_q=nq, gdn_beta=gdn)
+        o2, h2, _ = token_oracle.kla_recurrent_diag(q, k, v, lad, eta, eps, h0=S0, normalize_q=nq, gdn_beta=gdn)
+        np.testing.assert_allclose(o2, o1, rtol=1e-13, atol=1e-15)
+        np.testing.assert_allclose(h2, h1, rtol=1e-13, atol=1e-15)
+    lad2 = -np.log1p(np.exp(rng.standard_normal((2, T, H, dk))))
+    o0, h0_, _ = token_oracle.kla_recurrent_diag(q, k, v, lad2, eta, eps, h0=S0)
+    on, hn, _ = token_oracle.kla_recurrent_diag(q, k, v, lad2, eta, eps, h0=S0, normalize_q=True)
+    nq_ = np.linalg.norm(q.astype(np.float64), axis=-1, keepdims=True)
+    np.testing.assert_allclose(on, np.where(nq_ == 0, 0.0, o0 / np.where(nq_ == 0, 1.0, nq_)), rtol=1e-13, atol=1e-15)
+    np.testing.assert_array_equal(hn, h0_)
+    assert np.all(on[1, 4, 0] == 0.0)
+    eta_eq = eta * (np.sum(k.astype(np.float64) ** 2, axis=-1) + eps)
+    og, hg, _ = token_oracle.kla_recurrent_diag(q, k, v, lad2, eta, eps, h0=S0, gdn_beta=True)
+    ok_, hk, _ = token_oracle.kla_recurrent_diag(q, k, v, lad2, eta_eq, eps, h0=S0)
+    np.testing.assert_allclose(og, ok_, rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(hg, hk, rtol=1e-12, atol=1e-14)
+    # one decode step with the options is one token of the sequence oracle
+    od, Sd = token_oracle.kla_decode_diag(q[:, 0], k[:, 0], v[:, 0], lad2[:, 0], eta[:, 0], eps, S0, normalize_q=True, gdn_beta=True)
+    o1, h1, _ = token_oracle.kla_recurrent_diag(q[:, :1], k[:, :1], v[:, :1], lad2[:, :1], eta[:, :1], eps, h0=S0,
+                                                normalize_q=True, gdn_beta=True)
+    np.testing.assert_allclose(od, o1[:, 0], rtol=1e-13, atol=1e-15)
+    np.testing.assert_allclose(Sd, h1, rtol=1e-13, atol=1e-15)
+
+
 def test_diag_projection_property_is_decay_agnostic():
     """App. A, decay-agnostic remark: with eta = 1, eps = 0 the written state satisfies S_t^T k_t = v_t whatever
     linear decay produced the base point; and the residual contracts by 1 - eta |k|^2/(|k|^2+eps) in general."""
