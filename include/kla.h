@@ -210,6 +210,19 @@ int kla_decode_step_diag(const void *q, const void *k, const void *v,
                          float *S, void *o,
                          int B, int H, int dk, int dv, kla_dtype dt, void *hip_stream);
 
+/* The two diagonal-gating calls with the option bits of kla_chunk_fwd_opts (same meaning: Sec. 3.3 read-out, Table 2's
+ * beta_t = eta_t); kla_chunk_fwd_diag(...) and kla_decode_step_diag(...) are these with opts = 0.  Same workspace. */
+int kla_chunk_fwd_diag_opts(const void *q, const void *k, const void *v,
+                            const float *log_alpha, const float *eta, float eps,
+                            const float *h0, void *o, float *hT,
+                            const int32_t *cu_seqlens_dev, const int32_t *cu_seqlens_host, int n_seq,
+                            int N, int T, int H, int dk, int dv, int chunk, kla_dtype dt,
+                            void *workspace, size_t workspace_bytes, void *hip_stream, unsigned opts);
+int kla_decode_step_diag_opts(const void *q, const void *k, const void *v,
+                              const float *log_alpha, const float *eta, float eps,
+                              float *S, void *o,
+                              int B, int H, int dk, int dv, kla_dtype dt, void *hip_stream, unsigned opts);
+
 /*
  * The Kaczmarz coefficient alone (eq. (3)): beta[i] = eta[i] / (||k_i||^2 + eps), 0 when the
  * denominator is 0, for n_token_heads rows of dk elements.

@@ -34,6 +34,10 @@ _SIGNATURES = {
                            + [ctypes.c_int] * 6 + [ctypes.c_int, _vp, ctypes.c_size_t, _vp]),
     "kla_decode_step_diag": (ctypes.c_int, [_vp, _vp, _vp, _fp, _fp, ctypes.c_float, _fp, _vp]
                              + [ctypes.c_int] * 4 + [ctypes.c_int, _vp]),
+    "kla_chunk_fwd_diag_opts": (ctypes.c_int, [_vp, _vp, _vp, _fp, _fp, ctypes.c_float, _fp, _vp, _fp, _ip, _ip, ctypes.c_int]
+                                + [ctypes.c_int] * 6 + [ctypes.c_int, _vp, ctypes.c_size_t, _vp, ctypes.c_uint]),
+    "kla_decode_step_diag_opts": (ctypes.c_int, [_vp, _vp, _vp, _fp, _fp, ctypes.c_float, _fp, _vp]
+                                  + [ctypes.c_int] * 4 + [ctypes.c_int, _vp, ctypes.c_uint]),
     "kla_chunk_bwd_workspace_bytes": (ctypes.c_size_t, [ctypes.c_int] * 6 + [ctypes.c_int, _ip, ctypes.c_int]),
     "kla_chunk_bwd": (ctypes.c_int, [_vp, _vp, _vp, _fp, _fp, ctypes.c_float, _fp, _vp, _fp, _vp, _vp, _vp, _fp, _fp, _fp,
                                      _ip, _ip, ctypes.c_int] + [ctypes.c_int] * 6 + [ctypes.c_int, _vp, ctypes.c_size_t, _vp]),
@@ -161,9 +165,9 @@ def kla_chunk_fwd(q, k, v, log_alpha, eta, eps, h0=None, cu_seqlens=None, want_h
 
 
 def kla_chunk_fwd_diag(q, k, v, log_alpha, eta, eps, h0=None, cu_seqlens=None, want_hT=True, workspace=None,
-                       out=None, hT=None, chunk=64, cu_seqlens_host=None):
+                       out=None, hT=None, chunk=64, cu_seqlens_host=None, normalize_q=False, gdn_beta=False):
     """Chunkwise forward with diagonal gating: log_alpha is [N,T,H,dk] fp32 (one decay per key channel).
-    Everything else as kla_chunk_fwd; returns (o, hT)."""
+    Everything else, the options included, as kla_chunk_fwd; returns (o, hT)."""
     _dev(q, k, v, log_alpha, eta, h0, cu_seqlens, workspace, out, hT)
     N, T, H, dk = q.shape
     dv = v.shape[-1]
@@ -179,15 +183,17 @@ def kla_chunk_fwd_diag(q, k, v, log_alpha, eta, eps, h0=None, cu_seqlens=None, w
         out = torch.empty((N, T, H, dv), dtype=q.dtype, device=q.device)
     if hT is None and want_hT:
         hT = torch.empty((n_states, H, dk, dv), dtype=torch.float32, device=q.device)
-    rc = lib().kla_chunk_fwd_diag(_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(eta), float(eps), _ptr(h0), _ptr(out),
-                                  _ptr(hT), _ptr(cu_seqlens), cu_hp, n_seq, N, T, H, dk, dv, chunk, dt,
-                                  _ptr(workspace), workspace.numel() * workspace.element_size(), _stream())
+    args = (_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(eta), float(eps), _ptr(h0), _ptr(out),
+            _ptr(hT), _ptr(cu_seqlens), cu_hp, n_seq, N, T, H, dk, dv, chunk, dt,
+            _ptr(workspace), workspace.numel() * workspace.element_size(), _stream())
+    opts = _opts(normalize_q, gdn_beta)
+    rc = lib().kla_chunk_fwd_diag_opts(*args, opts) if opts else lib().kla_chunk_fwd_diag(*args)
     if rc != 0:
         raise KlaError(rc, "kla_chunk_fwd_diag")
     return out, hT
 
 
-def kla_decode_step_diag(q, k, v, log_alpha, eta, eps, S, out=None):
+def kla_decode_step_diag(q, k, v, log_alpha, eta, eps, S, out=None, normalize_q=False, gdn_beta=False):
     """One decode step with diagonal gating: log_alpha is [B,H,dk]; S [B,H,dk,dv] fp32 is updated in place."""
     _dev(q, k, v, log_alpha, eta, S, out)
     B, H, dk = q.shape
@@ -196,8 +202,10 @@ def kla_decode_step_diag(q, k, v, log_alpha, eta, eps, S, out=None):
         raise ValueError("log_alpha must be [B, H, dk] for diagonal gating")
     if out is None:
         out = torch.empty((B, H, dv), dtype=q.dtype, device=q.device)
-    rc = lib().kla_decode_step_diag(_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(eta), float(eps), _ptr(S), _ptr(out),
-                                    B, H, dk, dv, _dt(q), _stream())
+    args = (_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(eta), float(eps), _ptr(S), _ptr(out), B, H, dk, dv, _dt(q),
+            _stream())
+    opts = _opts(normalize_q, gdn_beta)
+    rc = lib().kla_decode_step_diag_opts(*args, opts) if opts else lib().kla_decode_step_diag(*args)
     if rc != 0:
         raise KlaError(rc, "kla_decode_step_diag")
     return out

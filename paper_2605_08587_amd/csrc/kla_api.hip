@@ -327,7 +327,7 @@ int make_diag_plan(int N, int T, int H, int dk, int dv, int chunk, int dt, const
 template <typename E>
 int chunk_fwd_diag_impl(const void* q, const void* k, const void* v, const float* log_alpha, const float* eta, float eps,
                         const float* h0, void* o, float* hT, const int32_t* cu_dev, int n_seq, int N, int T, int H,
-                        int dk, int dv, const DiagPlan& pl, char* ws, hipStream_t st)
+                        int dk, int dv, const DiagPlan& pl, char* ws, hipStream_t st, unsigned opts)
 {
     int* chunk_off = reinterpret_cast<int*>(ws + pl.base.off_C);
     const int NT = (T + 63) / 64;
@@ -340,6 +340,7 @@ int chunk_fwd_diag_impl(const void* q, const void* k, const void* v, const float
     ia.wsT = reinterpret_cast<E*>(ws + pl.base.off_T); ia.wsG = reinterpret_cast<float*>(ws + pl.base.off_G);
     ia.kplus = reinterpret_cast<E*>(ws + pl.off_kp); ia.qplus = reinterpret_cast<E*>(ws + pl.off_qp);
     ia.ktilde = reinterpret_cast<E*>(ws + pl.off_kt); ia.gc = reinterpret_cast<float*>(ws + pl.off_gc);
+    ia.opts = opts;
     if (kla::launch_intra_diag<E>(ia, dk, (int)pl.base.n_chunks, st) != hipSuccess) return KLA_ERR_HIP;
 
     kla::ScanArgs<E> sa;
@@ -499,6 +500,16 @@ int kla_chunk_fwd_diag(const void* q, const void* k, const void* v, const float*
                        const int32_t* cu_seqlens_host, int n_seq, int N, int T, int H, int dk, int dv, int chunk,
                        kla_dtype dt, void* workspace, size_t workspace_bytes, void* hip_stream)
 {
+    return kla_chunk_fwd_diag_opts(q, k, v, log_alpha, eta, eps, h0, o, hT, cu_seqlens_dev, cu_seqlens_host, n_seq, N, T, H,
+                                   dk, dv, chunk, dt, workspace, workspace_bytes, hip_stream, 0u);
+}
+
+int kla_chunk_fwd_diag_opts(const void* q, const void* k, const void* v, const float* log_alpha, const float* eta, float eps,
+                            const float* h0, void* o, float* hT, const int32_t* cu_seqlens_dev,
+                            const int32_t* cu_seqlens_host, int n_seq, int N, int T, int H, int dk, int dv, int chunk,
+                            kla_dtype dt, void* workspace, size_t workspace_bytes, void* hip_stream, unsigned opts)
+{
+    if (opts & ~(unsigned)(KLA_OPT_NORMALIZE_Q | KLA_OPT_GDN_BETA)) return KLA_ERR_SHAPE;
     DiagPlan pl;
     const int rc = make_diag_plan(N, T, H, dk, dv, chunk, (int)dt, cu_seqlens_host, n_seq, &pl);
     if (rc != KLA_OK) return rc;
@@ -517,15 +528,23 @@ int kla_chunk_fwd_diag(const void* q, const void* k, const void* v, const float*
     char* ws = static_cast<char*>(workspace);
     if (dt == KLA_BF16)
         return chunk_fwd_diag_impl<bf16_t>(q, k, v, log_alpha, eta, eps, h0, o, hT, cu_seqlens_dev, n_seq, N, T, H, dk, dv,
-                                           pl, ws, st);
+                                           pl, ws, st, opts);
     return chunk_fwd_diag_impl<float>(q, k, v, log_alpha, eta, eps, h0, o, hT, cu_seqlens_dev, n_seq, N, T, H, dk, dv, pl,
-                                      ws, st);
+                                      ws, st, opts);
 }
 
 int kla_decode_step_diag(const void* q, const void* k, const void* v, const float* log_alpha, const float* eta,
                          float eps, float* S, void* o, int B, int H, int dk, int dv, kla_dtype dt, void* hip_stream)
 {
+    return kla_decode_step_diag_opts(q, k, v, log_alpha, eta, eps, S, o, B, H, dk, dv, dt, hip_stream, 0u);
+}
+
+int kla_decode_step_diag_opts(const void* q, const void* k, const void* v, const float* log_alpha, const float* eta,
+                              float eps, float* S, void* o, int B, int H, int dk, int dv, kla_dtype dt, void* hip_stream,
+                              unsigned opts)
+{
     if (!dt_ok((int)dt)) return KLA_ERR_DTYPE;
+    if (opts & ~(unsigned)(KLA_OPT_NORMALIZE_Q | KLA_OPT_GDN_BETA)) return KLA_ERR_SHAPE;
     if (B < 0 || H <= 0 || !dk_ok(dk) || !dv_ok(dv) || (long)B * H > 0x7fffffffL) return KLA_ERR_SHAPE;
     if (!(eps >= 0.0f) || isinf(eps)) return KLA_ERR_SHAPE;
     if (B == 0) return KLA_OK;
@@ -539,11 +558,11 @@ int kla_decode_step_diag(const void* q, const void* k, const void* v, const floa
     if (dt == KLA_BF16)
         e = kla::launch_decode<bf16_t>(static_cast<const bf16_t*>(q), static_cast<const bf16_t*>(k),
                                        static_cast<const bf16_t*>(v), log_alpha, eta, eps, S, static_cast<bf16_t*>(o),
-                                       B * H, dk, dv, 64, kla::kOptDiagDecay, st);
+                                       B * H, dk, dv, 64, kla::kOptDiagDecay | opts, st);
     else
         e = kla::launch_decode<float>(static_cast<const float*>(q), static_cast<const float*>(k),
                                       static_cast<const float*>(v), log_alpha, eta, eps, S, static_cast<float*>(o),
-                                      B * H, dk, dv, 64, kla::kOptDiagDecay, st);
+                                      B * H, dk, dv, 64, kla::kOptDiagDecay | opts, st);
     return e == hipSuccess ? KLA_OK : KLA_ERR_HIP;
 }
 

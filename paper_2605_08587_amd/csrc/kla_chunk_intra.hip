@@ -344,7 +344,8 @@ template hipError_t launch_intra_bwd<bf16_t>(const IntraArgs<bf16_t>&, int, int,
 // summed pair by pair on the vector ALUs (there gamma_i/gamma_j <= 1 directly).  The triangular inverse and the records are those of
 // the scalar kernel, with unit decay vectors: the decay travels in the operands the scan is given instead,
 //     K+ = K o Gamma,  Q+ = Q o Gamma,  K~ = K o (gamma_C / Gamma)   (all factors <= 1)  and gamma_C per channel,
-// which this kernel writes next to the records.
+// which this kernel writes next to the records.  Options: kOptGdnBeta (beta = eta); kOptNormalizeQ, for which the
+// rows of Q+ and of P are divided by ||q_i|| here, so that the scan needs no variant of its own.
 template <typename E, int DK>
 __global__ __launch_bounds__(256) void intra_diag_kernel(IntraDiagArgs<E> a)
 {
@@ -356,6 +357,7 @@ __global__ __launch_bounds__(256) void intra_diag_kernel(IntraDiagArgs<E> a)
     constexpr int REC = ws_record_bytes<E>();
     __shared__ __attribute__((aligned(16))) char area[2 * TE + TG > 3 * 64 * kLdm * 4 ? 2 * TE + TG : 3 * 64 * kLdm * 4];
     __shared__ __attribute__((aligned(16))) float beta_s[64];
+    __shared__ __attribute__((aligned(16))) float rq_s[64];      // 1/||q_i|| for the normalised read-out (Sec. 3.3), else 1
     __shared__ float segsum[NSEG][DK];
     const E* Kp = reinterpret_cast<const E*>(area);           // K rows (element type), later overlaid by Lm, Pm, Tm
     const E* Qp = reinterpret_cast<const E*>(area + TE);      // Q rows
@@ -417,16 +419,18 @@ __global__ __launch_bounds__(256) void intra_diag_kernel(IntraDiagArgs<E> a)
             }
             *reinterpret_cast<uint4*>(area + (size_t)(row * LE + piece * EPP) * sizeof(E)) = kd;
             *reinterpret_cast<uint4*>(area + TE + (size_t)(row * LE + piece * EPP) * sizeof(E)) = qd;
-            float kf[EPP];
+            float kf[EPP], qf0[EPP];
             unpack(kd, kf);
-            float ss = 0.f;
+            unpack(qd, qf0);
+            float ss = 0.f, sq = 0.f;
 #pragma unroll
-            for (int i = 0; i < EPP; ++i) ss += kf[i] * kf[i];
+            for (int i = 0; i < EPP; ++i) { ss += kf[i] * kf[i]; sq += qf0[i] * qf0[i]; }
 #pragma unroll
-            for (int off = 1; off < PPR; off <<= 1) ss += __shfl_xor(ss, off, kWave);
+            for (int off = 1; off < PPR; off <<= 1) { ss += __shfl_xor(ss, off, kWave); sq += __shfl_xor(sq, off, kWave); }
             if (piece == 0) {
                 const float et = row < clen ? a.eta[(size_t)(tok0 + row) * a.H + h] : 0.f;
-                beta_s[row] = kaczmarz_beta(et, ss, a.eps);
+                beta_s[row] = (a.opts & kOptGdnBeta) ? et : kaczmarz_beta(et, ss, a.eps);
+                rq_s[row] = (a.opts & kOptNormalizeQ) ? (sq > 0.f ? 1.0f / sqrtf(sq) : 0.f) : 1.f;
             }
         }
 #pragma unroll
@@ -476,7 +480,7 @@ __global__ __launch_bounds__(256) void intra_diag_kernel(IntraDiagArgs<E> a)
                 for (int i = 0; i < EPP; ++i) {
                     const float gi = Gs[row * LD + piece * EPP + i], gl = Gs[63 * LD + piece * EPP + i];
                     const float up = __builtin_amdgcn_exp2f(gi);
-                    kp[i] = kf[i] * up; qp[i] = qf[i] * up; kt[i] = kf[i] * __builtin_amdgcn_exp2f(gl - gi);
+                    kp[i] = kf[i] * up; qp[i] = qf[i] * (up * rq_s[row]); kt[i] = kf[i] * __builtin_amdgcn_exp2f(gl - gi);
                 }
                 const size_t off = (size_t)row * row_stride + piece * EPP;
                 *reinterpret_cast<uint4*>(kpo + off) = pack(kp);
@@ -587,12 +591,12 @@ __global__ __launch_bounds__(256) void intra_diag_kernel(IntraDiagArgs<E> a)
             if (job < 6 || (il >= 8 && r < 8)) {
                 const int i = 16 * ti + il, j = 16 * tj + r;
                 Lm[i * kLdm + j] = beta_s[i] * tkk[jb][e];
-                Pm[i * kLdm + j] = tqk[jb][e];
+                Pm[i * kLdm + j] = tqk[jb][e] * rq_s[i];
             }
         }
     }
-    if (tid < 224) { Lm[pi * kLdm + pj] = beta_s[pi] * pkk; Pm[pi * kLdm + pj] = pqk; }
-    if (tid < 64) Pm[tid * kLdm + tid] = pdg;
+    if (tid < 224) { Lm[pi * kLdm + pj] = beta_s[pi] * pkk; Pm[pi * kLdm + pj] = pqk * rq_s[pi]; }
+    if (tid < 64) Pm[tid * kLdm + tid] = pdg * rq_s[tid];
     __syncthreads();
     invert_and_store<E, false>(Lm, Tm, Pm, beta_s, reinterpret_cast<char*>(a.wsT) + (size_t)blockIdx.x * REC, tid);
 }

@@ -140,8 +140,9 @@ static hipError_t launch_decode_nt(const T* q, const T* k, const T* v, const flo
                                    float eps, float* S, T* o, int BH, int dv, int slice, unsigned opts, hipStream_t st)
 {
     dim3 grid(BH, dv / slice), block(256);
-    if (opts & kOptDiagDecay) {                      // diagonal gating: one slice shape, the options do not apply
-        hipLaunchKernelGGL((decode_kernel<T, DK, 64, NT, true>), dim3(BH, dv / 64), block, 0, st, q, k, v, la, eta, eps, S, o, dv, 0u);
+    if (opts & kOptDiagDecay) {                      // diagonal gating: one slice shape
+        hipLaunchKernelGGL((decode_kernel<T, DK, 64, NT, true>), dim3(BH, dv / 64), block, 0, st, q, k, v, la, eta, eps, S, o, dv,
+                           opts & (kOptNormalizeQ | kOptGdnBeta));
         return hipGetLastError();
     }
     switch (slice) {

@@ -51,6 +51,7 @@ template <typename E> struct IntraDiagArgs {
     int T, NT, H;
     E* wsT; float* wsG;
     E* kplus; E* qplus; E* ktilde; float* gc;
+    unsigned opts;                               // kOptNormalizeQ (folded into qplus and P) | kOptGdnBeta
 };
 template <typename E> hipError_t launch_intra_diag(const IntraDiagArgs<E>& a, int dk, int n_chunks, hipStream_t st);
 

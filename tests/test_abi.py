@@ -271,3 +271,15 @@ def test_diag_entry_points_validate():
     assert dec(dv=100) == E_SHAPE
     assert dec(S=0x6008) == E_ALIGN
     assert dec(B=0) == OK
+    # the option variants validate the same way, and refuse unknown bits
+    copt = lambda opts, **o: lib.kla_chunk_fwd_diag_opts(*[{**base, **o}[n] for n in names], opts)
+    assert copt(4) == E_SHAPE
+    assert copt(kla.KLA_OPT_NORMALIZE_Q, la=None) == E_NULL
+    assert copt(kla.KLA_OPT_NORMALIZE_Q | kla.KLA_OPT_GDN_BETA, N=0) == OK
+    dopt = lambda opts, **o: lib.kla_decode_step_diag_opts(
+        *[{**dict(q=0x1000, k=0x2000, v=0x3000, la=0x4000, eta=0x5000, eps=1e-6, S=0x6000, o=0x7000, B=2, H=2, dk=128,
+                  dv=128, dt=kla.KLA_BF16, st=None), **o}[n]
+          for n in ("q", "k", "v", "la", "eta", "eps", "S", "o", "B", "H", "dk", "dv", "dt", "st")], opts)
+    assert dopt(16) == E_SHAPE
+    assert dopt(kla.KLA_OPT_GDN_BETA, S=None) == E_NULL
+    assert dopt(kla.KLA_OPT_NORMALIZE_Q, B=0) == OK

@@ -140,3 +140,78 @@ def test_diag_no_tokens(kla):
                                    torch.zeros((2, 0, H), device="cuda"), 1e-6, h0=h0)
     torch.cuda.synchronize()
     assert o.shape[1] == 0 and torch.equal(hT, h0)
+
+
+@pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("nq,gdn", [(True, False), (False, True), (True, True)])
+@pytest.mark.parametrize("T,dk,dv,varlen", [(200, 128, 128, False), (130, 64, 256, False), (300, 128, 64, True)])
+def test_diag_chunk_options(kla, dt, nq, gdn, T, dk, dv, varlen):
+    """The option bits on the diagonal-gating forward: normalised read-out (with one zero query and queries of very
+    different lengths) and beta_t = eta_t, alone and together; fixed and packed batches."""
+    if varlen:
+        d = kla_inputs.varlen_inputs(4, 1, T, 2, dk, dv, dtype=dt, seed=460, h0_std=0.3)
+    else:
+        d = kla_inputs.chunk_inputs(2, T, 3, dk, dv, dtype=dt, seed=461 + T, h0_std=0.3)
+    if gdn:
+        d["k"] = (d["k"].float() / d["k"].float().norm(dim=-1, keepdim=True)).to(dt)      # keeps the plain delta rule stable
+    scale = torch.logspace(-1.5, 1.5, d["T"]).reshape(1, d["T"], 1, 1)
+    d["q"] = (d["q"].float() * scale).to(dt)
+    d["q"][0, 7, 1] = 0
+    lad = kla_inputs.diag_gates(d, 6, 1.0)
+    o, hT = kla.kla_chunk_fwd_diag(_cuda(d["q"]), _cuda(d["k"]), _cuda(d["v"]), _cuda(lad), _cuda(d["eta"]), d["eps"],
+                                   h0=_cuda(d["h0"]), cu_seqlens=_cuda(d["cu_seqlens"]), normalize_q=nq, gdn_beta=gdn)
+    torch.cuda.synchronize()
+    q, k, v = (kla_inputs.to_numpy_f32(d[x]) for x in "qkv")
+    ro, rh, _ = token_oracle.kla_recurrent_diag(q, k, v, lad.numpy(), d["eta"].numpy(), d["eps"], h0=d["h0"].numpy(),
+                                                cu_seqlens=None if d["cu_seqlens"] is None else d["cu_seqlens"].numpy(),
+                                                normalize_q=nq, gdn_beta=gdn)
+    o = o.float().cpu().numpy()
+    if nq:
+        assert np.all(o[0, 7, 1] == 0.0)
+    else:                                          # without the normalisation o scales with ||q||: compare row by row in those units
+        qn = np.linalg.norm(q.astype(np.float64), axis=-1, keepdims=True)
+        qn = np.where(qn == 0.0, 1.0, qn)
+        o, ro = o / qn, ro / qn
+    eo, eh = token_oracle.rel_err(o, ro), token_oracle.rel_err(hT.cpu().numpy(), rh)
+    print("   rel err o=%.3e hT=%.3e" % (eo, eh), flush=True)
+    assert eo <= TOL[dt] and eh <= TOL[dt]
+
+
+def test_diag_options_generic_scan_on_bf16(kla, monkeypatch):
+    monkeypatch.setenv("KLA_SCAN_IMPL", "generic")
+    d = kla_inputs.chunk_inputs(2, 200, 2, 128, 128, dtype=torch.bfloat16, seed=465, h0_std=0.3)
+    lad = kla_inputs.diag_gates(d, 7, 1.0)
+    o, hT = kla.kla_chunk_fwd_diag(_cuda(d["q"]), _cuda(d["k"]), _cuda(d["v"]), _cuda(lad), _cuda(d["eta"]), d["eps"],
+                                   h0=_cuda(d["h0"]), normalize_q=True)
+    torch.cuda.synchronize()
+    q, k, v = (kla_inputs.to_numpy_f32(d[x]) for x in "qkv")
+    ro, rh, _ = token_oracle.kla_recurrent_diag(q, k, v, lad.numpy(), d["eta"].numpy(), d["eps"], h0=d["h0"].numpy(),
+                                                normalize_q=True)
+    assert token_oracle.rel_err(o.float().cpu().numpy(), ro) <= TOL[torch.bfloat16]
+    assert token_oracle.rel_err(hT.cpu().numpy(), rh) <= TOL[torch.bfloat16]
+
+
+@pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("nq,gdn", [(True, False), (False, True), (True, True)])
+def test_diag_decode_options(kla, dt, nq, gdn):
+    d = kla_inputs.decode_inputs(3, 5, 4, 128, 128, dtype=dt, seed=470, state_std=1.0)
+    gen = torch.Generator().manual_seed(471)
+    lad = -torch.nn.functional.softplus(torch.randn((3, 5, 4, 128), generator=gen))
+    kk = d["k"]
+    if gdn:
+        kk = (kk.float() / kk.float().norm(dim=-1, keepdim=True)).to(dt)
+    qq = d["q"].clone()
+    qq[0, 2, 1] = 0
+    S = d["S"].cuda().clone()
+    Sref = d["S"].double().numpy()
+    for t in range(3):
+        o = kla.kla_decode_step_diag(_cuda(qq[t].contiguous()), _cuda(kk[t].contiguous()), _cuda(d["v"][t].contiguous()),
+                                     _cuda(lad[t].contiguous()), _cuda(d["eta"][t].contiguous()), d["eps"], S,
+                                     normalize_q=nq, gdn_beta=gdn)
+        ro, Sref = token_oracle.kla_decode_diag(kla_inputs.to_numpy_f32(qq[t]), kla_inputs.to_numpy_f32(kk[t]),
+                                                kla_inputs.to_numpy_f32(d["v"][t]), lad[t].numpy(), d["eta"][t].numpy(),
+                                                d["eps"], Sref, normalize_q=nq, gdn_beta=gdn)
+        assert token_oracle.rel_err(o.float().cpu().numpy(), ro) <= (1e-5 if dt == torch.float32 else 1e-2)
+        assert token_oracle.rel_err(S.cpu().numpy(), Sref) <= 1e-5
+        if nq and t == 0:
+            assert np.all(o[2, 1].float().cpu().numpy() == 0.0)

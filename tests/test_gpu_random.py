@@ -83,8 +83,10 @@ def test_random_cases(kla, block, monkeypatch):
                 continue                           # a handful of entries: bf16 rounding of single products decides (see DESIGN)
         else:
             lad = kla_inputs.diag_gates(d, seed % 1000, float(rng.choice([1.0, 0.1, 5.0])))
-            o, hT = kla.kla_chunk_fwd_diag(a[0], a[1], a[2], _c(lad), a[4], d["eps"], h0=_c(d["h0"]), cu_seqlens=_c(d["cu_seqlens"]))
-            ro, rh, _ = token_oracle.kla_recurrent_diag(n[0], n[1], n[2], lad.numpy(), n[4], d["eps"], h0=h0n, cu_seqlens=cu)
+            o, hT = kla.kla_chunk_fwd_diag(a[0], a[1], a[2], _c(lad), a[4], d["eps"], h0=_c(d["h0"]), cu_seqlens=_c(d["cu_seqlens"]),
+                                           normalize_q=nq, gdn_beta=gdn)
+            ro, rh, _ = token_oracle.kla_recurrent_diag(n[0], n[1], n[2], lad.numpy(), n[4], d["eps"], h0=h0n, cu_seqlens=cu,
+                                                        normalize_q=nq, gdn_beta=gdn)
             errs = {"o": token_oracle.rel_err(o.float().cpu().numpy(), ro), "hT": token_oracle.rel_err(hT.cpu().numpy(), rh)}
         print("    " + " ".join("%s=%.2e" % kv for kv in errs.items()), flush=True)
         for k, e in errs.items():
