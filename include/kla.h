@@ -17,8 +17,10 @@
  * Conventions for every entry point
  *   - All data pointers are DEVICE pointers unless a parameter says "host".
  *   - The caller owns every buffer and keeps it alive until the stream has
- *     passed the call.  The library allocates and frees nothing, keeps no global
- *     state, and is thread-safe.  Work is enqueued on `hip_stream`
+ *     passed the call.  The library allocates and frees nothing and is thread-safe; the
+ *     only state it keeps is, per device, the address of the scratch array of
+ *     kla_chunk_fwd_static (and it reads a few tuning variables from the environment, see
+ *     the workspace queries).  Work is enqueued on `hip_stream`
  *     (a hipStream_t, NULL = the default stream); the call returns without
  *     waiting for it.
  *   - Return value: KLA_OK or a negative kla_status.  A validation failure is
@@ -93,6 +95,30 @@ int kla_chunk_fwd(const void *q, const void *k, const void *v,
                   const int32_t *cu_seqlens_dev, const int32_t *cu_seqlens_host, int n_seq,
                   int N, int T, int H, int dk, int dv, int chunk, kla_dtype dt,
                   void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * kla_chunk_fwd for callers that cannot allocate device memory and have no workspace to hand over: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and error
+ * codes as kla_chunk_fwd (same kernels) without `workspace` / `workspace_bytes`: the per-chunk objects go to a
+ * fixed scratch array of KLA_STATIC_SCRATCH_BYTES that is part of the library's device image (every GPU the
+ * library is used on holds its own copy from the first use there until the process ends).  The call allocates
+ * and frees nothing, neither directly nor through another library.
+ *   - A problem whose kla_chunk_fwd_workspace_bytes(...) exceeds KLA_STATIC_SCRATCH_BYTES is refused with
+ *     KLA_ERR_WORKSPACE before anything is launched (32 MiB holds about 2 400 chunk-heads in bf16, e.g. one
+ *     sequence of 16 384 tokens with 8 heads; fp32 takes twice as much per chunk-head).
+ *   - The first call on a device looks up the device address of the array (one hipGetSymbolAddress, which may load
+ *     the library's code onto that device): make it outside any stream capture.  KLA_ERR_HIP if the lookup fails.
+ *   - All calls on one GPU share the one array: two calls that may overlap in time on the same GPU (different
+ *     streams, or different threads) race; calls on one stream, or on different GPUs, do not.  Nothing in the
+ *     array has to start at zero, every call writes what it reads.
+ */
+#define KLA_STATIC_SCRATCH_BYTES (32u << 20)
+int kla_chunk_fwd_static(const void *q, const void *k, const void *v,
+                         const float *log_alpha, const float *eta, float eps,
+                         const float *h0, void *o, float *hT,
+                         const int32_t *cu_seqlens_dev, const int32_t *cu_seqlens_host, int n_seq,
+                         int N, int T, int H, int dk, int dv, int chunk, kla_dtype dt,
+                         void *hip_stream);
 
 /*
  * One recurrent decode step (Algorithm 1 left panel) for B*H independent states.

@@ -27,6 +27,8 @@ _SIGNATURES = {
     "kla_chunk_fwd_workspace_bytes": (ctypes.c_size_t, [ctypes.c_int] * 6 + [ctypes.c_int, _ip, ctypes.c_int]),
     "kla_chunk_fwd": (ctypes.c_int, [_vp, _vp, _vp, _fp, _fp, ctypes.c_float, _fp, _vp, _fp, _ip, _ip, ctypes.c_int]
                       + [ctypes.c_int] * 6 + [ctypes.c_int, _vp, ctypes.c_size_t, _vp]),
+    "kla_chunk_fwd_static": (ctypes.c_int, [_vp, _vp, _vp, _fp, _fp, ctypes.c_float, _fp, _vp, _fp, _ip, _ip, ctypes.c_int]
+                             + [ctypes.c_int] * 6 + [ctypes.c_int, _vp]),
     "kla_chunk_fwd_opts": (ctypes.c_int, [_vp, _vp, _vp, _fp, _fp, ctypes.c_float, _fp, _vp, _fp, _ip, _ip, ctypes.c_int]
                            + [ctypes.c_int] * 6 + [ctypes.c_int, _vp, ctypes.c_size_t, _vp, ctypes.c_uint]),
     "kla_chunk_fwd_diag_workspace_bytes": (ctypes.c_size_t, [ctypes.c_int] * 6 + [ctypes.c_int, _ip, ctypes.c_int]),
@@ -161,6 +163,26 @@ def kla_chunk_fwd(q, k, v, log_alpha, eta, eps, h0=None, cu_seqlens=None, want_h
         rc = lib().kla_chunk_fwd(*args)
     if rc != 0:
         raise KlaError(rc, "kla_chunk_fwd")
+    return out, hT
+
+
+KLA_STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def kla_chunk_fwd_static(q, k, v, log_alpha, eta, eps, out, hT=None, h0=None, cu_seqlens=None, cu_seqlens_host=None,
+                         chunk=64):
+    """kla_chunk_fwd without a workspace and without any allocation (kla_chunk_fwd_static of the C ABI): the caller
+    passes `out` (and `hT` if wanted); the per-chunk objects go to the library's fixed scratch array, so the problem
+    must need at most KLA_STATIC_SCRATCH_BYTES of workspace.  For a packed batch pass cu_seqlens_host as well if the
+    call must not synchronise.  Returns (out, hT)."""
+    _dev(q, k, v, log_alpha, eta, h0, cu_seqlens, out, hT)
+    N, T, H, dk = q.shape
+    dv = v.shape[-1]
+    cu_host, cu_hp, n_seq = _host_cu(cu_seqlens, cu_seqlens_host)
+    rc = lib().kla_chunk_fwd_static(_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(eta), float(eps), _ptr(h0), _ptr(out),
+                                    _ptr(hT), _ptr(cu_seqlens), cu_hp, n_seq, N, T, H, dk, dv, chunk, _dt(q), _stream())
+    if rc != 0:
+        raise KlaError(rc, "kla_chunk_fwd_static")
     return out, hT
 
 

@@ -3,6 +3,8 @@
 #include <math.h>
 #include <stdlib.h>
 
+#include <mutex>
+
 #include "../../include/kla.h"
 #include "kla_kernels.hpp"
 
@@ -360,6 +362,30 @@ int chunk_fwd_diag_impl(const void* q, const void* k, const void* v, const float
     return kla::launch_scan_diag<E>(sa, dk, waves, st) == hipSuccess ? KLA_OK : KLA_ERR_HIP;
 }
 
+// ---- scratch of the entry point that allocates nothing (kla_chunk_fwd_static) --------------------------
+// A file-scope device array: every GPU the library runs on holds its own copy at its own address until the
+// process ends.  In host code the array's name is only a handle for hipGetSymbolAddress; the address that
+// kernels receive is looked up once per device, with that device current, and kept.
+constexpr size_t kStaticScratchBytes = (size_t)KLA_STATIC_SCRATCH_BYTES;
+constexpr int kMaxDevices = 64;
+__device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+std::mutex scratch_mutex;
+void* scratch_ptr[kMaxDevices];        // device address of `scratch` per device ordinal, NULL until looked up
+
+// Device address of this device's copy of `scratch` (first call on a device: one symbol lookup), or NULL.
+void* static_scratch()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
+        scratch_ptr[dev] = p;
+    }
+    return scratch_ptr[dev];
+}
+
 }  // namespace
 
 extern "C" {
@@ -387,14 +413,13 @@ size_t kla_chunk_fwd_workspace_bytes(int N, int T, int H, int dk, int dv, int ch
     return pl.total;
 }
 
-static int chunk_fwd_checked(const void* q, const void* k, const void* v, const float* log_alpha, const float* eta,
-                             float eps, const float* h0, void* o, float* hT, const int32_t* cu_seqlens_dev,
-                             const int32_t* cu_seqlens_host, int n_seq, int N, int T, int H, int dk, int dv, int chunk,
-                             kla_dtype dt, void* workspace, size_t workspace_bytes, void* hip_stream, int stages,
-                             unsigned opts)
+// Everything kla_chunk_fwd checks except its workspace; fills the plan.
+static int chunk_fwd_validate(const void* q, const void* k, const void* v, const float* log_alpha, const float* eta,
+                              float eps, const float* h0, void* o, float* hT, const int32_t* cu_seqlens_dev,
+                              const int32_t* cu_seqlens_host, int n_seq, int N, int T, int H, int dk, int dv, int chunk,
+                              kla_dtype dt, unsigned opts, Plan* pl)
 {
-    Plan pl;
-    const int rc = make_plan(N, T, H, dk, dv, chunk, (int)dt, cu_seqlens_host, n_seq, &pl);
+    const int rc = make_plan(N, T, H, dk, dv, chunk, (int)dt, cu_seqlens_host, n_seq, pl);
     if (rc != KLA_OK) return rc;
     if (!(eps >= 0.0f) || isinf(eps)) return KLA_ERR_SHAPE;
     if (opts & ~(unsigned)(KLA_OPT_NORMALIZE_Q | KLA_OPT_GDN_BETA)) return KLA_ERR_SHAPE;
@@ -402,11 +427,17 @@ static int chunk_fwd_checked(const void* q, const void* k, const void* v, const 
     if (n_seq == 0 && cu_seqlens_dev) return KLA_ERR_SHAPE;
     const bool any_tokens = (long)N * T > 0;
     if (any_tokens && (!q || !k || !v || !log_alpha || !eta || !o)) return KLA_ERR_NULL;
-    if (!workspace) return KLA_ERR_WORKSPACE;
-    if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0 || workspace_bytes < pl.total) return KLA_ERR_WORKSPACE;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(h0) || !aligned16(hT) ||
         (reinterpret_cast<uintptr_t>(log_alpha) & 3u) || (reinterpret_cast<uintptr_t>(eta) & 3u))
         return KLA_ERR_ALIGN;
+    return KLA_OK;
+}
+
+static int chunk_fwd_launch(const void* q, const void* k, const void* v, const float* log_alpha, const float* eta,
+                            float eps, const float* h0, void* o, float* hT, const int32_t* cu_seqlens_dev, int n_seq,
+                            int N, int T, int H, int dk, int dv, kla_dtype dt, const Plan& pl, void* workspace,
+                            void* hip_stream, int stages, unsigned opts)
+{
     if (pl.n_states == 0) return KLA_OK;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     char* ws = static_cast<char*>(workspace);
@@ -415,6 +446,22 @@ static int chunk_fwd_checked(const void* q, const void* k, const void* v, const 
                                       pl, ws, stages, nullptr, nullptr, nullptr, st, opts);
     return chunk_fwd_impl<float>(q, k, v, log_alpha, eta, eps, h0, o, hT, cu_seqlens_dev, n_seq, N, T, H, dk, dv, pl, ws,
                                  stages, nullptr, nullptr, nullptr, st, opts);
+}
+
+static int chunk_fwd_checked(const void* q, const void* k, const void* v, const float* log_alpha, const float* eta,
+                             float eps, const float* h0, void* o, float* hT, const int32_t* cu_seqlens_dev,
+                             const int32_t* cu_seqlens_host, int n_seq, int N, int T, int H, int dk, int dv, int chunk,
+                             kla_dtype dt, void* workspace, size_t workspace_bytes, void* hip_stream, int stages,
+                             unsigned opts)
+{
+    Plan pl;
+    const int rc = chunk_fwd_validate(q, k, v, log_alpha, eta, eps, h0, o, hT, cu_seqlens_dev, cu_seqlens_host, n_seq, N,
+                                      T, H, dk, dv, chunk, dt, opts, &pl);
+    if (rc != KLA_OK) return rc;
+    if (!workspace) return KLA_ERR_WORKSPACE;
+    if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0 || workspace_bytes < pl.total) return KLA_ERR_WORKSPACE;
+    return chunk_fwd_launch(q, k, v, log_alpha, eta, eps, h0, o, hT, cu_seqlens_dev, n_seq, N, T, H, dk, dv, dt, pl,
+                            workspace, hip_stream, stages, opts);
 }
 
 int kla_chunk_fwd(const void* q, const void* k, const void* v, const float* log_alpha, const float* eta, float eps,
@@ -433,6 +480,23 @@ int kla_chunk_fwd_opts(const void* q, const void* k, const void* v, const float*
 {
     return chunk_fwd_checked(q, k, v, log_alpha, eta, eps, h0, o, hT, cu_seqlens_dev, cu_seqlens_host, n_seq, N, T, H,
                              dk, dv, chunk, dt, workspace, workspace_bytes, hip_stream, 3, opts);
+}
+
+int kla_chunk_fwd_static(const void* q, const void* k, const void* v, const float* log_alpha, const float* eta,
+                         float eps, const float* h0, void* o, float* hT, const int32_t* cu_seqlens_dev,
+                         const int32_t* cu_seqlens_host, int n_seq, int N, int T, int H, int dk, int dv, int chunk,
+                         kla_dtype dt, void* hip_stream)
+{
+    Plan pl;
+    const int rc = chunk_fwd_validate(q, k, v, log_alpha, eta, eps, h0, o, hT, cu_seqlens_dev, cu_seqlens_host, n_seq, N,
+                                      T, H, dk, dv, chunk, dt, 0u, &pl);
+    if (rc != KLA_OK) return rc;
+    if (pl.total > kStaticScratchBytes) return KLA_ERR_WORKSPACE;      // refused before any HIP call
+    if (pl.n_states == 0) return KLA_OK;
+    void* ws = static_scratch();
+    if (!ws) return KLA_ERR_HIP;
+    return chunk_fwd_launch(q, k, v, log_alpha, eta, eps, h0, o, hT, cu_seqlens_dev, n_seq, N, T, H, dk, dv, dt, pl, ws,
+                            hip_stream, 3, 0u);
 }
 
 size_t kla_chunk_bwd_workspace_bytes(int N, int T, int H, int dk, int dv, int chunk, kla_dtype dt,
