@@ -109,7 +109,9 @@ def main():
     d = kla_inputs.config(2)
     N, T, H, dk, dv = d["N"], d["T"], d["H"], d["dk"], d["dv"]
     dev = {n: d[n].cuda() for n in ("q", "k", "v", "log_alpha", "eta")}
-    ws = torch.empty(kla.kla_chunk_fwd_workspace_bytes(N, T, H, dk, dv, torch.bfloat16), dtype=torch.uint8, device="cuda")
+    # the workspace of the two-kernel form: the default (fused) call uses none of it, the per-stage hooks all of it
+    ws = torch.empty(kla.kla_chunk_fwd_workspace_bytes(N, T, H, dk, dv, torch.bfloat16, tune=kla.tune(unfused=True)),
+                     dtype=torch.uint8, device="cuda")
     out = torch.empty((N, T, H, dv), dtype=torch.bfloat16, device="cuda")
     hT = torch.empty((N, H, dk, dv), dtype=torch.float32, device="cuda")
 

@@ -19,8 +19,7 @@
  *   - The caller owns every buffer and keeps it alive until the stream has
  *     passed the call.  The library allocates and frees nothing and is thread-safe; the
  *     only state it keeps is, per device, the address of the scratch array of
- *     kla_chunk_fwd_static (and it reads a few tuning variables from the environment, see
- *     the workspace queries).  Work is enqueued on `hip_stream`
+ *     kla_chunk_fwd_static; it reads nothing from the environment.  Work is enqueued on `hip_stream`
  *     (a hipStream_t, NULL = the default stream); the call returns without
  *     waiting for it.
  *   - Return value: KLA_OK or a negative kla_status.  A validation failure is
@@ -60,7 +59,8 @@ const char *kla_status_string(int code);
 /*
  * Bytes of device scratch kla_chunk_fwd needs for these sizes (0 on invalid sizes).  It covers the per-chunk
  * objects of eqs. (6)-(7) and, for a small bf16 batch of long sequences, the per-segment state maps of the
- * segment-parallel scan; ask again whenever a size, the element type or a tuning variable changes.
+ * segment-parallel scan (where the fused bf16 kernel runs, which keeps those objects on chip, only a token 256
+ * bytes); ask again whenever a size or the element type changes.
  * For a packed batch pass the host copy of cu_seqlens and n_seq > 0 (then N must be 1
  * and T the total token count); otherwise cu_seqlens_host = NULL, n_seq = 0.
  */
@@ -99,13 +99,14 @@ int kla_chunk_fwd(const void *q, const void *k, const void *v,
 /*
  * kla_chunk_fwd for callers that cannot allocate device memory and have no workspace to hand over: code under
  * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and error
- * codes as kla_chunk_fwd (same kernels) without `workspace` / `workspace_bytes`: the per-chunk objects go to a
- * fixed scratch array of KLA_STATIC_SCRATCH_BYTES that is part of the library's device image (every GPU the
- * library is used on holds its own copy from the first use there until the process ends).  The call allocates
- * and frees nothing, neither directly nor through another library.
+ * codes as kla_chunk_fwd (same kernels) without `workspace` / `workspace_bytes`: whatever kla_chunk_fwd would
+ * keep in its workspace - the per-chunk objects of the two-kernel form (fp32 inputs, wide value heads), the maps
+ * and states of the segment-parallel scan - goes to a fixed scratch array of KLA_STATIC_SCRATCH_BYTES that is part
+ * of the library's device image (every GPU the library is used on holds its own copy from the first use there
+ * until the process ends).  The call allocates and frees nothing, neither directly nor through another library.
  *   - A problem whose kla_chunk_fwd_workspace_bytes(...) exceeds KLA_STATIC_SCRATCH_BYTES is refused with
- *     KLA_ERR_WORKSPACE before anything is launched (32 MiB holds about 2 400 chunk-heads in bf16, e.g. one
- *     sequence of 16 384 tokens with 8 heads; fp32 takes twice as much per chunk-head).
+ *     KLA_ERR_WORKSPACE before anything is launched (32 MiB holds about 2 400 chunk-heads of the two-kernel form
+ *     in bf16, 1 200 in fp32; bf16 problems that run the fused kernel need none of it and are never refused).
  *   - The first call on a device looks up the device address of the array (one hipGetSymbolAddress, which may load
  *     the library's code onto that device): make it outside any stream capture.  KLA_ERR_HIP if the lookup fails.
  *   - All calls on one GPU share the one array: two calls that may overlap in time on the same GPU (different
@@ -145,6 +146,35 @@ int kla_decode_step(const void *q, const void *k, const void *v,
  */
 enum { KLA_OPT_NORMALIZE_Q = 1, KLA_OPT_GDN_BETA = 2 };
 
+/*
+ * Tuning fields of the same `opts` argument (bits 8..24), for tests and A/B measurements: every setting computes
+ * the same results up to rounding, 0 in a field is the library's own choice (the measured best), and a value
+ * outside a field's range is KLA_ERR_SHAPE.  They replace any reading of the environment: a call's behaviour
+ * depends on its arguments alone.  The workspace needed depends on some of them (segments, the generic and
+ * unfused forms), so pass the same `opts` to the *_workspace_bytes_opts query and to the call.
+ *   KLA_TUNE_SCAN_WAVES(n)     n = 1, 2, 4: compute waves (16 state columns each) per workgroup of the scan stage
+ *   KLA_TUNE_SCAN_SEGMENTS(n)  n = 1: never cut sequences for the segment-parallel scan; n = 2..16: cut into n
+ *   KLA_TUNE_GENERIC_SCAN / _INTRA / _BWD   bf16 inputs through the element-type-generic kernels of the fp32 path
+ *   KLA_TUNE_UNFUSED           bf16 forward as two kernels (intra-chunk stage, then scan) where one fused kernel would run
+ *   KLA_TUNE_DECODE_SLICE(n)   n = 32, 64, 128, 256: state columns per workgroup of the decode step
+ *   KLA_TUNE_DECODE_NT(n)      n = 0..3: bit 0 non-temporal state loads, bit 1 non-temporal state stores
+ */
+#define KLA_TUNE_SCAN_WAVES(n)    ((unsigned)((n) == 4 ? 3 : (n)) << 8)
+#define KLA_TUNE_SCAN_SEGMENTS(n) ((unsigned)(n) << 10)
+#define KLA_TUNE_GENERIC_SCAN     (1u << 15)
+#define KLA_TUNE_GENERIC_INTRA    (1u << 16)
+#define KLA_TUNE_GENERIC_BWD      (1u << 17)
+#define KLA_TUNE_DECODE_SLICE(n)  ((unsigned)((n) == 32 ? 1 : (n) == 64 ? 2 : (n) == 128 ? 3 : (n) == 256 ? 4 : 7) << 18)
+#define KLA_TUNE_DECODE_NT(n)     ((unsigned)((n) + 1) << 21)
+#define KLA_TUNE_UNFUSED          (1u << 24)
+
+/* Workspace of kla_chunk_fwd_opts(..., opts) / kla_chunk_bwd_opts(..., opts) (0 on invalid sizes or fields);
+ * the plain queries are these with opts = 0. */
+size_t kla_chunk_fwd_workspace_bytes_opts(int N, int T, int H, int dk, int dv, int chunk, kla_dtype dt,
+                                          const int32_t *cu_seqlens_host, int n_seq, unsigned opts);
+size_t kla_chunk_bwd_workspace_bytes_opts(int N, int T, int H, int dk, int dv, int chunk, kla_dtype dt,
+                                          const int32_t *cu_seqlens_host, int n_seq, unsigned opts);
+
 /* kla_chunk_fwd with options; kla_chunk_fwd(...) is kla_chunk_fwd_opts(..., 0).  Same workspace. */
 int kla_chunk_fwd_opts(const void *q, const void *k, const void *v,
                        const float *log_alpha, const float *eta, float eps,
@@ -180,7 +210,7 @@ int kla_decode_step_opts(const void *q, const void *k, const void *v,
  *               (dk x dv each, in dt) and three [N, T, H, dv] arrays in dt, so it is much larger than the
  *               forward's: about (2 * dk * dv / 64 + 3 * dv) * sizeof(dt) bytes per token and head.
  *               For a small bf16 batch of long sequences it also holds the per-segment maps and states of the
- *               segment-parallel sweeps (as in kla_chunk_fwd; ask again when a tuning variable changes).
+ *               segment-parallel sweeps (as in kla_chunk_fwd).
  * Outputs must not alias inputs or each other.  Same error codes and conventions as kla_chunk_fwd;
  * rows of the outputs are written for every token of every sequence, nothing else is touched.
  * The result is deterministic (no atomics).
@@ -266,7 +296,8 @@ int kla_beta(const void *k, const float *eta, float eps, float *beta,
  *   P_out   [n_chunks, H, 64, 64]  A o Q K^T (lower triangle incl. diagonal) of eq. (7)
  *   g_out   [n_chunks, H, 64]      chunk-local running sum of log_alpha (log gamma_i)
  * Rows and columns beyond a short last chunk are zero (g repeats its last value).
- * The values are those the second stage consumes (rounded to dt for dt = bf16).
+ * The values are those the second stage of the two-kernel form consumes (rounded to dt for dt = bf16); workspace
+ * from kla_chunk_fwd_workspace_bytes_opts(..., KLA_TUNE_UNFUSED) with dv = 64.
  */
 int kla_debug_intra_chunk(const void *q, const void *k,
                           const float *log_alpha, const float *eta, float eps,
@@ -276,7 +307,8 @@ int kla_debug_intra_chunk(const void *q, const void *k,
                           void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
- * Profiling hook: one stage of kla_chunk_fwd alone, so that each kernel can be timed between two
+ * Profiling hook: one stage of the two-kernel form of kla_chunk_fwd alone (KLA_TUNE_UNFUSED; workspace from
+ * kla_chunk_fwd_workspace_bytes_opts(..., KLA_TUNE_UNFUSED)), so that each kernel can be timed between two
  * events.  Arguments as in kla_chunk_fwd.  stage = 1: the intra-chunk stage (fills the workspace);
  * stage = 2: the scan stage (consumes a workspace that stage 1 filled for the same inputs, writes
  * o and hT).  Any other stage is KLA_ERR_SHAPE.

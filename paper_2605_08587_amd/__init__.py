@@ -25,6 +25,8 @@ _vp, _fp, _ip = ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p
 _SIGNATURES = {
     "kla_status_string": (ctypes.c_char_p, [ctypes.c_int]),
     "kla_chunk_fwd_workspace_bytes": (ctypes.c_size_t, [ctypes.c_int] * 6 + [ctypes.c_int, _ip, ctypes.c_int]),
+    "kla_chunk_fwd_workspace_bytes_opts": (ctypes.c_size_t, [ctypes.c_int] * 6 + [ctypes.c_int, _ip, ctypes.c_int, ctypes.c_uint]),
+    "kla_chunk_bwd_workspace_bytes_opts": (ctypes.c_size_t, [ctypes.c_int] * 6 + [ctypes.c_int, _ip, ctypes.c_int, ctypes.c_uint]),
     "kla_chunk_fwd": (ctypes.c_int, [_vp, _vp, _vp, _fp, _fp, ctypes.c_float, _fp, _vp, _fp, _ip, _ip, ctypes.c_int]
                       + [ctypes.c_int] * 6 + [ctypes.c_int, _vp, ctypes.c_size_t, _vp]),
     "kla_chunk_fwd_static": (ctypes.c_int, [_vp, _vp, _vp, _fp, _fp, ctypes.c_float, _fp, _vp, _fp, _ip, _ip, ctypes.c_int]
@@ -105,11 +107,79 @@ def _stream():
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 
+# Tuning fields of the `opts` argument (KLA_TUNE_* of include/kla.h): for tests and A/B measurements.  DEFAULT_TUNE is
+# what a call uses when it is given no `tune` of its own (binding-side convenience; the library keeps no such state).
+KLA_TUNE_GENERIC_SCAN, KLA_TUNE_GENERIC_INTRA, KLA_TUNE_GENERIC_BWD, KLA_TUNE_UNFUSED = 1 << 15, 1 << 16, 1 << 17, 1 << 24
+DEFAULT_TUNE = 0
+
+
+def tune(scan_waves=0, segments=0, generic_scan=False, generic_intra=False, generic_bwd=False, unfused=False,
+         decode_slice=0, decode_nt=None) -> int:
+    """The tuning fields as one integer for the `tune` argument of the calls below (0 = the library's own choice)."""
+    if scan_waves not in (0, 1, 2, 4) or not 0 <= segments <= 16 or decode_slice not in (0, 32, 64, 128, 256) \
+            or decode_nt not in (None, 0, 1, 2, 3):
+        raise ValueError("tuning value out of range")
+    bits = ((3 if scan_waves == 4 else scan_waves) << 8) | (segments << 10)
+    bits |= (KLA_TUNE_GENERIC_SCAN if generic_scan else 0) | (KLA_TUNE_GENERIC_INTRA if generic_intra else 0)
+    bits |= (KLA_TUNE_GENERIC_BWD if generic_bwd else 0) | (KLA_TUNE_UNFUSED if unfused else 0)
+    bits |= {0: 0, 32: 1, 64: 2, 128: 3, 256: 4}[decode_slice] << 18
+    bits |= 0 if decode_nt is None else (decode_nt + 1) << 21
+    return bits
+
+
+def _tune(t):
+    return DEFAULT_TUNE if t is None else int(t)
+
+
+def _check(name, t, shape, dtype):
+    """The C ABI sees raw pointers only: extents and element types are checked here, before anything is launched."""
+    if t is None:
+        return
+    if tuple(t.shape) != tuple(shape):
+        raise ValueError("%s must have shape %s, got %s" % (name, tuple(shape), tuple(t.shape)))
+    if t.dtype != dtype:
+        raise TypeError("%s must be %s, got %s" % (name, dtype, t.dtype))
+
+
+def _check_chunk(q, k, v, log_alpha, eta, h0, n_states, la_shape=None, **others):
+    """q defines N, T, H, dk and the element type; everything else must fit it.  others: name -> (tensor, shape, dtype)."""
+    if q.dim() != 4 or v.dim() != 4:
+        raise ValueError("q, k must be [N, T, H, dk] and v [N, T, H, dv]")
+    N, T, H, dk = q.shape
+    dv = v.shape[-1]
+    _dt(q)
+    _check("k", k, (N, T, H, dk), q.dtype)
+    _check("v", v, (N, T, H, dv), q.dtype)
+    _check("log_alpha", log_alpha, la_shape or (N, T, H), torch.float32)
+    _check("eta", eta, (N, T, H), torch.float32)
+    _check("h0", h0, (n_states, H, dk, dv), torch.float32)
+    for name, (t, shape, dtype) in others.items():
+        _check(name, t, shape, dtype)
+    return N, T, H, dk, dv
+
+
+def _check_decode(q, k, v, log_alpha, eta, S, out, la_shape=None):
+    if q.dim() != 3 or v.dim() != 3:
+        raise ValueError("q, k must be [B, H, dk] and v [B, H, dv]")
+    B, H, dk = q.shape
+    dv = v.shape[-1]
+    _dt(q)
+    _check("k", k, (B, H, dk), q.dtype)
+    _check("v", v, (B, H, dv), q.dtype)
+    _check("log_alpha", log_alpha, la_shape or (B, H), torch.float32)
+    _check("eta", eta, (B, H), torch.float32)
+    _check("S", S, (B, H, dk, dv), torch.float32)
+    _check("out", out, (B, H, dv), q.dtype)
+    return B, H, dk, dv
+
+
 def _host_cu(cu_seqlens, cu_seqlens_host=None):
     """Host copy of the sequence offsets.  Copying a device tensor synchronises: callers that must not (inside a
     stream capture, in a serving loop) pass the host copy they already have as cu_seqlens_host."""
     if cu_seqlens is None:
         return None, None, 0
+    if cu_seqlens.dtype != torch.int32 or cu_seqlens.dim() != 1 or cu_seqlens.numel() < 1:
+        raise TypeError("cu_seqlens must be a 1-d int32 tensor of n_seq + 1 offsets")
     src = cu_seqlens if cu_seqlens_host is None else cu_seqlens_host
     cu_host = src.detach().to("cpu", torch.int32).contiguous()
     if cu_host.numel() != cu_seqlens.numel():
@@ -117,33 +187,45 @@ def _host_cu(cu_seqlens, cu_seqlens_host=None):
     return cu_host, ctypes.c_void_p(cu_host.data_ptr()), cu_host.numel() - 1
 
 
-def kla_chunk_fwd_workspace_bytes(N, T, H, dk, dv, dtype, cu_seqlens=None, chunk=64) -> int:
+def kla_chunk_fwd_workspace_bytes(N, T, H, dk, dv, dtype, cu_seqlens=None, chunk=64, tune=None) -> int:
     cu_host, cu_hp, n_seq = _host_cu(cu_seqlens)
     dt = KLA_BF16 if dtype == torch.bfloat16 else KLA_F32
-    return int(lib().kla_chunk_fwd_workspace_bytes(N, T, H, dk, dv, chunk, dt, cu_hp, n_seq))
+    return int(lib().kla_chunk_fwd_workspace_bytes_opts(N, T, H, dk, dv, chunk, dt, cu_hp, n_seq, _tune(tune)))
 
 
 def _opts(normalize_q, gdn_beta) -> int:
     return (KLA_OPT_NORMALIZE_Q if normalize_q else 0) | (KLA_OPT_GDN_BETA if gdn_beta else 0)
 
 
+def _ws_bytes(t):
+    return 0 if t is None else t.numel() * t.element_size()
+
+
 def kla_chunk_fwd(q, k, v, log_alpha, eta, eps, h0=None, cu_seqlens=None, want_hT=True, workspace=None,
-                  out=None, hT=None, chunk=64, _stage=None, normalize_q=False, gdn_beta=False, cu_seqlens_host=None):
+                  out=None, hT=None, chunk=64, _stage=None, normalize_q=False, gdn_beta=False, cu_seqlens_host=None,
+                  tune=None):
     """Chunkwise forward.  q,k [N,T,H,dk], v [N,T,H,dv], gates [N,T,H] fp32; returns (o, hT).
 
     cu_seqlens: int32 device tensor [n_seq+1] for a packed batch (then N == 1); cu_seqlens_host: the same offsets
     as a CPU tensor, if the caller has them (saves the device-to-host copy, which synchronises).
     workspace / out / hT may be passed in to avoid allocations (e.g. inside a timed loop or a stream capture).
     normalize_q: o_t = S_t^T q_t / ||q_t||;  gdn_beta: beta_t = eta_t (kla_chunk_fwd_opts of the C ABI).
+    tune: tuning fields (see tune()); None = DEFAULT_TUNE.
     """
-    _dev(q, k, v, log_alpha, eta, h0, cu_seqlens, workspace, out, hT)
-    N, T, H, dk = q.shape
-    dv = v.shape[-1]
-    dt = _dt(q)
     cu_host, cu_hp, n_seq = _host_cu(cu_seqlens, cu_seqlens_host)
-    n_states = n_seq if n_seq > 0 else N
-    need = int(lib().kla_chunk_fwd_workspace_bytes(N, T, H, dk, dv, chunk, dt, cu_hp, n_seq))
+    n_states = n_seq if n_seq > 0 else q.shape[0]
+    N, T, H, dk, dv = _check_chunk(q, k, v, log_alpha, eta, h0, n_states,
+                                   out=(out, (q.shape[0], q.shape[1], q.shape[2], v.shape[-1]), q.dtype),
+                                   hT=(hT, (n_states, q.shape[2], q.shape[3], v.shape[-1]), torch.float32))
+    _dev(q, k, v, log_alpha, eta, h0, cu_seqlens, workspace, out, hT)
+    dt = _dt(q)
+    bits = _opts(normalize_q, gdn_beta) | _tune(tune)
+    if _stage is not None:
+        if normalize_q or gdn_beta:
+            raise ValueError("the single-stage hook takes no options")
+        bits = KLA_TUNE_UNFUSED
     if workspace is None:
+        need = int(lib().kla_chunk_fwd_workspace_bytes_opts(N, T, H, dk, dv, chunk, dt, cu_hp, n_seq, bits & ~3))
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
     if out is None:
         out = torch.empty((N, T, H, dv), dtype=q.dtype, device=q.device)
@@ -151,14 +233,11 @@ def kla_chunk_fwd(q, k, v, log_alpha, eta, eps, h0=None, cu_seqlens=None, want_h
         hT = torch.empty((n_states, H, dk, dv), dtype=torch.float32, device=q.device)
     args = (_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(eta), float(eps), _ptr(h0), _ptr(out),
             _ptr(hT), _ptr(cu_seqlens), cu_hp, n_seq, N, T, H, dk, dv, chunk, dt,
-            _ptr(workspace), workspace.numel() * workspace.element_size(), _stream())
-    opts = _opts(normalize_q, gdn_beta)
+            _ptr(workspace), _ws_bytes(workspace), _stream())
     if _stage is not None:
-        if opts:
-            raise ValueError("the single-stage hook takes no options")
         rc = lib().kla_debug_chunk_stage(*args, int(_stage))
-    elif opts:
-        rc = lib().kla_chunk_fwd_opts(*args, opts)
+    elif bits:
+        rc = lib().kla_chunk_fwd_opts(*args, bits)
     else:
         rc = lib().kla_chunk_fwd(*args)
     if rc != 0:
@@ -175,10 +254,14 @@ def kla_chunk_fwd_static(q, k, v, log_alpha, eta, eps, out, hT=None, h0=None, cu
     passes `out` (and `hT` if wanted); the per-chunk objects go to the library's fixed scratch array, so the problem
     must need at most KLA_STATIC_SCRATCH_BYTES of workspace.  For a packed batch pass cu_seqlens_host as well if the
     call must not synchronise.  Returns (out, hT)."""
-    _dev(q, k, v, log_alpha, eta, h0, cu_seqlens, out, hT)
-    N, T, H, dk = q.shape
-    dv = v.shape[-1]
     cu_host, cu_hp, n_seq = _host_cu(cu_seqlens, cu_seqlens_host)
+    n_states = n_seq if n_seq > 0 else q.shape[0]
+    N, T, H, dk, dv = _check_chunk(q, k, v, log_alpha, eta, h0, n_states,
+                                   out=(out, (q.shape[0], q.shape[1], q.shape[2], v.shape[-1]), q.dtype),
+                                   hT=(hT, (n_states, q.shape[2], q.shape[3], v.shape[-1]), torch.float32))
+    _dev(q, k, v, log_alpha, eta, h0, cu_seqlens, out, hT)
+    if out is None:
+        raise ValueError("kla_chunk_fwd_static allocates nothing: pass `out`")
     rc = lib().kla_chunk_fwd_static(_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(eta), float(eps), _ptr(h0), _ptr(out),
                                     _ptr(hT), _ptr(cu_seqlens), cu_hp, n_seq, N, T, H, dk, dv, chunk, _dt(q), _stream())
     if rc != 0:
@@ -187,17 +270,16 @@ def kla_chunk_fwd_static(q, k, v, log_alpha, eta, eps, out, hT=None, h0=None, cu
 
 
 def kla_chunk_fwd_diag(q, k, v, log_alpha, eta, eps, h0=None, cu_seqlens=None, want_hT=True, workspace=None,
-                       out=None, hT=None, chunk=64, cu_seqlens_host=None, normalize_q=False, gdn_beta=False):
+                       out=None, hT=None, chunk=64, cu_seqlens_host=None, normalize_q=False, gdn_beta=False, tune=None):
     """Chunkwise forward with diagonal gating: log_alpha is [N,T,H,dk] fp32 (one decay per key channel).
     Everything else, the options included, as kla_chunk_fwd; returns (o, hT)."""
-    _dev(q, k, v, log_alpha, eta, h0, cu_seqlens, workspace, out, hT)
-    N, T, H, dk = q.shape
-    dv = v.shape[-1]
-    if tuple(log_alpha.shape) != (N, T, H, dk):
-        raise ValueError("log_alpha must be [N, T, H, dk] for diagonal gating")
-    dt = _dt(q)
     cu_host, cu_hp, n_seq = _host_cu(cu_seqlens, cu_seqlens_host)
-    n_states = n_seq if n_seq > 0 else N
+    n_states = n_seq if n_seq > 0 else q.shape[0]
+    N, T, H, dk, dv = _check_chunk(q, k, v, log_alpha, eta, h0, n_states, la_shape=tuple(q.shape),
+                                   out=(out, (q.shape[0], q.shape[1], q.shape[2], v.shape[-1]), q.dtype),
+                                   hT=(hT, (n_states, q.shape[2], q.shape[3], v.shape[-1]), torch.float32))
+    _dev(q, k, v, log_alpha, eta, h0, cu_seqlens, workspace, out, hT)
+    dt = _dt(q)
     need = int(lib().kla_chunk_fwd_diag_workspace_bytes(N, T, H, dk, dv, chunk, dt, cu_hp, n_seq))
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
@@ -207,40 +289,37 @@ def kla_chunk_fwd_diag(q, k, v, log_alpha, eta, eps, h0=None, cu_seqlens=None, w
         hT = torch.empty((n_states, H, dk, dv), dtype=torch.float32, device=q.device)
     args = (_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(eta), float(eps), _ptr(h0), _ptr(out),
             _ptr(hT), _ptr(cu_seqlens), cu_hp, n_seq, N, T, H, dk, dv, chunk, dt,
-            _ptr(workspace), workspace.numel() * workspace.element_size(), _stream())
-    opts = _opts(normalize_q, gdn_beta)
-    rc = lib().kla_chunk_fwd_diag_opts(*args, opts) if opts else lib().kla_chunk_fwd_diag(*args)
+            _ptr(workspace), _ws_bytes(workspace), _stream())
+    bits = _opts(normalize_q, gdn_beta) | _tune(tune)
+    rc = lib().kla_chunk_fwd_diag_opts(*args, bits) if bits else lib().kla_chunk_fwd_diag(*args)
     if rc != 0:
         raise KlaError(rc, "kla_chunk_fwd_diag")
     return out, hT
 
 
-def kla_decode_step_diag(q, k, v, log_alpha, eta, eps, S, out=None, normalize_q=False, gdn_beta=False):
+def kla_decode_step_diag(q, k, v, log_alpha, eta, eps, S, out=None, normalize_q=False, gdn_beta=False, tune=None):
     """One decode step with diagonal gating: log_alpha is [B,H,dk]; S [B,H,dk,dv] fp32 is updated in place."""
+    B, H, dk, dv = _check_decode(q, k, v, log_alpha, eta, S, out, la_shape=tuple(q.shape))
     _dev(q, k, v, log_alpha, eta, S, out)
-    B, H, dk = q.shape
-    dv = v.shape[-1]
-    if tuple(log_alpha.shape) != (B, H, dk):
-        raise ValueError("log_alpha must be [B, H, dk] for diagonal gating")
     if out is None:
         out = torch.empty((B, H, dv), dtype=q.dtype, device=q.device)
     args = (_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(eta), float(eps), _ptr(S), _ptr(out), B, H, dk, dv, _dt(q),
             _stream())
-    opts = _opts(normalize_q, gdn_beta)
-    rc = lib().kla_decode_step_diag_opts(*args, opts) if opts else lib().kla_decode_step_diag(*args)
+    bits = _opts(normalize_q, gdn_beta) | _tune(tune)
+    rc = lib().kla_decode_step_diag_opts(*args, bits) if bits else lib().kla_decode_step_diag(*args)
     if rc != 0:
         raise KlaError(rc, "kla_decode_step_diag")
     return out
 
 
-def kla_chunk_bwd_workspace_bytes(N, T, H, dk, dv, dtype, cu_seqlens=None, chunk=64) -> int:
+def kla_chunk_bwd_workspace_bytes(N, T, H, dk, dv, dtype, cu_seqlens=None, chunk=64, tune=None) -> int:
     cu_host, cu_hp, n_seq = _host_cu(cu_seqlens)
     dt = KLA_BF16 if dtype == torch.bfloat16 else KLA_F32
-    return int(lib().kla_chunk_bwd_workspace_bytes(N, T, H, dk, dv, chunk, dt, cu_hp, n_seq))
+    return int(lib().kla_chunk_bwd_workspace_bytes_opts(N, T, H, dk, dv, chunk, dt, cu_hp, n_seq, _tune(tune)))
 
 
 def kla_chunk_bwd(q, k, v, log_alpha, eta, eps, d_o, h0=None, d_hT=None, cu_seqlens=None, want_dh0=True,
-                  workspace=None, out=None, chunk=64, gdn_beta=False, normalize_q=False, cu_seqlens_host=None):
+                  workspace=None, out=None, chunk=64, gdn_beta=False, normalize_q=False, cu_seqlens_host=None, tune=None):
     """Backward of kla_chunk_fwd: gradients of sum <d_o, o> + sum <d_hT, hT>.  gdn_beta, normalize_q: of the forward
     with the same options (kla_chunk_bwd_opts of the C ABI).
 
@@ -248,16 +327,22 @@ def kla_chunk_bwd(q, k, v, log_alpha, eta, eps, d_o, h0=None, d_hT=None, cu_seql
     Returns a dict: dq, dk, dv (dtype of q), dlog_alpha, deta (fp32 [N,T,H]), dh0 (fp32, or None).
     `out` may hold preallocated tensors under the same names; `workspace` a uint8 buffer.
     """
-    _dev(q, k, v, log_alpha, eta, d_o, h0, d_hT, cu_seqlens, workspace)
-    N, T, H, dk = q.shape
-    dv = v.shape[-1]
-    dt = _dt(q)
     cu_host, cu_hp, n_seq = _host_cu(cu_seqlens, cu_seqlens_host)
-    n_states = n_seq if n_seq > 0 else N
-    need = int(lib().kla_chunk_bwd_workspace_bytes(N, T, H, dk, dv, chunk, dt, cu_hp, n_seq))
-    if workspace is None:
-        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+    n_states = n_seq if n_seq > 0 else q.shape[0]
     out = dict(out or {})
+    sq, sv, sg, ss = tuple(q.shape), tuple(q.shape[:3]) + (v.shape[-1],), tuple(q.shape[:3]), (n_states, q.shape[2], q.shape[3], v.shape[-1])
+    N, T, H, dk, dv = _check_chunk(q, k, v, log_alpha, eta, h0, n_states, d_o=(d_o, sv, q.dtype), d_hT=(d_hT, ss, torch.float32),
+                                   dq=(out.get("dq"), sq, q.dtype), dk=(out.get("dk"), sq, q.dtype),
+                                   dv=(out.get("dv"), sv, q.dtype), dlog_alpha=(out.get("dlog_alpha"), sg, torch.float32),
+                                   deta=(out.get("deta"), sg, torch.float32), dh0=(out.get("dh0"), ss, torch.float32))
+    if d_o is None:
+        raise ValueError("d_o is required")
+    _dev(q, k, v, log_alpha, eta, d_o, h0, d_hT, cu_seqlens, workspace, *out.values())
+    dt = _dt(q)
+    bits = _opts(normalize_q, gdn_beta) | _tune(tune)
+    if workspace is None:
+        need = int(lib().kla_chunk_bwd_workspace_bytes_opts(N, T, H, dk, dv, chunk, dt, cu_hp, n_seq, bits & ~3))
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
     for name, like in (("dq", q), ("dk", k), ("dv", v)):
         if name not in out:
             out[name] = torch.empty_like(like)
@@ -266,35 +351,33 @@ def kla_chunk_bwd(q, k, v, log_alpha, eta, eps, d_o, h0=None, d_hT=None, cu_seql
             out[name] = torch.empty((N, T, H), dtype=torch.float32, device=q.device)
     if "dh0" not in out:
         out["dh0"] = torch.empty((n_states, H, dk, dv), dtype=torch.float32, device=q.device) if want_dh0 else None
-    _dev(*out.values())
     args = (_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(eta), float(eps), _ptr(h0), _ptr(d_o),
             _ptr(d_hT), _ptr(out["dq"]), _ptr(out["dk"]), _ptr(out["dv"]), _ptr(out["dlog_alpha"]),
             _ptr(out["deta"]), _ptr(out["dh0"]), _ptr(cu_seqlens), cu_hp, n_seq, N, T, H, dk, dv, chunk,
-            dt, _ptr(workspace), workspace.numel() * workspace.element_size(), _stream())
-    opts = _opts(normalize_q, gdn_beta)
-    rc = lib().kla_chunk_bwd_opts(*args, opts) if opts else lib().kla_chunk_bwd(*args)
+            dt, _ptr(workspace), _ws_bytes(workspace), _stream())
+    rc = lib().kla_chunk_bwd_opts(*args, bits) if bits else lib().kla_chunk_bwd(*args)
     if rc != 0:
         raise KlaError(rc, "kla_chunk_bwd")
     return out
 
 
 def kla_debug_chunk_stage(stage, q, k, v, log_alpha, eta, eps, workspace, out, hT=None, h0=None, cu_seqlens=None):
-    """Profiling hook: stage 1 (intra-chunk) or stage 2 (scan) of kla_chunk_fwd alone, on preallocated buffers."""
+    """Profiling hook: stage 1 (intra-chunk) or stage 2 (scan) of the two-kernel form of kla_chunk_fwd alone, on
+    preallocated buffers; the workspace is that of kla_chunk_fwd_workspace_bytes(..., tune=tune(unfused=True))."""
     return kla_chunk_fwd(q, k, v, log_alpha, eta, eps, h0=h0, cu_seqlens=cu_seqlens, want_hT=hT is not None,
                          workspace=workspace, out=out, hT=hT, _stage=stage)
 
 
-def kla_decode_step(q, k, v, log_alpha, eta, eps, S, out=None, normalize_q=False, gdn_beta=False):
+def kla_decode_step(q, k, v, log_alpha, eta, eps, S, out=None, normalize_q=False, gdn_beta=False, tune=None):
     """One decode step; S [B,H,dk,dv] fp32 is updated in place; returns o [B,H,dv].  Options as in kla_chunk_fwd."""
+    B, H, dk, dv = _check_decode(q, k, v, log_alpha, eta, S, out)
     _dev(q, k, v, log_alpha, eta, S, out)
-    B, H, dk = q.shape
-    dv = v.shape[-1]
     if out is None:
         out = torch.empty((B, H, dv), dtype=q.dtype, device=q.device)
     args = (_ptr(q), _ptr(k), _ptr(v), _ptr(log_alpha), _ptr(eta), float(eps), _ptr(S), _ptr(out),
             B, H, dk, dv, _dt(q), _stream())
-    opts = _opts(normalize_q, gdn_beta)
-    rc = lib().kla_decode_step_opts(*args, opts) if opts else lib().kla_decode_step(*args)
+    bits = _opts(normalize_q, gdn_beta) | _tune(tune)
+    rc = lib().kla_decode_step_opts(*args, bits) if bits else lib().kla_decode_step(*args)
     if rc != 0:
         raise KlaError(rc, "kla_decode_step")
     return out
@@ -302,9 +385,12 @@ def kla_decode_step(q, k, v, log_alpha, eta, eps, S, out=None, normalize_q=False
 
 def kla_beta(k, eta, eps, out=None):
     """beta = eta / (||k||^2 + eps) for k [..., dk], eta [...]; returns fp32 [...]."""
-    _dev(k, eta, out)
+    _dt(k)
     dk = k.shape[-1]
     n = k.numel() // dk
+    _check("eta", eta, tuple(k.shape[:-1]), torch.float32)
+    _check("out", out, tuple(k.shape[:-1]), torch.float32)
+    _dev(k, eta, out)
     if out is None:
         out = torch.empty(k.shape[:-1], dtype=torch.float32, device=k.device)
     rc = lib().kla_beta(_ptr(k), _ptr(eta), float(eps), _ptr(out), n, dk, _dt(k), _stream())
@@ -315,15 +401,20 @@ def kla_beta(k, eta, eps, out=None):
 
 def kla_debug_intra_chunk(q, k, log_alpha, eta, eps, cu_seqlens=None, chunk=64):
     """Test hook: (Tb, P, g) of every chunk as fp32 [n_chunks, H, 64, 64] / [n_chunks, H, 64]."""
-    _dev(q, k, log_alpha, eta, cu_seqlens)
+    if q.dim() != 4:
+        raise ValueError("q, k must be [N, T, H, dk]")
     N, T, H, dk = q.shape
     dt = _dt(q)
+    _check("k", k, (N, T, H, dk), q.dtype)
+    _check("log_alpha", log_alpha, (N, T, H), torch.float32)
+    _check("eta", eta, (N, T, H), torch.float32)
+    _dev(q, k, log_alpha, eta, cu_seqlens)
     cu_host, cu_hp, n_seq = _host_cu(cu_seqlens)
     if n_seq > 0:
         n_chunks = int(((cu_host[1:] - cu_host[:-1] + 63) // 64).sum())
     else:
         n_chunks = N * ((T + 63) // 64)
-    need = int(lib().kla_chunk_fwd_workspace_bytes(N, T, H, dk, 64, chunk, dt, cu_hp, n_seq))
+    need = int(lib().kla_chunk_fwd_workspace_bytes_opts(N, T, H, dk, 64, chunk, dt, cu_hp, n_seq, KLA_TUNE_UNFUSED))
     ws = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
     Tb = torch.zeros((n_chunks, H, 64, 64), dtype=torch.float32, device=q.device)
     P = torch.zeros_like(Tb)

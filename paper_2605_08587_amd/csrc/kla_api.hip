@@ -1,7 +1,7 @@
 // C ABI of the library (declared in include/kla.h): argument validation, workspace carving and
-// launch sequencing.  No allocation, no global state; everything is enqueued on the caller's stream.
+// launch sequencing.  No allocation, no state but the per-device address of the static scratch array, nothing read
+// from the environment; everything is enqueued on the caller's stream.
 #include <math.h>
-#include <stdlib.h>
 
 #include <mutex>
 
@@ -21,26 +21,55 @@ inline size_t elem_bytes(int dt) { return dt == KLA_BF16 ? 2 : 4; }
 
 static_assert(KLA_OPT_NORMALIZE_Q == (int)kla::kOptNormalizeQ && KLA_OPT_GDN_BETA == (int)kla::kOptGdnBeta, "option bits");
 
+// The tuning fields of the `opts` argument (KLA_TUNE_* in include/kla.h), decoded.  Zero everywhere = the library's choice.
+struct Tune {
+    int scan_waves = 0;      // 1, 2, 4 compute waves per scan workgroup
+    int segments = 0;        // 1 = never cut sequences into segments, n = cut into n
+    bool generic_scan = false, generic_intra = false, generic_bwd = false, unfused = false;
+    int decode_slice = 0;    // 32, 64, 128, 256 state columns per decode workgroup
+    int decode_nt = -1;      // bit 0: non-temporal state loads, bit 1: non-temporal state stores
+};
+constexpr unsigned kOptMask = KLA_OPT_NORMALIZE_Q | KLA_OPT_GDN_BETA;
+constexpr unsigned kTuneMask = 0x01ffff00u;
+
+bool parse_tune(unsigned opts, Tune* t)
+{
+    if (opts & ~(kOptMask | kTuneMask)) return false;
+    const unsigned w = (opts >> 8) & 3u, sg = (opts >> 10) & 31u, ds = (opts >> 18) & 7u, nt = (opts >> 21) & 7u;
+    if (sg > 16 || ds > 4 || nt > 4) return false;
+    t->scan_waves = w == 0 ? 0 : (w == 3 ? 4 : (int)w);
+    t->segments = (int)sg;
+    t->generic_scan = (opts & KLA_TUNE_GENERIC_SCAN) != 0;
+    t->generic_intra = (opts & KLA_TUNE_GENERIC_INTRA) != 0;
+    t->generic_bwd = (opts & KLA_TUNE_GENERIC_BWD) != 0;
+    t->unfused = (opts & KLA_TUNE_UNFUSED) != 0;
+    t->decode_slice = ds == 0 ? 0 : 16 << ds;
+    t->decode_nt = nt == 0 ? -1 : (int)nt - 1;
+    return true;
+}
+
 struct Plan {
     long n_chunks;       // over all sequences
     int n_states;        // sequences
     size_t off_T, off_P, off_G, off_C, off_M, off_S, total;
     int seg_G, seg_Lc;   // segment-parallel scan: segments per sequence (1 = off) and chunks per segment
+    int waves;           // compute waves per scan workgroup (of the unsegmented scan)
+    bool fused;          // bf16 only: one kernel, no intra-chunk stage, nothing in the workspace
+    Tune tune;
 };
 
 // Segments per sequence for the scan stage.  A small fixed-length bf16 batch of long sequences (at most 128
 // sixteen-column chains, at least 64 chunks) is cut so that about 256 workgroups of two chains run (measured
 // on one 65K-token sequence of 8 heads: 1.24 ms unsegmented, 0.70 ms with 4 segments, 0.57 ms with 8, 0.71 ms
-// with 16); KLA_SCAN_SEGMENTS = n forces n (1 = never).  Returns the number of non-empty segments and sets the chunks per segment.
-int plan_segments(int N, int NT, int H, int dv, int dt, int n_seq, int* Lc)
+// with 16); the tuning field KLA_TUNE_SCAN_SEGMENTS(n) forces n (1 = never).  Returns the number of non-empty segments and sets the chunks per segment.
+int plan_segments(int N, int NT, int H, int dv, int dt, int n_seq, const Tune& tune, int* Lc)
 {
     *Lc = NT;
     if (dt != KLA_BF16 || n_seq > 0 || N <= 0 || NT < 2) return 1;
-    { const char* impl = getenv("KLA_SCAN_IMPL"); if (impl && impl[0] == 'g') return 1; }   // generic kernels: never
+    if (tune.generic_scan) return 1;                 // generic kernels: never
     const long groups = (long)N * H * (dv / 16);
     int want = 1;
-    const char* env = getenv("KLA_SCAN_SEGMENTS");
-    if (env && atoi(env) >= 1) want = atoi(env) > 16 ? 16 : atoi(env);
+    if (tune.segments >= 1) want = tune.segments;
     else if (groups <= 128 && NT >= 64) {
         // up to 512 sixteen-column chains (256 workgroups of two compute waves), segments of at least 16 chunks
         want = 1;
@@ -55,9 +84,12 @@ int plan_segments(int N, int NT, int H, int dv, int dt, int n_seq, int* Lc)
     return G;
 }
 
+int scan_waves(int n_chains, int dv, int dt, const Tune& tune);
+
 // Validates the size arguments shared by the chunk entry points and lays out the workspace.
-int make_plan(int N, int T, int H, int dk, int dv, int chunk, int dt, const int32_t* cu_host, int n_seq, Plan* p)
+int make_plan(int N, int T, int H, int dk, int dv, int chunk, int dt, const int32_t* cu_host, int n_seq, unsigned opts, Plan* p)
 {
+    if (!parse_tune(opts, &p->tune)) return KLA_ERR_SHAPE;
     if (!dt_ok(dt)) return KLA_ERR_DTYPE;
     if (N < 0 || T < 0 || H <= 0 || n_seq < 0 || !dk_ok(dk) || !dv_ok(dv) || chunk != 64) return KLA_ERR_SHAPE;
     long n_chunks = 0;
@@ -85,20 +117,25 @@ int make_plan(int N, int T, int H, int dk, int dv, int chunk, int dt, const int3
     p->off_G = round256((size_t)n_chunks * H * (2 * half + 768));   // + three vectors of 64 fp32 (see kla_mma.hpp)
     p->off_C = round256(p->off_G + (size_t)n_chunks * H * 128 * sizeof(float));      // g and 1/||q||
     p->off_M = round256(p->off_C + (size_t)(n_seq + 1) * sizeof(int32_t));
-    p->seg_G = plan_segments(N, (T + 63) / 64, H, dv, dt, n_seq, &p->seg_Lc);
+    p->seg_G = plan_segments(N, (T + 63) / 64, H, dv, dt, n_seq, p->tune, &p->seg_Lc);
     // per (sequence, head): G - 1 maps [N | M] and G incoming states, fp32
     const size_t maps = p->seg_G > 1 ? (size_t)N * (p->seg_G - 1) * H * dk * (dv + dk) * sizeof(float) : 0;
     const size_t states = p->seg_G > 1 ? (size_t)N * p->seg_G * H * dk * dv * sizeof(float) : 0;
     p->off_S = round256(p->off_M + maps);
     p->total = round256(p->off_S + states);
+    p->waves = scan_waves(p->n_states * H, dv, dt, p->tune);
+    // bf16, a plain scan of at most two compute waves per workgroup: the fused kernel, which keeps the per-chunk
+    // objects on chip and needs nothing of the workspace (a token size is still reported and asked for)
+    p->fused = dt == KLA_BF16 && p->seg_G <= 1 && p->waves <= 2 && !p->tune.unfused && !p->tune.generic_scan &&
+               !p->tune.generic_intra;
+    if (p->fused) p->total = 256;
     return KLA_OK;
 }
 
-int scan_waves(int n_chains, int dv, int dt)
+int scan_waves(int n_chains, int dv, int dt, const Tune& tune)
 {
     int w;
-    const char* env = getenv("KLA_SCAN_WAVES");   // tuning knob: 1, 2 or 4 waves (16 state columns each) per workgroup
-    if (env && (atoi(env) == 1 || atoi(env) == 2 || atoi(env) == 4)) w = atoi(env);
+    if (tune.scan_waves) w = tune.scan_waves;        // tuning field: 1, 2 or 4 waves (16 state columns each) per workgroup
     else {
         // enough workgroups to cover the 256 CUs, else the widest slice that still gives >= 2 waves of loaders
         // workgroups for w waves: chains8 * dv / (16 w).  Wide slices halve the operand re-reads but need
@@ -124,19 +161,31 @@ int chunk_fwd_impl(const void* q, const void* k, const void* v, const float* log
     int* chunk_off = reinterpret_cast<int*>(ws + pl.off_C);
     const int NT = (T + 63) / 64;
     const bool intra = (stages & 1) != 0, scan = (stages & 2) != 0, unpack = (stages & 4) != 0;
-    if (intra && n_seq > 0 && kla::launch_chunk_offsets(cu_dev, n_seq, chunk_off, st) != hipSuccess) return KLA_ERR_HIP;
 
     kla::IntraArgs<E> ia;
     ia.q = static_cast<const E*>(q); ia.k = static_cast<const E*>(k);
     ia.log_alpha = log_alpha; ia.eta = eta; ia.eps = eps;
     ia.cu_seqlens = n_seq > 0 ? cu_dev : nullptr; ia.chunk_off = chunk_off; ia.n_seq = n_seq;
     ia.T = T; ia.NT = NT; ia.H = H;
-    ia.wsT = wsT; ia.wsP = wsP; ia.wsG = wsG; ia.opts = opts;
+    ia.wsT = wsT; ia.wsP = wsP; ia.wsG = wsG; ia.opts = opts;   // option bits only (the callers strip the tuning fields)
+    if constexpr (sizeof(E) == 2) {
+        if (stages == 3 && pl.fused) {
+            kla::ScanArgs<E> fa;
+            fa.q = static_cast<const E*>(q); fa.k = static_cast<const E*>(k); fa.v = static_cast<const E*>(v);
+            fa.h0 = h0; fa.o = static_cast<E*>(o); fa.hT = hT;
+            fa.cu_seqlens = n_seq > 0 ? cu_dev : nullptr; fa.chunk_off = nullptr; fa.n_seq = n_seq;
+            fa.N = N; fa.T = T; fa.NT = NT; fa.H = H; fa.dv = dv;
+            fa.wsT = nullptr; fa.wsP = nullptr; fa.wsG = nullptr; fa.opts = opts;
+            fa.seg_G = 0; fa.seg_Lc = 0; fa.kt_src = nullptr; fa.gc_vec = nullptr;
+            fa.log_alpha = log_alpha; fa.eta = eta; fa.eps = eps;
+            return kla::launch_scan_fused_bf16(fa, dk, pl.waves, st) == hipSuccess ? KLA_OK : KLA_ERR_HIP;
+        }
+    }
+    if (intra && n_seq > 0 && kla::launch_chunk_offsets(cu_dev, n_seq, chunk_off, st) != hipSuccess) return KLA_ERR_HIP;
     if (intra) {
         bool done = false;
         if constexpr (sizeof(E) == 2) {
-            const char* impl = getenv("KLA_INTRA_IMPL");   // "generic": the element-type-generic kernel (A/B testing)
-            if (!(impl && impl[0] == 'g')) {
+            if (!pl.tune.generic_intra) {                // else the element-type-generic kernel (A/B testing)
                 if (kla::launch_intra_bf16(ia, dk, (int)pl.n_chunks, st) != hipSuccess) return KLA_ERR_HIP;
                 done = true;
             }
@@ -153,6 +202,7 @@ int chunk_fwd_impl(const void* q, const void* k, const void* v, const float* log
     sa.N = N; sa.T = T; sa.NT = NT; sa.H = H; sa.dv = dv;
     sa.wsT = wsT; sa.wsP = wsP; sa.wsG = wsG; sa.opts = opts;
     sa.seg_G = 0; sa.seg_Lc = 0; sa.kt_src = nullptr; sa.gc_vec = nullptr;
+    sa.log_alpha = log_alpha; sa.eta = eta; sa.eps = eps;
     if constexpr (sizeof(E) == 2) {
         if (pl.seg_G > 1) {
             // segment-parallel scan: maps of all segments but the last, their prefix composition, then every
@@ -163,17 +213,16 @@ int chunk_fwd_impl(const void* q, const void* k, const void* v, const float* log
             if (kla::launch_segment_maps_bf16(sa, dk, maps, st) != hipSuccess) return KLA_ERR_HIP;
             if (kla::launch_segment_combine(h0, maps, seg_state, N, H, dk, dv, pl.seg_G, st) != hipSuccess) return KLA_ERR_HIP;
             sa.h0 = seg_state; sa.hT = seg_state;
-            const int wseg = scan_waves(pl.n_states * pl.seg_G * H, dv, KLA_BF16);
+            const int wseg = scan_waves(pl.n_states * pl.seg_G * H, dv, KLA_BF16, pl.tune);
             if (kla::launch_scan_bf16(sa, dk, wseg, st) != hipSuccess) return KLA_ERR_HIP;
             if (hT && kla::launch_segment_gather(seg_state, hT, N, H, dk, dv, pl.seg_G, pl.seg_G - 1, st) != hipSuccess)
                 return KLA_ERR_HIP;
             return KLA_OK;
         }
     }
-    const int waves = scan_waves(pl.n_states * H, dv, sizeof(E) == 2 ? KLA_BF16 : KLA_F32);
+    const int waves = pl.waves;
     if constexpr (sizeof(E) == 2) {
-        const char* impl = getenv("KLA_SCAN_IMPL");   // "generic": the element-type-generic kernel (A/B testing)
-        if (!(impl && impl[0] == 'g'))
+        if (!pl.tune.generic_scan)                       // else the element-type-generic kernel (A/B testing)
             return kla::launch_scan_bf16(sa, dk, waves, st) == hipSuccess ? KLA_OK : KLA_ERR_HIP;
     }
     if (kla::launch_scan<E>(sa, dk, waves, st) != hipSuccess) return KLA_ERR_HIP;
@@ -189,9 +238,10 @@ struct BwdPlan {
     size_t off_maps, off_segS, off_segG, off_segB;
 };
 
-int make_bwd_plan(int N, int T, int H, int dk, int dv, int chunk, int dt, const int32_t* cu_host, int n_seq, BwdPlan* p)
+int make_bwd_plan(int N, int T, int H, int dk, int dv, int chunk, int dt, const int32_t* cu_host, int n_seq, unsigned opts,
+                  BwdPlan* p)
 {
-    const int rc = make_plan(N, T, H, dk, dv, chunk, dt, cu_host, n_seq, &p->base);
+    const int rc = make_plan(N, T, H, dk, dv, chunk, dt, cu_host, n_seq, opts, &p->base);
     if (rc != KLA_OK) return rc;
     const size_t half = (size_t)384 * 8 * elem_bytes(dt);
     const size_t ch = (size_t)p->base.n_chunks * H;
@@ -231,11 +281,8 @@ int chunk_bwd_impl(const void* q, const void* k, const void* v, const float* log
     ia.cu_seqlens = n_seq > 0 ? cu_dev : nullptr; ia.chunk_off = chunk_off; ia.n_seq = n_seq;
     ia.T = T; ia.NT = NT; ia.H = H;
     ia.wsT = reinterpret_cast<E*>(ws + pl.off_rec); ia.wsP = nullptr; ia.wsG = nullptr; ia.opts = opts;
-    bool fast = false;                                // bf16: the specialised kernels, unless KLA_BWD_IMPL=generic (A/B testing)
-    if constexpr (sizeof(E) == 2) {
-        const char* impl = getenv("KLA_BWD_IMPL");
-        fast = !(impl && impl[0] == 'g');
-    }
+    bool fast = false;                                // bf16: the specialised kernels, unless the generic ones are asked for (A/B testing)
+    if constexpr (sizeof(E) == 2) fast = !pl.base.tune.generic_bwd;
     if constexpr (sizeof(E) == 2) {
         if (fast && kla::launch_intra_bwd_bf16(ia, dk, (int)pl.base.n_chunks, st) != hipSuccess) return KLA_ERR_HIP;
     }
@@ -313,9 +360,11 @@ struct DiagPlan {
     size_t off_kp, off_qp, off_kt, off_gc, total;
 };
 
-int make_diag_plan(int N, int T, int H, int dk, int dv, int chunk, int dt, const int32_t* cu_host, int n_seq, DiagPlan* p)
+int make_diag_plan(int N, int T, int H, int dk, int dv, int chunk, int dt, const int32_t* cu_host, int n_seq, unsigned opts,
+                   DiagPlan* p)
 {
-    const int rc = make_plan(N, T, H, dk, dv, chunk, dt, cu_host, n_seq, &p->base);
+    // the layout of the two-kernel forward (the fused kernel has no diagonal-gating variant), no segments
+    const int rc = make_plan(N, T, H, dk, dv, chunk, dt, cu_host, n_seq, (opts & ~(31u << 10)) | KLA_TUNE_UNFUSED | KLA_TUNE_SCAN_SEGMENTS(1), &p->base);
     if (rc != KLA_OK) return rc;
     const size_t rows = (size_t)N * T * H * dk * elem_bytes(dt);
     p->off_kp = round256(p->base.off_M);             // the forward plan up to its chunk offsets; no segment maps here
@@ -355,8 +404,7 @@ int chunk_fwd_diag_impl(const void* q, const void* k, const void* v, const float
     const long chains8 = ((long)pl.base.n_states * H + 7) / 8 * 8;
     const int waves = (chains8 * (dv / 32) >= 192) ? 2 : 1;
     if constexpr (sizeof(E) == 2) {
-        const char* impl = getenv("KLA_SCAN_IMPL");   // "generic": the element-type-generic kernel (A/B testing)
-        if (!(impl && impl[0] == 'g'))
+        if (!pl.base.tune.generic_scan)                  // else the element-type-generic kernel (A/B testing)
             return kla::launch_scan_bf16_diag(sa, dk, waves, st) == hipSuccess ? KLA_OK : KLA_ERR_HIP;
     }
     return kla::launch_scan_diag<E>(sa, dk, waves, st) == hipSuccess ? KLA_OK : KLA_ERR_HIP;
@@ -408,8 +456,14 @@ const char* kla_status_string(int code)
 size_t kla_chunk_fwd_workspace_bytes(int N, int T, int H, int dk, int dv, int chunk, kla_dtype dt,
                                      const int32_t* cu_seqlens_host, int n_seq)
 {
+    return kla_chunk_fwd_workspace_bytes_opts(N, T, H, dk, dv, chunk, dt, cu_seqlens_host, n_seq, 0u);
+}
+
+size_t kla_chunk_fwd_workspace_bytes_opts(int N, int T, int H, int dk, int dv, int chunk, kla_dtype dt,
+                                          const int32_t* cu_seqlens_host, int n_seq, unsigned opts)
+{
     Plan pl;
-    if (make_plan(N, T, H, dk, dv, chunk, (int)dt, cu_seqlens_host, n_seq, &pl) != KLA_OK) return 0;
+    if (make_plan(N, T, H, dk, dv, chunk, (int)dt, cu_seqlens_host, n_seq, opts, &pl) != KLA_OK) return 0;
     return pl.total;
 }
 
@@ -419,10 +473,9 @@ static int chunk_fwd_validate(const void* q, const void* k, const void* v, const
                               const int32_t* cu_seqlens_host, int n_seq, int N, int T, int H, int dk, int dv, int chunk,
                               kla_dtype dt, unsigned opts, Plan* pl)
 {
-    const int rc = make_plan(N, T, H, dk, dv, chunk, (int)dt, cu_seqlens_host, n_seq, pl);
+    const int rc = make_plan(N, T, H, dk, dv, chunk, (int)dt, cu_seqlens_host, n_seq, opts, pl);
     if (rc != KLA_OK) return rc;
     if (!(eps >= 0.0f) || isinf(eps)) return KLA_ERR_SHAPE;
-    if (opts & ~(unsigned)(KLA_OPT_NORMALIZE_Q | KLA_OPT_GDN_BETA)) return KLA_ERR_SHAPE;
     if (n_seq > 0 && !cu_seqlens_dev) return KLA_ERR_NULL;
     if (n_seq == 0 && cu_seqlens_dev) return KLA_ERR_SHAPE;
     const bool any_tokens = (long)N * T > 0;
@@ -441,6 +494,7 @@ static int chunk_fwd_launch(const void* q, const void* k, const void* v, const f
     if (pl.n_states == 0) return KLA_OK;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     char* ws = static_cast<char*>(workspace);
+    opts &= kOptMask;                                    // the tuning fields live on in pl.tune
     if (dt == KLA_BF16)
         return chunk_fwd_impl<bf16_t>(q, k, v, log_alpha, eta, eps, h0, o, hT, cu_seqlens_dev, n_seq, N, T, H, dk, dv,
                                       pl, ws, stages, nullptr, nullptr, nullptr, st, opts);
@@ -502,8 +556,14 @@ int kla_chunk_fwd_static(const void* q, const void* k, const void* v, const floa
 size_t kla_chunk_bwd_workspace_bytes(int N, int T, int H, int dk, int dv, int chunk, kla_dtype dt,
                                      const int32_t* cu_seqlens_host, int n_seq)
 {
+    return kla_chunk_bwd_workspace_bytes_opts(N, T, H, dk, dv, chunk, dt, cu_seqlens_host, n_seq, 0u);
+}
+
+size_t kla_chunk_bwd_workspace_bytes_opts(int N, int T, int H, int dk, int dv, int chunk, kla_dtype dt,
+                                          const int32_t* cu_seqlens_host, int n_seq, unsigned opts)
+{
     BwdPlan pl;
-    if (make_bwd_plan(N, T, H, dk, dv, chunk, (int)dt, cu_seqlens_host, n_seq, &pl) != KLA_OK) return 0;
+    if (make_bwd_plan(N, T, H, dk, dv, chunk, (int)dt, cu_seqlens_host, n_seq, opts, &pl) != KLA_OK) return 0;
     return pl.total;
 }
 
@@ -524,10 +584,10 @@ int kla_chunk_bwd_opts(const void* q, const void* k, const void* v, const float*
                        const int32_t* cu_seqlens_host, int n_seq, int N, int T, int H, int dk, int dv, int chunk,
                        kla_dtype dt, void* workspace, size_t workspace_bytes, void* hip_stream, unsigned opts)
 {
-    if (opts & ~(unsigned)(KLA_OPT_NORMALIZE_Q | KLA_OPT_GDN_BETA)) return KLA_ERR_SHAPE;
     BwdPlan pl;
-    const int rc = make_bwd_plan(N, T, H, dk, dv, chunk, (int)dt, cu_seqlens_host, n_seq, &pl);
+    const int rc = make_bwd_plan(N, T, H, dk, dv, chunk, (int)dt, cu_seqlens_host, n_seq, opts, &pl);
     if (rc != KLA_OK) return rc;
+    opts &= kOptMask;
     if (!(eps >= 0.0f) || isinf(eps)) return KLA_ERR_SHAPE;
     if (n_seq > 0 && !cu_seqlens_dev) return KLA_ERR_NULL;
     if (n_seq == 0 && cu_seqlens_dev) return KLA_ERR_SHAPE;
@@ -555,7 +615,7 @@ size_t kla_chunk_fwd_diag_workspace_bytes(int N, int T, int H, int dk, int dv, i
                                           const int32_t* cu_seqlens_host, int n_seq)
 {
     DiagPlan pl;
-    if (make_diag_plan(N, T, H, dk, dv, chunk, (int)dt, cu_seqlens_host, n_seq, &pl) != KLA_OK) return 0;
+    if (make_diag_plan(N, T, H, dk, dv, chunk, (int)dt, cu_seqlens_host, n_seq, 0u, &pl) != KLA_OK) return 0;
     return pl.total;
 }
 
@@ -573,10 +633,10 @@ int kla_chunk_fwd_diag_opts(const void* q, const void* k, const void* v, const f
                             const int32_t* cu_seqlens_host, int n_seq, int N, int T, int H, int dk, int dv, int chunk,
                             kla_dtype dt, void* workspace, size_t workspace_bytes, void* hip_stream, unsigned opts)
 {
-    if (opts & ~(unsigned)(KLA_OPT_NORMALIZE_Q | KLA_OPT_GDN_BETA)) return KLA_ERR_SHAPE;
     DiagPlan pl;
-    const int rc = make_diag_plan(N, T, H, dk, dv, chunk, (int)dt, cu_seqlens_host, n_seq, &pl);
+    const int rc = make_diag_plan(N, T, H, dk, dv, chunk, (int)dt, cu_seqlens_host, n_seq, opts, &pl);
     if (rc != KLA_OK) return rc;
+    opts &= kOptMask;
     if (!(eps >= 0.0f) || isinf(eps)) return KLA_ERR_SHAPE;
     if (n_seq > 0 && !cu_seqlens_dev) return KLA_ERR_NULL;
     if (n_seq == 0 && cu_seqlens_dev) return KLA_ERR_SHAPE;
@@ -608,25 +668,27 @@ int kla_decode_step_diag_opts(const void* q, const void* k, const void* v, const
                               unsigned opts)
 {
     if (!dt_ok((int)dt)) return KLA_ERR_DTYPE;
-    if (opts & ~(unsigned)(KLA_OPT_NORMALIZE_Q | KLA_OPT_GDN_BETA)) return KLA_ERR_SHAPE;
+    Tune tune;
+    if (!parse_tune(opts, &tune)) return KLA_ERR_SHAPE;
+    opts &= kOptMask;
     if (B < 0 || H <= 0 || !dk_ok(dk) || !dv_ok(dv) || (long)B * H > 0x7fffffffL) return KLA_ERR_SHAPE;
     if (!(eps >= 0.0f) || isinf(eps)) return KLA_ERR_SHAPE;
     if (B == 0) return KLA_OK;
     if (!q || !k || !v || !log_alpha || !eta || !S || !o) return KLA_ERR_NULL;
     if (!aligned16(S) || (reinterpret_cast<uintptr_t>(q) & 3u) || (reinterpret_cast<uintptr_t>(k) & 3u) ||
         (reinterpret_cast<uintptr_t>(v) & 3u) || (reinterpret_cast<uintptr_t>(o) & 3u) ||
-        (reinterpret_cast<uintptr_t>(log_alpha) & 3u))
+        (reinterpret_cast<uintptr_t>(log_alpha) & 3u) || (reinterpret_cast<uintptr_t>(eta) & 3u))
         return KLA_ERR_ALIGN;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     hipError_t e;
     if (dt == KLA_BF16)
         e = kla::launch_decode<bf16_t>(static_cast<const bf16_t*>(q), static_cast<const bf16_t*>(k),
                                        static_cast<const bf16_t*>(v), log_alpha, eta, eps, S, static_cast<bf16_t*>(o),
-                                       B * H, dk, dv, 64, kla::kOptDiagDecay | opts, st);
+                                       B * H, dk, dv, 64, tune.decode_nt, kla::kOptDiagDecay | opts, st);
     else
         e = kla::launch_decode<float>(static_cast<const float*>(q), static_cast<const float*>(k),
                                       static_cast<const float*>(v), log_alpha, eta, eps, S, static_cast<float*>(o),
-                                      B * H, dk, dv, 64, kla::kOptDiagDecay | opts, st);
+                                      B * H, dk, dv, 64, tune.decode_nt, kla::kOptDiagDecay | opts, st);
     return e == hipSuccess ? KLA_OK : KLA_ERR_HIP;
 }
 
@@ -637,7 +699,7 @@ int kla_debug_chunk_stage(const void* q, const void* k, const void* v, const flo
 {
     if (stage != 1 && stage != 2) return KLA_ERR_SHAPE;
     return chunk_fwd_checked(q, k, v, log_alpha, eta, eps, h0, o, hT, cu_seqlens_dev, cu_seqlens_host, n_seq, N, T, H,
-                             dk, dv, chunk, dt, workspace, workspace_bytes, hip_stream, stage, 0u);
+                             dk, dv, chunk, dt, workspace, workspace_bytes, hip_stream, stage, KLA_TUNE_UNFUSED);
 }
 
 int kla_debug_intra_chunk(const void* q, const void* k, const float* log_alpha, const float* eta, float eps,
@@ -646,7 +708,7 @@ int kla_debug_intra_chunk(const void* q, const void* k, const float* log_alpha, 
                           kla_dtype dt, void* workspace, size_t workspace_bytes, void* hip_stream)
 {
     Plan pl;
-    const int rc = make_plan(N, T, H, dk, 64, chunk, (int)dt, cu_seqlens_host, n_seq, &pl);
+    const int rc = make_plan(N, T, H, dk, 64, chunk, (int)dt, cu_seqlens_host, n_seq, KLA_TUNE_UNFUSED, &pl);
     if (rc != KLA_OK) return rc;
     if (!(eps >= 0.0f) || isinf(eps)) return KLA_ERR_SHAPE;
     if (n_seq > 0 && !cu_seqlens_dev) return KLA_ERR_NULL;
@@ -676,32 +738,34 @@ int kla_decode_step_opts(const void* q, const void* k, const void* v, const floa
                          unsigned opts)
 {
     if (!dt_ok((int)dt)) return KLA_ERR_DTYPE;
-    if (opts & ~(unsigned)(KLA_OPT_NORMALIZE_Q | KLA_OPT_GDN_BETA)) return KLA_ERR_SHAPE;
+    Tune tune;
+    if (!parse_tune(opts, &tune)) return KLA_ERR_SHAPE;
+    opts &= kOptMask;
     if (B < 0 || H <= 0 || !dk_ok(dk) || !dv_ok(dv) || (long)B * H > 0x7fffffffL) return KLA_ERR_SHAPE;
     if (!(eps >= 0.0f) || isinf(eps)) return KLA_ERR_SHAPE;
     if (B == 0) return KLA_OK;
     if (!q || !k || !v || !log_alpha || !eta || !S || !o) return KLA_ERR_NULL;
     if (!aligned16(S) || (reinterpret_cast<uintptr_t>(q) & 3u) || (reinterpret_cast<uintptr_t>(k) & 3u) ||
-        (reinterpret_cast<uintptr_t>(v) & 3u) || (reinterpret_cast<uintptr_t>(o) & 3u))
+        (reinterpret_cast<uintptr_t>(v) & 3u) || (reinterpret_cast<uintptr_t>(o) & 3u) ||
+        (reinterpret_cast<uintptr_t>(log_alpha) & 3u) || (reinterpret_cast<uintptr_t>(eta) & 3u))
         return KLA_ERR_ALIGN;
     // State columns per workgroup: 128 (measured best at 512 workgroups, e.g. 64 x 8 states of 128 columns), narrower for
     // small batches so that about 512 workgroups still share the chip (B = 1, H = 8: 3.2 us per step with 32 columns,
-    // 4.2 us with 128).  KLA_DECODE_SLICE = 32, 64, 128 or 256 overrides.
+    // 4.2 us with 128).  The tuning field KLA_TUNE_DECODE_SLICE(32 | 64 | 128 | 256) overrides.
     int slice = dv < 128 ? dv : 128;
     while (slice > 32 && (long)B * H * (dv / slice) < 512) slice >>= 1;
-    const char* env = getenv("KLA_DECODE_SLICE");
-    if (env) { const int x = atoi(env); if (x == 32 || x == 64 || x == 128 || x == 256) slice = x; }
+    if (tune.decode_slice) slice = tune.decode_slice;
     if (slice > dv) slice = dv;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     hipError_t e;
     if (dt == KLA_BF16)
         e = kla::launch_decode<bf16_t>(static_cast<const bf16_t*>(q), static_cast<const bf16_t*>(k),
                                        static_cast<const bf16_t*>(v), log_alpha, eta, eps, S, static_cast<bf16_t*>(o),
-                                       B * H, dk, dv, slice, opts, st);
+                                       B * H, dk, dv, slice, tune.decode_nt, opts, st);
     else
         e = kla::launch_decode<float>(static_cast<const float*>(q), static_cast<const float*>(k),
                                       static_cast<const float*>(v), log_alpha, eta, eps, S, static_cast<float*>(o),
-                                      B * H, dk, dv, slice, opts, st);
+                                      B * H, dk, dv, slice, tune.decode_nt, opts, st);
     return e == hipSuccess ? KLA_OK : KLA_ERR_HIP;
 }
 

@@ -24,6 +24,10 @@
 //     i of that block.  No transposed copy of K exists anywhere.
 //   * Every per-lane LDS offset is computed once before the loop; inside it an access is
 //     stage base + lane offset + immediate.
+//   * Fused mode (FU): no separate intra-chunk stage and no workspace.  Four more waves of the workgroup
+//     ("helpers", on the SIMDs that have no compute wave) produce the solve operands, P and the decay vectors of
+//     the chunks two and one steps ahead, straight into two LDS record buffers, so K and Q are read from memory
+//     once and the per-chunk objects never leave the CU (see the helper section below).
 //   * A short last chunk is handled without zero filling: rows beyond it re-read the last valid row;
 //     their T' rows and columns are zero (beta = 0 there), so they contribute nothing to U, to the
 //     state or to any stored output.
@@ -36,9 +40,10 @@ namespace kla {
 
 namespace {
 
-template <int DK, int NW, bool DG = false>
+template <int DK, int NW, bool DG = false, bool FU = false>
 struct Cfg {
-    static constexpr int NTH = 64 * NW;                  // compute threads (the workgroup has one more wave)
+    static_assert(!(DG && FU), "the fused mode has no diagonal-gating variant");
+    static constexpr int NTH = 64 * NW;                  // compute threads (the workgroup has one or three more waves)
     static constexpr int KB = DK / 16, KP = DK / 32;
     static constexpr int SLW = 16 * NW;                  // state columns per workgroup
     static constexpr int RB = DK * 2;                    // bytes per K/Q row
@@ -51,18 +56,444 @@ struct Cfg {
     static constexpr int NVB = 64 / RPV;                 // copy blocks of the V slice (= 2 NW)
     static constexpr int TPB = kTriPairs * 64 * 16;      // bytes of one T' or P area; [T' | P] is one 12 KiB record
     static constexpr int NTB = 2 * TPB / 1024;           // = 12
-    // DG (diagonal gating): a third [64 x d_k] tile, the K operand of the state update, and gamma_C per channel
+    // DG (diagonal gating): a third [64 x d_k] tile, the K operand of the state update, and gamma_C per channel.
+    // FU: a ring stage holds K, Q and the V slice only; the record [T' | P | three vectors] of a chunk lives in one of
+    // two record buffers behind the ring, written by a helper wave.
     static constexpr int OFF_Q = 64 * RB, OFF_K2 = 2 * 64 * RB, OFF_T = (DG ? 3 : 2) * 64 * RB, OFF_P = OFF_T + TPB,
-                         OFF_V = OFF_T + 2 * TPB, OFF_EG = OFF_V + 64 * VRW, OFF_ED = OFF_EG + 256, OFF_EQ = OFF_ED + 256,
-                         OFF_GC = OFF_EQ + 256, STAGE = OFF_GC + (DG ? 512 : 0);
+                         OFF_V = FU ? OFF_T : OFF_T + 2 * TPB, OFF_EG = OFF_V + 64 * VRW, OFF_ED = OFF_EG + 256,
+                         OFF_EQ = OFF_ED + 256, OFF_GC = OFF_EQ + 256, STAGE = FU ? OFF_EG : OFF_GC + (DG ? 512 : 0);
+    // where a compute wave finds T', P and the vectors, relative to the ring stage (not fused) or the record buffer
+    static constexpr int R_T = FU ? 0 : OFF_T, R_P = FU ? TPB : OFF_P, R_EG = FU ? 2 * TPB : OFF_EG;
+    static constexpr int RECB = 2 * TPB + 1024;          // bytes of a record buffer: [T-area | P | four vectors of 64 fp32]
+    static constexpr int HSCR_T = 4096 + 6 * 256, HSCR_P = 6 * 256;   // private LDS of a T-side / P-side helper wave
     // row stride of the output staging tile: 24 (NW <= 2) or 40 (NW = 4) dwords, so that the 8-dword spans which
     // one wave writes into 8 consecutive rows fall into disjoint banks
     static constexpr int ORB = NW <= 2 ? 96 : 160;
     static constexpr int OSB = 64 * ORB;
-    static constexpr int NST = (3 * STAGE + 2 * OSB <= 160 * 1024) ? 3 : 2;   // LDS ring depth
-    static constexpr int LDS = NST * STAGE + 2 * OSB;
-    static constexpr int NDMA = (DG ? 3 : 2) * NKB + NTB + NVB + 1 + (DG ? 1 : 0);   // copy instructions per chunk (+1: decay factors)
+    static constexpr int EXTRA = FU ? 2 * RECB + 2 * HSCR_T + 2 * HSCR_P : 0;
+    static constexpr int NST = (3 * STAGE + 2 * OSB + EXTRA <= 160 * 1024) ? 3 : 2;   // LDS ring depth
+    static constexpr int LDS = NST * STAGE + 2 * OSB + EXTRA;
+    static constexpr int OFF_REC = NST * STAGE + 2 * OSB, OFF_HST = OFF_REC + 2 * RECB, OFF_HSP = OFF_HST + 2 * HSCR_T;   // FU only
+    // copy instructions per chunk (+1: decay factors)
+    static constexpr int NDMA = FU ? NVB : (DG ? 3 : 2) * NKB + NTB + NVB + 1 + (DG ? 1 : 0);
+    // waves of a workgroup: compute waves, then (fused) two T-side helpers, the copy wave, one wave that only keeps the
+    // barriers company - so that the two P-side helpers after it land on the SIMDs of the T-side ones - and those two
+    static constexpr int NWAVES = NW + (FU ? 6 : 1);
+    static constexpr int W_COPY = FU ? NW + 2 : NW;
     static_assert(LDS <= 160 * 1024 && (NST != 3 || NDMA < 64), "LDS budget of a gfx950 CU; 6-bit vmcnt (counted waits only with three stages)");
+    static_assert(!FU || NST == 3, "fused mode is laid out for the three-stage ring");
+};
+
+
+// ---- helper waves of the fused mode ------------------------------------------------------------------------
+// Four waves, on the two SIMDs that have no compute wave, produce the record of every chunk two steps ahead of its use:
+// a "T-side" and a "P-side" wave for the even chunks, another pair for the odd ones; a wave takes two chunk steps per
+// record (phase A in step c - 2, phase B in step c - 1), and the two waves that share a SIMD fill each other's stalls.
+//
+// T-side.  The unit lower triangular system of eq. (6), (I + L) U = B X with L = B (A^- o K K^T), is handed to the
+// compute waves as a block forward substitution over its four 16-row blocks,
+//
+//     U_0 = (D_0 B_0) X_0,     U_t = D_t (B_t X_t - sum_{j<t} L_tj U_j),     D_t = (I + L_tt)^{-1},
+//
+// so only the four 16x16 diagonal blocks are inverted and no product of blocks is formed: the 64x64 "T-area" of the
+// record holds [D_0 B_0; L10 D_1; L20 L21 D_2; L30 L31 L32 D_3] in the tile-pair layout of T' (kla_mma.hpp), and a
+// fourth vector carries beta.  The wave works on transposed tiles: the accumulator tile of (K_tj K_ti^T) - lane
+// (r, g) holds rows 4g..4g+3 of column r - is exactly the A-operand quad order of tile (ti, tj) of L that the record
+// stores.  Tiles live in registers; the only LDS the wave touches is its private scratch (per-token tables, the four
+// diagonal blocks on their way between layouts) and, at the very end, the record buffer.
+//   phase A  g = prefix sum of log alpha (units of log 2), decay tables; K K^T on bf16 MFMA (the ten lower tiles)
+//            from K row slots read straight from global memory; beta of eq. (3) from its diagonal; decay, mask
+//            and beta applied; the diagonal blocks to the scratch.
+//   phase B  the four diagonal blocks inverted by forward substitution, each block by one group of 16 lanes (lane =
+//            column, the rows of L read from the scratch by the whole group at once); everything rounded to bf16
+//            and written in operand order.
+// P-side.  P = A o Q K^T of eq. (7) (with 1/||q_i|| on its rows for the normalised read-out), the ten lower tiles as
+// (Q K^T)^T so that they too come out in A-operand order, and the three decay vectors gamma_i, gamma_C/gamma_i,
+// gamma_i/||q_i||.  Phase A does all of it in registers, phase B writes the record.
+//
+// The helpers' reads of K and Q are the first touch of these rows (the ring's copies of the same chunk follow and find
+// them in L2).  They are requested one step before phase A uses them - a chunk step is shorter than a trip to memory:
+// the gates and the K row slots into registers; of the Q rows only one dword per 128-byte line, which brings them
+// into L2, from where phase A loads them.
+//
+// Decay ratios off the diagonal tiles are the product of two factors <= 1, gamma_I / gamma_ref and
+// gamma_ref / gamma_J with ref the first token of I's tile (J < ref <= I there): 2^x is evaluated a few times per
+// lane instead of once per element, and no factor can overflow.  On the diagonal tiles 2^(g_I - g_J) is taken
+// directly (masked to J <= I before the exponential).
+template <int DK>
+struct HelperBase {
+    static constexpr int KP = DK / 32;
+    static constexpr int TPB = kTriPairs * 64 * 16;
+
+    float la_pre;                           // log alpha of token `lane`
+
+    __device__ __forceinline__ static void wave_lds_fence()
+    {
+        // One wave, and the LDS executes a wave's operations in order: all that is needed between a write by one lane
+        // and a read by another is that the compiler keeps them in program order.  (A real fence would also wait for the
+        // global loads in flight, which are the very thing these phases overlap with.)
+        asm volatile("" ::: "memory");
+    }
+    // the instruction scheduler does not move anything across this point: keeps the loads where the register budget
+    // of 256 per lane (two waves per SIMD) has room for them
+    __device__ __forceinline__ static void pin() { __builtin_amdgcn_sched_barrier(0); }
+    // Every phase starts from a lane index the compiler cannot see through: otherwise it computes the dozens of
+    // lane-dependent addresses and masks of all phases once, before the chunk loop, and keeps them in registers for
+    // its whole length - registers the phases themselves need.
+    __device__ __forceinline__ static int opaque(int x) { asm volatile("" : "+v"(x)); return x; }
+
+    // lane (r, g) takes, for each block of 16 rows, the eight features 32 kp + 8 g .. + 7 of row r of the block
+    // (rows beyond a short chunk repeat its last row).  The byte offsets of the four rows inside a full chunk are kept
+    // in registers for the whole sequence.
+    int ro_full[4];
+    __device__ __forceinline__ void init_rows(int lane, int kq_row)
+    {
+#pragma unroll
+        for (int it = 0; it < 4; ++it) ro_full[it] = (16 * it + (lane & 15)) * kq_row + 16 * (lane >> 4);
+    }
+    // tile: chunk base of K or of Q for this head; dst: KP x 4 row slots
+    __device__ __forceinline__ void load_slots(u32x4 (&dst)[KP][4], const char* tile, int lane, int clen, int kq_row) const
+    {
+        const int lim = (clen - 1) * kq_row + 16 * (lane >> 4);     // the offsets grow with the row: clamping them clamps the row
+        static_for<4>([&](auto itc) {
+            constexpr int it = itc;
+            const int ro = min(ro_full[it], lim);
+            static_for<KP>([&](auto kpc) {
+                constexpr int kp = kpc;
+                dst[kp][it] = ld16(tile + ro + 64 * kp);
+            });
+        });
+    }
+    // The helpers are also the ones that bring K and Q on chip: the row slots they loaded for their own products go
+    // on into the ring stage of the chunk, in the swizzled token-major layout the compute waves read (row 16 it + r,
+    // logical 16-byte column 4 kp + g).
+    __device__ __forceinline__ static void store_slots(const u32x4 (&src)[KP][4], char* tile, int lane)
+    {
+        const int r = lane & 15, g = lane >> 4;
+        static_for<4>([&](auto itc) {
+            constexpr int it = itc;
+            char* row = tile + (16 * it + r) * (DK * 2);
+            static_for<KP>([&](auto kpc) {
+                constexpr int kp = kpc;
+                st16(row + (((4 * kp + g) ^ swz_bits(r)) * 16), src[kp][it]);      // (16 it + r) & 7 == r & 7
+            });
+        });
+    }
+    __device__ __forceinline__ static u32x4 ring_slot(const char* tile, int it, int kp, int lane)
+    {
+        const int r = lane & 15, g = lane >> 4;
+        return ld16(tile + (16 * it + r) * (DK * 2) + (((4 * kp + g) ^ swz_bits(r)) * 16));
+    }
+
+    // Inclusive prefix sum of log alpha over the 64 lanes, in units of log 2 (every decay factor is then one
+    // v_exp_f32): inside each row of 16 lanes by DPP shifts, the rows joined through the scalar unit.  Writes the
+    // tables every consumer needs - g, and gamma_ref(ti) / gamma_J for ti = 1..3 - and returns g of this lane;
+    // av = gamma_I / gamma_ref(I), gl2 = g of the last token.
+    __device__ __forceinline__ float scan_gates(float* tab_g2, float* tab_b, int lane, float& av, float& gl2) const
+    {
+        const int g = lane >> 4;
+        float x = la_pre;
+        x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x111, 0xf, 0xf, true));   // row_shr:1
+        x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x112, 0xf, 0xf, true));   // row_shr:2
+        x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x114, 0xf, 0xf, true));   // row_shr:4
+        x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x118, 0xf, 0xf, true));   // row_shr:8
+        {
+            const float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 15));
+            const float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 31));
+            const float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 47));
+            x += g == 0 ? 0.f : (g == 1 ? r0 : (g == 2 ? r0 + r1 : (r0 + r1) + r2));
+        }
+        const float x2 = x * 1.44269504088896341f;
+        gl2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x2), 63));
+        // ref = first lane of I's row (DPP row_newbcast:0)
+        av = __builtin_amdgcn_exp2f(x2 - __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(x2), 0x150, 0xf, 0xf, true)));
+        tab_g2[lane] = x2;
+#pragma unroll
+        for (int ti = 1; ti < 4; ++ti) {                 // unused for J >= 16 ti
+            const float gref = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x2), 16 * ti));
+            tab_b[64 * (ti - 1) + lane] = __builtin_amdgcn_exp2f(fminf(gref - x2, 0.f));
+        }
+        return x2;
+    }
+    // The results of phase A are wanted in registers when the phase ends: without this the compiler moves the arithmetic
+    // that produces them behind the barrier, next to their use in phase B, where the prefetched operands need the room.
+    __device__ __forceinline__ static void keep(u32x2& q) { asm volatile("" : "+v"(q.x), "+v"(q.y)); }
+    __device__ __forceinline__ static void keep(floatx4& x) { asm volatile("" : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3])); }
+    __device__ __forceinline__ static void slot(char* rec, int base, int ctp, int lane, u32x2 q0, u32x2 q1)
+    {
+        const u32x4 v = {q0.x, q0.y, q1.x, q1.y};
+        st16(rec + base + (ctp * 64 + lane) * 16, v);
+    }
+};
+
+template <int DK>
+struct THelper : HelperBase<DK> {
+    typedef HelperBase<DK> B;
+    using B::KP; using B::wave_lds_fence; using B::pin; using B::opaque;
+    static constexpr int SCR = 4096 + 6 * 256;           // private scratch: four 16x16 fp32 blocks, six tables of 64
+    // tables (floats): g, ||k||^2 then beta gamma_I/gamma_ref (same lane reads the one and writes the other), beta, b x 3
+    static constexpr int T_G2 = 1024, T_BA = 1088, T_BETA = 1152, T_B = 1216;
+
+    u32x4 ka[KP][4];                        // K row slots of the wave's next record
+    float eta_pre;
+    // carried from phase A to phase B: the six strictly lower tiles of L as A-operand quads, bf16; tile (ti, tj) at
+    // index ti (ti - 1) / 2 + tj, lane (r, g) holds L[16 ti + r][16 tj + 4 g + e]
+    u32x2 Lq[6];
+
+    __device__ __forceinline__ void prefetch(const ScanArgs<bf16_t>& a, long tok0, int clen, int h, int lane_, const char* kc,
+                                             int kq_row)
+    {
+        const int lane = opaque(lane_);
+        eta_pre = lane < clen ? a.eta[(size_t)(tok0 + lane) * a.H + h] : 0.f;
+        this->la_pre = lane < clen ? a.log_alpha[(size_t)(tok0 + lane) * a.H + h] : 0.f;
+        this->load_slots(ka, kc, lane, clen, kq_row);
+    }
+
+    // ktile: the K tile of this chunk's ring stage
+    __device__ __forceinline__ void phase_a(const ScanArgs<bf16_t>& a, float* hs, char* ktile, int lane_)
+    {
+        const int lane = opaque(lane_);
+        const int r = lane & 15, g = lane >> 4;
+        const bool gdn = (a.opts & kOptGdnBeta) != 0;
+        B::store_slots(ka, ktile, lane);
+        float av, gl2;
+        this->scan_gates(hs + T_G2, hs + T_B, lane, av, gl2);
+
+        // ---- K K^T: the diagonal tiles and the six strictly lower ones, all transposed (rows <- block tj, column <-
+        //      block ti): scaled, they are handed on as they are, in A-operand order
+        const floatx4 z4 = {0.f, 0.f, 0.f, 0.f};
+        floatx4 Gd[4] = {z4, z4, z4, z4}, Gt[6] = {z4, z4, z4, z4, z4, z4};
+        static_for<KP>([&](auto kc_) {
+            constexpr int kp = kc_;
+            const u32x4* kk = ka[kp];
+            static_for<4>([&](auto tic) {
+                constexpr int ti = tic;
+                const u32x2 kb0 = {kk[ti][0], kk[ti][1]}, kb1 = {kk[ti][2], kk[ti][3]};
+                mma_bf16(Gd[ti], kk[ti], kb0, kb1);
+                static_for<ti>([&](auto tjc) {
+                    constexpr int tj = tjc;
+                    mma_bf16(Gt[ti * (ti - 1) / 2 + tj], kk[tj], kb0, kb1);
+                });
+            });
+        });
+        wave_lds_fence();
+        // ---- beta of eq. (3): ||k_i||^2 is the diagonal of K K^T (exact bf16 products, fp32 sums); the lane holding
+        //      (i, i) hands it to lane i, which has eta_i and gamma_i / gamma_ref in registers
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const float gii = (r & 3) == 0 ? Gd[t][0] : ((r & 3) == 1 ? Gd[t][1] : ((r & 3) == 2 ? Gd[t][2] : Gd[t][3]));
+            if ((r >> 2) == g) hs[T_BA + 16 * t + r] = gii;
+        }
+        wave_lds_fence();
+        {
+            const float b = gdn ? eta_pre : kaczmarz_beta_fast(eta_pre, hs[T_BA + lane], a.eps);
+            hs[T_BETA + lane] = b;
+            hs[T_BA + lane] = b * av;
+        }
+        wave_lds_fence();
+
+        // ---- decay, mask, beta on the tiles of L.  Row token I, column token J:
+        //   I = 16 ti + r, J = 16 tj + 4 g + e
+        static_for<4>([&](auto tc) {                     // diagonal tiles: 2^(g_I - g_J), J < I
+            constexpr int t = tc;
+            const floatx4 gq = *reinterpret_cast<const floatx4*>(hs + T_G2 + 16 * t + 4 * g);
+            const float g2_r = hs[T_G2 + 16 * t + r], beta_r = hs[T_BETA + 16 * t + r];
+            floatx4 l;
+#pragma unroll
+            for (int e = 0; e < 4; ++e)                  // strictly lower
+                l[e] = (4 * g + e < r) ? beta_r * __builtin_amdgcn_exp2f(fminf(g2_r - gq[e], 0.f)) * Gd[t][e] : 0.f;
+            // block t of L, row-major, for the substitution: L_tt[r][4 g + e]
+            *reinterpret_cast<floatx4*>(hs + 256 * t + 16 * r + 4 * g) = l;
+        });
+        static_for<4>([&](auto tic) {                    // strictly lower tiles: gamma_I/gamma_ref(I) gamma_ref(I)/gamma_J
+            constexpr int ti = tic;
+            const float ba_r = hs[T_BA + 16 * ti + r];
+            static_for<ti>([&](auto tjc) {
+                constexpr int tj = tjc;
+                const floatx4 bq = *reinterpret_cast<const floatx4*>(hs + T_B + 64 * (ti - 1) + 16 * tj + 4 * g);
+                Lq[ti * (ti - 1) / 2 + tj] = to_quad((bq * ba_r) * Gt[ti * (ti - 1) / 2 + tj]);
+            });
+        });
+#pragma unroll
+        for (int i = 0; i < 6; ++i) B::keep(Lq[i]);
+    }
+
+    __device__ __forceinline__ void phase_b(float* hs, char* rec, int lane_)
+    {
+        const int lane = opaque(lane_);
+        const int r = lane & 15, g = lane >> 4;
+        wave_lds_fence();
+        // ---- diagonal blocks: D_t = (I + L_tt)^{-1} by forward substitution on the blocks phase A left in the scratch;
+        //      lane group g takes block g, lane r its column r; row i of L_tt is read by all 16 lanes of the group at
+        //      once (a broadcast read), four rows ahead of its use
+        {
+            float* Lb = hs + 256 * g;
+            float xs[16];
+            xs[0] = (r == 0) ? 1.f : 0.f;
+            floatx4 rows[5][4];
+            auto read_row = [&](auto ic) {
+                constexpr int i = ic;
+                if constexpr (i < 16) {
+#pragma unroll
+                    for (int c4 = 0; c4 < (i + 3) / 4; ++c4) rows[i % 5][c4] = *reinterpret_cast<const floatx4*>(Lb + 16 * i + 4 * c4);
+                }
+            };
+            read_row(IntC<1>()); read_row(IntC<2>()); read_row(IntC<3>()); read_row(IntC<4>());
+            static_for<15>([&](auto ic) {
+                constexpr int i = ic + 1;
+                read_row(IntC<i + 4>());
+                float s0 = (i == r) ? 1.f : 0.f, s1 = 0.f;
+                static_for<i>([&](auto rc) {
+                    constexpr int rr = rc;
+                    if constexpr (rr & 1) s1 -= rows[i % 5][rr >> 2][rr & 3] * xs[rr]; else s0 -= rows[i % 5][rr >> 2][rr & 3] * xs[rr];
+                });
+                xs[i] = s0 + s1;
+            });
+            wave_lds_fence();                            // every lane has read its rows of L
+            // R_tt = D_t^T, row-major: R_tt[r][i] = D_t[i][r]
+#pragma unroll
+            for (int c4 = 0; c4 < 4; ++c4) {
+                const floatx4 v = {xs[4 * c4], xs[4 * c4 + 1], xs[4 * c4 + 2], xs[4 * c4 + 3]};
+                *reinterpret_cast<floatx4*>(Lb + 16 * r + 4 * c4) = v;
+            }
+        }
+        wave_lds_fence();
+        floatx4 DA[4];                                   // D_t in A-operand order: D_t[r][4 g + j] = R_tt[4 g + j][r]
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) DA[t][e] = hs[256 * t + 16 * (4 * g + e) + r];
+
+        // T-area of the record: the 16x16 blocks of the block forward substitution, in the tile-pair layout of T'
+        // (record order (ti, jp) = (0,0) (1,0) (2,0) (2,1) (3,0) (3,1)):
+        //     [D0 B0 | 0] [L10 | D1] [L20 | L21] [D2 | 0] [L30 | L31] [L32 | D3]
+        // Only D0 carries beta on its columns (J = 4 g + e); for the other rows the scan applies beta to the right-hand side.
+        const floatx4 bq0 = *reinterpret_cast<const floatx4*>(hs + T_BETA + 4 * g);
+        const u32x2 zq = {0u, 0u};
+        B::slot(rec, 0, 0, lane, to_quad(DA[0] * bq0), zq);
+        B::slot(rec, 0, 1, lane, Lq[0], to_quad(DA[1]));
+        B::slot(rec, 0, 2, lane, Lq[1], Lq[2]);
+        B::slot(rec, 0, 3, lane, to_quad(DA[2]), zq);
+        B::slot(rec, 0, 4, lane, Lq[3], Lq[4]);
+        B::slot(rec, 0, 5, lane, Lq[5], to_quad(DA[3]));
+        reinterpret_cast<float*>(rec + 2 * B::TPB)[192 + lane] = hs[T_BETA + lane];
+    }
+};
+
+template <int DK, bool NQ>
+struct PHelper : HelperBase<DK> {
+    typedef HelperBase<DK> B;
+    using B::KP; using B::wave_lds_fence; using B::pin; using B::opaque;
+    static constexpr int SCR = 6 * 256;                  // private scratch: six tables of 64 floats
+    static constexpr int T_G2 = 0, T_A = 64, T_RQ = 128, T_B = 192;
+    // P^T tile (tj, ti), tj <= ti
+    __host__ __device__ static constexpr int pidx(int tj, int ti) { return ti * (ti + 1) / 2 + tj; }
+
+    u32x4 ka[KP][4], qa[KP][4];             // K and Q row slots of the wave's next record
+    // carried from phase A to phase B
+    floatx4 GP[10];                         // (K_tj Q_ti^T): accumulator tile (tj, ti), lane (r, g) holds k_J . q_I, I = 16 ti + r, J = 16 tj + 4 g + e
+    float vgam, vdec, vgq;                  // lane = token: gamma_i, gamma_C / gamma_i, gamma_i / ||q_i||
+
+    __device__ __forceinline__ void prefetch(const ScanArgs<bf16_t>& a, long tok0, int clen, int h, int lane_, const char* kc,
+                                             const char* qc, int kq_row)
+    {
+        const int lane = opaque(lane_);
+        this->la_pre = lane < clen ? a.log_alpha[(size_t)(tok0 + lane) * a.H + h] : 0.f;
+        this->load_slots(qa, qc, lane, clen, kq_row);
+        this->load_slots(ka, kc, lane, clen, kq_row);
+    }
+
+    // Phase A (step c - 2): Q goes on into the ring (the T-side wave does the same with K); gates, tables, query
+    // norms; (Q K^T)^T on the matrix pipe.  qtile: the Q tile of the chunk's ring stage.
+    __device__ __forceinline__ void phase_a(float* hs, char* qtile, int lane_)
+    {
+        const int lane = opaque(lane_);
+        const int r = lane & 15, g = lane >> 4;
+        B::store_slots(qa, qtile, lane);
+        float av, gl2;
+        const float x2 = this->scan_gates(hs + T_G2, hs + T_B, lane, av, gl2);
+        vgam = __builtin_amdgcn_exp2f(x2);
+        vdec = __builtin_amdgcn_exp2f(gl2 - x2);
+        hs[T_A + lane] = av;
+        const floatx4 z4 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int i = 0; i < 10; ++i) GP[i] = z4;
+        float qss[4] = {0.f, 0.f, 0.f, 0.f};
+        static_for<KP>([&](auto kc_) {
+            constexpr int kp = kc_;
+            static_for<4>([&](auto tic) {
+                constexpr int ti = tic;
+                const u32x4 q = qa[kp][ti];
+                const u32x2 qb0 = {q[0], q[1]}, qb1 = {q[2], q[3]};
+                static_for<ti + 1>([&](auto tjc) {
+                    constexpr int tj = tjc;
+                    mma_bf16(GP[pidx(tj, ti)], ka[kp][tj], qb0, qb1);      // rows <- K block tj, column <- Q block ti
+                });
+                if constexpr (NQ) {
+#pragma unroll
+                    for (int m = 0; m < 4; ++m) {
+                        const float x0 = __uint_as_float(q[m] << 16), x1 = __uint_as_float(q[m] & 0xffff0000u);
+                        qss[ti] += x0 * x0; qss[ti] += x1 * x1;
+                    }
+                }
+            });
+        });
+        if constexpr (NQ) {
+#pragma unroll
+            for (int it = 0; it < 4; ++it) {
+                float ss = qss[it];
+                ss += __shfl_xor(ss, 16, kWave);
+                ss += __shfl_xor(ss, 32, kWave);
+                if (g == 0) hs[T_RQ + 16 * it + r] = ss > 0.f ? 1.0f / sqrtf(ss) : 0.f;
+            }
+            wave_lds_fence();
+            vgq = vgam * hs[T_RQ + lane];
+        } else {
+            vgq = vgam;
+        }
+#pragma unroll
+        for (int i = 0; i < 10; ++i) B::keep(GP[i]);
+    }
+
+    // Phase B (step c - 1): decay and mask, the record.  Row token I = 16 ti + r, column token J = 16 tj + 4 g + e.
+    __device__ __forceinline__ void phase_b(const float* hs, char* rec, int clen, int lane_)
+    {
+        const int lane = opaque(lane_);
+        const int r = lane & 15, g = lane >> 4;
+        const u32x2 zq = {0u, 0u};
+        u32x2 Pt[10];
+        static_for<4>([&](auto tic) {
+            constexpr int ti = tic;
+            const float rq_r = NQ ? hs[T_RQ + 16 * ti + r] : 1.f;
+            // rows beyond a short chunk are zero: folded into the row factors
+            const float live = (clen == 64 || 16 * ti + r < clen) ? 1.f : 0.f;
+            const float aq_r = hs[T_A + 16 * ti + r] * rq_r * live;
+            static_for<ti>([&](auto tjc) {
+                constexpr int tj = tjc;
+                const floatx4 bq = *reinterpret_cast<const floatx4*>(hs + T_B + 64 * (ti - 1) + 16 * tj + 4 * g);
+                Pt[pidx(tj, ti)] = to_quad((bq * aq_r) * GP[pidx(tj, ti)]);
+            });
+            const floatx4 gq = *reinterpret_cast<const floatx4*>(hs + T_G2 + 16 * ti + 4 * g);
+            const float g2r = hs[T_G2 + 16 * ti + r], rl = rq_r * live;
+            floatx4 p;
+#pragma unroll
+            for (int e = 0; e < 4; ++e)                  // diagonal tile: 2^(g_I - g_J), J <= I
+                p[e] = (4 * g + e <= r) ? __builtin_amdgcn_exp2f(fminf(g2r - gq[e], 0.f)) * rl * GP[pidx(ti, ti)][e] : 0.f;
+            Pt[pidx(ti, ti)] = to_quad(p);
+        });
+        // tile-pairs in record order (ti, jp) = (0,0) (1,0) (2,0) (2,1) (3,0) (3,1); tile (ti, tj) of P in A-operand order
+        // is (P^T)(tj, ti)
+        B::slot(rec, B::TPB, 0, lane, Pt[pidx(0, 0)], zq);
+        B::slot(rec, B::TPB, 1, lane, Pt[pidx(0, 1)], Pt[pidx(1, 1)]);
+        B::slot(rec, B::TPB, 2, lane, Pt[pidx(0, 2)], Pt[pidx(1, 2)]);
+        B::slot(rec, B::TPB, 3, lane, Pt[pidx(2, 2)], zq);
+        B::slot(rec, B::TPB, 4, lane, Pt[pidx(0, 3)], Pt[pidx(1, 3)]);
+        B::slot(rec, B::TPB, 5, lane, Pt[pidx(2, 3)], Pt[pidx(3, 3)]);
+        float* dec = reinterpret_cast<float*>(rec + 2 * B::TPB);
+        dec[lane] = vgam;
+        dec[64 + lane] = vdec;
+        dec[128 + lane] = vgq;
+    }
 };
 
 }  // namespace
@@ -71,10 +502,11 @@ struct Cfg {
 // into the third vector of the record, gamma_i/||q_i||, read here in place of gamma_i for the Q S term.
 // DG: diagonal gating (App. B): a.k = K o Gamma and a.q = Q o Gamma feed K S and Q S, a.kt_src = K o (gamma_C/Gamma)
 // the state update, the records carry unit decay vectors and the state rows decay by a.gc_vec (see intra_diag_kernel).
-template <int DK, int NW, bool NQ, bool DG = false>
-__global__ __launch_bounds__(64 * NW + 64) void scan_bf16_kernel(ScanArgs<bf16_t> a)
+// FU: fused mode, see the top of the file; a.wsT / a.wsP / a.wsG are not used, a.log_alpha / a.eta / a.eps are.
+template <int DK, int NW, bool NQ, bool DG = false, bool FU = false>
+__global__ __launch_bounds__(64 * NW + (FU ? 384 : 64)) void scan_bf16_kernel(ScanArgs<bf16_t> a)
 {
-    typedef Cfg<DK, NW, DG> C;
+    typedef Cfg<DK, NW, DG, FU> C;
     constexpr int NTH = C::NTH, KB = C::KB, KP = C::KP, SLW = C::SLW, RB = C::RB, PPR = C::PPR, RPB = C::RPB,
                   VRW = C::VRW, VPP = C::VPP, RPV = C::RPV, ORB = C::ORB, NST = C::NST;
 
@@ -93,7 +525,7 @@ __global__ __launch_bounds__(64 * NW + 64) void scan_bf16_kernel(ScanArgs<bf16_t
     if (chain >= n_chains) return;
     const int s = chain / a.H, h = chain % a.H;
     long t0; int len, ch0;
-    if (a.cu_seqlens) { t0 = a.cu_seqlens[s]; len = a.cu_seqlens[s + 1] - (int)t0; ch0 = a.chunk_off[s]; }
+    if (a.cu_seqlens) { t0 = a.cu_seqlens[s]; len = a.cu_seqlens[s + 1] - (int)t0; ch0 = FU ? 0 : a.chunk_off[s]; }
     else if (a.seg_G > 0) {                              // segment sg of sequence n: chunks [sg Lc, (sg + 1) Lc)
         const int n = s / a.seg_G, sg = s % a.seg_G;
         const int tok = min(sg * a.seg_Lc * 64, a.T);
@@ -122,7 +554,7 @@ __global__ __launch_bounds__(64 * NW + 64) void scan_bf16_kernel(ScanArgs<bf16_t
     const char* k2base = DG ? reinterpret_cast<const char*>(a.kt_src) + (size_t)t0 * kq_row + (size_t)h * DK * 2 : nullptr;
     const char* gcbase = DG ? reinterpret_cast<const char*>(a.gc_vec) + ((size_t)ch0 * a.H + h) * DK * 4 : nullptr;
     constexpr int REC = ws_record_bytes<bf16_t>();
-    const char* tpbase = reinterpret_cast<const char*>(a.wsT) + ((size_t)ch0 * a.H + h) * REC;
+    const char* tpbase = FU ? nullptr : reinterpret_cast<const char*>(a.wsT) + ((size_t)ch0 * a.H + h) * REC;
 
     // ---- loop-invariant per-lane offsets ------------------------------------------------------------
     // copy engine, global side: lane l of copy block b fills LDS bytes [1024 b + 16 l, +16) of a tile, i.e.
@@ -159,52 +591,59 @@ __global__ __launch_bounds__(64 * NW + 64) void scan_bf16_kernel(ScanArgs<bf16_t
         const char* vc = vbase + (size_t)(64 * c) * v_row;
         const char* tc = tpbase + (size_t)c * a.H * REC;
         if (clen == 64) {
-            static_for<C::NKB>([&](auto i) {
-                const int b = i;
-                const size_t o = (size_t)(b * RPB) * kq_row;
-                const int lo = (RPB == 4 && (b & 1)) ? gk[1] : gk[0];
-                dma16(kc + o, lo, st + b * 1024);
-                dma16(qc + o, lo, st + C::OFF_Q + b * 1024);
-                if constexpr (DG) dma16(k2base + (size_t)(64 * c) * kq_row + o, lo, st + C::OFF_K2 + b * 1024);
-            });
+            if constexpr (!FU) {                         // fused mode: the helper waves bring K and Q
+                static_for<C::NKB>([&](auto i) {
+                    const int b = i;
+                    const size_t o = (size_t)(b * RPB) * kq_row;
+                    const int lo = (RPB == 4 && (b & 1)) ? gk[1] : gk[0];
+                    dma16(kc + o, lo, st + b * 1024);
+                    dma16(qc + o, lo, st + C::OFF_Q + b * 1024);
+                    if constexpr (DG) dma16(k2base + (size_t)(64 * c) * kq_row + o, lo, st + C::OFF_K2 + b * 1024);
+                });
+            }
             static_for<C::NVB>([&](auto i) {
                 const int b = i;
                 dma16(vc + (size_t)(b * RPV) * v_row, gv, st + C::OFF_V + b * 1024);
             });
         } else {                                         // ragged last chunk: clamp the row
-            static_for<C::NKB>([&](auto i) {
-                const int b = i;
-                const int row = b * RPB + lrow;
-                const int lo = min(row, clen - 1) * (int)kq_row + ((pcol ^ swz_bits(row)) * 16);
-                dma16(kc, lo, st + b * 1024);
-                dma16(qc, lo, st + C::OFF_Q + b * 1024);
-                if constexpr (DG) dma16(k2base + (size_t)(64 * c) * kq_row, lo, st + C::OFF_K2 + b * 1024);
-            });
+            if constexpr (!FU) {
+                static_for<C::NKB>([&](auto i) {
+                    const int b = i;
+                    const int row = b * RPB + lrow;
+                    const int lo = min(row, clen - 1) * (int)kq_row + ((pcol ^ swz_bits(row)) * 16);
+                    dma16(kc, lo, st + b * 1024);
+                    dma16(qc, lo, st + C::OFF_Q + b * 1024);
+                    if constexpr (DG) dma16(k2base + (size_t)(64 * c) * kq_row, lo, st + C::OFF_K2 + b * 1024);
+                });
+            }
             static_for<C::NVB>([&](auto i) {
                 const int b = i;
                 const int row = b * RPV + lane / VPP;
                 dma16(vc, min(row, clen - 1) * (int)v_row + (lane % VPP) * 16, st + C::OFF_V + b * 1024);
             });
         }
-        static_for<C::NTB>([&](auto i) {
-            const int b = i;
-            dma16(tc + b * 1024, lane * 16, st + C::OFF_T + b * 1024);
-        });
-        if (lane < 48) dma16(tc + 2 * C::TPB, lane * 16, st + C::OFF_EG);   // gamma_i | gamma_C/gamma_i | gamma_i/||q_i||: 768 bytes
+        if constexpr (!FU) {
+            static_for<C::NTB>([&](auto i) {
+                const int b = i;
+                dma16(tc + b * 1024, lane * 16, st + C::OFF_T + b * 1024);
+            });
+            if (lane < 48) dma16(tc + 2 * C::TPB, lane * 16, st + C::OFF_EG);   // gamma_i | gamma_C/gamma_i | gamma_i/||q_i||: 768 bytes
+        }
         if constexpr (DG) {
             if (lane < DK / 4) dma16(gcbase + (size_t)c * a.H * DK * 4, lane * 16, st + C::OFF_GC);   // gamma_C per channel
         }
     };
 
     // ---- one chunk of the recurrence for this wave's 16 columns ------------------------------------
-    auto compute = [&](const char* st, char* ost) {
+    // rc: where T', P and the vectors of this chunk are (the ring stage itself, or a record buffer when fused)
+    auto compute = [&](const char* st, const char* rc, char* ost) {
         const char* pK0 = st + oK[0];
         const char* pK1 = st + oK[1];
         const char* pT0 = st + oKT[0];
         const char* pT1 = st + oKT[1];
-        const char* pS = st + lane * 16;                 // T' / P slots
+        const char* pS = rc + lane * 16;                 // T' / P slots
         const char* pV = st + C::OFF_V + oV;
-        const char* pG = st + C::OFF_EG + 16 * g;        // 4 consecutive floats: rows 4 g .. 4 g + 3
+        const char* pG = rc + C::R_EG + 16 * g;          // 4 consecutive floats: rows 4 g .. 4 g + 3
         auto kslot = [&](int it, int kp, int base) {     // base 0: K, OFF_Q: Q
             return ld16(((kp & 1) ? pK1 : pK0) + base + 16 * it * RB + 128 * (kp >> 1));
         };
@@ -216,7 +655,7 @@ __global__ __launch_bounds__(64 * NW + 64) void scan_bf16_kernel(ScanArgs<bf16_t
         };
 
         // bf16 copy of the incoming state (B operand of K S and Q S); the fp32 state is decayed right away
-        const float gC = *reinterpret_cast<const float*>(st + C::OFF_EG + 63 * 4);
+        const float gC = *reinterpret_cast<const float*>(rc + C::R_EG + 63 * 4);
         u32x2 Sq[KB];
 #pragma unroll
         for (int kt = 0; kt < KB; ++kt) {
@@ -256,7 +695,7 @@ __global__ __launch_bounds__(64 * NW + 64) void scan_bf16_kernel(ScanArgs<bf16_t
         }
         u32x4 tsl[kTriPairs];
 #pragma unroll
-        for (int i = 0; i < kTriPairs; ++i) tsl[i] = ld16(pS + C::OFF_T + i * 1024);
+        for (int i = 0; i < kTriPairs; ++i) tsl[i] = ld16(pS + C::R_T + i * 1024);
         u32x4 qa[2][4];
 #pragma unroll
         for (int it = 0; it < 4; ++it) qa[0][it] = kslot(it, 0, C::OFF_Q);
@@ -272,51 +711,95 @@ __global__ __launch_bounds__(64 * NW + 64) void scan_bf16_kernel(ScanArgs<bf16_t
             for (int it = 0; it < 4; ++it) mma_bf16(qs[it], qa[kp & 1][it], Sq[2 * kp], Sq[2 * kp + 1]);
         }
         u32x2 Xq[4];
+        floatx4 Xf[3];                                   // fused mode: rows 16.. of X stay in fp32 until beta and the L U terms are in
+        Xq[0] = to_quad(quad_to_f(vq[0]) - egv[0] * ks[0]);
 #pragma unroll
-        for (int it = 0; it < 4; ++it) Xq[it] = to_quad(quad_to_f(vq[it]) - egv[it] * ks[it]);
+        for (int it = 1; it < 4; ++it) {
+            Xf[it - 1] = quad_to_f(vq[it]) - egv[it] * ks[it];
+            if constexpr (!FU) Xq[it] = to_quad(Xf[it - 1]);
+        }
 
         // K^T slots of the first state tiles and the P slots: on their way during the solve
         u32x2 kt[2][KB][2];                              // [token pair jp][state tile][token block]
 #pragma unroll
         for (int t = 0; t < KB; ++t) ktslot(t, 0, kt[0][t][0], kt[0][t][1]);
 
-        // ---- U = T' X (T' lower triangular)
+        // ---- U = T' X (T' lower triangular); fused mode: the solve split at row 32 (see the helper section),
+        //      U_top = T'11 X_top, U_bot = T22 (B_bot X_bot - L21 U_top)
         floatx4 U[4];
-#pragma unroll
-        for (int it = 0; it < 4; ++it) {
-            U[it] = floatx4{0.f, 0.f, 0.f, 0.f};
-            mma_bf16(U[it], tsl[tri_pair(it, 0)], Xq[0], Xq[1]);
-        }
-        mma_bf16(U[2], tsl[tri_pair(2, 1)], Xq[2], Xq[3]);
-        mma_bf16(U[3], tsl[tri_pair(3, 1)], Xq[2], Xq[3]);
-#pragma unroll
-        for (int t = 0; t < KB; ++t) ktslot(t, 1, kt[1][t][0], kt[1][t][1]);
-        u32x4 psl[kTriPairs];
-#pragma unroll
-        for (int i = 0; i < kTriPairs; ++i) psl[i] = ld16(pS + C::OFF_P + i * 1024);
-
         u32x2 Uq[4], Udq[4];
+        u32x4 psl[kTriPairs];
+        if constexpr (!FU) {
 #pragma unroll
-        for (int it = 0; it < 4; ++it) {
-            Udq[it] = to_quad(U[it] * edv[it]);
-            Uq[it] = to_quad(U[it]);
+            for (int it = 0; it < 4; ++it) {
+                U[it] = floatx4{0.f, 0.f, 0.f, 0.f};
+                mma_bf16(U[it], tsl[tri_pair(it, 0)], Xq[0], Xq[1]);
+            }
+            mma_bf16(U[2], tsl[tri_pair(2, 1)], Xq[2], Xq[3]);
+            mma_bf16(U[3], tsl[tri_pair(3, 1)], Xq[2], Xq[3]);
+#pragma unroll
+            for (int t = 0; t < KB; ++t) ktslot(t, 1, kt[1][t][0], kt[1][t][1]);
+#pragma unroll
+            for (int i = 0; i < kTriPairs; ++i) psl[i] = ld16(pS + C::R_P + i * 1024);
+#pragma unroll
+            for (int it = 0; it < 4; ++it) {
+                Udq[it] = to_quad(U[it] * edv[it]);
+                Uq[it] = to_quad(U[it]);
+            }
         }
-
-        // ---- S = gamma_C S + K^T (diag(gamma_C/gamma_i) U): the only thing the next chunk waits for
-#pragma unroll
-        for (int t = 0; t < KB; ++t) mma_bf16(S[t], kt[0][t][0], kt[0][t][1], Udq[0], Udq[1]);
-#pragma unroll
-        for (int t = 0; t < KB; ++t) mma_bf16(S[t], kt[1][t][0], kt[1][t][1], Udq[2], Udq[3]);
-
-        // ---- O = D_gamma Q S + P U (P lower triangular), staged token-major for 16-byte global stores
         floatx4 o[4];
+        if constexpr (!FU) {
+            // ---- S = gamma_C S + K^T (diag(gamma_C/gamma_i) U): the only thing the next chunk waits for
 #pragma unroll
-        for (int it = 0; it < 4; ++it) {
-            if constexpr (NQ) o[it] = ld_f4(pG + 512 + 64 * it) * qs[it]; else o[it] = egv[it] * qs[it];
-            mma_bf16(o[it], psl[tri_pair(it, 0)], Uq[0], Uq[1]);
+            for (int t = 0; t < KB; ++t) mma_bf16(S[t], kt[0][t][0], kt[0][t][1], Udq[0], Udq[1]);
+#pragma unroll
+            for (int t = 0; t < KB; ++t) mma_bf16(S[t], kt[1][t][0], kt[1][t][1], Udq[2], Udq[3]);
+
+            // ---- O = D_gamma Q S + P U (P lower triangular), staged token-major for 16-byte global stores
+#pragma unroll
+            for (int it = 0; it < 4; ++it) {
+                if constexpr (NQ) o[it] = ld_f4(pG + 512 + 64 * it) * qs[it]; else o[it] = egv[it] * qs[it];
+                mma_bf16(o[it], psl[tri_pair(it, 0)], Uq[0], Uq[1]);
+            }
+            mma_bf16(o[2], psl[tri_pair(2, 1)], Uq[2], Uq[3]);
+            mma_bf16(o[3], psl[tri_pair(3, 1)], Uq[2], Uq[3]);
+        } else {
+            // Fused mode: block forward substitution over the four 16-row blocks (see the helper section for the record's
+            // tiles), U_0 = (D0 B0) X_0, U_t = D_t (B_t X_t - sum_{j<t} L_tj U_j).  Its chain of eight dependent
+            // products is interleaved with the products that need only the rows already solved: the first half of the
+            // state update and of P U.
+            const u32x2 zq = {0u, 0u};
+            const floatx4 z4 = {0.f, 0.f, 0.f, 0.f};
+            const floatx4 bv1 = ld_f4(pG + 768 + 64), bv2 = ld_f4(pG + 768 + 128), bv3 = ld_f4(pG + 768 + 192);   // beta of rows 16 t + 4 g ..
+            U[0] = z4; mma_bf16(U[0], tsl[tri_pair(0, 0)], Xq[0], zq);
+#pragma unroll
+            for (int t = 0; t < KB; ++t) ktslot(t, 1, kt[1][t][0], kt[1][t][1]);
+#pragma unroll
+            for (int i = 0; i < kTriPairs; ++i) psl[i] = ld16(pS + C::R_P + i * 1024);
+#pragma unroll
+            for (int it = 0; it < 4; ++it) {
+                if constexpr (NQ) o[it] = ld_f4(pG + 512 + 64 * it) * qs[it]; else o[it] = egv[it] * qs[it];
+            }
+            Uq[0] = to_quad(U[0]); Udq[0] = to_quad(U[0] * edv[0]);
+            floatx4 W = z4; mma_bf16(W, tsl[tri_pair(1, 0)], Uq[0], zq);                 // L10 U_0
+            U[1] = z4; mma_bf16(U[1], tsl[tri_pair(1, 0)], zq, to_quad(bv1 * Xf[0] - W));   // D1 (..)
+            Uq[1] = to_quad(U[1]); Udq[1] = to_quad(U[1] * edv[1]);
+            W = z4; mma_bf16(W, tsl[tri_pair(2, 0)], Uq[0], Uq[1]);                       // L20 U_0 + L21 U_1
+            floatx4 W3 = z4; mma_bf16(W3, tsl[tri_pair(3, 0)], Uq[0], Uq[1]);             // L30 U_0 + L31 U_1
+#pragma unroll
+            for (int t = 0; t < KB; ++t) mma_bf16(S[t], kt[0][t][0], kt[0][t][1], Udq[0], Udq[1]);
+#pragma unroll
+            for (int it = 0; it < 4; ++it) mma_bf16(o[it], psl[tri_pair(it, 0)], Uq[0], Uq[1]);
+            U[2] = z4; mma_bf16(U[2], tsl[tri_pair(2, 1)], to_quad(bv2 * Xf[1] - W), zq);    // D2 (..)
+            Uq[2] = to_quad(U[2]); Udq[2] = to_quad(U[2] * edv[2]);
+            mma_bf16(W3, tsl[tri_pair(3, 1)], Uq[2], zq);                                  // + L32 U_2
+            U[3] = z4; mma_bf16(U[3], tsl[tri_pair(3, 1)], zq, to_quad(bv3 * Xf[2] - W3));   // D3 (..)
+            Uq[3] = to_quad(U[3]); Udq[3] = to_quad(U[3] * edv[3]);
+#pragma unroll
+            for (int t = 0; t < KB; ++t) mma_bf16(S[t], kt[1][t][0], kt[1][t][1], Udq[2], Udq[3]);
+            mma_bf16(o[2], psl[tri_pair(2, 1)], Uq[2], Uq[3]);
+            mma_bf16(o[3], psl[tri_pair(3, 1)], Uq[2], Uq[3]);
         }
-        mma_bf16(o[2], psl[tri_pair(2, 1)], Uq[2], Uq[3]);
-        mma_bf16(o[3], psl[tri_pair(3, 1)], Uq[2], Uq[3]);
         // transposed 4x4 inside each quad of lanes (see quad_transpose4x4): one 64-bit LDS write per tile (a compute
         // wave is bound by its instruction count)
 #pragma unroll
@@ -339,11 +822,72 @@ __global__ __launch_bounds__(64 * NW + 64) void scan_bf16_kernel(ScanArgs<bf16_t
     char* ost0 = lds + NST * C::STAGE;
     char* ost1 = ost0 + C::OSB;
 
-    if (wave == NW) {
+    // Fused mode: every wave passes nch + 2 barriers.  Step s = -2 .. nch - 1 ends with one; in step s the compute waves
+    // work on chunk s, the helpers of parity (s & 1) are in phase A of chunk s + 2 and those of the other parity in
+    // phase B of chunk s + 1, whose record goes into buffer (s + 1) & 1, which chunk s - 1 left free.
+    if constexpr (FU) {
+        if (wave == NW + 3) {                            // keeps the barriers company (see Cfg::NWAVES)
+            for (int s = -2; s < nch; ++s) __syncthreads();
+            return;
+        }
+        // A helper of parity hh takes the chunks c = hh, hh + 2, ..: phase A in step c - 2, phase B in step c - 1, so it
+        // simply alternates the two (the odd one idles through step -2), and tops up the barrier count at the end.
+        if (wave == NW || wave == NW + 1) {              // T-side helpers
+            const int hh = wave - NW;
+            float* hs = reinterpret_cast<float*>(lds + C::OFF_HST + hh * C::HSCR_T);
+            THelper<DK> hp;
+            hp.init_rows(lane, (int)kq_row);
+            auto fetch = [&](int c) {
+                hp.prefetch(a, t0 + 64L * c, min(64, len - 64 * c), h, lane, kbase + (size_t)(64 * c) * kq_row, (int)kq_row);
+            };
+            int nb = 0;
+            if (hh < nch) fetch(hh);                     // this wave's first record
+            if (hh == 1) { __syncthreads(); ++nb; }
+            for (int c = hh; c < nch; c += 2) {
+                hp.phase_a(a, hs, lds + (c % NST) * C::STAGE, lane);
+                __syncthreads(); ++nb;
+                if (c + 2 < nch) fetch(c + 2);           // on their way during this step, used in the next
+                hp.phase_b(hs, lds + C::OFF_REC + (c & 1) * C::RECB, lane);
+                __syncthreads(); ++nb;
+            }
+            for (; nb < nch + 2; ++nb) __syncthreads();
+            return;
+        }
+        if (wave == NW + 4 || wave == NW + 5) {          // P-side helpers
+            // the P-side wave of the even chunks shares its SIMD with the T-side wave of the odd ones and vice versa: in
+            // every step each of the two SIMDs then has one wave in phase A and one in phase B
+            const int hh = 1 - (wave - NW - 4);
+            float* hs = reinterpret_cast<float*>(lds + C::OFF_HSP + hh * C::HSCR_P);
+            PHelper<DK, NQ> hp;
+            hp.init_rows(lane, (int)kq_row);
+            auto fetch = [&](int c) {
+                hp.prefetch(a, t0 + 64L * c, min(64, len - 64 * c), h, lane, kbase + (size_t)(64 * c) * kq_row,
+                            qbase + (size_t)(64 * c) * kq_row, (int)kq_row);
+            };
+            int nb = 0;
+            if (hh < nch) fetch(hh);
+            if (hh == 1) { __syncthreads(); ++nb; }
+            for (int c = hh; c < nch; c += 2) {
+                hp.phase_a(hs, lds + (c % NST) * C::STAGE + C::OFF_Q, lane);
+                __syncthreads(); ++nb;
+                if (c + 2 < nch) fetch(c + 2);
+                hp.phase_b(hs, lds + C::OFF_REC + (c & 1) * C::RECB, min(64, len - 64 * c), lane);
+                __syncthreads(); ++nb;
+            }
+            for (; nb < nch + 2; ++nb) __syncthreads();
+            return;
+        }
+    }
+
+    if (wave == C::W_COPY) {
         // ---- the copy wave: keeps chunks c+1 .. c+NST-1 on their way while chunk c is computed ---------
+        // In the fused mode it shares its SIMD with a compute wave, which would otherwise leave it an issue slot only
+        // now and then (measured: 4 000 cycles to issue one chunk's 36 copies): its few instructions go first.
+        if constexpr (FU) __builtin_amdgcn_s_setprio(3);
 #pragma unroll
         for (int p = 0; p < NST - 1; ++p)
             if (p < nch) issue(p, lds + p * C::STAGE);
+        if constexpr (FU) __syncthreads();               // step -2
         if (NST == 3 && nch > 1) wait_vmcnt<(NST == 3 ? C::NDMA : 0)>(); else wait_vmcnt<0>();      // chunk 0 has landed
         __syncthreads();
         int spre = NST - 1;                              // ring position of chunk c + NST - 1
@@ -361,11 +905,12 @@ __global__ __launch_bounds__(64 * NW + 64) void scan_bf16_kernel(ScanArgs<bf16_t
     }
 
     // ---- compute waves ---------------------------------------------------------------------------------
-    __syncthreads();                                     // chunk 0 is in stage 0
+    if constexpr (FU) __syncthreads();                   // step -2
+    __syncthreads();                                     // chunk 0 is in stage 0 (and its record in buffer 0)
     int scur = 0;                                        // ring position of chunk c
     for (int c = 0; c < nch; ++c) {
         char* ost = (c & 1) ? ost1 : ost0;
-        compute(lds + scur * C::STAGE, ost);
+        compute(lds + scur * C::STAGE, FU ? lds + C::OFF_REC + (c & 1) * C::RECB : lds + scur * C::STAGE, ost);
         // One barrier per chunk: staged outputs before their write-out; chunk c+1's operands before their
         // use; all reads of this stage before it is refilled next iteration; and the write-out of chunk
         // c-1 (finished by every compute wave before it arrives here) before the staging tile of that
@@ -416,6 +961,29 @@ hipError_t launch_scan_bf16(const ScanArgs<bf16_t>& a, int dk, int waves, hipStr
 {
     if (dk == 64) return launch_dk<64>(a, waves, st);
     return launch_dk<128>(a, waves, st);
+}
+
+template <int DK>
+static hipError_t launch_fused_dk(const ScanArgs<bf16_t>& a, int waves, hipStream_t st)
+{
+    const int n_states = a.n_seq > 0 ? a.n_seq : (a.seg_G > 0 ? a.N * a.seg_G : a.N);
+    const int n_chains = n_states * a.H;
+    if (n_chains == 0) return hipSuccess;
+    const dim3 grid((unsigned)(((n_chains + 7) / 8) * 8 * (a.dv / (16 * waves))));
+    const bool nq = (a.opts & kOptNormalizeQ) != 0;
+    if (waves == 1) {
+        if (nq) hipLaunchKernelGGL((scan_bf16_kernel<DK, 1, true, false, true>), grid, dim3(448), 0, st, a);
+        else    hipLaunchKernelGGL((scan_bf16_kernel<DK, 1, false, false, true>), grid, dim3(448), 0, st, a);
+    } else {
+        if (nq) hipLaunchKernelGGL((scan_bf16_kernel<DK, 2, true, false, true>), grid, dim3(512), 0, st, a);
+        else    hipLaunchKernelGGL((scan_bf16_kernel<DK, 2, false, false, true>), grid, dim3(512), 0, st, a);
+    }
+    return hipGetLastError();
+}
+hipError_t launch_scan_fused_bf16(const ScanArgs<bf16_t>& a, int dk, int waves, hipStream_t st)
+{
+    if ((waves != 1 && waves != 2) || !a.log_alpha || !a.eta) return hipErrorInvalidValue;
+    return dk == 64 ? launch_fused_dk<64>(a, waves, st) : launch_fused_dk<128>(a, waves, st);
 }
 
 // diagonal gating: waves = 1 or 2, fixed-length or packed batches, no options, no segments

@@ -5,8 +5,6 @@
 // columns of a few rows, issues all of its 128-bit loads before anything else, and the two
 // reductions over d_k that the step needs (p = S^T k and r = S^T q) are taken from the same
 // registers.  The read-out uses o = S_new^T q = alpha r + beta (k.q) e, which avoids a second pass.
-#include <stdlib.h>
-
 #include "kla_common.hpp"
 #include "kla_kernels.hpp"
 
@@ -157,14 +155,13 @@ static hipError_t launch_decode_nt(const T* q, const T* k, const T* v, const flo
 // Cache policy of the state accesses.  A state set that cannot stay in the 256 MB Infinity Cache between
 // two steps (large batch, or many layers taking turns) is streamed with non-temporal loads and stores:
 // measured 12.7 us instead of 16.8 us per 67 MB step.  A small one is left cacheable (8.7 us when it is
-// resident).  KLA_DECODE_NT = 0..3 overrides (bit 0: loads, bit 1: stores).
+// resident).  nt_force = 0..3 overrides (bit 0: loads, bit 1: stores); -1 = this rule.
 template <typename T, int DK>
 static hipError_t launch_decode_dk(const T* q, const T* k, const T* v, const float* la, const float* eta,
-                                   float eps, float* S, T* o, int BH, int dv, int slice, unsigned opts, hipStream_t st)
+                                   float eps, float* S, T* o, int BH, int dv, int slice, int nt_force, unsigned opts, hipStream_t st)
 {
     int nt = ((size_t)BH * DK * dv * sizeof(float) >= ((size_t)16 << 20)) ? 3 : 0;
-    const char* env = getenv("KLA_DECODE_NT");
-    if (env && env[0] >= '0' && env[0] <= '3') nt = env[0] - '0';
+    if (nt_force >= 0 && nt_force <= 3) nt = nt_force;
     switch (nt) {
         case 0:  return launch_decode_nt<T, DK, 0>(q, k, v, la, eta, eps, S, o, BH, dv, slice, opts, st);
         case 1:  return launch_decode_nt<T, DK, 1>(q, k, v, la, eta, eps, S, o, BH, dv, slice, opts, st);
@@ -175,15 +172,15 @@ static hipError_t launch_decode_dk(const T* q, const T* k, const T* v, const flo
 
 template <typename T>
 hipError_t launch_decode(const T* q, const T* k, const T* v, const float* la, const float* eta, float eps,
-                         float* S, T* o, int BH, int dk, int dv, int slice, unsigned opts, hipStream_t st)
+                         float* S, T* o, int BH, int dk, int dv, int slice, int nt_force, unsigned opts, hipStream_t st)
 {
-    if (dk == 64) return launch_decode_dk<T, 64>(q, k, v, la, eta, eps, S, o, BH, dv, slice, opts, st);
-    return launch_decode_dk<T, 128>(q, k, v, la, eta, eps, S, o, BH, dv, slice, opts, st);
+    if (dk == 64) return launch_decode_dk<T, 64>(q, k, v, la, eta, eps, S, o, BH, dv, slice, nt_force, opts, st);
+    return launch_decode_dk<T, 128>(q, k, v, la, eta, eps, S, o, BH, dv, slice, nt_force, opts, st);
 }
 template hipError_t launch_decode<float>(const float*, const float*, const float*, const float*, const float*,
-                                         float, float*, float*, int, int, int, int, unsigned, hipStream_t);
+                                         float, float*, float*, int, int, int, int, int, unsigned, hipStream_t);
 template hipError_t launch_decode<bf16_t>(const bf16_t*, const bf16_t*, const bf16_t*, const float*, const float*,
-                                          float, float*, bf16_t*, int, int, int, int, unsigned, hipStream_t);
+                                          float, float*, bf16_t*, int, int, int, int, int, unsigned, hipStream_t);
 
 // eq. (3) alone: one group of DK/8 lanes per row, each lane squares 8 consecutive elements.
 template <typename T, int DK>

@@ -17,7 +17,7 @@ constexpr unsigned kOptNoStore = 0x200u;
 // ---- decode step and stand-alone coefficient -----------------------------------------------
 template <typename T>
 hipError_t launch_decode(const T* q, const T* k, const T* v, const float* log_alpha, const float* eta, float eps,
-                         float* S, T* o, int BH, int dk, int dv, int slice, unsigned opts, hipStream_t st);
+                         float* S, T* o, int BH, int dk, int dv, int slice, int nt_force, unsigned opts, hipStream_t st);
 template <typename T>
 hipError_t launch_beta(const T* k, const float* eta, float eps, float* beta, long n_rows, int dk, hipStream_t st);
 
@@ -69,6 +69,8 @@ template <typename E> struct ScanArgs {
     // Diagonal gating (generic kernel only): the transposed K operand of the state update comes from kt_src instead of
     // k, and the state decays per row by gc_vec[chunk-head][dk] instead of by gamma_C.  Both NULL otherwise.
     const E* kt_src; const float* gc_vec;
+    // Fused bf16 scan only (the stage forms T', P and the decay vectors itself; wsT, wsP, wsG unused): the gates.
+    const float* log_alpha = nullptr; const float* eta = nullptr; float eps = 0.f;
 };
 // waves = 1, 2 or 4: each wave of a workgroup carries 16 state columns through the whole sequence
 template <typename E> hipError_t launch_scan(const ScanArgs<E>& a, int dk, int waves, hipStream_t st);
@@ -78,6 +80,8 @@ template <typename E> hipError_t launch_scan_diag(const ScanArgs<E>& a, int dk, 
 hipError_t launch_intra_bf16(const IntraArgs<bf16_t>& a, int dk, int n_chunks, hipStream_t st);
 hipError_t launch_scan_bf16(const ScanArgs<bf16_t>& a, int dk, int waves, hipStream_t st);
 hipError_t launch_scan_bf16_diag(const ScanArgs<bf16_t>& a, int dk, int waves, hipStream_t st);   // diagonal gating
+// Fused forward (no intra-chunk stage, no workspace): waves = 1 or 2; fixed-length, packed or segmented batches.
+hipError_t launch_scan_fused_bf16(const ScanArgs<bf16_t>& a, int dk, int waves, hipStream_t st);
 
 // Segment-parallel scan of long sequences in small batches (bf16): per-segment affine maps of the state, their
 // prefix composition, then the ordinary scan over all segments at once.  `maps` holds (G-1) x [N | M] per

@@ -38,11 +38,14 @@ def test_status_strings():
     assert "unknown" in lib.kla_status_string(-99).decode()
 
 
+UNFUSED = kla.tune(unfused=True)
+
+
 def test_workspace_bytes():
     lib = kla.lib()
-    f = lib.kla_chunk_fwd_workspace_bytes
-    # 4096 chunk-heads, bf16: a record of 2 x 6 KiB operand areas + 3 x 256 B of per-token factors, and 512 B of
-    # g and 1/|q| each, plus the (empty) offsets table
+    f = lambda *a: lib.kla_chunk_fwd_workspace_bytes_opts(*a, UNFUSED)
+    # two-kernel form, 4096 chunk-heads, bf16: a record of 2 x 6 KiB operand areas + 3 x 256 B of per-token factors, and
+    # 512 B of g and 1/|q| each, plus the (empty) offsets table
     n = f(8, 4096, 8, 128, 128, 64, kla.KLA_BF16, None, 0)
     assert n >= 4096 * (2 * 6144 + 768 + 512) and n <= 4096 * (2 * 6144 + 768 + 512) + 4 * 256
     assert f(8, 4096, 8, 128, 128, 64, kla.KLA_F32, None, 0) > n
@@ -53,6 +56,35 @@ def test_workspace_bytes():
     assert n2 >= 4 * 2 * (2 * 6144 + 768 + 512)
     bad = np.array([0, 10, 5, 200], dtype=np.int32)
     assert f(1, 200, 2, 64, 64, 64, kla.KLA_BF16, bad.ctypes.data, 3) == 0
+    # the plain query is the one with opts = 0; where the fused bf16 kernel runs nothing of the workspace is used and
+    # a token 256 bytes are reported; fp32 and wide value heads (four compute waves per workgroup) keep the two kernels
+    g = lib.kla_chunk_fwd_workspace_bytes
+    assert g(8, 4096, 8, 128, 128, 64, kla.KLA_BF16, None, 0) == 256
+    assert g(8, 4096, 8, 128, 128, 64, kla.KLA_BF16, None, 0) == lib.kla_chunk_fwd_workspace_bytes_opts(
+        8, 4096, 8, 128, 128, 64, kla.KLA_BF16, None, 0, 0)
+    assert g(8, 4096, 8, 128, 128, 64, kla.KLA_F32, None, 0) == f(8, 4096, 8, 128, 128, 64, kla.KLA_F32, None, 0)
+    assert g(64, 4096, 16, 128, 256, 64, kla.KLA_BF16, None, 0) == f(64, 4096, 16, 128, 256, 64, kla.KLA_BF16, None, 0)
+    assert g(1, 200, 2, 64, 64, 64, kla.KLA_BF16, bad.ctypes.data, 3) == 0
+    # tuning fields out of range are refused (0 from the queries, KLA_ERR_SHAPE from the calls)
+    assert lib.kla_chunk_fwd_workspace_bytes_opts(8, 4096, 8, 128, 128, 64, kla.KLA_BF16, None, 0, 17 << 10) == 0
+    assert lib.kla_chunk_fwd_workspace_bytes_opts(8, 4096, 8, 128, 128, 64, kla.KLA_BF16, None, 0, 1 << 25) == 0
+    assert lib.kla_chunk_fwd_workspace_bytes_opts(8, 4096, 8, 128, 128, 64, kla.KLA_BF16, None, 0, 4) == 0
+
+
+def test_tune_bits_match_the_header():
+    """The binding's tune() builds the KLA_TUNE_* fields of include/kla.h."""
+    hdr = open(kla.HEADER_PATH).read()
+    for name, val in (("KLA_TUNE_GENERIC_SCAN", 15), ("KLA_TUNE_GENERIC_INTRA", 16), ("KLA_TUNE_GENERIC_BWD", 17),
+                      ("KLA_TUNE_UNFUSED", 24)):
+        assert re.search(r"#define %s\s+\(1u << %d\)" % (name, val), hdr), name
+        assert getattr(kla, name) == 1 << val
+    assert kla.tune(scan_waves=4) == 3 << 8 and kla.tune(scan_waves=2) == 2 << 8
+    assert kla.tune(segments=16) == 16 << 10
+    assert kla.tune(decode_slice=256) == 4 << 18 and kla.tune(decode_slice=32) == 1 << 18
+    assert kla.tune(decode_nt=0) == 1 << 21 and kla.tune(decode_nt=3) == 4 << 21
+    assert kla.tune(generic_scan=True, generic_intra=True, generic_bwd=True, unfused=True) == (7 << 15) | (1 << 24)
+    with pytest.raises(ValueError):
+        kla.tune(scan_waves=3)
 
 
 def _chunk_call(**over):
@@ -111,6 +143,8 @@ def test_decode_and_beta_validation_errors():
     assert d(eps=-1e-3) == E_SHAPE
     assert d(dt=2) == E_DTYPE
     assert d(S=0x6004) == E_ALIGN
+    assert d(eta=0x5002) == E_ALIGN                 # the gates are fp32: 4-byte aligned, as in the chunk entry points
+    assert d(la=0x4001) == E_ALIGN
     assert d(B=0) == OK
     b = lambda **o: lib.kla_beta(*[{**dict(k=0x1000, eta=0x2000, eps=1e-6, beta=0x3000, n=10, dk=128,
                                            dt=kla.KLA_F32, st=None), **o}[n]
@@ -165,23 +199,19 @@ def test_option_entry_points_validate_like_the_plain_ones():
     assert dec(3, B=0) == OK
 
 
-def test_workspace_bytes_of_the_segmented_scan(monkeypatch):
+def test_workspace_bytes_of_the_segmented_scan():
     """A long sequence in a small bf16 batch is scanned in segments: the workspace then also holds, per
     (sequence, head), G-1 maps [N | M] and G incoming states in fp32."""
-    f = kla.lib().kla_chunk_fwd_workspace_bytes
-    monkeypatch.setenv("KLA_SCAN_SEGMENTS", "1")
-    base = f(1, 65536, 8, 128, 128, 64, kla.KLA_BF16, None, 0)
-    monkeypatch.setenv("KLA_SCAN_SEGMENTS", "4")
+    f = lambda *a, **kw: kla.lib().kla_chunk_fwd_workspace_bytes_opts(*a, kla.tune(**kw))
+    base = f(1, 65536, 8, 128, 128, 64, kla.KLA_BF16, None, 0, segments=1, unfused=True)
     extra = 8 * 128 * (3 * (128 + 128) + 4 * 128) * 4
-    assert base + extra <= f(1, 65536, 8, 128, 128, 64, kla.KLA_BF16, None, 0) <= base + extra + 512
-    assert f(1, 65536, 8, 128, 128, 64, kla.KLA_F32, None, 0) == \
-        (monkeypatch.setenv("KLA_SCAN_SEGMENTS", "1"), f(1, 65536, 8, 128, 128, 64, kla.KLA_F32, None, 0))[1]   # bf16 only
-    monkeypatch.delenv("KLA_SCAN_SEGMENTS")
+    assert base + extra <= f(1, 65536, 8, 128, 128, 64, kla.KLA_BF16, None, 0, segments=4) <= base + extra + 512
+    assert f(1, 65536, 8, 128, 128, 64, kla.KLA_F32, None, 0, segments=4) == \
+        f(1, 65536, 8, 128, 128, 64, kla.KLA_F32, None, 0, segments=1)                      # bf16 only
     assert f(1, 65536, 8, 128, 128, 64, kla.KLA_BF16, None, 0) > base          # chosen automatically here
-    # a large batch is never segmented: same size with and without the knob at 1
-    big = f(8, 4096, 8, 128, 128, 64, kla.KLA_BF16, None, 0)
-    monkeypatch.setenv("KLA_SCAN_SEGMENTS", "1")
-    assert f(8, 4096, 8, 128, 128, 64, kla.KLA_BF16, None, 0) == big
+    # a large batch is never segmented: same size with and without the field at 1
+    assert f(8, 4096, 8, 128, 128, 64, kla.KLA_BF16, None, 0, unfused=True) == \
+        f(8, 4096, 8, 128, 128, 64, kla.KLA_BF16, None, 0, unfused=True, segments=1)
 
 
 def test_chunk_bwd_validation_and_workspace():
@@ -229,8 +259,8 @@ def test_chunk_bwd_validation_and_workspace():
         x = r256(r256(n_ch * (3 * 384 * 8 * eb + 1280)) + 4) + 2 * r256(n_ch * dk * dv * eb) + 3 * r256(N * T * H * dv * eb)
         plain[dt] = x
     seg = plain[kla.KLA_BF16] + r256(N * 7 * H * dk * (dv + dk) * 4) + 3 * r256(N * 8 * H * dk * dv * 4)
-    if not os.environ.get("KLA_SCAN_SEGMENTS") and not os.environ.get("KLA_SCAN_IMPL"):
-        assert lib.kla_chunk_bwd_workspace_bytes(N, T, H, dk, dv, 64, kla.KLA_BF16, None, 0) == seg
+    assert lib.kla_chunk_bwd_workspace_bytes(N, T, H, dk, dv, 64, kla.KLA_BF16, None, 0) == seg
+    assert lib.kla_chunk_bwd_workspace_bytes_opts(N, T, H, dk, dv, 64, kla.KLA_BF16, None, 0, kla.tune(segments=1)) == plain[kla.KLA_BF16]
     assert lib.kla_chunk_bwd_workspace_bytes(N, T, H, dk, dv, 64, kla.KLA_F32, None, 0) == plain[kla.KLA_F32]
     opt = lambda opts, **o: lib.kla_chunk_bwd_opts(*[{**base, **o}[n] for n in names], opts)
     assert opt(8) == E_SHAPE
@@ -270,6 +300,8 @@ def test_diag_entry_points_validate():
     assert dec(la=None) == E_NULL
     assert dec(dv=100) == E_SHAPE
     assert dec(S=0x6008) == E_ALIGN
+    assert dec(eta=0x5002) == E_ALIGN
+    assert dec(la=0x4002) == E_ALIGN
     assert dec(B=0) == OK
     # the option variants validate the same way, and refuse unknown bits
     copt = lambda opts, **o: lib.kla_chunk_fwd_diag_opts(*[{**base, **o}[n] for n in names], opts)
@@ -283,3 +315,56 @@ def test_diag_entry_points_validate():
     assert dopt(16) == E_SHAPE
     assert dopt(kla.KLA_OPT_GDN_BETA, S=None) == E_NULL
     assert dopt(kla.KLA_OPT_NORMALIZE_Q, B=0) == OK
+
+
+def test_binding_refuses_wrong_shapes_and_dtypes():
+    """The C ABI sees raw pointers, so the binding checks extents and element types of every tensor before it calls
+    (a mismatch would otherwise be an out-of-bounds access on the GPU).  CPU tensors suffice: the checks come first,
+    and tensors that pass them are then refused for not being on the GPU (there is no CPU fallback)."""
+    import torch
+    N, T, H, dk, dv = 2, 70, 3, 64, 128
+    mk = lambda *shape, dtype=torch.bfloat16: torch.zeros(shape, dtype=dtype)
+    good = dict(q=mk(N, T, H, dk), k=mk(N, T, H, dk), v=mk(N, T, H, dv), log_alpha=mk(N, T, H, dtype=torch.float32),
+                eta=mk(N, T, H, dtype=torch.float32), eps=1e-6)
+    call = lambda f, **o: f(**{**good, **o})
+    with pytest.raises(RuntimeError, match="GPU"):
+        call(kla.kla_chunk_fwd)
+    bad = [dict(k=mk(N, T, H + 1, dk)), dict(k=mk(N, T, H, dk, dtype=torch.float32)), dict(v=mk(N, T + 1, H, dv)),
+           dict(log_alpha=mk(N, T, H, dtype=torch.float64)), dict(log_alpha=mk(N, T, H, dtype=torch.bfloat16)),
+           dict(eta=mk(N, T)), dict(eta=mk(N * T * H, dtype=torch.float32)), dict(h0=mk(N, H, dk, dv)),
+           dict(h0=mk(N + 1, H, dk, dv, dtype=torch.float32)), dict(out=mk(N, T, H, dk)),
+           dict(hT=mk(N, H, dv, dk, dtype=torch.float32)), dict(q=mk(N, T, H, dk, dtype=torch.float16)),
+           dict(cu_seqlens=torch.tensor([0, 70, 140], dtype=torch.int64))]
+    for o in bad:
+        with pytest.raises((ValueError, TypeError)):
+            call(kla.kla_chunk_fwd, **o)
+    for o in (dict(log_alpha=mk(N, T, H, dtype=torch.float32)), dict(log_alpha=mk(N, T, H, dk)), dict(k=mk(N, T, H, dv))):
+        with pytest.raises((ValueError, TypeError)):
+            call(kla.kla_chunk_fwd_diag, **o)
+    d_o = mk(N, T, H, dv)
+    for o in (dict(d_o=mk(N, T, H, dk)), dict(d_o=d_o.float()), dict(d_o=d_o, d_hT=mk(N, H, dk, dv)),
+              dict(d_o=d_o, out=dict(dq=mk(N, T, H, dv))), dict(d_o=d_o, out=dict(deta=mk(N, T, H))),
+              dict(d_o=d_o, out=dict(dlog_alpha=mk(N, T, dtype=torch.float32))), dict(d_o=d_o, eta=mk(N, T, H))):
+        with pytest.raises((ValueError, TypeError)):
+            call(kla.kla_chunk_bwd, **o)
+    with pytest.raises(RuntimeError, match="GPU"):
+        call(kla.kla_chunk_bwd, d_o=d_o)
+    B = 4
+    dgood = dict(q=mk(B, H, dk), k=mk(B, H, dk), v=mk(B, H, dv), log_alpha=mk(B, H, dtype=torch.float32),
+                 eta=mk(B, H, dtype=torch.float32), eps=1e-6, S=mk(B, H, dk, dv, dtype=torch.float32))
+    dcall = lambda f, **o: f(**{**dgood, **o})
+    with pytest.raises(RuntimeError, match="GPU"):
+        dcall(kla.kla_decode_step)
+    for o in (dict(S=mk(B, H, dk, dv)), dict(S=mk(B, H, dv, dk, dtype=torch.float32)), dict(eta=mk(B, H + 1, dtype=torch.float32)),
+              dict(log_alpha=mk(B, H)), dict(k=mk(B, H, dv)), dict(out=mk(B, H, dk)), dict(v=mk(B, H, dv, dtype=torch.float32))):
+        with pytest.raises((ValueError, TypeError)):
+            dcall(kla.kla_decode_step, **o)
+    for o in (dict(), dict(log_alpha=mk(B, H, dk))):                     # diagonal gating wants fp32 [B, H, dk]
+        with pytest.raises((ValueError, TypeError)):
+            dcall(kla.kla_decode_step_diag, **o)
+    with pytest.raises((ValueError, TypeError)):
+        kla.kla_beta(mk(5, dk), mk(5, dtype=torch.bfloat16), 1e-6)
+    with pytest.raises((ValueError, TypeError)):
+        kla.kla_beta(mk(5, dk), mk(6, dtype=torch.float32), 1e-6)
+    with pytest.raises(RuntimeError, match="GPU"):
+        kla.kla_beta(mk(5, dk), mk(5, dtype=torch.float32), 1e-6)

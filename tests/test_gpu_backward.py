@@ -105,8 +105,8 @@ def test_bwd_varlen(kla, dt):
 
 @pytest.mark.parametrize("dk,dv,T", [(128, 128, 200), (64, 256, 130)])
 def test_bwd_generic_kernels_on_bf16(kla, dk, dv, T, monkeypatch):
-    """KLA_BWD_IMPL=generic: the element-type-generic kernels (the fp32 path's) on bf16 inputs."""
-    monkeypatch.setenv("KLA_BWD_IMPL", "generic")
+    """The element-type-generic kernels (the fp32 path's) on bf16 inputs."""
+    monkeypatch.setattr(kla, "DEFAULT_TUNE", kla.tune(generic_bwd=True))
     _check(kla, kla_inputs.chunk_inputs(2, T, 2, dk, dv, dtype=torch.bfloat16, seed=325, h0_std=0.3), seed=9)
 
 
@@ -173,7 +173,7 @@ def test_bwd_both_options(kla, dt):
 
 def test_bwd_normalize_q_generic_kernels_on_bf16(kla, monkeypatch):
     """The element-type-generic backward kernels with the normalised read-out, on bf16 inputs."""
-    monkeypatch.setenv("KLA_BWD_IMPL", "generic")
+    monkeypatch.setattr(kla, "DEFAULT_TUNE", kla.tune(generic_bwd=True))
     d = kla_inputs.chunk_inputs(2, 130, 2, 128, 128, dtype=torch.bfloat16, seed=386, h0_std=0.3)
     d_o, g = kla_inputs.grad_inputs(d, 13)
     got = _run(kla, d, d_o, g, normalize_q=True)
@@ -271,15 +271,15 @@ def test_bwd_config5_sampled(kla):
 @pytest.mark.parametrize("N,T,H,dk,dv,h0,ghT", [(2, 1000, 2, 128, 128, None, True), (1, 777, 3, 64, 256, 0.3, True),
                                                (1, 130, 1, 128, 64, 0.3, False)])
 def test_bwd_segmented(kla, segs, N, T, H, dk, dv, h0, ghT, monkeypatch):
-    """KLA_SCAN_SEGMENTS forces the segmented sweeps; ragged last segments, two segments (no reverse composition
+    """The tuning field forces the segmented sweeps; ragged last segments, two segments (no reverse composition
     step), with and without h0 and d_hT.  The two routes agree far inside the bar, and the segmented one really ran
     (its workspace holds the maps and the per-segment states)."""
     d = kla_inputs.chunk_inputs(N, T, H, dk, dv, dtype=torch.bfloat16, seed=197 + T, h0_std=h0)
     d_o, g = kla_inputs.grad_inputs(d, 21, d_hT=ghT)
-    monkeypatch.setenv("KLA_SCAN_SEGMENTS", "1")
+    monkeypatch.setattr(kla, "DEFAULT_TUNE", kla.tune(segments=1))
     w1 = kla.kla_chunk_bwd_workspace_bytes(N, T, H, dk, dv, torch.bfloat16)
     one = _run(kla, d, d_o, g)
-    monkeypatch.setenv("KLA_SCAN_SEGMENTS", segs)
+    monkeypatch.setattr(kla, "DEFAULT_TUNE", kla.tune(segments=int(segs)))
     assert kla.kla_chunk_bwd_workspace_bytes(N, T, H, dk, dv, torch.bfloat16) > w1
     got = _run(kla, d, d_o, g)
     ref = _oracle(d, d_o, g)
@@ -297,9 +297,9 @@ def test_bwd_segmented_slow_decay(kla, segs, monkeypatch):
     differently from the plain one (checked: they differ) and both stay inside the bar."""
     d = kla_inputs.chunk_inputs(1, 1500, 2, 128, 128, dtype=torch.bfloat16, seed=352, log_alpha_scale=0.02, h0_std=0.2)
     d_o, g = kla_inputs.grad_inputs(d, 24)
-    monkeypatch.setenv("KLA_SCAN_SEGMENTS", "1")
+    monkeypatch.setattr(kla, "DEFAULT_TUNE", kla.tune(segments=1))
     one = _run(kla, d, d_o, g)
-    monkeypatch.setenv("KLA_SCAN_SEGMENTS", segs)
+    monkeypatch.setattr(kla, "DEFAULT_TUNE", kla.tune(segments=int(segs)))
     got = _run(kla, d, d_o, g)
     ref = _oracle(d, d_o, g)
     errs = {n: token_oracle.rel_err(got[n], ref[n]) for n in NAMES}
@@ -313,7 +313,7 @@ def test_bwd_segmented_slow_decay(kla, segs, monkeypatch):
 
 
 def test_bwd_segmented_with_options(kla, monkeypatch):
-    monkeypatch.setenv("KLA_SCAN_SEGMENTS", "4")
+    monkeypatch.setattr(kla, "DEFAULT_TUNE", kla.tune(segments=4))
     d = kla_inputs.chunk_inputs(1, 900, 2, 128, 128, dtype=torch.bfloat16, seed=199, h0_std=0.2)
     d["k"] = (d["k"].float() / d["k"].float().norm(dim=-1, keepdim=True)).to(torch.bfloat16)
     d_o, g = kla_inputs.grad_inputs(d, 22)

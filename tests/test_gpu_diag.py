@@ -78,8 +78,8 @@ def test_diag_chunk_decay_range(kla, dt, scale):
 
 
 def test_diag_generic_scan_on_bf16(kla, monkeypatch):
-    """KLA_SCAN_IMPL=generic: the element-type-generic scan kernel (the fp32 path's) on bf16 inputs."""
-    monkeypatch.setenv("KLA_SCAN_IMPL", "generic")
+    """The element-type-generic scan kernel (the fp32 path's) on bf16 inputs."""
+    monkeypatch.setattr(kla, "DEFAULT_TUNE", kla.tune(generic_scan=True))
     _check(kla, kla_inputs.chunk_inputs(2, 200, 2, 128, 128, dtype=torch.bfloat16, seed=435, h0_std=0.3), seed=4)
 
 
@@ -178,7 +178,7 @@ def test_diag_chunk_options(kla, dt, nq, gdn, T, dk, dv, varlen):
 
 
 def test_diag_options_generic_scan_on_bf16(kla, monkeypatch):
-    monkeypatch.setenv("KLA_SCAN_IMPL", "generic")
+    monkeypatch.setattr(kla, "DEFAULT_TUNE", kla.tune(generic_scan=True))
     d = kla_inputs.chunk_inputs(2, 200, 2, 128, 128, dtype=torch.bfloat16, seed=465, h0_std=0.3)
     lad = kla_inputs.diag_gates(d, 7, 1.0)
     o, hT = kla.kla_chunk_fwd_diag(_cuda(d["q"]), _cuda(d["k"]), _cuda(d["v"]), _cuda(lad), _cuda(d["eta"]), d["eps"],

@@ -103,12 +103,9 @@ def test_decode_small(kla, dt, dk, dv):
 @pytest.mark.parametrize("B", [1, 16, 40])
 @pytest.mark.parametrize("sl", [None, "32", "64", "128", "256"])
 def test_decode_slice_widths(kla, B, sl, monkeypatch):
-    """Every width of the state slice a workgroup takes (the library picks 32 .. 128 columns by batch size;
-    KLA_DECODE_SLICE forces one), on a batch of 1, 16 and 40 x 8 heads: same results."""
-    if sl is None:
-        monkeypatch.delenv("KLA_DECODE_SLICE", raising=False)
-    else:
-        monkeypatch.setenv("KLA_DECODE_SLICE", sl)
+    """Every width of the state slice a workgroup takes (the library picks 32 .. 128 columns by batch size; the
+    tuning field forces one), on a batch of 1, 16 and 40 x 8 heads: same results."""
+    monkeypatch.setattr(kla, "DEFAULT_TUNE", 0 if sl is None else kla.tune(decode_slice=int(sl)))
     d = kla_inputs.decode_inputs(2, B, 8, 128, 256, dtype=torch.bfloat16, seed=23, state_std=1.0)
     S = d["S"].cuda().clone()
     Sref = d["S"].double().numpy()
@@ -182,12 +179,34 @@ def test_chunk_small_shapes(kla, dt, dk, dv, T):
     _check_chunk(kla, d)
 
 
+@pytest.mark.parametrize("unfused", [False, True])
 @pytest.mark.parametrize("waves", ["1", "2", "4"])
-def test_chunk_wave_shapes(kla, waves, monkeypatch):
-    """Same result for every workgroup shape of the scan stage (also an LDS hazard check)."""
-    monkeypatch.setenv("KLA_SCAN_WAVES", waves)
+def test_chunk_wave_shapes(kla, waves, unfused, monkeypatch):
+    """Same result for every workgroup shape of the scan stage (also an LDS hazard check), as one fused kernel (one or
+    two compute waves) and as the two-kernel form."""
+    monkeypatch.setattr(kla, "DEFAULT_TUNE", kla.tune(scan_waves=int(waves), unfused=unfused))
     d = kla_inputs.chunk_inputs(2, 300, 2, 128, 128, dtype=torch.bfloat16, seed=51, h0_std=0.1)
     _check_chunk(kla, d)
+    d = kla_inputs.chunk_inputs(1, 200, 3, 64, 256, dtype=torch.bfloat16, seed=52, h0_std=0.1)
+    _check_chunk(kla, d)
+
+
+@pytest.mark.parametrize("dk,dv", [(64, 64), (128, 128), (128, 256), (64, 128)])
+@pytest.mark.parametrize("T", [1, 63, 64, 65, 129, 200])
+def test_chunk_small_shapes_two_kernel_form(kla, dk, dv, T, monkeypatch):
+    """test_chunk_small_shapes runs bf16 through the fused kernel; the two-kernel form (still the route of segmented
+    scans and wide value heads) on the same shapes, and the two forms against each other."""
+    d = kla_inputs.chunk_inputs(2, T, 3, dk, dv, dtype=torch.bfloat16, seed=41 + T, h0_std=0.5)
+    o1, h1 = _run_chunk(kla, d)
+    monkeypatch.setattr(kla, "DEFAULT_TUNE", kla.tune(unfused=True))
+    _check_chunk(kla, d)
+    o2, h2 = _run_chunk(kla, d)
+    assert token_oracle.rel_err(o2, o1) <= TOL[torch.bfloat16] and token_oracle.rel_err(h2, h1) <= TOL[torch.bfloat16]
+
+
+def test_chunk_config2_two_kernel_form(kla, monkeypatch):
+    monkeypatch.setattr(kla, "DEFAULT_TUNE", kla.tune(unfused=True))
+    _check_chunk(kla, kla_inputs.config(2))
 
 
 def test_chunk_varlen_small(kla):
@@ -334,17 +353,15 @@ def test_decode_options(kla, dt, nq, gdn):
 @pytest.mark.parametrize("N,T,H,dk,dv,h0", [(2, 1000, 2, 128, 128, None), (1, 777, 3, 64, 256, 0.3), (1, 130, 1, 128, 64, 0.3)])
 def test_chunk_segmented(kla, segs, N, T, H, dk, dv, h0, monkeypatch):
     d = kla_inputs.chunk_inputs(N, T, H, dk, dv, dtype=torch.bfloat16, seed=97 + T, h0_std=h0)
-    monkeypatch.setenv("KLA_SCAN_SEGMENTS", "1")
+    monkeypatch.setattr(kla, "DEFAULT_TUNE", kla.tune(segments=1))
     o1, h1 = _run_chunk(kla, d)
-    monkeypatch.setenv("KLA_SCAN_SEGMENTS", segs)
+    monkeypatch.setattr(kla, "DEFAULT_TUNE", kla.tune(segments=int(segs)))
     eo, eh = _check_chunk(kla, d)
     o2, h2 = _run_chunk(kla, d)
     # the two routes round differently but agree far inside the bar
     assert token_oracle.rel_err(o2, o1) <= TOL[torch.bfloat16] and token_oracle.rel_err(h2, h1) <= TOL[torch.bfloat16]
     # the segmented route really ran: its workspace holds the maps and the per-segment states
-    monkeypatch.setenv("KLA_SCAN_SEGMENTS", "1")
-    w1 = kla.kla_chunk_fwd_workspace_bytes(N, T, H, dk, dv, torch.bfloat16)
-    monkeypatch.setenv("KLA_SCAN_SEGMENTS", segs)
+    w1 = kla.kla_chunk_fwd_workspace_bytes(N, T, H, dk, dv, torch.bfloat16, tune=kla.tune(segments=1, unfused=True))
     assert kla.kla_chunk_fwd_workspace_bytes(N, T, H, dk, dv, torch.bfloat16) > w1
 
 
@@ -356,9 +373,9 @@ def test_chunk_segmented_slow_decay(kla, segs, monkeypatch):
     composed maps.  The segmented route then rounds differently from the plain one (checked: they differ) and both
     stay inside the bar."""
     d = kla_inputs.chunk_inputs(1, 2000, 2, 128, 128, dtype=torch.bfloat16, seed=98, h0_std=0.3, log_alpha_scale=0.01)
-    monkeypatch.setenv("KLA_SCAN_SEGMENTS", "1")
+    monkeypatch.setattr(kla, "DEFAULT_TUNE", kla.tune(segments=1))
     o1, h1 = _run_chunk(kla, d)
-    monkeypatch.setenv("KLA_SCAN_SEGMENTS", segs)
+    monkeypatch.setattr(kla, "DEFAULT_TUNE", kla.tune(segments=int(segs)))
     _check_chunk(kla, d)
     o2, h2 = _run_chunk(kla, d)
     assert np.any(h2 != h1)
@@ -367,7 +384,7 @@ def test_chunk_segmented_slow_decay(kla, segs, monkeypatch):
 
 @pytest.mark.gpu
 def test_chunk_segmented_with_options(kla, monkeypatch):
-    monkeypatch.setenv("KLA_SCAN_SEGMENTS", "4")
+    monkeypatch.setattr(kla, "DEFAULT_TUNE", kla.tune(segments=4))
     d = kla_inputs.chunk_inputs(1, 900, 2, 128, 128, dtype=torch.bfloat16, seed=99, h0_std=0.2)
     q, k, v, la, eta, h0 = _gpu(d, "q", "k", "v", "log_alpha", "eta", "h0")
     o, hT = kla.kla_chunk_fwd(q, k, v, la, eta, d["eps"], h0=h0, normalize_q=True)

@@ -51,16 +51,13 @@ def test_random_cases(kla, block, monkeypatch):
         kind = str(rng.choice(["fwd", "bwd", "diag"]))
         nq, gdn = bool(rng.random() < 0.3), bool(rng.random() < 0.2)
         segs, waves = str(rng.choice(["", "2", "3", "7"])), str(rng.choice(["", "1", "2", "4"]))
-        for var, val in (("KLA_SCAN_SEGMENTS", segs), ("KLA_SCAN_WAVES", waves)):
-            if val:
-                monkeypatch.setenv(var, val)
-            else:
-                monkeypatch.delenv(var, raising=False)
+        unfused = bool(rng.random() < 0.3)
+        monkeypatch.setattr(kla, "DEFAULT_TUNE", kla.tune(segments=int(segs or 0), scan_waves=int(waves or 0), unfused=unfused))
         if gdn:                                    # the plain delta rule is only stable for short keys
             d["k"] = (d["k"].float() / d["k"].float().norm(dim=-1, keepdim=True).clamp_min(1e-6)).to(dt)
-        print("block %d case %d: %s %s N=%d T=%d H=%d dk=%d dv=%d packed=%s h0=%s nq=%s gdn=%s segments=%s waves=%s" % (
+        print("block %d case %d: %s %s N=%d T=%d H=%d dk=%d dv=%d packed=%s h0=%s nq=%s gdn=%s segments=%s waves=%s unfused=%s" % (
             block, case, kind, str(dt)[6:], d["N"], d["T"], d["H"], d["dk"], d["dv"], d["cu_seqlens"] is not None,
-            d["h0"] is not None, nq, gdn, segs or "-", waves or "-"), flush=True)
+            d["h0"] is not None, nq, gdn, segs or "-", waves or "-", unfused), flush=True)
         a = [_c(d[x]) for x in ("q", "k", "v", "log_alpha", "eta")]
         n = [f32(d[x]) for x in "qkv"] + [d["log_alpha"].numpy(), d["eta"].numpy()]
         cu = None if d["cu_seqlens"] is None else d["cu_seqlens"].numpy()

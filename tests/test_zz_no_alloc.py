@@ -19,13 +19,17 @@ needs_lib = pytest.mark.skipif(not os.path.exists(kla.LIB_PATH), reason="libkla.
 
 @needs_lib
 def test_static_refuses_what_does_not_fit():
-    """Config 2 needs 53.5 MB of per-chunk objects: KLA_ERR_WORKSPACE, decided on the host before any HIP call
-    (the pointers are fakes; nothing may be launched).  Argument errors come out as from kla_chunk_fwd."""
+    """Config 2's sizes with fp32 inputs need 107 MB of per-chunk objects: KLA_ERR_WORKSPACE, decided on the host
+    before any HIP call (the pointers are fakes; nothing may be launched).  Argument errors come out as from
+    kla_chunk_fwd.  (With bf16 inputs the same sizes run the fused kernel, which needs no scratch at all.)"""
     f = kla.lib().kla_chunk_fwd_static
-    args = lambda N, T, H, q=0x1000: (q, 0x2000, 0x3000, 0x4000, 0x5000, 1e-6, None, 0x6000, None, None, None, 0,
-                                      N, T, H, 128, 128, 64, kla.KLA_BF16, None)
-    assert kla.lib().kla_chunk_fwd_workspace_bytes(8, 4096, 8, 128, 128, 64, kla.KLA_BF16, None, 0) > kla.KLA_STATIC_SCRATCH_BYTES
+    args = lambda N, T, H, q=0x1000, dt=kla.KLA_F32: (q, 0x2000, 0x3000, 0x4000, 0x5000, 1e-6, None, 0x6000, None, None,
+                                                      None, 0, N, T, H, 128, 128, 64, dt, None)
+    assert kla.lib().kla_chunk_fwd_workspace_bytes(8, 4096, 8, 128, 128, 64, kla.KLA_F32, None, 0) > kla.KLA_STATIC_SCRATCH_BYTES
     assert f(*args(8, 4096, 8)) == -5
+    # a small bf16 batch of one long sequence runs the segment-parallel scan, whose maps and records live in the scratch
+    assert kla.lib().kla_chunk_fwd_workspace_bytes(1, 65536, 8, 128, 128, 64, kla.KLA_BF16, None, 0) > kla.KLA_STATIC_SCRATCH_BYTES
+    assert f(*args(1, 65536, 8, dt=kla.KLA_BF16)) == -5
     assert f(*args(1, 64, 1, q=None)) == -1
     assert f(*args(1, 64, 1, q=0x1004)) == -4
     assert f(*args(0, 64, 1)) == 0
@@ -50,8 +54,9 @@ def _case(N, T, H, dk, dv, dtype, seed, packed=False):
 def test_static_matches_workspace_entry_point(dtype):
     tol = TOL_BF16 if dtype == torch.bfloat16 else TOL_F32
     # first a larger problem (ragged tail, several chunks; the packed one also has a one-token sequence), then a
-    # smaller one on the same GPU: the array still holds the first call's records
-    # (the 4100-token case runs the segment-parallel scan for bf16, whose maps and states live in the array too)
+    # smaller one on the same GPU: the array still holds the first call's records.  fp32 inputs always go through the
+    # scratch; of the bf16 cases the 4100-token one does (segment-parallel scan: records, maps and states), the others
+    # run the fused kernel, which leaves the array alone.
     for (N, T, H, dk, dv, seed, packed) in ((1, 4100, 2, 128, 128, 30, False), (2, 1000, 4, 128, 128, 31, False), (1, 200, 2, 128, 128, 32, False),
                                             (1, 333, 3, 64, 256, 33, True), (1, 70, 2, 64, 64, 34, False)):
         d = _case(N, T, H, dk, dv, dtype, seed, packed)
