@@ -147,7 +147,7 @@ int kla_decode_step(const void *q, const void *k, const void *v,
 enum { KLA_OPT_NORMALIZE_Q = 1, KLA_OPT_GDN_BETA = 2 };
 
 /*
- * Tuning fields of the same `opts` argument (bits 8..24), for tests and A/B measurements: every setting computes
+ * Tuning fields of the same `opts` argument (bits 8..25), for tests and A/B measurements: every setting computes
  * the same results up to rounding, 0 in a field is the library's own choice (the measured best), and a value
  * outside a field's range is KLA_ERR_SHAPE.  They replace any reading of the environment: a call's behaviour
  * depends on its arguments alone.  The workspace needed depends on some of them (segments, the generic and
@@ -156,6 +156,8 @@ enum { KLA_OPT_NORMALIZE_Q = 1, KLA_OPT_GDN_BETA = 2 };
  *   KLA_TUNE_SCAN_SEGMENTS(n)  n = 1: never cut sequences for the segment-parallel scan; n = 2..16: cut into n
  *   KLA_TUNE_GENERIC_SCAN / _INTRA / _BWD   bf16 inputs through the element-type-generic kernels of the fp32 path
  *   KLA_TUNE_UNFUSED           bf16 forward as two kernels (intra-chunk stage, then scan) where one fused kernel would run
+ *   KLA_TUNE_FUSED             bf16 forward as the one fused kernel wherever it can run (one or two compute waves per
+ *                              workgroup, no segments), also where the two-kernel form is the library's choice
  *   KLA_TUNE_DECODE_SLICE(n)   n = 32, 64, 128, 256: state columns per workgroup of the decode step
  *   KLA_TUNE_DECODE_NT(n)      n = 0..3: bit 0 non-temporal state loads, bit 1 non-temporal state stores
  */
@@ -167,6 +169,7 @@ enum { KLA_OPT_NORMALIZE_Q = 1, KLA_OPT_GDN_BETA = 2 };
 #define KLA_TUNE_DECODE_SLICE(n)  ((unsigned)((n) == 32 ? 1 : (n) == 64 ? 2 : (n) == 128 ? 3 : (n) == 256 ? 4 : 7) << 18)
 #define KLA_TUNE_DECODE_NT(n)     ((unsigned)((n) + 1) << 21)
 #define KLA_TUNE_UNFUSED          (1u << 24)
+#define KLA_TUNE_FUSED            (1u << 25)
 
 /* Workspace of kla_chunk_fwd_opts(..., opts) / kla_chunk_bwd_opts(..., opts) (0 on invalid sizes or fields);
  * the plain queries are these with opts = 0. */
@@ -319,6 +322,19 @@ int kla_debug_chunk_stage(const void *q, const void *k, const void *v,
                           const int32_t *cu_seqlens_dev, const int32_t *cu_seqlens_host, int n_seq,
                           int N, int T, int H, int dk, int dv, int chunk, kla_dtype dt,
                           void *workspace, size_t workspace_bytes, void *hip_stream, int stage);
+
+/*
+ * Measurement hook: what this GPU delivers for the access patterns the rooflines of the hot path are quoted
+ * against (none of the method's arithmetic runs).  bench.py reports the results as second denominators beside the
+ * published peaks.
+ *   kind 0  in-place streaming, x <- 2 x over `bytes` of fp32 at buf (a multiple of 65536): every byte read once and
+ *           written once, one workgroup per 64 KiB with all loads first, as in the decode step; iters != 0 selects
+ *           non-temporal loads and stores.  aux unused.
+ *   kind 1  read-only streaming of `bytes` at buf; aux receives bytes / 16384 floats.
+ *   kind 2  dense bf16 matrix pipe: `bytes` workgroups of four waves, each wave `iters` rounds of eight
+ *           independent 16x16x32 products (16384 flop each per wave); aux receives 256 floats per workgroup.
+ */
+int kla_debug_peak_probe(int kind, void *buf, void *aux, size_t bytes, int iters, void *hip_stream);
 
 #ifdef __cplusplus
 }

@@ -55,6 +55,7 @@ _SIGNATURES = {
     "kla_decode_step_opts": (ctypes.c_int, [_vp, _vp, _vp, _fp, _fp, ctypes.c_float, _fp, _vp]
                              + [ctypes.c_int] * 4 + [ctypes.c_int, _vp, ctypes.c_uint]),
     "kla_beta": (ctypes.c_int, [_vp, _fp, ctypes.c_float, _fp, ctypes.c_long, ctypes.c_int, ctypes.c_int, _vp]),
+    "kla_debug_peak_probe": (ctypes.c_int, [ctypes.c_int, _vp, _vp, ctypes.c_size_t, ctypes.c_int, _vp]),
     "kla_debug_intra_chunk": (ctypes.c_int, [_vp, _vp, _fp, _fp, ctypes.c_float, _fp, _fp, _fp, _ip, _ip, ctypes.c_int]
                               + [ctypes.c_int] * 5 + [ctypes.c_int, _vp, ctypes.c_size_t, _vp]),
 }
@@ -109,11 +110,11 @@ def _stream():
 
 # Tuning fields of the `opts` argument (KLA_TUNE_* of include/kla.h): for tests and A/B measurements.  DEFAULT_TUNE is
 # what a call uses when it is given no `tune` of its own (binding-side convenience; the library keeps no such state).
-KLA_TUNE_GENERIC_SCAN, KLA_TUNE_GENERIC_INTRA, KLA_TUNE_GENERIC_BWD, KLA_TUNE_UNFUSED = 1 << 15, 1 << 16, 1 << 17, 1 << 24
+KLA_TUNE_GENERIC_SCAN, KLA_TUNE_GENERIC_INTRA, KLA_TUNE_GENERIC_BWD, KLA_TUNE_UNFUSED, KLA_TUNE_FUSED = 1 << 15, 1 << 16, 1 << 17, 1 << 24, 1 << 25
 DEFAULT_TUNE = 0
 
 
-def tune(scan_waves=0, segments=0, generic_scan=False, generic_intra=False, generic_bwd=False, unfused=False,
+def tune(scan_waves=0, segments=0, generic_scan=False, generic_intra=False, generic_bwd=False, unfused=False, fused=False,
          decode_slice=0, decode_nt=None) -> int:
     """The tuning fields as one integer for the `tune` argument of the calls below (0 = the library's own choice)."""
     if scan_waves not in (0, 1, 2, 4) or not 0 <= segments <= 16 or decode_slice not in (0, 32, 64, 128, 256) \
@@ -121,7 +122,7 @@ def tune(scan_waves=0, segments=0, generic_scan=False, generic_intra=False, gene
         raise ValueError("tuning value out of range")
     bits = ((3 if scan_waves == 4 else scan_waves) << 8) | (segments << 10)
     bits |= (KLA_TUNE_GENERIC_SCAN if generic_scan else 0) | (KLA_TUNE_GENERIC_INTRA if generic_intra else 0)
-    bits |= (KLA_TUNE_GENERIC_BWD if generic_bwd else 0) | (KLA_TUNE_UNFUSED if unfused else 0)
+    bits |= (KLA_TUNE_GENERIC_BWD if generic_bwd else 0) | (KLA_TUNE_UNFUSED if unfused else 0) | (KLA_TUNE_FUSED if fused else 0)
     bits |= {0: 0, 32: 1, 64: 2, 128: 3, 256: 4}[decode_slice] << 18
     bits |= 0 if decode_nt is None else (decode_nt + 1) << 21
     return bits
@@ -425,6 +426,21 @@ def kla_debug_intra_chunk(q, k, log_alpha, eta, eps, cu_seqlens=None, chunk=64):
     if rc != 0:
         raise KlaError(rc, "kla_debug_intra_chunk")
     return Tb, P, g
+
+
+def kla_debug_peak_probe(kind, buf=None, aux=None, n=0, iters=0):
+    """Measurement hook (kla_debug_peak_probe of the C ABI): kind 0 in-place streaming over the fp32 tensor `buf`
+    (iters != 0: non-temporal), kind 1 read-only streaming of `buf` (aux: fp32, buf bytes / 16384 elements), kind 2 dense
+    bf16 matrix pipe on `n` workgroups x `iters` rounds (aux: fp32, 256 n elements)."""
+    _dev(buf, aux)
+    size = n if kind == 2 else buf.numel() * buf.element_size()
+    if kind == 1 and (aux is None or aux.numel() * aux.element_size() < size // 4096):
+        raise ValueError("aux too small")
+    if kind == 2 and (aux is None or aux.numel() < 256 * n):
+        raise ValueError("aux too small")
+    rc = lib().kla_debug_peak_probe(int(kind), _ptr(buf), _ptr(aux), size, int(iters), _stream())
+    if rc != 0:
+        raise KlaError(rc, "kla_debug_peak_probe")
 
 
 class _KlaChunk(torch.autograd.Function):

@@ -12,7 +12,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libkla.so")
 SOURCES = ["kla_api.hip", "kla_decode.hip", "kla_chunk_intra.hip", "kla_chunk_intra_bf16.hip", "kla_chunk_scan.hip",
-           "kla_chunk_scan_bf16.hip", "kla_chunk_segments.hip", "kla_chunk_bwd.hip", "kla_chunk_bwd_bf16.hip"]
+           "kla_chunk_scan_bf16.hip", "kla_chunk_segments.hip", "kla_chunk_bwd.hip", "kla_chunk_bwd_bf16.hip", "kla_probe.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          # hipcc -O3 must not form packed-fp32 instructions on the test machines
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

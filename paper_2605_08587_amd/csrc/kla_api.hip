@@ -25,12 +25,12 @@ static_assert(KLA_OPT_NORMALIZE_Q == (int)kla::kOptNormalizeQ && KLA_OPT_GDN_BET
 struct Tune {
     int scan_waves = 0;      // 1, 2, 4 compute waves per scan workgroup
     int segments = 0;        // 1 = never cut sequences into segments, n = cut into n
-    bool generic_scan = false, generic_intra = false, generic_bwd = false, unfused = false;
+    bool generic_scan = false, generic_intra = false, generic_bwd = false, unfused = false, fused = false;
     int decode_slice = 0;    // 32, 64, 128, 256 state columns per decode workgroup
     int decode_nt = -1;      // bit 0: non-temporal state loads, bit 1: non-temporal state stores
 };
 constexpr unsigned kOptMask = KLA_OPT_NORMALIZE_Q | KLA_OPT_GDN_BETA;
-constexpr unsigned kTuneMask = 0x01ffff00u;
+constexpr unsigned kTuneMask = 0x03ffff00u;
 
 bool parse_tune(unsigned opts, Tune* t)
 {
@@ -43,6 +43,8 @@ bool parse_tune(unsigned opts, Tune* t)
     t->generic_intra = (opts & KLA_TUNE_GENERIC_INTRA) != 0;
     t->generic_bwd = (opts & KLA_TUNE_GENERIC_BWD) != 0;
     t->unfused = (opts & KLA_TUNE_UNFUSED) != 0;
+    t->fused = (opts & KLA_TUNE_FUSED) != 0;
+    if (t->fused && t->unfused) return false;
     t->decode_slice = ds == 0 ? 0 : 16 << ds;
     t->decode_nt = nt == 0 ? -1 : (int)nt - 1;
     return true;
@@ -124,10 +126,15 @@ int make_plan(int N, int T, int H, int dk, int dv, int chunk, int dt, const int3
     p->off_S = round256(p->off_M + maps);
     p->total = round256(p->off_S + states);
     p->waves = scan_waves(p->n_states * H, dv, dt, p->tune);
-    // bf16, a plain scan of at most two compute waves per workgroup: the fused kernel, which keeps the per-chunk
-    // objects on chip and needs nothing of the workspace (a token size is still reported and asked for)
-    p->fused = dt == KLA_BF16 && p->seg_G <= 1 && p->waves <= 2 && !p->tune.unfused && !p->tune.generic_scan &&
-               !p->tune.generic_intra;
+    // bf16, a plain scan of two compute waves per workgroup (512 .. 2047 sixteen-column chains, e.g. 8 x 8 heads of 128
+    // columns): the fused kernel, which keeps the per-chunk objects on chip and needs nothing of the workspace (a token
+    // size is still reported and asked for).  Measured: 0.116 against 0.124 ms on 8 x 8 heads x 4096 tokens; with one
+    // compute wave per workgroup (few chains) its helper waves redo the per-chunk work once per 16 columns and the
+    // two-kernel form wins (1.38 against 1.83 ms on one 65K sequence, unsegmented), as it does for wide value heads
+    // run with two waves (0.55 against 0.64 ms on 16 packed sequences, 16 heads, d_v = 256).  KLA_TUNE_FUSED forces it
+    // wherever it can run (one or two compute waves, no segments).
+    p->fused = dt == KLA_BF16 && p->seg_G <= 1 && !p->tune.unfused && !p->tune.generic_scan && !p->tune.generic_intra &&
+               (p->tune.fused ? p->waves <= 2 : (p->waves == 2 && dv <= 128));
     if (p->fused) p->total = 256;
     return KLA_OK;
 }
@@ -364,7 +371,7 @@ int make_diag_plan(int N, int T, int H, int dk, int dv, int chunk, int dt, const
                    DiagPlan* p)
 {
     // the layout of the two-kernel forward (the fused kernel has no diagonal-gating variant), no segments
-    const int rc = make_plan(N, T, H, dk, dv, chunk, dt, cu_host, n_seq, (opts & ~(31u << 10)) | KLA_TUNE_UNFUSED | KLA_TUNE_SCAN_SEGMENTS(1), &p->base);
+    const int rc = make_plan(N, T, H, dk, dv, chunk, dt, cu_host, n_seq, (opts & ~(31u << 10) & ~KLA_TUNE_FUSED) | KLA_TUNE_UNFUSED | KLA_TUNE_SCAN_SEGMENTS(1), &p->base);
     if (rc != KLA_OK) return rc;
     const size_t rows = (size_t)N * T * H * dk * elem_bytes(dt);
     p->off_kp = round256(p->base.off_M);             // the forward plan up to its chunk offsets; no segment maps here
@@ -725,6 +732,20 @@ int kla_debug_intra_chunk(const void* q, const void* k, const float* log_alpha, 
                                       n_seq, N, T, H, dk, 64, pl, ws, 5, Tb_out, P_out, g_out, st, 0u);
     return chunk_fwd_impl<float>(q, k, nullptr, log_alpha, eta, eps, nullptr, nullptr, nullptr, cu_seqlens_dev, n_seq, N,
                                  T, H, dk, 64, pl, ws, 5, Tb_out, P_out, g_out, st, 0u);
+}
+
+int kla_debug_peak_probe(int kind, void* buf, void* aux, size_t bytes, int iters, void* hip_stream)
+{
+    if (kind < 0 || kind > 2 || iters < 0) return KLA_ERR_SHAPE;
+    if (kind == 2) {
+        if (bytes == 0 || bytes > 0x7fffffffu || iters == 0) return KLA_ERR_SHAPE;
+        if (!aux) return KLA_ERR_NULL;
+    } else {
+        if (bytes == 0 || bytes % 65536 != 0 || bytes / 65536 > 0x7fffffffu) return KLA_ERR_SHAPE;
+        if (!buf || (kind == 1 && !aux)) return KLA_ERR_NULL;
+        if (!aligned16(buf)) return KLA_ERR_ALIGN;
+    }
+    return kla::launch_probe(kind, buf, aux, bytes, iters, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? KLA_OK : KLA_ERR_HIP;
 }
 
 int kla_decode_step(const void* q, const void* k, const void* v, const float* log_alpha, const float* eta, float eps,

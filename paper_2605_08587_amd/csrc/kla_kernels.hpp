@@ -133,6 +133,9 @@ hipError_t launch_bwd_scan_bf16(const BwdArgs<bf16_t>& a, int dk, int waves, hip
 hipError_t launch_bwd_assemble_bf16(const BwdArgs<bf16_t>& a, int dk, long n_chunks, hipStream_t st);
 template <typename E> hipError_t launch_bwd_assemble(const BwdArgs<E>& a, int dk, long n_chunks, hipStream_t st);
 
+// measurement probes (kla_probe.hip)
+hipError_t launch_probe(int kind, void* buf, void* aux, size_t bytes, int iters, hipStream_t st);
+
 hipError_t launch_chunk_offsets(const int* cu_seqlens, int n_seq, int* chunk_off, hipStream_t st);
 template <typename E>
 hipError_t launch_unpack(const E* wsT, const E* wsP, const float* wsG, float* Tb, float* P, float* gout, long n_ch,

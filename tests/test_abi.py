@@ -64,10 +64,13 @@ def test_workspace_bytes():
         8, 4096, 8, 128, 128, 64, kla.KLA_BF16, None, 0, 0)
     assert g(8, 4096, 8, 128, 128, 64, kla.KLA_F32, None, 0) == f(8, 4096, 8, 128, 128, 64, kla.KLA_F32, None, 0)
     assert g(64, 4096, 16, 128, 256, 64, kla.KLA_BF16, None, 0) == f(64, 4096, 16, 128, 256, 64, kla.KLA_BF16, None, 0)
+    assert g(2, 2048, 8, 128, 128, 64, kla.KLA_BF16, None, 0) == f(2, 2048, 8, 128, 128, 64, kla.KLA_BF16, None, 0)    # few chains
+    assert lib.kla_chunk_fwd_workspace_bytes_opts(2, 2048, 8, 128, 128, 64, kla.KLA_BF16, None, 0, kla.tune(fused=True)) == 256
     assert g(1, 200, 2, 64, 64, 64, kla.KLA_BF16, bad.ctypes.data, 3) == 0
     # tuning fields out of range are refused (0 from the queries, KLA_ERR_SHAPE from the calls)
     assert lib.kla_chunk_fwd_workspace_bytes_opts(8, 4096, 8, 128, 128, 64, kla.KLA_BF16, None, 0, 17 << 10) == 0
-    assert lib.kla_chunk_fwd_workspace_bytes_opts(8, 4096, 8, 128, 128, 64, kla.KLA_BF16, None, 0, 1 << 25) == 0
+    assert lib.kla_chunk_fwd_workspace_bytes_opts(8, 4096, 8, 128, 128, 64, kla.KLA_BF16, None, 0, 1 << 26) == 0
+    assert lib.kla_chunk_fwd_workspace_bytes_opts(8, 4096, 8, 128, 128, 64, kla.KLA_BF16, None, 0, 3 << 24) == 0   # fused and unfused
     assert lib.kla_chunk_fwd_workspace_bytes_opts(8, 4096, 8, 128, 128, 64, kla.KLA_BF16, None, 0, 4) == 0
 
 
@@ -75,7 +78,7 @@ def test_tune_bits_match_the_header():
     """The binding's tune() builds the KLA_TUNE_* fields of include/kla.h."""
     hdr = open(kla.HEADER_PATH).read()
     for name, val in (("KLA_TUNE_GENERIC_SCAN", 15), ("KLA_TUNE_GENERIC_INTRA", 16), ("KLA_TUNE_GENERIC_BWD", 17),
-                      ("KLA_TUNE_UNFUSED", 24)):
+                      ("KLA_TUNE_UNFUSED", 24), ("KLA_TUNE_FUSED", 25)):
         assert re.search(r"#define %s\s+\(1u << %d\)" % (name, val), hdr), name
         assert getattr(kla, name) == 1 << val
     assert kla.tune(scan_waves=4) == 3 << 8 and kla.tune(scan_waves=2) == 2 << 8

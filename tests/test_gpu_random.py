@@ -6,6 +6,7 @@ import numpy as np
 import pytest
 import torch
 
+import bwd_bounds
 import kla_inputs
 from oracle import token_oracle
 
@@ -51,13 +52,14 @@ def test_random_cases(kla, block, monkeypatch):
         kind = str(rng.choice(["fwd", "bwd", "diag"]))
         nq, gdn = bool(rng.random() < 0.3), bool(rng.random() < 0.2)
         segs, waves = str(rng.choice(["", "2", "3", "7"])), str(rng.choice(["", "1", "2", "4"]))
-        unfused = bool(rng.random() < 0.3)
-        monkeypatch.setattr(kla, "DEFAULT_TUNE", kla.tune(segments=int(segs or 0), scan_waves=int(waves or 0), unfused=unfused))
+        form = str(rng.choice(["auto", "fused", "unfused"]))
+        monkeypatch.setattr(kla, "DEFAULT_TUNE", kla.tune(segments=int(segs or 0), scan_waves=int(waves or 0), fused=form == "fused",
+                                                        unfused=form == "unfused"))
         if gdn:                                    # the plain delta rule is only stable for short keys
             d["k"] = (d["k"].float() / d["k"].float().norm(dim=-1, keepdim=True).clamp_min(1e-6)).to(dt)
-        print("block %d case %d: %s %s N=%d T=%d H=%d dk=%d dv=%d packed=%s h0=%s nq=%s gdn=%s segments=%s waves=%s unfused=%s" % (
+        print("block %d case %d: %s %s N=%d T=%d H=%d dk=%d dv=%d packed=%s h0=%s nq=%s gdn=%s segments=%s waves=%s form=%s" % (
             block, case, kind, str(dt)[6:], d["N"], d["T"], d["H"], d["dk"], d["dv"], d["cu_seqlens"] is not None,
-            d["h0"] is not None, nq, gdn, segs or "-", waves or "-", unfused), flush=True)
+            d["h0"] is not None, nq, gdn, segs or "-", waves or "-", form), flush=True)
         a = [_c(d[x]) for x in ("q", "k", "v", "log_alpha", "eta")]
         n = [f32(d[x]) for x in "qkv"] + [d["log_alpha"].numpy(), d["eta"].numpy()]
         cu = None if d["cu_seqlens"] is None else d["cu_seqlens"].numpy()
@@ -77,7 +79,13 @@ def test_random_cases(kla, block, monkeypatch):
                 qn = np.linalg.norm(n[0].astype(np.float64), axis=-1, keepdims=True)
                 errs["dq"] = token_oracle.rel_err(out["dq"].float().cpu().numpy() * qn, ref["dq"] * qn)
             if d["T"] * d["H"] < 64 and dt == torch.bfloat16:
-                continue                           # a handful of entries: bf16 rounding of single products decides (see DESIGN)
+                # a handful of entries, each a sum over d_v products of bf16-rounded rows that mostly cancel: d eta is
+                # held to the first-order bound of that rounding where it exceeds the plain bar (see bwd_bounds.py)
+                be, _ = bwd_bounds.bounds(d, d_o, g, lambda t: f32(t).astype(np.float64))
+                bound = float(be.max() / max(np.abs(ref["deta"]).max(), 1e-300))
+                print("    deta: first-order bound of the bf16 intermediates %.2e" % bound, flush=True)
+                assert errs["deta"] <= max(TOL[dt], bound), errs["deta"]
+                errs.pop("deta")
         else:
             lad = kla_inputs.diag_gates(d, seed % 1000, float(rng.choice([1.0, 0.1, 5.0])))
             o, hT = kla.kla_chunk_fwd_diag(a[0], a[1], a[2], _c(lad), a[4], d["eps"], h0=_c(d["h0"]), cu_seqlens=_c(d["cu_seqlens"]),

@@ -670,3 +670,18 @@ def test_gradient_normalize_q_central_differences_and_scale_invariance():
             minus[idx] -= h
             fd = (loss(**{**base, name: plus}) - loss(**{**base, name: minus})) / (2 * h)
             assert abs(fd - g[key][idx]) <= 5e-5 * scale + 1e-8, (name, idx, fd, g[key][idx])
+
+
+def test_rel_err_metric_by_hand():
+    """The parity metric every GPU test rests on, max|x - ref| / max|ref| over the whole tensor, on arrays worked by hand:
+    the largest deviation (0.5, at the entry whose reference is -8) over the largest reference magnitude (8); a zero
+    reference falls back to the absolute deviation; empty tensors compare equal; the metric is not symmetric."""
+    ref = np.array([[1.0, -8.0], [2.0, 0.0]])
+    x = np.array([[1.25, -7.5], [2.0, 0.125]])
+    assert token_oracle.rel_err(x, ref) == 0.5 / 8.0
+    assert token_oracle.rel_err(ref, x) == 0.5 / 7.5
+    assert token_oracle.rel_err(ref, ref) == 0.0
+    assert token_oracle.rel_err(np.array([0.0, -0.25]), np.zeros(2)) == 0.25
+    assert token_oracle.rel_err(np.zeros((0, 3)), np.zeros((0, 3))) == 0.0
+    assert token_oracle.rel_err(np.array([3.0], dtype=np.float32), np.array([2.0])) == 0.5
+    assert np.isnan(token_oracle.rel_err(np.array([np.nan, 1.0]), np.array([1.0, 1.0])))
