@@ -60,10 +60,14 @@ def _warm(torch, fn, ms=50.0):
         torch.cuda.synchronize()
 
 
+MAX_GROUPS = 1 << 30   # --max-groups: a counter run needs only a few launches of each kernel
+
+
 def _events(torch, fn, reps, warm_ms=50.0, groups=1):
     """Milliseconds per fn() by events on the current stream (the stream the binding launches on), after an untimed
     warm-up: `groups` groups of `reps` launches, each group between its own pair of events; returns the median group."""
     _warm(torch, fn, warm_ms)
+    groups = max(1, min(groups, MAX_GROUPS))
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(groups)]
     torch.cuda.synchronize()
     for e0, e1 in ev:
@@ -115,9 +119,24 @@ def main():
     ap.add_argument("--skip-extra", action="store_true",
                     help="skip everything but the headline step and its roofline (so that a kernel trace or a counter run "
                          "of this command holds the benchmarked launches only)")
+    ap.add_argument("--sections", default="all",
+                    help="comma-separated secondary measurements to run beside the headline step: two_kernel, rotating, "
+                         "peaks, config3, config5, backward, backward_config3, diag, decode (default: all)")
+    ap.add_argument("--max-groups", type=int, default=0,
+                    help="cap on the event groups per measurement (for rocprofv3 --pmc runs, which serialise every dispatch)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="only run a plain device copy of 1 GiB five times (reference for the rocprofv3 byte counters)")
     args = ap.parse_args()
+    sections = set(args.sections.split(","))
+
+    def want(name):
+        if args.skip_extra or (name == "decode" and args.skip_decode) or (name == "rotating" and args.skip_rotating):
+            return False
+        return "all" in sections or name in sections
+
+    if args.max_groups > 0:
+        global MAX_GROUPS
+        MAX_GROUPS = args.max_groups
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is single-GPU by design (no collectives, no sharding); run with --gpus 1",
               file=sys.stderr)
@@ -203,7 +222,7 @@ def main():
     # segmented scans
     two = None
     rotating = None
-    if not args.skip_extra:
+    if want("two_kernel"):
         ms_two = _events(torch, step_two_kernels, 10, groups=20)
         ms_intra = _events(torch, lambda: stage(1), 10, groups=20)
         ms_scan = _events(torch, lambda: stage(2), 10, groups=20)
@@ -212,7 +231,7 @@ def main():
                "note": "kla_chunk_fwd with KLA_TUNE_UNFUSED on the same tensors"}
     # The same step over three copies of the inputs and outputs in turn (1 GB in all): nothing of a step's tensors is
     # still in the 256 MB memory-side cache when the step comes round again.
-    if not args.skip_rotating and not args.skip_extra:
+    if want("rotating"):
         rot = [{n: t.clone() for n, t in dev.items()} for _ in range(3)]
         rot_out = [torch.empty_like(out) for _ in range(3)]
         rot_i = [0]
@@ -231,7 +250,7 @@ def main():
 
     # ------------------------------------------------------------------ what this GPU delivers (second denominators)
     measured = None
-    if not args.skip_extra:
+    if want("peaks"):
         big = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1e-30)     # 1 GiB
         aux = torch.empty(max(big.numel() * 4 // 16384, 256 * 2048), dtype=torch.float32, device="cuda")
         ms_rw = _events(torch, lambda: kla.kla_debug_peak_probe(0, big, aux, iters=1), 5, groups=5)
@@ -249,10 +268,12 @@ def main():
 
     # ------------------------------------------------------------------ secondary chunk workloads (not the headline)
     extra = None
-    if not args.skip_extra:
+    if want("config3") or want("config5"):
         extra = {}
         for ci, name, chain in ((3, "config3: N=1,H=8,T=65536,d=128 (one long sequence; segment-parallel scan)", None),
                                 (5, "config5: 16 packed sequences of 512..4096 tokens,H=16,dk=128,dv=256,h0", None)):
+            if not want("config%d" % ci):
+                continue
             e = kla_inputs.config(ci)
             g = {n: e[n].cuda() for n in ("q", "k", "v", "log_alpha", "eta")}
             cu = None if e["cu_seqlens"] is None else e["cu_seqlens"].cuda()
@@ -285,7 +306,7 @@ def main():
 
     # ------------------------------------------------------------------ backward of the chunk path, config 2 (secondary)
     backward = None
-    if not args.skip_extra:
+    if want("backward"):
         d_o, d_hT = kla_inputs.grad_inputs(d, 1)
         d_o, d_hT = d_o.cuda(), d_hT.cuda()
         wb = torch.empty(kla.kla_chunk_bwd_workspace_bytes(N, T, H, dk, dv, torch.bfloat16), dtype=torch.uint8, device="cuda")
@@ -301,6 +322,7 @@ def main():
                     "times_forward": round(msb / ms_per_step, 2), "workspace_MB": round(wb.numel() / 1e6, 1),
                     "traffic": _traffic("chunk_bwd_config2")}
         del wb, grads, d_o, d_hT
+    if backward is not None and want("backward_config3"):
         # the same on config 3 (one 65K-token sequence): segment-parallel sweeps
         e3 = kla_inputs.config(3)
         g3 = {n: e3[n].cuda() for n in ("q", "k", "v", "log_alpha", "eta")}
@@ -320,7 +342,7 @@ def main():
 
     # ------------------------------------------------------------------ diagonal gating on config 2's tensors (secondary)
     diag = None
-    if not args.skip_extra:
+    if want("diag"):
         lad = kla_inputs.diag_gates(d, 1).cuda()
         wd = torch.empty(int(kla.lib().kla_chunk_fwd_diag_workspace_bytes(N, T, H, dk, dv, 64, kla.KLA_BF16, None, 0)),
                          dtype=torch.uint8, device="cuda")
@@ -335,7 +357,7 @@ def main():
 
     # ------------------------------------------------------------------ decode, config 4
     decode = None
-    if not args.skip_decode:
+    if want("decode"):
         dd = kla_inputs.config(4)
         B, Hd, steps = dd["B"], dd["H"], dd["steps"]
         g = {n: dd[n].cuda() for n in ("q", "k", "v", "log_alpha", "eta")}
