@@ -104,18 +104,19 @@ __global__ __launch_bounds__(64 * NW + 64) void bwd_sweep_bf16_kernel(BwdArgs<bf
 
     // ---- loop-invariant per-lane offsets (as in the forward kernel) -----------------------------------
     const int lrow = lane / PPR, pcol = lane % PPR;
-    int gk[2];
+    constexpr int NGK = 8 / RPB;                        // the swizzle has period 8 rows
+    int gk[NGK];
 #pragma unroll
-    for (int par = 0; par < 2; ++par)
-        gk[par] = lrow * (int)kq_row + ((pcol ^ swz_bits(RPB * par + lrow)) * 16);
+    for (int j = 0; j < NGK; ++j)
+        gk[j] = lrow * (int)kq_row + ((pcol ^ swz_piece<DK>(RPB * j + lrow)) * 16);
     const int gv = (lane / VPP) * (int)v_row + (lane % VPP) * 16;
-    int oK[2];
+    int oK[KP];
 #pragma unroll
-    for (int par = 0; par < 2; ++par) oK[par] = r * RB + (((4 * par + g) ^ swz_bits(r)) * 16);
+    for (int kp = 0; kp < KP; ++kp) oK[kp] = r * RB + (((4 * kp + g) ^ swz_piece<DK>(r)) * 16);
     const int a4 = r >> 2, c4 = r & 3;
-    int oKT[2];
+    int oKT[KP];
 #pragma unroll
-    for (int par = 0; par < 2; ++par) oKT[par] = (4 * g + a4) * RB + (((4 * par + c4) ^ swz_bits(4 * g + a4)) * 16);
+    for (int kp = 0; kp < KP; ++kp) oKT[kp] = (4 * g + a4) * RB + (((4 * kp + c4) ^ swz_piece<DK>(4 * g + a4)) * 16);
     const int oV = (4 * g + a4) * VRW + (16 * wave + 4 * c4) * 2;
     const int oO = (4 * g + (r & 3)) * ORB + (16 * wave + 4 * (r >> 2)) * 2;
     const bool q_lo = (r & 3) < 2;
@@ -132,7 +133,7 @@ __global__ __launch_bounds__(64 * NW + 64) void bwd_sweep_bf16_kernel(BwdArgs<bf
             static_for<C::NKB>([&](auto i) {
                 const int b = i;
                 const size_t o = (size_t)(b * RPB) * kq_row;
-                const int lo = (RPB == 4 && (b & 1)) ? gk[1] : gk[0];
+                const int lo = gk[b % NGK];
                 dma16(kc + o, lo, st + b * 1024);
                 if constexpr (REV) dma16(qc + o, lo, st + C::OFF_Q + b * 1024);
             });
@@ -144,7 +145,7 @@ __global__ __launch_bounds__(64 * NW + 64) void bwd_sweep_bf16_kernel(BwdArgs<bf
             static_for<C::NKB>([&](auto i) {
                 const int b = i;
                 const int row = b * RPB + lrow;
-                const int lo = min(row, clen - 1) * (int)kq_row + ((pcol ^ swz_bits(row)) * 16);
+                const int lo = min(row, clen - 1) * (int)kq_row + ((pcol ^ swz_piece<DK>(row)) * 16);
                 dma16(kc, lo, st + b * 1024);
                 if constexpr (REV) dma16(qc, lo, st + C::OFF_Q + b * 1024);
             });
@@ -170,19 +171,15 @@ __global__ __launch_bounds__(64 * NW + 64) void bwd_sweep_bf16_kernel(BwdArgs<bf
 
     // ---- one chunk for this wave's 16 columns -----------------------------------------------------------
     auto compute = [&](const char* st, char* ost, int c) {
-        const char* pK0 = st + oK[0];
-        const char* pK1 = st + oK[1];
-        const char* pT0 = st + oKT[0];
-        const char* pT1 = st + oKT[1];
         const char* pS = st + lane * 16;
         const char* pV = st + C::OFF_V + oV;
         const char* pG = st + C::OFF_EG + 16 * g;
         auto kslot = [&](int it, int kp) {
-            return ld16(((kp & 1) ? pK1 : pK0) + 16 * it * RB + 128 * (kp >> 1));
+            return ld16(st + oK[kp] + 16 * it * RB);
         };
         auto ktslot = [&](int kt, int jp, int base, u32x2& q0, u32x2& q1) {      // base 0: K^T, OFF_Q: Q^T
             const int kp = kt >> 1, b = kt & 1;
-            const char* p = ((kp & 1) ? pT1 : pT0) + base + 32 * jp * RB + 128 * (kp >> 1) + 8 * b;
+            const char* p = st + oKT[kp] + base + 32 * jp * RB + 8 * b;
             q0 = lds_read_tr(p);
             q1 = lds_read_tr(p + 16 * RB);
         };
@@ -447,30 +444,27 @@ __global__ __launch_bounds__(256, 2) void bwd_assemble_bf16_kernel(BwdArgs<bf16_
 
     // ---- per-lane offsets ---------------------------------------------------------------------------
     // copies of [rows x d_k] tiles and of [64 x 32] slabs, swizzled on the global side (the 16-byte column index is
-    // XORed with swz_bits(row) resp. (row / 2) % 4)
+    // XORed with swz_piece(row) resp. (row / 2) % 4)
     const int lrow = lane / PPR, pcol = lane % PPR;
     const int lrowA = lane >> 2, pcolA = lane & 3;
-    // The per-lane part of a copy's address does not depend on the block, or only on its parity (4 rows per block),
-    // unless the chunk is ragged, where rows past its end re-read the last one.
+    // The per-lane part of a checkpoint copy's address depends on the block only through b % NGK (the swizzle has
+    // period 8 rows).  Rows past the end of a ragged chunk re-read its last one.
     const bool full = clen == 64;
-    int gkq[2], gst[2];
+    constexpr int NGK = 8 / RPB;
+    int gst[NGK];
 #pragma unroll
-    for (int par = 0; par < 2; ++par) {
-        gkq[par] = lrow * (int)kq_row + ((pcol ^ swz_bits(RPB * par + lrow)) * 16);
-        gst[par] = lrow * RB + ((pcol ^ swz_bits(RPB * par + lrow)) * 16);
-    }
+    for (int j = 0; j < NGK; ++j) gst[j] = lrow * RB + ((pcol ^ swz_piece<DK>(RPB * j + lrow)) * 16);
     const int gsl = lrowA * (int)v_row + ((pcolA ^ ((lrowA >> 1) & 3)) * 16);
     auto copy_tile = [&](const char* src, size_t stride, char* dst, int b0, int b1) {       // blocks [b0, b1) of a [64 x d_k] tile
         for (int b = b0; b < b1; ++b) {
             const int row = b * RPB + lrow;
-            if (full) dma16(src + (size_t)(b * RPB) * stride, gkq[(RPB == 4) ? (b & 1) : 0], dst + b * 1024);
-            else      dma16(src, min(row, clen - 1) * (int)stride + ((pcol ^ swz_bits(row)) * 16), dst + b * 1024);
+            dma16(src, min(row, clen - 1) * (int)stride + ((pcol ^ swz_piece<DK>(row)) * 16), dst + b * 1024);
         }
     };
     auto copy_state = [&](const char* src, char* dst) {                                      // 32 rows of a checkpoint: never ragged
         static_for<NSB>([&](auto bb) {
             const int b = bb;
-            dma16(src + b * RPB * RB, gst[(RPB == 4) ? (b & 1) : 0], dst + b * 1024);
+            dma16(src + b * RPB * RB, gst[b % NGK], dst + b * 1024);
         });
     };
     auto copy_slab = [&](const char* src, char* dst) {                                       // 4 blocks of 16 token rows x 64 bytes
@@ -490,12 +484,12 @@ __global__ __launch_bounds__(256, 2) void bwd_assemble_bf16_kernel(BwdArgs<bf16_
     };
     // column-contracted operand of a [64 x d_k] tile through the transposing read (as K^T in the sweeps)
     const int a4 = r >> 2, c4 = r & 3;
-    int oKT[2];
+    int oKT[KP];
 #pragma unroll
-    for (int par = 0; par < 2; ++par) oKT[par] = (4 * g + a4) * RB + (((4 * par + c4) ^ swz_bits(4 * g + a4)) * 16);
+    for (int kp = 0; kp < KP; ++kp) oKT[kp] = (4 * g + a4) * RB + (((4 * kp + c4) ^ swz_piece<DK>(4 * g + a4)) * 16);
     auto tslot = [&](const char* tile, int kt, int jp, u32x2& q0, u32x2& q1) {
         const int kp = kt >> 1, b = kt & 1;
-        const char* p = tile + oKT[kp & 1] + 32 * jp * RB + 128 * (kp >> 1) + 8 * b;
+        const char* p = tile + oKT[kp] + 32 * jp * RB + 8 * b;
         q0 = lds_read_tr(p);
         q1 = lds_read_tr(p + 16 * RB);
     };

@@ -136,7 +136,7 @@ __global__ __launch_bounds__(256, 3) void intra_bf16_kernel(IntraArgs<bf16_t> a)
         for (int i = 0; i < NKB / 4; ++i) {
             const int b = wave + 4 * i;
             const int row = b * RPB + lrow;
-            const int lo = min(row, clen - 1) * (int)kq_row + ((pcol ^ swz_bits(row)) * 16);
+            const int lo = min(row, clen - 1) * (int)kq_row + ((pcol ^ swz_piece<DK>(row)) * 16);
             dma16(kb, lo, kq + b * 1024);
             dma16(qb, lo, kq + TILE + b * 1024);
         }
@@ -169,7 +169,7 @@ __global__ __launch_bounds__(256, 3) void intra_bf16_kernel(IntraArgs<bf16_t> a)
         float ss = 0.f;
 #pragma unroll
         for (int i = 0; i < PPR / 4; ++i) {
-            const u32x4 w = ld16(qrow + ((((PPR / 4) * g + i) ^ swz_bits(row)) * 16));
+            const u32x4 w = ld16(qrow + ((((PPR / 4) * g + i) ^ swz_piece<DK>(row)) * 16));
 #pragma unroll
             for (int m = 0; m < 4; ++m) {
                 const float x0 = __uint_as_float(w[m] << 16), x1 = __uint_as_float(w[m] & 0xffff0000u);
@@ -187,7 +187,7 @@ __global__ __launch_bounds__(256, 3) void intra_bf16_kernel(IntraArgs<bf16_t> a)
 #pragma unroll
     for (int jb = 0; jb < 5; ++jb) acc[jb] = floatx4{0.f, 0.f, 0.f, 0.f};
     {
-        const int sw = swz_bits(r);                  // (16 t + r) & 7 == r & 7
+        const int sw = swz_piece<DK>(r);             // the swizzle has period 8 rows
         const char* rowp = kq + r * RB;              // row r of row block 0 of K; block b: + (b & 3) 16 RB (+ TILE for Q)
         static_for<4>([&](auto wc) {
             constexpr int W = wc;

@@ -175,14 +175,14 @@ struct HelperBase {
             char* row = tile + (16 * it + r) * (DK * 2);
             static_for<KP>([&](auto kpc) {
                 constexpr int kp = kpc;
-                st16(row + (((4 * kp + g) ^ swz_bits(r)) * 16), src[kp][it]);      // (16 it + r) & 7 == r & 7
+                st16(row + (((4 * kp + g) ^ swz_piece<DK>(r)) * 16), src[kp][it]);     // the swizzle has period 8 rows
             });
         });
     }
     __device__ __forceinline__ static u32x4 ring_slot(const char* tile, int it, int kp, int lane)
     {
         const int r = lane & 15, g = lane >> 4;
-        return ld16(tile + (16 * it + r) * (DK * 2) + (((4 * kp + g) ^ swz_bits(r)) * 16));
+        return ld16(tile + (16 * it + r) * (DK * 2) + (((4 * kp + g) ^ swz_piece<DK>(r)) * 16));
     }
 
     // Inclusive prefix sum of log alpha over the 64 lanes, in units of log 2 (every decay factor is then one
@@ -236,6 +236,11 @@ struct THelper : HelperBase<DK> {
 
     u32x4 ka[KP][4];                        // K row slots of the wave's next record
     float eta_pre;
+    // The four 16x16 fp32 blocks in the scratch are row-major with the 16-byte pieces of a row permuted: piece c of row
+    // `row` of block t sits at position c ^ (row / 2 % 4) ^ t.  With that, the stores of a tile (8 consecutive rows at one
+    // piece per cycle), the broadcast row reads of the substitution (the four lane groups read the same row of four
+    // different blocks) and the column reads that follow all spread over the LDS banks.
+    __device__ __forceinline__ static int blk_piece(int t, int row, int c) { return (c ^ (row >> 1) ^ t) & 3; }
     // carried from phase A to phase B: the six strictly lower tiles of L as A-operand quads, bf16; tile (ti, tj) at
     // index ti (ti - 1) / 2 + tj, lane (r, g) holds L[16 ti + r][16 tj + 4 g + e]
     u32x2 Lq[6];
@@ -302,8 +307,8 @@ struct THelper : HelperBase<DK> {
 #pragma unroll
             for (int e = 0; e < 4; ++e)                  // strictly lower
                 l[e] = (4 * g + e < r) ? beta_r * __builtin_amdgcn_exp2f(fminf(g2_r - gq[e], 0.f)) * Gd[t][e] : 0.f;
-            // block t of L, row-major, for the substitution: L_tt[r][4 g + e]
-            *reinterpret_cast<floatx4*>(hs + 256 * t + 16 * r + 4 * g) = l;
+            // block t of L, row-major, for the substitution: L_tt[r][4 g + e] (see blk_piece)
+            *reinterpret_cast<floatx4*>(hs + 256 * t + 16 * r + 4 * blk_piece(t, r, g)) = l;
         });
         static_for<4>([&](auto tic) {                    // strictly lower tiles: gamma_I/gamma_ref(I) gamma_ref(I)/gamma_J
             constexpr int ti = tic;
@@ -328,6 +333,9 @@ struct THelper : HelperBase<DK> {
         //      once (a broadcast read), four rows ahead of its use
         {
             float* Lb = hs + 256 * g;
+            const float* Lp[4];                          // Lp[x]: where piece x ^ g of a row starts
+#pragma unroll
+            for (int x = 0; x < 4; ++x) Lp[x] = Lb + 4 * (x ^ g);
             float xs[16];
             xs[0] = (r == 0) ? 1.f : 0.f;
             floatx4 rows[5][4];
@@ -335,7 +343,8 @@ struct THelper : HelperBase<DK> {
                 constexpr int i = ic;
                 if constexpr (i < 16) {
 #pragma unroll
-                    for (int c4 = 0; c4 < (i + 3) / 4; ++c4) rows[i % 5][c4] = *reinterpret_cast<const floatx4*>(Lb + 16 * i + 4 * c4);
+                    for (int c4 = 0; c4 < (i + 3) / 4; ++c4)
+                        rows[i % 5][c4] = *reinterpret_cast<const floatx4*>(Lp[c4 ^ ((i >> 1) & 3)] + 16 * i);
                 }
             };
             read_row(IntC<1>()); read_row(IntC<2>()); read_row(IntC<3>()); read_row(IntC<4>());
@@ -354,15 +363,22 @@ struct THelper : HelperBase<DK> {
 #pragma unroll
             for (int c4 = 0; c4 < 4; ++c4) {
                 const floatx4 v = {xs[4 * c4], xs[4 * c4 + 1], xs[4 * c4 + 2], xs[4 * c4 + 3]};
-                *reinterpret_cast<floatx4*>(Lb + 16 * r + 4 * c4) = v;
+                *reinterpret_cast<floatx4*>(Lb + 16 * r + 4 * blk_piece(g, r, c4)) = v;
             }
         }
         wave_lds_fence();
         floatx4 DA[4];                                   // D_t in A-operand order: D_t[r][4 g + j] = R_tt[4 g + j][r]
+        {
+            // element (row 4 g + e, column r) of block t sits in piece (r >> 2) ^ (2 g & 3) ^ (e >> 1) ^ t of its row
+            const int cr = (r >> 2) ^ ((2 * g) & 3);
+            int da[4];
 #pragma unroll
-        for (int t = 0; t < 4; ++t)
+            for (int x = 0; x < 4; ++x) da[x] = 64 * g + 4 * (cr ^ x) + (r & 3);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) DA[t][e] = hs[256 * t + 16 * (4 * g + e) + r];
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) DA[t][e] = hs[256 * t + 16 * e + da[(e >> 1) ^ t]];
+        }
 
         // T-area of the record: the 16x16 blocks of the block forward substitution, in the tile-pair layout of T'
         // (record order (ti, jp) = (0,0) (1,0) (2,0) (2,1) (3,0) (3,1)):
@@ -559,23 +575,24 @@ __global__ __launch_bounds__(64 * NW + (FU ? 384 : 64)) void scan_bf16_kernel(Sc
     // ---- loop-invariant per-lane offsets ------------------------------------------------------------
     // copy engine, global side: lane l of copy block b fills LDS bytes [1024 b + 16 l, +16) of a tile, i.e.
     // row 1024 b / RB + l / PPR, physical column l % PPR, which holds logical column (l % PPR) ^ swz(row).
-    // (row & 7) depends on the block only through its parity (RPB = 4) or not at all (RPB = 8).
+    // The swizzle has period 8 rows: it depends on the block through b % NGK.
+    constexpr int NGK = 8 / RPB;
     const int lrow = lane / PPR, pcol = lane % PPR;
-    int gk[2];
+    int gk[NGK];
 #pragma unroll
-    for (int par = 0; par < 2; ++par)
-        gk[par] = lrow * (int)kq_row + ((pcol ^ swz_bits(RPB * par + lrow)) * 16);
+    for (int j = 0; j < NGK; ++j)
+        gk[j] = lrow * (int)kq_row + ((pcol ^ swz_piece<DK>(RPB * j + lrow)) * 16);
     const int gv = (lane / VPP) * (int)v_row + (lane % VPP) * 16;
-    // LDS reads.  K/Q row slots: token row 16 it + r, logical column 4 kp + g = 8 m + 4 par + g:
-    int oK[2];
+    // LDS reads.  K/Q row slots: token row 16 it + r, logical column 4 kp + g:
+    int oK[KP];
 #pragma unroll
-    for (int par = 0; par < 2; ++par) oK[par] = r * RB + (((4 * par + g) ^ swz_bits(r)) * 16);
+    for (int kp = 0; kp < KP; ++kp) oK[kp] = r * RB + (((4 * kp + g) ^ swz_piece<DK>(r)) * 16);
     // K^T slots through the transposing read: source lane (a4, c4) points at token 4 g + a4 (+ 16 beta + 32 jp),
-    // logical column 8 m + 4 par + c4, half b.
+    // logical column 4 kp + c4, half b.
     const int a4 = r >> 2, c4 = r & 3;
-    int oKT[2];
+    int oKT[KP];
 #pragma unroll
-    for (int par = 0; par < 2; ++par) oKT[par] = (4 * g + a4) * RB + (((4 * par + c4) ^ swz_bits(4 * g + a4)) * 16);
+    for (int kp = 0; kp < KP; ++kp) oKT[kp] = (4 * g + a4) * RB + (((4 * kp + c4) ^ swz_piece<DK>(4 * g + a4)) * 16);
     const int oV = (4 * g + a4) * VRW + (16 * wave + 4 * c4) * 2;      // V tile rows 4 g + a4 (+ 16 it)
     // staging tile: after the 4x4 transposition below lane (r, g) holds row 4 g + (r & 3) (+ 16 it), columns
     // 4 (r >> 2) .. + 3 of this wave's 16
@@ -595,7 +612,7 @@ __global__ __launch_bounds__(64 * NW + (FU ? 384 : 64)) void scan_bf16_kernel(Sc
                 static_for<C::NKB>([&](auto i) {
                     const int b = i;
                     const size_t o = (size_t)(b * RPB) * kq_row;
-                    const int lo = (RPB == 4 && (b & 1)) ? gk[1] : gk[0];
+                    const int lo = gk[b % NGK];
                     dma16(kc + o, lo, st + b * 1024);
                     dma16(qc + o, lo, st + C::OFF_Q + b * 1024);
                     if constexpr (DG) dma16(k2base + (size_t)(64 * c) * kq_row + o, lo, st + C::OFF_K2 + b * 1024);
@@ -610,7 +627,7 @@ __global__ __launch_bounds__(64 * NW + (FU ? 384 : 64)) void scan_bf16_kernel(Sc
                 static_for<C::NKB>([&](auto i) {
                     const int b = i;
                     const int row = b * RPB + lrow;
-                    const int lo = min(row, clen - 1) * (int)kq_row + ((pcol ^ swz_bits(row)) * 16);
+                    const int lo = min(row, clen - 1) * (int)kq_row + ((pcol ^ swz_piece<DK>(row)) * 16);
                     dma16(kc, lo, st + b * 1024);
                     dma16(qc, lo, st + C::OFF_Q + b * 1024);
                     if constexpr (DG) dma16(k2base + (size_t)(64 * c) * kq_row, lo, st + C::OFF_K2 + b * 1024);
@@ -637,19 +654,15 @@ __global__ __launch_bounds__(64 * NW + (FU ? 384 : 64)) void scan_bf16_kernel(Sc
     // ---- one chunk of the recurrence for this wave's 16 columns ------------------------------------
     // rc: where T', P and the vectors of this chunk are (the ring stage itself, or a record buffer when fused)
     auto compute = [&](const char* st, const char* rc, char* ost) {
-        const char* pK0 = st + oK[0];
-        const char* pK1 = st + oK[1];
-        const char* pT0 = st + oKT[0];
-        const char* pT1 = st + oKT[1];
         const char* pS = rc + lane * 16;                 // T' / P slots
         const char* pV = st + C::OFF_V + oV;
         const char* pG = rc + C::R_EG + 16 * g;          // 4 consecutive floats: rows 4 g .. 4 g + 3
         auto kslot = [&](int it, int kp, int base) {     // base 0: K, OFF_Q: Q
-            return ld16(((kp & 1) ? pK1 : pK0) + base + 16 * it * RB + 128 * (kp >> 1));
+            return ld16(st + oK[kp] + base + 16 * it * RB);
         };
         auto ktslot = [&](int kt, int jp, u32x2& q0, u32x2& q1) {
             const int kp = kt >> 1, b = kt & 1;
-            const char* p = ((kp & 1) ? pT1 : pT0) + (DG ? C::OFF_K2 : 0) + 32 * jp * RB + 128 * (kp >> 1) + 8 * b;
+            const char* p = st + oKT[kp] + (DG ? C::OFF_K2 : 0) + 32 * jp * RB + 8 * b;
             q0 = lds_read_tr(p);
             q1 = lds_read_tr(p + 16 * RB);
         };

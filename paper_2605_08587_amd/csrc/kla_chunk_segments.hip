@@ -94,17 +94,18 @@ __global__ __launch_bounds__(192) void scan_maps_bf16_kernel(ScanArgs<bf16_t> a,
     if (wave == NW) {
         // ---- the copy wave ---------------------------------------------------------------------------
         const int lrow = lane / PPR, pcol = lane % PPR;
-        int gk[2];
+        constexpr int NGK = 8 / RPB;                    // the swizzle has period 8 rows
+        int gk[NGK];
 #pragma unroll
-        for (int par = 0; par < 2; ++par)
-            gk[par] = lrow * (int)kq_row + ((pcol ^ swz_bits(RPB * par + lrow)) * 16);
+        for (int j = 0; j < NGK; ++j)
+            gk[j] = lrow * (int)kq_row + ((pcol ^ swz_piece<DK>(RPB * j + lrow)) * 16);
         const int gv = (lane / VPP) * (int)v_row + (lane % VPP) * 16;
         auto issue = [&](int c, char* st) {
             const char* kc = kbase + (size_t)(64 * c) * kq_row;
             const char* tc = tpbase + (size_t)c * a.H * REC;
             static_for<C::NKB>([&](auto i) {
                 const int b = i;
-                dma16(kc + (size_t)(b * RPB) * kq_row, (RPB == 4 && (b & 1)) ? gk[1] : gk[0], st + b * 1024);
+                dma16(kc + (size_t)(b * RPB) * kq_row, gk[b % NGK], st + b * 1024);
             });
             static_for<C::NTB>([&](auto i) {
                 const int b = i;
@@ -141,12 +142,12 @@ __global__ __launch_bounds__(192) void scan_maps_bf16_kernel(ScanArgs<bf16_t> a,
     }
 
     // ---- compute waves: the chain part of the chunk recurrence ---------------------------------------
-    int oK[2], oKT[2];
+    int oK[KP], oKT[KP];
     const int a4 = r >> 2, c4 = r & 3;
 #pragma unroll
-    for (int par = 0; par < 2; ++par) {
-        oK[par] = r * RB + (((4 * par + g) ^ swz_bits(r)) * 16);
-        oKT[par] = (4 * g + a4) * RB + (((4 * par + c4) ^ swz_bits(4 * g + a4)) * 16);
+    for (int kp = 0; kp < KP; ++kp) {
+        oK[kp] = r * RB + (((4 * kp + g) ^ swz_piece<DK>(r)) * 16);
+        oKT[kp] = (4 * g + a4) * RB + (((4 * kp + c4) ^ swz_piece<DK>(4 * g + a4)) * 16);
     }
     const int oV = (4 * g + a4) * VRW + (16 * wave + 4 * c4) * 2;
 
@@ -154,10 +155,6 @@ __global__ __launch_bounds__(192) void scan_maps_bf16_kernel(ScanArgs<bf16_t> a,
     int scur = 0;
     for (int c = 0; c < nch; ++c) {
         const char* st = lds + scur * C::STAGE;
-        const char* pK0 = st + oK[0];
-        const char* pK1 = st + oK[1];
-        const char* pT0 = st + oKT[0];
-        const char* pT1 = st + oKT[1];
         const char* pG = st + C::OFF_EG + 16 * g;
         const float gC = *reinterpret_cast<const float*>(st + C::OFF_EG + 63 * 4);
         u32x2 Sq[KB];
@@ -172,7 +169,7 @@ __global__ __launch_bounds__(192) void scan_maps_bf16_kernel(ScanArgs<bf16_t> a,
         for (int kp = 0; kp < KP; ++kp)
 #pragma unroll
             for (int it = 0; it < 4; ++it)
-                mma_bf16(ks[it], ld16(((kp & 1) ? pK1 : pK0) + 16 * it * RB + 128 * (kp >> 1)), Sq[2 * kp], Sq[2 * kp + 1]);
+                mma_bf16(ks[it], ld16(st + oK[kp] + 16 * it * RB), Sq[2 * kp], Sq[2 * kp + 1]);
 
         // X = V - D_gamma K S (V = 0 in the phi columns);  U = T' X
         u32x2 Xq[4];
@@ -205,7 +202,7 @@ __global__ __launch_bounds__(192) void scan_maps_bf16_kernel(ScanArgs<bf16_t> a,
 #pragma unroll
             for (int t = 0; t < KB; ++t) {
                 const int kp = t >> 1, b = t & 1;
-                const char* p = ((kp & 1) ? pT1 : pT0) + 32 * jp * RB + 128 * (kp >> 1) + 8 * b;
+                const char* p = st + oKT[kp] + 32 * jp * RB + 8 * b;
                 mma_bf16(S[t], lds_read_tr(p), lds_read_tr(p + 16 * RB), Udq[2 * jp], Udq[2 * jp + 1]);
             }
         __syncthreads();   // chunk c+1's operands before their use; all reads of this stage before its refill
