@@ -80,6 +80,7 @@ struct Cfg {
     // barriers company - so that the two P-side helpers after it land on the SIMDs of the T-side ones - and those two
     static constexpr int NWAVES = NW + (FU ? 6 : 1);
     static constexpr int W_COPY = FU ? NW + 2 : NW;
+    static constexpr int W_P = NW + 4, W_IDLE = NW + 3;
     static_assert(LDS <= 160 * 1024 && (NST != 3 || NDMA < 64), "LDS budget of a gfx950 CU; 6-bit vmcnt (counted waits only with three stages)");
     static_assert(!FU || NST == 3, "fused mode is laid out for the three-stage ring");
 };
@@ -299,24 +300,36 @@ struct THelper : HelperBase<DK> {
 
         // ---- decay, mask, beta on the tiles of L.  Row token I, column token J:
         //   I = 16 ti + r, J = 16 tj + 4 g + e
+        // Every table value is read before the first block is written: the compiler keeps LDS reads behind earlier LDS
+        // writes it cannot tell apart, and one round trip per tile would put this wave's whole phase on the LDS latency.
+        floatx4 gq[4], bq[6];
+        float g2_r[4], beta_r[4], ba_r[4];
+        static_for<4>([&](auto tc) {
+            constexpr int t = tc;
+            gq[t] = *reinterpret_cast<const floatx4*>(hs + T_G2 + 16 * t + 4 * g);
+            g2_r[t] = hs[T_G2 + 16 * t + r];
+            beta_r[t] = hs[T_BETA + 16 * t + r];
+            ba_r[t] = hs[T_BA + 16 * t + r];
+            static_for<t>([&](auto tjc) {
+                constexpr int tj = tjc;
+                bq[t * (t - 1) / 2 + tj] = *reinterpret_cast<const floatx4*>(hs + T_B + 64 * (t - 1) + 16 * tj + 4 * g);
+            });
+        });
         static_for<4>([&](auto tc) {                     // diagonal tiles: 2^(g_I - g_J), J < I
             constexpr int t = tc;
-            const floatx4 gq = *reinterpret_cast<const floatx4*>(hs + T_G2 + 16 * t + 4 * g);
-            const float g2_r = hs[T_G2 + 16 * t + r], beta_r = hs[T_BETA + 16 * t + r];
             floatx4 l;
 #pragma unroll
             for (int e = 0; e < 4; ++e)                  // strictly lower
-                l[e] = (4 * g + e < r) ? beta_r * __builtin_amdgcn_exp2f(fminf(g2_r - gq[e], 0.f)) * Gd[t][e] : 0.f;
+                l[e] = (4 * g + e < r) ? beta_r[t] * __builtin_amdgcn_exp2f(fminf(g2_r[t] - gq[t][e], 0.f)) * Gd[t][e] : 0.f;
             // block t of L, row-major, for the substitution: L_tt[r][4 g + e] (see blk_piece)
             *reinterpret_cast<floatx4*>(hs + 256 * t + 16 * r + 4 * blk_piece(t, r, g)) = l;
         });
         static_for<4>([&](auto tic) {                    // strictly lower tiles: gamma_I/gamma_ref(I) gamma_ref(I)/gamma_J
             constexpr int ti = tic;
-            const float ba_r = hs[T_BA + 16 * ti + r];
             static_for<ti>([&](auto tjc) {
                 constexpr int tj = tjc;
-                const floatx4 bq = *reinterpret_cast<const floatx4*>(hs + T_B + 64 * (ti - 1) + 16 * tj + 4 * g);
-                Lq[ti * (ti - 1) / 2 + tj] = to_quad((bq * ba_r) * Gt[ti * (ti - 1) / 2 + tj]);
+                constexpr int i = ti * (ti - 1) / 2 + tj;
+                Lq[i] = to_quad((bq[i] * ba_r[ti]) * Gt[i]);
             });
         });
 #pragma unroll
@@ -407,7 +420,8 @@ struct PHelper : HelperBase<DK> {
 
     u32x4 ka[KP][4], qa[KP][4];             // K and Q row slots of the wave's next record
     // carried from phase A to phase B
-    floatx4 GP[10];                         // (K_tj Q_ti^T): accumulator tile (tj, ti), lane (r, g) holds k_J . q_I, I = 16 ti + r, J = 16 tj + 4 g + e
+    floatx4 GPd[4];                         // diagonal tiles of (K Q^T), row factors applied, before decay and mask
+    u32x2 Pt[10];                           // P^T tile (tj, ti) as A-operand quads, bf16: lane (r, g) holds P[I][J], I = 16 ti + r, J = 16 tj + 4 g + e
     float vgam, vdec, vgq;                  // lane = token: gamma_i, gamma_C / gamma_i, gamma_i / ||q_i||
 
     __device__ __forceinline__ void prefetch(const ScanArgs<bf16_t>& a, long tok0, int clen, int h, int lane_, const char* kc,
@@ -420,11 +434,12 @@ struct PHelper : HelperBase<DK> {
     }
 
     // Phase A (step c - 2): Q goes on into the ring (the T-side wave does the same with K); gates, tables, query
-    // norms; (Q K^T)^T on the matrix pipe.  qtile: the Q tile of the chunk's ring stage.
-    __device__ __forceinline__ void phase_a(float* hs, char* qtile, int lane_)
+    // norms; (Q K^T)^T on the matrix pipe; decay and mask.  qtile: the Q tile of the chunk's ring stage.
+    __device__ __forceinline__ void phase_a(float* hs, char* qtile, int clen, int lane_)
     {
         const int lane = opaque(lane_);
         const int r = lane & 15, g = lane >> 4;
+        floatx4 GP[10];                     // (K_tj Q_ti^T): accumulator tile (tj, ti), lane (r, g) holds k_J . q_I
         B::store_slots(qa, qtile, lane);
         float av, gl2;
         const float x2 = this->scan_gates(hs + T_G2, hs + T_B, lane, av, gl2);
@@ -466,18 +481,9 @@ struct PHelper : HelperBase<DK> {
             vgq = vgam * hs[T_RQ + lane];
         } else {
             vgq = vgam;
+            wave_lds_fence();
         }
-#pragma unroll
-        for (int i = 0; i < 10; ++i) B::keep(GP[i]);
-    }
-
-    // Phase B (step c - 1): decay and mask, the record.  Row token I = 16 ti + r, column token J = 16 tj + 4 g + e.
-    __device__ __forceinline__ void phase_b(const float* hs, char* rec, int clen, int lane_)
-    {
-        const int lane = opaque(lane_);
-        const int r = lane & 15, g = lane >> 4;
-        const u32x2 zq = {0u, 0u};
-        u32x2 Pt[10];
+        // ---- decay and mask.  Row token I = 16 ti + r, column token J = 16 tj + 4 g + e.
         static_for<4>([&](auto tic) {
             constexpr int ti = tic;
             const float rq_r = NQ ? hs[T_RQ + 16 * ti + r] : 1.f;
@@ -489,12 +495,29 @@ struct PHelper : HelperBase<DK> {
                 const floatx4 bq = *reinterpret_cast<const floatx4*>(hs + T_B + 64 * (ti - 1) + 16 * tj + 4 * g);
                 Pt[pidx(tj, ti)] = to_quad((bq * aq_r) * GP[pidx(tj, ti)]);
             });
+            GPd[ti] = GP[pidx(ti, ti)] * (rq_r * live);  // the diagonal tiles get their decay and mask in phase B
+        });
+        static_for<4>([&](auto tic) {
+            constexpr int ti = tic;
+            B::keep(GPd[ti]);
+            static_for<ti>([&](auto tjc) { B::keep(Pt[pidx(tjc, ti)]); });
+        });
+    }
+
+    // Phase B (step c - 1): decay and mask of the diagonal tiles, the record.
+    __device__ __forceinline__ void phase_b(const float* hs, char* rec, int lane_)
+    {
+        const int lane = opaque(lane_);
+        const int r = lane & 15, g = lane >> 4;
+        const u32x2 zq = {0u, 0u};
+        static_for<4>([&](auto tic) {                    // diagonal tiles: 2^(g_I - g_J), J <= I
+            constexpr int ti = tic;
             const floatx4 gq = *reinterpret_cast<const floatx4*>(hs + T_G2 + 16 * ti + 4 * g);
-            const float g2r = hs[T_G2 + 16 * ti + r], rl = rq_r * live;
+            const float g2r = hs[T_G2 + 16 * ti + r];
             floatx4 p;
 #pragma unroll
-            for (int e = 0; e < 4; ++e)                  // diagonal tile: 2^(g_I - g_J), J <= I
-                p[e] = (4 * g + e <= r) ? __builtin_amdgcn_exp2f(fminf(g2r - gq[e], 0.f)) * rl * GP[pidx(ti, ti)][e] : 0.f;
+            for (int e = 0; e < 4; ++e)
+                p[e] = (4 * g + e <= r) ? __builtin_amdgcn_exp2f(fminf(g2r - gq[e], 0.f)) * GPd[ti][e] : 0.f;
             Pt[pidx(ti, ti)] = to_quad(p);
         });
         // tile-pairs in record order (ti, jp) = (0,0) (1,0) (2,0) (2,1) (3,0) (3,1); tile (ti, tj) of P in A-operand order
@@ -839,7 +862,7 @@ __global__ __launch_bounds__(64 * NW + (FU ? 384 : 64)) void scan_bf16_kernel(Sc
     // work on chunk s, the helpers of parity (s & 1) are in phase A of chunk s + 2 and those of the other parity in
     // phase B of chunk s + 1, whose record goes into buffer (s + 1) & 1, which chunk s - 1 left free.
     if constexpr (FU) {
-        if (wave == NW + 3) {                            // keeps the barriers company (see Cfg::NWAVES)
+        if (wave == C::W_IDLE) {                            // keeps the barriers company (see Cfg::NWAVES)
             for (int s = -2; s < nch; ++s) __syncthreads();
             return;
         }
@@ -866,10 +889,10 @@ __global__ __launch_bounds__(64 * NW + (FU ? 384 : 64)) void scan_bf16_kernel(Sc
             for (; nb < nch + 2; ++nb) __syncthreads();
             return;
         }
-        if (wave == NW + 4 || wave == NW + 5) {          // P-side helpers
+        if (wave == C::W_P || wave == C::W_P + 1) {          // P-side helpers
             // the P-side wave of the even chunks shares its SIMD with the T-side wave of the odd ones and vice versa: in
             // every step each of the two SIMDs then has one wave in phase A and one in phase B
-            const int hh = 1 - (wave - NW - 4);
+            const int hh = 1 - (wave - C::W_P);
             float* hs = reinterpret_cast<float*>(lds + C::OFF_HSP + hh * C::HSCR_P);
             PHelper<DK, NQ> hp;
             hp.init_rows(lane, (int)kq_row);
@@ -881,10 +904,10 @@ __global__ __launch_bounds__(64 * NW + (FU ? 384 : 64)) void scan_bf16_kernel(Sc
             if (hh < nch) fetch(hh);
             if (hh == 1) { __syncthreads(); ++nb; }
             for (int c = hh; c < nch; c += 2) {
-                hp.phase_a(hs, lds + (c % NST) * C::STAGE + C::OFF_Q, lane);
+                hp.phase_a(hs, lds + (c % NST) * C::STAGE + C::OFF_Q, min(64, len - 64 * c), lane);
                 __syncthreads(); ++nb;
                 if (c + 2 < nch) fetch(c + 2);
-                hp.phase_b(hs, lds + C::OFF_REC + (c & 1) * C::RECB, min(64, len - 64 * c), lane);
+                hp.phase_b(hs, lds + C::OFF_REC + (c & 1) * C::RECB, lane);
                 __syncthreads(); ++nb;
             }
             for (; nb < nch + 2; ++nb) __syncthreads();
@@ -985,11 +1008,11 @@ static hipError_t launch_fused_dk(const ScanArgs<bf16_t>& a, int waves, hipStrea
     const dim3 grid((unsigned)(((n_chains + 7) / 8) * 8 * (a.dv / (16 * waves))));
     const bool nq = (a.opts & kOptNormalizeQ) != 0;
     if (waves == 1) {
-        if (nq) hipLaunchKernelGGL((scan_bf16_kernel<DK, 1, true, false, true>), grid, dim3(448), 0, st, a);
-        else    hipLaunchKernelGGL((scan_bf16_kernel<DK, 1, false, false, true>), grid, dim3(448), 0, st, a);
+        if (nq) hipLaunchKernelGGL((scan_bf16_kernel<DK, 1, true, false, true>), grid, dim3(64 * Cfg<DK, 1, false, true>::NWAVES), 0, st, a);
+        else    hipLaunchKernelGGL((scan_bf16_kernel<DK, 1, false, false, true>), grid, dim3(64 * Cfg<DK, 1, false, true>::NWAVES), 0, st, a);
     } else {
-        if (nq) hipLaunchKernelGGL((scan_bf16_kernel<DK, 2, true, false, true>), grid, dim3(512), 0, st, a);
-        else    hipLaunchKernelGGL((scan_bf16_kernel<DK, 2, false, false, true>), grid, dim3(512), 0, st, a);
+        if (nq) hipLaunchKernelGGL((scan_bf16_kernel<DK, 2, true, false, true>), grid, dim3(64 * Cfg<DK, 2, false, true>::NWAVES), 0, st, a);
+        else    hipLaunchKernelGGL((scan_bf16_kernel<DK, 2, false, false, true>), grid, dim3(64 * Cfg<DK, 2, false, true>::NWAVES), 0, st, a);
     }
     return hipGetLastError();
 }
