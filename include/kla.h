@@ -40,7 +40,10 @@
 extern "C" {
 #endif
 
-typedef enum { KLA_F32 = 0, KLA_BF16 = 1 } kla_dtype;
+/* Element type of q, k, v, o.  Passed as a plain int, so that a value that is neither of the two comes back as
+ * KLA_ERR_DTYPE (an enum parameter holding any other value is undefined behaviour in C++). */
+enum { KLA_F32 = 0, KLA_BF16 = 1 };
+typedef int kla_dtype;
 
 typedef enum {
     KLA_OK = 0,

@@ -27,7 +27,10 @@ _lib = None
 
 
 def build(force: bool = False) -> str:
-    """Compile the C oracle with gcc (no fast-math: summation order is kept)."""
+    """Compile the C oracle with gcc (no fast-math: summation order is kept).  KLA_ORACLE_LIBRARY names another build
+    of the same source (the host-sanitizer run of tests/host_sanitizers.py uses it)."""
+    if os.environ.get("KLA_ORACLE_LIBRARY"):
+        return os.environ["KLA_ORACLE_LIBRARY"]
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         tmp = _LIB + ".tmp.%d" % os.getpid()
         subprocess.check_call(["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-o", tmp, _SRC, "-lm"])

@@ -13,7 +13,8 @@ import threading
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libkla.so")
+# KLA_LIBRARY names another build of the same library (the host-sanitizer run of tests/host_sanitizers.py uses it)
+LIB_PATH = os.environ.get("KLA_LIBRARY") or os.path.join(_HERE, "libkla.so")
 HEADER_PATH = os.path.join(os.path.dirname(_HERE), "include", "kla.h")
 
 KLA_F32, KLA_BF16 = 0, 1
