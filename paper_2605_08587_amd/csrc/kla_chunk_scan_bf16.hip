@@ -256,12 +256,15 @@ struct THelper : HelperBase<DK> {
     }
 
     // ktile: the K tile of this chunk's ring stage
-    __device__ __forceinline__ void phase_a(const ScanArgs<bf16_t>& a, float* hs, char* ktile, int lane_)
+    __device__ __forceinline__ void phase_a(const ScanArgs<bf16_t>& a, float* hs, char* ktile, int* kflag, int c, int lane_)
     {
         const int lane = opaque(lane_);
         const int r = lane & 15, g = lane >> 4;
         const bool gdn = (a.opts & kOptGdnBeta) != 0;
         B::store_slots(ka, ktile, lane);
+        wave_lds_fence();
+        // a wave's LDS instructions are carried out in order: whoever sees the word sees the tile
+        if (lane == 0) *reinterpret_cast<volatile int*>(kflag) = c;
         float av, gl2;
         this->scan_gates(hs + T_G2, hs + T_B, lane, av, gl2);
 
@@ -418,24 +421,24 @@ struct PHelper : HelperBase<DK> {
     // P^T tile (tj, ti), tj <= ti
     __host__ __device__ static constexpr int pidx(int tj, int ti) { return ti * (ti + 1) / 2 + tj; }
 
-    u32x4 ka[KP][4], qa[KP][4];             // K and Q row slots of the wave's next record
+    u32x4 qa[KP][4];                        // Q row slots of the wave's next record (K comes through the ring stage)
     // carried from phase A to phase B
     floatx4 GPd[4];                         // diagonal tiles of (K Q^T), row factors applied, before decay and mask
     u32x2 Pt[10];                           // P^T tile (tj, ti) as A-operand quads, bf16: lane (r, g) holds P[I][J], I = 16 ti + r, J = 16 tj + 4 g + e
     float vgam, vdec, vgq;                  // lane = token: gamma_i, gamma_C / gamma_i, gamma_i / ||q_i||
 
-    __device__ __forceinline__ void prefetch(const ScanArgs<bf16_t>& a, long tok0, int clen, int h, int lane_, const char* kc,
-                                             const char* qc, int kq_row)
+    __device__ __forceinline__ void prefetch(const ScanArgs<bf16_t>& a, long tok0, int clen, int h, int lane_, const char* qc,
+                                             int kq_row)
     {
         const int lane = opaque(lane_);
         this->la_pre = lane < clen ? a.log_alpha[(size_t)(tok0 + lane) * a.H + h] : 0.f;
         this->load_slots(qa, qc, lane, clen, kq_row);
-        this->load_slots(ka, kc, lane, clen, kq_row);
     }
 
     // Phase A (step c - 2): Q goes on into the ring (the T-side wave does the same with K); gates, tables, query
     // norms; (Q K^T)^T on the matrix pipe; decay and mask.  qtile: the Q tile of the chunk's ring stage.
-    __device__ __forceinline__ void phase_a(float* hs, char* qtile, int clen, int lane_)
+    // ktile, kflag, c: the K tile of the same ring stage, and the word that says the T-side wave has filled it for chunk c
+    __device__ __forceinline__ void phase_a(float* hs, char* qtile, const char* ktile, const int* kflag, int c, int clen, int lane_)
     {
         const int lane = opaque(lane_);
         const int r = lane & 15, g = lane >> 4;
@@ -446,6 +449,15 @@ struct PHelper : HelperBase<DK> {
         vgam = __builtin_amdgcn_exp2f(x2);
         vdec = __builtin_amdgcn_exp2f(gl2 - x2);
         hs[T_A + lane] = av;
+        // K row slots from the ring stage, once the T-side wave of this chunk has stored them (it does so first thing in
+        // the same step and waits for nobody, so the wait is short and always ends; the bound is a safeguard only)
+        for (int spin = 0; *reinterpret_cast<const volatile int*>(kflag) != c && spin < (1 << 20); ++spin)
+            __builtin_amdgcn_s_sleep(1);
+        wave_lds_fence();
+        u32x4 ka[KP][4];
+        static_for<KP>([&](auto kpc) {
+            static_for<4>([&](auto itc) { ka[kpc][itc] = B::ring_slot(ktile, itc, kpc, lane); });
+        });
         const floatx4 z4 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int i = 0; i < 10; ++i) GP[i] = z4;
@@ -843,12 +855,15 @@ __global__ __launch_bounds__(64 * NW + (FU ? 384 : 64)) void scan_bf16_kernel(Sc
             *reinterpret_cast<u32x2*>(ost + oO + 16 * it * ORB) = quad_transpose4x4(to_quad(o[it]), q_lo, psel);
     };
 
-    auto write_out = [&](int c, const char* ost) {
+    // The staged output tile of chunk c goes to memory 16 bytes per thread: by the compute waves themselves, or (fused
+    // mode) by the wave that has nothing else to do, so that the compute waves go straight on to the next chunk.
+    auto write_out = [&](int c, const char* ost, int t_idx, auto n_thr) {
+        constexpr int NT = decltype(n_thr)::value;
         const int clen = min(64, len - 64 * c);
         char* ob = reinterpret_cast<char*>(a.o) + (size_t)(t0 + 64L * c) * v_row + ((size_t)h * a.dv + slice * SLW) * 2;
 #pragma unroll
-        for (int it = 0; it < 64 * VPP / NTH; ++it) {
-            const int i = tid + NTH * it;
+        for (int it = 0; it < 64 * VPP / NT; ++it) {
+            const int i = t_idx + NT * it;
             const int row = i / VPP, pv = i % VPP;
             // outputs are written once and not read again by this kernel: streamed past the caches
             if (row < clen) __builtin_nontemporal_store(ld16(ost + row * ORB + pv * 16), reinterpret_cast<u32x4*>(ob + (size_t)row * v_row + pv * 16));
@@ -862,8 +877,19 @@ __global__ __launch_bounds__(64 * NW + (FU ? 384 : 64)) void scan_bf16_kernel(Sc
     // work on chunk s, the helpers of parity (s & 1) are in phase A of chunk s + 2 and those of the other parity in
     // phase B of chunk s + 1, whose record goes into buffer (s + 1) & 1, which chunk s - 1 left free.
     if constexpr (FU) {
-        if (wave == C::W_IDLE) {                            // keeps the barriers company (see Cfg::NWAVES)
-            for (int s = -2; s < nch; ++s) __syncthreads();
+        // K reaches the P-side wave of a chunk through the ring stage, where the T-side wave of the same chunk puts it in
+        // the same step: a word per chunk parity says which chunk's K is there.  The two words live in the padding of the
+        // first two rows of the output staging tile (a row holds at most 64 of its ORB = 96 bytes).
+        if (tid < 2) *reinterpret_cast<int*>(ost0 + 64 + C::ORB * tid) = -1;
+        __syncthreads();
+        if (wave == C::W_IDLE) {
+            // Sits where it does so that the P-side helpers land on the SIMDs of the T-side ones (see Cfg::NWAVES); its
+            // work is the write-out: after the barrier that ends step s, chunk s is complete in the staging tile of its
+            // parity, which the compute waves write again only in step s + 2, behind the barrier this wave reaches next.
+            for (int s = -2; s < nch; ++s) {
+                __syncthreads();
+                if (s >= 0) write_out(s, (s & 1) ? ost1 : ost0, lane, IntC<64>());
+            }
             return;
         }
         // A helper of parity hh takes the chunks c = hh, hh + 2, ..: phase A in step c - 2, phase B in step c - 1, so it
@@ -880,7 +906,7 @@ __global__ __launch_bounds__(64 * NW + (FU ? 384 : 64)) void scan_bf16_kernel(Sc
             if (hh < nch) fetch(hh);                     // this wave's first record
             if (hh == 1) { __syncthreads(); ++nb; }
             for (int c = hh; c < nch; c += 2) {
-                hp.phase_a(a, hs, lds + (c % NST) * C::STAGE, lane);
+                hp.phase_a(a, hs, lds + (c % NST) * C::STAGE, reinterpret_cast<int*>(ost0 + 64 + C::ORB * hh), c, lane);
                 __syncthreads(); ++nb;
                 if (c + 2 < nch) fetch(c + 2);           // on their way during this step, used in the next
                 hp.phase_b(hs, lds + C::OFF_REC + (c & 1) * C::RECB, lane);
@@ -897,14 +923,14 @@ __global__ __launch_bounds__(64 * NW + (FU ? 384 : 64)) void scan_bf16_kernel(Sc
             PHelper<DK, NQ> hp;
             hp.init_rows(lane, (int)kq_row);
             auto fetch = [&](int c) {
-                hp.prefetch(a, t0 + 64L * c, min(64, len - 64 * c), h, lane, kbase + (size_t)(64 * c) * kq_row,
-                            qbase + (size_t)(64 * c) * kq_row, (int)kq_row);
+                hp.prefetch(a, t0 + 64L * c, min(64, len - 64 * c), h, lane, qbase + (size_t)(64 * c) * kq_row, (int)kq_row);
             };
             int nb = 0;
             if (hh < nch) fetch(hh);
             if (hh == 1) { __syncthreads(); ++nb; }
             for (int c = hh; c < nch; c += 2) {
-                hp.phase_a(hs, lds + (c % NST) * C::STAGE + C::OFF_Q, min(64, len - 64 * c), lane);
+                hp.phase_a(hs, lds + (c % NST) * C::STAGE + C::OFF_Q, lds + (c % NST) * C::STAGE,
+                           reinterpret_cast<const int*>(ost0 + 64 + C::ORB * hh), c, min(64, len - 64 * c), lane);
                 __syncthreads(); ++nb;
                 if (c + 2 < nch) fetch(c + 2);
                 hp.phase_b(hs, lds + C::OFF_REC + (c & 1) * C::RECB, lane);
@@ -952,7 +978,7 @@ __global__ __launch_bounds__(64 * NW + (FU ? 384 : 64)) void scan_bf16_kernel(Sc
         // c-1 (finished by every compute wave before it arrives here) before the staging tile of that
         // parity is written again in chunk c+1.
         __syncthreads();
-        write_out(c, ost);
+        if constexpr (!FU) write_out(c, ost, tid, IntC<NTH>());
         scur = (scur + 1 == NST) ? 0 : scur + 1;
     }
 
