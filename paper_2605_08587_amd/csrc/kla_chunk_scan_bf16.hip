@@ -242,9 +242,10 @@ struct THelper : HelperBase<DK> {
     // piece per cycle), the broadcast row reads of the substitution (the four lane groups read the same row of four
     // different blocks) and the column reads that follow all spread over the LDS banks.
     __device__ __forceinline__ static int blk_piece(int t, int row, int c) { return (c ^ (row >> 1) ^ t) & 3; }
-    // carried from phase A to phase B: the six strictly lower tiles of L as A-operand quads, bf16; tile (ti, tj) at
-    // index ti (ti - 1) / 2 + tj, lane (r, g) holds L[16 ti + r][16 tj + 4 g + e]
-    u32x2 Lq[6];
+    // carried from phase A to phase B: the six strictly lower tiles of K K^T, transposed (tile (ti, tj) at index
+    // ti (ti - 1) / 2 + tj, lane (r, g) holds k_I . k_J for I = 16 ti + r, J = 16 tj + 4 g + e); phase B scales them into
+    // the tiles of L in A-operand order, in the shadow of its substitution chain
+    floatx4 Gt[6];
 
     __device__ __forceinline__ void prefetch(const ScanArgs<bf16_t>& a, long tok0, int clen, int h, int lane_, const char* kc,
                                              int kq_row)
@@ -271,7 +272,9 @@ struct THelper : HelperBase<DK> {
         // ---- K K^T: the diagonal tiles and the six strictly lower ones, all transposed (rows <- block tj, column <-
         //      block ti): scaled, they are handed on as they are, in A-operand order
         const floatx4 z4 = {0.f, 0.f, 0.f, 0.f};
-        floatx4 Gd[4] = {z4, z4, z4, z4}, Gt[6] = {z4, z4, z4, z4, z4, z4};
+        floatx4 Gd[4] = {z4, z4, z4, z4};
+#pragma unroll
+        for (int i = 0; i < 6; ++i) Gt[i] = z4;
         static_for<KP>([&](auto kc_) {
             constexpr int kp = kc_;
             const u32x4* kk = ka[kp];
@@ -305,18 +308,13 @@ struct THelper : HelperBase<DK> {
         //   I = 16 ti + r, J = 16 tj + 4 g + e
         // Every table value is read before the first block is written: the compiler keeps LDS reads behind earlier LDS
         // writes it cannot tell apart, and one round trip per tile would put this wave's whole phase on the LDS latency.
-        floatx4 gq[4], bq[6];
-        float g2_r[4], beta_r[4], ba_r[4];
+        floatx4 gq[4];
+        float g2_r[4], beta_r[4];
         static_for<4>([&](auto tc) {
             constexpr int t = tc;
             gq[t] = *reinterpret_cast<const floatx4*>(hs + T_G2 + 16 * t + 4 * g);
             g2_r[t] = hs[T_G2 + 16 * t + r];
             beta_r[t] = hs[T_BETA + 16 * t + r];
-            ba_r[t] = hs[T_BA + 16 * t + r];
-            static_for<t>([&](auto tjc) {
-                constexpr int tj = tjc;
-                bq[t * (t - 1) / 2 + tj] = *reinterpret_cast<const floatx4*>(hs + T_B + 64 * (t - 1) + 16 * tj + 4 * g);
-            });
         });
         static_for<4>([&](auto tc) {                     // diagonal tiles: 2^(g_I - g_J), J < I
             constexpr int t = tc;
@@ -327,16 +325,8 @@ struct THelper : HelperBase<DK> {
             // block t of L, row-major, for the substitution: L_tt[r][4 g + e] (see blk_piece)
             *reinterpret_cast<floatx4*>(hs + 256 * t + 16 * r + 4 * blk_piece(t, r, g)) = l;
         });
-        static_for<4>([&](auto tic) {                    // strictly lower tiles: gamma_I/gamma_ref(I) gamma_ref(I)/gamma_J
-            constexpr int ti = tic;
-            static_for<ti>([&](auto tjc) {
-                constexpr int tj = tjc;
-                constexpr int i = ti * (ti - 1) / 2 + tj;
-                Lq[i] = to_quad((bq[i] * ba_r[ti]) * Gt[i]);
-            });
-        });
 #pragma unroll
-        for (int i = 0; i < 6; ++i) B::keep(Lq[i]);
+        for (int i = 0; i < 6; ++i) B::keep(Gt[i]);
     }
 
     __device__ __forceinline__ void phase_b(float* hs, char* rec, int lane_)
@@ -344,6 +334,20 @@ struct THelper : HelperBase<DK> {
         const int lane = opaque(lane_);
         const int r = lane & 15, g = lane >> 4;
         wave_lds_fence();
+        // ---- strictly lower tiles of L: beta_I gamma_I/gamma_ref(I) (per row, lane r) times gamma_ref(I)/gamma_J
+        u32x2 Lq[6];
+        static_for<4>([&](auto tic) {
+            constexpr int ti = tic;
+            if constexpr (ti > 0) {
+                const float ba_r = hs[T_BA + 16 * ti + r];
+                static_for<ti>([&](auto tjc) {
+                    constexpr int tj = tjc;
+                    constexpr int i = ti * (ti - 1) / 2 + tj;
+                    const floatx4 bq = *reinterpret_cast<const floatx4*>(hs + T_B + 64 * (ti - 1) + 16 * tj + 4 * g);
+                    Lq[i] = to_quad((bq * ba_r) * Gt[i]);
+                });
+            }
+        });
         // ---- diagonal blocks: D_t = (I + L_tt)^{-1} by forward substitution on the blocks phase A left in the scratch;
         //      lane group g takes block g, lane r its column r; row i of L_tt is read by all 16 lanes of the group at
         //      once (a broadcast read), four rows ahead of its use
@@ -423,7 +427,9 @@ struct PHelper : HelperBase<DK> {
 
     u32x4 qa[KP][4];                        // Q row slots of the wave's next record (K comes through the ring stage)
     // carried from phase A to phase B
+    static constexpr int TI_B = 3;          // strictly lower tiles (tj, ti) with ti >= TI_B are finished in phase B
     floatx4 GPd[4];                         // diagonal tiles of (K Q^T), row factors applied, before decay and mask
+    floatx4 GPl[3];                         // tiles (tj, 3), row factors applied, before decay
     u32x2 Pt[10];                           // P^T tile (tj, ti) as A-operand quads, bf16: lane (r, g) holds P[I][J], I = 16 ti + r, J = 16 tj + 4 g + e
     float vgam, vdec, vgq;                  // lane = token: gamma_i, gamma_C / gamma_i, gamma_i / ||q_i||
 
@@ -504,15 +510,19 @@ struct PHelper : HelperBase<DK> {
             const float aq_r = hs[T_A + 16 * ti + r] * rq_r * live;
             static_for<ti>([&](auto tjc) {
                 constexpr int tj = tjc;
-                const floatx4 bq = *reinterpret_cast<const floatx4*>(hs + T_B + 64 * (ti - 1) + 16 * tj + 4 * g);
-                Pt[pidx(tj, ti)] = to_quad((bq * aq_r) * GP[pidx(tj, ti)]);
+                if constexpr (ti < TI_B) {
+                    const floatx4 bq = *reinterpret_cast<const floatx4*>(hs + T_B + 64 * (ti - 1) + 16 * tj + 4 * g);
+                    Pt[pidx(tj, ti)] = to_quad((bq * aq_r) * GP[pidx(tj, ti)]);
+                } else {
+                    GPl[tj] = GP[pidx(tj, ti)] * aq_r;   // the last row of tiles gets its decay in phase B
+                }
             });
             GPd[ti] = GP[pidx(ti, ti)] * (rq_r * live);  // the diagonal tiles get their decay and mask in phase B
         });
         static_for<4>([&](auto tic) {
             constexpr int ti = tic;
             B::keep(GPd[ti]);
-            static_for<ti>([&](auto tjc) { B::keep(Pt[pidx(tjc, ti)]); });
+            static_for<ti>([&](auto tjc) { if constexpr (ti < TI_B) B::keep(Pt[pidx(tjc, ti)]); else B::keep(GPl[tjc]); });
         });
     }
 
@@ -522,6 +532,11 @@ struct PHelper : HelperBase<DK> {
         const int lane = opaque(lane_);
         const int r = lane & 15, g = lane >> 4;
         const u32x2 zq = {0u, 0u};
+        static_for<3>([&](auto tjc) {                    // tiles (tj, 3): gamma_ref(I) / gamma_J
+            constexpr int tj = tjc;
+            const floatx4 bq = *reinterpret_cast<const floatx4*>(hs + T_B + 64 * 2 + 16 * tj + 4 * g);
+            Pt[pidx(tj, 3)] = to_quad(bq * GPl[tj]);
+        });
         static_for<4>([&](auto tic) {                    // diagonal tiles: 2^(g_I - g_J), J <= I
             constexpr int ti = tic;
             const floatx4 gq = *reinterpret_cast<const floatx4*>(hs + T_G2 + 16 * ti + 4 * g);
