@@ -58,8 +58,9 @@ def main() -> int:
         if p.wait() != 0:
             raise SystemExit("compile failed")
     klib = os.path.join(tmp, "libkla_san.so")
-    run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-fsanitize=address", "-fsanitize=undefined", "-shared-libsan",
-         "-o", klib, *objs])
+    # host-only link of the sanitizer runtimes (no -Xarch_ option on this line, device sanitizers explicitly off)
+    run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-fno-gpu-sanitize", "-fsanitize=address", "-fsanitize=undefined",
+         "-shared-libsan", "-o", klib, *objs])
     rt = glob.glob("/opt/rocm/lib/llvm/lib/clang/*/lib/linux/libclang_rt.asan-x86_64.so")
     if not rt:
         raise SystemExit("clang's shared AddressSanitizer runtime not found")
