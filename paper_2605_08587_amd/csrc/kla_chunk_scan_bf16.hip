@@ -27,7 +27,8 @@
 //   * Fused mode (FU): no separate intra-chunk stage and no workspace.  Four more waves of the workgroup
 //     ("helpers", on the SIMDs that have no compute wave) produce the solve operands, P and the decay vectors of
 //     the chunks two and one steps ahead, straight into two LDS record buffers, so K and Q are read from memory
-//     once and the per-chunk objects never leave the CU (see the helper section below).
+//     once and the per-chunk objects never leave the CU (see the helper section below).  A seventh wave, otherwise
+//     idle, writes the staged outputs to memory.
 //   * A short last chunk is handled without zero filling: rows beyond it re-read the last valid row;
 //     their T' rows and columns are zero (beta = 0 there), so they contribute nothing to U, to the
 //     state or to any stored output.
@@ -102,20 +103,24 @@ struct Cfg {
 // (r, g) holds rows 4g..4g+3 of column r - is exactly the A-operand quad order of tile (ti, tj) of L that the record
 // stores.  Tiles live in registers; the only LDS the wave touches is its private scratch (per-token tables, the four
 // diagonal blocks on their way between layouts) and, at the very end, the record buffer.
-//   phase A  g = prefix sum of log alpha (units of log 2), decay tables; K K^T on bf16 MFMA (the ten lower tiles)
-//            from K row slots read straight from global memory; beta of eq. (3) from its diagonal; decay, mask
-//            and beta applied; the diagonal blocks to the scratch.
-//   phase B  the four diagonal blocks inverted by forward substitution, each block by one group of 16 lanes (lane =
-//            column, the rows of L read from the scratch by the whole group at once); everything rounded to bf16
-//            and written in operand order.
+//   phase A  the K row slots (loaded from global memory during the step before) go on into the ring stage of the
+//            chunk; g = prefix sum of log alpha (units of log 2), decay tables; K K^T on bf16 MFMA (the ten lower
+//            tiles); beta of eq. (3) from its diagonal; decay, mask and beta applied to the diagonal tiles, which go
+//            to the scratch.
+//   phase B  decay and beta on the six strictly lower tiles; the four diagonal blocks inverted by forward
+//            substitution, each block by one group of 16 lanes (lane = column, the rows of L read from the scratch by
+//            the whole group at once); everything rounded to bf16 and written in operand order.
 // P-side.  P = A o Q K^T of eq. (7) (with 1/||q_i|| on its rows for the normalised read-out), the ten lower tiles as
 // (Q K^T)^T so that they too come out in A-operand order, and the three decay vectors gamma_i, gamma_C/gamma_i,
-// gamma_i/||q_i||.  Phase A does all of it in registers, phase B writes the record.
+// gamma_i/||q_i||.  Phase A stores its Q row slots into the ring stage, takes the K row slots from there (the T-side wave
+// of the same chunk stores them in the same step and says so through a word in LDS), forms the products and scales the
+// upper rows of tiles; phase B finishes the diagonal tiles and the last row and writes the record.
 //
-// The helpers' reads of K and Q are the first touch of these rows (the ring's copies of the same chunk follow and find
-// them in L2).  They are requested one step before phase A uses them - a chunk step is shorter than a trip to memory:
-// the gates and the K row slots into registers; of the Q rows only one dword per 128-byte line, which brings them
-// into L2, from where phase A loads them.
+// K and Q are therefore read from memory once per workgroup, into registers, one step before phase A uses them (a chunk
+// step is shorter than a trip to memory); the ring's K and Q tiles are written from those registers, and only the V slice
+// comes through the copy engine.  How the work is split between the two phases of each wave follows from per-wave
+// timestamps: in every step each of the two helper SIMDs runs one phase A and one phase B, and the four phases are
+// balanced to within a few percent of each other and of a compute wave's step.
 //
 // Decay ratios off the diagonal tiles are the product of two factors <= 1, gamma_I / gamma_ref and
 // gamma_ref / gamma_J with ref the first token of I's tile (J < ref <= I there): 2^x is evaluated a few times per
