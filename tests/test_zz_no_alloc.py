@@ -54,9 +54,9 @@ def _case(N, T, H, dk, dv, dtype, seed, packed=False):
 def test_static_matches_workspace_entry_point(dtype):
     tol = TOL_BF16 if dtype == torch.bfloat16 else TOL_F32
     # first a larger problem (ragged tail, several chunks; the packed one also has a one-token sequence), then a
-    # smaller one on the same GPU: the array still holds the first call's records.  fp32 inputs always go through the
-    # scratch; of the bf16 cases the 4100-token one does (segment-parallel scan: records, maps and states), the others
-    # run the fused kernel, which leaves the array alone.
+    # smaller one on the same GPU: the array still holds the first call's records.  All of these go through the scratch
+    # (fp32 always does; bf16 batches this small run the two-kernel form, the 4100-token one the segment-parallel scan
+    # with records, maps and states); only large bf16 batches run the fused kernel, which leaves the array alone.
     for (N, T, H, dk, dv, seed, packed) in ((1, 4100, 2, 128, 128, 30, False), (2, 1000, 4, 128, 128, 31, False), (1, 200, 2, 128, 128, 32, False),
                                             (1, 333, 3, 64, 256, 33, True), (1, 70, 2, 64, 64, 34, False)):
         d = _case(N, T, H, dk, dv, dtype, seed, packed)
