@@ -43,8 +43,10 @@ struct SweepCfg16 {
                          OFF_EG = OFF_V + 64 * VRW, STAGE = OFF_EG + (REV ? 1024 : 768);
     static constexpr int ORB = NW <= 2 ? 96 : 160;       // row stride of a staging tile (see the forward kernel)
     static constexpr int OSB = 64 * ORB;
-    static constexpr int NST = (3 * STAGE + 4 * OSB <= 160 * 1024) ? 3 : 2;   // LDS ring depth
-    static constexpr int LDS = NST * STAGE + 4 * OSB;    // two staged tiles per chunk, two parities
+    static constexpr int CKB = SLW * DK * 2;             // the workgroup's part of a checkpoint, staged for the store wave
+    static constexpr int NST = (3 * STAGE + 4 * OSB + 2 * CKB <= 160 * 1024) ? 3 : 2;   // LDS ring depth
+    static constexpr int OFF_CK = NST * STAGE + 4 * OSB;
+    static constexpr int LDS = OFF_CK + 2 * CKB;         // two staged tiles and a checkpoint per chunk, two parities
     static constexpr int NDMA = (REV ? 2 : 1) * NKB + NTB + NVB + 1;
     static_assert(LDS <= 160 * 1024 && NDMA < 64, "LDS budget of a gfx950 CU; 6-bit vmcnt");
 };
@@ -52,7 +54,7 @@ struct SweepCfg16 {
 }  // namespace
 
 template <int DK, int NW, bool REV>
-__global__ __launch_bounds__(64 * NW + 64) void bwd_sweep_bf16_kernel(BwdArgs<bf16_t> a)
+__global__ __launch_bounds__(64 * NW + 128) void bwd_sweep_bf16_kernel(BwdArgs<bf16_t> a)
 {
     typedef SweepCfg16<DK, NW, REV> C;
     constexpr int NTH = C::NTH, KB = C::KB, KP = C::KP, SLW = C::SLW, RB = C::RB, PPR = C::PPR, RPB = C::RPB,
@@ -170,7 +172,7 @@ __global__ __launch_bounds__(64 * NW + 64) void bwd_sweep_bf16_kernel(BwdArgs<bf
     auto stage_quad = [&](u32x2 ob, char* dst) { *reinterpret_cast<u32x2*>(dst) = quad_transpose4x4(ob, q_lo, psel); };
 
     // ---- one chunk for this wave's 16 columns -----------------------------------------------------------
-    auto compute = [&](const char* st, char* ost, int c) {
+    auto compute = [&](const char* st, char* ost, char* ckb, int c) {
         const char* pS = st + lane * 16;
         const char* pV = st + C::OFF_V + oV;
         const char* pG = st + C::OFF_EG + 16 * g;
@@ -188,12 +190,16 @@ __global__ __launch_bounds__(64 * NW + 64) void bwd_sweep_bf16_kernel(BwdArgs<bf
         u32x2 Sq[KB];
 #pragma unroll
         for (int kt = 0; kt < KB; ++kt) { Sq[kt] = to_quad(S[kt]); S[kt] = S[kt] * gC; }
-        if (store) {   // checkpoint, transposed: features 32 kp + 8 g .. + 7 of column `col` are 16 contiguous bytes
-            bf16_t* ck = (REV ? a.ds_chk : a.s_chk) + (((size_t)(ch0 + c) * a.H + h) * a.dv_dim + col) * DK + 8 * g;
+        if (store) {
+            // checkpoint, transposed ([column][feature]): features 32 kp + 8 g .. + 7 of this lane's column are 16
+            // contiguous bytes.  Staged in LDS for the store wave; the 16-byte pieces of a column are XORed with the
+            // column so that the eight lanes a 128-bit write serves per cycle fall into different banks.
+            const int cl = 16 * wave + r;
+            char* ck = ckb + cl * (DK * 2);
 #pragma unroll
             for (int kp = 0; kp < KP; ++kp) {
                 const u32x4 w = {Sq[2 * kp].x, Sq[2 * kp].y, Sq[2 * kp + 1].x, Sq[2 * kp + 1].y};
-                st16(ck + 32 * kp, w);
+                st16(ck + (((4 * kp + g) ^ (cl & 7)) * 16), w);
             }
         }
 
@@ -311,27 +317,50 @@ __global__ __launch_bounds__(64 * NW + 64) void bwd_sweep_bf16_kernel(BwdArgs<bf
         }
     };
 
-    // the two staged tiles of chunk c -> global (forward: X, U; backward: Y, dV), 16 bytes per lane
-    auto write_out = [&](int c, const char* ost) {
+    // Everything chunk c leaves in memory goes out through one wave that does nothing else, 16 bytes per lane: the two
+    // staged tiles (forward: X, U; backward: Y, dV) and the workgroup's columns of the checkpoint.  The compute waves
+    // never issue a global store, so they never stand in the store queue.
+    auto write_out = [&](int c, const char* ost, const char* ckb) {
         const int clen = min(64, len - 64 * c);
         const size_t off = (size_t)(t0 + 64L * c) * v_row + ((size_t)h * a.dv_dim + slice * SLW) * 2;
         char* o0 = reinterpret_cast<char*>(REV ? a.Y : a.X) + off;
         char* o1 = reinterpret_cast<char*>(REV ? a.dv : a.U) + off;
 #pragma unroll
-        for (int it = 0; it < 64 * VPP / NTH; ++it) {
-            const int i = tid + NTH * it;
+        for (int it = 0; it < VPP; ++it) {
+            const int i = lane + 64 * it;
             const int row = i / VPP, pv = i % VPP;
-            if (row < clen && store) {
+            if (row < clen) {
                 st16(o0 + (size_t)row * v_row + pv * 16, ld16(ost + row * ORB + pv * 16));
                 st16(o1 + (size_t)row * v_row + pv * 16, ld16(ost + C::OSB + row * ORB + pv * 16));
             }
+        }
+        char* ck = reinterpret_cast<char*>(REV ? a.ds_chk : a.s_chk) +
+                   (((size_t)(ch0 + c) * a.H + h) * a.dv_dim + slice * SLW) * (DK * 2);
+#pragma unroll
+        for (int it = 0; it < C::CKB / 1024; ++it) {
+            const int i = lane + 64 * it;
+            const int cl = i / PPR, pp = i % PPR;        // column of the workgroup, physical piece
+            st16(ck + cl * (DK * 2) + ((pp ^ (cl & 7)) * 16), ld16(ckb + i * 16));
         }
     };
 
     char* ost0 = lds + NST * C::STAGE;
     char* ost1 = ost0 + 2 * C::OSB;
+    char* ckb0 = lds + C::OFF_CK;
     // chunks are visited in the order i = 0 .. nch-1; the backward sweep starts at the last chunk
     auto chunk_of = [&](int i) { return REV ? nch - 1 - i : i; };
+
+    if (wave == NW + 1) {
+        // ---- the store wave: after the barrier that ends visit i, chunk_of(i) is complete in the staging areas of
+        //      parity i & 1, which the compute waves write again only in visit i + 2, behind the barrier this wave
+        //      reaches next
+        __syncthreads();
+        for (int i = 0; i < nch; ++i) {
+            __syncthreads();
+            if (store) write_out(chunk_of(i), (i & 1) ? ost1 : ost0, ckb0 + (i & 1) * C::CKB);
+        }
+        return;
+    }
 
     if (wave == NW) {
         // ---- the copy wave: keeps the next NST-1 chunks on their way while one is computed -----------------
@@ -357,9 +386,8 @@ __global__ __launch_bounds__(64 * NW + 64) void bwd_sweep_bf16_kernel(BwdArgs<bf
     for (int i = 0; i < nch; ++i) {
         const int c = chunk_of(i);
         char* ost = (i & 1) ? ost1 : ost0;
-        compute(lds + scur * C::STAGE, ost, c);
+        compute(lds + scur * C::STAGE, ost, ckb0 + (i & 1) * C::CKB, c);
         __syncthreads();
-        write_out(c, ost);
         scur = (scur + 1 == NST) ? 0 : scur + 1;
     }
 
@@ -754,8 +782,8 @@ static hipError_t launch_sweep_dk(const BwdArgs<bf16_t>& a, int waves, hipStream
     const int n_chains = (a.n_seq > 0 ? a.n_seq : (a.seg_G > 0 ? a.N * a.seg_G : a.N)) * a.H;
     if (n_chains == 0) return hipSuccess;
     const dim3 grid((unsigned)(((n_chains + 7) / 8) * 8 * (a.dv_dim / (16 * waves))));
-    if (waves == 1) hipLaunchKernelGGL((bwd_sweep_bf16_kernel<DK, 1, REV>), grid, dim3(128), 0, st, a);
-    else            hipLaunchKernelGGL((bwd_sweep_bf16_kernel<DK, 2, REV>), grid, dim3(192), 0, st, a);
+    if (waves == 1) hipLaunchKernelGGL((bwd_sweep_bf16_kernel<DK, 1, REV>), grid, dim3(192), 0, st, a);
+    else            hipLaunchKernelGGL((bwd_sweep_bf16_kernel<DK, 2, REV>), grid, dim3(256), 0, st, a);
     return hipGetLastError();
 }
 
