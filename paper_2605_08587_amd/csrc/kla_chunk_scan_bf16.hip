@@ -339,17 +339,19 @@ struct THelper : HelperBase<DK> {
         const int lane = opaque(lane_);
         const int r = lane & 15, g = lane >> 4;
         wave_lds_fence();
-        // ---- strictly lower tiles of L: beta_I gamma_I/gamma_ref(I) (per row, lane r) times gamma_ref(I)/gamma_J
+        // ---- strictly lower tiles of L: beta_I gamma_I/gamma_ref(I) (per row, lane r) times gamma_ref(I)/gamma_J.
+        //      The factors are requested here; the products are formed below, while the first rows of the substitution
+        //      are on their way from LDS.
         u32x2 Lq[6];
+        floatx4 bq[6];
+        float ba_r[4];
         static_for<4>([&](auto tic) {
             constexpr int ti = tic;
             if constexpr (ti > 0) {
-                const float ba_r = hs[T_BA + 16 * ti + r];
+                ba_r[ti] = hs[T_BA + 16 * ti + r];
                 static_for<ti>([&](auto tjc) {
                     constexpr int tj = tjc;
-                    constexpr int i = ti * (ti - 1) / 2 + tj;
-                    const floatx4 bq = *reinterpret_cast<const floatx4*>(hs + T_B + 64 * (ti - 1) + 16 * tj + 4 * g);
-                    Lq[i] = to_quad((bq * ba_r) * Gt[i]);
+                    bq[ti * (ti - 1) / 2 + tj] = *reinterpret_cast<const floatx4*>(hs + T_B + 64 * (ti - 1) + 16 * tj + 4 * g);
                 });
             }
         });
@@ -373,6 +375,13 @@ struct THelper : HelperBase<DK> {
                 }
             };
             read_row(IntC<1>()); read_row(IntC<2>()); read_row(IntC<3>()); read_row(IntC<4>());
+            static_for<4>([&](auto tic) {
+                constexpr int ti = tic;
+                static_for<ti>([&](auto tjc) {
+                    constexpr int i = ti * (ti - 1) / 2 + tjc;
+                    Lq[i] = to_quad((bq[i] * ba_r[ti]) * Gt[i]);
+                });
+            });
             static_for<15>([&](auto ic) {
                 constexpr int i = ic + 1;
                 read_row(IntC<i + 4>());
