@@ -193,6 +193,66 @@ def test_chunk_small_shapes_fused(kla, dk, dv, T, monkeypatch):
     assert token_oracle.rel_err(o2, o1) <= TOL[torch.bfloat16] and token_oracle.rel_err(h2, h1) <= TOL[torch.bfloat16]
 
 
+@pytest.mark.parametrize("case", ["options", "packed", "extreme_decay", "zero_keys_and_eta", "long_carry", "no_h0_ragged"])
+def test_chunk_fused_edge_cases(kla, case, monkeypatch):
+    """The fused kernel (what large bf16 batches run) forced on the cases the other tests send through the two-kernel
+    form: both option bits, packed batches with one-token and exactly-one-chunk sequences, decay that wipes the state
+    within a token, zero keys and eta = 0 tokens, a state carried over ~60 chunks, and ragged tails without h0."""
+    monkeypatch.setattr(kla, "DEFAULT_TUNE", kla.tune(fused=True))
+    bf = torch.bfloat16
+    if case == "options":
+        for nq, gdn, (T, dk, dv) in ((True, False, (200, 128, 128)), (False, True, (65, 64, 128)), (True, True, (130, 128, 64))):
+            d = kla_inputs.chunk_inputs(2, T, 3, dk, dv, dtype=bf, seed=191 + T, h0_std=0.5)
+            if gdn:
+                d["k"] = (d["k"].float() * 0.08).to(bf)
+            if nq:
+                d["q"][1, min(7, T - 1), 2] = 0
+            q, k, v, la, eta, h0 = _gpu(d, "q", "k", "v", "log_alpha", "eta", "h0")
+            o, hT = kla.kla_chunk_fwd(q, k, v, la, eta, d["eps"], h0=h0, normalize_q=nq, gdn_beta=gdn)
+            torch.cuda.synchronize()
+            o, hT = o.float().cpu().numpy(), hT.cpu().numpy()
+            qn, kn, vn = (kla_inputs.to_numpy_f32(d[x]) for x in "qkv")
+            ro, rh, _ = token_oracle.kla_recurrent(qn, kn, vn, d["log_alpha"].numpy(), d["eta"].numpy(), d["eps"],
+                                                   h0=d["h0"].numpy(), normalize_q=nq, gdn_beta=gdn)
+            eo, eh = token_oracle.rel_err(o, ro), token_oracle.rel_err(hT, rh)
+            print("fused, options nq=%s gdn=%s T=%d: rel err o=%.3e hT=%.3e" % (nq, gdn, T, eo, eh), flush=True)
+            assert eo <= TOL[bf] and eh <= TOL[bf]
+            if nq:
+                assert np.all(o[1, min(7, T - 1), 2] == 0.0)
+        return
+    if case == "packed":
+        d = kla_inputs.varlen_inputs(6, 1, 300, 3, 128, 128, dtype=bf, seed=161, h0_std=0.3)
+        _check_chunk(kla, d)
+        d = kla_inputs.varlen_inputs(5, 1, 130, 2, 64, 64, dtype=bf, seed=162, h0_std=0.3)
+        _check_chunk(kla, d)
+        # hand-made lengths: a one-token sequence, exactly one chunk, one chunk + 1, an empty sequence
+        lens = [1, 64, 65, 0, 200]
+        d = kla_inputs.chunk_inputs(1, sum(lens), 2, 128, 64, dtype=bf, seed=163)
+        d["cu_seqlens"] = torch.tensor(np.concatenate([[0], np.cumsum(lens)]), dtype=torch.int32)
+        d["h0"] = torch.randn(len(lens), 2, 128, 64, generator=torch.Generator().manual_seed(164)) * 0.3
+        _check_chunk(kla, d)
+        return
+    if case == "extreme_decay":
+        d = kla_inputs.chunk_inputs(2, 300, 2, 128, 128, dtype=bf, seed=171, h0_std=0.5, log_alpha_scale=50.0)
+        _check_chunk(kla, d)
+        return
+    if case == "zero_keys_and_eta":
+        d = kla_inputs.chunk_inputs(2, 200, 2, 128, 128, dtype=bf, seed=181, h0_std=0.5)
+        d["k"][0, 5:9] = 0                      # zero keys: beta = 0 for eps = 0, no write
+        d["k"][1, 64:128] = 0                   # a whole chunk of them
+        d["eta"][0, 20:40] = 0                  # pure decay steps
+        d["eta"][1, :, 1] = 0                   # a head that never writes
+        d["eps"] = 0.0
+        _check_chunk(kla, d)
+        return
+    if case == "long_carry":
+        d = kla_inputs.chunk_inputs(1, 4000, 2, 128, 128, dtype=bf, seed=175, log_alpha_scale=0.01, h0_std=0.2)
+        _check_chunk(kla, d)
+        return
+    for T in (3, 127, 191, 1000):
+        _check_chunk(kla, kla_inputs.chunk_inputs(3, T, 2, 64, 128, dtype=bf, seed=201 + T))
+
+
 def test_chunk_config2_two_kernel_form(kla, monkeypatch):
     monkeypatch.setattr(kla, "DEFAULT_TUNE", kla.tune(unfused=True))
     _check_chunk(kla, kla_inputs.config(2))
