@@ -454,15 +454,18 @@ def main():
         from oracle import token_oracle
         qn, kn, vn = (kla_inputs.to_numpy_f32(d[x]) for x in "qkv")
         la, et = d["log_alpha"].numpy(), d["eta"].numpy()
-        t0 = time.perf_counter()
-        ro, rh, nthr = token_oracle.kla_recurrent(qn, kn, vn, la, et, d["eps"])
-        dt = time.perf_counter() - t0
+        # the whole of config 2, three times over (about 25 s of CPU work on 16 threads); the rate is that of the best pass
+        dt = float("inf")
+        for _ in range(3):
+            t0 = time.perf_counter()
+            ro, rh, nthr = token_oracle.kla_recurrent(qn, kn, vn, la, et, d["eps"])
+            dt = min(dt, time.perf_counter() - t0)
         # one thread on a 1/8 slice: the first sequence of the batch (8 of the 64 sequence-heads)
         t0 = time.perf_counter()
         token_oracle.kla_recurrent(qn[:1], kn[:1], vn[:1], la[:1], et[:1], d["eps"], threads=1)
         dt1 = time.perf_counter() - t0
         cpu = {"value": round(tokens / dt, 1), "unit": "tokens/s", "cores": nthr, "kind": "oracle",
-               "sample": "all of config 2 (64 sequence-heads x 4096 tokens), fp64 token loop, %.1f s wall" % dt,
+               "sample": "all of config 2 (64 sequence-heads x 4096 tokens), fp64 token loop, best of 3 passes, %.1f s wall each" % dt,
                "single_thread": {"value": round(T / dt1, 1), "unit": "tokens/s (of 8 heads)", "cores": 1,
                                  "sample": "1/8 slice: the first sequence (8 sequence-heads x 4096 tokens), %.1f s wall" % dt1}}
         step()
