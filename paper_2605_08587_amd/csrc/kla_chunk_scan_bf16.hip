@@ -972,9 +972,6 @@ __global__ __launch_bounds__(64 * NW + (FU ? 384 : 64)) void scan_bf16_kernel(Sc
 
     if (wave == C::W_COPY) {
         // ---- the copy wave: keeps chunks c+1 .. c+NST-1 on their way while chunk c is computed ---------
-        // In the fused mode it shares its SIMD with a compute wave, which would otherwise leave it an issue slot only
-        // now and then (measured: 4 000 cycles to issue one chunk's 36 copies): its few instructions go first.
-        if constexpr (FU) __builtin_amdgcn_s_setprio(3);
 #pragma unroll
         for (int p = 0; p < NST - 1; ++p)
             if (p < nch) issue(p, lds + p * C::STAGE);
