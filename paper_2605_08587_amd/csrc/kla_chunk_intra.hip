@@ -349,16 +349,20 @@ template hipError_t launch_intra_bwd<bf16_t>(const IntraArgs<bf16_t>&, int, int,
 template <typename E, int DK>
 __global__ __launch_bounds__(256) void intra_diag_kernel(IntraDiagArgs<E> a)
 {
-    constexpr int EPP = 16 / (int)sizeof(E), PPR = DK / EPP;
-    constexpr int LE = DK + EPP;                     // row stride of the K, Q tables (elements): one 16-byte piece of padding
-    constexpr int LD = DK + 4;                       // row stride of the log-sum table (floats)
+    // The tables hold CH = 64 channels at a time: d_k = 128 takes two passes, whose partial sums meet in the registers
+    // that hold the products.  That keeps the kernel at the LDS footprint of the 64x64 fp32 matrices of the later
+    // phases (52.5 KB), i.e. three workgroups per CU instead of two.
+    constexpr int CH = 64, NPASS = DK / CH;
+    constexpr int EPP = 16 / (int)sizeof(E), PPR = DK / EPP, PPH = CH / EPP;
+    constexpr int LE = CH + EPP;                     // row stride of the K, Q tables (elements): one 16-byte piece of padding
+    constexpr int LD = CH + 4;                       // row stride of the log-sum table (floats)
     constexpr int TE = 64 * LE * (int)sizeof(E), TG = 64 * LD * 4;
-    constexpr int NSEG = 256 / DK, SROWS = 64 / NSEG;   // the running sums: 256 threads = d_k channels x NSEG row segments
+    constexpr int NSEG = 256 / CH, SROWS = 64 / NSEG;   // the running sums: 256 threads = CH channels x NSEG row segments
     constexpr int REC = ws_record_bytes<E>();
     __shared__ __attribute__((aligned(16))) char area[2 * TE + TG > 3 * 64 * kLdm * 4 ? 2 * TE + TG : 3 * 64 * kLdm * 4];
     __shared__ __attribute__((aligned(16))) float beta_s[64];
     __shared__ __attribute__((aligned(16))) float rq_s[64];      // 1/||q_i|| for the normalised read-out (Sec. 3.3), else 1
-    __shared__ float segsum[NSEG][DK];
+    __shared__ float segsum[NSEG][CH];
     const E* Kp = reinterpret_cast<const E*>(area);           // K rows (element type), later overlaid by Lm, Pm, Tm
     const E* Qp = reinterpret_cast<const E*>(area + TE);      // Q rows
     float* Gs = reinterpret_cast<float*>(area + 2 * TE);      // running sums of log2 alpha per channel
@@ -403,57 +407,33 @@ __global__ __launch_bounds__(256) void intra_diag_kernel(IntraDiagArgs<E> a)
     };
     auto ld4f = [](const float* p) { const float4 w = *reinterpret_cast<const float4*>(p); floatx4 f; f[0] = w.x; f[1] = w.y; f[2] = w.z; f[3] = w.w; return f; };
 
-    // ---- phase 1: K, Q rows and log2 alpha -> LDS; key norms -> beta ---------------------------------------------
-    {
-        const E* kb = a.k + (size_t)tok0 * row_stride + (size_t)h * DK;
-        const E* qb = a.q + (size_t)tok0 * row_stride + (size_t)h * DK;
-        const float* lb = a.log_alpha + (size_t)tok0 * row_stride + (size_t)h * DK;
+    const E* kb = a.k + (size_t)tok0 * row_stride + (size_t)h * DK;
+    const E* qb = a.q + (size_t)tok0 * row_stride + (size_t)h * DK;
+    const float* lb = a.log_alpha + (size_t)tok0 * row_stride + (size_t)h * DK;
+
+    // ---- phase 0: key and query norms over all channels -> beta, 1/||q|| (the rows are read again, pass by pass, below)
 #pragma unroll
-        for (int it = 0; it < 64 * PPR / 256; ++it) {
-            const int pi = tid + 256 * it;
-            const int row = pi / PPR, piece = pi % PPR;
-            uint4 kd = make_uint4(0, 0, 0, 0), qd = make_uint4(0, 0, 0, 0);
-            if (row < clen) {
-                kd = *reinterpret_cast<const uint4*>(kb + (size_t)row * row_stride + piece * EPP);
-                qd = *reinterpret_cast<const uint4*>(qb + (size_t)row * row_stride + piece * EPP);
-            }
-            *reinterpret_cast<uint4*>(area + (size_t)(row * LE + piece * EPP) * sizeof(E)) = kd;
-            *reinterpret_cast<uint4*>(area + TE + (size_t)(row * LE + piece * EPP) * sizeof(E)) = qd;
-            float kf[EPP], qf0[EPP];
-            unpack(kd, kf);
-            unpack(qd, qf0);
-            float ss = 0.f, sq = 0.f;
-#pragma unroll
-            for (int i = 0; i < EPP; ++i) { ss += kf[i] * kf[i]; sq += qf0[i] * qf0[i]; }
-#pragma unroll
-            for (int off = 1; off < PPR; off <<= 1) { ss += __shfl_xor(ss, off, kWave); sq += __shfl_xor(sq, off, kWave); }
-            if (piece == 0) {
-                const float et = row < clen ? a.eta[(size_t)(tok0 + row) * a.H + h] : 0.f;
-                beta_s[row] = (a.opts & kOptGdnBeta) ? et : kaczmarz_beta(et, ss, a.eps);
-                rq_s[row] = (a.opts & kOptNormalizeQ) ? (sq > 0.f ? 1.0f / sqrtf(sq) : 0.f) : 1.f;
-            }
+    for (int it = 0; it < 64 * PPR / 256; ++it) {
+        const int pi = tid + 256 * it;
+        const int row = pi / PPR, piece = pi % PPR;
+        uint4 kd = make_uint4(0, 0, 0, 0), qd = make_uint4(0, 0, 0, 0);
+        if (row < clen) {
+            kd = *reinterpret_cast<const uint4*>(kb + (size_t)row * row_stride + piece * EPP);
+            qd = *reinterpret_cast<const uint4*>(qb + (size_t)row * row_stride + piece * EPP);
         }
+        float kf[EPP], qf0[EPP];
+        unpack(kd, kf);
+        unpack(qd, qf0);
+        float ss = 0.f, sq = 0.f;
 #pragma unroll
-        for (int it = 0; it < 64 * DK / 4 / 256; ++it) {
-            const int x = tid + 256 * it, row = x / (DK / 4), c4 = x % (DK / 4);
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (row < clen) v = *reinterpret_cast<const float4*>(lb + (size_t)row * row_stride + 4 * c4);
-            const float s2 = 1.44269504088896341f;
-            *reinterpret_cast<float4*>(Gs + row * LD + 4 * c4) = make_float4(v.x * s2, v.y * s2, v.z * s2, v.w * s2);
+        for (int i = 0; i < EPP; ++i) { ss += kf[i] * kf[i]; sq += qf0[i] * qf0[i]; }
+#pragma unroll
+        for (int off = 1; off < PPR; off <<= 1) { ss += __shfl_xor(ss, off, kWave); sq += __shfl_xor(sq, off, kWave); }
+        if (piece == 0) {
+            const float et = row < clen ? a.eta[(size_t)(tok0 + row) * a.H + h] : 0.f;
+            beta_s[row] = (a.opts & kOptGdnBeta) ? et : kaczmarz_beta(et, ss, a.eps);
+            rq_s[row] = (a.opts & kOptNormalizeQ) ? (sq > 0.f ? 1.0f / sqrtf(sq) : 0.f) : 1.f;
         }
-    }
-    __syncthreads();
-    {   // per channel: running sum over the tokens of the chunk, NSEG row segments side by side, then their offsets
-        const int c = tid % DK, sg = tid / DK;
-        float acc = 0.f;
-        for (int i = sg * SROWS; i < (sg + 1) * SROWS; ++i) { acc += Gs[i * LD + c]; Gs[i * LD + c] = acc; }
-        segsum[sg][c] = acc;
-        __syncthreads();
-        float base = 0.f;
-        for (int s2 = 0; s2 < sg; ++s2) base += segsum[s2][c];
-        if (sg > 0)
-            for (int i = sg * SROWS; i < (sg + 1) * SROWS; ++i) Gs[i * LD + c] += base;
-        if (sg == NSEG - 1) a.gc[(size_t)blockIdx.x * DK + c] = __builtin_amdgcn_exp2f(base + acc);      // gamma_C
     }
     if (tid < 128) {                                 // unit decay vectors for the scan: g = 0, 1/||q|| = 1
         a.wsG[(size_t)blockIdx.x * 128 + tid] = tid < 64 ? 0.f : 1.f;
@@ -461,87 +441,12 @@ __global__ __launch_bounds__(256) void intra_diag_kernel(IntraDiagArgs<E> a)
         dec[tid] = 1.f;
         if (tid < 64) dec[128 + tid] = 1.f;
     }
-    __syncthreads();
 
-    // ---- phase 1b: the scan's operands K+, Q+, K~ in the element type -----------------------------------------
-    {
-        E* kpo = a.kplus + (size_t)tok0 * row_stride + (size_t)h * DK;
-        E* qpo = a.qplus + (size_t)tok0 * row_stride + (size_t)h * DK;
-        E* kto = a.ktilde + (size_t)tok0 * row_stride + (size_t)h * DK;
-#pragma unroll
-        for (int it = 0; it < 64 * PPR / 256; ++it) {
-            const int pi = tid + 256 * it;
-            const int row = pi / PPR, piece = pi % PPR;
-            if (row < clen) {
-                float kf[EPP], qf[EPP], kp[EPP], qp[EPP], kt[EPP];
-                unpack(*reinterpret_cast<const uint4*>(area + (size_t)(row * LE + piece * EPP) * sizeof(E)), kf);
-                unpack(*reinterpret_cast<const uint4*>(area + TE + (size_t)(row * LE + piece * EPP) * sizeof(E)), qf);
-#pragma unroll
-                for (int i = 0; i < EPP; ++i) {
-                    const float gi = Gs[row * LD + piece * EPP + i], gl = Gs[63 * LD + piece * EPP + i];
-                    const float up = __builtin_amdgcn_exp2f(gi);
-                    kp[i] = kf[i] * up; qp[i] = qf[i] * (up * rq_s[row]); kt[i] = kf[i] * __builtin_amdgcn_exp2f(gl - gi);
-                }
-                const size_t off = (size_t)row * row_stride + piece * EPP;
-                *reinterpret_cast<uint4*>(kpo + off) = pack(kp);
-                *reinterpret_cast<uint4*>(qpo + off) = pack(qp);
-                *reinterpret_cast<uint4*>(kto + off) = pack(kt);
-            }
-        }
-    }
-    // (no barrier: phase 2a only reads the tables, like phase 1b)
-
-    // ---- phase 2a: K K^T and Q K^T with the decay ratios inside the sums ---------------------------------------
-    // (1) MFMA jobs, operands formed in registers from the tables: the six off-diagonal 16x16 tiles (ti > tj), split at
-    //     e = last row of tile tj, A row i = k_i (or q_i) o gamma_i/gamma_e, B row j = k_j o gamma_e/gamma_j; and of
-    //     each diagonal tile the lower-left 8x8 block, split at e = row 7 of the tile, the other rows of both operands
-    //     zero.  Every factor is <= 1.  Jobs 0..9 go to wave (job % 4).
-    // (2) the 8x8 blocks on the diagonal, one (i, j) pair per thread over all channels: gamma_i/gamma_j <= 1 directly.
+    // accumulators of phase 2a, over all passes
     const int r = lane & 15, g = lane >> 4;
     floatx4 tkk[3], tqk[3];
 #pragma unroll
     for (int jb = 0; jb < 3; ++jb) { tkk[jb] = floatx4{0.f, 0.f, 0.f, 0.f}; tqk[jb] = tkk[jb]; }
-#pragma unroll
-    for (int jb = 0; jb < 3; ++jb) {
-        const int job = wave + 4 * jb;
-        if (job >= 10) break;
-        int ti, tj, e_row; bool a_ok, b_ok;
-        if (job < 6) {
-            ti = job < 1 ? 1 : (job < 3 ? 2 : 3);
-            tj = job < 1 ? 0 : (job < 3 ? job - 1 : job - 3);
-            e_row = 16 * tj + 15; a_ok = true; b_ok = true;
-        } else {
-            ti = tj = job - 6;
-            e_row = 16 * ti + 7; a_ok = r >= 8; b_ok = r < 8;
-        }
-        const float* gi = Gs + (16 * ti + r) * LD;
-        const float* gj = Gs + (16 * tj + r) * LD;
-        const float* ge = Gs + e_row * LD;
-        const E* ki = Kp + (16 * ti + r) * LE;
-        const E* qi = Qp + (16 * ti + r) * LE;
-        const E* kj = Kp + (16 * tj + r) * LE;
-        for (int kp = 0; kp < DK / 32; ++kp) {
-            floatx4 ka[2], qa[2], kb[2];
-#pragma unroll
-            for (int blk = 0; blk < 2; ++blk) {
-                const int c = 32 * kp + 16 * blk + 4 * g;
-                const floatx4 gev = ld4f(ge + c), giv = ld4f(gi + c), gjv = ld4f(gj + c);
-                const floatx4 kiv = ld4e(ki + c), qiv = ld4e(qi + c), kjv = ld4e(kj + c);
-#pragma unroll
-                for (int x = 0; x < 4; ++x) {
-                    const float up = a_ok ? __builtin_amdgcn_exp2f(giv[x] - gev[x]) : 0.f;      // gamma_i / gamma_e
-                    const float dn = b_ok ? __builtin_amdgcn_exp2f(gev[x] - gjv[x]) : 0.f;      // gamma_e / gamma_j
-                    ka[blk][x] = kiv[x] * up; qa[blk][x] = qiv[x] * up; kb[blk][x] = kjv[x] * dn;
-                }
-            }
-            Slot<E> sk, sq;
-            sk.q0 = acc_to_quad<E>(ka[0]); sk.q1 = acc_to_quad<E>(ka[1]);
-            sq.q0 = acc_to_quad<E>(qa[0]); sq.q1 = acc_to_quad<E>(qa[1]);
-            const typename QuadT<E>::type b0 = acc_to_quad<E>(kb[0]), b1 = acc_to_quad<E>(kb[1]);
-            mma32<E>(tkk[jb], sk, b0, b1);
-            mma32<E>(tqk[jb], sq, b0, b1);
-        }
-    }
     float pkk = 0.f, pqk = 0.f, pdg = 0.f;
     int pi = 0, pj = 0;
     if (tid < 224) {                                 // 8 blocks x 28 pairs with j < i
@@ -549,25 +454,143 @@ __global__ __launch_bounds__(256) void intra_diag_kernel(IntraDiagArgs<E> a)
         int ii = 1;
         while ((ii * (ii + 1)) / 2 <= p) ++ii;       // ii (ii - 1) / 2 <= p < ii (ii + 1) / 2
         pi = 8 * b8 + ii; pj = 8 * b8 + p - (ii * (ii - 1)) / 2;
-        const float* gi = Gs + pi * LD; const float* gj = Gs + pj * LD;
-        const E* ki = Kp + pi * LE; const E* qi = Qp + pi * LE; const E* kj = Kp + pj * LE;
-#pragma unroll 2
-        for (int c = 0; c < DK; c += 4) {
-            const floatx4 giv = ld4f(gi + c), gjv = ld4f(gj + c);
-            const floatx4 kiv = ld4e(ki + c), qiv = ld4e(qi + c), kjv = ld4e(kj + c);
+    }
+
+    for (int pass = 0; pass < NPASS; ++pass) {
+        const int c0 = pass * CH;                    // first channel of this pass
+        if (pass > 0) __syncthreads();               // the previous pass has read its tables
+        // ---- phase 1: K, Q rows and log2 alpha of CH channels -> LDS ---------------------------------------------
 #pragma unroll
-            for (int x = 0; x < 4; ++x) {
-                const float w = kjv[x] * __builtin_amdgcn_exp2f(giv[x] - gjv[x]);
-                pkk += kiv[x] * w; pqk += qiv[x] * w;
+        for (int it = 0; it < 64 * PPH / 256; ++it) {
+            const int x = tid + 256 * it;
+            const int row = x / PPH, piece = x % PPH;
+            uint4 kd = make_uint4(0, 0, 0, 0), qd = make_uint4(0, 0, 0, 0);
+            if (row < clen) {
+                kd = *reinterpret_cast<const uint4*>(kb + (size_t)row * row_stride + c0 + piece * EPP);
+                qd = *reinterpret_cast<const uint4*>(qb + (size_t)row * row_stride + c0 + piece * EPP);
+            }
+            *reinterpret_cast<uint4*>(area + (size_t)(row * LE + piece * EPP) * sizeof(E)) = kd;
+            *reinterpret_cast<uint4*>(area + TE + (size_t)(row * LE + piece * EPP) * sizeof(E)) = qd;
+        }
+#pragma unroll
+        for (int it = 0; it < 64 * CH / 4 / 256; ++it) {
+            const int x = tid + 256 * it, row = x / (CH / 4), c4 = x % (CH / 4);
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (row < clen) v = *reinterpret_cast<const float4*>(lb + (size_t)row * row_stride + c0 + 4 * c4);
+            const float s2 = 1.44269504088896341f;
+            *reinterpret_cast<float4*>(Gs + row * LD + 4 * c4) = make_float4(v.x * s2, v.y * s2, v.z * s2, v.w * s2);
+        }
+        __syncthreads();
+        {   // per channel: running sum over the tokens of the chunk, NSEG row segments side by side, then their offsets
+            const int c = tid % CH, sg = tid / CH;
+            float acc = 0.f;
+            for (int i = sg * SROWS; i < (sg + 1) * SROWS; ++i) { acc += Gs[i * LD + c]; Gs[i * LD + c] = acc; }
+            segsum[sg][c] = acc;
+            __syncthreads();
+            float base = 0.f;
+            for (int s2 = 0; s2 < sg; ++s2) base += segsum[s2][c];
+            if (sg > 0)
+                for (int i = sg * SROWS; i < (sg + 1) * SROWS; ++i) Gs[i * LD + c] += base;
+            if (sg == NSEG - 1) a.gc[(size_t)blockIdx.x * DK + c0 + c] = __builtin_amdgcn_exp2f(base + acc);      // gamma_C
+        }
+        __syncthreads();
+
+        // ---- phase 1b: the scan's operands K+, Q+, K~ in the element type -------------------------------------
+        {
+            E* kpo = a.kplus + (size_t)tok0 * row_stride + (size_t)h * DK + c0;
+            E* qpo = a.qplus + (size_t)tok0 * row_stride + (size_t)h * DK + c0;
+            E* kto = a.ktilde + (size_t)tok0 * row_stride + (size_t)h * DK + c0;
+#pragma unroll
+            for (int it = 0; it < 64 * PPH / 256; ++it) {
+                const int x = tid + 256 * it;
+                const int row = x / PPH, piece = x % PPH;
+                if (row < clen) {
+                    float kf[EPP], qf[EPP], kp[EPP], qp[EPP], kt[EPP];
+                    unpack(*reinterpret_cast<const uint4*>(area + (size_t)(row * LE + piece * EPP) * sizeof(E)), kf);
+                    unpack(*reinterpret_cast<const uint4*>(area + TE + (size_t)(row * LE + piece * EPP) * sizeof(E)), qf);
+#pragma unroll
+                    for (int i = 0; i < EPP; ++i) {
+                        const float gi = Gs[row * LD + piece * EPP + i], gl = Gs[63 * LD + piece * EPP + i];
+                        const float up = __builtin_amdgcn_exp2f(gi);
+                        kp[i] = kf[i] * up; qp[i] = qf[i] * (up * rq_s[row]); kt[i] = kf[i] * __builtin_amdgcn_exp2f(gl - gi);
+                    }
+                    const size_t off = (size_t)row * row_stride + piece * EPP;
+                    *reinterpret_cast<uint4*>(kpo + off) = pack(kp);
+                    *reinterpret_cast<uint4*>(qpo + off) = pack(qp);
+                    *reinterpret_cast<uint4*>(kto + off) = pack(kt);
+                }
             }
         }
-    }
-    if (tid < 64) {                                  // P_ii = q_i . k_i
-        const E* ki = Kp + tid * LE; const E* qi = Qp + tid * LE;
-        for (int c = 0; c < DK; c += 4) {
-            const floatx4 kiv = ld4e(ki + c), qiv = ld4e(qi + c);
+        // (no barrier: phase 2a only reads the tables, like phase 1b)
+
+        // ---- phase 2a: K K^T and Q K^T with the decay ratios inside the sums, the channels of this pass ---------
+        // (1) MFMA jobs, operands formed in registers from the tables: the six off-diagonal 16x16 tiles (ti > tj), split at
+        //     e = last row of tile tj, A row i = k_i (or q_i) o gamma_i/gamma_e, B row j = k_j o gamma_e/gamma_j; and of
+        //     each diagonal tile the lower-left 8x8 block, split at e = row 7 of the tile, the other rows of both operands
+        //     zero.  Every factor is <= 1.  Jobs 0..9 go to wave (job % 4).
+        // (2) the 8x8 blocks on the diagonal, one (i, j) pair per thread over all channels: gamma_i/gamma_j <= 1 directly.
 #pragma unroll
-            for (int x = 0; x < 4; ++x) pdg += qiv[x] * kiv[x];
+        for (int jb = 0; jb < 3; ++jb) {
+            const int job = wave + 4 * jb;
+            if (job >= 10) break;
+            int ti, tj, e_row; bool a_ok, b_ok;
+            if (job < 6) {
+                ti = job < 1 ? 1 : (job < 3 ? 2 : 3);
+                tj = job < 1 ? 0 : (job < 3 ? job - 1 : job - 3);
+                e_row = 16 * tj + 15; a_ok = true; b_ok = true;
+            } else {
+                ti = tj = job - 6;
+                e_row = 16 * ti + 7; a_ok = r >= 8; b_ok = r < 8;
+            }
+            const float* gi = Gs + (16 * ti + r) * LD;
+            const float* gj = Gs + (16 * tj + r) * LD;
+            const float* ge = Gs + e_row * LD;
+            const E* ki = Kp + (16 * ti + r) * LE;
+            const E* qi = Qp + (16 * ti + r) * LE;
+            const E* kj = Kp + (16 * tj + r) * LE;
+            for (int kp = 0; kp < CH / 32; ++kp) {
+                floatx4 ka[2], qa[2], kbv[2];
+#pragma unroll
+                for (int blk = 0; blk < 2; ++blk) {
+                    const int c = 32 * kp + 16 * blk + 4 * g;
+                    const floatx4 gev = ld4f(ge + c), giv = ld4f(gi + c), gjv = ld4f(gj + c);
+                    const floatx4 kiv = ld4e(ki + c), qiv = ld4e(qi + c), kjv = ld4e(kj + c);
+#pragma unroll
+                    for (int x = 0; x < 4; ++x) {
+                        const float up = a_ok ? __builtin_amdgcn_exp2f(giv[x] - gev[x]) : 0.f;      // gamma_i / gamma_e
+                        const float dn = b_ok ? __builtin_amdgcn_exp2f(gev[x] - gjv[x]) : 0.f;      // gamma_e / gamma_j
+                        ka[blk][x] = kiv[x] * up; qa[blk][x] = qiv[x] * up; kbv[blk][x] = kjv[x] * dn;
+                    }
+                }
+                Slot<E> sk, sq;
+                sk.q0 = acc_to_quad<E>(ka[0]); sk.q1 = acc_to_quad<E>(ka[1]);
+                sq.q0 = acc_to_quad<E>(qa[0]); sq.q1 = acc_to_quad<E>(qa[1]);
+                const typename QuadT<E>::type b0 = acc_to_quad<E>(kbv[0]), b1 = acc_to_quad<E>(kbv[1]);
+                mma32<E>(tkk[jb], sk, b0, b1);
+                mma32<E>(tqk[jb], sq, b0, b1);
+            }
+        }
+        if (tid < 224) {
+            const float* gi = Gs + pi * LD; const float* gj = Gs + pj * LD;
+            const E* ki = Kp + pi * LE; const E* qi = Qp + pi * LE; const E* kj = Kp + pj * LE;
+#pragma unroll 2
+            for (int c = 0; c < CH; c += 4) {
+                const floatx4 giv = ld4f(gi + c), gjv = ld4f(gj + c);
+                const floatx4 kiv = ld4e(ki + c), qiv = ld4e(qi + c), kjv = ld4e(kj + c);
+#pragma unroll
+                for (int x = 0; x < 4; ++x) {
+                    const float w = kjv[x] * __builtin_amdgcn_exp2f(giv[x] - gjv[x]);
+                    pkk += kiv[x] * w; pqk += qiv[x] * w;
+                }
+            }
+        }
+        if (tid < 64) {                                  // P_ii = q_i . k_i
+            const E* ki = Kp + tid * LE; const E* qi = Qp + tid * LE;
+            for (int c = 0; c < CH; c += 4) {
+                const floatx4 kiv = ld4e(ki + c), qiv = ld4e(qi + c);
+#pragma unroll
+                for (int x = 0; x < 4; ++x) pdg += qiv[x] * kiv[x];
+            }
         }
     }
     __syncthreads();   // the tables are dead from here on; Lm, Pm, Tm overlay them
