@@ -444,9 +444,24 @@ __global__ __launch_bounds__(256) void intra_diag_kernel(IntraDiagArgs<E> a)
 
     // accumulators of phase 2a, over all passes
     const int r = lane & 15, g = lane >> 4;
-    floatx4 tkk[3], tqk[3];
+    floatx4 tkk[2], tqk[2];
 #pragma unroll
-    for (int jb = 0; jb < 3; ++jb) { tkk[jb] = floatx4{0.f, 0.f, 0.f, 0.f}; tqk[jb] = tkk[jb]; }
+    for (int jb = 0; jb < 2; ++jb) { tkk[jb] = floatx4{0.f, 0.f, 0.f, 0.f}; tqk[jb] = tkk[jb]; }
+    // The MFMA jobs of phase 2a, two per wave: jobs 0..5 are the off-diagonal tiles (ti, tj); jobs 6 and 7 each take the
+    // lower-left 8x8 blocks of TWO diagonal tiles (2 (job - 6) and the next) in one 16x16 product - operand rows 0..7 belong
+    // to the first tile, rows 8..15 to the second, and the two off-diagonal 8x8 blocks of the result are not used.
+    // Per lane: the table row of its A operand row (ja), of its B operand row (jbr) and of the reference rows they are
+    // split at.
+    auto job_rows = [&](int job, int& ja, int& jbr, int& ea, int& eb) {
+        if (job < 6) {
+            const int ti = job < 1 ? 1 : (job < 3 ? 2 : 3);
+            const int tj = job < 1 ? 0 : (job < 3 ? job - 1 : job - 3);
+            ja = 16 * ti + r; jbr = 16 * tj + r; ea = eb = 16 * tj + 15;
+        } else {
+            const int t = 2 * (job - 6) + (r >> 3);      // the diagonal tile this lane's operand rows belong to
+            ja = 16 * t + 8 + (r & 7); jbr = 16 * t + (r & 7); ea = eb = 16 * t + 7;
+        }
+    };
     float pkk = 0.f, pqk = 0.f, pdg = 0.f;
     int pi = 0, pj = 0;
     if (tid < 224) {                                 // 8 blocks x 28 pairs with j < i
@@ -530,35 +545,28 @@ __global__ __launch_bounds__(256) void intra_diag_kernel(IntraDiagArgs<E> a)
         //     zero.  Every factor is <= 1.  Jobs 0..9 go to wave (job % 4).
         // (2) the 8x8 blocks on the diagonal, one (i, j) pair per thread over all channels: gamma_i/gamma_j <= 1 directly.
 #pragma unroll
-        for (int jb = 0; jb < 3; ++jb) {
+        for (int jb = 0; jb < 2; ++jb) {
             const int job = wave + 4 * jb;
-            if (job >= 10) break;
-            int ti, tj, e_row; bool a_ok, b_ok;
-            if (job < 6) {
-                ti = job < 1 ? 1 : (job < 3 ? 2 : 3);
-                tj = job < 1 ? 0 : (job < 3 ? job - 1 : job - 3);
-                e_row = 16 * tj + 15; a_ok = true; b_ok = true;
-            } else {
-                ti = tj = job - 6;
-                e_row = 16 * ti + 7; a_ok = r >= 8; b_ok = r < 8;
-            }
-            const float* gi = Gs + (16 * ti + r) * LD;
-            const float* gj = Gs + (16 * tj + r) * LD;
-            const float* ge = Gs + e_row * LD;
-            const E* ki = Kp + (16 * ti + r) * LE;
-            const E* qi = Qp + (16 * ti + r) * LE;
-            const E* kj = Kp + (16 * tj + r) * LE;
+            int ja, jbr, ea, eb;
+            job_rows(job, ja, jbr, ea, eb);
+            const float* gi = Gs + ja * LD;
+            const float* gj = Gs + jbr * LD;
+            const float* gea = Gs + ea * LD;
+            const float* geb = Gs + eb * LD;
+            const E* ki = Kp + ja * LE;
+            const E* qi = Qp + ja * LE;
+            const E* kj = Kp + jbr * LE;
             for (int kp = 0; kp < CH / 32; ++kp) {
                 floatx4 ka[2], qa[2], kbv[2];
 #pragma unroll
                 for (int blk = 0; blk < 2; ++blk) {
                     const int c = 32 * kp + 16 * blk + 4 * g;
-                    const floatx4 gev = ld4f(ge + c), giv = ld4f(gi + c), gjv = ld4f(gj + c);
+                    const floatx4 geav = ld4f(gea + c), gebv = ld4f(geb + c), giv = ld4f(gi + c), gjv = ld4f(gj + c);
                     const floatx4 kiv = ld4e(ki + c), qiv = ld4e(qi + c), kjv = ld4e(kj + c);
 #pragma unroll
                     for (int x = 0; x < 4; ++x) {
-                        const float up = a_ok ? __builtin_amdgcn_exp2f(giv[x] - gev[x]) : 0.f;      // gamma_i / gamma_e
-                        const float dn = b_ok ? __builtin_amdgcn_exp2f(gev[x] - gjv[x]) : 0.f;      // gamma_e / gamma_j
+                        const float up = __builtin_amdgcn_exp2f(giv[x] - geav[x]);      // gamma_i / gamma_e <= 1
+                        const float dn = __builtin_amdgcn_exp2f(gebv[x] - gjv[x]);      // gamma_e / gamma_j <= 1
                         ka[blk][x] = kiv[x] * up; qa[blk][x] = qiv[x] * up; kbv[blk][x] = kjv[x] * dn;
                     }
                 }
@@ -602,17 +610,21 @@ __global__ __launch_bounds__(256) void intra_diag_kernel(IntraDiagArgs<E> a)
     }
     __syncthreads();
 #pragma unroll
-    for (int jb = 0; jb < 3; ++jb) {
+    for (int jb = 0; jb < 2; ++jb) {
         const int job = wave + 4 * jb;
-        if (job >= 10) break;
-        int ti, tj;
-        if (job < 6) { ti = job < 1 ? 1 : (job < 3 ? 2 : 3); tj = job < 1 ? 0 : (job < 3 ? job - 1 : job - 3); }
-        else         { ti = tj = job - 6; }
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            const int il = 4 * g + e;                // row inside the tile; column inside the tile is r
-            if (job < 6 || (il >= 8 && r < 8)) {
-                const int i = 16 * ti + il, j = 16 * tj + r;
+            const int il = 4 * g + e;                // row inside the product tile; its column is r
+            int i, j; bool ok;
+            if (job < 6) {
+                const int ti = job < 1 ? 1 : (job < 3 ? 2 : 3);
+                const int tj = job < 1 ? 0 : (job < 3 ? job - 1 : job - 3);
+                i = 16 * ti + il; j = 16 * tj + r; ok = true;
+            } else {                                 // the two diagonal 8x8 blocks of the product
+                const int t = 2 * (job - 6) + (il >> 3);
+                i = 16 * t + 8 + (il & 7); j = 16 * t + (r & 7); ok = (il >> 3) == (r >> 3);
+            }
+            if (ok) {
                 Lm[i * kLdm + j] = beta_s[i] * tkk[jb][e];
                 Pm[i * kLdm + j] = tqk[jb][e] * rq_s[i];
             }
