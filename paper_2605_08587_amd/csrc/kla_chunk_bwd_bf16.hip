@@ -330,8 +330,8 @@ __global__ __launch_bounds__(64 * NW + 128) void bwd_sweep_bf16_kernel(BwdArgs<b
             const int i = lane + 64 * it;
             const int row = i / VPP, pv = i % VPP;
             if (row < clen) {
-                st16(o0 + (size_t)row * v_row + pv * 16, ld16(ost + row * ORB + pv * 16));
-                st16(o1 + (size_t)row * v_row + pv * 16, ld16(ost + C::OSB + row * ORB + pv * 16));
+                __builtin_nontemporal_store(ld16(ost + row * ORB + pv * 16), reinterpret_cast<u32x4*>(o0 + (size_t)row * v_row + pv * 16));
+                __builtin_nontemporal_store(ld16(ost + C::OSB + row * ORB + pv * 16), reinterpret_cast<u32x4*>(o1 + (size_t)row * v_row + pv * 16));
             }
         }
         char* ck = reinterpret_cast<char*>(REV ? a.ds_chk : a.s_chk) +
@@ -340,7 +340,7 @@ __global__ __launch_bounds__(64 * NW + 128) void bwd_sweep_bf16_kernel(BwdArgs<b
         for (int it = 0; it < C::CKB / 1024; ++it) {
             const int i = lane + 64 * it;
             const int cl = i / PPR, pp = i % PPR;        // column of the workgroup, physical piece
-            st16(ck + cl * (DK * 2) + ((pp ^ (cl & 7)) * 16), ld16(ckb + i * 16));
+            __builtin_nontemporal_store(ld16(ckb + i * 16), reinterpret_cast<u32x4*>(ck + cl * (DK * 2) + ((pp ^ (cl & 7)) * 16)));
         }
     };
 
@@ -750,8 +750,8 @@ __global__ __launch_bounds__(256, 2) void bwd_assemble_bf16_kernel(BwdArgs<bf16_
         for (int it = 0; it < 64 * PPR / 256; ++it) {
             const int i = tid + 256 * it, row = i / PPR, pc = i % PPR;
             if (row < clen) {
-                st16(qo + (size_t)row * kq_row + pc * 16, ld16(sq + row * ORQ + pc * 16));
-                st16(ko + (size_t)row * kq_row + pc * 16, ld16(sk + row * ORQ + pc * 16));
+                __builtin_nontemporal_store(ld16(sq + row * ORQ + pc * 16), reinterpret_cast<u32x4*>(qo + (size_t)row * kq_row + pc * 16));
+                __builtin_nontemporal_store(ld16(sk + row * ORQ + pc * 16), reinterpret_cast<u32x4*>(ko + (size_t)row * kq_row + pc * 16));
             }
         }
     }
