@@ -530,9 +530,11 @@ __global__ __launch_bounds__(256) void intra_diag_kernel(IntraDiagArgs<E> a)
                         kp[i] = kf[i] * up; qp[i] = qf[i] * (up * rq_s[row]); kt[i] = kf[i] * __builtin_amdgcn_exp2f(gl - gi);
                     }
                     const size_t off = (size_t)row * row_stride + piece * EPP;
-                    *reinterpret_cast<uint4*>(kpo + off) = pack(kp);
-                    *reinterpret_cast<uint4*>(qpo + off) = pack(qp);
-                    *reinterpret_cast<uint4*>(kto + off) = pack(kt);
+                    typedef uint32_t u32x4n __attribute__((ext_vector_type(4)));
+                    auto nts = [](E* p, uint4 v) { const u32x4n w = {v.x, v.y, v.z, v.w}; __builtin_nontemporal_store(w, reinterpret_cast<u32x4n*>(p)); };
+                    nts(kpo + off, pack(kp));
+                    nts(qpo + off, pack(qp));
+                    nts(kto + off, pack(kt));
                 }
             }
         }
