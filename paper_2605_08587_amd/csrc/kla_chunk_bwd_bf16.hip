@@ -43,10 +43,15 @@ struct SweepCfg16 {
                          OFF_EG = OFF_V + 64 * VRW, STAGE = OFF_EG + (REV ? 1024 : 768);
     static constexpr int ORB = NW <= 2 ? 96 : 160;       // row stride of a staging tile (see the forward kernel)
     static constexpr int OSB = 64 * ORB;
-    static constexpr int CKB = SLW * DK * 2;             // the workgroup's part of a checkpoint, staged for the store wave
-    static constexpr int NST = (3 * STAGE + 4 * OSB + 2 * CKB <= 160 * 1024) ? 3 : 2;   // LDS ring depth
-    static constexpr int OFF_CK = NST * STAGE + 4 * OSB;
-    static constexpr int LDS = OFF_CK + 2 * CKB;         // two staged tiles and a checkpoint per chunk, two parities
+    // Forward: two staged tiles and the workgroup's part of the checkpoint per chunk, in two parities, all written out by
+    // the store wave.  Reverse: a stage also holds Q, M^T and P^T, and what decides its speed is a ring of three stages
+    // (the copies of a chunk then have two visits to arrive): the staging tiles get one parity only (a counter in LDS
+    // tells the compute waves that the store wave has read them) and the checkpoint is stored by the compute waves.
+    static constexpr int NPAR = REV ? 1 : 2;
+    static constexpr int CKB = REV ? 0 : SLW * DK * 2;
+    static constexpr int NST = (3 * STAGE + 2 * NPAR * OSB + 2 * CKB <= 160 * 1024) ? 3 : 2;   // LDS ring depth
+    static constexpr int OFF_CK = NST * STAGE + 2 * NPAR * OSB;
+    static constexpr int LDS = OFF_CK + 2 * CKB;
     static constexpr int NDMA = (REV ? 2 : 1) * NKB + NTB + NVB + 1;
     static_assert(LDS <= 160 * 1024 && NDMA < 64, "LDS budget of a gfx950 CU; 6-bit vmcnt");
 };
@@ -172,7 +177,7 @@ __global__ __launch_bounds__(64 * NW + 128) void bwd_sweep_bf16_kernel(BwdArgs<b
     auto stage_quad = [&](u32x2 ob, char* dst) { *reinterpret_cast<u32x2*>(dst) = quad_transpose4x4(ob, q_lo, psel); };
 
     // ---- one chunk for this wave's 16 columns -----------------------------------------------------------
-    auto compute = [&](const char* st, char* ost, char* ckb, int c) {
+    auto compute = [&](const char* st, char* ost, char* ckb, int c, int vis) {
         const char* pS = st + lane * 16;
         const char* pV = st + C::OFF_V + oV;
         const char* pG = st + C::OFF_EG + 16 * g;
@@ -192,14 +197,24 @@ __global__ __launch_bounds__(64 * NW + 128) void bwd_sweep_bf16_kernel(BwdArgs<b
         for (int kt = 0; kt < KB; ++kt) { Sq[kt] = to_quad(S[kt]); S[kt] = S[kt] * gC; }
         if (store) {
             // checkpoint, transposed ([column][feature]): features 32 kp + 8 g .. + 7 of this lane's column are 16
-            // contiguous bytes.  Staged in LDS for the store wave; the 16-byte pieces of a column are XORed with the
-            // column so that the eight lanes a 128-bit write serves per cycle fall into different banks.
-            const int cl = 16 * wave + r;
-            char* ck = ckb + cl * (DK * 2);
+            // contiguous bytes.
+            if constexpr (C::CKB > 0) {
+                // staged in LDS for the store wave; the 16-byte pieces of a column are XORed with the column so that the
+                // eight lanes a 128-bit write serves per cycle fall into different banks
+                const int cl = 16 * wave + r;
+                char* ck = ckb + cl * (DK * 2);
 #pragma unroll
-            for (int kp = 0; kp < KP; ++kp) {
-                const u32x4 w = {Sq[2 * kp].x, Sq[2 * kp].y, Sq[2 * kp + 1].x, Sq[2 * kp + 1].y};
-                st16(ck + (((4 * kp + g) ^ (cl & 7)) * 16), w);
+                for (int kp = 0; kp < KP; ++kp) {
+                    const u32x4 w = {Sq[2 * kp].x, Sq[2 * kp].y, Sq[2 * kp + 1].x, Sq[2 * kp + 1].y};
+                    st16(ck + (((4 * kp + g) ^ (cl & 7)) * 16), w);
+                }
+            } else {
+                bf16_t* ck = (REV ? a.ds_chk : a.s_chk) + (((size_t)(ch0 + c) * a.H + h) * a.dv_dim + col) * DK + 8 * g;
+#pragma unroll
+                for (int kp = 0; kp < KP; ++kp) {
+                    const u32x4 w = {Sq[2 * kp].x, Sq[2 * kp].y, Sq[2 * kp + 1].x, Sq[2 * kp + 1].y};
+                    __builtin_nontemporal_store(w, reinterpret_cast<u32x4*>(ck + 32 * kp));
+                }
             }
         }
 
@@ -290,6 +305,13 @@ __global__ __launch_bounds__(64 * NW + 128) void bwd_sweep_bf16_kernel(BwdArgs<b
 #pragma unroll
             for (int t = 0; t < KB; ++t) ktslot(t, 1, C::OFF_Q, kt[1][t][0], kt[1][t][1]);
             u32x2 gdOq[4], gdXq[4];
+            if constexpr (C::NPAR == 1) {
+                // one staging parity: the store wave must have read the tiles of the previous visit (it does so right
+                // after the barrier, a whole visit ago; the wait is a formality, and bounded)
+                for (int spin = 0; *reinterpret_cast<const volatile int*>(lds + NST * C::STAGE + 64) < vis - 1 && spin < (1 << 15); ++spin)
+                    __builtin_amdgcn_s_sleep(1);
+                asm volatile("" ::: "memory");
+            }
 #pragma unroll
             for (int it = 0; it < 4; ++it) {
                 const floatx4 dx = Y[it] * ld_f4(pG + 512 + 64 * it);           // dV = B Y
@@ -334,19 +356,25 @@ __global__ __launch_bounds__(64 * NW + 128) void bwd_sweep_bf16_kernel(BwdArgs<b
                 __builtin_nontemporal_store(ld16(ost + C::OSB + row * ORB + pv * 16), reinterpret_cast<u32x4*>(o1 + (size_t)row * v_row + pv * 16));
             }
         }
-        char* ck = reinterpret_cast<char*>(REV ? a.ds_chk : a.s_chk) +
-                   (((size_t)(ch0 + c) * a.H + h) * a.dv_dim + slice * SLW) * (DK * 2);
+        if constexpr (C::CKB > 0) {
+            char* ck = reinterpret_cast<char*>(REV ? a.ds_chk : a.s_chk) +
+                       (((size_t)(ch0 + c) * a.H + h) * a.dv_dim + slice * SLW) * (DK * 2);
 #pragma unroll
-        for (int it = 0; it < C::CKB / 1024; ++it) {
-            const int i = lane + 64 * it;
-            const int cl = i / PPR, pp = i % PPR;        // column of the workgroup, physical piece
-            __builtin_nontemporal_store(ld16(ckb + i * 16), reinterpret_cast<u32x4*>(ck + cl * (DK * 2) + ((pp ^ (cl & 7)) * 16)));
+            for (int it = 0; it < C::CKB / 1024; ++it) {
+                const int i = lane + 64 * it;
+                const int cl = i / PPR, pp = i % PPR;        // column of the workgroup, physical piece
+                __builtin_nontemporal_store(ld16(ckb + i * 16), reinterpret_cast<u32x4*>(ck + cl * (DK * 2) + ((pp ^ (cl & 7)) * 16)));
+            }
         }
     };
 
     char* ost0 = lds + NST * C::STAGE;
-    char* ost1 = ost0 + 2 * C::OSB;
+    char* ost1 = C::NPAR == 2 ? ost0 + 2 * C::OSB : ost0;
     char* ckb0 = lds + C::OFF_CK;
+    // last visit whose staged tiles the store wave has read (one staging parity only); in the padding of the first
+    // staging row (a row holds at most 64 of its ORB = 96 bytes)
+    int* oflag = reinterpret_cast<int*>(ost0 + 64);
+    if (C::NPAR == 1 && tid == 0) *oflag = -1;
     // chunks are visited in the order i = 0 .. nch-1; the backward sweep starts at the last chunk
     auto chunk_of = [&](int i) { return REV ? nch - 1 - i : i; };
 
@@ -358,6 +386,10 @@ __global__ __launch_bounds__(64 * NW + 128) void bwd_sweep_bf16_kernel(BwdArgs<b
         for (int i = 0; i < nch; ++i) {
             __syncthreads();
             if (store) write_out(chunk_of(i), (i & 1) ? ost1 : ost0, ckb0 + (i & 1) * C::CKB);
+            if constexpr (C::NPAR == 1) {
+                asm volatile("" ::: "memory");
+                if (lane == 0) *reinterpret_cast<volatile int*>(oflag) = i;      // behind the reads above, in order
+            }
         }
         return;
     }
@@ -386,7 +418,7 @@ __global__ __launch_bounds__(64 * NW + 128) void bwd_sweep_bf16_kernel(BwdArgs<b
     for (int i = 0; i < nch; ++i) {
         const int c = chunk_of(i);
         char* ost = (i & 1) ? ost1 : ost0;
-        compute(lds + scur * C::STAGE, ost, ckb0 + (i & 1) * C::CKB, c);
+        compute(lds + scur * C::STAGE, ost, ckb0 + (i & 1) * C::CKB, c, i);
         __syncthreads();
         scur = (scur + 1 == NST) ? 0 : scur + 1;
     }
