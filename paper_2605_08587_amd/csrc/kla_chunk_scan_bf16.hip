@@ -77,6 +77,12 @@ struct Cfg {
     static constexpr int OFF_REC = NST * STAGE + 2 * OSB, OFF_HST = OFF_REC + 2 * RECB, OFF_HSP = OFF_HST + 2 * HSCR_T;   // FU only
     // copy instructions per chunk (+1: decay factors)
     static constexpr int NDMA = FU ? NVB : (DG ? 3 : 2) * NKB + NTB + NVB + 1 + (DG ? 1 : 0);
+    // Split schedule of a two-stage ring (diagonal gating at d_k = 128, whose stage holds three K-sized tiles): a chunk's
+    // copies go out in two halves, each a full step before its first use, with a second barrier in the middle of the
+    // step between them.  N_EARLY / N_LATE: copy instructions of the two halves.
+    static constexpr bool SPLIT = DG && NST == 2;
+    static constexpr int N_EARLY = NKB + NVB + NTB / 2 + 2, N_LATE = 2 * NKB + NTB / 2;
+    static_assert(!SPLIT || (N_EARLY + N_LATE == NDMA && N_EARLY < 64 && N_LATE < 64), "halves of the split schedule");
     // waves of a workgroup: compute waves, then (fused) two T-side helpers, the copy wave, one wave that only keeps the
     // barriers company - so that the two P-side helpers after it land on the SIMDs of the T-side ones - and those two
     static constexpr int NWAVES = NW + (FU ? 6 : 1);
@@ -664,53 +670,62 @@ __global__ __launch_bounds__(64 * NW + (FU ? 384 : 64)) void scan_bf16_kernel(Sc
     const bool q_lo = (r & 3) < 2;                       // lane sits in the upper half of its quad's 4x4 block
     const uint32_t psel = (r & 1) ? 0x03020706u : 0x05040100u;   // byte selectors of the 2x2 step (see below)
 
-    // ---- global -> LDS copy of everything chunk c needs except the decay factors ---------------------
-    auto issue = [&](int c, char* st) {
+    // ---- global -> LDS copy of what chunk c needs ---------------------------------------------------
+    // part 0: everything; parts 1 and 2: the two halves of the split schedule (two-stage ring, see the copy wave):
+    // 1 = what a chunk step needs first (K, the V slice, T', the vectors), 2 = the rest (Q, the second K tile, P).
+    // One tile after the other: the K, Q and second-K rows of one token sit at the same offset of three arrays, and
+    // requests for them issued back to back meet in the same memory channel.
+    auto issue = [&](int c, char* st, auto part_c) {
+        constexpr int part = decltype(part_c)::value;
+        constexpr bool early = part != 2, late = part != 1;
         const int clen = min(64, len - 64 * c);
-        const char* kc = kbase + (size_t)(64 * c) * kq_row;
-        const char* qc = qbase + (size_t)(64 * c) * kq_row;
-        const char* vc = vbase + (size_t)(64 * c) * v_row;
-        const char* tc = tpbase + (size_t)c * a.H * REC;
-        if (clen == 64) {
-            if constexpr (!FU) {                         // fused mode: the helper waves bring K and Q
+        auto tile = [&](const char* src, char* dst) {    // src: the chunk's first row of a [tokens][H][d_k] array
+            if (clen == 64) {
                 static_for<C::NKB>([&](auto i) {
                     const int b = i;
-                    const size_t o = (size_t)(b * RPB) * kq_row;
-                    const int lo = gk[b % NGK];
-                    dma16(kc + o, lo, st + b * 1024);
-                    dma16(qc + o, lo, st + C::OFF_Q + b * 1024);
-                    if constexpr (DG) dma16(k2base + (size_t)(64 * c) * kq_row + o, lo, st + C::OFF_K2 + b * 1024);
+                    dma16(src + (size_t)(b * RPB) * kq_row, gk[b % NGK], dst + b * 1024);
                 });
-            }
-            static_for<C::NVB>([&](auto i) {
-                const int b = i;
-                dma16(vc + (size_t)(b * RPV) * v_row, gv, st + C::OFF_V + b * 1024);
-            });
-        } else {                                         // ragged last chunk: clamp the row
-            if constexpr (!FU) {
+            } else {                                     // ragged last chunk: clamp the row
                 static_for<C::NKB>([&](auto i) {
                     const int b = i;
                     const int row = b * RPB + lrow;
-                    const int lo = min(row, clen - 1) * (int)kq_row + ((pcol ^ swz_piece<DK>(row)) * 16);
-                    dma16(kc, lo, st + b * 1024);
-                    dma16(qc, lo, st + C::OFF_Q + b * 1024);
-                    if constexpr (DG) dma16(k2base + (size_t)(64 * c) * kq_row, lo, st + C::OFF_K2 + b * 1024);
+                    dma16(src, min(row, clen - 1) * (int)kq_row + ((pcol ^ swz_piece<DK>(row)) * 16), dst + b * 1024);
                 });
             }
-            static_for<C::NVB>([&](auto i) {
-                const int b = i;
-                const int row = b * RPV + lane / VPP;
-                dma16(vc, min(row, clen - 1) * (int)v_row + (lane % VPP) * 16, st + C::OFF_V + b * 1024);
-            });
+        };
+        if constexpr (!FU) {                             // fused mode: the helper waves bring K and Q
+            if constexpr (early) tile(kbase + (size_t)(64 * c) * kq_row, st);
+            if constexpr (late) {
+                tile(qbase + (size_t)(64 * c) * kq_row, st + C::OFF_Q);
+                if constexpr (DG) tile(k2base + (size_t)(64 * c) * kq_row, st + C::OFF_K2);
+            }
+        }
+        if constexpr (early) {
+            const char* vc = vbase + (size_t)(64 * c) * v_row;
+            if (clen == 64) {
+                static_for<C::NVB>([&](auto i) {
+                    const int b = i;
+                    dma16(vc + (size_t)(b * RPV) * v_row, gv, st + C::OFF_V + b * 1024);
+                });
+            } else {
+                static_for<C::NVB>([&](auto i) {
+                    const int b = i;
+                    const int row = b * RPV + lane / VPP;
+                    dma16(vc, min(row, clen - 1) * (int)v_row + (lane % VPP) * 16, st + C::OFF_V + b * 1024);
+                });
+            }
         }
         if constexpr (!FU) {
-            static_for<C::NTB>([&](auto i) {
-                const int b = i;
-                dma16(tc + b * 1024, lane * 16, st + C::OFF_T + b * 1024);
+            const char* tc = tpbase + (size_t)c * a.H * REC;
+            static_for<C::NTB>([&](auto i) {             // T' is the first half of the record's tile area, P the second
+                constexpr int b = decltype(i)::value;
+                if constexpr (b < C::NTB / 2 ? early : late) dma16(tc + b * 1024, lane * 16, st + C::OFF_T + b * 1024);
             });
-            if (lane < 48) dma16(tc + 2 * C::TPB, lane * 16, st + C::OFF_EG);   // gamma_i | gamma_C/gamma_i | gamma_i/||q_i||: 768 bytes
+            if constexpr (early) {
+                if (lane < 48) dma16(tc + 2 * C::TPB, lane * 16, st + C::OFF_EG);   // gamma_i | gamma_C/gamma_i | gamma_i/||q_i||: 768 bytes
+            }
         }
-        if constexpr (DG) {
+        if constexpr (DG && early) {
             if (lane < DK / 4) dma16(gcbase + (size_t)c * a.H * DK * 4, lane * 16, st + C::OFF_GC);   // gamma_C per channel
         }
     };
@@ -773,6 +788,8 @@ __global__ __launch_bounds__(64 * NW + (FU ? 384 : 64)) void scan_bf16_kernel(Sc
         u32x4 tsl[kTriPairs];
 #pragma unroll
         for (int i = 0; i < kTriPairs; ++i) tsl[i] = ld16(pS + C::R_T + i * 1024);
+        // split schedule: Q, the second K tile and P of this chunk are guaranteed only behind this barrier
+        if constexpr (C::SPLIT) __syncthreads();
         u32x4 qa[2][4];
 #pragma unroll
         for (int it = 0; it < 4; ++it) qa[0][it] = kslot(it, 0, C::OFF_Q);
@@ -970,11 +987,37 @@ __global__ __launch_bounds__(64 * NW + (FU ? 384 : 64)) void scan_bf16_kernel(Sc
         }
     }
 
+    if constexpr (C::SPLIT) {
+        if (wave == C::W_COPY) {
+            // ---- the copy wave, split schedule.  With two stages a chunk's copies cannot start before the step in
+            // which the chunk before it is computed; issued and awaited in one piece they would have to be issued and
+            // to land, one after the other, within that step (measured: 2.2 us for the 66 KB, against 1.2 us of
+            // compute).  In two halves, each has a full step: the first half of chunk c + 1 goes out at the start of
+            // step c and is awaited at its end; the second half goes out behind the barrier in the middle of step c
+            // and is awaited before the middle barrier of step c + 1.  The stage they fill was left by chunk c - 1 at
+            // the end of its step.  Copies retire in order, so "all but the last n" is a wait on the counter.
+            if (nch > 0) {
+                issue(0, lds, IntC<1>());
+                issue(0, lds, IntC<2>());
+                wait_vmcnt<C::N_LATE>();                 // first half of chunk 0
+            }
+            __syncthreads();
+            for (int c = 0; c < nch; ++c) {
+                const bool ahead = c + 1 < nch;
+                char* nx = lds + ((c + 1) & 1) * C::STAGE;
+                if (ahead) { issue(c + 1, nx, IntC<1>()); wait_vmcnt<C::N_EARLY>(); } else wait_vmcnt<0>();   // second half of chunk c
+                __syncthreads();                         // middle of step c
+                if (ahead) { issue(c + 1, nx, IntC<2>()); wait_vmcnt<C::N_LATE>(); } else wait_vmcnt<0>();    // first half of chunk c + 1
+                __syncthreads();                         // end of step c
+            }
+            return;
+        }
+    }
     if (wave == C::W_COPY) {
         // ---- the copy wave: keeps chunks c+1 .. c+NST-1 on their way while chunk c is computed ---------
 #pragma unroll
         for (int p = 0; p < NST - 1; ++p)
-            if (p < nch) issue(p, lds + p * C::STAGE);
+            if (p < nch) issue(p, lds + p * C::STAGE, IntC<0>());
         if constexpr (FU) __syncthreads();               // step -2
         if (NST == 3 && nch > 1) wait_vmcnt<(NST == 3 ? C::NDMA : 0)>(); else wait_vmcnt<0>();      // chunk 0 has landed
         __syncthreads();
@@ -982,7 +1025,7 @@ __global__ __launch_bounds__(64 * NW + (FU ? 384 : 64)) void scan_bf16_kernel(Sc
         for (int c = 0; c < nch; ++c) {
             const bool ahead = c + NST - 1 < nch;
             // the stage being refilled was read by chunk c-1, which every wave finished before the last barrier
-            if (ahead) issue(c + NST - 1, lds + spre * C::STAGE);
+            if (ahead) issue(c + NST - 1, lds + spre * C::STAGE, IntC<0>());
             // Copies retire in order and this wave issues nothing else: all but the NDMA just issued (when
             // NST = 3) have landed once the counter is down to NDMA, i.e. chunk c+1 is complete.
             if (NST == 3 && ahead) wait_vmcnt<(NST == 3 ? C::NDMA : 0)>(); else wait_vmcnt<0>();
