@@ -293,7 +293,7 @@ def test_diag_entry_points_validate():
     expect = r256(n_ch * (2 * 6144 + 768))
     expect = r256(expect + n_ch * 512)
     expect = r256(expect + 4)
-    expect += 3 * r256(N * T * H * dk * 2) + r256(n_ch * dk * 4)
+    expect += 3 * (r256(N * T * H * dk * 2) + 256) + r256(n_ch * dk * 4)   # the three arrays are 256 bytes out of step
     assert lib.kla_chunk_fwd_diag_workspace_bytes(N, T, H, dk, dv, 64, kla.KLA_BF16, None, 0) == expect
     dec = lambda **o: lib.kla_decode_step_diag(*[{**dict(q=0x1000, k=0x2000, v=0x3000, la=0x4000, eta=0x5000, eps=1e-6,
                                                         S=0x6000, o=0x7000, B=2, H=2, dk=128, dv=128, dt=kla.KLA_BF16,
