@@ -78,16 +78,17 @@ struct Cfg {
     // copy instructions per chunk (+1: decay factors)
     static constexpr int NDMA = FU ? NVB : (DG ? 3 : 2) * NKB + NTB + NVB + 1 + (DG ? 1 : 0);
     // Split schedule of a two-stage ring (diagonal gating at d_k = 128, whose stage holds three K-sized tiles): a chunk's
-    // copies go out in two halves, each a full step before its first use, with a second barrier in the middle of the
-    // step between them.  N_EARLY / N_LATE: copy instructions of the two halves.
+    // copies go out in two parts, each a full step before its first use, with a second barrier in the step between
+    // them.  N_FIRST, N_REST: copy instructions of the two parts.
     static constexpr bool SPLIT = DG && NST == 2;
-    static constexpr int N_EARLY = NKB + NVB + NTB / 2 + 2, N_LATE = 2 * NKB + NTB / 2;
-    static_assert(!SPLIT || (N_EARLY + N_LATE == NDMA && N_EARLY < 64 && N_LATE < 64), "halves of the split schedule");
-    // waves of a workgroup: compute waves, then (fused) two T-side helpers, the copy wave, one wave that only keeps the
-    // barriers company - so that the two P-side helpers after it land on the SIMDs of the T-side ones - and those two
-    static constexpr int NWAVES = NW + (FU ? 6 : 1);
+    static constexpr int N_FIRST = NKB + NVB + NTB / 2 + 2, N_REST = 2 * NKB + NTB / 2;
+    static_assert(!SPLIT || (N_FIRST + N_REST == NDMA && N_FIRST < 64 && N_REST < 64), "parts of the split schedule; 6-bit vmcnt");
+    // waves of a workgroup: compute waves, then the copy wave and the wave that writes the outputs; fused: compute
+    // waves, two T-side helpers, the copy wave, the write-out wave - placed so that the two P-side helpers after it land
+    // on the SIMDs of the T-side ones - and those two
+    static constexpr int NWAVES = NW + (FU ? 6 : 2);
     static constexpr int W_COPY = FU ? NW + 2 : NW;
-    static constexpr int W_P = NW + 4, W_IDLE = NW + 3;
+    static constexpr int W_P = NW + 4, W_IDLE = FU ? NW + 3 : NW + 1;
     static_assert(LDS <= 160 * 1024 && (NST != 3 || NDMA < 64), "LDS budget of a gfx950 CU; 6-bit vmcnt (counted waits only with three stages)");
     static_assert(!FU || NST == 3, "fused mode is laid out for the three-stage ring");
 };
@@ -590,7 +591,7 @@ struct PHelper : HelperBase<DK> {
 // the state update, the records carry unit decay vectors and the state rows decay by a.gc_vec (see intra_diag_kernel).
 // FU: fused mode, see the top of the file; a.wsT / a.wsP / a.wsG are not used, a.log_alpha / a.eta / a.eps are.
 template <int DK, int NW, bool NQ, bool DG = false, bool FU = false>
-__global__ __launch_bounds__(64 * NW + (FU ? 384 : 64)) void scan_bf16_kernel(ScanArgs<bf16_t> a)
+__global__ __launch_bounds__((64 * Cfg<DK, NW, DG, FU>::NWAVES)) void scan_bf16_kernel(ScanArgs<bf16_t> a)
 {
     typedef Cfg<DK, NW, DG, FU> C;
     constexpr int NTH = C::NTH, KB = C::KB, KP = C::KP, SLW = C::SLW, RB = C::RB, PPR = C::PPR, RPB = C::RPB,
@@ -671,13 +672,13 @@ __global__ __launch_bounds__(64 * NW + (FU ? 384 : 64)) void scan_bf16_kernel(Sc
     const uint32_t psel = (r & 1) ? 0x03020706u : 0x05040100u;   // byte selectors of the 2x2 step (see below)
 
     // ---- global -> LDS copy of what chunk c needs ---------------------------------------------------
-    // part 0: everything; parts 1 and 2: the two halves of the split schedule (two-stage ring, see the copy wave):
-    // 1 = what a chunk step needs first (K, the V slice, T', the vectors), 2 = the rest (Q, the second K tile, P).
-    // One tile after the other: the K, Q and second-K rows of one token sit at the same offset of three arrays, and
-    // requests for them issued back to back meet in the same memory channel.
+    // part 0: everything; parts 1 and 2: the split schedule of a two-stage ring (see the copy wave): 1 = what a chunk
+    // step reads first (the K tile, the V slice, T', the vectors), 2 = the rest (Q, the second K tile, P).  One tile
+    // after the other: the K, Q and second-K rows of one token sit at the same offset of three arrays, and requests for
+    // them issued back to back meet in the same memory channel.
     auto issue = [&](int c, char* st, auto part_c) {
         constexpr int part = decltype(part_c)::value;
-        constexpr bool early = part != 2, late = part != 1;
+        constexpr bool first = part != 2, rest = part != 1;
         const int clen = min(64, len - 64 * c);
         auto tile = [&](const char* src, char* dst) {    // src: the chunk's first row of a [tokens][H][d_k] array
             if (clen == 64) {
@@ -693,14 +694,9 @@ __global__ __launch_bounds__(64 * NW + (FU ? 384 : 64)) void scan_bf16_kernel(Sc
                 });
             }
         };
-        if constexpr (!FU) {                             // fused mode: the helper waves bring K and Q
-            if constexpr (early) tile(kbase + (size_t)(64 * c) * kq_row, st);
-            if constexpr (late) {
-                tile(qbase + (size_t)(64 * c) * kq_row, st + C::OFF_Q);
-                if constexpr (DG) tile(k2base + (size_t)(64 * c) * kq_row, st + C::OFF_K2);
-            }
-        }
-        if constexpr (early) {
+        const char* tc = FU ? nullptr : tpbase + (size_t)c * a.H * REC;
+        if constexpr (!FU && first) tile(kbase + (size_t)(64 * c) * kq_row, st);   // fused mode: the helper waves bring K and Q
+        if constexpr (first) {
             const char* vc = vbase + (size_t)(64 * c) * v_row;
             if (clen == 64) {
                 static_for<C::NVB>([&](auto i) {
@@ -714,19 +710,26 @@ __global__ __launch_bounds__(64 * NW + (FU ? 384 : 64)) void scan_bf16_kernel(Sc
                     dma16(vc, min(row, clen - 1) * (int)v_row + (lane % VPP) * 16, st + C::OFF_V + b * 1024);
                 });
             }
-        }
-        if constexpr (!FU) {
-            const char* tc = tpbase + (size_t)c * a.H * REC;
-            static_for<C::NTB>([&](auto i) {             // T' is the first half of the record's tile area, P the second
-                constexpr int b = decltype(i)::value;
-                if constexpr (b < C::NTB / 2 ? early : late) dma16(tc + b * 1024, lane * 16, st + C::OFF_T + b * 1024);
-            });
-            if constexpr (early) {
+            if constexpr (!FU) {
+                static_for<C::NTB / 2>([&](auto i) {     // T': the first half of the record's tile area
+                    const int b = i;
+                    dma16(tc + b * 1024, lane * 16, st + C::OFF_T + b * 1024);
+                });
                 if (lane < 48) dma16(tc + 2 * C::TPB, lane * 16, st + C::OFF_EG);   // gamma_i | gamma_C/gamma_i | gamma_i/||q_i||: 768 bytes
             }
+            if constexpr (DG) {
+                if (lane < DK / 4) dma16(gcbase + (size_t)c * a.H * DK * 4, lane * 16, st + C::OFF_GC);   // gamma_C per channel
+            }
         }
-        if constexpr (DG && early) {
-            if (lane < DK / 4) dma16(gcbase + (size_t)c * a.H * DK * 4, lane * 16, st + C::OFF_GC);   // gamma_C per channel
+        if constexpr (rest) {
+            if constexpr (!FU) {
+                tile(qbase + (size_t)(64 * c) * kq_row, st + C::OFF_Q);
+                if constexpr (DG) tile(k2base + (size_t)(64 * c) * kq_row, st + C::OFF_K2);
+                static_for<C::NTB / 2>([&](auto i) {     // P: the second half
+                    const int b = C::NTB / 2 + i;
+                    dma16(tc + b * 1024, lane * 16, st + C::OFF_T + b * 1024);
+                });
+            }
         }
     };
 
@@ -901,8 +904,8 @@ __global__ __launch_bounds__(64 * NW + (FU ? 384 : 64)) void scan_bf16_kernel(Sc
             *reinterpret_cast<u32x2*>(ost + oO + 16 * it * ORB) = quad_transpose4x4(to_quad(o[it]), q_lo, psel);
     };
 
-    // The staged output tile of chunk c goes to memory 16 bytes per thread: by the compute waves themselves, or (fused
-    // mode) by the wave that has nothing else to do, so that the compute waves go straight on to the next chunk.
+    // The staged output tile of chunk c goes to memory 16 bytes per thread, by a wave that has nothing else to do, so
+    // that the compute waves go straight on to the next chunk (the write-out cost them 250 of a step's 2 800 cycles).
     auto write_out = [&](int c, const char* ost, int t_idx, auto n_thr) {
         constexpr int NT = decltype(n_thr)::value;
         const int clen = min(64, len - 64 * c);
@@ -992,22 +995,22 @@ __global__ __launch_bounds__(64 * NW + (FU ? 384 : 64)) void scan_bf16_kernel(Sc
             // ---- the copy wave, split schedule.  With two stages a chunk's copies cannot start before the step in
             // which the chunk before it is computed; issued and awaited in one piece they would have to be issued and
             // to land, one after the other, within that step (measured: 2.2 us for the 66 KB, against 1.2 us of
-            // compute).  In two halves, each has a full step: the first half of chunk c + 1 goes out at the start of
-            // step c and is awaited at its end; the second half goes out behind the barrier in the middle of step c
-            // and is awaited before the middle barrier of step c + 1.  The stage they fill was left by chunk c - 1 at
-            // the end of its step.  Copies retire in order, so "all but the last n" is a wait on the counter.
+            // compute).  In two parts, each has a full step: the first part of chunk c + 1 goes out at the start of
+            // step c and is awaited at its end; the second part goes out behind the barrier in step c and is awaited
+            // before that barrier of step c + 1.  The stage they fill was left by chunk c - 1 at the end of its step.
+            // Copies retire in order, so "all but the last n" is a wait on the counter.
             if (nch > 0) {
                 issue(0, lds, IntC<1>());
                 issue(0, lds, IntC<2>());
-                wait_vmcnt<C::N_LATE>();                 // first half of chunk 0
+                wait_vmcnt<C::N_REST>();                 // first part of chunk 0
             }
             __syncthreads();
             for (int c = 0; c < nch; ++c) {
                 const bool ahead = c + 1 < nch;
                 char* nx = lds + ((c + 1) & 1) * C::STAGE;
-                if (ahead) { issue(c + 1, nx, IntC<1>()); wait_vmcnt<C::N_EARLY>(); } else wait_vmcnt<0>();   // second half of chunk c
-                __syncthreads();                         // middle of step c
-                if (ahead) { issue(c + 1, nx, IntC<2>()); wait_vmcnt<C::N_LATE>(); } else wait_vmcnt<0>();    // first half of chunk c + 1
+                if (ahead) { issue(c + 1, nx, IntC<1>()); wait_vmcnt<C::N_FIRST>(); } else wait_vmcnt<0>();   // second part of chunk c
+                __syncthreads();                         // in step c, before the first read of Q
+                if (ahead) { issue(c + 1, nx, IntC<2>()); wait_vmcnt<C::N_REST>(); } else wait_vmcnt<0>();    // first part of chunk c + 1
                 __syncthreads();                         // end of step c
             }
             return;
@@ -1035,6 +1038,21 @@ __global__ __launch_bounds__(64 * NW + (FU ? 384 : 64)) void scan_bf16_kernel(Sc
         return;
     }
 
+    if constexpr (!FU) {
+        if (wave == C::W_IDLE) {
+            // ---- the write-out wave: behind the barrier that ends step c, chunk c is complete in the staging tile of
+            // its parity, which the compute waves write again only in step c + 2, behind the barrier this wave reaches
+            // after the write-out
+            __syncthreads();
+            for (int c = 0; c < nch; ++c) {
+                if constexpr (C::SPLIT) __syncthreads();
+                __syncthreads();
+                write_out(c, (c & 1) ? ost1 : ost0, lane, IntC<64>());
+            }
+            return;
+        }
+    }
+
     // ---- compute waves ---------------------------------------------------------------------------------
     if constexpr (FU) __syncthreads();                   // step -2
     __syncthreads();                                     // chunk 0 is in stage 0 (and its record in buffer 0)
@@ -1042,12 +1060,10 @@ __global__ __launch_bounds__(64 * NW + (FU ? 384 : 64)) void scan_bf16_kernel(Sc
     for (int c = 0; c < nch; ++c) {
         char* ost = (c & 1) ? ost1 : ost0;
         compute(lds + scur * C::STAGE, FU ? lds + C::OFF_REC + (c & 1) * C::RECB : lds + scur * C::STAGE, ost);
-        // One barrier per chunk: staged outputs before their write-out; chunk c+1's operands before their
-        // use; all reads of this stage before it is refilled next iteration; and the write-out of chunk
-        // c-1 (finished by every compute wave before it arrives here) before the staging tile of that
-        // parity is written again in chunk c+1.
+        // The barrier that ends a chunk step: staged outputs before their write-out; chunk c+1's operands before
+        // their use; all reads of this stage before it is refilled; and the write-out of chunk c-1 (finished by
+        // its wave before it arrives here) before the staging tile of that parity is written again in chunk c+1.
         __syncthreads();
-        if constexpr (!FU) write_out(c, ost, tid, IntC<NTH>());
         scur = (scur + 1 == NST) ? 0 : scur + 1;
     }
 
@@ -1073,16 +1089,16 @@ static hipError_t launch_dk(const ScanArgs<bf16_t>& a, int waves, hipStream_t st
     const bool nq = (a.opts & kOptNormalizeQ) != 0;
     switch (waves) {
         case 1:
-            if (nq) hipLaunchKernelGGL((scan_bf16_kernel<DK, 1, true>), grid, dim3(128), 0, st, a);
-            else    hipLaunchKernelGGL((scan_bf16_kernel<DK, 1, false>), grid, dim3(128), 0, st, a);
+            if (nq) hipLaunchKernelGGL((scan_bf16_kernel<DK, 1, true>), grid, dim3(64 * 3), 0, st, a);
+            else    hipLaunchKernelGGL((scan_bf16_kernel<DK, 1, false>), grid, dim3(64 * 3), 0, st, a);
             break;
         case 2:
-            if (nq) hipLaunchKernelGGL((scan_bf16_kernel<DK, 2, true>), grid, dim3(192), 0, st, a);
-            else    hipLaunchKernelGGL((scan_bf16_kernel<DK, 2, false>), grid, dim3(192), 0, st, a);
+            if (nq) hipLaunchKernelGGL((scan_bf16_kernel<DK, 2, true>), grid, dim3(64 * 4), 0, st, a);
+            else    hipLaunchKernelGGL((scan_bf16_kernel<DK, 2, false>), grid, dim3(64 * 4), 0, st, a);
             break;
         default:
-            if (nq) hipLaunchKernelGGL((scan_bf16_kernel<DK, 4, true>), grid, dim3(320), 0, st, a);
-            else    hipLaunchKernelGGL((scan_bf16_kernel<DK, 4, false>), grid, dim3(320), 0, st, a);
+            if (nq) hipLaunchKernelGGL((scan_bf16_kernel<DK, 4, true>), grid, dim3(64 * 6), 0, st, a);
+            else    hipLaunchKernelGGL((scan_bf16_kernel<DK, 4, false>), grid, dim3(64 * 6), 0, st, a);
             break;
     }
     return hipGetLastError();
@@ -1124,8 +1140,8 @@ static hipError_t launch_diag_dk(const ScanArgs<bf16_t>& a, int waves, hipStream
     const int n_chains = (a.n_seq > 0 ? a.n_seq : a.N) * a.H;
     if (n_chains == 0) return hipSuccess;
     const dim3 grid((unsigned)(((n_chains + 7) / 8) * 8 * (a.dv / (16 * waves))));
-    if (waves == 1) hipLaunchKernelGGL((scan_bf16_kernel<DK, 1, false, true>), grid, dim3(128), 0, st, a);
-    else            hipLaunchKernelGGL((scan_bf16_kernel<DK, 2, false, true>), grid, dim3(192), 0, st, a);
+    if (waves == 1) hipLaunchKernelGGL((scan_bf16_kernel<DK, 1, false, true>), grid, dim3(64 * 3), 0, st, a);
+    else            hipLaunchKernelGGL((scan_bf16_kernel<DK, 2, false, true>), grid, dim3(64 * 4), 0, st, a);
     return hipGetLastError();
 }
 hipError_t launch_scan_bf16_diag(const ScanArgs<bf16_t>& a, int dk, int waves, hipStream_t st)
