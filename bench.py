@@ -262,6 +262,15 @@ def main():
                     "mfma_bf16_TFLOPs": round(n_wg * 4 * iters * 8 * 16384 / (ms_mm * 1e-3) / 1e12, 1),
                     "note": "kla_debug_peak_probe: 1 GiB read once; 1 GiB read and written in place (non-temporal); "
                             "2048 workgroups of back-to-back 16x16x32 bf16 MFMA from registers"}
+        # the copy wave of the chunk kernels alone: 256 workgroups x 64 steps of n KiB per step (one LDS-DMA copy per KiB)
+        ring = {}
+        for n_kib, depth in ((16, 2), (32, 2), (48, 2), (60, 2), (16, 1), (32, 1), (48, 1), (60, 1)):
+            ms_rc = _events(torch, lambda: kla.kla_debug_peak_probe(3, big, None, iters=n_kib + 256 * (depth - 1)), 5, groups=5)
+            ring["%dKiB_depth%d" % (n_kib, depth)] = round(ms_rc * 1e3 / 64, 3)
+        measured["ring_copy_us_per_step"] = ring
+        measured["ring_copy_note"] = ("kla_debug_peak_probe kind 3: one workgroup per CU, one wave issuing n LDS-DMA copies of 1 KiB "
+                                      "per step (256-byte rows 2 KiB apart, shared by the four workgroups of a head) through a ring "
+                                      "one or two steps deep, a barrier per step; us per step")
         roofline["frac_of_measured_stream_read"] = round(achieved / measured["stream_read_GBps"], 4)
         mfma["frac_of_measured_mfma"] = round(tflops / measured["mfma_bf16_TFLOPs"], 4)
         del big, aux

@@ -336,6 +336,10 @@ int kla_debug_chunk_stage(const void *q, const void *k, const void *v,
  *   kind 1  read-only streaming of `bytes` at buf; aux receives bytes / 16384 floats.
  *   kind 2  dense bf16 matrix pipe: `bytes` workgroups of four waves, each wave `iters` rounds of eight
  *           independent 16x16x32 products (16384 flop each per wave); aux receives 256 floats per workgroup.
+ *   kind 3  the copy wave of the chunk kernels alone: 256 workgroups, 64 steps; per step one wave brings n copies of
+ *           1 KiB (256-byte rows 2 KiB apart; four workgroups of an XCD share the rows) from buf into LDS through a
+ *           ring one or two steps deep, one barrier per step.  iters = n + 256 (depth - 1), n one of 16, 32, 48, 60;
+ *           `bytes` = size of buf, at least n x 4 MiB (else KLA_ERR_WORKSPACE).  aux unused.
  */
 int kla_debug_peak_probe(int kind, void *buf, void *aux, size_t bytes, int iters, void *hip_stream);
 

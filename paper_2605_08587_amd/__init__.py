@@ -432,7 +432,8 @@ def kla_debug_intra_chunk(q, k, log_alpha, eta, eps, cu_seqlens=None, chunk=64):
 def kla_debug_peak_probe(kind, buf=None, aux=None, n=0, iters=0):
     """Measurement hook (kla_debug_peak_probe of the C ABI): kind 0 in-place streaming over the fp32 tensor `buf`
     (iters != 0: non-temporal), kind 1 read-only streaming of `buf` (aux: fp32, buf bytes / 16384 elements), kind 2 dense
-    bf16 matrix pipe on `n` workgroups x `iters` rounds (aux: fp32, 256 n elements)."""
+    bf16 matrix pipe on `n` workgroups x `iters` rounds (aux: fp32, 256 n elements), kind 3 the chunk kernels' copy wave
+    alone reading `buf` (iters = copies of 1 KiB per step + 256 (ring depth - 1))."""
     _dev(buf, aux)
     size = n if kind == 2 else buf.numel() * buf.element_size()
     if kind == 1 and (aux is None or aux.numel() * aux.element_size() < size // 4096):

@@ -739,8 +739,14 @@ int kla_debug_intra_chunk(const void* q, const void* k, const float* log_alpha, 
 
 int kla_debug_peak_probe(int kind, void* buf, void* aux, size_t bytes, int iters, void* hip_stream)
 {
-    if (kind < 0 || kind > 2 || iters < 0) return KLA_ERR_SHAPE;
-    if (kind == 2) {
+    if (kind < 0 || kind > 3 || iters < 0) return KLA_ERR_SHAPE;
+    if (kind == 3) {
+        const int ni = iters & 255, depth = 1 + (iters >> 8);
+        if ((ni != 16 && ni != 32 && ni != 48 && ni != 60) || depth > 2) return KLA_ERR_SHAPE;
+        if (!buf) return KLA_ERR_NULL;
+        if (!aligned16(buf)) return KLA_ERR_ALIGN;
+        if (bytes < (size_t)8 * 64 * ni * 4 * 2048) return KLA_ERR_WORKSPACE;
+    } else if (kind == 2) {
         if (bytes == 0 || bytes > 0x7fffffffu || iters == 0) return KLA_ERR_SHAPE;
         if (!aux) return KLA_ERR_NULL;
     } else {

@@ -371,3 +371,20 @@ def test_binding_refuses_wrong_shapes_and_dtypes():
         kla.kla_beta(mk(5, dk), mk(6, dtype=torch.float32), 1e-6)
     with pytest.raises(RuntimeError, match="GPU"):
         kla.kla_beta(mk(5, dk), mk(5, dtype=torch.float32), 1e-6)
+
+
+def test_peak_probe_validates():
+    """The measurement hook checks its arguments before it launches anything (no GPU needed for the error paths)."""
+    lib = kla.lib()
+    call = lambda kind, buf, aux, size, iters: lib.kla_debug_peak_probe(kind, buf, aux, size, iters, None)
+    assert call(4, 0x1000, None, 65536, 0) == E_SHAPE
+    assert call(0, None, None, 65536, 0) == E_NULL
+    assert call(0, 0x1000, None, 1000, 0) == E_SHAPE
+    assert call(1, 0x1000, None, 65536, 0) == E_NULL
+    assert call(2, None, None, 16, 4) == E_NULL
+    # kind 3: copies per step one of 16 / 32 / 48 / 60, ring depth 1 or 2, buffer of at least n x 4 MiB
+    assert call(3, 0x1000, None, 1 << 30, 17) == E_SHAPE
+    assert call(3, 0x1000, None, 1 << 30, 16 + 512) == E_SHAPE
+    assert call(3, None, None, 1 << 30, 16) == E_NULL
+    assert call(3, 0x1008, None, 1 << 30, 16) == E_ALIGN
+    assert call(3, 0x1000, None, (16 << 22) - 1, 16) == E_WS
