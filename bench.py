@@ -121,7 +121,7 @@ def main():
                          "of this command holds the benchmarked launches only)")
     ap.add_argument("--sections", default="all",
                     help="comma-separated secondary measurements to run beside the headline step: two_kernel, rotating, "
-                         "peaks, config3, config5, backward, backward_config3, diag, decode (default: all)")
+                         "peaks, fp32, config3, config5, backward, backward_config3, diag, decode (default: all)")
     ap.add_argument("--max-groups", type=int, default=0,
                     help="cap on the event groups per measurement (for rocprofv3 --pmc runs, which serialise every dispatch)")
     ap.add_argument("--copy-probe", action="store_true",
@@ -274,6 +274,24 @@ def main():
         roofline["frac_of_measured_stream_read"] = round(achieved / measured["stream_read_GBps"], 4)
         mfma["frac_of_measured_mfma"] = round(tflops / measured["mfma_bf16_TFLOPs"], 4)
         del big, aux
+
+    # ------------------------------------------------------------------ fp32 inputs: the element-type-generic kernels
+    fp32_path = None
+    if want("fp32"):
+        fp32_path = {"note": "fp32 q/k/v run the element-type-generic kernels (two-kernel form, fp32 MFMA and vector sums): "
+                             "the path that carries the 1e-4 parity bar, not tuned for speed"}
+        for name, cfg, shape in (("config1", kla_inputs.config(1), None), ("config2_shape", d, "fp32 copies of config 2's tensors")):
+            f = {n: cfg[n].float().cuda() for n in ("q", "k", "v")}
+            g = {n: cfg[n].cuda() for n in ("log_alpha", "eta")}
+            n1, t1, h1, k1, v1 = cfg["N"], cfg["T"], cfg["H"], cfg["dk"], cfg["dv"]
+            w32 = torch.empty(kla.kla_chunk_fwd_workspace_bytes(n1, t1, h1, k1, v1, torch.float32), dtype=torch.uint8, device="cuda")
+            o32 = torch.empty((n1, t1, h1, v1), dtype=torch.float32, device="cuda")
+            h32 = torch.empty((n1, h1, k1, v1), dtype=torch.float32, device="cuda")
+            fn32 = lambda: kla.kla_chunk_fwd(f["q"], f["k"], f["v"], g["log_alpha"], g["eta"], cfg["eps"], workspace=w32, out=o32, hT=h32)
+            ms32 = _events(torch, fn32, 5, groups=10)
+            fp32_path[name] = {"ms_per_call": round(ms32, 4), "tokens_per_s": round(n1 * t1 / (ms32 * 1e-3), 1),
+                               "workload": shape or "N=%d,H=%d,T=%d,dk=%d,dv=%d" % (n1, h1, t1, k1, v1)}
+            del f, w32, o32, h32
 
     # ------------------------------------------------------------------ secondary chunk workloads (not the headline)
     extra = None
@@ -487,7 +505,7 @@ def main():
             "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
             "config": {"workload": "config2: N=8,H=8,T=4096,dk=dv=128,chunk=64,bf16 q/k/v,fp32 gates+state",
                        "global_batch": N, "seq_len": T, "heads": H},
-            "roofline": roofline, "mfma": mfma, "measured_peaks": measured, "two_kernel_form": two, "rotating_inputs": rotating,
+            "roofline": roofline, "mfma": mfma, "measured_peaks": measured, "two_kernel_form": two, "fp32_path": fp32_path, "rotating_inputs": rotating,
             "other_chunk_workloads": extra, "backward": backward, "diagonal_gating": diag, "decode": decode,
             "cpu_baseline": cpu, "parity": parity, "clocks": {"start": clocks_start, "end": _clocks()}}
     print(json.dumps(line), flush=True)
