@@ -411,30 +411,25 @@ __global__ __launch_bounds__(256) void intra_diag_kernel(IntraDiagArgs<E> a)
     const E* qb = a.q + (size_t)tok0 * row_stride + (size_t)h * DK;
     const float* lb = a.log_alpha + (size_t)tok0 * row_stride + (size_t)h * DK;
 
-    // ---- phase 0: key and query norms over all channels -> beta, 1/||q|| (the rows are read again, pass by pass, below)
+    // ---- phase 0: the normalised read-out (Sec. 3.3) needs 1/||q_i|| over all channels before the first pass scales
+    //      Q; otherwise nothing is read ahead of the passes (the key norms are summed up pass by pass)
+    if (a.opts & kOptNormalizeQ) {
 #pragma unroll
-    for (int it = 0; it < 64 * PPR / 256; ++it) {
-        const int pi = tid + 256 * it;
-        const int row = pi / PPR, piece = pi % PPR;
-        uint4 kd = make_uint4(0, 0, 0, 0), qd = make_uint4(0, 0, 0, 0);
-        if (row < clen) {
-            kd = *reinterpret_cast<const uint4*>(kb + (size_t)row * row_stride + piece * EPP);
-            qd = *reinterpret_cast<const uint4*>(qb + (size_t)row * row_stride + piece * EPP);
+        for (int it = 0; it < 64 * PPR / 256; ++it) {
+            const int pi = tid + 256 * it;
+            const int row = pi / PPR, piece = pi % PPR;
+            uint4 qd = make_uint4(0, 0, 0, 0);
+            if (row < clen) qd = *reinterpret_cast<const uint4*>(qb + (size_t)row * row_stride + piece * EPP);
+            float qf0[EPP];
+            unpack(qd, qf0);
+            float sq = 0.f;
+#pragma unroll
+            for (int i = 0; i < EPP; ++i) sq += qf0[i] * qf0[i];
+#pragma unroll
+            for (int off = 1; off < PPR; off <<= 1) sq += __shfl_xor(sq, off, kWave);
+            if (piece == 0) rq_s[row] = sq > 0.f ? 1.0f / sqrtf(sq) : 0.f;
         }
-        float kf[EPP], qf0[EPP];
-        unpack(kd, kf);
-        unpack(qd, qf0);
-        float ss = 0.f, sq = 0.f;
-#pragma unroll
-        for (int i = 0; i < EPP; ++i) { ss += kf[i] * kf[i]; sq += qf0[i] * qf0[i]; }
-#pragma unroll
-        for (int off = 1; off < PPR; off <<= 1) { ss += __shfl_xor(ss, off, kWave); sq += __shfl_xor(sq, off, kWave); }
-        if (piece == 0) {
-            const float et = row < clen ? a.eta[(size_t)(tok0 + row) * a.H + h] : 0.f;
-            beta_s[row] = (a.opts & kOptGdnBeta) ? et : kaczmarz_beta(et, ss, a.eps);
-            rq_s[row] = (a.opts & kOptNormalizeQ) ? (sq > 0.f ? 1.0f / sqrtf(sq) : 0.f) : 1.f;
-        }
-    }
+    } else if (tid < 64) rq_s[tid] = 1.f;
     if (tid < 128) {                                 // unit decay vectors for the scan: g = 0, 1/||q|| = 1
         a.wsG[(size_t)blockIdx.x * 128 + tid] = tid < 64 ? 0.f : 1.f;
         float* dec = reinterpret_cast<float*>(reinterpret_cast<char*>(a.wsT) + (size_t)blockIdx.x * REC + 2 * ws_half_bytes<E>());
@@ -471,10 +466,13 @@ __global__ __launch_bounds__(256) void intra_diag_kernel(IntraDiagArgs<E> a)
         pi = 8 * b8 + ii; pj = 8 * b8 + p - (ii * (ii - 1)) / 2;
     }
 
+    float ksq[64 * PPH / 256];                       // this thread's share of ||k_row||^2, rows (tid + 256 it) / PPH
+#pragma unroll
+    for (int it = 0; it < 64 * PPH / 256; ++it) ksq[it] = 0.f;
     for (int pass = 0; pass < NPASS; ++pass) {
         const int c0 = pass * CH;                    // first channel of this pass
         if (pass > 0) __syncthreads();               // the previous pass has read its tables
-        // ---- phase 1: K, Q rows and log2 alpha of CH channels -> LDS ---------------------------------------------
+        // ---- phase 1: K, Q rows and log2 alpha of CH channels -> LDS (the squares of K summed for the key norms on the way)
 #pragma unroll
         for (int it = 0; it < 64 * PPH / 256; ++it) {
             const int x = tid + 256 * it;
@@ -486,6 +484,10 @@ __global__ __launch_bounds__(256) void intra_diag_kernel(IntraDiagArgs<E> a)
             }
             *reinterpret_cast<uint4*>(area + (size_t)(row * LE + piece * EPP) * sizeof(E)) = kd;
             *reinterpret_cast<uint4*>(area + TE + (size_t)(row * LE + piece * EPP) * sizeof(E)) = qd;
+            float kf[EPP];
+            unpack(kd, kf);
+#pragma unroll
+            for (int i = 0; i < EPP; ++i) ksq[it] += kf[i] * kf[i];
         }
 #pragma unroll
         for (int it = 0; it < 64 * CH / 4 / 256; ++it) {
@@ -601,6 +603,19 @@ __global__ __launch_bounds__(256) void intra_diag_kernel(IntraDiagArgs<E> a)
 #pragma unroll
                 for (int x = 0; x < 4; ++x) pdg += qiv[x] * kiv[x];
             }
+        }
+    }
+    // ---- beta of eq. (3) from the key norms (the PPH threads of a row sit in consecutive lanes)
+#pragma unroll
+    for (int it = 0; it < 64 * PPH / 256; ++it) {
+        const int x = tid + 256 * it;
+        const int row = x / PPH;
+        float ss = ksq[it];
+#pragma unroll
+        for (int off = 1; off < PPH; off <<= 1) ss += __shfl_xor(ss, off, kWave);
+        if (x % PPH == 0) {
+            const float et = row < clen ? a.eta[(size_t)(tok0 + row) * a.H + h] : 0.f;
+            beta_s[row] = (a.opts & kOptGdnBeta) ? et : kaczmarz_beta(et, ss, a.eps);
         }
     }
     __syncthreads();   // the tables are dead from here on; Lm, Pm, Tm overlay them
