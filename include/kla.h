@@ -213,8 +213,8 @@ int kla_decode_step_opts(const void *q, const void *k, const void *v,
  *   dh0         [n_states, H, dk, dv] fp32       out  or NULL if unwanted
  *   workspace   device scratch of at least kla_chunk_bwd_workspace_bytes(...) bytes, 256-byte aligned.
  *               It holds, per chunk and head, the incoming state and the gradient of the outgoing state
- *               (dk x dv each, in dt) and three [N, T, H, dv] arrays in dt, so it is much larger than the
- *               forward's: about (2 * dk * dv / 64 + 3 * dv) * sizeof(dt) bytes per token and head.
+ *               (dk x dv each, in dt) and three [N, T, H, dv] arrays in dt (two for bf16), so it is much larger
+ *               than the forward's: about (2 * dk * dv / 64 + 3 * dv) * sizeof(dt) bytes per token and head.
  *               For a small bf16 batch of long sequences it also holds the per-segment maps and states of the
  *               segment-parallel sweeps (as in kla_chunk_fwd).
  * Outputs must not alias inputs or each other.  Same error codes and conventions as kla_chunk_fwd;

@@ -258,9 +258,11 @@ int make_bwd_plan(int N, int T, int H, int dk, int dv, int chunk, int dt, const 
     p->off_C = round256(ch * (3 * half + 1280));
     p->off_S = round256(p->off_C + (size_t)(n_seq + 1) * sizeof(int32_t));
     p->off_dS = round256(p->off_S + states);
+    // the bf16 kernels do not keep U (their assembly forms it again from T' and X); the generic ones do
+    const size_t rows_u = (dt == KLA_BF16 && !p->base.tune.generic_bwd) ? 0 : rows;
     p->off_X = round256(p->off_dS + states);
     p->off_U = round256(p->off_X + rows);
-    p->off_Y = round256(p->off_U + rows);
+    p->off_Y = round256(p->off_U + rows_u);
     const int G = p->base.seg_G;
     const size_t maps = G > 1 ? (size_t)N * (G - 1) * H * dk * (dv + dk) * sizeof(float) : 0;
     const size_t segst = G > 1 ? (size_t)N * G * H * dk * dv * sizeof(float) : 0;

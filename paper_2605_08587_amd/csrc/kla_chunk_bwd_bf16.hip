@@ -268,10 +268,7 @@ __global__ __launch_bounds__(64 * NW + 128) void bwd_sweep_bf16_kernel(BwdArgs<b
             for (int t = 0; t < KB; ++t) ktslot(t, 1, 0, kt[1][t][0], kt[1][t][1]);
             u32x2 Udq[4];
 #pragma unroll
-            for (int it = 0; it < 4; ++it) {
-                Udq[it] = to_quad(U[it] * edv[it]);
-                stage_quad(to_quad(U[it]), ost + C::OSB + oO + 16 * it * ORB);
-            }
+            for (int it = 0; it < 4; ++it) Udq[it] = to_quad(U[it] * edv[it]);   // U itself is not kept: the assembly forms it again from T' and X
 #pragma unroll
             for (int t = 0; t < KB; ++t) mma_bf16(S[t], kt[0][t][0], kt[0][t][1], Udq[0], Udq[1]);
 #pragma unroll
@@ -346,14 +343,14 @@ __global__ __launch_bounds__(64 * NW + 128) void bwd_sweep_bf16_kernel(BwdArgs<b
         const int clen = min(64, len - 64 * c);
         const size_t off = (size_t)(t0 + 64L * c) * v_row + ((size_t)h * a.dv_dim + slice * SLW) * 2;
         char* o0 = reinterpret_cast<char*>(REV ? a.Y : a.X) + off;
-        char* o1 = reinterpret_cast<char*>(REV ? a.dv : a.U) + off;
+        char* o1 = reinterpret_cast<char*>(a.dv) + off;          // backward sweep only
 #pragma unroll
         for (int it = 0; it < VPP; ++it) {
             const int i = lane + 64 * it;
             const int row = i / VPP, pv = i % VPP;
             if (row < clen) {
                 __builtin_nontemporal_store(ld16(ost + row * ORB + pv * 16), reinterpret_cast<u32x4*>(o0 + (size_t)row * v_row + pv * 16));
-                __builtin_nontemporal_store(ld16(ost + C::OSB + row * ORB + pv * 16), reinterpret_cast<u32x4*>(o1 + (size_t)row * v_row + pv * 16));
+                if constexpr (REV) __builtin_nontemporal_store(ld16(ost + C::OSB + row * ORB + pv * 16), reinterpret_cast<u32x4*>(o1 + (size_t)row * v_row + pv * 16));
             }
         }
         if constexpr (C::CKB > 0) {
@@ -462,7 +459,7 @@ __global__ __launch_bounds__(256, 2) void bwd_assemble_bf16_kernel(BwdArgs<bf16_
     constexpr int RBA = 64, NAB = 4;                 // [64 tokens x 32 columns] slabs: 4 blocks of 16 rows of 64 bytes
     constexpr int TK = 64 * RB, TS = 32 * RB, NSB = TS / 1024, TA = 64 * RBA;
     constexpr int kLd = 68, MB = 64 * kLd * 4;
-    // first phase, two buffers of one 32-column slab each: S^T | dS'^T | dO | U | Y | X
+    // first phase, two buffers of one 32-column slab each: S^T | dS'^T | dO | U | Y | X (U is formed here, from T' and X)
     constexpr int OFF_S = 0, OFF_DS = TS, OFF_DO = 2 * TS, OFF_U = OFF_DO + TA, OFF_Y = OFF_U + TA, OFF_X = OFF_Y + TA;
     constexpr int SLAB = 2 * TS + 4 * TA;
     constexpr int PH1 = 2 * SLAB;
@@ -475,6 +472,7 @@ __global__ __launch_bounds__(256, 2) void bwd_assemble_bf16_kernel(BwdArgs<bf16_
     constexpr int ORQ = RB + 16;                     // row stride of the dq / dk staging tiles (over A o dP and D')
     static_assert(64 * ORQ <= MB, "staging tiles fit the fp32 matrices they replace");
     __shared__ __attribute__((aligned(1024))) char lds[BIG];
+    __shared__ __attribute__((aligned(1024))) char tp_s[kTriPairs * 1024];       // T' of the chunk, as the record holds it
     __shared__ __attribute__((aligned(16))) float eg_s[64], ed_s[64], beta_s[64], invden_s[64], rq_s[64], g_s[64], yx_s[64],
         dg_s[64], dbeta_s[64];
     __shared__ float red_s[8];
@@ -554,6 +552,14 @@ __global__ __launch_bounds__(256, 2) void bwd_assemble_bf16_kernel(BwdArgs<bf16_
         q1 = lds_read_tr(p + 16 * RB);
     };
 
+    // U = T' X is not read back from the forward sweep but formed again, slab by slab: the T' tile pairs of this wave's 16
+    // rows (A operands, copied from the record into LDS once), the X slab through the transposing read (B operands), the
+    // result put into the slab's U area in the layout a copied slab has.  Per lane: where its 8 bytes of an X row sit.
+    for (int i = wave; i < kTriPairs; i += 4) dma16(rec + i * 1024, lane * 16, tp_s + i * 1024);   // lands with the first slab
+    // (column tile 0; tile 1 is two 16-byte pieces further, i.e. the same offsets with bit 5 flipped)
+    const int xo = (4 * g + a4) * RBA + ((((c4 >> 1)) ^ ((2 * g + (a4 >> 1)) & 3)) * 16) + (c4 & 1) * 8;
+    const int urow = 16 * wave + 4 * g + (r & 3);            // after the 4x4 transposition a lane holds 4 columns of one row
+    const int uo = urow * RBA + ((((r >> 3)) ^ ((urow >> 1) & 3)) * 16) + ((r >> 2) & 1) * 8;
     floatx4 dQ[KB], dKr[KB], dKw[KB], dP[4], N1[4];
 #pragma unroll
     for (int ct = 0; ct < KB; ++ct) { dQ[ct] = floatx4{0.f, 0.f, 0.f, 0.f}; dKr[ct] = dQ[ct]; dKw[ct] = dQ[ct]; }
@@ -569,10 +575,8 @@ __global__ __launch_bounds__(256, 2) void bwd_assemble_bf16_kernel(BwdArgs<bf16_
     auto issue_slab = [&](int sl, char* buf) {
         if (wave == 0)      copy_state(Sg + (size_t)(32 * sl) * RB, buf + OFF_S);
         else if (wave == 1) copy_state(dSg + (size_t)(32 * sl) * RB, buf + OFF_DS);
-        else if (wave == 2) {
-            copy_slab(reinterpret_cast<const char*>(a.d_o) + vrow0 + 64 * sl, buf + OFF_DO);
-            copy_slab(reinterpret_cast<const char*>(a.U) + vrow0 + 64 * sl, buf + OFF_U);
-        } else {
+        else if (wave == 2) copy_slab(reinterpret_cast<const char*>(a.d_o) + vrow0 + 64 * sl, buf + OFF_DO);
+        else {
             copy_slab(reinterpret_cast<const char*>(a.Y) + vrow0 + 64 * sl, buf + OFF_Y);
             copy_slab(reinterpret_cast<const char*>(a.X) + vrow0 + 64 * sl, buf + OFF_X);
         }
@@ -590,6 +594,25 @@ __global__ __launch_bounds__(256, 2) void bwd_assemble_bf16_kernel(BwdArgs<bf16_
             if (wave < 2) copy_tile(kb, kq_row, lds + OFF_K, wave * (NKB / 2), (wave + 1) * (NKB / 2));
             else          copy_tile(qb, kq_row, lds + OFF_Q, (wave - 2) * (NKB / 2), (wave - 1) * (NKB / 2));
         }
+        // U = T' X: this wave's 16 rows of the slab.  (The lane index is passed through an empty asm so that the two
+        // transposition constants are formed here and not kept in registers until the staging of dq and dk, where the
+        // kernel has none to spare.)
+        int r1 = r;
+        asm volatile("" : "+v"(r1));
+        const bool q_lo = (r1 & 3) < 2;
+        const uint32_t psel = (r1 & 1) ? 0x03020706u : 0x05040100u;
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct) {
+            floatx4 u = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int jp = 0; jp < 2; ++jp) {
+                if (2 * jp <= wave) {                      // T' is lower triangular (wave-uniform)
+                    const char* xp = buf + OFF_X + 32 * jp * RBA + (xo ^ (32 * ct));
+                    mma_bf16(u, ld16(tp_s + tri_pair(wave, jp) * 1024 + lane * 16), lds_read_tr(xp), lds_read_tr(xp + 16 * RBA));
+                }
+            }
+            *reinterpret_cast<u32x2*>(lds + (sl & 1) * SLAB + OFF_U + (uo ^ (32 * ct))) = quad_transpose4x4(to_quad(u), q_lo, psel);
+        }
         // Y_i . X_i and <dS', S>: plain 16-byte pieces, the swizzle is the same for both tiles of a pair
         {
             const u32x4 y = ld16(buf + OFF_Y + tid * 16), x = ld16(buf + OFF_X + tid * 16);
@@ -603,6 +626,7 @@ __global__ __launch_bounds__(256, 2) void bwd_assemble_bf16_kernel(BwdArgs<bf16_
                 for (int m = 0; m < 4; ++m) sdot = dot2_bf16(sv[m], dv[m], sdot);
             }
         }
+        __syncthreads();                             // every wave's rows of U are in the slab
         u32x2 do0, do1, u0, u1, y0, y1;
         aslot(buf + OFF_DO, wave, do0, do1);
         aslot(buf + OFF_U, wave, u0, u1);

@@ -219,8 +219,8 @@ def test_workspace_bytes_of_the_segmented_scan():
 
 def test_chunk_bwd_validation_and_workspace():
     """kla_chunk_bwd validates like kla_chunk_fwd (before any launch), and its workspace is the documented sum:
-    per chunk-head a record [T' | M^T | P^T | 4 vectors], two state checkpoints in the element type, and three
-    [tokens, H, dv] arrays in the element type."""
+    per chunk-head a record [T' | M^T | P^T | 4 vectors], two state checkpoints in the element type, and the
+    [tokens, H, dv] arrays X, Y (and U, which only the element-type-generic kernels keep) in the element type."""
     lib = kla.lib()
     names = ("q", "k", "v", "la", "eta", "eps", "h0", "d_o", "d_hT", "dq", "dk_", "dv_", "dla", "deta", "dh0", "cu_dev",
              "cu_host", "n_seq", "N", "T", "H", "dk", "dv", "chunk", "dt", "ws", "ws_bytes", "stream")
@@ -250,7 +250,9 @@ def test_chunk_bwd_validation_and_workspace():
         expect = r256(n_ch * (3 * 384 * 8 * eb + 1280))
         expect = r256(expect + 4)                              # chunk offsets of a packed batch (n_seq + 1 ints)
         expect += 2 * r256(n_ch * dk * dv * eb)                # S_c and dS'_c
-        expect += 3 * r256(N * T * H * dv * eb)                # X, U, Y
+        rows = r256(N * T * H * dv * eb)
+        assert lib.kla_chunk_bwd_workspace_bytes_opts(N, T, H, dk, dv, 64, dt, None, 0, kla.tune(generic_bwd=True)) == expect + 3 * rows   # X, U, Y
+        expect += (2 if dt == kla.KLA_BF16 else 3) * rows      # the bf16 kernels form U again instead of keeping it
         assert lib.kla_chunk_bwd_workspace_bytes(N, T, H, dk, dv, 64, dt, None, 0) == expect
     assert lib.kla_chunk_bwd_workspace_bytes(1, 64, 1, 100, 64, 64, kla.KLA_BF16, None, 0) == 0
     # one long bf16 sequence on few heads: the sweeps run in segments (here 8 of 16 chunks), and the workspace also holds
@@ -259,7 +261,7 @@ def test_chunk_bwd_validation_and_workspace():
     plain = {}
     for dt, eb in ((kla.KLA_BF16, 2), (kla.KLA_F32, 4)):
         n_ch = N * (T // 64) * H
-        x = r256(r256(n_ch * (3 * 384 * 8 * eb + 1280)) + 4) + 2 * r256(n_ch * dk * dv * eb) + 3 * r256(N * T * H * dv * eb)
+        x = r256(r256(n_ch * (3 * 384 * 8 * eb + 1280)) + 4) + 2 * r256(n_ch * dk * dv * eb) + (2 if dt == kla.KLA_BF16 else 3) * r256(N * T * H * dv * eb)
         plain[dt] = x
     seg = plain[kla.KLA_BF16] + r256(N * 7 * H * dk * (dv + dk) * 4) + 3 * r256(N * 8 * H * dk * dv * 4)
     assert lib.kla_chunk_bwd_workspace_bytes(N, T, H, dk, dv, 64, kla.KLA_BF16, None, 0) == seg
