@@ -347,7 +347,7 @@ template hipError_t launch_intra_bwd<bf16_t>(const IntraArgs<bf16_t>&, int, int,
 // which this kernel writes next to the records.  Options: kOptGdnBeta (beta = eta); kOptNormalizeQ, for which the
 // rows of Q+ and of P are divided by ||q_i|| here, so that the scan needs no variant of its own.
 template <typename E, int DK>
-__global__ __launch_bounds__(256) void intra_diag_kernel(IntraDiagArgs<E> a)
+__global__ __launch_bounds__(256, 3) void intra_diag_kernel(IntraDiagArgs<E> a)
 {
     // The tables hold CH = 64 channels at a time: d_k = 128 takes two passes, whose partial sums meet in the registers
     // that hold the products.  That keeps the kernel at the LDS footprint of the 64x64 fp32 matrices of the later
@@ -469,31 +469,52 @@ __global__ __launch_bounds__(256) void intra_diag_kernel(IntraDiagArgs<E> a)
     float ksq[64 * PPH / 256];                       // this thread's share of ||k_row||^2, rows (tid + 256 it) / PPH
 #pragma unroll
     for (int it = 0; it < 64 * PPH / 256; ++it) ksq[it] = 0.f;
+    // A pass's rows of K, Q and log alpha come from memory into registers (fetch) and go on into the tables once the
+    // pass before has read them; the fetch of the next pass is issued ahead of the last, long, lightly loaded phase of
+    // a pass, so that a workgroup waits for memory once, not once per pass.
+    constexpr int NKQ = 64 * PPH / 256, NLA = 64 * CH / 4 / 256;
+    uint4 kd[NKQ], qd[NKQ];
+    float4 lad[NLA];
+    auto fetch = [&](int c0) {
+#pragma unroll
+        for (int it = 0; it < NKQ; ++it) {
+            const int x = tid + 256 * it;
+            const int row = x / PPH, piece = x % PPH;
+            kd[it] = make_uint4(0, 0, 0, 0); qd[it] = make_uint4(0, 0, 0, 0);
+            if (row < clen) {
+                kd[it] = *reinterpret_cast<const uint4*>(kb + (size_t)row * row_stride + c0 + piece * EPP);
+                qd[it] = *reinterpret_cast<const uint4*>(qb + (size_t)row * row_stride + c0 + piece * EPP);
+            }
+        }
+#pragma unroll
+        for (int it = 0; it < NLA; ++it) {
+            const int x = tid + 256 * it, row = x / (CH / 4), c4 = x % (CH / 4);
+            lad[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (row < clen) lad[it] = *reinterpret_cast<const float4*>(lb + (size_t)row * row_stride + c0 + 4 * c4);
+        }
+    };
+    constexpr bool AHEAD = sizeof(E) == 2;           // fp32 rows are twice the registers: fetched pass by pass
+    if constexpr (AHEAD) fetch(0);
     for (int pass = 0; pass < NPASS; ++pass) {
         const int c0 = pass * CH;                    // first channel of this pass
         if (pass > 0) __syncthreads();               // the previous pass has read its tables
+        if constexpr (!AHEAD) fetch(c0);
         // ---- phase 1: K, Q rows and log2 alpha of CH channels -> LDS (the squares of K summed for the key norms on the way)
 #pragma unroll
-        for (int it = 0; it < 64 * PPH / 256; ++it) {
+        for (int it = 0; it < NKQ; ++it) {
             const int x = tid + 256 * it;
             const int row = x / PPH, piece = x % PPH;
-            uint4 kd = make_uint4(0, 0, 0, 0), qd = make_uint4(0, 0, 0, 0);
-            if (row < clen) {
-                kd = *reinterpret_cast<const uint4*>(kb + (size_t)row * row_stride + c0 + piece * EPP);
-                qd = *reinterpret_cast<const uint4*>(qb + (size_t)row * row_stride + c0 + piece * EPP);
-            }
-            *reinterpret_cast<uint4*>(area + (size_t)(row * LE + piece * EPP) * sizeof(E)) = kd;
-            *reinterpret_cast<uint4*>(area + TE + (size_t)(row * LE + piece * EPP) * sizeof(E)) = qd;
+            *reinterpret_cast<uint4*>(area + (size_t)(row * LE + piece * EPP) * sizeof(E)) = kd[it];
+            *reinterpret_cast<uint4*>(area + TE + (size_t)(row * LE + piece * EPP) * sizeof(E)) = qd[it];
             float kf[EPP];
-            unpack(kd, kf);
+            unpack(kd[it], kf);
 #pragma unroll
             for (int i = 0; i < EPP; ++i) ksq[it] += kf[i] * kf[i];
         }
 #pragma unroll
-        for (int it = 0; it < 64 * CH / 4 / 256; ++it) {
+        for (int it = 0; it < NLA; ++it) {
             const int x = tid + 256 * it, row = x / (CH / 4), c4 = x % (CH / 4);
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (row < clen) v = *reinterpret_cast<const float4*>(lb + (size_t)row * row_stride + c0 + 4 * c4);
+            const float4 v = lad[it];
             const float s2 = 1.44269504088896341f;
             *reinterpret_cast<float4*>(Gs + row * LD + 4 * c4) = make_float4(v.x * s2, v.y * s2, v.z * s2, v.w * s2);
         }
@@ -582,6 +603,7 @@ __global__ __launch_bounds__(256) void intra_diag_kernel(IntraDiagArgs<E> a)
                 mma32<E>(tqk[jb], sq, b0, b1);
             }
         }
+        if constexpr (AHEAD) { if (pass + 1 < NPASS) fetch(c0 + CH); }   // on their way during the pair sums
         if (tid < 224) {
             const float* gi = Gs + pi * LD; const float* gj = Gs + pj * LD;
             const E* ki = Kp + pi * LE; const E* qi = Qp + pi * LE; const E* kj = Kp + pj * LE;
