@@ -53,6 +53,13 @@ def test_diag_chunk_small_shapes(kla, dt, dk, dv, T):
     _check(kla, kla_inputs.chunk_inputs(2, T, 3, dk, dv, dtype=dt, seed=400 + T + dk + dv, h0_std=0.5), seed=T)
 
 
+@pytest.mark.parametrize("T", [1, 64, 65, 130, 200])
+def test_diag_chunk_two_wave_scan_short_sequences(kla, T):
+    """Enough (sequence, head) pairs for the scan with two compute waves per workgroup, whose two-stage ring at d_k = 128
+    is filled in two parts per chunk: sequences of one, two, three and four chunks walk through its start and its end."""
+    _check(kla, kla_inputs.chunk_inputs(8, T, 8, 128, 128, dtype=torch.bfloat16, seed=470 + T, h0_std=0.3), seed=T)
+
+
 @pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16])
 def test_diag_chunk_varlen(kla, dt):
     d = kla_inputs.varlen_inputs(6, 1, 300, 2, 128, 128, dtype=dt, seed=420, h0_std=0.3)
